@@ -1,0 +1,188 @@
+/*
+ * libcrisp -- hybrid-sparse (block AND N:M) GEMM for AMD MI355X (gfx950).
+ *
+ * C ABI of the inference hot path of CRISP (arXiv 2311.14272): a pruned
+ * convolution is lowered to Y = W_hybrid * X, where W_hybrid (S x K, S output
+ * channels, K = kh*kw*C) has whole B x B blocks dropped, the same number in
+ * every row of the block grid, and at most n non-zeros in every m consecutive
+ * columns inside the blocks that remain (Sec. 3.1).
+ *
+ * Conventions that hold for every entry point
+ *   - Returns a crisp_status; CRISP_OK is 0.  No exceptions, no errno, no
+ *     global state; calls on different streams may run concurrently.
+ *   - All arguments are validated on the host before any device call, so bad
+ *     arguments are reported even on a machine without a GPU.
+ *   - "device" pointers are HIP device memory owned by the caller, 16-byte
+ *     aligned.  The library does not allocate, free or synchronise; work is
+ *     enqueued on `stream` (a hipStream_t passed as void*, NULL = default
+ *     stream) and the buffers must stay alive until that work has finished.
+ *   - bf16 values travel as raw uint16_t bit patterns.
+ *   - Matrices are row-major.  W is S x K.  X is K x ldx (K rows of Ncol
+ *     used columns); Y is S x ldy.
+ */
+#ifndef CRISP_H
+#define CRISP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CRISP_API __attribute__((visibility("default")))
+
+typedef int32_t crisp_status;
+enum {
+    CRISP_OK = 0,
+    CRISP_EINVAL = 1,       /* null pointer, n/m/B/density/kind out of range       */
+    CRISP_ESHAPE = 2,       /* S, K, Ncol, ld*, conv geometry inconsistent         */
+    CRISP_EBUFSIZE = 3,     /* workspace smaller than crisp_pack_sizes reports     */
+    CRISP_EALIGN = 4,       /* pointer or leading dimension alignment              */
+    CRISP_EUNSUPPORTED = 5, /* valid request this build has no kernel for          */
+    CRISP_EDEVICE = 6       /* a HIP launch reported an error                      */
+};
+
+/* saliency kinds (Sec. 3.4, Eq. 1) */
+enum {
+    CRISP_SAL_GIVEN = 0, /* T_or_G is the saliency T itself (fp32, S x K)                 */
+    CRISP_SAL_GRAD = 1,  /* T = |W * G| with G = T_or_G, one fp32 multiply (Eq. 1; the     */
+                         /* 1/H averaging factor is positive and cannot change a ranking)  */
+    CRISP_SAL_MAG = 2    /* T = |W|, T_or_G unused (magnitude pruning, the 2:4 prior art)  */
+};
+
+/* block selection modes */
+enum {
+    CRISP_ROW_UNIFORM = 0, /* same number of kept blocks in every block-row (Sec. 3.1, 3.3) */
+    CRISP_LAYER_TOPK = 1   /* plain block pruning over the whole grid; rows may be uneven   */
+};
+
+enum { CRISP_X_KN = 0 };               /* X layout: K rows, columns contiguous              */
+enum { CRISP_Y_F32 = 0, CRISP_Y_BF16 = 1 };
+enum { CRISP_ACT_CBHW = 0 };           /* activation layout: [C][batch][H][W], W contiguous */
+
+typedef struct {
+    double block_density;  /* (0,1]; kept blocks per block-row k_row = clamp(floor(d*Kb+0.5),1,Kb) */
+    int32_t S, K;          /* weight rows (output channels) and reduction length, >= 1            */
+    int32_t n, m;          /* 1 <= n <= m, m in {4,8}; n == m switches the fine-grained part off   */
+    int32_t B;             /* block edge, 16 | 32 | 64, B % m == 0                                 */
+    int32_t sal_kind;      /* CRISP_SAL_*                                                          */
+    int32_t select_mode;   /* CRISP_ROW_UNIFORM | CRISP_LAYER_TOPK                                 */
+    int32_t reserved;      /* must be 0                                                            */
+} crisp_layer_desc;
+
+typedef struct {
+    int32_t Sb, Kb;            /* block grid: ceil(S/B) x ceil(K/B)                              */
+    int32_t k_row;             /* kept blocks per block-row                                      */
+    int32_t nk;                /* kept blocks in total = Sb * k_row (both selection modes)       */
+    int32_t slots_per_row;     /* B*n/m value slots per block row                                */
+    int32_t idx_bits;          /* log2(m) bits per slot                                          */
+    int32_t idx_words_per_row; /* ceil(slots_per_row*idx_bits/32)                                */
+    int32_t mask_words_per_row;/* ceil(K/32)                                                     */
+    int64_t mask_words;        /* S * mask_words_per_row  (uint32)                               */
+    int64_t row_ptr_elems;     /* Sb + 1                  (int32)                                */
+    int64_t col_idx_elems;     /* nk                      (int32)                                */
+    int64_t score_elems;       /* Sb * Kb                 (double)                               */
+    int64_t vals_elems;        /* nk * B * slots_per_row  (uint16 bf16)                          */
+    int64_t idx_words;         /* nk * B * idx_words_per_row (uint32)                            */
+    int64_t flags_elems;       /* 4                       (int32)                                */
+    size_t select_ws_bytes;    /* workspace of crisp_select_mask                                 */
+    size_t pack_ws_bytes;      /* workspace of crisp_pack                                        */
+    size_t spmm_ws_bytes;      /* workspace of crisp_spmm                                        */
+} crisp_sizes;
+
+typedef struct {
+    int32_t C, H, W, batch;    /* input channels, height, width, batch                           */
+    int32_t kh, kw, stride, pad;
+    int32_t act_layout;        /* CRISP_ACT_CBHW                                                 */
+    int32_t x_layout;          /* CRISP_X_KN                                                     */
+} crisp_conv_desc;
+
+/* Text for a status code (static storage, never NULL). */
+CRISP_API const char *crisp_status_str(crisp_status st);
+
+/*
+ * Buffer sizes for a layer.  Host only, pure function of the descriptor.
+ * Derived from the storage format of Sec. 3.1: block column indices in
+ * Blocked-ELL / block-CSR order, one log2(m)-bit in-group position per kept
+ * value.  Errors: CRISP_EINVAL for a bad descriptor or null pointer.
+ */
+CRISP_API crisp_status crisp_pack_sizes(const crisp_layer_desc *desc, crisp_sizes *out);
+
+/*
+ * Mask selection for one layer (Alg. 1 lines 2, 4-6 and 10; Sec. 3.3).
+ *   1. saliency T (Eq. 1) per desc->sal_kind, fp32;
+ *   2. N:M: in each aligned group of m consecutive columns of a row keep the n
+ *      positions that come first under (T descending, column ascending); a short
+ *      last group keeps min(n, length);
+ *   3. block score = sum of T over the N:M-kept, in-range elements of the block,
+ *      in fp64, columns ascending inside a row, then rows ascending;
+ *   4. ROW_UNIFORM: per block-row keep the k_row blocks first under (score
+ *      descending, column ascending).  LAYER_TOPK: keep the Sb*k_row blocks first
+ *      under (score descending, block-row ascending, column ascending).
+ * Inputs (device):  W  S x K bf16;  T_or_G  S x K fp32 (may be NULL for SAL_MAG).
+ * Outputs (device): nm_mask  S x ceil(K/32) uint32, bit k%32 of word k/32 set when
+ *                   column k is kept by step 2 (the block choice is NOT folded in);
+ *                   row_ptr  Sb+1 int32;  col_idx  nk int32, ascending inside a row;
+ *                   block_score  Sb x Kb fp64, optional (NULL to skip).
+ * ws: device workspace of select_ws_bytes (may be NULL when that is 0).
+ * NaN saliency is outside the contract (order undefined).
+ * Errors: EINVAL, EALIGN, EBUFSIZE, EUNSUPPORTED (block grid beyond 8192 blocks
+ * in LAYER_TOPK mode, Kb > 4096), EDEVICE.
+ */
+CRISP_API crisp_status crisp_select_mask(const crisp_layer_desc *desc, const uint16_t *W, const float *T_or_G,
+                               uint32_t *nm_mask, int32_t *row_ptr, int32_t *col_idx,
+                               double *block_score, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Packing (Sec. 3.1 metadata paragraph; Sec. 3.5, second step).  For kept block t
+ * (row_ptr/col_idx order), block row r, group g of m columns there are n slots;
+ * kept elements fill them in ascending column order.
+ *   vals       [nk][B][B*n/m] bf16
+ *   idx_words  [nk][B][idx_words_per_row] uint32: per block row a little-endian bit
+ *              stream, slot q at bits [q*w, q*w+w), w = log2 m, 0-based position of
+ *              the value inside its group ("second value ... index of 1").
+ *   Padding: unused slots of a short group hold value 0, position 0; groups wholly
+ *   outside the matrix (row >= S or first column >= K) hold value 0, positions 0..n-1.
+ *   flags[0] = 1 when no aligned group of 4 columns in a kept block holds more
+ *   than 2 kept elements (eligible for the 2-of-4 sparse matrix instruction).
+ * All pointers device.  Errors as above.
+ */
+CRISP_API crisp_status crisp_pack(const crisp_layer_desc *desc, const uint16_t *W, const uint32_t *nm_mask,
+                        const int32_t *row_ptr, const int32_t *col_idx, uint16_t *vals,
+                        uint32_t *idx_words, int32_t *flags, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Convolution lowering (Sec. 3 "Notation": the kernel tensor is reshaped so that
+ * the convolution becomes a matrix product).  act is [C][batch][H][W] bf16;
+ *   X[(a*kw + b)*C + c][(i*Ho + oh)*Wo + ow] = act[c][i][oh*stride + a - pad][ow*stride + b - pad]
+ * and zero outside the image.  X is K x ldx with K = kh*kw*C, Ncol = batch*Ho*Wo
+ * columns written, ldx >= Ncol.  For kh = kw = stride = 1, pad = 0 the result equals
+ * act viewed as C x (batch*H*W); callers may skip the call and pass act as X.
+ * All pointers device.  Errors: EINVAL, ESHAPE, EUNSUPPORTED (layouts), EDEVICE.
+ */
+CRISP_API crisp_status crisp_im2col(const crisp_conv_desc *conv, const uint16_t *act, uint16_t *X, int64_t ldx,
+                          void *stream);
+
+/*
+ * The product (Sec. 3.5): Y[s][j] = sum over kept blocks (bi = s/B, bj) of the
+ * block-row, over the block's slots, of value * X[bj*B + g*m + position][j];
+ * bf16 x bf16 products accumulated in fp32.  Blocks that were dropped are never
+ * touched, neither their weights nor the X rows only they would need.
+ *   row_ptr/col_idx/vals/idx_words: output of crisp_pack (device).
+ *   X: K x ldx bf16 (device), Ncol used columns, ldx >= Ncol, ldx % 8 == 0; the
+ *      allocation must cover K*ldx elements.  x_layout = CRISP_X_KN.
+ *   Y: S x ldy, fp32 or bf16 per y_dtype (device), ldy >= Ncol, ldy % 8 == 0.
+ *      Every element Y[0..S)[0..Ncol) is written (rows of empty block-rows get 0).
+ *   desc->block_density and sal_kind are not used here.
+ * Errors: EINVAL, ESHAPE, EALIGN, EUNSUPPORTED (B = 16, x_layout), EDEVICE.
+ */
+CRISP_API crisp_status crisp_spmm(const crisp_layer_desc *desc, const int32_t *row_ptr, const int32_t *col_idx,
+                        const uint16_t *vals, const uint32_t *idx_words, const uint16_t *X,
+                        int64_t Ncol, int64_t ldx, int32_t x_layout, void *Y, int64_t ldy,
+                        int32_t y_dtype, void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CRISP_H */

@@ -1,0 +1,168 @@
+"""Thin binding of libcrisp.so: argument marshalling only, every step runs in the HIP kernels.
+
+Function names mirror the C ABI (include/crisp.h).  Device buffers are torch tensors used as
+plain memory; the current torch stream is passed as the HIP stream.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libcrisp.so")
+
+OK, EINVAL, ESHAPE, EBUFSIZE, EALIGN, EUNSUPPORTED, EDEVICE = range(7)
+SAL_GIVEN, SAL_GRAD, SAL_MAG = 0, 1, 2
+ROW_UNIFORM, LAYER_TOPK = 0, 1
+X_KN = 0
+Y_F32, Y_BF16 = 0, 1
+ACT_CBHW = 0
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [("block_density", C.c_double), ("S", C.c_int32), ("K", C.c_int32), ("n", C.c_int32),
+                ("m", C.c_int32), ("B", C.c_int32), ("sal_kind", C.c_int32), ("select_mode", C.c_int32),
+                ("reserved", C.c_int32)]
+
+
+class Sizes(C.Structure):
+    _fields_ = [("Sb", C.c_int32), ("Kb", C.c_int32), ("k_row", C.c_int32), ("nk", C.c_int32),
+                ("slots_per_row", C.c_int32), ("idx_bits", C.c_int32), ("idx_words_per_row", C.c_int32),
+                ("mask_words_per_row", C.c_int32), ("mask_words", C.c_int64), ("row_ptr_elems", C.c_int64),
+                ("col_idx_elems", C.c_int64), ("score_elems", C.c_int64), ("vals_elems", C.c_int64),
+                ("idx_words", C.c_int64), ("flags_elems", C.c_int64), ("select_ws_bytes", C.c_size_t),
+                ("pack_ws_bytes", C.c_size_t), ("spmm_ws_bytes", C.c_size_t)]
+
+
+class ConvDesc(C.Structure):
+    _fields_ = [("C", C.c_int32), ("H", C.c_int32), ("W", C.c_int32), ("batch", C.c_int32), ("kh", C.c_int32),
+                ("kw", C.c_int32), ("stride", C.c_int32), ("pad", C.c_int32), ("act_layout", C.c_int32),
+                ("x_layout", C.c_int32)]
+
+
+class CrispError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (fn, status_str(status), status))
+
+
+_lib = None
+
+
+def lib():
+    """Load libcrisp.so; there is no fallback path when it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libcrisp.so is not built (run `python -m paper_2311_14272_amd.build`); "
+                               "there is no CPU fallback")
+        L = C.CDLL(LIB_PATH)
+        vp = C.c_void_p
+        L.crisp_status_str.restype = C.c_char_p
+        L.crisp_status_str.argtypes = [C.c_int32]
+        L.crisp_pack_sizes.argtypes = [C.POINTER(LayerDesc), C.POINTER(Sizes)]
+        L.crisp_select_mask.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.crisp_pack.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.crisp_im2col.argtypes = [C.POINTER(ConvDesc), vp, vp, C.c_int64, vp]
+        L.crisp_spmm.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp, vp, C.c_int64, C.c_int64, C.c_int32, vp,
+                                 C.c_int64, C.c_int32, vp, C.c_size_t, vp]
+        for f in (L.crisp_pack_sizes, L.crisp_select_mask, L.crisp_pack, L.crisp_im2col, L.crisp_spmm):
+            f.restype = C.c_int32
+        _lib = L
+    return _lib
+
+
+def status_str(st: int) -> str:
+    return lib().crisp_status_str(st).decode()
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream() -> Optional[int]:
+    import torch
+    return torch.cuda.current_stream().cuda_stream or None
+
+
+def layer_desc(S, K, n, m, B, block_density=1.0, sal_kind=SAL_MAG, select_mode=ROW_UNIFORM) -> LayerDesc:
+    return LayerDesc(float(block_density), S, K, n, m, B, sal_kind, select_mode, 0)
+
+
+def crisp_pack_sizes(desc: LayerDesc) -> Sizes:
+    out = Sizes()
+    st = lib().crisp_pack_sizes(C.byref(desc), C.byref(out))
+    if st != OK:
+        raise CrispError("crisp_pack_sizes", st)
+    return out
+
+
+def crisp_select_mask(desc, W, T_or_G, nm_mask, row_ptr, col_idx, block_score=None, ws=None, ws_bytes=0, stream=-1):
+    st = lib().crisp_select_mask(C.byref(desc), _ptr(W), _ptr(T_or_G), _ptr(nm_mask), _ptr(row_ptr), _ptr(col_idx),
+                                 _ptr(block_score), _ptr(ws), ws_bytes, _stream() if stream == -1 else stream)
+    if st != OK:
+        raise CrispError("crisp_select_mask", st)
+
+
+def crisp_pack(desc, W, nm_mask, row_ptr, col_idx, vals, idx_words, flags, ws=None, ws_bytes=0, stream=-1):
+    st = lib().crisp_pack(C.byref(desc), _ptr(W), _ptr(nm_mask), _ptr(row_ptr), _ptr(col_idx), _ptr(vals),
+                          _ptr(idx_words), _ptr(flags), _ptr(ws), ws_bytes, _stream() if stream == -1 else stream)
+    if st != OK:
+        raise CrispError("crisp_pack", st)
+
+
+def crisp_im2col(conv: ConvDesc, act, X, ldx, stream=-1):
+    st = lib().crisp_im2col(C.byref(conv), _ptr(act), _ptr(X), ldx, _stream() if stream == -1 else stream)
+    if st != OK:
+        raise CrispError("crisp_im2col", st)
+
+
+def crisp_spmm(desc, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, Y, ldy, y_dtype=Y_F32, x_layout=X_KN,
+               ws=None, ws_bytes=0, stream=-1):
+    st = lib().crisp_spmm(C.byref(desc), _ptr(row_ptr), _ptr(col_idx), _ptr(vals), _ptr(idx_words), _ptr(X), Ncol,
+                          ldx, x_layout, _ptr(Y), ldy, y_dtype, _ptr(ws), ws_bytes,
+                          _stream() if stream == -1 else stream)
+    if st != OK:
+        raise CrispError("crisp_spmm", st)
+
+
+@dataclass
+class DeviceLayer:
+    """Device buffers of one pruned layer (plain torch tensors used as memory)."""
+    desc: LayerDesc
+    sizes: Sizes
+    nm_mask: object
+    row_ptr: object
+    col_idx: object
+    score: object
+    vals: object
+    idx_words: object
+    flags: object
+
+
+def alloc_layer(desc: LayerDesc, device="cuda") -> DeviceLayer:
+    """Allocate the outputs of crisp_select_mask and crisp_pack for a layer."""
+    import torch
+    sz = crisp_pack_sizes(desc)
+    i32, dev = torch.int32, device
+    return DeviceLayer(
+        desc, sz,
+        torch.empty(max(1, sz.mask_words), dtype=i32, device=dev),
+        torch.empty(sz.row_ptr_elems, dtype=i32, device=dev),
+        torch.empty(max(1, sz.col_idx_elems), dtype=i32, device=dev),
+        torch.empty(sz.score_elems, dtype=torch.float64, device=dev),
+        torch.empty(max(1, sz.vals_elems), dtype=torch.int16, device=dev),
+        torch.empty(max(1, sz.idx_words), dtype=i32, device=dev),
+        torch.empty(4, dtype=i32, device=dev))
+
+
+def prune_and_pack(layer: DeviceLayer, W, T_or_G=None):
+    """crisp_select_mask followed by crisp_pack on the current stream."""
+    crisp_select_mask(layer.desc, W, T_or_G, layer.nm_mask, layer.row_ptr, layer.col_idx, layer.score)
+    crisp_pack(layer.desc, W, layer.nm_mask, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, layer.flags)

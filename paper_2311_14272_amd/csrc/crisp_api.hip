@@ -1,0 +1,169 @@
+// C ABI of libcrisp: argument validation on the host, size queries, dispatch to the launchers.
+#include "crisp_internal.h"
+
+#include <cmath>
+
+namespace crisp {
+
+static int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+crisp_status make_geometry(const crisp_layer_desc* d, bool need_density, Geometry* g) {
+    if (!d || !g) return CRISP_EINVAL;
+    if (d->S < 1 || d->K < 1) return CRISP_ESHAPE;
+    if (d->m != 4 && d->m != 8) return CRISP_EINVAL;
+    if (d->n < 1 || d->n > d->m) return CRISP_EINVAL;
+    if (d->B != 16 && d->B != 32 && d->B != 64) return CRISP_EINVAL;
+    if (d->B % d->m != 0) return CRISP_EINVAL;
+    if (d->sal_kind < CRISP_SAL_GIVEN || d->sal_kind > CRISP_SAL_MAG) return CRISP_EINVAL;
+    if (d->select_mode != CRISP_ROW_UNIFORM && d->select_mode != CRISP_LAYER_TOPK) return CRISP_EINVAL;
+    if (d->reserved != 0) return CRISP_EINVAL;
+    g->S = d->S; g->K = d->K; g->n = d->n; g->m = d->m; g->B = d->B;
+    g->Sb = ceil_div(d->S, d->B);
+    g->Kb = ceil_div(d->K, d->B);
+    g->w = d->m == 4 ? 2 : 3;
+    g->slots = d->B / d->m * d->n;
+    g->wpr = ceil_div(g->slots * g->w, 32);
+    g->mwpr = ceil_div(d->K, 32);
+    g->k_row = 0;
+    g->nk = 0;
+    if (need_density) {
+        // Kept blocks per block-row for the layer's block density; at least one so that a
+        // layer cannot collapse (Sec. 3.3, last paragraph).
+        if (!(d->block_density > 0.0) || d->block_density > 1.0) return CRISP_EINVAL;
+        double v = std::floor(d->block_density * (double)g->Kb + 0.5);
+        int k = (int)v;
+        if (k < 1) k = 1;
+        if (k > g->Kb) k = g->Kb;
+        g->k_row = k;
+        if ((int64_t)g->Sb * k > INT32_MAX) return CRISP_ESHAPE;
+        g->nk = g->Sb * k;
+    }
+    return CRISP_OK;
+}
+
+static bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
+
+}  // namespace crisp
+
+using namespace crisp;
+
+extern "C" {
+
+const char* crisp_status_str(crisp_status st) {
+    switch (st) {
+        case CRISP_OK: return "ok";
+        case CRISP_EINVAL: return "invalid argument";
+        case CRISP_ESHAPE: return "inconsistent shape";
+        case CRISP_EBUFSIZE: return "workspace too small";
+        case CRISP_EALIGN: return "misaligned pointer or leading dimension";
+        case CRISP_EUNSUPPORTED: return "unsupported configuration";
+        case CRISP_EDEVICE: return "device error";
+        default: return "unknown status";
+    }
+}
+
+crisp_status crisp_pack_sizes(const crisp_layer_desc* desc, crisp_sizes* out) {
+    if (!out) return CRISP_EINVAL;
+    Geometry g;
+    crisp_status st = make_geometry(desc, true, &g);
+    if (st != CRISP_OK) return st;
+    out->Sb = g.Sb; out->Kb = g.Kb; out->k_row = g.k_row; out->nk = g.nk;
+    out->slots_per_row = g.slots;
+    out->idx_bits = g.w;
+    out->idx_words_per_row = g.wpr;
+    out->mask_words_per_row = g.mwpr;
+    out->mask_words = (int64_t)g.S * g.mwpr;
+    out->row_ptr_elems = (int64_t)g.Sb + 1;
+    out->col_idx_elems = g.nk;
+    out->score_elems = (int64_t)g.Sb * g.Kb;
+    out->vals_elems = (int64_t)g.nk * g.B * g.slots;
+    out->idx_words = (int64_t)g.nk * g.B * g.wpr;
+    out->flags_elems = 4;
+    // block scores live in the workspace when the caller does not ask for them
+    out->select_ws_bytes = (size_t)g.Sb * g.Kb * sizeof(double);
+    out->pack_ws_bytes = 0;
+    out->spmm_ws_bytes = 0;
+    return CRISP_OK;
+}
+
+crisp_status crisp_select_mask(const crisp_layer_desc* desc, const uint16_t* W, const float* T_or_G,
+                               uint32_t* nm_mask, int32_t* row_ptr, int32_t* col_idx, double* block_score,
+                               void* ws, size_t ws_bytes, void* stream) {
+    Geometry g;
+    crisp_status st = make_geometry(desc, true, &g);
+    if (st != CRISP_OK) return st;
+    if (!nm_mask || !row_ptr || !col_idx) return CRISP_EINVAL;
+    if (desc->sal_kind != CRISP_SAL_GIVEN && !W) return CRISP_EINVAL;
+    if (desc->sal_kind != CRISP_SAL_MAG && !T_or_G) return CRISP_EINVAL;
+    if (misaligned(W, 16) || misaligned(T_or_G, 16) || misaligned(nm_mask, 16) || misaligned(row_ptr, 4) ||
+        misaligned(col_idx, 4) || misaligned(block_score, 8) || misaligned(ws, 16))
+        return CRISP_EALIGN;
+    double* score = block_score;
+    if (!score) {
+        size_t need = (size_t)g.Sb * g.Kb * sizeof(double);
+        if (!ws || ws_bytes < need) return CRISP_EBUFSIZE;
+        score = (double*)ws;
+    }
+    if (g.Kb > 4096) return CRISP_EUNSUPPORTED;
+    if (desc->select_mode == CRISP_LAYER_TOPK && ((int64_t)g.Sb * g.Kb > 8192 || g.Sb > 1024)) return CRISP_EUNSUPPORTED;
+    hipError_t e = launch_select(g, desc->sal_kind, desc->select_mode, W, T_or_G, nm_mask, row_ptr, col_idx,
+                                 block_score, score, (hipStream_t)stream);
+    return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
+}
+
+crisp_status crisp_pack(const crisp_layer_desc* desc, const uint16_t* W, const uint32_t* nm_mask,
+                        const int32_t* row_ptr, const int32_t* col_idx, uint16_t* vals, uint32_t* idx_words,
+                        int32_t* flags, void* ws, size_t ws_bytes, void* stream) {
+    (void)ws; (void)ws_bytes;
+    Geometry g;
+    crisp_status st = make_geometry(desc, true, &g);
+    if (st != CRISP_OK) return st;
+    if (!W || !nm_mask || !row_ptr || !col_idx || !vals || !idx_words || !flags) return CRISP_EINVAL;
+    if (misaligned(W, 16) || misaligned(nm_mask, 16) || misaligned(row_ptr, 4) || misaligned(col_idx, 4) ||
+        misaligned(vals, 16) || misaligned(idx_words, 16) || misaligned(flags, 4))
+        return CRISP_EALIGN;
+    hipError_t e = launch_pack(g, W, nm_mask, row_ptr, col_idx, vals, idx_words, flags, (hipStream_t)stream);
+    return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
+}
+
+crisp_status crisp_im2col(const crisp_conv_desc* c, const uint16_t* act, uint16_t* X, int64_t ldx, void* stream) {
+    if (!c || !act || !X) return CRISP_EINVAL;
+    if (c->C < 1 || c->H < 1 || c->W < 1 || c->batch < 1 || c->kh < 1 || c->kw < 1 || c->stride < 1 || c->pad < 0)
+        return CRISP_ESHAPE;
+    if (c->act_layout != CRISP_ACT_CBHW || c->x_layout != CRISP_X_KN) return CRISP_EUNSUPPORTED;
+    int64_t Ho = ((int64_t)c->H + 2 * c->pad - c->kh) / c->stride + 1;
+    int64_t Wo = ((int64_t)c->W + 2 * c->pad - c->kw) / c->stride + 1;
+    if (c->H + 2 * c->pad < c->kh || c->W + 2 * c->pad < c->kw || Ho < 1 || Wo < 1) return CRISP_ESHAPE;
+    int64_t Ncol = (int64_t)c->batch * Ho * Wo;
+    int64_t K = (int64_t)c->kh * c->kw * c->C;
+    if (ldx < Ncol || Ncol > INT32_MAX || K > INT32_MAX) return CRISP_ESHAPE;
+    if ((int64_t)c->C * c->batch * c->H * c->W > ((int64_t)1 << 40)) return CRISP_ESHAPE;
+    if (misaligned(act, 16) || misaligned(X, 16)) return CRISP_EALIGN;
+    hipError_t e = launch_im2col(*c, act, X, ldx, (hipStream_t)stream);
+    return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
+}
+
+crisp_status crisp_spmm(const crisp_layer_desc* desc, const int32_t* row_ptr, const int32_t* col_idx,
+                        const uint16_t* vals, const uint32_t* idx_words, const uint16_t* X, int64_t Ncol,
+                        int64_t ldx, int32_t x_layout, void* Y, int64_t ldy, int32_t y_dtype, void* ws,
+                        size_t ws_bytes, void* stream) {
+    (void)ws; (void)ws_bytes;
+    Geometry g;
+    crisp_status st = make_geometry(desc, false, &g);
+    if (st != CRISP_OK) return st;
+    if (!row_ptr || !col_idx || !vals || !idx_words || !X || !Y) return CRISP_EINVAL;
+    if (y_dtype != CRISP_Y_F32 && y_dtype != CRISP_Y_BF16) return CRISP_EINVAL;
+    if (Ncol < 1 || ldx < Ncol || ldy < Ncol) return CRISP_ESHAPE;
+    if (Ncol > ((int64_t)1 << 30) || ldx > ((int64_t)1 << 30) || ldy > ((int64_t)1 << 30)) return CRISP_ESHAPE;
+    if ((ldx & 7) || (ldy & 7)) return CRISP_EALIGN;
+    if (misaligned(row_ptr, 4) || misaligned(col_idx, 4) || misaligned(vals, 16) || misaligned(idx_words, 16) ||
+        misaligned(X, 16) || misaligned(Y, 16))
+        return CRISP_EALIGN;
+    if (x_layout != CRISP_X_KN) return CRISP_EUNSUPPORTED;
+    if (g.B == 16) return CRISP_EUNSUPPORTED;
+    hipError_t e = launch_spmm(g, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, Y, ldy, y_dtype,
+                               (hipStream_t)stream);
+    return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
+}
+
+}  // extern "C"

@@ -1,0 +1,35 @@
+// Internal declarations shared by the libcrisp translation units (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "crisp.h"
+
+namespace crisp {
+
+struct Geometry {
+    int S, K, n, m, B;
+    int Sb, Kb, k_row, nk;
+    int w;      // bits per in-group position
+    int slots;  // value slots per block row
+    int wpr;    // index words per block row
+    int mwpr;   // mask words per weight row
+};
+
+// Host-side validation + derived sizes; no device calls.
+crisp_status make_geometry(const crisp_layer_desc* d, bool need_density, Geometry* g);
+
+// Launchers (enqueue only).  Each returns hipGetLastError() of its launches.
+hipError_t launch_select(const Geometry& g, int sal_kind, int select_mode, const uint16_t* W, const float* TG,
+                         uint32_t* nm_mask, int32_t* row_ptr, int32_t* col_idx, double* score, double* score_ws,
+                         hipStream_t st);
+hipError_t launch_pack(const Geometry& g, const uint16_t* W, const uint32_t* nm_mask, const int32_t* row_ptr,
+                       const int32_t* col_idx, uint16_t* vals, uint32_t* idxw, int32_t* flags, hipStream_t st);
+hipError_t launch_im2col(const crisp_conv_desc& c, const uint16_t* act, uint16_t* X, int64_t ldx, hipStream_t st);
+hipError_t launch_spmm(const Geometry& g, const int32_t* row_ptr, const int32_t* col_idx, const uint16_t* vals,
+                       const uint32_t* idxw, const uint16_t* X, int64_t Ncol, int64_t ldx, void* Y, int64_t ldy,
+                       int y_dtype, hipStream_t st);
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+}  // namespace crisp

@@ -1,0 +1,94 @@
+// Packing kernels: kept blocks -> compressed values + in-group positions (Sec. 3.1, Sec. 3.5).
+#include "crisp_internal.h"
+
+namespace crisp {
+
+__global__ void pack_init_flags_kernel(int32_t* flags) {
+    if (threadIdx.x == 0) { flags[0] = 1; flags[1] = 0; flags[2] = 0; flags[3] = 0; }
+}
+
+// Block-row that owns kept block t: the last bi with row_ptr[bi] <= t (rows may be empty).
+__device__ __forceinline__ int owner_row(const int32_t* __restrict__ row_ptr, int Sb, int t) {
+    int lo = 0, hi = Sb;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (row_ptr[mid] <= t) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// Keep bits of the aligned group of m columns starting at column k0 of weight row s.
+__device__ __forceinline__ uint32_t group_bits(const uint32_t* __restrict__ nm_mask, int mwpr, int s, int k0, int m) {
+    return (nm_mask[(size_t)s * mwpr + (k0 >> 5)] >> (k0 & 31)) & ((1u << m) - 1u);
+}
+
+// Position stored in slot j of a group: the j-th kept column of the group (0-based inside the
+// group), 0 when the group holds fewer kept elements (short last group), j when the group lies
+// wholly outside the matrix.
+__device__ __forceinline__ uint32_t slot_position(uint32_t bits, int j, bool outside) {
+    if (outside) return (uint32_t)j;
+    for (int i = 0; i < j; ++i) bits &= bits - 1u;  // drop the j lowest set bits
+    return bits ? (uint32_t)(__ffs(bits) - 1) : 0u;
+}
+
+// One workgroup per kept block.  Phase 1: one thread per (block row, group) gathers the kept
+// values in ascending column order.  Phase 2: one thread per (block row, index word) assembles
+// the little-endian stream of log2(m)-bit positions.
+__global__ __launch_bounds__(256) void pack_block_kernel(int S, int K, int n, int m, int B, int Sb, int w, int slots,
+                                                         int wpr, int mwpr, const uint16_t* __restrict__ W,
+                                                         const uint32_t* __restrict__ nm_mask,
+                                                         const int32_t* __restrict__ row_ptr,
+                                                         const int32_t* __restrict__ col_idx,
+                                                         uint16_t* __restrict__ vals, uint32_t* __restrict__ idxw,
+                                                         int32_t* __restrict__ flags) {
+    const int t = blockIdx.x;
+    const int bi = owner_row(row_ptr, Sb, t);
+    const int bj = col_idx[t];
+    const int G = B / m;
+    bool violates = false;
+    for (int e = threadIdx.x; e < B * G; e += 256) {
+        const int r = e / G, g = e % G;
+        const int s = bi * B + r, k0 = bj * B + g * m;
+        uint16_t* out = vals + ((size_t)t * B + r) * slots + g * n;
+        int filled = 0;
+        if (s < S && k0 < K) {
+            const uint32_t bits = group_bits(nm_mask, mwpr, s, k0, m);
+            for (int o = 0; o < m; ++o)
+                if ((bits >> o) & 1u) {
+                    if (filled < n) out[filled] = W[(size_t)s * K + k0 + o];
+                    ++filled;
+                }
+            if (__popc(bits & 0xFu) > 2 || __popc(bits >> 4) > 2) violates = true;
+        }
+        for (; filled < n; ++filled) out[filled] = 0;
+    }
+    if (violates) atomicAnd(flags, 0);
+    for (int e = threadIdx.x; e < B * wpr; e += 256) {
+        const int r = e / wpr, x = e % wpr;
+        const int s = bi * B + r;
+        const int q_begin = (32 * x) / w;                         // first slot touching this word
+        const int q_end = min(slots, (32 * x + 31) / w + 1);      // one past the last
+        uint32_t word = 0;
+        for (int q = q_begin; q < q_end; ++q) {
+            const int g = q / n, j = q % n;
+            const int k0 = bj * B + g * m;
+            const bool outside = (s >= S) || (k0 >= K);
+            const uint32_t bits = outside ? 0u : group_bits(nm_mask, mwpr, s, k0, m);
+            const uint32_t pos = slot_position(bits, j, outside);
+            const int bit = q * w - 32 * x;                       // may be negative: field began in the previous word
+            word |= bit >= 0 ? (pos << bit) : (pos >> (-bit));
+        }
+        idxw[((size_t)t * B + r) * wpr + x] = word;
+    }
+}
+
+hipError_t launch_pack(const Geometry& g, const uint16_t* W, const uint32_t* nm_mask, const int32_t* row_ptr,
+                       const int32_t* col_idx, uint16_t* vals, uint32_t* idxw, int32_t* flags, hipStream_t st) {
+    pack_init_flags_kernel<<<1, 64, 0, st>>>(flags);
+    if (g.nk > 0)
+        pack_block_kernel<<<g.nk, 256, 0, st>>>(g.S, g.K, g.n, g.m, g.B, g.Sb, g.w, g.slots, g.wpr, g.mwpr, W,
+                                                nm_mask, row_ptr, col_idx, vals, idxw, flags);
+    return hipGetLastError();
+}
+
+}  // namespace crisp

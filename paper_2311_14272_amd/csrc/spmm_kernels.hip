@@ -1,0 +1,307 @@
+// Hybrid-sparse product Y = W_hybrid * X on gfx950 (Sec. 3.5 of the CRISP paper, re-thought for
+// CDNA4): a workgroup owns one block-row of W and a strip of output columns and walks the
+// block-row's list of kept blocks, so dropped blocks cost neither weight nor activation traffic.
+//
+// Per kept block:
+//   * the compressed values and in-group positions are streamed (16-byte coalesced loads) into
+//     an LDS staging area and expanded there into a dense bf16 B x B tile, stored fragment-major
+//     so that each lane later fetches its MFMA A operand with one conflict-free ds_read_b128;
+//   * each wave loads its own X rows straight from global memory into registers, row-wise and
+//     coalesced.  A lane holds, for each of 8 K-rows, 2*WD consecutive columns.  Transposing
+//     pairs of 16-bit halves turns that into 2*WD MFMA B operands (8 K-values of one column
+//     each); the c-th operand belongs to column (lane%32)*2*WD + c, so the 2*WD accumulators of
+//     a lane are 2*WD *consecutive* output columns and Y is written with wide stores;
+//   * v_mfma_f32_32x32x16_bf16 accumulates in fp32.
+// The X rows of the next kept block are requested while the current block is multiplied.
+#include "crisp_internal.h"
+
+namespace crisp {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+struct SpmmArgs {
+    int S, K, n, m, w, slots, wpr;
+    int Sb;          // block-rows
+    int NT;          // column strips
+    int64_t Ncol, ldx, ldy;
+    const int32_t* row_ptr;
+    const int32_t* col_idx;
+    const uint16_t* vals;
+    const uint32_t* idxw;
+    const uint16_t* X;
+    void* Y;
+    int y_bf16;
+};
+
+__device__ __forceinline__ uint16_t float_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);  // NaN stays NaN
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+template <int WD>
+struct XVec;
+template <>
+struct XVec<1> { typedef uint32_t type; };
+template <>
+struct XVec<2> { typedef uint2 type; };
+
+template <int WD>
+__device__ __forceinline__ void xvec_unpack(const typename XVec<WD>::type& v, uint32_t (&d)[WD]);
+template <>
+__device__ __forceinline__ void xvec_unpack<1>(const uint32_t& v, uint32_t (&d)[1]) { d[0] = v; }
+template <>
+__device__ __forceinline__ void xvec_unpack<2>(const uint2& v, uint32_t (&d)[2]) { d[0] = v.x; d[1] = v.y; }
+
+// B: block edge (32 or 64).  WD: dwords a lane loads per X row (2*WD columns per lane, 64*WD
+// columns per wave).  NW: waves per workgroup (workgroup strip = NW*64*WD columns).
+template <int B, int WD, int NW>
+__global__ __launch_bounds__(64 * NW) void spmm_expand_mfma_kernel(SpmmArgs p) {
+    constexpr int RT = B / 32;            // 32-row MFMA tiles per block
+    constexpr int KS = B / 16;            // 16-deep MFMA steps per block
+    constexpr int NTHR = 64 * NW;
+    constexpr int A_BYTES = B * B * 2;    // dense bf16 tile
+    constexpr int STAGE_MAX = B * B * 2 + B * 6 * 4;           // values (n == m) + positions (8:8)
+    constexpr int NCHUNK = (STAGE_MAX / 16 + NTHR - 1) / NTHR;  // 16-byte chunks per thread
+    typedef typename XVec<WD>::type xvec_t;
+
+    __shared__ __attribute__((aligned(16))) unsigned char lds_a[2 * A_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char lds_stage[STAGE_MAX];
+
+    // Workgroup -> (block-row, column strip).  Consecutive workgroup ids go round-robin over the
+    // 8 XCDs; all block-rows of one column strip are given ids that land on the same XCD next to
+    // each other, so the X rows they share are served by that XCD's L2.
+    const int id = blockIdx.x;
+    const int xcd = id & 7;
+    const int slot = id >> 3;
+    const int bi = slot % p.Sb;
+    const int nt = (slot / p.Sb) * 8 + xcd;
+    if (nt >= p.NT) return;  // whole workgroup leaves before any barrier
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int jj = lane & 31, hh = lane >> 5;
+    const int64_t wave_col = ((int64_t)nt * NW + wave) * (64 * WD);
+    const bool wave_on = wave_col < p.Ncol;
+    const int64_t col0 = wave_col + jj * (2 * WD);
+    const bool col_ok = col0 < p.Ncol;
+    // Lanes past the last column read column 0 instead (in bounds); their results are never stored.
+    const uint16_t* xlane = p.X + (col_ok ? col0 : 0) + (int64_t)hh * 8 * p.ldx;
+
+    const int t_begin = p.row_ptr[bi], t_end = p.row_ptr[bi + 1];
+    const int vbytes = B * p.slots * 2;             // compressed values of one block
+    const int sbytes = vbytes + B * p.wpr * 4;      // + positions
+    const int G = B / p.m;
+
+    f32x16 acc[RT][2 * WD];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int c = 0; c < 2 * WD; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[rt][c][r] = 0.0f;
+
+    xvec_t xr[KS][8];
+    u32x4 raw[NCHUNK];
+
+    // ---- helpers -------------------------------------------------------------------------
+    auto load_raw = [&](int t) {
+#pragma unroll
+        for (int i = 0; i < NCHUNK; ++i) {
+            const int off = (tid + i * NTHR) * 16;
+            if (off < sbytes) {
+                const unsigned char* src = off < vbytes
+                    ? reinterpret_cast<const unsigned char*>(p.vals) + (size_t)t * vbytes + off
+                    : reinterpret_cast<const unsigned char*>(p.idxw) + (size_t)t * (sbytes - vbytes) + (off - vbytes);
+                raw[i] = *reinterpret_cast<const u32x4*>(src);
+            }
+        }
+    };
+    auto store_raw = [&]() {
+#pragma unroll
+        for (int i = 0; i < NCHUNK; ++i) {
+            const int off = (tid + i * NTHR) * 16;
+            if (off < sbytes) *reinterpret_cast<u32x4*>(lds_stage + off) = raw[i];
+        }
+    };
+    // Staging area -> dense tile in lds_a[buf], fragment-major:
+    //   element (row, kl) lives at ((rt*KS + ks)*64 + h*32 + j)*8 + e  with row = rt*32 + j,
+    //   kl = ks*16 + h*8 + e, i.e. exactly the 8 bf16 lane (h*32+j) feeds to MFMA step ks.
+    auto expand = [&](int buf) {
+        const uint16_t* sv = reinterpret_cast<const uint16_t*>(lds_stage);
+        const uint32_t* si = reinterpret_cast<const uint32_t*>(lds_stage + vbytes);
+        uint16_t* dst = reinterpret_cast<uint16_t*>(lds_a + buf * A_BYTES);
+        for (int e = tid; e < B * G; e += NTHR) {
+            const int r = e / G, g = e - r * G;
+            uint32_t d[4] = {0u, 0u, 0u, 0u};
+            for (int s = 0; s < p.n; ++s) {
+                const int q = g * p.n + s;
+                const int bit = q * p.w;
+                const int wi = bit >> 5;
+                uint64_t two = si[r * p.wpr + wi];
+                if (wi + 1 < p.wpr) two |= (uint64_t)si[r * p.wpr + wi + 1] << 32;
+                const uint32_t pos = (uint32_t)(two >> (bit & 31)) & (uint32_t)(p.m - 1);
+                const uint32_t v = (uint32_t)sv[r * p.slots + q] << ((pos & 1u) * 16u);
+                const uint32_t dw = pos >> 1;
+#pragma unroll
+                for (int x = 0; x < 4; ++x) d[x] |= (dw == (uint32_t)x) ? v : 0u;
+            }
+            const int kl = g * p.m;
+            const int rt = r >> 5, j = r & 31, ks = kl >> 4, h = (kl >> 3) & 1, e8 = kl & 7;
+            uint16_t* o = dst + ((((rt * KS + ks) * 64) + h * 32 + j) * 8 + e8);
+            if (p.m == 4) {
+                *reinterpret_cast<uint2*>(o) = make_uint2(d[0], d[1]);
+            } else {
+                u32x4 v4 = {d[0], d[1], d[2], d[3]};
+                *reinterpret_cast<u32x4*>(o) = v4;
+            }
+        }
+    };
+    // X rows of block column bj, MFMA step ks: lane (hh, jj) takes rows bj*B + ks*16 + hh*8 + i.
+    auto load_x = [&](xvec_t (&dst)[8], int bj, int ks) {
+        const int kbase = bj * B + ks * 16;
+        const uint16_t* src = xlane + (int64_t)kbase * p.ldx;
+        if (kbase + 16 <= p.K) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) dst[i] = *reinterpret_cast<const xvec_t*>(src + (int64_t)i * p.ldx);
+        } else {
+            // ragged last block column: rows >= K do not exist; they must read as zero because
+            // the matching weights are zero padding and 0 * garbage could be NaN
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                xvec_t z = {};
+                if (kbase + hh * 8 + i < p.K) z = *reinterpret_cast<const xvec_t*>(src + (int64_t)i * p.ldx);
+                dst[i] = z;
+            }
+        }
+    };
+
+    // ---- prologue ------------------------------------------------------------------------
+    if (t_begin < t_end) {
+        load_raw(t_begin);
+        if (wave_on) {
+            const int bj = p.col_idx[t_begin];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) load_x(xr[ks], bj, ks);
+        }
+        store_raw();
+        __syncthreads();
+        expand(0);
+        __syncthreads();
+    }
+
+    // ---- walk the kept blocks of this block-row -------------------------------------------
+    for (int t = t_begin; t < t_end; ++t) {
+        const int buf = (t - t_begin) & 1;
+        const bool has_next = t + 1 < t_end;
+        const int bj_next = has_next ? p.col_idx[t + 1] : 0;
+        if (has_next) load_raw(t + 1);
+        if (wave_on) {
+            const unsigned char* abase = lds_a + buf * A_BYTES + lane * 16;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                // 8 rows x 2*WD columns of 16-bit halves -> 2*WD operands of 8 K-values each
+                uint32_t xd[8][WD];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) xvec_unpack<WD>(xr[ks][i], xd[i]);
+                bf16x8 bfrag[2 * WD];
+#pragma unroll
+                for (int pdw = 0; pdw < WD; ++pdw) {
+                    u32x4 lo, hi;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const uint32_t r0 = xd[2 * q][pdw], r1 = xd[2 * q + 1][pdw];
+                        lo[q] = (r0 & 0xFFFFu) | (r1 << 16);
+                        hi[q] = (r0 >> 16) | (r1 & 0xFFFF0000u);
+                    }
+                    bfrag[2 * pdw] = __builtin_bit_cast(bf16x8, lo);
+                    bfrag[2 * pdw + 1] = __builtin_bit_cast(bf16x8, hi);
+                }
+                if (has_next) load_x(xr[ks], bj_next, ks);
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) {
+                    const u32x4 av = *reinterpret_cast<const u32x4*>(abase + (rt * KS + ks) * 1024);
+                    const bf16x8 afrag = __builtin_bit_cast(bf16x8, av);
+#pragma unroll
+                    for (int c = 0; c < 2 * WD; ++c)
+                        acc[rt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag[c], acc[rt][c], 0, 0, 0);
+                }
+            }
+        }
+        if (has_next) store_raw();
+        __syncthreads();
+        if (has_next) expand(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: accumulator register r of a 32x32 tile is row 8*(r/4) + 4*hh + r%4,
+    //      column jj; the 2*WD accumulators of a lane are consecutive columns ---------------
+    if (!wave_on || !col_ok) return;
+    const bool full = col0 + 2 * WD <= p.Ncol;
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = bi * B + rt * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
+            if (row >= p.S) continue;
+            float v[2 * WD];
+#pragma unroll
+            for (int c = 0; c < 2 * WD; ++c) v[c] = acc[rt][c][r];
+            if (p.y_bf16) {
+                uint16_t* y = reinterpret_cast<uint16_t*>(p.Y) + (int64_t)row * p.ldy + col0;
+                if (full) {
+                    uint32_t pk[WD];
+#pragma unroll
+                    for (int c = 0; c < WD; ++c)
+                        pk[c] = float_to_bf16_rne(v[2 * c]) | ((uint32_t)float_to_bf16_rne(v[2 * c + 1]) << 16);
+                    if (WD == 1) *reinterpret_cast<uint32_t*>(y) = pk[0];
+                    else *reinterpret_cast<uint2*>(y) = make_uint2(pk[0], pk[WD - 1]);
+                } else {
+#pragma unroll
+                    for (int c = 0; c < 2 * WD; ++c)
+                        if (col0 + c < p.Ncol) y[c] = float_to_bf16_rne(v[c]);
+                }
+            } else {
+                float* y = reinterpret_cast<float*>(p.Y) + (int64_t)row * p.ldy + col0;
+                if (full) {
+                    if (WD == 1) *reinterpret_cast<float2*>(y) = make_float2(v[0], v[1]);
+                    else *reinterpret_cast<float4*>(y) = make_float4(v[0], v[1], v[2 * WD - 2], v[2 * WD - 1]);
+                } else {
+#pragma unroll
+                    for (int c = 0; c < 2 * WD; ++c)
+                        if (col0 + c < p.Ncol) y[c] = v[c];
+                }
+            }
+        }
+}
+
+template <int B, int WD, int NW>
+static hipError_t launch_one(const SpmmArgs& a, hipStream_t st) {
+    SpmmArgs p = a;
+    const int64_t strip = (int64_t)NW * 64 * WD;
+    p.NT = (int)((a.Ncol + strip - 1) / strip);
+    const int64_t groups = (int64_t)((p.NT + 7) / 8) * p.Sb * 8;
+    if (groups > INT32_MAX) return hipErrorInvalidValue;
+    spmm_expand_mfma_kernel<B, WD, NW><<<dim3((unsigned)groups), dim3(64 * NW), 0, st>>>(p);
+    return hipGetLastError();
+}
+
+hipError_t launch_spmm(const Geometry& g, const int32_t* row_ptr, const int32_t* col_idx, const uint16_t* vals,
+                       const uint32_t* idxw, const uint16_t* X, int64_t Ncol, int64_t ldx, void* Y, int64_t ldy,
+                       int y_dtype, hipStream_t st) {
+    SpmmArgs a;
+    a.S = g.S; a.K = g.K; a.n = g.n; a.m = g.m; a.w = g.w; a.slots = g.slots; a.wpr = g.wpr;
+    a.Sb = g.Sb; a.NT = 0; a.Ncol = Ncol; a.ldx = ldx; a.ldy = ldy;
+    a.row_ptr = row_ptr; a.col_idx = col_idx; a.vals = vals; a.idxw = idxw; a.X = X; a.Y = Y;
+    a.y_bf16 = (y_dtype == CRISP_Y_BF16);
+    // Strip width: wide strips (more reuse of the expanded tile, wider loads) once there are
+    // enough of them to fill 256 CUs, narrow ones for small problems.
+    const int64_t wide_groups = ((Ncol + 511) / 512) * g.Sb;
+    const bool wide = wide_groups >= 512;
+    if (g.B == 64) return wide ? launch_one<64, 2, 4>(a, st) : launch_one<64, 1, 4>(a, st);
+    return wide ? launch_one<32, 2, 4>(a, st) : launch_one<32, 1, 4>(a, st);
+}
+
+}  // namespace crisp

@@ -1,0 +1,72 @@
+"""Helpers for the GPU tests: numpy <-> device memory, and one run of the HIP path per layer."""
+import numpy as np
+import torch
+
+from paper_2311_14272_amd import crisp
+
+
+def dev(a: np.ndarray):
+    """Upload a numpy array; 16/32-bit unsigned patterns travel as signed torch dtypes."""
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    elif a.dtype == np.uint32:
+        a = a.view(np.int32)
+    return torch.from_numpy(a).cuda()
+
+
+def host(t, dtype):
+    a = t.cpu().numpy()
+    return a.view(dtype) if a.dtype != dtype else a
+
+
+def desc_of(L):
+    return crisp.layer_desc(L.S, L.K, L.n, L.m, L.B, L.density, L.sal_kind, L.select_mode)
+
+
+def run_select_pack(L, W, G):
+    """crisp_select_mask + crisp_pack on the device; returns the DeviceLayer and host copies."""
+    layer = crisp.alloc_layer(desc_of(L))
+    dW = dev(W)
+    dG = dev(G) if G is not None else None
+    crisp.prune_and_pack(layer, dW, dG)
+    torch.cuda.synchronize()
+    sz = layer.sizes
+    out = dict(
+        nm_bits=host(layer.nm_mask, np.uint32)[: sz.mask_words].reshape(L.S, sz.mask_words_per_row),
+        row_ptr=host(layer.row_ptr, np.int32),
+        col_idx=host(layer.col_idx, np.int32)[: sz.nk],
+        score=host(layer.score, np.float64).reshape(sz.Sb, sz.Kb),
+        vals=host(layer.vals, np.uint16)[: sz.vals_elems].reshape(sz.nk, L.B, sz.slots_per_row),
+        idxw=host(layer.idx_words, np.uint32)[: sz.idx_words].reshape(sz.nk, L.B, sz.idx_words_per_row),
+        flags=host(layer.flags, np.int32))
+    return layer, out
+
+
+def run_spmm(layer, dX, Ncol, ldx, y_dtype, S, ldy=None, fill=None):
+    """crisp_spmm into a fresh Y with a guard band of columns (ldy > Ncol) that must stay untouched."""
+    if ldy is None:
+        ldy = (Ncol + 7) // 8 * 8 + 8
+    tdt = torch.float32 if y_dtype == crisp.Y_F32 else torch.bfloat16
+    Y = torch.full((S + 1, ldy), float("nan") if fill is None else fill, dtype=tdt, device="cuda")
+    crisp.crisp_spmm(layer.desc, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dX, Ncol, ldx, Y, ldy,
+                     y_dtype)
+    torch.cuda.synchronize()
+    Yh = Y.float().cpu().numpy().astype(np.float64)
+    assert np.isnan(Yh[:S, Ncol:]).all(), "columns beyond Ncol were written"
+    assert np.isnan(Yh[S]).all(), "row beyond S was written"
+    return Yh[:S, :Ncol]
+
+
+def check_product(Y, Yref, Aref, y_dtype, what=""):
+    """Tolerance of the product: relative Frobenius error <= 2e-3 and |err| <= 1e-2 * (|W||X|)
+    element-wise (bf16 inputs, fp32 accumulation).  With fp32 output the only error source is
+    the summation order, so a much tighter tripwire of 1e-5 applies as well."""
+    assert np.isfinite(Y).all(), what
+    err = np.abs(Y - Yref)
+    fro = np.linalg.norm(Y - Yref) / max(np.linalg.norm(Yref), 1e-300)
+    assert fro <= 2e-3, (what, fro)
+    assert (err <= 1e-2 * Aref + 1e-30).all(), (what, float((err - 1e-2 * Aref).max()))
+    if y_dtype == crisp.Y_F32:
+        assert fro <= 1e-5, (what, fro)
+    return fro

@@ -1,0 +1,128 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every entry
+point the header declares, and rejects bad arguments before touching a device."""
+import ctypes as C
+import os
+import re
+import subprocess
+
+import pytest
+
+from paper_2311_14272_amd import crisp
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "crisp.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    return sorted(set(re.findall(r"CRISP_API[^;(]*?\b(crisp_\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert names == ["crisp_im2col", "crisp_pack", "crisp_pack_sizes", "crisp_select_mask", "crisp_spmm",
+                     "crisp_status_str"]
+    L = crisp.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+    out = subprocess.run(["nm", "-D", "--defined-only", crisp.LIB_PATH], capture_output=True, text=True).stdout
+    exported = {l.split()[-1] for l in out.splitlines() if " T " in l}
+    assert set(names) <= exported
+    assert all(e.startswith("crisp_") or e.startswith("_") for e in exported)
+
+
+def test_header_compiles_as_c():
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-fsyntax-only", "-x", "c", HEADER],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+
+
+def test_struct_layout_matches_header():
+    src = r'''
+    #include <stdio.h>
+    #include <stddef.h>
+    #include "crisp.h"
+    int main(void) {
+      printf("%zu %zu %zu %zu %zu %zu\n", sizeof(crisp_layer_desc), offsetof(crisp_layer_desc, S),
+             sizeof(crisp_sizes), offsetof(crisp_sizes, mask_words), offsetof(crisp_sizes, select_ws_bytes),
+             sizeof(crisp_conv_desc));
+      return 0; }'''
+    exe = "/tmp/crisp_layout_check"
+    r = subprocess.run(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), "-x", "c", "-", "-o", exe],
+                       input=src, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    got = [int(x) for x in subprocess.run([exe], capture_output=True, text=True).stdout.split()]
+    assert got == [C.sizeof(crisp.LayerDesc), crisp.LayerDesc.S.offset, C.sizeof(crisp.Sizes),
+                   crisp.Sizes.mask_words.offset, crisp.Sizes.select_ws_bytes.offset, C.sizeof(crisp.ConvDesc)]
+
+
+def test_pack_sizes_values():
+    sz = crisp.crisp_pack_sizes(crisp.layer_desc(256, 1152, 2, 4, 32, 0.5))
+    assert (sz.Sb, sz.Kb, sz.k_row, sz.nk) == (8, 36, 18, 144)
+    assert (sz.slots_per_row, sz.idx_bits, sz.idx_words_per_row) == (16, 2, 1)
+    assert sz.vals_elems == 144 * 32 * 16 and sz.idx_words == 144 * 32
+    assert sz.mask_words == 256 * 36 and sz.row_ptr_elems == 9 and sz.score_elems == 8 * 36
+    sz = crisp.crisp_pack_sizes(crisp.layer_desc(24, 144, 2, 4, 32, 0.6))
+    assert (sz.Sb, sz.Kb, sz.k_row, sz.nk) == (1, 5, 3, 3)
+    sz = crisp.crisp_pack_sizes(crisp.layer_desc(64, 147, 4, 8, 64, 0.5))
+    assert (sz.Sb, sz.Kb, sz.k_row) == (1, 3, 2) and sz.idx_words_per_row == 3 and sz.mask_words_per_row == 5
+    for cfg, kr in (((256, 1024, 1, 4, 64, 0.3), 5), ((256, 2304, 1, 4, 64, 0.3), 11), ((1024, 256, 1, 4, 64, 0.3), 1),
+                    ((512, 4608, 2, 8, 64, 0.25), 18), ((160, 960, 2, 4, 32, 0.6), 18)):
+        assert crisp.crisp_pack_sizes(crisp.layer_desc(*cfg)).k_row == kr
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(m=5), crisp.EINVAL), (dict(n=0), crisp.EINVAL), (dict(n=5), crisp.EINVAL), (dict(B=48), crisp.EINVAL),
+    (dict(B=16, m=8, n=2), None), (dict(block_density=0.0), crisp.EINVAL), (dict(block_density=1.5), crisp.EINVAL),
+    (dict(block_density=float("nan")), crisp.EINVAL), (dict(S=0), crisp.ESHAPE), (dict(K=-3), crisp.ESHAPE),
+    (dict(sal_kind=7), crisp.EINVAL), (dict(select_mode=2), crisp.EINVAL)])
+def test_descriptor_validation(kw, status):
+    base = dict(S=64, K=128, n=2, m=4, B=32, block_density=0.5)
+    base.update(kw)
+    d = crisp.layer_desc(**base)
+    if status is None:
+        crisp.crisp_pack_sizes(d)
+        return
+    with pytest.raises(crisp.CrispError) as e:
+        crisp.crisp_pack_sizes(d)
+    assert e.value.status == status
+
+
+def test_entry_points_reject_bad_arguments_without_a_device():
+    L = crisp.lib()
+    d = crisp.layer_desc(64, 128, 2, 4, 32, 0.5)
+    fake = 0x1000  # never dereferenced: every call below must fail validation first
+    assert L.crisp_select_mask(C.byref(d), None, None, None, None, None, None, None, 0, None) == crisp.EINVAL
+    assert L.crisp_select_mask(C.byref(d), fake, None, fake, fake, fake, None, None, 0, None) == crisp.EBUFSIZE
+    assert L.crisp_select_mask(C.byref(d), fake + 2, None, fake, fake, fake, fake, None, 0, None) == crisp.EALIGN
+    dg = crisp.layer_desc(64, 128, 2, 4, 32, 0.5, sal_kind=crisp.SAL_GRAD)
+    assert L.crisp_select_mask(C.byref(dg), fake, None, fake, fake, fake, fake, None, 0, None) == crisp.EINVAL
+    assert L.crisp_pack(C.byref(d), fake, fake, fake, fake, None, fake, fake, None, 0, None) == crisp.EINVAL
+    assert L.crisp_pack(C.byref(d), fake, fake, fake, fake, fake + 8, fake, fake, None, 0, None) == crisp.EALIGN
+    spmm = lambda **k: L.crisp_spmm(C.byref(k.get("d", d)), fake, fake, fake, fake, k.get("X", fake), k.get("N", 64),
+                                    k.get("ldx", 64), k.get("xl", 0), k.get("Y", fake), k.get("ldy", 64),
+                                    k.get("yd", 0), None, 0, None)
+    assert spmm(X=None) == crisp.EINVAL
+    assert spmm(N=0) == crisp.ESHAPE
+    assert spmm(ldx=56) == crisp.ESHAPE
+    assert spmm(N=60, ldx=60, ldy=64) == crisp.EALIGN
+    assert spmm(ldy=100, N=64) == crisp.EALIGN
+    assert spmm(yd=3) == crisp.EINVAL
+    assert spmm(xl=1) == crisp.EUNSUPPORTED
+    assert spmm(d=crisp.layer_desc(64, 128, 2, 4, 16, 0.5)) == crisp.EUNSUPPORTED
+    assert spmm(Y=fake + 4) == crisp.EALIGN
+    cv = crisp.ConvDesc(3, 8, 8, 1, 3, 3, 1, 1, 0, 0)
+    assert L.crisp_im2col(C.byref(cv), None, fake, 64, None) == crisp.EINVAL
+    assert L.crisp_im2col(C.byref(cv), fake, fake, 8, None) == crisp.ESHAPE
+    cv2 = crisp.ConvDesc(3, 2, 2, 1, 5, 5, 1, 0, 0, 0)
+    assert L.crisp_im2col(C.byref(cv2), fake, fake, 64, None) == crisp.ESHAPE
+    cv3 = crisp.ConvDesc(3, 8, 8, 1, 3, 3, 1, 1, 1, 0)
+    assert L.crisp_im2col(C.byref(cv3), fake, fake, 64, None) == crisp.EUNSUPPORTED
+    assert crisp.status_str(crisp.EALIGN).startswith("misaligned")
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(crisp, "_lib", None)
+    monkeypatch.setattr(crisp, "LIB_PATH", "/nonexistent/libcrisp.so")
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        crisp.lib()

@@ -1,0 +1,161 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs:
+masks, block scores, block lists and packing bit-exact; products within the stated tolerance."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2311_14272_amd import crisp, synth
+
+from gpu_util import check_product, desc_of, dev, host, run_select_pack, run_spmm
+
+pytestmark = pytest.mark.gpu
+
+
+def oracle_all(L, W, G):
+    sel = oracle.select(W, G, L.n, L.m, L.B, L.density, L.sal_kind, L.select_mode)
+    vals, idxw, flags = oracle.pack(W, sel.keep, L.n, L.m, L.B, sel.row_ptr, sel.col_idx)
+    return sel, vals, idxw, flags
+
+
+def assert_select_pack_equal(L, out, sel, vals, idxw, flags):
+    assert (out["nm_bits"] == sel.nm_bits).all(), "n:m mask"
+    assert (out["score"].view(np.uint64) == sel.score.view(np.uint64)).all(), "block scores (bit pattern)"
+    assert (out["row_ptr"] == sel.row_ptr).all(), "row_ptr"
+    assert (out["col_idx"] == sel.col_idx).all(), "col_idx"
+    assert (out["vals"] == vals).all(), "packed values"
+    assert (out["idxw"] == idxw).all(), "packed positions"
+    assert out["flags"][0] == flags[0], "2-of-4 flag"
+
+
+@pytest.mark.parametrize("L", synth.small_cases(), ids=lambda L: L.name)
+def test_small_cases_end_to_end(L):
+    print("case", L.name, flush=True)
+    W, G, X = synth.draw_small(L, 21)
+    sel, vals, idxw, flags = oracle_all(L, W, G)
+    layer, out = run_select_pack(L, W, G)
+    assert_select_pack_equal(L, out, sel, vals, idxw, flags)
+    Yref, Aref = oracle.gemm_masked(W, sel.mask, X)
+    ldx = (L.Ncol + 7) // 8 * 8
+    Xp = np.zeros((L.K, ldx), dtype=np.uint16)
+    Xp[:, : L.Ncol] = X
+    # poison the padding columns: they must not leak into valid outputs
+    Xp[:, L.Ncol:] = 0x7FC0
+    dX = dev(Xp)
+    for yd in (crisp.Y_F32, crisp.Y_BF16):
+        Y = run_spmm(layer, dX, L.Ncol, ldx, yd, L.S)
+        check_product(Y, Yref, Aref, yd, L.name)
+
+
+@pytest.mark.parametrize("L", synth.small_cases()[:6], ids=lambda L: L.name)
+def test_spmm_from_oracle_pack(L):
+    """The product kernel alone, fed with the oracle's packed structure."""
+    print("case", L.name, flush=True)
+    W, G, X = synth.draw_small(L, 22)
+    sel, vals, idxw, flags = oracle_all(L, W, G)
+    layer = crisp.alloc_layer(desc_of(L))
+    layer.row_ptr.copy_(dev(sel.row_ptr))
+    layer.col_idx[: sel.col_idx.size].copy_(dev(sel.col_idx))
+    layer.vals[: vals.size].copy_(dev(vals.reshape(-1)))
+    layer.idx_words[: idxw.size].copy_(dev(idxw.reshape(-1)))
+    ldx = (L.Ncol + 7) // 8 * 8
+    Xp = np.zeros((L.K, ldx), dtype=np.uint16)
+    Xp[:, : L.Ncol] = X
+    Yref, Aref = oracle.gemm_masked(W, sel.mask, X)
+    Y = run_spmm(layer, dev(Xp), L.Ncol, ldx, crisp.Y_F32, L.S)
+    check_product(Y, Yref, Aref, crisp.Y_F32, L.name)
+
+
+def test_ties_and_zero_weights():
+    """Constant saliency (every comparison is a tie) and weights with exact zeros / negative zeros."""
+    L = synth.LayerSpec("ties", 64, 128, 64, 2, 4, 32, 0.5, synth.SAL_GIVEN, 1.0)
+    rng = np.random.default_rng(3)
+    Wf = rng.standard_normal((L.S, L.K)).astype(np.float32)
+    Wf[rng.random((L.S, L.K)) < 0.3] = 0.0
+    Wf[rng.random((L.S, L.K)) < 0.1] = -0.0
+    W = synth.f32_to_bf16_bits(Wf)
+    for T in (np.ones((L.S, L.K), dtype=np.float32),
+              rng.integers(0, 3, (L.S, L.K)).astype(np.float32)):
+        sel, vals, idxw, flags = oracle_all(L, W, T)
+        layer, out = run_select_pack(L, W, T)
+        assert_select_pack_equal(L, out, sel, vals, idxw, flags)
+
+
+def test_im2col_matches_oracle():
+    rng = np.random.default_rng(5)
+    for (C_, H, Wd, b, kh, kw, st, pad) in [(3, 9, 8, 2, 3, 3, 1, 1), (4, 8, 8, 1, 1, 1, 2, 0), (2, 11, 11, 2, 7, 7, 2, 3),
+                                            (16, 14, 14, 3, 3, 3, 1, 1), (8, 15, 13, 2, 3, 3, 2, 1), (5, 6, 7, 3, 1, 1, 1, 0)]:
+        print("im2col", C_, H, Wd, b, kh, kw, st, pad, flush=True)
+        act = synth.f32_to_bf16_bits(rng.standard_normal((C_, b, H, Wd)).astype(np.float32))
+        Xref = oracle.im2col(act, kh, kw, st, pad)
+        K, Ncol = Xref.shape
+        for ldx in ((Ncol + 7) // 8 * 8, Ncol + 3):
+            X = torch.full((K, ldx), -1, dtype=torch.int16, device="cuda")
+            cv = crisp.ConvDesc(C_, H, Wd, b, kh, kw, st, pad, crisp.ACT_CBHW, crisp.X_KN)
+            crisp.crisp_im2col(cv, dev(act), X, ldx)
+            torch.cuda.synchronize()
+            Xh = host(X, np.uint16)
+            assert (Xh[:, :Ncol] == Xref).all()
+            assert (Xh[:, Ncol:] == 0xFFFF).all()
+
+
+def _sample_columns(Ncol, count, rng):
+    """First strip, last (ragged) strip and random columns."""
+    cols = set(range(min(Ncol, 96))) | set(range(max(0, Ncol - 96), Ncol))
+    cols |= set(int(c) for c in rng.integers(0, Ncol, count))
+    return np.array(sorted(cols), dtype=np.int64)
+
+
+@pytest.mark.parametrize("cid", [1, 2, 3, 4])
+def test_config_full_size(cid):
+    """The benchmark workloads at full size, in the launch configuration bench.py times.
+    Selection and packing are compared in full; the product on all columns when the oracle
+    finishes in seconds, otherwise on sampled columns (each output column is an independent sum)."""
+    wl = synth.config(cid)
+    for li, L in enumerate(wl.layers):
+        print("config", wl.name, L.name, flush=True)
+        t = synth.draw_layer(wl, li)
+        W, G = t["W"], t["G"]
+        sel, vals, idxw, flags = oracle_all(L, W, G)
+        layer, out = run_select_pack(L, W, G)
+        assert_select_pack_equal(L, out, sel, vals, idxw, flags)
+        if t["X"] is None:
+            cv = L.conv
+            dact = dev(t["act"])
+            dX = torch.empty((L.K, L.Ncol), dtype=torch.int16, device="cuda")
+            crisp.crisp_im2col(crisp.ConvDesc(cv.C, cv.H, cv.W, cv.batch, cv.kh, cv.kw, cv.stride, cv.pad, 0, 0),
+                               dact, dX, L.Ncol)
+            torch.cuda.synchronize()
+            X = host(dX, np.uint16)
+            assert (X == oracle.im2col(t["act"], cv.kh, cv.kw, cv.stride, cv.pad)).all()
+        else:
+            X = t["X"]
+            dX = dev(X)
+        rng = np.random.default_rng(cid * 10 + li)
+        full = L.S * L.K * L.Ncol <= 4e9
+        cols = np.arange(L.Ncol) if full else _sample_columns(L.Ncol, 1500, rng)
+        Xs = np.ascontiguousarray(X[:, cols])
+        Yref, Aref = oracle.gemm_masked(W, sel.mask, Xs)
+        for yd in (crisp.Y_F32, crisp.Y_BF16):
+            Y = run_spmm(layer, dX, L.Ncol, L.Ncol, yd, L.S, ldy=L.Ncol)
+            check_product(Y[:, cols], Yref, Aref, yd, L.name)
+            if not full:
+                # properties that hold at any size: rows of all-zero weight rows are zero, output finite
+                assert np.isfinite(Y).all()
+                dead = ~sel.mask.any(axis=1)
+                assert (Y[dead] == 0).all()
+        del dX
+        torch.cuda.empty_cache()
+
+
+def test_determinism():
+    L = synth.small_cases()[1]
+    W, G, X = synth.draw_small(L, 30)
+    layer, _ = run_select_pack(L, W, G)
+    ldx = (L.Ncol + 7) // 8 * 8
+    Xp = np.zeros((L.K, ldx), dtype=np.uint16)
+    Xp[:, : L.Ncol] = X
+    dX = dev(Xp)
+    a = run_spmm(layer, dX, L.Ncol, ldx, crisp.Y_F32, L.S)
+    b = run_spmm(layer, dX, L.Ncol, ldx, crisp.Y_F32, L.S)
+    assert (a == b).all()
