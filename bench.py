@@ -1,0 +1,260 @@
+#!/usr/bin/env python3
+"""Benchmark of the CRISP hybrid-sparse hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input: for every layer of the
+workload crisp_select_mask + crisp_pack (saliency, N:M choice, block scores, block choice,
+packing), crisp_im2col for the layers that are real convolutions, crisp_spmm.  Inputs are
+resident in HBM before the timed region; batches rotate through several independent input sets
+so that consecutive steps do not find their activations in the last-level cache.
+
+Prints one JSON line: effective TFLOP/s counting only non-zero-weight FLOPs (whole step), the
+roofline of the dominant kernel measured with events on the launch stream, and the CPU oracle
+timed on the host cores as a reported baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, help="workload 1..4 (default 2: ResNet-50 stage-3 bottleneck)")
+    ap.add_argument("--sets", type=int, default=0, help="independent input sets to rotate through (0 = enough for 600 MB)")
+    ap.add_argument("--y-dtype", choices=["bf16", "f32"], default="bf16")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--spmm-only", action="store_true", help="time only the products (selection and packing done once)")
+    return ap.parse_args()
+
+
+class LayerState:
+    pass
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2311_14272_amd import crisp, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    crisp.lib()
+    dev = "cuda"
+    wl = synth.config(args.config)
+    y_dtype = crisp.Y_BF16 if args.y_dtype == "bf16" else crisp.Y_F32
+    ybytes = 2 if y_dtype == crisp.Y_BF16 else 4
+    ytorch = torch.bfloat16 if y_dtype == crisp.Y_BF16 else torch.float32
+
+    def to_dev(a):
+        a = np.ascontiguousarray(a)
+        if a.dtype == np.uint16:
+            a = a.view(np.int16)
+        return torch.from_numpy(a).to(dev)
+
+    # ---- resident data ------------------------------------------------------------------
+    host_inputs = [synth.draw_layer(wl, i) for i in range(len(wl.layers))]
+    per_set = 0
+    for L in wl.layers:
+        per_set += 2 * L.K * L.Ncol + ybytes * L.S * L.Ncol
+        if L.conv is not None and (L.conv.kh > 1 or L.conv.stride > 1):
+            per_set += 2 * L.conv.C * L.conv.batch * L.conv.H * L.conv.W
+    nsets = args.sets if args.sets > 0 else max(2, min(16, int(600e6 // per_set) + 1))
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(wl.seed)
+    layers = []
+    for i, L in enumerate(wl.layers):
+        st = LayerState()
+        st.L = L
+        st.desc = crisp.layer_desc(L.S, L.K, L.n, L.m, L.B, L.density, L.sal_kind, L.select_mode)
+        st.dl = crisp.alloc_layer(st.desc, dev)
+        st.W = to_dev(host_inputs[i]["W"])
+        st.G = to_dev(host_inputs[i]["G"]) if host_inputs[i]["G"] is not None else None
+        cv = L.conv
+        st.is_conv = cv is not None and (cv.kh > 1 or cv.kw > 1 or cv.stride > 1)
+        st.conv = crisp.ConvDesc(cv.C, cv.H, cv.W, cv.batch, cv.kh, cv.kw, cv.stride, cv.pad, crisp.ACT_CBHW,
+                                 crisp.X_KN) if st.is_conv else None
+        st.act, st.X, st.Y = [], [], []
+        for s in range(nsets):
+            if st.is_conv:
+                if s == 0:
+                    a = to_dev(host_inputs[i]["act"])
+                else:
+                    a = torch.randn((cv.C, cv.batch, cv.H, cv.W), generator=gen, device=dev).clamp_(min=0).to(torch.bfloat16).view(torch.int16)
+                st.act.append(a)
+                st.X.append(torch.empty((L.K, L.Ncol), dtype=torch.int16, device=dev))
+            else:
+                if s == 0:
+                    x = to_dev(host_inputs[i]["X"])
+                else:
+                    x = torch.randn((L.K, L.Ncol), generator=gen, device=dev).clamp_(min=0).to(torch.bfloat16).view(torch.int16)
+                st.X.append(x)
+            st.Y.append(torch.empty((L.S, L.Ncol), dtype=ytorch, device=dev))
+        layers.append(st)
+
+    def prune(st):
+        crisp.prune_and_pack(st.dl, st.W, st.G)
+
+    def forward(st, s, events=None):
+        L = st.L
+        if st.is_conv:
+            crisp.crisp_im2col(st.conv, st.act[s], st.X[s], L.Ncol)
+        if events is not None:
+            events[0].record()
+        crisp.crisp_spmm(st.desc, st.dl.row_ptr, st.dl.col_idx, st.dl.vals, st.dl.idx_words, st.X[s], L.Ncol, L.Ncol,
+                         st.Y[s], L.Ncol, y_dtype)
+        if events is not None:
+            events[1].record()
+
+    def step(k, dom=None, events=None):
+        s = k % nsets
+        for i, st in enumerate(layers):
+            if not args.spmm_only:
+                prune(st)
+            forward(st, s, events if i == dom else None)
+
+    # ---- one untimed pass to learn the mask statistics (metric bookkeeping, from device output) ----
+    for st in layers:
+        prune(st)
+    torch.cuda.synchronize()
+    info = []
+    for st in layers:
+        L, sz = st.L, st.dl.sizes
+        row_ptr = st.dl.row_ptr.cpu().numpy()
+        col_idx = st.dl.col_idx.cpu().numpy()[: sz.nk]
+        bits = st.dl.nm_mask.cpu().numpy().view(np.uint32)[: sz.mask_words].reshape(L.S, sz.mask_words_per_row)
+        keep = np.unpackbits(bits.view(np.uint8), axis=1, bitorder="little")[:, : L.K]
+        ones = 0
+        for bi in range(sz.Sb):
+            for bj in col_idx[row_ptr[bi]:row_ptr[bi + 1]]:
+                ones += int(keep[bi * L.B:(bi + 1) * L.B, bj * L.B:(bj + 1) * L.B].sum())
+        used_cols = np.unique(col_idx)
+        k_used = int(sum(min(L.K, (bj + 1) * L.B) - bj * L.B for bj in used_cols))
+        kept_vals = sz.nk * L.B * sz.slots_per_row
+        w_bytes = kept_vals * 2 + sz.idx_words * 4 + sz.nk * 4 + (sz.Sb + 1) * 4
+        alg_bytes = 2 * k_used * L.Ncol + ybytes * L.S * L.Ncol + w_bytes
+        info.append(dict(name=L.name, S=L.S, K=L.K, Ncol=L.Ncol, nm="%d:%d" % (L.n, L.m), B=L.B, k_row=sz.k_row,
+                         ones=ones, useful_flop=2.0 * ones * L.Ncol, dense_flop=2.0 * L.S * L.K * L.Ncol,
+                         alg_bytes=alg_bytes, smfmac_ok=int(st.dl.flags.cpu()[0])))
+    useful = sum(x["useful_flop"] for x in info)
+    dense_eq = sum(x["dense_flop"] for x in info)
+    dom = int(np.argmax([x["alg_bytes"] for x in info]))   # dominant kernel: the product with the most traffic
+
+    # ---- warm-up, then the timed region ----------------------------------------------------
+    for k in range(args.warmup):
+        step(k)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(args.warmup + k, dom, ev[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    dom_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    dom_med_ms = float(np.median([a.elapsed_time(b) for a, b in ev]))
+
+    # ---- per-phase breakdown (untimed extras, reported for context) --------------------------
+    def timed(fn, reps=50):
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for r in range(reps):
+            fn(r)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    for i, st in enumerate(layers):
+        info[i]["prune_pack_ms"] = round(timed(lambda r, st=st: prune(st)), 5)
+        info[i]["forward_ms"] = round(timed(lambda r, st=st: forward(st, r % nsets)), 5)
+        fw = info[i]["forward_ms"] * 1e-3
+        info[i]["useful_tflops_forward"] = round(info[i]["useful_flop"] / fw / 1e12, 3)
+        info[i]["hbm_frac_forward"] = round(info[i]["alg_bytes"] / fw / 1e9 / HBM_PEAK_GBS, 4)
+
+    achieved = info[dom]["alg_bytes"] / (dom_ms * 1e-3) / 1e9
+    out = {
+        "metric": "effective TFLOP/s (nonzero FLOPs) of hybrid-sparse GEMM + % roofline",
+        "value": round(useful / (ms_per_step * 1e-3) / 1e12, 4),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "%s: %s" % (wl.name, ", ".join("%s %dx%dx%d %s B%d k_row %d" % (
+            x["name"], x["S"], x["K"], x["Ncol"], x["nm"], x["B"], x["k_row"]) for x in info)),
+                   "step": "select_mask+pack+im2col+spmm per layer" if not args.spmm_only else "im2col+spmm per layer",
+                   "y_dtype": args.y_dtype, "x_layout": "KN", "input_sets": nsets},
+        "dense_equivalent_tflops": round(dense_eq / (ms_per_step * 1e-3) / 1e12, 3),
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": TRAFFIC.get((wl.name, info[dom]["name"], args.y_dtype)),
+                     "kernel": "spmm_expand_mfma_kernel (%s)" % info[dom]["name"],
+                     "avg_launch_ms": round(dom_ms, 5), "median_launch_ms": round(dom_med_ms, 5),
+                     "algorithmic_bytes": info[dom]["alg_bytes"]},
+        "layers": info,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, host_inputs, useful)
+    print(json.dumps(out))
+
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE,
+# scaled by the same counters on a plain copy of known size); filled in from profiles/.
+TRAFFIC = {}
+
+
+def cpu_baseline(wl, host_inputs, useful_flop):
+    """The CPU oracle as it stands, timed on the host cores on the same workload (one pass)."""
+    import oracle
+    t0 = time.perf_counter()
+    for i, L in enumerate(wl.layers):
+        h = host_inputs[i]
+        sel = oracle.select(h["W"], h["G"], L.n, L.m, L.B, L.density, L.sal_kind, L.select_mode)
+        oracle.pack(h["W"], sel.keep, L.n, L.m, L.B, sel.row_ptr, sel.col_idx)
+        X = h["X"]
+        if X is None:
+            cv = L.conv
+            X = oracle.im2col(h["act"], cv.kh, cv.kw, cv.stride, cv.pad)
+        frac = 1.0
+        ncols = X.shape[1]
+        budget = 6e9                     # multiply-adds per layer that keep the whole leg within ~30 s
+        if L.S * L.K * ncols > budget:
+            ncols = max(64, int(budget // (L.S * L.K)))
+            frac = ncols / X.shape[1]
+        tg = time.perf_counter()
+        oracle.gemm_masked(h["W"], sel.mask, X, 0, ncols, want_abs=False)
+        tg = time.perf_counter() - tg
+        t0 -= tg * (1.0 / frac - 1.0)    # scale the sampled columns to the full width
+    dt = time.perf_counter() - t0
+    cores = oracle.num_threads()
+    return {"value": round(useful_flop / dt / 1e12, 6), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "seconds": round(dt, 3),
+            "sample": "one pass of the full workload (select, pack, im2col, dense masked fp64 product); "
+                      "products above 6e9 multiply-adds are timed on their first columns and scaled"}
+
+
+if __name__ == "__main__":
+    main()

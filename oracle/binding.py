@@ -181,3 +181,7 @@ def select(W: np.ndarray, G_or_T: Optional[np.ndarray], n: int, m: int, B: int, 
     row_ptr, col_idx = block_select(sc, kr, select_mode)
     mask = dense_mask(keep, B, row_ptr, col_idx)
     return Selection(T, keep, keep_to_bits(keep), sc, kr, row_ptr, col_idx, mask)
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())

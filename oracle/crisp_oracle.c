@@ -439,3 +439,11 @@ int oracle_metadata_bits(int S, int K, int Kp, int n, int m, int B, double *out)
     out[2] = (double)S * (double)Kp * ((double)n / (double)m) * (double)log2_exact(m);
     return 0;
 }
+
+/* Threads the OpenMP loops above will use (for reporting next to timings). */
+#ifdef _OPENMP
+#include <omp.h>
+int oracle_num_threads(void) { return omp_get_max_threads(); }
+#else
+int oracle_num_threads(void) { return 1; }
+#endif
