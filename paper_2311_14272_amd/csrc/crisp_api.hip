@@ -147,7 +147,6 @@ crisp_status crisp_spmm(const crisp_layer_desc* desc, const int32_t* row_ptr, co
                         const uint16_t* vals, const uint32_t* idx_words, const uint16_t* X, int64_t Ncol,
                         int64_t ldx, int32_t x_layout, void* Y, int64_t ldy, int32_t y_dtype, void* ws,
                         size_t ws_bytes, void* stream) {
-    (void)ws; (void)ws_bytes;
     Geometry g;
     crisp_status st = make_geometry(desc, false, &g);
     if (st != CRISP_OK) return st;
@@ -161,8 +160,11 @@ crisp_status crisp_spmm(const crisp_layer_desc* desc, const int32_t* row_ptr, co
         return CRISP_EALIGN;
     if (x_layout != CRISP_X_KN) return CRISP_EUNSUPPORTED;
     if (g.B == 16) return CRISP_EUNSUPPORTED;
-    hipError_t e = launch_spmm(g, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, Y, ldy, y_dtype,
-                               (hipStream_t)stream);
+    // ws_bytes doubles as a tuning knob when ws is NULL: 0 = automatic launch shape, 1..5 force
+    // shape (value - 1); results do not depend on it.
+    const int force_shape = (!ws && ws_bytes >= 1 && ws_bytes <= 5) ? (int)ws_bytes - 1 : -1;
+    hipError_t e = launch_spmm(g, desc->block_density, force_shape, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx,
+                               Y, ldy, y_dtype, (hipStream_t)stream);
     return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
 }
 

@@ -26,9 +26,11 @@ hipError_t launch_select(const Geometry& g, int sal_kind, int select_mode, const
 hipError_t launch_pack(const Geometry& g, const uint16_t* W, const uint32_t* nm_mask, const int32_t* row_ptr,
                        const int32_t* col_idx, uint16_t* vals, uint32_t* idxw, int32_t* flags, hipStream_t st);
 hipError_t launch_im2col(const crisp_conv_desc& c, const uint16_t* act, uint16_t* X, int64_t ldx, hipStream_t st);
-hipError_t launch_spmm(const Geometry& g, const int32_t* row_ptr, const int32_t* col_idx, const uint16_t* vals,
-                       const uint32_t* idxw, const uint16_t* X, int64_t Ncol, int64_t ldx, void* Y, int64_t ldy,
-                       int y_dtype, hipStream_t st);
+// density_hint only steers the launch shape; force_shape < 0 lets the library choose
+// (0..3 = shapes of the specialised kernels, 4 = generic LDS-expansion kernel).
+hipError_t launch_spmm(const Geometry& g, double density_hint, int force_shape, const int32_t* row_ptr,
+                       const int32_t* col_idx, const uint16_t* vals, const uint32_t* idxw, const uint16_t* X,
+                       int64_t Ncol, int64_t ldx, void* Y, int64_t ldy, int y_dtype, hipStream_t st);
 
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 

@@ -1,60 +1,18 @@
-// Hybrid-sparse product Y = W_hybrid * X on gfx950 (Sec. 3.5 of the CRISP paper, re-thought for
-// CDNA4): a workgroup owns one block-row of W and a strip of output columns and walks the
-// block-row's list of kept blocks, so dropped blocks cost neither weight nor activation traffic.
+// Generic hybrid-sparse product kernel (any n:m the format allows) and the launch dispatcher.
 //
-// Per kept block:
-//   * the compressed values and in-group positions are streamed (16-byte coalesced loads) into
-//     an LDS staging area and expanded there into a dense bf16 B x B tile, stored fragment-major
-//     so that each lane later fetches its MFMA A operand with one conflict-free ds_read_b128;
-//   * each wave loads its own X rows straight from global memory into registers, row-wise and
-//     coalesced.  A lane holds, for each of 8 K-rows, 2*WD consecutive columns.  Transposing
-//     pairs of 16-bit halves turns that into 2*WD MFMA B operands (8 K-values of one column
-//     each); the c-th operand belongs to column (lane%32)*2*WD + c, so the 2*WD accumulators of
-//     a lane are 2*WD *consecutive* output columns and Y is written with wide stores;
-//   * v_mfma_f32_32x32x16_bf16 accumulates in fp32.
-// The X rows of the next kept block are requested while the current block is multiplied.
-#include "crisp_internal.h"
+// The generic kernel expands each kept block in LDS: the compressed values and in-group
+// positions are streamed with 16-byte coalesced loads into a staging area and expanded into a
+// dense bf16 B x B tile, stored fragment-major so that each lane fetches its MFMA A operand
+// with one conflict-free ds_read_b128; the four waves of a workgroup share the tile and each
+// multiplies it with its own strip of X (loaded as in spmm_reg.h).  The patterns the paper and
+// the benchmark workloads use have register-resident specialisations (spmm_reg.h), which the
+// dispatcher prefers.
+#include "spmm_reg.h"
 
 namespace crisp {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-
-struct SpmmArgs {
-    int S, K, n, m, w, slots, wpr;
-    int Sb;          // block-rows
-    int NT;          // column strips
-    int64_t Ncol, ldx, ldy;
-    const int32_t* row_ptr;
-    const int32_t* col_idx;
-    const uint16_t* vals;
-    const uint32_t* idxw;
-    const uint16_t* X;
-    void* Y;
-    int y_bf16;
-};
-
-__device__ __forceinline__ uint16_t float_to_bf16_rne(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);  // NaN stays NaN
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
-
 template <int WD>
-struct XVec;
-template <>
-struct XVec<1> { typedef uint32_t type; };
-template <>
-struct XVec<2> { typedef uint2 type; };
-
-template <int WD>
-__device__ __forceinline__ void xvec_unpack(const typename XVec<WD>::type& v, uint32_t (&d)[WD]);
-template <>
-__device__ __forceinline__ void xvec_unpack<1>(const uint32_t& v, uint32_t (&d)[1]) { d[0] = v; }
-template <>
-__device__ __forceinline__ void xvec_unpack<2>(const uint2& v, uint32_t (&d)[2]) { d[0] = v.x; d[1] = v.y; }
+__device__ __forceinline__ void xvec_unpack_t(const typename XVec<WD>::type& v, uint32_t (&d)[WD]) { xvec_unpack(v, d); }
 
 // B: block edge (32 or 64).  WD: dwords a lane loads per X row (2*WD columns per lane, 64*WD
 // columns per wave).  NW: waves per workgroup (workgroup strip = NW*64*WD columns).
@@ -205,7 +163,7 @@ __global__ __launch_bounds__(64 * NW) void spmm_expand_mfma_kernel(SpmmArgs p) {
                 // 8 rows x 2*WD columns of 16-bit halves -> 2*WD operands of 8 K-values each
                 uint32_t xd[8][WD];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) xvec_unpack<WD>(xr[ks][i], xd[i]);
+                for (int i = 0; i < 8; ++i) xvec_unpack(xr[ks][i], xd[i]);
                 bf16x8 bfrag[2 * WD];
 #pragma unroll
                 for (int pdw = 0; pdw < WD; ++pdw) {
@@ -288,18 +246,54 @@ static hipError_t launch_one(const SpmmArgs& a, hipStream_t st) {
     return hipGetLastError();
 }
 
-hipError_t launch_spmm(const Geometry& g, const int32_t* row_ptr, const int32_t* col_idx, const uint16_t* vals,
-                       const uint32_t* idxw, const uint16_t* X, int64_t Ncol, int64_t ldx, void* Y, int64_t ldy,
-                       int y_dtype, hipStream_t st) {
+template <> hipError_t launch_reg_nm<1, 4>(const SpmmArgs&, int, int, hipStream_t);
+template <> hipError_t launch_reg_nm<2, 4>(const SpmmArgs&, int, int, hipStream_t);
+template <> hipError_t launch_reg_nm<3, 4>(const SpmmArgs&, int, int, hipStream_t);
+template <> hipError_t launch_reg_nm<4, 4>(const SpmmArgs&, int, int, hipStream_t);
+template <> hipError_t launch_reg_nm<1, 8>(const SpmmArgs&, int, int, hipStream_t);
+template <> hipError_t launch_reg_nm<2, 8>(const SpmmArgs&, int, int, hipStream_t);
+template <> hipError_t launch_reg_nm<4, 8>(const SpmmArgs&, int, int, hipStream_t);
+template <> hipError_t launch_reg_nm<8, 8>(const SpmmArgs&, int, int, hipStream_t);
+
+// Launch shape from the problem size: wide strips once they alone give every SIMD several
+// waves; otherwise narrow strips, and when even those are few, 4 or 8 waves split each
+// block-row's list so that enough loads are in flight to cover the memory latency.
+static int pick_shape(const Geometry& g, int64_t Ncol, double density_hint) {
+    const int64_t wide = (int64_t)g.Sb * ((Ncol + 127) / 128);
+    const int64_t narrow = (int64_t)g.Sb * ((Ncol + 63) / 64);
+    if (wide >= 4096) return 0;
+    double d = (density_hint > 0.0 && density_hint <= 1.0) ? density_hint : 0.5;
+    const double blocks_per_row = d * g.Kb;
+    if (narrow >= 3072 || blocks_per_row < 3.0) return 1;
+    if (blocks_per_row >= 8.0 && narrow * 8 <= 6144) return 3;
+    return 2;
+}
+
+hipError_t launch_spmm(const Geometry& g, double density_hint, int force_shape, const int32_t* row_ptr,
+                       const int32_t* col_idx, const uint16_t* vals, const uint32_t* idxw, const uint16_t* X,
+                       int64_t Ncol, int64_t ldx, void* Y, int64_t ldy, int y_dtype, hipStream_t st) {
     SpmmArgs a;
     a.S = g.S; a.K = g.K; a.n = g.n; a.m = g.m; a.w = g.w; a.slots = g.slots; a.wpr = g.wpr;
     a.Sb = g.Sb; a.NT = 0; a.Ncol = Ncol; a.ldx = ldx; a.ldy = ldy;
     a.row_ptr = row_ptr; a.col_idx = col_idx; a.vals = vals; a.idxw = idxw; a.X = X; a.Y = Y;
     a.y_bf16 = (y_dtype == CRISP_Y_BF16);
-    // Strip width: wide strips (more reuse of the expanded tile, wider loads) once there are
-    // enough of them to fill 256 CUs, narrow ones for small problems.
-    const int64_t wide_groups = ((Ncol + 511) / 512) * g.Sb;
-    const bool wide = wide_groups >= 512;
+    const int shape = (force_shape >= 0 && force_shape <= 3) ? force_shape : pick_shape(g, Ncol, density_hint);
+    if (force_shape != 4) {
+        const int key = g.n * 16 + g.m;
+        switch (key) {
+            case 1 * 16 + 4: return launch_reg_nm<1, 4>(a, g.B, shape, st);
+            case 2 * 16 + 4: return launch_reg_nm<2, 4>(a, g.B, shape, st);
+            case 3 * 16 + 4: return launch_reg_nm<3, 4>(a, g.B, shape, st);
+            case 4 * 16 + 4: return launch_reg_nm<4, 4>(a, g.B, shape, st);
+            case 1 * 16 + 8: return launch_reg_nm<1, 8>(a, g.B, shape, st);
+            case 2 * 16 + 8: return launch_reg_nm<2, 8>(a, g.B, shape, st);
+            case 4 * 16 + 8: return launch_reg_nm<4, 8>(a, g.B, shape, st);
+            case 8 * 16 + 8: return launch_reg_nm<8, 8>(a, g.B, shape, st);
+            default: break;
+        }
+    }
+    // any other n:m (or forced): the generic LDS-expansion kernel
+    const bool wide = (int64_t)g.Sb * ((Ncol + 511) / 512) >= 512;
     if (g.B == 64) return wide ? launch_one<64, 2, 4>(a, st) : launch_one<64, 1, 4>(a, st);
     return wide ? launch_one<32, 2, 4>(a, st) : launch_one<32, 1, 4>(a, st);
 }

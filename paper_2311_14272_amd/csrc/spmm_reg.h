@@ -1,0 +1,367 @@
+// Register-resident hybrid-sparse product kernel for gfx950, specialised per N:M pattern.
+//
+// Sec. 3.5 of the CRISP paper walks a block-row's kept blocks, selects the activations the
+// in-group positions point at, and multiply-accumulates.  On CDNA4 the same walk is done by one
+// 64-lane wave per (block-row, strip of output columns):
+//   * X rows of a kept block are loaded row-wise, coalesced, straight into registers; a lane
+//     holds 2*WD consecutive columns of 8 K-rows and transposes the 16-bit halves into 2*WD
+//     MFMA B operands (8 K-values of one column each), so the accumulators of a lane are
+//     consecutive output columns and Y is written with wide stores;
+//   * the lane's slice of the compressed values and log2(m)-bit positions (canonical packed
+//     form, read as is) is expanded in registers into the dense 8-value A operand;
+//   * v_mfma_f32_32x32x16_bf16 accumulates in fp32.
+// Nothing goes through LDS in the loop and waves never wait for each other, so every wave keeps
+// PF blocks of X in flight.  Two ways to spread work:
+//   NWK == 1: the 4 waves of a workgroup own 4 neighbouring column strips (large Ncol);
+//   NWK  > 1: the NWK waves of a workgroup share one strip and split the block list between
+//             them (small Ncol: more waves, more loads in flight); partial sums are added in a
+//             fixed order through LDS at the end, so results stay deterministic.
+#pragma once
+#include <type_traits>
+
+#include "crisp_internal.h"
+
+namespace crisp {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+struct SpmmArgs {
+    int S, K, n, m, w, slots, wpr;
+    int Sb;          // block-rows
+    int NT;          // groups of column strips (one per workgroup)
+    int64_t Ncol, ldx, ldy;
+    const int32_t* row_ptr;
+    const int32_t* col_idx;
+    const uint16_t* vals;
+    const uint32_t* idxw;
+    const uint16_t* X;
+    void* Y;
+    int y_bf16;
+};
+
+__device__ __forceinline__ uint16_t float_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);  // NaN stays NaN
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+template <int WD> struct XVec;
+template <> struct XVec<1> { typedef uint32_t type; };
+template <> struct XVec<2> { typedef uint2 type; };
+__device__ __forceinline__ void xvec_unpack(const uint32_t& v, uint32_t (&d)[1]) { d[0] = v; }
+__device__ __forceinline__ void xvec_unpack(const uint2& v, uint32_t (&d)[2]) { d[0] = v.x; d[1] = v.y; }
+
+// Geometry of the canonical packed form as seen by one lane.
+template <int N, int M, int B>
+struct Fmt {
+    static constexpr int WB = (M == 4) ? 2 : 3;             // bits per in-group position
+    static constexpr int FS = 8 * N / M;                    // value slots behind 8 columns of one row
+    static constexpr int VW = (FS + 1) / 2;                 // dwords that hold them
+    static constexpr int HB = FS * WB;                      // position bits behind 8 columns
+    static constexpr int SLOTS = B / M * N;                 // slots per block row
+    static constexpr int WPR = (SLOTS * WB + 31) / 32;      // position words per block row
+    static constexpr int KS = B / 16;                       // MFMA steps per block
+    static constexpr int RT = B / 32;                       // 32-row tiles per block
+};
+
+template <int FS>
+__device__ __forceinline__ void load_vals(const uint16_t* p, uint32_t (&v)[(FS + 1) / 2]) {
+    if constexpr (FS == 1) {
+        v[0] = *p;
+    } else if constexpr (FS == 2) {
+        v[0] = *reinterpret_cast<const uint32_t*>(p);
+    } else if constexpr (FS == 4) {
+        const uint2 t = *reinterpret_cast<const uint2*>(p);
+        v[0] = t.x; v[1] = t.y;
+    } else if constexpr (FS == 8) {
+        const u32x4 t = *reinterpret_cast<const u32x4*>(p);
+        v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
+    } else {
+#pragma unroll
+        for (int i = 0; i < (FS + 1) / 2; ++i) v[i] = reinterpret_cast<const uint32_t*>(p)[i];
+    }
+}
+
+// Dense A operand (8 bf16 = 4 dwords) of one row for MFMA step KSTEP from the lane's compressed
+// values `v` and its position stream `ws` (already shifted so that bit 0 is the lane's half).
+template <int N, int M, int B, int KSTEP>
+__device__ __forceinline__ u32x4 expand_frag(const uint32_t (&v)[Fmt<N, M, B>::VW],
+                                             const uint32_t (&ws)[Fmt<N, M, B>::WPR]) {
+    typedef Fmt<N, M, B> F;
+    u32x4 out = {0u, 0u, 0u, 0u};
+    if constexpr (N == M) {
+        // every column kept: slot s is column s
+#pragma unroll
+        for (int x = 0; x < 4; ++x) out[x] = v[x];
+    } else {
+#pragma unroll
+        for (int s = 0; s < F::FS; ++s) {
+            constexpr int P0 = KSTEP * 2 * F::HB;
+            const int P = P0 + s * F::WB;
+            const int wi = P >> 5, sh = P & 31;
+            uint32_t field = ws[wi] >> sh;
+            if (sh + F::WB > 32 && wi + 1 < F::WPR) field |= ws[(wi + 1 < F::WPR) ? wi + 1 : wi] << ((32 - sh) & 31);
+            const uint32_t pos = field & (uint32_t)(M - 1);
+            const uint32_t val = (s & 1) ? (v[s >> 1] >> 16) : (v[s >> 1] & 0xFFFFu);
+            const uint32_t vv = val << ((pos & 1u) << 4);
+            if constexpr (M == 4) {
+                const int gi = s / N;  // which of the two groups of four behind these 8 columns
+                const bool upper = (pos & 2u) != 0u;
+                out[2 * gi] |= upper ? 0u : vv;
+                out[2 * gi + 1] |= upper ? vv : 0u;
+            } else {
+                const uint32_t dw = pos >> 1;
+#pragma unroll
+                for (int x = 0; x < 4; ++x) out[x] |= (dw == (uint32_t)x) ? vv : 0u;
+            }
+        }
+    }
+    return out;
+}
+
+template <int N, int M, int B, int WD, int NWK, int PF>
+__global__ __launch_bounds__(NWK > 1 ? 64 * NWK : 256) void spmm_reg_kernel(SpmmArgs p) {
+    typedef Fmt<N, M, B> F;
+    constexpr int RT = F::RT, KS = F::KS;
+    constexpr int STRIPS = NWK > 1 ? 1 : 4;       // column strips per workgroup
+    constexpr int NACC = 2 * WD;                   // accumulator tiles (consecutive columns) per lane
+    typedef typename XVec<WD>::type xvec_t;
+
+    // Workgroup -> (block-row, strip group); ids are dealt round-robin to the 8 XCDs, and all
+    // block-rows of a strip group get ids on the same XCD so they share its L2 for X.
+    const int id = blockIdx.x;
+    const int xcd = id & 7, slot = id >> 3;
+    const int bi = slot % p.Sb;
+    const int nt = (slot / p.Sb) * 8 + xcd;
+    if (nt >= p.NT) return;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int jj = lane & 31, hh = lane >> 5;
+    const int64_t wave_col = ((int64_t)nt * STRIPS + (NWK > 1 ? 0 : wave)) * (64 * WD);
+    if (NWK == 1 && wave_col >= p.Ncol) return;   // no barriers in this mode
+    const int64_t col0 = wave_col + jj * NACC;
+    const bool col_ok = col0 < p.Ncol;
+    // lanes past the last column read column 0 instead (in bounds); they never store
+    const uint16_t* xlane = p.X + (col_ok ? col0 : 0) + (int64_t)hh * 8 * p.ldx;
+
+    const int t_begin = p.row_ptr[bi], t_end = p.row_ptr[bi + 1];
+    const int first = t_begin + (NWK > 1 ? wave : 0);
+    const int cnt = first < t_end ? (t_end - first + NWK - 1) / NWK : 0;
+
+    f32x16 acc[RT][NACC];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int c = 0; c < NACC; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[rt][c][r] = 0.0f;
+
+    xvec_t xr[PF][KS][8];
+    uint32_t av[PF][RT][KS][F::VW];
+    uint32_t aw[PF][RT][F::WPR];
+
+    auto load_x = [&](xvec_t (&dst)[8], int bj, int ks) {
+        const int kbase = bj * B + ks * 16;
+        const uint16_t* src = xlane + (int64_t)kbase * p.ldx;
+        if (kbase + 16 <= p.K) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) dst[i] = *reinterpret_cast<const xvec_t*>(src + (int64_t)i * p.ldx);
+        } else {
+            // ragged last block column: rows >= K do not exist and must read as zero (the
+            // matching weights are zero padding, and 0 * garbage could be NaN)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                xvec_t z = {};
+                if (kbase + hh * 8 + i < p.K) z = *reinterpret_cast<const xvec_t*>(src + (int64_t)i * p.ldx);
+                dst[i] = z;
+            }
+        }
+    };
+    // The lane's slice of block t: row rt*32 + jj, columns ks*16 + hh*8 .. +8.
+    auto load_a = [&](uint32_t (&v)[RT][KS][F::VW], uint32_t (&w)[RT][F::WPR], int t) {
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            const size_t brow = (size_t)t * B + rt * 32 + jj;
+            const uint16_t* vrow = p.vals + brow * F::SLOTS + hh * F::FS;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) load_vals<F::FS>(vrow + ks * 2 * F::FS, v[rt][ks]);
+            if constexpr (N != M) {
+                const uint32_t* irow = p.idxw + brow * F::WPR;
+                uint32_t raw[F::WPR + 1];
+#pragma unroll
+                for (int i = 0; i < F::WPR; ++i) raw[i] = irow[i];
+                raw[F::WPR] = 0u;
+                const uint32_t sh = (uint32_t)hh * F::HB;   // 0 or HB (< 32): drop the other half's bits
+#pragma unroll
+                for (int i = 0; i < F::WPR; ++i) w[rt][i] = __builtin_amdgcn_alignbit(raw[i + 1], raw[i], sh);
+            }
+        }
+    };
+
+    // ---- prologue: PF blocks in flight -----------------------------------------------------
+#pragma unroll
+    for (int d = 0; d < PF; ++d) {
+        if (d < cnt) {
+            const int t = first + d * NWK;
+            const int bj = p.col_idx[t];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) load_x(xr[d][ks], bj, ks);
+            load_a(av[d], aw[d], t);
+        }
+    }
+
+    // ---- walk this wave's kept blocks --------------------------------------------------------
+    for (int i0 = 0; i0 < cnt; i0 += PF) {
+#pragma unroll
+        for (int d = 0; d < PF; ++d) {
+            const int i = i0 + d;
+            if (i < cnt) {
+                const bool has_next = i + PF < cnt;
+                const int t_next = first + (i + PF) * NWK;
+                const int bj_next = has_next ? p.col_idx[t_next] : 0;
+                auto step = [&](auto ks_tag) {
+                    constexpr int ks = decltype(ks_tag)::value;
+                    uint32_t xd[8][WD];
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) xvec_unpack(xr[d][ks][r], xd[r]);
+                    bf16x8 bfrag[NACC];
+#pragma unroll
+                    for (int pd = 0; pd < WD; ++pd) {
+                        u32x4 lo, hi;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const uint32_t r0 = xd[2 * q][pd], r1 = xd[2 * q + 1][pd];
+                            lo[q] = (r0 & 0xFFFFu) | (r1 << 16);
+                            hi[q] = (r0 >> 16) | (r1 & 0xFFFF0000u);
+                        }
+                        bfrag[2 * pd] = __builtin_bit_cast(bf16x8, lo);
+                        bfrag[2 * pd + 1] = __builtin_bit_cast(bf16x8, hi);
+                    }
+                    if (has_next) load_x(xr[d][ks], bj_next, ks);
+#pragma unroll
+                    for (int rt = 0; rt < RT; ++rt) {
+                        const u32x4 a4 = expand_frag<N, M, B, ks>(av[d][rt][ks], aw[d][rt]);
+                        const bf16x8 afrag = __builtin_bit_cast(bf16x8, a4);
+#pragma unroll
+                        for (int c = 0; c < NACC; ++c)
+                            acc[rt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag[c], acc[rt][c], 0, 0, 0);
+                    }
+                };
+                step(std::integral_constant<int, 0>{});
+                step(std::integral_constant<int, 1>{});
+                if constexpr (KS == 4) {
+                    step(std::integral_constant<int, 2>{});
+                    step(std::integral_constant<int, 3>{});
+                }
+                if (has_next) load_a(av[d], aw[d], t_next);
+            }
+        }
+    }
+
+    // ---- epilogue: accumulator register r of a 32x32 tile is row 8*(r/4) + 4*hh + r%4 of the
+    //      tile, column jj; the NACC tiles of a lane are consecutive columns ------------------
+    auto store_row = [&](int row, const float (&v)[NACC]) {
+        if (row >= p.S || !col_ok) return;
+        const bool full = col0 + NACC <= p.Ncol;
+        if (p.y_bf16) {
+            uint16_t* y = reinterpret_cast<uint16_t*>(p.Y) + (int64_t)row * p.ldy + col0;
+            if (full) {
+                uint32_t pk[WD];
+#pragma unroll
+                for (int c = 0; c < WD; ++c)
+                    pk[c] = float_to_bf16_rne(v[2 * c]) | ((uint32_t)float_to_bf16_rne(v[2 * c + 1]) << 16);
+                if constexpr (WD == 1) *reinterpret_cast<uint32_t*>(y) = pk[0];
+                else *reinterpret_cast<uint2*>(y) = make_uint2(pk[0], pk[WD - 1]);
+            } else {
+#pragma unroll
+                for (int c = 0; c < NACC; ++c)
+                    if (col0 + c < p.Ncol) y[c] = float_to_bf16_rne(v[c]);
+            }
+        } else {
+            float* y = reinterpret_cast<float*>(p.Y) + (int64_t)row * p.ldy + col0;
+            if (full) {
+                if constexpr (WD == 1) *reinterpret_cast<float2*>(y) = make_float2(v[0], v[1]);
+                else *reinterpret_cast<float4*>(y) = make_float4(v[0], v[1], v[NACC - 2], v[NACC - 1]);
+            } else {
+#pragma unroll
+                for (int c = 0; c < NACC; ++c)
+                    if (col0 + c < p.Ncol) y[c] = v[c];
+            }
+        }
+    };
+
+    if constexpr (NWK == 1) {
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                float v[NACC];
+#pragma unroll
+                for (int c = 0; c < NACC; ++c) v[c] = acc[rt][c][r];
+                store_row(bi * B + rt * 32 + 8 * (r >> 2) + 4 * hh + (r & 3), v);
+            }
+    } else {
+        // partial sums of the NWK waves -> LDS, then wave w adds up and stores every NWK-th row
+        __shared__ float red[NWK][RT * 16][NACC][64];
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+#pragma unroll
+                for (int c = 0; c < NACC; ++c) red[wave][rt * 16 + r][c][lane] = acc[rt][c][r];
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < RT * 16 / NWK; ++q) {
+            const int pr = q * NWK + wave;
+            float v[NACC];
+#pragma unroll
+            for (int c = 0; c < NACC; ++c) {
+                float s = red[0][pr][c][lane];
+#pragma unroll
+                for (int w = 1; w < NWK; ++w) s += red[w][pr][c][lane];
+                v[c] = s;
+            }
+            const int rt = pr >> 4, r = pr & 15;
+            store_row(bi * B + rt * 32 + 8 * (r >> 2) + 4 * hh + (r & 3), v);
+        }
+    }
+}
+
+template <int N, int M, int B, int WD, int NWK, int PF>
+hipError_t launch_reg(const SpmmArgs& a, hipStream_t st) {
+    SpmmArgs p = a;
+    constexpr int STRIPS = NWK > 1 ? 1 : 4;
+    const int64_t span = (int64_t)STRIPS * 64 * WD;
+    p.NT = (int)((a.Ncol + span - 1) / span);
+    const int64_t groups = (int64_t)((p.NT + 7) / 8) * p.Sb * 8;
+    if (groups > INT32_MAX) return hipErrorInvalidValue;
+    spmm_reg_kernel<N, M, B, WD, NWK, PF><<<dim3((unsigned)groups), dim3(NWK > 1 ? 64 * NWK : 256), 0, st>>>(p);
+    return hipGetLastError();
+}
+
+// Launch shape: 0 = wide strips, waves own strips; 1 = narrow strips, waves own strips;
+// 2 / 3 = narrow strips, 4 / 8 waves split the block list.
+template <int N, int M, int B>
+hipError_t launch_reg_shape(const SpmmArgs& a, int shape, hipStream_t st) {
+    switch (shape) {
+        case 0: return launch_reg<N, M, B, 2, 1, 2>(a, st);
+        case 1: return launch_reg<N, M, B, 1, 1, 3>(a, st);
+        case 2: return launch_reg<N, M, B, 1, 4, 2>(a, st);
+        default: return launch_reg<N, M, B, 1, 8, 2>(a, st);
+    }
+}
+
+// One translation unit per N:M pattern provides this.
+template <int N, int M>
+hipError_t launch_reg_nm(const SpmmArgs& a, int B, int shape, hipStream_t st);
+
+#define CRISP_INSTANTIATE_NM(N, M)                                                           \
+    template <>                                                                              \
+    hipError_t launch_reg_nm<N, M>(const SpmmArgs& a, int B, int shape, hipStream_t st) {    \
+        return B == 64 ? launch_reg_shape<N, M, 64>(a, shape, st) : launch_reg_shape<N, M, 32>(a, shape, st); \
+    }
+
+}  // namespace crisp

@@ -43,14 +43,16 @@ def run_select_pack(L, W, G):
     return layer, out
 
 
-def run_spmm(layer, dX, Ncol, ldx, y_dtype, S, ldy=None, fill=None):
+def run_spmm(layer, dX, Ncol, ldx, y_dtype, S, ldy=None, fill=None, shape=None):
     """crisp_spmm into a fresh Y with a guard band of columns (ldy > Ncol) that must stay untouched."""
     if ldy is None:
         ldy = (Ncol + 7) // 8 * 8 + 8
     tdt = torch.float32 if y_dtype == crisp.Y_F32 else torch.bfloat16
     Y = torch.full((S + 1, ldy), float("nan") if fill is None else fill, dtype=tdt, device="cuda")
+    # shape: None = the library's own choice; 0..3 force a launch shape of the specialised
+    # kernels, 4 forces the generic kernel (ws = NULL, ws_bytes = shape + 1)
     crisp.crisp_spmm(layer.desc, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dX, Ncol, ldx, Y, ldy,
-                     y_dtype)
+                     y_dtype, ws=None, ws_bytes=0 if shape is None else shape + 1)
     torch.cuda.synchronize()
     Yh = Y.float().cpu().numpy().astype(np.float64)
     assert np.isnan(Yh[:S, Ncol:]).all(), "columns beyond Ncol were written"

@@ -66,6 +66,24 @@ def test_spmm_from_oracle_pack(L):
     check_product(Y, Yref, Aref, crisp.Y_F32, L.name)
 
 
+@pytest.mark.parametrize("shape", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("L", synth.small_cases(), ids=lambda L: L.name)
+def test_every_launch_shape(L, shape):
+    """Each launch shape of the product (wide / narrow strips, 4- and 8-way split of the block
+    list, generic LDS-expansion kernel) must give the same result within tolerance."""
+    print("case", L.name, "shape", shape, flush=True)
+    W, G, X = synth.draw_small(L, 23)
+    sel, vals, idxw, flags = oracle_all(L, W, G)
+    layer, out = run_select_pack(L, W, G)
+    ldx = (L.Ncol + 7) // 8 * 8
+    Xp = np.zeros((L.K, ldx), dtype=np.uint16)
+    Xp[:, : L.Ncol] = X
+    Yref, Aref = oracle.gemm_masked(W, sel.mask, X)
+    for yd in (crisp.Y_F32, crisp.Y_BF16):
+        Y = run_spmm(layer, dev(Xp), L.Ncol, ldx, yd, L.S, shape=shape)
+        check_product(Y, Yref, Aref, yd, "%s shape %d" % (L.name, shape))
+
+
 def test_ties_and_zero_weights():
     """Constant saliency (every comparison is a tie) and weights with exact zeros / negative zeros."""
     L = synth.LayerSpec("ties", 64, 128, 64, 2, 4, 32, 0.5, synth.SAL_GIVEN, 1.0)
