@@ -122,7 +122,8 @@ crisp_status crisp_pack(const crisp_layer_desc* desc, const uint16_t* W, const u
     if (misaligned(W, 16) || misaligned(nm_mask, 16) || misaligned(row_ptr, 4) || misaligned(col_idx, 4) ||
         misaligned(vals, 16) || misaligned(idx_words, 16) || misaligned(flags, 4))
         return CRISP_EALIGN;
-    hipError_t e = launch_pack(g, W, nm_mask, row_ptr, col_idx, vals, idx_words, flags, (hipStream_t)stream);
+    hipError_t e = launch_pack(g, desc->select_mode, W, nm_mask, row_ptr, col_idx, vals, idx_words, flags,
+                               (hipStream_t)stream);
     return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
 }
 
@@ -153,7 +154,7 @@ crisp_status crisp_spmm(const crisp_layer_desc* desc, const int32_t* row_ptr, co
     if (!row_ptr || !col_idx || !vals || !idx_words || !X || !Y) return CRISP_EINVAL;
     if (y_dtype != CRISP_Y_F32 && y_dtype != CRISP_Y_BF16) return CRISP_EINVAL;
     if (Ncol < 1 || ldx < Ncol || ldy < Ncol) return CRISP_ESHAPE;
-    if (Ncol > ((int64_t)1 << 30) || ldx > ((int64_t)1 << 30) || ldy > ((int64_t)1 << 30)) return CRISP_ESHAPE;
+    if (Ncol > ((int64_t)1 << 27) || ldx > ((int64_t)1 << 27) || ldy > ((int64_t)1 << 27)) return CRISP_ESHAPE;
     if ((ldx & 7) || (ldy & 7)) return CRISP_EALIGN;
     if (misaligned(row_ptr, 4) || misaligned(col_idx, 4) || misaligned(vals, 16) || misaligned(idx_words, 16) ||
         misaligned(X, 16) || misaligned(Y, 16))

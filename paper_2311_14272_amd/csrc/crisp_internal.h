@@ -23,8 +23,9 @@ crisp_status make_geometry(const crisp_layer_desc* d, bool need_density, Geometr
 hipError_t launch_select(const Geometry& g, int sal_kind, int select_mode, const uint16_t* W, const float* TG,
                          uint32_t* nm_mask, int32_t* row_ptr, int32_t* col_idx, double* score, double* score_ws,
                          hipStream_t st);
-hipError_t launch_pack(const Geometry& g, const uint16_t* W, const uint32_t* nm_mask, const int32_t* row_ptr,
-                       const int32_t* col_idx, uint16_t* vals, uint32_t* idxw, int32_t* flags, hipStream_t st);
+hipError_t launch_pack(const Geometry& g, int select_mode, const uint16_t* W, const uint32_t* nm_mask,
+                       const int32_t* row_ptr, const int32_t* col_idx, uint16_t* vals, uint32_t* idxw,
+                       int32_t* flags, hipStream_t st);
 hipError_t launch_im2col(const crisp_conv_desc& c, const uint16_t* act, uint16_t* X, int64_t ldx, hipStream_t st);
 // density_hint only steers the launch shape; force_shape < 0 lets the library choose
 // (0..3 = shapes of the specialised kernels, 4 = generic LDS-expansion kernel).

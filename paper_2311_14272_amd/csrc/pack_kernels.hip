@@ -34,35 +34,51 @@ __device__ __forceinline__ uint32_t slot_position(uint32_t bits, int j, bool out
 // One workgroup per kept block.  Phase 1: one thread per (block row, group) gathers the kept
 // values in ascending column order.  Phase 2: one thread per (block row, index word) assembles
 // the little-endian stream of log2(m)-bit positions.
+// uniform_k_row > 0: every block-row holds exactly that many blocks, so the owner of block t is
+// t / uniform_k_row and no search is needed.  flag_mode: 0 = flags[0] was preset to 1 and is
+// cleared when an aligned group of four holds more than two kept elements; 1 = the pattern can
+// never do that (n <= 2), workgroup 0 writes the constant.
 __global__ __launch_bounds__(256) void pack_block_kernel(int S, int K, int n, int m, int B, int Sb, int w, int slots,
-                                                         int wpr, int mwpr, const uint16_t* __restrict__ W,
+                                                         int wpr, int mwpr, int uniform_k_row, int flag_mode,
+                                                         const uint16_t* __restrict__ W,
                                                          const uint32_t* __restrict__ nm_mask,
                                                          const int32_t* __restrict__ row_ptr,
                                                          const int32_t* __restrict__ col_idx,
                                                          uint16_t* __restrict__ vals, uint32_t* __restrict__ idxw,
                                                          int32_t* __restrict__ flags) {
     const int t = blockIdx.x;
-    const int bi = owner_row(row_ptr, Sb, t);
+    const int bi = uniform_k_row > 0 ? t / uniform_k_row : owner_row(row_ptr, Sb, t);
     const int bj = col_idx[t];
     const int G = B / m;
+    if (flag_mode == 1 && t == 0 && threadIdx.x == 0) { flags[0] = 1; flags[1] = 0; flags[2] = 0; flags[3] = 0; }
     bool violates = false;
     for (int e = threadIdx.x; e < B * G; e += 256) {
         const int r = e / G, g = e % G;
         const int s = bi * B + r, k0 = bj * B + g * m;
         uint16_t* out = vals + ((size_t)t * B + r) * slots + g * n;
-        int filled = 0;
+        uint16_t v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
         if (s < S && k0 < K) {
             const uint32_t bits = group_bits(nm_mask, mwpr, s, k0, m);
-            for (int o = 0; o < m; ++o)
-                if ((bits >> o) & 1u) {
-                    if (filled < n) out[filled] = W[(size_t)s * K + k0 + o];
-                    ++filled;
-                }
+            const uint16_t* src = W + (size_t)s * K + k0;
+            uint16_t wv[8];
+#pragma unroll
+            for (int o = 0; o < 8; ++o) wv[o] = (o < m && k0 + o < K) ? src[o] : (uint16_t)0;
+            int filled = 0;
+#pragma unroll
+            for (int o = 0; o < 8; ++o) {
+                const bool on = (bits >> o) & 1u;
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+                    if (on && filled == q) v[q] = wv[o];
+                filled += on;
+            }
             if (__popc(bits & 0xFu) > 2 || __popc(bits >> 4) > 2) violates = true;
         }
-        for (; filled < n; ++filled) out[filled] = 0;
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            if (q < n) out[q] = v[q];
     }
-    if (violates) atomicAnd(flags, 0);
+    if (flag_mode == 0 && violates) atomicAnd(flags, 0);
     for (int e = threadIdx.x; e < B * wpr; e += 256) {
         const int r = e / wpr, x = e % wpr;
         const int s = bi * B + r;
@@ -82,11 +98,15 @@ __global__ __launch_bounds__(256) void pack_block_kernel(int S, int K, int n, in
     }
 }
 
-hipError_t launch_pack(const Geometry& g, const uint16_t* W, const uint32_t* nm_mask, const int32_t* row_ptr,
-                       const int32_t* col_idx, uint16_t* vals, uint32_t* idxw, int32_t* flags, hipStream_t st) {
-    pack_init_flags_kernel<<<1, 64, 0, st>>>(flags);
+hipError_t launch_pack(const Geometry& g, int select_mode, const uint16_t* W, const uint32_t* nm_mask,
+                       const int32_t* row_ptr, const int32_t* col_idx, uint16_t* vals, uint32_t* idxw,
+                       int32_t* flags, hipStream_t st) {
+    // n <= 2 can never put three kept elements into an aligned group of four
+    const int flag_mode = (g.n <= 2 && g.nk > 0) ? 1 : 0;
+    if (flag_mode == 0) pack_init_flags_kernel<<<1, 64, 0, st>>>(flags);
     if (g.nk > 0)
-        pack_block_kernel<<<g.nk, 256, 0, st>>>(g.S, g.K, g.n, g.m, g.B, g.Sb, g.w, g.slots, g.wpr, g.mwpr, W,
+        pack_block_kernel<<<g.nk, 256, 0, st>>>(g.S, g.K, g.n, g.m, g.B, g.Sb, g.w, g.slots, g.wpr, g.mwpr,
+                                                select_mode == CRISP_ROW_UNIFORM ? g.k_row : 0, flag_mode, W,
                                                 nm_mask, row_ptr, col_idx, vals, idxw, flags);
     return hipGetLastError();
 }

@@ -5,67 +5,98 @@
 
 namespace crisp {
 
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
 // Saliency of one element (Sec. 3.4, Eq. 1): one fp32 multiply, then the absolute value.
 template <int KIND>
-__device__ __forceinline__ float saliency_at(const uint16_t* __restrict__ W, const float* __restrict__ TG, size_t e) {
-    if (KIND == CRISP_SAL_GIVEN) return TG[e];
-    if (KIND == CRISP_SAL_GRAD) return fabsf(__fmul_rn(bf16_bits_to_float(W[e]), TG[e]));
-    return fabsf(bf16_bits_to_float(W[e]));
+__device__ __forceinline__ float saliency_of(uint16_t w, float tg) {
+    if (KIND == CRISP_SAL_GIVEN) return tg;
+    if (KIND == CRISP_SAL_GRAD) return fabsf(__fmul_rn(bf16_bits_to_float(w), tg));
+    return fabsf(bf16_bits_to_float(w));
 }
 
-// One thread per aligned group of M columns.  The M keep bits of the 32/M groups that share a
-// mask word are OR-combined across neighbouring lanes with xor-shuffles; one lane stores the word.
-// grid.x covers ceil(K/32)*(32/M) groups in units of 64 lanes, grid.y covers rows in units of 4.
-template <int M, int KIND>
-__global__ __launch_bounds__(256) void nm_select_kernel(int S, int K, int n, int mwpr,
-                                                        const uint16_t* __restrict__ W,
-                                                        const float* __restrict__ TG,
-                                                        uint32_t* __restrict__ nm_mask) {
-    constexpr int GPW = 32 / M;  // groups per mask word
-    const int gx = blockIdx.x * 64 + threadIdx.x;
-    const int s = blockIdx.y * 4 + threadIdx.y;
-    const int word = gx / GPW;
-    const bool live = (s < S) && (word < mwpr);
-    uint32_t bits = 0;
-    if (live) {
-        const int k0 = gx * M;
-        const int len = min(M, K - k0);  // may be <= 0 in the last word of a ragged row
-        float t[M];
-#pragma unroll
-        for (int i = 0; i < M; ++i) t[i] = (i < len) ? saliency_at<KIND>(W, TG, (size_t)s * K + k0 + i) : -1.0f;
-#pragma unroll
-        for (int i = 0; i < M; ++i) {
-            int before = 0;
-#pragma unroll
-            for (int j = 0; j < M; ++j) before += (j < len) && (t[j] > t[i] || (t[j] == t[i] && j < i));
-            if (i < len && before < n) bits |= 1u << i;
-        }
-        bits <<= (gx % GPW) * M;
-    }
-    // all 64 lanes of the wave take part in the shuffles; GPW consecutive lanes form one word
-#pragma unroll
-    for (int d = 1; d < GPW; d <<= 1) bits |= __shfl_xor(bits, d, 64);
-    if (live && (gx % GPW) == 0) nm_mask[(size_t)s * mwpr + word] = bits;
-}
-
-// One workgroup (one wave) per block.  Lane r walks row r of the block left to right and adds
-// the kept saliencies in fp64; lane 0 then adds the row sums top to bottom.  This order is part
-// of the definition of the score (a tree reduction would round differently).
-template <int KIND>
-__global__ __launch_bounds__(64) void block_score_kernel(int S, int K, int B, int Kb, int mwpr,
-                                                         const uint16_t* __restrict__ W,
-                                                         const float* __restrict__ TG,
-                                                         const uint32_t* __restrict__ nm_mask,
-                                                         double* __restrict__ score) {
+// One wave per B x B block; lane r owns row r of the block.  The lane loads its B weights (and
+// B gradient / saliency values) with 16-byte loads, ranks every aligned group of M columns
+// (keep the n first under: larger saliency first, on a tie the smaller column first), writes its
+// part of the N:M mask, and adds the kept saliencies left to right in fp64.  Lane 0 then adds the
+// row sums top to bottom.  That summation order is part of the definition of the block score
+// (a tree reduction would round differently).
+// VEC: row segments are 16-byte aligned and lie wholly inside the matrix (K % B == 0).
+template <int B, int M, int KIND, bool VEC>
+__global__ __launch_bounds__(64) void score_select_kernel(int S, int K, int n, int Kb, int mwpr,
+                                                          const uint16_t* __restrict__ W,
+                                                          const float* __restrict__ TG,
+                                                          uint32_t* __restrict__ nm_mask,
+                                                          double* __restrict__ score) {
     __shared__ double rowsum[64];
     const int bj = blockIdx.x, bi = blockIdx.y, r = threadIdx.x;
     const int s = bi * B + r;
+    const int k_begin = bj * B;
     double acc = 0.0;
     if (r < B && s < S) {
-        const int k_begin = bj * B, k_end = min(K, k_begin + B);
-        for (int k = k_begin; k < k_end; ++k) {
-            const uint32_t wbits = nm_mask[(size_t)s * mwpr + (k >> 5)];
-            if ((wbits >> (k & 31)) & 1u) acc = __dadd_rn(acc, (double)saliency_at<KIND>(W, TG, (size_t)s * K + k));
+        uint16_t w[B];
+        float tg[B];
+        const size_t e0 = (size_t)s * K + k_begin;
+        const int len = min(B, K - k_begin);
+        if (VEC) {
+            if (KIND != CRISP_SAL_GIVEN) {
+#pragma unroll
+                for (int i = 0; i < B / 8; ++i) {
+                    const u32x4 v = *reinterpret_cast<const u32x4*>(W + e0 + 8 * i);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        w[8 * i + 2 * q] = (uint16_t)(v[q] & 0xFFFFu);
+                        w[8 * i + 2 * q + 1] = (uint16_t)(v[q] >> 16);
+                    }
+                }
+            }
+            if (KIND != CRISP_SAL_MAG) {
+#pragma unroll
+                for (int i = 0; i < B / 4; ++i) {
+                    const f32x4 v = *reinterpret_cast<const f32x4*>(TG + e0 + 4 * i);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) tg[4 * i + q] = v[q];
+                }
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < B; ++i) {
+                w[i] = (KIND != CRISP_SAL_GIVEN && i < len) ? W[e0 + i] : (uint16_t)0;
+                tg[i] = (KIND != CRISP_SAL_MAG && i < len) ? TG[e0 + i] : 0.0f;
+            }
+        }
+        uint32_t bits[B / 32 > 0 ? B / 32 : 1] = {};
+#pragma unroll
+        for (int g = 0; g < B / M; ++g) {
+            float t[M];
+#pragma unroll
+            for (int i = 0; i < M; ++i) t[i] = saliency_of<KIND>(w[g * M + i], tg[g * M + i]);
+            const int glen = len - g * M;  // columns of this group that exist (may be <= 0)
+#pragma unroll
+            for (int i = 0; i < M; ++i) {
+                int before = 0;
+#pragma unroll
+                for (int j = 0; j < M; ++j) before += (j < glen) && (t[j] > t[i] || (t[j] == t[i] && j < i));
+                if (i < glen && before < n) {
+                    bits[(g * M + i) / 32] |= 1u << ((g * M + i) % 32);
+                    acc = __dadd_rn(acc, (double)t[i]);
+                }
+            }
+        }
+        if (B >= 32) {
+#pragma unroll
+            for (int x = 0; x < B / 32; ++x) {
+                const int word = (k_begin >> 5) + x;
+                if (word < mwpr) nm_mask[(size_t)s * mwpr + word] = bits[x];
+            }
+        } else {
+            // B == 16: two blocks share a mask word; each writes its own half
+            uint16_t* half = reinterpret_cast<uint16_t*>(nm_mask) + ((size_t)s * mwpr) * 2;
+            const int h = k_begin >> 4;
+            half[h] = (uint16_t)bits[0];
+            // an odd number of block columns leaves the upper half of the last word to nobody
+            if (bj == Kb - 1 && (h & 1) == 0) half[h + 1] = 0;
         }
     }
     rowsum[r] = acc;
@@ -159,18 +190,29 @@ __global__ __launch_bounds__(1024) void block_topk_layer_kernel(int Sb, int Kb, 
     for (int bi = wave; bi < Sb; bi += 16) wave_compact(kept + bi * Kb, Kb, col_idx + rowcnt[bi], lane);
 }
 
+template <int B, int M, int KIND>
+static void launch_score_select(const Geometry& g, const uint16_t* W, const float* TG, uint32_t* nm_mask,
+                                double* score, hipStream_t st) {
+    const dim3 grd(g.Kb, g.Sb);
+    if (g.K % B == 0)
+        score_select_kernel<B, M, KIND, true><<<grd, 64, 0, st>>>(g.S, g.K, g.n, g.Kb, g.mwpr, W, TG, nm_mask, score);
+    else
+        score_select_kernel<B, M, KIND, false><<<grd, 64, 0, st>>>(g.S, g.K, g.n, g.Kb, g.mwpr, W, TG, nm_mask, score);
+}
+
 template <int KIND>
 static hipError_t launch_select_kind(const Geometry& g, int select_mode, const uint16_t* W, const float* TG,
                                      uint32_t* nm_mask, int32_t* row_ptr, int32_t* col_idx, double* score,
                                      hipStream_t st) {
-    const int gpw = 32 / g.m;
-    dim3 blk(64, 4);
-    dim3 grd((g.mwpr * gpw + 63) / 64, (g.S + 3) / 4);
-    if (g.m == 4)
-        nm_select_kernel<4, KIND><<<grd, blk, 0, st>>>(g.S, g.K, g.n, g.mwpr, W, TG, nm_mask);
-    else
-        nm_select_kernel<8, KIND><<<grd, blk, 0, st>>>(g.S, g.K, g.n, g.mwpr, W, TG, nm_mask);
-    block_score_kernel<KIND><<<dim3(g.Kb, g.Sb), 64, 0, st>>>(g.S, g.K, g.B, g.Kb, g.mwpr, W, TG, nm_mask, score);
+    const int key = g.B * 16 + g.m;
+    switch (key) {
+        case 64 * 16 + 4: launch_score_select<64, 4, KIND>(g, W, TG, nm_mask, score, st); break;
+        case 64 * 16 + 8: launch_score_select<64, 8, KIND>(g, W, TG, nm_mask, score, st); break;
+        case 32 * 16 + 4: launch_score_select<32, 4, KIND>(g, W, TG, nm_mask, score, st); break;
+        case 32 * 16 + 8: launch_score_select<32, 8, KIND>(g, W, TG, nm_mask, score, st); break;
+        case 16 * 16 + 4: launch_score_select<16, 4, KIND>(g, W, TG, nm_mask, score, st); break;
+        default: launch_score_select<16, 8, KIND>(g, W, TG, nm_mask, score, st); break;
+    }
     if (select_mode == CRISP_ROW_UNIFORM)
         block_topk_rows_kernel<<<g.Sb, 256, 0, st>>>(g.Sb, g.Kb, g.k_row, score, row_ptr, col_idx);
     else

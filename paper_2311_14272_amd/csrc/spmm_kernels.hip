@@ -278,7 +278,9 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, int force_shape, 
     a.row_ptr = row_ptr; a.col_idx = col_idx; a.vals = vals; a.idxw = idxw; a.X = X; a.Y = Y;
     a.y_bf16 = (y_dtype == CRISP_Y_BF16);
     const int shape = (force_shape >= 0 && force_shape <= 3) ? force_shape : pick_shape(g, Ncol, density_hint);
-    if (force_shape != 4) {
+    // the specialised kernels assume whole 16-row MFMA steps of X (K % 16 == 0) and whole groups
+    // of four output columns per lane (Ncol % 4 == 0)
+    if (force_shape != 4 && (g.K % 16) == 0 && (Ncol % 4) == 0 && ldy <= ((int64_t)1 << 23)) {
         const int key = g.n * 16 + g.m;
         switch (key) {
             case 1 * 16 + 4: return launch_reg_nm<1, 4>(a, g.B, shape, st);

@@ -48,11 +48,31 @@ __device__ __forceinline__ uint16_t float_to_bf16_rne(float f) {
     return (uint16_t)(u >> 16);
 }
 
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 template <int WD> struct XVec;
 template <> struct XVec<1> { typedef uint32_t type; };
-template <> struct XVec<2> { typedef uint2 type; };
+template <> struct XVec<2> { typedef u32x2 type; };
 __device__ __forceinline__ void xvec_unpack(const uint32_t& v, uint32_t (&d)[1]) { d[0] = v; }
-__device__ __forceinline__ void xvec_unpack(const uint2& v, uint32_t (&d)[2]) { d[0] = v.x; d[1] = v.y; }
+__device__ __forceinline__ void xvec_unpack(const u32x2& v, uint32_t (&d)[2]) { d[0] = v[0]; d[1] = v[1]; }
+
+// Buffer addressing (MUBUF): a 128-bit resource in SGPRs gives the base, a 32-bit SGPR a
+// uniform offset and a 32-bit VGPR the lane's offset, so per-load address arithmetic is scalar.
+// Resource words: base[31:0], base[47:32] (stride 0), number of bytes, 0x00020000 (raw 32-bit
+// data format on gfx9-family targets).  The range is left at its maximum: every address formed
+// below is in bounds by construction.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0xFFFFFFFFu, 0x00020000);
+}
+template <int WD> __device__ __forceinline__ typename XVec<WD>::type buf_load_x(rsrc_t r, uint32_t voff, uint32_t soff);
+template <> __device__ __forceinline__ uint32_t buf_load_x<1>(rsrc_t r, uint32_t voff, uint32_t soff) {
+    return __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0);
+}
+template <> __device__ __forceinline__ u32x2 buf_load_x<2>(rsrc_t r, uint32_t voff, uint32_t soff) {
+    return __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0));
+}
 
 // Geometry of the canonical packed form as seen by one lane.
 template <int N, int M, int B>
@@ -68,20 +88,20 @@ struct Fmt {
 };
 
 template <int FS>
-__device__ __forceinline__ void load_vals(const uint16_t* p, uint32_t (&v)[(FS + 1) / 2]) {
+__device__ __forceinline__ void load_vals(rsrc_t r, uint32_t voff, uint32_t soff, uint32_t (&v)[(FS + 1) / 2]) {
     if constexpr (FS == 1) {
-        v[0] = *p;
+        v[0] = __builtin_amdgcn_raw_buffer_load_b16(r, voff, soff, 0);
     } else if constexpr (FS == 2) {
-        v[0] = *reinterpret_cast<const uint32_t*>(p);
+        v[0] = __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0);
     } else if constexpr (FS == 4) {
-        const uint2 t = *reinterpret_cast<const uint2*>(p);
-        v[0] = t.x; v[1] = t.y;
+        const u32x2 t = __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0));
+        v[0] = t[0]; v[1] = t[1];
     } else if constexpr (FS == 8) {
-        const u32x4 t = *reinterpret_cast<const u32x4*>(p);
+        const u32x4 t = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0));
         v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
     } else {
 #pragma unroll
-        for (int i = 0; i < (FS + 1) / 2; ++i) v[i] = reinterpret_cast<const uint32_t*>(p)[i];
+        for (int i = 0; i < (FS + 1) / 2; ++i) v[i] = __builtin_amdgcn_raw_buffer_load_b32(r, voff + 4 * i, soff, 0);
     }
 }
 
@@ -122,6 +142,107 @@ __device__ __forceinline__ u32x4 expand_frag(const uint32_t (&v)[Fmt<N, M, B>::V
     return out;
 }
 
+// One kept block: multiply the block held in ring slot (xr, av, aw) into acc.  With PREFETCH the
+// X rows of block column bj_next are requested into the same registers as soon as their
+// current contents have been turned into MFMA operands, and block t_next's compressed slice
+// after the last step; the body is straight-line code, so the compiler's wait counters stay exact.
+template <int N, int M, int B, int WD, bool PREFETCH>
+struct BlockBody {
+    typedef Fmt<N, M, B> F;
+    typedef typename XVec<WD>::type xvec_t;
+    static constexpr int RT = F::RT, KS = F::KS, NACC = 2 * WD;
+
+    // X rows of block column bj, MFMA step ks.  K is a multiple of 16 here, so a step lies either
+    // wholly inside the matrix or wholly past its end; a step past the end re-reads the last 16
+    // rows instead (finite values times the zero padding of the packed block).
+    __device__ static __forceinline__ void load_x(xvec_t (&dst)[8], const SpmmArgs& p, uint32_t lane_off, int bj,
+                                                   int ks) {
+        const int kb = min(bj * B + ks * 16, p.K - 16);
+        const rsrc_t r = make_rsrc(p.X + (int64_t)kb * p.ldx);
+        const uint32_t row_bytes = (uint32_t)p.ldx * 2u;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) dst[i] = buf_load_x<WD>(r, lane_off, (uint32_t)i * row_bytes);
+    }
+
+    // Requests the lane's slice of block t: values of rows rt*32 + jj, columns ks*16 + hh*8 .. +8,
+    // and the whole position stream of those rows (a_off / i_off carry the lane part of the
+    // address).  Nothing is consumed here, so no wait is placed next to the requests.
+    __device__ static __forceinline__ void load_a(uint32_t (&v)[RT][KS][F::VW], uint32_t (&w)[RT][F::WPR],
+                                                   const SpmmArgs& p, uint32_t a_off, uint32_t i_off, int t) {
+        const rsrc_t rv = make_rsrc(p.vals);
+        const rsrc_t ri = make_rsrc(p.idxw);
+        const uint32_t vb = (uint32_t)t * (B * F::SLOTS * 2);
+        const uint32_t ib = (uint32_t)t * (B * F::WPR * 4);
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                load_vals<F::FS>(rv, a_off + (rt * 32 * F::SLOTS + ks * 2 * F::FS) * 2, vb, v[rt][ks]);
+            if constexpr (N != M) {
+#pragma unroll
+                for (int i = 0; i < F::WPR; ++i)
+                    w[rt][i] = __builtin_amdgcn_raw_buffer_load_b32(ri, i_off + (rt * 32 * F::WPR + i) * 4, ib, 0);
+            }
+        }
+    }
+
+    template <int ks>
+    __device__ static __forceinline__ void step(f32x16 (&acc)[RT][NACC], xvec_t (&xr)[KS][8],
+                                                const uint32_t (&av)[RT][KS][F::VW], const uint32_t (&ws)[RT][F::WPR],
+                                                const SpmmArgs& p, uint32_t lane_off, int bj_next) {
+        // 8 rows x 2*WD columns of 16-bit halves -> 2*WD operands of 8 K-values each
+        uint32_t xd[8][WD];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) xvec_unpack(xr[ks][r], xd[r]);
+        bf16x8 bfrag[NACC];
+#pragma unroll
+        for (int pd = 0; pd < WD; ++pd) {
+            u32x4 lo, hi;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t r0 = xd[2 * q][pd], r1 = xd[2 * q + 1][pd];
+                lo[q] = (r0 & 0xFFFFu) | (r1 << 16);
+                hi[q] = (r0 >> 16) | (r1 & 0xFFFF0000u);
+            }
+            bfrag[2 * pd] = __builtin_bit_cast(bf16x8, lo);
+            bfrag[2 * pd + 1] = __builtin_bit_cast(bf16x8, hi);
+        }
+        if constexpr (PREFETCH) load_x(xr[ks], p, lane_off, bj_next, ks);
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            const u32x4 a4 = expand_frag<N, M, B, ks>(av[rt][ks], ws[rt]);
+            const bf16x8 afrag = __builtin_bit_cast(bf16x8, a4);
+#pragma unroll
+            for (int c = 0; c < NACC; ++c)
+                acc[rt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag[c], acc[rt][c], 0, 0, 0);
+        }
+    }
+
+    __device__ static __forceinline__ void run(f32x16 (&acc)[RT][NACC], xvec_t (&xr)[KS][8],
+                                               uint32_t (&av)[RT][KS][F::VW], uint32_t (&aw)[RT][F::WPR],
+                                               const SpmmArgs& p, uint32_t lane_off, uint32_t a_off, uint32_t i_off,
+                                               uint32_t aw_sh, int t_next) {
+        int bj_next = 0;
+        if constexpr (PREFETCH) bj_next = p.col_idx[t_next];
+        // drop the other half-wave's position bits: bit 0 of ws is this lane's first slot
+        uint32_t ws[RT][F::WPR];
+        if constexpr (N != M) {
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                for (int i = 0; i < F::WPR; ++i)
+                    ws[rt][i] = __builtin_amdgcn_alignbit(i + 1 < F::WPR ? aw[rt][i + 1] : 0u, aw[rt][i], aw_sh);
+        }
+        step<0>(acc, xr, av, ws, p, lane_off, bj_next);
+        step<1>(acc, xr, av, ws, p, lane_off, bj_next);
+        if constexpr (KS == 4) {
+            step<2>(acc, xr, av, ws, p, lane_off, bj_next);
+            step<3>(acc, xr, av, ws, p, lane_off, bj_next);
+        }
+        if constexpr (PREFETCH) load_a(av, aw, p, a_off, i_off, t_next);
+    }
+};
+
 template <int N, int M, int B, int WD, int NWK, int PF>
 __global__ __launch_bounds__(NWK > 1 ? 64 * NWK : 256) void spmm_reg_kernel(SpmmArgs p) {
     typedef Fmt<N, M, B> F;
@@ -129,6 +250,8 @@ __global__ __launch_bounds__(NWK > 1 ? 64 * NWK : 256) void spmm_reg_kernel(Spmm
     constexpr int STRIPS = NWK > 1 ? 1 : 4;       // column strips per workgroup
     constexpr int NACC = 2 * WD;                   // accumulator tiles (consecutive columns) per lane
     typedef typename XVec<WD>::type xvec_t;
+    typedef BlockBody<N, M, B, WD, true> BodyP;
+    typedef BlockBody<N, M, B, WD, false> BodyL;
 
     // Workgroup -> (block-row, strip group); ids are dealt round-robin to the 8 XCDs, and all
     // block-rows of a strip group get ids on the same XCD so they share its L2 for X.
@@ -144,8 +267,12 @@ __global__ __launch_bounds__(NWK > 1 ? 64 * NWK : 256) void spmm_reg_kernel(Spmm
     if (NWK == 1 && wave_col >= p.Ncol) return;   // no barriers in this mode
     const int64_t col0 = wave_col + jj * NACC;
     const bool col_ok = col0 < p.Ncol;
-    // lanes past the last column read column 0 instead (in bounds); they never store
-    const uint16_t* xlane = p.X + (col_ok ? col0 : 0) + (int64_t)hh * 8 * p.ldx;
+    // lane part of every X address (bytes): its 8-row half and its columns; lanes past the last
+    // column read column 0 instead (in bounds) and never store
+    const uint32_t lane_off = (uint32_t)(((int64_t)hh * 8 * p.ldx + (col_ok ? col0 : 0)) * 2);
+    const uint32_t a_off = (uint32_t)((jj * F::SLOTS + hh * F::FS) * 2);
+    const uint32_t i_off = (uint32_t)(jj * F::WPR * 4);
+    const uint32_t aw_sh = (uint32_t)hh * F::HB;
 
     const int t_begin = p.row_ptr[bi], t_end = p.row_ptr[bi + 1];
     const int first = t_begin + (NWK > 1 ? wave : 0);
@@ -163,132 +290,73 @@ __global__ __launch_bounds__(NWK > 1 ? 64 * NWK : 256) void spmm_reg_kernel(Spmm
     uint32_t av[PF][RT][KS][F::VW];
     uint32_t aw[PF][RT][F::WPR];
 
-    auto load_x = [&](xvec_t (&dst)[8], int bj, int ks) {
-        const int kbase = bj * B + ks * 16;
-        const uint16_t* src = xlane + (int64_t)kbase * p.ldx;
-        if (kbase + 16 <= p.K) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) dst[i] = *reinterpret_cast<const xvec_t*>(src + (int64_t)i * p.ldx);
-        } else {
-            // ragged last block column: rows >= K do not exist and must read as zero (the
-            // matching weights are zero padding, and 0 * garbage could be NaN)
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                xvec_t z = {};
-                if (kbase + hh * 8 + i < p.K) z = *reinterpret_cast<const xvec_t*>(src + (int64_t)i * p.ldx);
-                dst[i] = z;
-            }
-        }
-    };
-    // The lane's slice of block t: row rt*32 + jj, columns ks*16 + hh*8 .. +8.
-    auto load_a = [&](uint32_t (&v)[RT][KS][F::VW], uint32_t (&w)[RT][F::WPR], int t) {
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-            const size_t brow = (size_t)t * B + rt * 32 + jj;
-            const uint16_t* vrow = p.vals + brow * F::SLOTS + hh * F::FS;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) load_vals<F::FS>(vrow + ks * 2 * F::FS, v[rt][ks]);
-            if constexpr (N != M) {
-                const uint32_t* irow = p.idxw + brow * F::WPR;
-                uint32_t raw[F::WPR + 1];
-#pragma unroll
-                for (int i = 0; i < F::WPR; ++i) raw[i] = irow[i];
-                raw[F::WPR] = 0u;
-                const uint32_t sh = (uint32_t)hh * F::HB;   // 0 or HB (< 32): drop the other half's bits
-#pragma unroll
-                for (int i = 0; i < F::WPR; ++i) w[rt][i] = __builtin_amdgcn_alignbit(raw[i + 1], raw[i], sh);
-            }
-        }
-    };
-
-    // ---- prologue: PF blocks in flight -----------------------------------------------------
+    // ---- prologue: up to PF blocks in flight -------------------------------------------------
 #pragma unroll
     for (int d = 0; d < PF; ++d) {
         if (d < cnt) {
             const int t = first + d * NWK;
             const int bj = p.col_idx[t];
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) load_x(xr[d][ks], bj, ks);
-            load_a(av[d], aw[d], t);
+            for (int ks = 0; ks < KS; ++ks) BodyL::load_x(xr[d][ks], p, lane_off, bj, ks);
+            BodyL::load_a(av[d], aw[d], p, a_off, i_off, t);
         }
     }
 
-    // ---- walk this wave's kept blocks --------------------------------------------------------
-    for (int i0 = 0; i0 < cnt; i0 += PF) {
+    // ---- steady state: every block of the group of PF has a successor PF blocks later ---------
+    int i0 = 0;
+    for (; i0 + 2 * PF <= cnt; i0 += PF) {
 #pragma unroll
-        for (int d = 0; d < PF; ++d) {
-            const int i = i0 + d;
-            if (i < cnt) {
-                const bool has_next = i + PF < cnt;
-                const int t_next = first + (i + PF) * NWK;
-                const int bj_next = has_next ? p.col_idx[t_next] : 0;
-                auto step = [&](auto ks_tag) {
-                    constexpr int ks = decltype(ks_tag)::value;
-                    uint32_t xd[8][WD];
+        for (int d = 0; d < PF; ++d)
+            BodyP::run(acc, xr[d], av[d], aw[d], p, lane_off, a_off, i_off, aw_sh, first + (i0 + d + PF) * NWK);
+    }
+    // ---- tail: at most 2*PF-1 blocks; the first PF-1 of them may still have a successor -------
 #pragma unroll
-                    for (int r = 0; r < 8; ++r) xvec_unpack(xr[d][ks][r], xd[r]);
-                    bf16x8 bfrag[NACC];
-#pragma unroll
-                    for (int pd = 0; pd < WD; ++pd) {
-                        u32x4 lo, hi;
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const uint32_t r0 = xd[2 * q][pd], r1 = xd[2 * q + 1][pd];
-                            lo[q] = (r0 & 0xFFFFu) | (r1 << 16);
-                            hi[q] = (r0 >> 16) | (r1 & 0xFFFF0000u);
-                        }
-                        bfrag[2 * pd] = __builtin_bit_cast(bf16x8, lo);
-                        bfrag[2 * pd + 1] = __builtin_bit_cast(bf16x8, hi);
-                    }
-                    if (has_next) load_x(xr[d][ks], bj_next, ks);
-#pragma unroll
-                    for (int rt = 0; rt < RT; ++rt) {
-                        const u32x4 a4 = expand_frag<N, M, B, ks>(av[d][rt][ks], aw[d][rt]);
-                        const bf16x8 afrag = __builtin_bit_cast(bf16x8, a4);
-#pragma unroll
-                        for (int c = 0; c < NACC; ++c)
-                            acc[rt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag[c], acc[rt][c], 0, 0, 0);
-                    }
-                };
-                step(std::integral_constant<int, 0>{});
-                step(std::integral_constant<int, 1>{});
-                if constexpr (KS == 4) {
-                    step(std::integral_constant<int, 2>{});
-                    step(std::integral_constant<int, 3>{});
-                }
-                if (has_next) load_a(av[d], aw[d], t_next);
-            }
+    for (int e = 0; e < 2 * PF - 1; ++e) {
+        const int i = i0 + e;
+        if (i < cnt) {
+            if (e < PF - 1 && i + PF < cnt)
+                BodyP::run(acc, xr[e % PF], av[e % PF], aw[e % PF], p, lane_off, a_off, i_off, aw_sh,
+                           first + (i + PF) * NWK);
+            else
+                BodyL::run(acc, xr[e % PF], av[e % PF], aw[e % PF], p, lane_off, a_off, i_off, aw_sh, 0);
         }
     }
 
     // ---- epilogue: accumulator register r of a 32x32 tile is row 8*(r/4) + 4*hh + r%4 of the
-    //      tile, column jj; the NACC tiles of a lane are consecutive columns ------------------
-    auto store_row = [&](int row, const float (&v)[NACC]) {
-        if (row >= p.S || !col_ok) return;
-        const bool full = col0 + NACC <= p.Ncol;
+    //      tile, column jj; the NACC tiles of a lane are consecutive columns.  Y is written
+    //      through a buffer resource that spans the block-row's existing rows: rows past S and
+    //      lanes past the last column fall outside its range and the hardware drops them, so the
+    //      stores need no branches.  (Ncol is a multiple of 4 here, so a lane's columns are all
+    //      inside or all outside.)
+    const uint32_t esz = p.y_bf16 ? 2u : 4u;
+    const uint32_t row_bytes = (uint32_t)p.ldy * esz;
+    const int rows_here = min(B, p.S - bi * B);
+    const rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(
+        reinterpret_cast<char*>(p.Y) + (int64_t)bi * B * p.ldy * esz, 0, (uint32_t)rows_here * row_bytes, 0x00020000);
+    const uint32_t y_off = col_ok ? (uint32_t)(4 * hh) * row_bytes + (uint32_t)col0 * esz : 0x80000000u;
+    auto store_row = [&](int tile_row, const float (&v)[NACC]) {
+        const uint32_t off = y_off + (uint32_t)tile_row * row_bytes;
         if (p.y_bf16) {
-            uint16_t* y = reinterpret_cast<uint16_t*>(p.Y) + (int64_t)row * p.ldy + col0;
-            if (full) {
-                uint32_t pk[WD];
+            uint32_t pk[WD];
 #pragma unroll
-                for (int c = 0; c < WD; ++c)
-                    pk[c] = float_to_bf16_rne(v[2 * c]) | ((uint32_t)float_to_bf16_rne(v[2 * c + 1]) << 16);
-                if constexpr (WD == 1) *reinterpret_cast<uint32_t*>(y) = pk[0];
-                else *reinterpret_cast<uint2*>(y) = make_uint2(pk[0], pk[WD - 1]);
+            for (int c = 0; c < WD; ++c) {
+                const f32x2 two = {v[2 * c], v[2 * c + 1]};
+                pk[c] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2));  // v_cvt_pk_bf16_f32 (RNE)
+            }
+            if constexpr (WD == 1) {
+                __builtin_amdgcn_raw_buffer_store_b32(pk[0], ry, off, 0, 0);
             } else {
-#pragma unroll
-                for (int c = 0; c < NACC; ++c)
-                    if (col0 + c < p.Ncol) y[c] = float_to_bf16_rne(v[c]);
+                const u32x2 two = {pk[0], pk[WD - 1]};
+                __builtin_amdgcn_raw_buffer_store_b64(two, ry, off, 0, 0);
             }
         } else {
-            float* y = reinterpret_cast<float*>(p.Y) + (int64_t)row * p.ldy + col0;
-            if (full) {
-                if constexpr (WD == 1) *reinterpret_cast<float2*>(y) = make_float2(v[0], v[1]);
-                else *reinterpret_cast<float4*>(y) = make_float4(v[0], v[1], v[NACC - 2], v[NACC - 1]);
+            if constexpr (WD == 1) {
+                const u32x2 two = {__float_as_uint(v[0]), __float_as_uint(v[1])};
+                __builtin_amdgcn_raw_buffer_store_b64(two, ry, off, 0, 0);
             } else {
-#pragma unroll
-                for (int c = 0; c < NACC; ++c)
-                    if (col0 + c < p.Ncol) y[c] = v[c];
+                const u32x4 four = {__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[NACC - 2]),
+                                    __float_as_uint(v[NACC - 1])};
+                __builtin_amdgcn_raw_buffer_store_b128(four, ry, off, 0, 0);
             }
         }
     };
@@ -301,7 +369,7 @@ __global__ __launch_bounds__(NWK > 1 ? 64 * NWK : 256) void spmm_reg_kernel(Spmm
                 float v[NACC];
 #pragma unroll
                 for (int c = 0; c < NACC; ++c) v[c] = acc[rt][c][r];
-                store_row(bi * B + rt * 32 + 8 * (r >> 2) + 4 * hh + (r & 3), v);
+                store_row(rt * 32 + 8 * (r >> 2) + (r & 3), v);
             }
     } else {
         // partial sums of the NWK waves -> LDS, then wave w adds up and stores every NWK-th row
@@ -325,7 +393,7 @@ __global__ __launch_bounds__(NWK > 1 ? 64 * NWK : 256) void spmm_reg_kernel(Spmm
                 v[c] = s;
             }
             const int rt = pr >> 4, r = pr & 15;
-            store_row(bi * B + rt * 32 + 8 * (r >> 2) + 4 * hh + (r & 3), v);
+            store_row(rt * 32 + 8 * (r >> 2) + (r & 3), v);
         }
     }
 }
@@ -347,10 +415,10 @@ hipError_t launch_reg(const SpmmArgs& a, hipStream_t st) {
 template <int N, int M, int B>
 hipError_t launch_reg_shape(const SpmmArgs& a, int shape, hipStream_t st) {
     switch (shape) {
-        case 0: return launch_reg<N, M, B, 2, 1, 2>(a, st);
-        case 1: return launch_reg<N, M, B, 1, 1, 3>(a, st);
-        case 2: return launch_reg<N, M, B, 1, 4, 2>(a, st);
-        default: return launch_reg<N, M, B, 1, 8, 2>(a, st);
+        case 0: return launch_reg<N, M, B, 2, 1, 1>(a, st);
+        case 1: return launch_reg<N, M, B, 1, 1, 1>(a, st);
+        case 2: return launch_reg<N, M, B, 1, 4, 1>(a, st);
+        default: return launch_reg<N, M, B, 1, 8, 1>(a, st);
     }
 }
 

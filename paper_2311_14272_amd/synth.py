@@ -223,10 +223,23 @@ def small_cases() -> List[LayerSpec]:
         mk("t_ragged_b32", 24, 144, 1000, 2, 4, 32, 0.6, SAL_MAG, 0.1),
         mk("t_ragged_b64", 70, 147, 392, 2, 4, 64, 0.67, SAL_GRAD, 0.1),
         mk("t_ragged_m8", 40, 150, 80, 2, 8, 32, 0.5, SAL_GRAD, 0.1),
+        mk("t_odd_ncol", 64, 128, 1003, 2, 4, 32, 0.5, SAL_MAG, 0.05),
         mk("t_dense_nm", 64, 128, 96, 4, 4, 32, 0.5, SAL_MAG, 0.05),
+        mk("t_dense_m8", 64, 128, 160, 8, 8, 64, 0.5, SAL_MAG, 0.05),
         mk("t_all_blocks", 64, 128, 64, 2, 4, 64, 1.0, SAL_MAG, 0.05),
         mk("t_uneven_rows", 256, 512, 264, 2, 4, 64, 0.3, SAL_GRAD, 0.05, None, LAYER_TOPK),
         mk("t_uneven_b32", 160, 320, 136, 1, 4, 32, 0.25, SAL_MAG, 0.05, None, LAYER_TOPK),
+    ]
+
+
+def b16_cases() -> List[LayerSpec]:
+    """16 x 16 blocks (the paper's smallest block size): selection and packing only."""
+    mk = LayerSpec
+    return [
+        mk("b16_2:4", 48, 80, 8, 2, 4, 16, 0.5, SAL_GRAD, 0.05),
+        mk("b16_1:4", 64, 48, 8, 1, 4, 16, 0.67, SAL_MAG, 0.05),
+        mk("b16_2:8_ragged", 40, 90, 8, 2, 8, 16, 0.5, SAL_MAG, 0.05),
+        mk("b16_3:4_uneven", 64, 128, 8, 3, 4, 16, 0.4, SAL_GRAD, 0.05, None, LAYER_TOPK),
     ]
 
 

@@ -84,6 +84,34 @@ def test_every_launch_shape(L, shape):
         check_product(Y, Yref, Aref, yd, "%s shape %d" % (L.name, shape))
 
 
+@pytest.mark.parametrize("L", synth.b16_cases(), ids=lambda L: L.name)
+def test_select_pack_block16(L):
+    """16 x 16 blocks: selection and packing are bit-exact; the product reports EUNSUPPORTED."""
+    W, G, X = synth.draw_small(L, 24)
+    sel, vals, idxw, flags = oracle_all(L, W, G)
+    layer, out = run_select_pack(L, W, G)
+    assert_select_pack_equal(L, out, sel, vals, idxw, flags)
+    with pytest.raises(crisp.CrispError) as e:
+        Y = torch.zeros((L.S, 8), dtype=torch.float32, device="cuda")
+        crisp.crisp_spmm(layer.desc, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dev(X), 8, 8, Y, 8)
+    assert e.value.status == crisp.EUNSUPPORTED
+
+
+def test_bf16_output_is_rounded_fp32_output():
+    """bf16 Y must be the round-to-nearest-even of the fp32 Y the same launch shape produces."""
+    for L in synth.small_cases()[:4]:
+        W, G, X = synth.draw_small(L, 25)
+        layer, _ = run_select_pack(L, W, G)
+        ldx = (L.Ncol + 7) // 8 * 8
+        Xp = np.zeros((L.K, ldx), dtype=np.uint16)
+        Xp[:, : L.Ncol] = X
+        dX = dev(Xp)
+        for shape in (0, 1, 2, 4):
+            y32 = run_spmm(layer, dX, L.Ncol, ldx, crisp.Y_F32, L.S, shape=shape).astype(np.float32)
+            y16 = run_spmm(layer, dX, L.Ncol, ldx, crisp.Y_BF16, L.S, shape=shape).astype(np.float32)
+            assert (synth.f32_to_bf16_bits(y16) == synth.f32_to_bf16_bits(y32)).all(), (L.name, shape)
+
+
 def test_ties_and_zero_weights():
     """Constant saliency (every comparison is a tie) and weights with exact zeros / negative zeros."""
     L = synth.LayerSpec("ties", 64, 128, 64, 2, 4, 32, 0.5, synth.SAL_GIVEN, 1.0)

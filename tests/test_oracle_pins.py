@@ -176,7 +176,7 @@ def _pipeline(L, seed=7):
     return W, G, X, sel
 
 
-@pytest.mark.parametrize("L", synth.small_cases(), ids=lambda L: L.name)
+@pytest.mark.parametrize("L", synth.small_cases() + synth.b16_cases(), ids=lambda L: L.name)
 def test_mask_invariants(L):
     W, G, X, sel = _pipeline(L)
     S, K, B, n, m = L.S, L.K, L.B, L.n, L.m
@@ -292,7 +292,7 @@ def test_block_score_summation_order_is_fixed():
 
 
 # ------------------------------------------------------------------ pack
-@pytest.mark.parametrize("L", synth.small_cases(), ids=lambda L: L.name)
+@pytest.mark.parametrize("L", synth.small_cases() + synth.b16_cases(), ids=lambda L: L.name)
 def test_pack_round_trip_and_sizes(L):
     W, G, X, sel = _pipeline(L, seed=9)
     S, K, B, n, m = L.S, L.K, L.B, L.n, L.m
