@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--y-dtype", choices=["bf16", "f32"], default="bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--spmm-only", action="store_true", help="time only the products (selection and packing done once)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 512 MiB device copy a few times (known traffic, for scaling profiler counters)")
     return ap.parse_args()
 
 
@@ -156,6 +158,16 @@ def main():
     useful = sum(x["useful_flop"] for x in info)
     dense_eq = sum(x["dense_flop"] for x in info)
     dom = int(np.argmax([x["alg_bytes"] for x in info]))   # dominant kernel: the product with the most traffic
+
+    if args.copy_calibration:
+        # a plain elementwise pass of known traffic (reads 512 MiB, writes 512 MiB) whose profiler
+        # counters give the scale of FETCH_SIZE / WRITE_SIZE on this machine
+        a = torch.ones(128 << 20, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(5):
+            torch.add(a, 1.0, out=b)
+        torch.cuda.synchronize()
+        del a, b
 
     # ---- warm-up, then the timed region ----------------------------------------------------
     for k in range(args.warmup):

@@ -138,7 +138,7 @@ crisp_status crisp_im2col(const crisp_conv_desc* c, const uint16_t* act, uint16_
     int64_t Ncol = (int64_t)c->batch * Ho * Wo;
     int64_t K = (int64_t)c->kh * c->kw * c->C;
     if (ldx < Ncol || Ncol > INT32_MAX || K > INT32_MAX) return CRISP_ESHAPE;
-    if ((int64_t)c->C * c->batch * c->H * c->W > ((int64_t)1 << 40)) return CRISP_ESHAPE;
+    if ((int64_t)c->batch * c->H * c->W >= ((int64_t)1 << 31) || K > 65535) return CRISP_EUNSUPPORTED;
     if (misaligned(act, 16) || misaligned(X, 16)) return CRISP_EALIGN;
     hipError_t e = launch_im2col(*c, act, X, ldx, (hipStream_t)stream);
     return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;

@@ -17,11 +17,6 @@ __device__ __forceinline__ int owner_row(const int32_t* __restrict__ row_ptr, in
     return lo;
 }
 
-// Keep bits of the aligned group of m columns starting at column k0 of weight row s.
-__device__ __forceinline__ uint32_t group_bits(const uint32_t* __restrict__ nm_mask, int mwpr, int s, int k0, int m) {
-    return (nm_mask[(size_t)s * mwpr + (k0 >> 5)] >> (k0 & 31)) & ((1u << m) - 1u);
-}
-
 // Position stored in slot j of a group: the j-th kept column of the group (0-based inside the
 // group), 0 when the group holds fewer kept elements (short last group), j when the group lies
 // wholly outside the matrix.
@@ -31,13 +26,31 @@ __device__ __forceinline__ uint32_t slot_position(uint32_t bits, int j, bool out
     return bits ? (uint32_t)(__ffs(bits) - 1) : 0u;
 }
 
+// The N:M keep bits of row s for the B columns of block column bj, as one 64-bit value
+// (bit c = column bj*B + c; bits of columns past K are zero because the mask never sets them).
+__device__ __forceinline__ uint64_t block_row_bits(const uint32_t* __restrict__ nm_mask, int mwpr, int s, int bj,
+                                                    int B) {
+    const uint32_t* row = nm_mask + (size_t)s * mwpr;
+    if (B == 64) {
+        const int w0 = bj * 2;
+        const uint64_t lo = row[w0];
+        const uint64_t hi = (w0 + 1 < mwpr) ? row[w0 + 1] : 0u;
+        return lo | (hi << 32);
+    }
+    if (B == 32) return row[bj];
+    return (row[bj >> 1] >> ((bj & 1) * 16)) & 0xFFFFu;
+}
+
 // One workgroup per kept block.  Phase 1: one thread per (block row, group) gathers the kept
 // values in ascending column order.  Phase 2: one thread per (block row, index word) assembles
-// the little-endian stream of log2(m)-bit positions.
+// the little-endian stream of log2(m)-bit positions.  Loops have fixed trip counts with guards
+// so that the loads of all iterations are in flight together.
 // uniform_k_row > 0: every block-row holds exactly that many blocks, so the owner of block t is
 // t / uniform_k_row and no search is needed.  flag_mode: 0 = flags[0] was preset to 1 and is
 // cleared when an aligned group of four holds more than two kept elements; 1 = the pattern can
 // never do that (n <= 2), workgroup 0 writes the constant.
+// VEC: K % m == 0, so a group's m weights are one aligned 8- or 16-byte load.
+template <bool VEC>
 __global__ __launch_bounds__(256) void pack_block_kernel(int S, int K, int n, int m, int B, int Sb, int w, int slots,
                                                          int wpr, int mwpr, int uniform_k_row, int flag_mode,
                                                          const uint16_t* __restrict__ W,
@@ -52,49 +65,71 @@ __global__ __launch_bounds__(256) void pack_block_kernel(int S, int K, int n, in
     const int G = B / m;
     if (flag_mode == 1 && t == 0 && threadIdx.x == 0) { flags[0] = 1; flags[1] = 0; flags[2] = 0; flags[3] = 0; }
     bool violates = false;
-    for (int e = threadIdx.x; e < B * G; e += 256) {
-        const int r = e / G, g = e % G;
-        const int s = bi * B + r, k0 = bj * B + g * m;
-        uint16_t* out = vals + ((size_t)t * B + r) * slots + g * n;
-        uint16_t v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (s < S && k0 < K) {
-            const uint32_t bits = group_bits(nm_mask, mwpr, s, k0, m);
-            const uint16_t* src = W + (size_t)s * K + k0;
-            uint16_t wv[8];
+    // B*G <= 64*16 = 1024 items -> at most 4 per thread
 #pragma unroll
-            for (int o = 0; o < 8; ++o) wv[o] = (o < m && k0 + o < K) ? src[o] : (uint16_t)0;
-            int filled = 0;
+    for (int it = 0; it < 4; ++it) {
+        const int e = threadIdx.x + it * 256;
+        if (e < B * G) {
+            const int r = e / G, g = e % G;
+            const int s = bi * B + r, k0 = bj * B + g * m;
+            uint16_t* out = vals + ((size_t)t * B + r) * slots + g * n;
+            uint16_t v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (s < S && k0 < K) {
+                const uint32_t bits = (uint32_t)(block_row_bits(nm_mask, mwpr, s, bj, B) >> (g * m)) & ((1u << m) - 1u);
+                const uint16_t* src = W + (size_t)s * K + k0;
+                uint16_t wv[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+                if (VEC) {
+                    if (m == 4) {
+                        const uint2 q = *reinterpret_cast<const uint2*>(src);
+                        wv[0] = q.x & 0xFFFFu; wv[1] = q.x >> 16; wv[2] = q.y & 0xFFFFu; wv[3] = q.y >> 16;
+                    } else {
+                        const uint4 q = *reinterpret_cast<const uint4*>(src);
+                        wv[0] = q.x & 0xFFFFu; wv[1] = q.x >> 16; wv[2] = q.y & 0xFFFFu; wv[3] = q.y >> 16;
+                        wv[4] = q.z & 0xFFFFu; wv[5] = q.z >> 16; wv[6] = q.w & 0xFFFFu; wv[7] = q.w >> 16;
+                    }
+                } else {
 #pragma unroll
-            for (int o = 0; o < 8; ++o) {
-                const bool on = (bits >> o) & 1u;
+                    for (int o = 0; o < 8; ++o) wv[o] = (o < m && k0 + o < K) ? src[o] : (uint16_t)0;
+                }
+                int filled = 0;
 #pragma unroll
-                for (int q = 0; q < 8; ++q)
-                    if (on && filled == q) v[q] = wv[o];
-                filled += on;
+                for (int o = 0; o < 8; ++o) {
+                    const bool on = (bits >> o) & 1u;
+#pragma unroll
+                    for (int q = 0; q < 8; ++q)
+                        if (on && filled == q) v[q] = wv[o];
+                    filled += on;
+                }
+                if (__popc(bits & 0xFu) > 2 || __popc(bits >> 4) > 2) violates = true;
             }
-            if (__popc(bits & 0xFu) > 2 || __popc(bits >> 4) > 2) violates = true;
-        }
 #pragma unroll
-        for (int q = 0; q < 8; ++q)
-            if (q < n) out[q] = v[q];
+            for (int q = 0; q < 8; ++q)
+                if (q < n) out[q] = v[q];
+        }
     }
     if (flag_mode == 0 && violates) atomicAnd(flags, 0);
-    for (int e = threadIdx.x; e < B * wpr; e += 256) {
-        const int r = e / wpr, x = e % wpr;
-        const int s = bi * B + r;
-        const int q_begin = (32 * x) / w;                         // first slot touching this word
-        const int q_end = min(slots, (32 * x + 31) / w + 1);      // one past the last
-        uint32_t word = 0;
-        for (int q = q_begin; q < q_end; ++q) {
-            const int g = q / n, j = q % n;
-            const int k0 = bj * B + g * m;
-            const bool outside = (s >= S) || (k0 >= K);
-            const uint32_t bits = outside ? 0u : group_bits(nm_mask, mwpr, s, k0, m);
-            const uint32_t pos = slot_position(bits, j, outside);
-            const int bit = q * w - 32 * x;                       // may be negative: field began in the previous word
-            word |= bit >= 0 ? (pos << bit) : (pos >> (-bit));
+    // B*wpr <= 64*6 = 384 words -> at most 2 per thread
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int e = threadIdx.x + it * 256;
+        if (e < B * wpr) {
+            const int r = e / wpr, x = e % wpr;
+            const int s = bi * B + r;
+            const bool row_outside = s >= S;
+            const uint64_t rowbits = row_outside ? 0ull : block_row_bits(nm_mask, mwpr, s, bj, B);
+            const int q_begin = (32 * x) / w;                         // first slot touching this word
+            const int q_end = min(slots, (32 * x + 31) / w + 1);      // one past the last
+            uint32_t word = 0;
+            for (int q = q_begin; q < q_end; ++q) {
+                const int g = q / n, j = q % n;
+                const bool outside = row_outside || (bj * B + g * m >= K);
+                const uint32_t bits = (uint32_t)(rowbits >> (g * m)) & ((1u << m) - 1u);
+                const uint32_t pos = slot_position(bits, j, outside);
+                const int bit = q * w - 32 * x;                       // may be negative: field began in the previous word
+                word |= bit >= 0 ? (pos << bit) : (pos >> (-bit));
+            }
+            idxw[((size_t)t * B + r) * wpr + x] = word;
         }
-        idxw[((size_t)t * B + r) * wpr + x] = word;
     }
 }
 
@@ -104,10 +139,15 @@ hipError_t launch_pack(const Geometry& g, int select_mode, const uint16_t* W, co
     // n <= 2 can never put three kept elements into an aligned group of four
     const int flag_mode = (g.n <= 2 && g.nk > 0) ? 1 : 0;
     if (flag_mode == 0) pack_init_flags_kernel<<<1, 64, 0, st>>>(flags);
-    if (g.nk > 0)
-        pack_block_kernel<<<g.nk, 256, 0, st>>>(g.S, g.K, g.n, g.m, g.B, g.Sb, g.w, g.slots, g.wpr, g.mwpr,
-                                                select_mode == CRISP_ROW_UNIFORM ? g.k_row : 0, flag_mode, W,
-                                                nm_mask, row_ptr, col_idx, vals, idxw, flags);
+    const int ukr = select_mode == CRISP_ROW_UNIFORM ? g.k_row : 0;
+    if (g.nk > 0) {
+        if (g.K % g.m == 0)
+            pack_block_kernel<true><<<g.nk, 256, 0, st>>>(g.S, g.K, g.n, g.m, g.B, g.Sb, g.w, g.slots, g.wpr, g.mwpr,
+                                                          ukr, flag_mode, W, nm_mask, row_ptr, col_idx, vals, idxw, flags);
+        else
+            pack_block_kernel<false><<<g.nk, 256, 0, st>>>(g.S, g.K, g.n, g.m, g.B, g.Sb, g.w, g.slots, g.wpr, g.mwpr,
+                                                           ukr, flag_mode, W, nm_mask, row_ptr, col_idx, vals, idxw, flags);
+    }
     return hipGetLastError();
 }
 

@@ -16,94 +16,123 @@ __device__ __forceinline__ float saliency_of(uint16_t w, float tg) {
     return fabsf(bf16_bits_to_float(w));
 }
 
-// One wave per B x B block; lane r owns row r of the block.  The lane loads its B weights (and
-// B gradient / saliency values) with 16-byte loads, ranks every aligned group of M columns
-// (keep the n first under: larger saliency first, on a tie the smaller column first), writes its
-// part of the N:M mask, and adds the kept saliencies left to right in fp64.  Lane 0 then adds the
-// row sums top to bottom.  That summation order is part of the definition of the block score
-// (a tree reduction would round differently).
+// One workgroup per B x B block, Q lanes per block row (Q * CPT = B columns, CPT = 16 or 8).
+// Each lane loads its CPT weights (and gradient / saliency values) with 16-byte loads, ranks
+// every aligned group of M columns (keep the n first under: larger saliency first, on a tie the
+// smaller column first), and leaves "saliency if kept else +0" in LDS.  The Q lanes of a row
+// OR their mask bits together with xor-shuffles.  Then lane r of the first wave adds row r's B
+// values left to right in fp64 and lane 0 adds the row sums top to bottom: that summation order
+// is part of the definition of the block score (a tree reduction would round differently;
+// adding +0.0 for a pruned element leaves the non-negative running sum unchanged bit for bit).
 // VEC: row segments are 16-byte aligned and lie wholly inside the matrix (K % B == 0).
 template <int B, int M, int KIND, bool VEC>
-__global__ __launch_bounds__(64) void score_select_kernel(int S, int K, int n, int Kb, int mwpr,
-                                                          const uint16_t* __restrict__ W,
-                                                          const float* __restrict__ TG,
-                                                          uint32_t* __restrict__ nm_mask,
-                                                          double* __restrict__ score) {
-    __shared__ double rowsum[64];
-    const int bj = blockIdx.x, bi = blockIdx.y, r = threadIdx.x;
+__global__ __launch_bounds__(B * (B / 16)) void score_select_kernel(int S, int K, int n, int Kb, int mwpr,
+                                                                   const uint16_t* __restrict__ W,
+                                                                   const float* __restrict__ TG,
+                                                                   uint32_t* __restrict__ nm_mask,
+                                                                   double* __restrict__ score) {
+    constexpr int CPT = 16;          // columns per lane
+    constexpr int Q = B / CPT;       // lanes per block row (1, 2 or 4)
+    constexpr int LDT = B + 4;       // padded LDS row stride in floats (keeps 16-byte alignment)
+    __shared__ __attribute__((aligned(16))) float tkept[B * LDT];
+    __shared__ double rowsum[B];
+    const int bj = blockIdx.x, bi = blockIdx.y;
+    const int r = threadIdx.x / Q, q = threadIdx.x % Q;
     const int s = bi * B + r;
-    const int k_begin = bj * B;
-    double acc = 0.0;
-    if (r < B && s < S) {
-        uint16_t w[B];
-        float tg[B];
-        const size_t e0 = (size_t)s * K + k_begin;
-        const int len = min(B, K - k_begin);
-        if (VEC) {
+    const int c0 = q * CPT;                      // first column of this lane inside the block
+    const int k0 = bj * B + c0;
+    uint32_t bits = 0;
+    {
+        uint16_t w[CPT];
+        float tg[CPT];
+        const int len = (s < S) ? min(CPT, K - k0) : 0;   // columns of this lane that exist (may be <= 0)
+        const size_t e0 = (size_t)s * K + k0;
+        if (VEC && s < S) {
             if (KIND != CRISP_SAL_GIVEN) {
 #pragma unroll
-                for (int i = 0; i < B / 8; ++i) {
+                for (int i = 0; i < CPT / 8; ++i) {
                     const u32x4 v = *reinterpret_cast<const u32x4*>(W + e0 + 8 * i);
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        w[8 * i + 2 * q] = (uint16_t)(v[q] & 0xFFFFu);
-                        w[8 * i + 2 * q + 1] = (uint16_t)(v[q] >> 16);
+                    for (int x = 0; x < 4; ++x) {
+                        w[8 * i + 2 * x] = (uint16_t)(v[x] & 0xFFFFu);
+                        w[8 * i + 2 * x + 1] = (uint16_t)(v[x] >> 16);
                     }
                 }
             }
             if (KIND != CRISP_SAL_MAG) {
 #pragma unroll
-                for (int i = 0; i < B / 4; ++i) {
+                for (int i = 0; i < CPT / 4; ++i) {
                     const f32x4 v = *reinterpret_cast<const f32x4*>(TG + e0 + 4 * i);
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) tg[4 * i + q] = v[q];
+                    for (int x = 0; x < 4; ++x) tg[4 * i + x] = v[x];
                 }
             }
         } else {
 #pragma unroll
-            for (int i = 0; i < B; ++i) {
+            for (int i = 0; i < CPT; ++i) {
                 w[i] = (KIND != CRISP_SAL_GIVEN && i < len) ? W[e0 + i] : (uint16_t)0;
                 tg[i] = (KIND != CRISP_SAL_MAG && i < len) ? TG[e0 + i] : 0.0f;
             }
         }
-        uint32_t bits[B / 32 > 0 ? B / 32 : 1] = {};
+        float kept_t[CPT];
 #pragma unroll
-        for (int g = 0; g < B / M; ++g) {
+        for (int g = 0; g < CPT / M; ++g) {
             float t[M];
 #pragma unroll
             for (int i = 0; i < M; ++i) t[i] = saliency_of<KIND>(w[g * M + i], tg[g * M + i]);
-            const int glen = len - g * M;  // columns of this group that exist (may be <= 0)
+            const int glen = len - g * M;
 #pragma unroll
             for (int i = 0; i < M; ++i) {
                 int before = 0;
 #pragma unroll
                 for (int j = 0; j < M; ++j) before += (j < glen) && (t[j] > t[i] || (t[j] == t[i] && j < i));
-                if (i < glen && before < n) {
-                    bits[(g * M + i) / 32] |= 1u << ((g * M + i) % 32);
-                    acc = __dadd_rn(acc, (double)t[i]);
-                }
+                const bool kept = (i < glen) && (before < n);
+                bits |= (kept ? 1u : 0u) << (g * M + i);
+                kept_t[g * M + i] = kept ? t[i] : 0.0f;
             }
         }
-        if (B >= 32) {
 #pragma unroll
-            for (int x = 0; x < B / 32; ++x) {
-                const int word = (k_begin >> 5) + x;
-                if (word < mwpr) nm_mask[(size_t)s * mwpr + word] = bits[x];
-            }
-        } else {
-            // B == 16: two blocks share a mask word; each writes its own half
-            uint16_t* half = reinterpret_cast<uint16_t*>(nm_mask) + ((size_t)s * mwpr) * 2;
-            const int h = k_begin >> 4;
-            half[h] = (uint16_t)bits[0];
-            // an odd number of block columns leaves the upper half of the last word to nobody
-            if (bj == Kb - 1 && (h & 1) == 0) half[h + 1] = 0;
+        for (int i = 0; i < CPT / 4; ++i) {
+            const f32x4 v = {kept_t[4 * i], kept_t[4 * i + 1], kept_t[4 * i + 2], kept_t[4 * i + 3]};
+            *reinterpret_cast<f32x4*>(&tkept[r * LDT + c0 + 4 * i]) = v;
         }
     }
-    rowsum[r] = acc;
+    // mask: the Q lanes of a row hold 16 bits each; pairs of lanes form one 32-bit word
+    if (Q >= 2) {
+        uint32_t word = bits << ((q & 1) * 16);
+        word |= __shfl_xor(word, 1, 64);
+        const int widx = (bj * B + c0) >> 5;
+        if ((q & 1) == 0 && s < S && widx < mwpr) nm_mask[(size_t)s * mwpr + widx] = word;
+    } else if (s < S) {
+        // B == 16: two blocks share a mask word; each writes its own half
+        uint16_t* half = reinterpret_cast<uint16_t*>(nm_mask) + ((size_t)s * mwpr) * 2;
+        const int h = (bj * B) >> 4;
+        half[h] = (uint16_t)bits;
+        // an odd number of block columns leaves the upper half of the last word to nobody
+        if (bj == Kb - 1 && (h & 1) == 0) half[h + 1] = 0;
+    }
     __syncthreads();
-    if (r == 0) {
+    if (threadIdx.x < B) {
+        const int row = threadIdx.x;
+        double acc = 0.0;
+#pragma unroll
+        for (int i = 0; i < B / 4; ++i) {
+            const f32x4 v = *reinterpret_cast<const f32x4*>(&tkept[row * LDT + 4 * i]);
+            acc = __dadd_rn(acc, (double)v[0]);
+            acc = __dadd_rn(acc, (double)v[1]);
+            acc = __dadd_rn(acc, (double)v[2]);
+            acc = __dadd_rn(acc, (double)v[3]);
+        }
+        rowsum[row] = acc;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double part[B];
+#pragma unroll
+        for (int i = 0; i < B; ++i) part[i] = rowsum[i];
         double total = 0.0;
-        for (int i = 0; i < B; ++i) total = __dadd_rn(total, rowsum[i]);
+#pragma unroll
+        for (int i = 0; i < B; ++i) total = __dadd_rn(total, part[i]);
         score[(size_t)bi * Kb + bj] = total;
     }
 }
@@ -195,9 +224,9 @@ static void launch_score_select(const Geometry& g, const uint16_t* W, const floa
                                 double* score, hipStream_t st) {
     const dim3 grd(g.Kb, g.Sb);
     if (g.K % B == 0)
-        score_select_kernel<B, M, KIND, true><<<grd, 64, 0, st>>>(g.S, g.K, g.n, g.Kb, g.mwpr, W, TG, nm_mask, score);
+        score_select_kernel<B, M, KIND, true><<<grd, B * (B / 16), 0, st>>>(g.S, g.K, g.n, g.Kb, g.mwpr, W, TG, nm_mask, score);
     else
-        score_select_kernel<B, M, KIND, false><<<grd, 64, 0, st>>>(g.S, g.K, g.n, g.Kb, g.mwpr, W, TG, nm_mask, score);
+        score_select_kernel<B, M, KIND, false><<<grd, B * (B / 16), 0, st>>>(g.S, g.K, g.n, g.Kb, g.mwpr, W, TG, nm_mask, score);
 }
 
 template <int KIND>

@@ -265,7 +265,10 @@ static int pick_shape(const Geometry& g, int64_t Ncol, double density_hint) {
     double d = (density_hint > 0.0 && density_hint <= 1.0) ? density_hint : 0.5;
     const double blocks_per_row = d * g.Kb;
     if (narrow >= 3072 || blocks_per_row < 3.0) return 1;
-    if (blocks_per_row >= 8.0 && narrow * 8 <= 6144) return 3;
+    // the 8-way split keeps 8 partial tiles in LDS (128 KB for 64-row blocks: one workgroup per
+    // CU), so it only pays when all workgroups are resident at once
+    const int64_t resident8 = g.B == 64 ? 256 : 512;
+    if (blocks_per_row >= 8.0 && narrow <= resident8) return 3;
     return 2;
 }
 

@@ -19,6 +19,10 @@
 #pragma once
 #include <type_traits>
 
+#ifndef CRISP_DEBUG_VARIANT
+#define CRISP_DEBUG_VARIANT 0  // timing experiments only: 1 no X loads, 2 no MFMA, 3 no expansion
+#endif
+
 #include "crisp_internal.h"
 
 namespace crisp {
@@ -160,8 +164,20 @@ struct BlockBody {
         const int kb = min(bj * B + ks * 16, p.K - 16);
         const rsrc_t r = make_rsrc(p.X + (int64_t)kb * p.ldx);
         const uint32_t row_bytes = (uint32_t)p.ldx * 2u;
+#if CRISP_DEBUG_VARIANT == 4
+        // every load of the strip hits the same X row: same instruction stream, all cache hits
+        const rsrc_t r4 = make_rsrc(p.X);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) dst[i] = buf_load_x<WD>(r4, lane_off & 0xFFFu, 0u);
+        (void)r; (void)row_bytes;
+#elif CRISP_DEBUG_VARIANT == 1
+        (void)r; (void)row_bytes;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) dst[i] = xvec_t{};
+#else
 #pragma unroll
         for (int i = 0; i < 8; ++i) dst[i] = buf_load_x<WD>(r, lane_off, (uint32_t)i * row_bytes);
+#endif
     }
 
     // Requests the lane's slice of block t: values of rows rt*32 + jj, columns ks*16 + hh*8 .. +8,
@@ -190,6 +206,23 @@ struct BlockBody {
     __device__ static __forceinline__ void step(f32x16 (&acc)[RT][NACC], xvec_t (&xr)[KS][8],
                                                 const uint32_t (&av)[RT][KS][F::VW], const uint32_t (&ws)[RT][F::WPR],
                                                 const SpmmArgs& p, uint32_t lane_off, int bj_next) {
+#if CRISP_DEBUG_VARIANT == 5
+        // loads only: fold the loaded words into one accumulator element, no transposes, no MFMA
+        {
+            uint32_t x5 = 0;
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                uint32_t t5[WD];
+                xvec_unpack(xr[ks][r], t5);
+#pragma unroll
+                for (int q = 0; q < WD; ++q) x5 ^= t5[q];
+            }
+            acc[0][0][ks] += __uint_as_float(x5 & 0x3FFFFFFFu);
+            if constexpr (PREFETCH) load_x(xr[ks], p, lane_off, bj_next, ks);
+            (void)av; (void)ws;
+            return;
+        }
+#endif
         // 8 rows x 2*WD columns of 16-bit halves -> 2*WD operands of 8 K-values each
         uint32_t xd[8][WD];
 #pragma unroll
@@ -200,9 +233,10 @@ struct BlockBody {
             u32x4 lo, hi;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
+                // v_perm_b32: result bytes picked from {r1 (bytes 4..7), r0 (bytes 0..3)}
                 const uint32_t r0 = xd[2 * q][pd], r1 = xd[2 * q + 1][pd];
-                lo[q] = (r0 & 0xFFFFu) | (r1 << 16);
-                hi[q] = (r0 >> 16) | (r1 & 0xFFFF0000u);
+                lo[q] = __builtin_amdgcn_perm(r1, r0, 0x05040100u);  // low halves:  r0.lo | r1.lo << 16
+                hi[q] = __builtin_amdgcn_perm(r1, r0, 0x07060302u);  // high halves: r0.hi | r1.hi << 16
             }
             bfrag[2 * pd] = __builtin_bit_cast(bf16x8, lo);
             bfrag[2 * pd + 1] = __builtin_bit_cast(bf16x8, hi);
@@ -210,11 +244,23 @@ struct BlockBody {
         if constexpr (PREFETCH) load_x(xr[ks], p, lane_off, bj_next, ks);
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
+#if CRISP_DEBUG_VARIANT == 3
+            u32x4 a4 = {av[rt][ks][0], ws[rt][0], av[rt][ks][0], ws[rt][0]};
+#else
             const u32x4 a4 = expand_frag<N, M, B, ks>(av[rt][ks], ws[rt]);
+#endif
             const bf16x8 afrag = __builtin_bit_cast(bf16x8, a4);
+#if CRISP_DEBUG_VARIANT == 2
+#pragma unroll
+            for (int c = 0; c < NACC; ++c) {
+                const u32x4 bb = __builtin_bit_cast(u32x4, bfrag[c]);
+                acc[rt][c][0] += __uint_as_float((a4[0] ^ bb[0] ^ bb[1] ^ bb[2] ^ bb[3] ^ a4[1] ^ a4[2] ^ a4[3]) & 0x3FFFFFFFu);
+            }
+#else
 #pragma unroll
             for (int c = 0; c < NACC; ++c)
                 acc[rt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag[c], acc[rt][c], 0, 0, 0);
+#endif
         }
     }
 
@@ -244,7 +290,8 @@ struct BlockBody {
 };
 
 template <int N, int M, int B, int WD, int NWK, int PF>
-__global__ __launch_bounds__(NWK > 1 ? 64 * NWK : 256) void spmm_reg_kernel(SpmmArgs p) {
+__global__ __launch_bounds__(NWK > 1 ? 64 * NWK : 256) __attribute__((amdgpu_waves_per_eu(2)))
+void spmm_reg_kernel(SpmmArgs p) {
     typedef Fmt<N, M, B> F;
     constexpr int RT = F::RT, KS = F::KS;
     constexpr int STRIPS = NWK > 1 ? 1 : 4;       // column strips per workgroup
