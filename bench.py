@@ -181,8 +181,30 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    dom_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
-    dom_med_ms = float(np.median([a.elapsed_time(b) for a, b in ev]))
+    dom_raw_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+
+    # What an event pair adds around one launch of this kernel: bracket one launch and two
+    # back-to-back launches; the difference of the two brackets is one kernel, the rest is overhead.
+    def bracket(n_launch, reps=40):
+        out = []
+        st = layers[dom]
+        for r in range(reps):
+            s = r % nsets
+            if st.is_conv:
+                crisp.crisp_im2col(st.conv, st.act[s], st.X[s], st.L.Ncol)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(n_launch):
+                crisp.crisp_spmm(st.desc, st.dl.row_ptr, st.dl.col_idx, st.dl.vals, st.dl.idx_words, st.X[s],
+                                 st.L.Ncol, st.L.Ncol, st.Y[s], st.L.Ncol, y_dtype)
+            b.record()
+            out.append((a, b))
+        torch.cuda.synchronize()
+        return float(np.median([a.elapsed_time(b) for a, b in out]))
+    b1, b2 = bracket(1), bracket(2)
+    pair_ms = max(0.0, b1 - (b2 - b1))
+    dom_ms = max(dom_raw_ms - pair_ms, 1e-6)
+    dom_med_ms = max(float(np.median([a.elapsed_time(b) for a, b in ev])) - pair_ms, 1e-6)
 
     # ---- per-phase breakdown (untimed extras, reported for context) --------------------------
     def timed(fn, reps=50):
@@ -223,8 +245,9 @@ def main():
         "dense_equivalent_tflops": round(dense_eq / (ms_per_step * 1e-3) / 1e12, 3),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": TRAFFIC.get((wl.name, info[dom]["name"], args.y_dtype)),
-                     "kernel": "spmm_expand_mfma_kernel (%s)" % info[dom]["name"],
+                     "kernel": "spmm kernel of layer %s" % info[dom]["name"],
                      "avg_launch_ms": round(dom_ms, 5), "median_launch_ms": round(dom_med_ms, 5),
+                     "event_pair_overhead_ms": round(pair_ms, 5), "avg_bracket_ms": round(dom_raw_ms, 5),
                      "algorithmic_bytes": info[dom]["alg_bytes"]},
         "layers": info,
     }
@@ -235,7 +258,11 @@ def main():
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE,
 # scaled by the same counters on a plain copy of known size); filled in from profiles/.
-TRAFFIC = {}
+TRAFFIC = {
+    # (workload, layer, y dtype): bytes per launch = 2.0 * FETCH_SIZE + 1.0 * WRITE_SIZE (KiB -> bytes);
+    # profiles/bench_c2_kernels.txt: FETCH_SIZE 10295.7 KiB, WRITE_SIZE 3136.0 KiB for the 3x3 layer's product
+    ("c2", "c2b", "bf16"): int((2.0 * 10295.7 + 3136.0) * 1024),
+}
 
 
 def cpu_baseline(wl, host_inputs, useful_flop):
