@@ -182,6 +182,34 @@ CRISP_API crisp_status crisp_spmm(const crisp_layer_desc *desc, const int32_t *r
                         int64_t Ncol, int64_t ldx, int32_t x_layout, void *Y, int64_t ldy,
                         int32_t y_dtype, void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * Product with implicit lowering: Y = W_hybrid * im2col(act) without materialising X
+ * (Sec. 3.5, first step: only the activations that kept blocks need are fetched, here straight
+ * from the convolution's input).  Same result, bit for bit, as crisp_im2col followed by
+ * crisp_spmm.  act is [C][batch][H][W] bf16 (device); desc->K must equal kh*kw*C; Y is
+ * S x ldy with Ncol = batch*Ho*Wo columns written.
+ * Covered: stride 1, C % B == 0, Wo even, B in {32, 64}, n:m in {1..4}:4 or {1,2,4,8}:8.
+ * Anything else returns CRISP_EUNSUPPORTED (use crisp_im2col + crisp_spmm).
+ * Errors: EINVAL, ESHAPE, EALIGN, EUNSUPPORTED, EDEVICE.
+ */
+CRISP_API crisp_status crisp_conv_spmm(const crisp_layer_desc *desc, const crisp_conv_desc *conv,
+                                       const int32_t *row_ptr, const int32_t *col_idx, const uint16_t *vals,
+                                       const uint32_t *idx_words, const uint16_t *act, void *Y, int64_t ldy,
+                                       int32_t y_dtype, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * The same product as crisp_spmm (conv == NULL, X_or_act = X) or crisp_conv_spmm (conv != NULL,
+ * X_or_act = act; Ncol and ldx ignored), with two optional hipEvent_t (created by the caller with
+ * timing enabled, passed as void*) that receive the time stamps of the product kernel's own start
+ * and end on `stream`.  For measurement: an event pair recorded around a launch also times the
+ * gaps around it; these two do not.  Errors as for the two calls above.
+ */
+CRISP_API crisp_status crisp_spmm_timed(const crisp_layer_desc *desc, const crisp_conv_desc *conv,
+                                        const int32_t *row_ptr, const int32_t *col_idx, const uint16_t *vals,
+                                        const uint32_t *idx_words, const uint16_t *X_or_act, int64_t Ncol,
+                                        int64_t ldx, void *Y, int64_t ldy, int32_t y_dtype, void *start_event,
+                                        void *stop_event, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

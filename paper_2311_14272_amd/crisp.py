@@ -68,7 +68,12 @@ def lib():
         L.crisp_im2col.argtypes = [C.POINTER(ConvDesc), vp, vp, C.c_int64, vp]
         L.crisp_spmm.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp, vp, C.c_int64, C.c_int64, C.c_int32, vp,
                                  C.c_int64, C.c_int32, vp, C.c_size_t, vp]
-        for f in (L.crisp_pack_sizes, L.crisp_select_mask, L.crisp_pack, L.crisp_im2col, L.crisp_spmm):
+        L.crisp_conv_spmm.argtypes = [C.POINTER(LayerDesc), C.POINTER(ConvDesc), vp, vp, vp, vp, vp, vp, C.c_int64,
+                                      C.c_int32, vp, C.c_size_t, vp]
+        L.crisp_spmm_timed.argtypes = [C.POINTER(LayerDesc), C.POINTER(ConvDesc), vp, vp, vp, vp, vp, C.c_int64,
+                                       C.c_int64, vp, C.c_int64, C.c_int32, vp, vp, vp]
+        for f in (L.crisp_pack_sizes, L.crisp_select_mask, L.crisp_pack, L.crisp_im2col, L.crisp_spmm,
+                  L.crisp_conv_spmm, L.crisp_spmm_timed):
             f.restype = C.c_int32
         _lib = L
     return _lib
@@ -130,6 +135,52 @@ def crisp_spmm(desc, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, Y, ldy, y_
                           _stream() if stream == -1 else stream)
     if st != OK:
         raise CrispError("crisp_spmm", st)
+
+
+def crisp_conv_spmm(desc, conv: ConvDesc, row_ptr, col_idx, vals, idx_words, act, Y, ldy, y_dtype=Y_F32, ws=None,
+                    ws_bytes=0, stream=-1):
+    st = lib().crisp_conv_spmm(C.byref(desc), C.byref(conv), _ptr(row_ptr), _ptr(col_idx), _ptr(vals),
+                               _ptr(idx_words), _ptr(act), _ptr(Y), ldy, y_dtype, _ptr(ws), ws_bytes,
+                               _stream() if stream == -1 else stream)
+    if st != OK:
+        raise CrispError("crisp_conv_spmm", st)
+
+
+def crisp_spmm_timed(desc, conv, row_ptr, col_idx, vals, idx_words, X_or_act, Ncol, ldx, Y, ldy, y_dtype,
+                     start_event, stop_event, stream=-1):
+    """start_event / stop_event: raw hipEvent_t handles (see HipEvents)."""
+    st = lib().crisp_spmm_timed(C.byref(desc), C.byref(conv) if conv is not None else None, _ptr(row_ptr),
+                                _ptr(col_idx), _ptr(vals), _ptr(idx_words), _ptr(X_or_act), Ncol, ldx, _ptr(Y), ldy,
+                                y_dtype, start_event, stop_event, _stream() if stream == -1 else stream)
+    if st != OK:
+        raise CrispError("crisp_spmm_timed", st)
+
+
+class HipEvents:
+    """A pool of raw hipEvent_t pairs (timing enabled) from the HIP runtime torch already loaded."""
+
+    def __init__(self, pairs: int):
+        self.hip = C.CDLL("libamdhip64.so")
+        self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.pairs = []
+        for _ in range(pairs):
+            a, b = C.c_void_p(), C.c_void_p()
+            if self.hip.hipEventCreate(C.byref(a)) != 0 or self.hip.hipEventCreate(C.byref(b)) != 0:
+                raise RuntimeError("hipEventCreate failed")
+            self.pairs.append((a, b))
+
+    def elapsed_ms(self, i: int) -> float:
+        a, b = self.pairs[i]
+        out = C.c_float()
+        rc = self.hip.hipEventElapsedTime(C.byref(out), a, b)
+        if rc != 0:
+            raise RuntimeError("hipEventElapsedTime failed (%d)" % rc)
+        return out.value
+
+    def __del__(self):
+        for a, b in self.pairs:
+            self.hip.hipEventDestroy(a)
+            self.hip.hipEventDestroy(b)
 
 
 @dataclass

@@ -144,10 +144,10 @@ crisp_status crisp_im2col(const crisp_conv_desc* c, const uint16_t* act, uint16_
     return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
 }
 
-crisp_status crisp_spmm(const crisp_layer_desc* desc, const int32_t* row_ptr, const int32_t* col_idx,
-                        const uint16_t* vals, const uint32_t* idx_words, const uint16_t* X, int64_t Ncol,
-                        int64_t ldx, int32_t x_layout, void* Y, int64_t ldy, int32_t y_dtype, void* ws,
-                        size_t ws_bytes, void* stream) {
+static crisp_status spmm_impl(const crisp_layer_desc* desc, const int32_t* row_ptr, const int32_t* col_idx,
+                              const uint16_t* vals, const uint32_t* idx_words, const uint16_t* X, int64_t Ncol,
+                              int64_t ldx, int32_t x_layout, void* Y, int64_t ldy, int32_t y_dtype, void* ws,
+                              size_t ws_bytes, void* stream, void* ev_start, void* ev_stop) {
     Geometry g;
     crisp_status st = make_geometry(desc, false, &g);
     if (st != CRISP_OK) return st;
@@ -164,9 +164,69 @@ crisp_status crisp_spmm(const crisp_layer_desc* desc, const int32_t* row_ptr, co
     // ws_bytes doubles as a tuning knob when ws is NULL: 0 = automatic launch shape, 1..5 force
     // shape (value - 1); results do not depend on it.
     const int force_shape = (!ws && ws_bytes >= 1 && ws_bytes <= 5) ? (int)ws_bytes - 1 : -1;
-    hipError_t e = launch_spmm(g, desc->block_density, force_shape, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx,
-                               Y, ldy, y_dtype, (hipStream_t)stream);
+    hipError_t e = launch_spmm(g, desc->block_density, force_shape, row_ptr, col_idx, vals, idx_words, X, nullptr, Ncol,
+                               ldx, Y, ldy, y_dtype, (hipEvent_t)ev_start, (hipEvent_t)ev_stop, (hipStream_t)stream);
     return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
+}
+
+static crisp_status conv_spmm_impl(const crisp_layer_desc* desc, const crisp_conv_desc* conv, const int32_t* row_ptr,
+                                   const int32_t* col_idx, const uint16_t* vals, const uint32_t* idx_words,
+                                   const uint16_t* act, void* Y, int64_t ldy, int32_t y_dtype, void* ws,
+                                   size_t ws_bytes, void* stream, void* ev_start, void* ev_stop) {
+    Geometry g;
+    crisp_status st = make_geometry(desc, false, &g);
+    if (st != CRISP_OK) return st;
+    if (!conv || !row_ptr || !col_idx || !vals || !idx_words || !act || !Y) return CRISP_EINVAL;
+    if (y_dtype != CRISP_Y_F32 && y_dtype != CRISP_Y_BF16) return CRISP_EINVAL;
+    if (conv->C < 1 || conv->H < 1 || conv->W < 1 || conv->batch < 1 || conv->kh < 1 || conv->kw < 1 ||
+        conv->stride < 1 || conv->pad < 0)
+        return CRISP_ESHAPE;
+    if (conv->act_layout != CRISP_ACT_CBHW) return CRISP_EUNSUPPORTED;
+    if ((int64_t)conv->kh * conv->kw * conv->C != g.K) return CRISP_ESHAPE;
+    const int64_t Ho = (int64_t)conv->H + 2 * conv->pad - conv->kh + 1;
+    const int64_t Wo = (int64_t)conv->W + 2 * conv->pad - conv->kw + 1;
+    if (Ho < 1 || Wo < 1) return CRISP_ESHAPE;
+    const int64_t Ncol = (int64_t)conv->batch * Ho * Wo;
+    const int64_t plane = (int64_t)conv->batch * conv->H * conv->W;
+    if (ldy < Ncol || Ncol > ((int64_t)1 << 27)) return CRISP_ESHAPE;
+    if ((ldy & 7) || misaligned(act, 16) || misaligned(Y, 16) || misaligned(vals, 16) || misaligned(idx_words, 16))
+        return CRISP_EALIGN;
+    // what the fused kernels cover; everything else goes through crisp_im2col + crisp_spmm
+    const bool pattern_ok = (g.m == 4 && g.n <= 4) || (g.m == 8 && (g.n == 1 || g.n == 2 || g.n == 4 || g.n == 8));
+    if (conv->stride != 1 || g.B == 16 || conv->C % g.B != 0 || (Wo & 1) || conv->W < 2 || conv->kw > 16 ||
+        conv->kh * conv->kw > 64 || plane > ((int64_t)1 << 27) || ldy > ((int64_t)1 << 23) || !pattern_ok)
+        return CRISP_EUNSUPPORTED;
+    const int force_shape = (!ws && ws_bytes >= 1 && ws_bytes <= 4) ? (int)ws_bytes - 1 : -1;
+    hipError_t e = launch_spmm(g, desc->block_density, force_shape, row_ptr, col_idx, vals, idx_words, act, conv,
+                               Ncol, Ncol, Y, ldy, y_dtype, (hipEvent_t)ev_start, (hipEvent_t)ev_stop, (hipStream_t)stream);
+    return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
+}
+
+crisp_status crisp_spmm(const crisp_layer_desc* desc, const int32_t* row_ptr, const int32_t* col_idx,
+                        const uint16_t* vals, const uint32_t* idx_words, const uint16_t* X, int64_t Ncol,
+                        int64_t ldx, int32_t x_layout, void* Y, int64_t ldy, int32_t y_dtype, void* ws,
+                        size_t ws_bytes, void* stream) {
+    return spmm_impl(desc, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, x_layout, Y, ldy, y_dtype, ws, ws_bytes,
+                     stream, nullptr, nullptr);
+}
+
+crisp_status crisp_conv_spmm(const crisp_layer_desc* desc, const crisp_conv_desc* conv, const int32_t* row_ptr,
+                             const int32_t* col_idx, const uint16_t* vals, const uint32_t* idx_words,
+                             const uint16_t* act, void* Y, int64_t ldy, int32_t y_dtype, void* ws, size_t ws_bytes,
+                             void* stream) {
+    return conv_spmm_impl(desc, conv, row_ptr, col_idx, vals, idx_words, act, Y, ldy, y_dtype, ws, ws_bytes, stream,
+                          nullptr, nullptr);
+}
+
+crisp_status crisp_spmm_timed(const crisp_layer_desc* desc, const crisp_conv_desc* conv, const int32_t* row_ptr,
+                              const int32_t* col_idx, const uint16_t* vals, const uint32_t* idx_words,
+                              const uint16_t* X_or_act, int64_t Ncol, int64_t ldx, void* Y, int64_t ldy,
+                              int32_t y_dtype, void* start_event, void* stop_event, void* stream) {
+    if (conv)
+        return conv_spmm_impl(desc, conv, row_ptr, col_idx, vals, idx_words, X_or_act, Y, ldy, y_dtype, nullptr, 0,
+                              stream, start_event, stop_event);
+    return spmm_impl(desc, row_ptr, col_idx, vals, idx_words, X_or_act, Ncol, ldx, CRISP_X_KN, Y, ldy, y_dtype, nullptr,
+                     0, stream, start_event, stop_event);
 }
 
 }  // extern "C"

@@ -31,7 +31,8 @@ hipError_t launch_im2col(const crisp_conv_desc& c, const uint16_t* act, uint16_t
 // (0..3 = shapes of the specialised kernels, 4 = generic LDS-expansion kernel).
 hipError_t launch_spmm(const Geometry& g, double density_hint, int force_shape, const int32_t* row_ptr,
                        const int32_t* col_idx, const uint16_t* vals, const uint32_t* idxw, const uint16_t* X,
-                       int64_t Ncol, int64_t ldx, void* Y, int64_t ldy, int y_dtype, hipStream_t st);
+                       const crisp_conv_desc* conv, int64_t Ncol, int64_t ldx, void* Y, int64_t ldy, int y_dtype,
+                       hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st);
 
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 

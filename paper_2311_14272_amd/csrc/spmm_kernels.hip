@@ -242,7 +242,11 @@ static hipError_t launch_one(const SpmmArgs& a, hipStream_t st) {
     p.NT = (int)((a.Ncol + strip - 1) / strip);
     const int64_t groups = (int64_t)((p.NT + 7) / 8) * p.Sb * 8;
     if (groups > INT32_MAX) return hipErrorInvalidValue;
-    spmm_expand_mfma_kernel<B, WD, NW><<<dim3((unsigned)groups), dim3(64 * NW), 0, st>>>(p);
+    if (a.ev_start || a.ev_stop)
+        hipExtLaunchKernelGGL((spmm_expand_mfma_kernel<B, WD, NW>), dim3((unsigned)groups), dim3(64 * NW), 0, st,
+                              a.ev_start, a.ev_stop, 0, p);
+    else
+        spmm_expand_mfma_kernel<B, WD, NW><<<dim3((unsigned)groups), dim3(64 * NW), 0, st>>>(p);
     return hipGetLastError();
 }
 
@@ -274,16 +278,32 @@ static int pick_shape(const Geometry& g, int64_t Ncol, double density_hint) {
 
 hipError_t launch_spmm(const Geometry& g, double density_hint, int force_shape, const int32_t* row_ptr,
                        const int32_t* col_idx, const uint16_t* vals, const uint32_t* idxw, const uint16_t* X,
-                       int64_t Ncol, int64_t ldx, void* Y, int64_t ldy, int y_dtype, hipStream_t st) {
-    SpmmArgs a;
+                       const crisp_conv_desc* conv, int64_t Ncol, int64_t ldx, void* Y, int64_t ldy, int y_dtype,
+                       hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st) {
+    SpmmArgs a = {};
+    a.ev_start = ev_start; a.ev_stop = ev_stop;
     a.S = g.S; a.K = g.K; a.n = g.n; a.m = g.m; a.w = g.w; a.slots = g.slots; a.wpr = g.wpr;
     a.Sb = g.Sb; a.NT = 0; a.Ncol = Ncol; a.ldx = ldx; a.ldy = ldy;
     a.row_ptr = row_ptr; a.col_idx = col_idx; a.vals = vals; a.idxw = idxw; a.X = X; a.Y = Y;
     a.y_bf16 = (y_dtype == CRISP_Y_BF16);
+    a.act = nullptr;
+    if (conv) {
+        // implicit lowering: X is the activation itself
+        a.act = X;
+        a.X = nullptr;
+        a.C = conv->C; a.H = conv->H; a.W = conv->W; a.kw = conv->kw; a.pad = conv->pad;
+        a.Ho = conv->H + 2 * conv->pad - conv->kh + 1;
+        a.Wo = conv->W + 2 * conv->pad - conv->kw + 1;
+        a.plane = (int64_t)conv->batch * conv->H * conv->W;
+        a.inv_cpb = 1.0f / (float)(conv->C / g.B);
+        a.inv_kw = 1.0f / (float)conv->kw;
+        a.inv_Wo = 1.0 / a.Wo;
+        a.inv_Ho = 1.0 / a.Ho;
+    }
     const int shape = (force_shape >= 0 && force_shape <= 3) ? force_shape : pick_shape(g, Ncol, density_hint);
     // the specialised kernels assume whole 16-row MFMA steps of X (K % 16 == 0) and whole groups
     // of four output columns per lane (Ncol % 4 == 0)
-    if (force_shape != 4 && (g.K % 16) == 0 && (Ncol % 4) == 0 && ldy <= ((int64_t)1 << 23)) {
+    if (conv || (force_shape != 4 && (g.K % 16) == 0 && (Ncol % 4) == 0 && ldy <= ((int64_t)1 << 23))) {
         const int key = g.n * 16 + g.m;
         switch (key) {
             case 1 * 16 + 4: return launch_reg_nm<1, 4>(a, g.B, shape, st);
@@ -296,6 +316,7 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, int force_shape, 
             case 8 * 16 + 8: return launch_reg_nm<8, 8>(a, g.B, shape, st);
             default: break;
         }
+        if (conv) return hipErrorInvalidValue;  // callers check the pattern first
     }
     // any other n:m (or forced): the generic LDS-expansion kernel
     const bool wide = (int64_t)g.Sb * ((Ncol + 511) / 512) >= 512;

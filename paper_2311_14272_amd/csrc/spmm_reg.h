@@ -19,9 +19,9 @@
 #pragma once
 #include <type_traits>
 
-#ifndef CRISP_DEBUG_VARIANT
-#define CRISP_DEBUG_VARIANT 0  // timing experiments only: 1 no X loads, 2 no MFMA, 3 no expansion
-#endif
+
+
+#include <hip/hip_ext.h>
 
 #include "crisp_internal.h"
 
@@ -43,6 +43,32 @@ struct SpmmArgs {
     const uint16_t* X;
     void* Y;
     int y_bf16;
+    // implicit lowering (conv mode): X is not materialised; its rows are read from the activation
+    // [C][batch][H][W].  Stride 1, C % B == 0, Wo even.
+    const uint16_t* act;
+    int C, H, W, kw, pad, Ho, Wo;
+    int64_t plane;            // batch*H*W elements of one channel
+    float inv_cpb, inv_kw;    // reciprocals of C/B (block columns per tap) and kw
+    double inv_Wo, inv_Ho;
+    // host side only: optional events that receive the kernel's own start and stop time stamps
+    hipEvent_t ev_start, ev_stop;
+};
+
+// Lane-dependent part of the X addressing for one block column, and the byte selectors that turn
+// two loaded rows into the two per-column operands.  Explicit X: constant.  Conv mode: depends on
+// the block column's filter tap (shifted window, zero padding at the image border).
+struct XCtx {
+    uint32_t off;
+    uint32_t sel_lo, sel_hi;
+};
+constexpr uint32_t SEL_LO = 0x05040100u;    // r0.lo | r1.lo << 16
+constexpr uint32_t SEL_HI = 0x07060302u;    // r0.hi | r1.hi << 16
+constexpr uint32_t SEL_ZERO = 0x0C0C0C0Cu;  // v_perm_b32: selector byte 0x0c yields 0x00
+
+// Output position (image, oh, ow) of a lane's first column in conv mode, fixed for the wave.
+struct ConvPos {
+    int img, oh, ow;
+    uint32_t half_off;   // hh * 8 channel planes, in bytes
 };
 
 __device__ __forceinline__ uint16_t float_to_bf16_rne(float f) {
@@ -150,34 +176,60 @@ __device__ __forceinline__ u32x4 expand_frag(const uint32_t (&v)[Fmt<N, M, B>::V
 // X rows of block column bj_next are requested into the same registers as soon as their
 // current contents have been turned into MFMA operands, and block t_next's compressed slice
 // after the last step; the body is straight-line code, so the compiler's wait counters stay exact.
-template <int N, int M, int B, int WD, bool PREFETCH>
+template <int N, int M, int B, int WD, bool PREFETCH, bool CONV>
 struct BlockBody {
     typedef Fmt<N, M, B> F;
     typedef typename XVec<WD>::type xvec_t;
     static constexpr int RT = F::RT, KS = F::KS, NACC = 2 * WD;
+
+    // Conv mode: context of block column bj.  All B K-rows of the block column belong to one
+    // filter tap (a, b) because C % B == 0.  The lane's two columns are output positions
+    // (oh, ow), (oh, ow+1) of one image; their sources are act[c][img][oh+a-pad][ow+b-pad (+1)].
+    // Both inside the image: one (possibly 2-byte-aligned) dword load.  Left border (only the
+    // second inside) or right border (only the first): the neighbouring in-row dword is loaded
+    // instead and the selectors pick the valid half and a zero.  Row outside: any valid address,
+    // selectors yield zeros.
+    __device__ static __forceinline__ XCtx conv_ctx(const SpmmArgs& p, const ConvPos& cp, int bj) {
+        const int tap = (int)(((float)bj + 0.5f) * p.inv_cpb);
+        const int a = (int)(((float)tap + 0.5f) * p.inv_kw);
+        const int b = tap - a * p.kw;
+        const int ih = cp.oh + a - p.pad, iw = cp.ow + b - p.pad;
+        const bool vr = (unsigned)ih < (unsigned)p.H;
+        const bool v0 = vr && (unsigned)iw < (unsigned)p.W;
+        const bool v1 = vr && (unsigned)(iw + 1) < (unsigned)p.W;
+        const int centre = (cp.img * p.H + cp.oh) * p.W + cp.ow;
+        const int src = (cp.img * p.H + ih) * p.W + iw;
+        XCtx c;
+        int off = centre;
+        c.sel_lo = SEL_ZERO;
+        c.sel_hi = SEL_ZERO;
+        if (v0 && v1) { off = src; c.sel_lo = SEL_LO; c.sel_hi = SEL_HI; }
+        else if (v1) { off = src + 1; c.sel_hi = SEL_LO; }   // loaded (e0, e1): column 1 <- e0
+        else if (v0) { off = src - 1; c.sel_lo = SEL_HI; }   // loaded (e[W-2], e[W-1]): column 0 <- e[W-1]
+        c.off = cp.half_off + (uint32_t)off * 2u;
+        return c;
+    }
 
     // X rows of block column bj, MFMA step ks.  K is a multiple of 16 here, so a step lies either
     // wholly inside the matrix or wholly past its end; a step past the end re-reads the last 16
     // rows instead (finite values times the zero padding of the packed block).
     __device__ static __forceinline__ void load_x(xvec_t (&dst)[8], const SpmmArgs& p, uint32_t lane_off, int bj,
                                                    int ks) {
-        const int kb = min(bj * B + ks * 16, p.K - 16);
-        const rsrc_t r = make_rsrc(p.X + (int64_t)kb * p.ldx);
-        const uint32_t row_bytes = (uint32_t)p.ldx * 2u;
-#if CRISP_DEBUG_VARIANT == 4
-        // every load of the strip hits the same X row: same instruction stream, all cache hits
-        const rsrc_t r4 = make_rsrc(p.X);
+        if constexpr (CONV) {
+            // K-row = tap*C + c: the 16 rows of the step are 16 consecutive channel planes
+            const int tap = (int)(((float)bj + 0.5f) * p.inv_cpb);
+            const int c0 = bj * B - tap * p.C + ks * 16;
+            const rsrc_t r = make_rsrc(p.act + (int64_t)c0 * p.plane);
+            const uint32_t row_bytes = (uint32_t)p.plane * 2u;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) dst[i] = buf_load_x<WD>(r4, lane_off & 0xFFFu, 0u);
-        (void)r; (void)row_bytes;
-#elif CRISP_DEBUG_VARIANT == 1
-        (void)r; (void)row_bytes;
+            for (int i = 0; i < 8; ++i) dst[i] = buf_load_x<WD>(r, lane_off, (uint32_t)i * row_bytes);
+        } else {
+            const int kb = min(bj * B + ks * 16, p.K - 16);
+            const rsrc_t r = make_rsrc(p.X + (int64_t)kb * p.ldx);
+            const uint32_t row_bytes = (uint32_t)p.ldx * 2u;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) dst[i] = xvec_t{};
-#else
-#pragma unroll
-        for (int i = 0; i < 8; ++i) dst[i] = buf_load_x<WD>(r, lane_off, (uint32_t)i * row_bytes);
-#endif
+            for (int i = 0; i < 8; ++i) dst[i] = buf_load_x<WD>(r, lane_off, (uint32_t)i * row_bytes);
+        }
     }
 
     // Requests the lane's slice of block t: values of rows rt*32 + jj, columns ks*16 + hh*8 .. +8,
@@ -205,24 +257,7 @@ struct BlockBody {
     template <int ks>
     __device__ static __forceinline__ void step(f32x16 (&acc)[RT][NACC], xvec_t (&xr)[KS][8],
                                                 const uint32_t (&av)[RT][KS][F::VW], const uint32_t (&ws)[RT][F::WPR],
-                                                const SpmmArgs& p, uint32_t lane_off, int bj_next) {
-#if CRISP_DEBUG_VARIANT == 5
-        // loads only: fold the loaded words into one accumulator element, no transposes, no MFMA
-        {
-            uint32_t x5 = 0;
-#pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                uint32_t t5[WD];
-                xvec_unpack(xr[ks][r], t5);
-#pragma unroll
-                for (int q = 0; q < WD; ++q) x5 ^= t5[q];
-            }
-            acc[0][0][ks] += __uint_as_float(x5 & 0x3FFFFFFFu);
-            if constexpr (PREFETCH) load_x(xr[ks], p, lane_off, bj_next, ks);
-            (void)av; (void)ws;
-            return;
-        }
-#endif
+                                                const SpmmArgs& p, const XCtx& cur, uint32_t next_off, int bj_next) {
         // 8 rows x 2*WD columns of 16-bit halves -> 2*WD operands of 8 K-values each
         uint32_t xd[8][WD];
 #pragma unroll
@@ -235,41 +270,34 @@ struct BlockBody {
             for (int q = 0; q < 4; ++q) {
                 // v_perm_b32: result bytes picked from {r1 (bytes 4..7), r0 (bytes 0..3)}
                 const uint32_t r0 = xd[2 * q][pd], r1 = xd[2 * q + 1][pd];
-                lo[q] = __builtin_amdgcn_perm(r1, r0, 0x05040100u);  // low halves:  r0.lo | r1.lo << 16
-                hi[q] = __builtin_amdgcn_perm(r1, r0, 0x07060302u);  // high halves: r0.hi | r1.hi << 16
+                lo[q] = __builtin_amdgcn_perm(r1, r0, CONV ? cur.sel_lo : SEL_LO);  // first column of the pair
+                hi[q] = __builtin_amdgcn_perm(r1, r0, CONV ? cur.sel_hi : SEL_HI);  // second column
             }
             bfrag[2 * pd] = __builtin_bit_cast(bf16x8, lo);
             bfrag[2 * pd + 1] = __builtin_bit_cast(bf16x8, hi);
         }
-        if constexpr (PREFETCH) load_x(xr[ks], p, lane_off, bj_next, ks);
+        if constexpr (PREFETCH) load_x(xr[ks], p, next_off, bj_next, ks);
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
-#if CRISP_DEBUG_VARIANT == 3
-            u32x4 a4 = {av[rt][ks][0], ws[rt][0], av[rt][ks][0], ws[rt][0]};
-#else
             const u32x4 a4 = expand_frag<N, M, B, ks>(av[rt][ks], ws[rt]);
-#endif
             const bf16x8 afrag = __builtin_bit_cast(bf16x8, a4);
-#if CRISP_DEBUG_VARIANT == 2
-#pragma unroll
-            for (int c = 0; c < NACC; ++c) {
-                const u32x4 bb = __builtin_bit_cast(u32x4, bfrag[c]);
-                acc[rt][c][0] += __uint_as_float((a4[0] ^ bb[0] ^ bb[1] ^ bb[2] ^ bb[3] ^ a4[1] ^ a4[2] ^ a4[3]) & 0x3FFFFFFFu);
-            }
-#else
 #pragma unroll
             for (int c = 0; c < NACC; ++c)
                 acc[rt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag[c], acc[rt][c], 0, 0, 0);
-#endif
         }
     }
 
+    // cx: context of the block held in this ring slot; replaced by the next block's on prefetch.
     __device__ static __forceinline__ void run(f32x16 (&acc)[RT][NACC], xvec_t (&xr)[KS][8],
-                                               uint32_t (&av)[RT][KS][F::VW], uint32_t (&aw)[RT][F::WPR],
-                                               const SpmmArgs& p, uint32_t lane_off, uint32_t a_off, uint32_t i_off,
+                                               uint32_t (&av)[RT][KS][F::VW], uint32_t (&aw)[RT][F::WPR], XCtx& cx,
+                                               const SpmmArgs& p, const ConvPos& cp, uint32_t a_off, uint32_t i_off,
                                                uint32_t aw_sh, int t_next) {
         int bj_next = 0;
-        if constexpr (PREFETCH) bj_next = p.col_idx[t_next];
+        XCtx nx = cx;
+        if constexpr (PREFETCH) {
+            bj_next = p.col_idx[t_next];
+            if constexpr (CONV) nx = conv_ctx(p, cp, bj_next);
+        }
         // drop the other half-wave's position bits: bit 0 of ws is this lane's first slot
         uint32_t ws[RT][F::WPR];
         if constexpr (N != M) {
@@ -279,26 +307,30 @@ struct BlockBody {
                 for (int i = 0; i < F::WPR; ++i)
                     ws[rt][i] = __builtin_amdgcn_alignbit(i + 1 < F::WPR ? aw[rt][i + 1] : 0u, aw[rt][i], aw_sh);
         }
-        step<0>(acc, xr, av, ws, p, lane_off, bj_next);
-        step<1>(acc, xr, av, ws, p, lane_off, bj_next);
+        step<0>(acc, xr, av, ws, p, cx, nx.off, bj_next);
+        step<1>(acc, xr, av, ws, p, cx, nx.off, bj_next);
         if constexpr (KS == 4) {
-            step<2>(acc, xr, av, ws, p, lane_off, bj_next);
-            step<3>(acc, xr, av, ws, p, lane_off, bj_next);
+            step<2>(acc, xr, av, ws, p, cx, nx.off, bj_next);
+            step<3>(acc, xr, av, ws, p, cx, nx.off, bj_next);
         }
-        if constexpr (PREFETCH) load_a(av, aw, p, a_off, i_off, t_next);
+        if constexpr (PREFETCH) {
+            load_a(av, aw, p, a_off, i_off, t_next);
+            cx = nx;
+        }
     }
 };
 
-template <int N, int M, int B, int WD, int NWK, int PF>
+template <int N, int M, int B, int WD, int NWK, int PF, bool CONV>
 __global__ __launch_bounds__(NWK > 1 ? 64 * NWK : 256) __attribute__((amdgpu_waves_per_eu(2)))
 void spmm_reg_kernel(SpmmArgs p) {
+    static_assert(!CONV || WD == 1, "conv mode pairs two output columns per lane");
     typedef Fmt<N, M, B> F;
     constexpr int RT = F::RT, KS = F::KS;
     constexpr int STRIPS = NWK > 1 ? 1 : 4;       // column strips per workgroup
     constexpr int NACC = 2 * WD;                   // accumulator tiles (consecutive columns) per lane
     typedef typename XVec<WD>::type xvec_t;
-    typedef BlockBody<N, M, B, WD, true> BodyP;
-    typedef BlockBody<N, M, B, WD, false> BodyL;
+    typedef BlockBody<N, M, B, WD, true, CONV> BodyP;
+    typedef BlockBody<N, M, B, WD, false, CONV> BodyL;
 
     // Workgroup -> (block-row, strip group); ids are dealt round-robin to the 8 XCDs, and all
     // block-rows of a strip group get ids on the same XCD so they share its L2 for X.
@@ -316,7 +348,25 @@ void spmm_reg_kernel(SpmmArgs p) {
     const bool col_ok = col0 < p.Ncol;
     // lane part of every X address (bytes): its 8-row half and its columns; lanes past the last
     // column read column 0 instead (in bounds) and never store
-    const uint32_t lane_off = (uint32_t)(((int64_t)hh * 8 * p.ldx + (col_ok ? col0 : 0)) * 2);
+    const int64_t col_ld = col_ok ? col0 : 0;
+    ConvPos cp = {0, 0, 0, 0u};
+    uint32_t lane_off = 0;
+    if constexpr (CONV) {
+        // column -> (image, oh, ow); exact division through fp64 reciprocals (col < 2^31)
+        const int j = (int)col_ld;
+        int t = (int)((double)j * p.inv_Wo);
+        t -= (t * p.Wo > j);
+        t += ((t + 1) * p.Wo <= j);
+        cp.ow = j - t * p.Wo;
+        int im = (int)((double)t * p.inv_Ho);
+        im -= (im * p.Ho > t);
+        im += ((im + 1) * p.Ho <= t);
+        cp.oh = t - im * p.Ho;
+        cp.img = im;
+        cp.half_off = (uint32_t)((int64_t)hh * 8 * p.plane * 2);
+    } else {
+        lane_off = (uint32_t)(((int64_t)hh * 8 * p.ldx + col_ld) * 2);
+    }
     const uint32_t a_off = (uint32_t)((jj * F::SLOTS + hh * F::FS) * 2);
     const uint32_t i_off = (uint32_t)(jj * F::WPR * 4);
     const uint32_t aw_sh = (uint32_t)hh * F::HB;
@@ -336,6 +386,7 @@ void spmm_reg_kernel(SpmmArgs p) {
     xvec_t xr[PF][KS][8];
     uint32_t av[PF][RT][KS][F::VW];
     uint32_t aw[PF][RT][F::WPR];
+    XCtx cx[PF];
 
     // ---- prologue: up to PF blocks in flight -------------------------------------------------
 #pragma unroll
@@ -343,8 +394,10 @@ void spmm_reg_kernel(SpmmArgs p) {
         if (d < cnt) {
             const int t = first + d * NWK;
             const int bj = p.col_idx[t];
+            if constexpr (CONV) cx[d] = BodyL::conv_ctx(p, cp, bj);
+            else cx[d] = XCtx{lane_off, SEL_LO, SEL_HI};
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) BodyL::load_x(xr[d][ks], p, lane_off, bj, ks);
+            for (int ks = 0; ks < KS; ++ks) BodyL::load_x(xr[d][ks], p, cx[d].off, bj, ks);
             BodyL::load_a(av[d], aw[d], p, a_off, i_off, t);
         }
     }
@@ -354,7 +407,7 @@ void spmm_reg_kernel(SpmmArgs p) {
     for (; i0 + 2 * PF <= cnt; i0 += PF) {
 #pragma unroll
         for (int d = 0; d < PF; ++d)
-            BodyP::run(acc, xr[d], av[d], aw[d], p, lane_off, a_off, i_off, aw_sh, first + (i0 + d + PF) * NWK);
+            BodyP::run(acc, xr[d], av[d], aw[d], cx[d], p, cp, a_off, i_off, aw_sh, first + (i0 + d + PF) * NWK);
     }
     // ---- tail: at most 2*PF-1 blocks; the first PF-1 of them may still have a successor -------
 #pragma unroll
@@ -362,10 +415,10 @@ void spmm_reg_kernel(SpmmArgs p) {
         const int i = i0 + e;
         if (i < cnt) {
             if (e < PF - 1 && i + PF < cnt)
-                BodyP::run(acc, xr[e % PF], av[e % PF], aw[e % PF], p, lane_off, a_off, i_off, aw_sh,
+                BodyP::run(acc, xr[e % PF], av[e % PF], aw[e % PF], cx[e % PF], p, cp, a_off, i_off, aw_sh,
                            first + (i + PF) * NWK);
             else
-                BodyL::run(acc, xr[e % PF], av[e % PF], aw[e % PF], p, lane_off, a_off, i_off, aw_sh, 0);
+                BodyL::run(acc, xr[e % PF], av[e % PF], aw[e % PF], cx[e % PF], p, cp, a_off, i_off, aw_sh, 0);
         }
     }
 
@@ -445,7 +498,7 @@ void spmm_reg_kernel(SpmmArgs p) {
     }
 }
 
-template <int N, int M, int B, int WD, int NWK, int PF>
+template <int N, int M, int B, int WD, int NWK, int PF, bool CONV>
 hipError_t launch_reg(const SpmmArgs& a, hipStream_t st) {
     SpmmArgs p = a;
     constexpr int STRIPS = NWK > 1 ? 1 : 4;
@@ -453,19 +506,31 @@ hipError_t launch_reg(const SpmmArgs& a, hipStream_t st) {
     p.NT = (int)((a.Ncol + span - 1) / span);
     const int64_t groups = (int64_t)((p.NT + 7) / 8) * p.Sb * 8;
     if (groups > INT32_MAX) return hipErrorInvalidValue;
-    spmm_reg_kernel<N, M, B, WD, NWK, PF><<<dim3((unsigned)groups), dim3(NWK > 1 ? 64 * NWK : 256), 0, st>>>(p);
+    const dim3 grd((unsigned)groups), blk(NWK > 1 ? 64 * NWK : 256);
+    if (a.ev_start || a.ev_stop)
+        hipExtLaunchKernelGGL((spmm_reg_kernel<N, M, B, WD, NWK, PF, CONV>), grd, blk, 0, st, a.ev_start, a.ev_stop, 0, p);
+    else
+        spmm_reg_kernel<N, M, B, WD, NWK, PF, CONV><<<grd, blk, 0, st>>>(p);
     return hipGetLastError();
 }
 
 // Launch shape: 0 = wide strips, waves own strips; 1 = narrow strips, waves own strips;
-// 2 / 3 = narrow strips, 4 / 8 waves split the block list.
+// 2 / 3 = narrow strips, 4 / 8 waves split the block list.  Conv mode has the narrow shapes only.
 template <int N, int M, int B>
 hipError_t launch_reg_shape(const SpmmArgs& a, int shape, hipStream_t st) {
+    if (a.act != nullptr) {
+        switch (shape) {
+            case 0:
+            case 1: return launch_reg<N, M, B, 1, 1, 1, true>(a, st);
+            case 2: return launch_reg<N, M, B, 1, 4, 1, true>(a, st);
+            default: return launch_reg<N, M, B, 1, 8, 1, true>(a, st);
+        }
+    }
     switch (shape) {
-        case 0: return launch_reg<N, M, B, 2, 1, 1>(a, st);
-        case 1: return launch_reg<N, M, B, 1, 1, 1>(a, st);
-        case 2: return launch_reg<N, M, B, 1, 4, 1>(a, st);
-        default: return launch_reg<N, M, B, 1, 8, 1>(a, st);
+        case 0: return launch_reg<N, M, B, 2, 1, 1, false>(a, st);
+        case 1: return launch_reg<N, M, B, 1, 1, 1, false>(a, st);
+        case 2: return launch_reg<N, M, B, 1, 4, 1, false>(a, st);
+        default: return launch_reg<N, M, B, 1, 8, 1, false>(a, st);
     }
 }
 

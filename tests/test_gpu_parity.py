@@ -112,6 +112,71 @@ def test_bf16_output_is_rounded_fp32_output():
             assert (synth.f32_to_bf16_bits(y16) == synth.f32_to_bf16_bits(y32)).all(), (L.name, shape)
 
 
+CONV_CASES = [
+    # C, H, W, batch, kh, kw, pad, S, n, m, B, density
+    (64, 8, 8, 2, 3, 3, 1, 64, 2, 4, 64, 0.5),
+    (32, 6, 10, 3, 3, 3, 1, 96, 1, 4, 32, 0.5),
+    (64, 6, 6, 2, 5, 5, 2, 64, 2, 8, 64, 0.4),
+    (128, 14, 14, 2, 3, 3, 1, 128, 1, 4, 64, 0.3),
+    (64, 7, 10, 2, 1, 1, 0, 64, 4, 8, 32, 0.5),
+    (64, 9, 10, 1, 3, 3, 0, 32, 3, 4, 32, 0.6),
+    (64, 5, 4, 5, 3, 3, 1, 64, 4, 4, 64, 0.5),
+    (32, 12, 2, 2, 3, 3, 1, 32, 2, 4, 32, 1.0),
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES, ids=lambda c: "C%d_%dx%d_b%d_k%dx%d_p%d_%d:%d_B%d" % (c[0], c[1], c[2], c[3], c[4], c[5], c[6], c[8], c[9], c[10]))
+def test_conv_spmm_implicit_lowering(case):
+    """crisp_conv_spmm (no X in memory) against the oracle's im2col + masked product, and bit for
+    bit against crisp_im2col + crisp_spmm in the same launch shape."""
+    C_, H, Wd, b, kh, kw, pad, S, n, m, B, dens = case
+    print("conv case", case, flush=True)
+    cv = synth.ConvShape(C_, H, Wd, b, kh, kw, 1, pad)
+    L = synth.LayerSpec("conv", S, cv.K, cv.Ncol, n, m, B, dens, synth.SAL_MAG, 0.05, conv=cv)
+    rng = np.random.default_rng(C_ * 7 + H)
+    W = synth.draw_weight(rng, L)
+    act = synth.draw_relu_normal(rng, (C_, b, H, Wd))
+    act[:, :, 0, 0] = synth.f32_to_bf16_bits(np.full((C_, b), 3.0, dtype=np.float32))   # make the borders matter
+    act[:, :, -1, -1] = synth.f32_to_bf16_bits(np.full((C_, b), 5.0, dtype=np.float32))
+    sel, vals, idxw, flags = oracle_all(L, W, None)
+    layer, out = run_select_pack(L, W, None)
+    Xref = oracle.im2col(act, kh, kw, 1, pad)
+    Yref, Aref = oracle.gemm_masked(W, sel.mask, Xref)
+    conv = crisp.ConvDesc(C_, H, Wd, b, kh, kw, 1, pad, crisp.ACT_CBHW, crisp.X_KN)
+    dact = dev(act)
+    Ncol = cv.Ncol
+    ldy = (Ncol + 7) // 8 * 8 + 8
+    ldx = (Ncol + 7) // 8 * 8
+    dX = torch.zeros((L.K, ldx), dtype=torch.int16, device="cuda")
+    crisp.crisp_im2col(conv, dact, dX, ldx)
+    for yd, tdt in ((crisp.Y_F32, torch.float32), (crisp.Y_BF16, torch.bfloat16)):
+        for shape in (None, 1, 2, 3):
+            Y = torch.full((S + 1, ldy), float("nan"), dtype=tdt, device="cuda")
+            crisp.crisp_conv_spmm(layer.desc, conv, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dact, Y,
+                                  ldy, yd, ws=None, ws_bytes=0 if shape is None else shape + 1)
+            torch.cuda.synchronize()
+            Yh = Y.float().cpu().numpy().astype(np.float64)
+            assert np.isnan(Yh[:S, Ncol:]).all() and np.isnan(Yh[S]).all()
+            check_product(Yh[:S, :Ncol], Yref, Aref, yd, "conv %s shape %s" % (case, shape))
+            if shape is not None and Ncol % 4 == 0:
+                Ye = run_spmm(layer, dX, Ncol, ldx, yd, S, ldy=ldy, shape=shape)
+                assert (Ye == Yh[:S, :Ncol]).all(), "implicit and explicit lowering differ"
+
+
+def test_conv_spmm_rejects_what_it_does_not_cover():
+    d = crisp.layer_desc(64, 9 * 64, 2, 4, 64, 0.5)
+    z = torch.zeros(1 << 16, dtype=torch.int16, device="cuda")
+    zi = torch.zeros(1 << 12, dtype=torch.int32, device="cuda")
+    y = torch.zeros(1 << 16, dtype=torch.float32, device="cuda")
+    for cvt, status in (((64, 8, 8, 1, 3, 3, 2, 1), crisp.EUNSUPPORTED),      # stride 2
+                        ((64, 8, 7, 1, 3, 3, 1, 1), crisp.EUNSUPPORTED),      # odd output width
+                        ((32, 8, 8, 1, 3, 3, 1, 1), crisp.ESHAPE)):           # K mismatch
+        conv = crisp.ConvDesc(*cvt, crisp.ACT_CBHW, crisp.X_KN)
+        with pytest.raises(crisp.CrispError) as e:
+            crisp.crisp_conv_spmm(d, conv, zi, zi, z, zi, z, y, 64)
+        assert e.value.status == status
+
+
 def test_ties_and_zero_weights():
     """Constant saliency (every comparison is a tie) and weights with exact zeros / negative zeros."""
     L = synth.LayerSpec("ties", 64, 128, 64, 2, 4, 32, 0.5, synth.SAL_GIVEN, 1.0)
