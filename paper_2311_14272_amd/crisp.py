@@ -217,3 +217,51 @@ def prune_and_pack(layer: DeviceLayer, W, T_or_G=None):
     """crisp_select_mask followed by crisp_pack on the current stream."""
     crisp_select_mask(layer.desc, W, T_or_G, layer.nm_mask, layer.row_ptr, layer.col_idx, layer.score)
     crisp_pack(layer.desc, W, layer.nm_mask, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, layer.flags)
+
+
+def conv_desc_of(cv) -> ConvDesc:
+    """ConvDesc from a synth.ConvShape-like object (C, H, W, batch, kh, kw, stride, pad)."""
+    return ConvDesc(cv.C, cv.H, cv.W, cv.batch, cv.kh, cv.kw, cv.stride, cv.pad, ACT_CBHW, X_KN)
+
+
+def fused_lowering_ok(cv, B: int, n: int, m: int) -> bool:
+    """Whether crisp_conv_spmm covers this convolution (otherwise crisp_im2col + crisp_spmm)."""
+    Wo = cv.W + 2 * cv.pad - cv.kw + 1
+    pattern = (m == 4 and n <= 4) or (m == 8 and n in (1, 2, 4, 8))
+    return (cv.stride == 1 and B in (32, 64) and cv.C % B == 0 and Wo % 2 == 0 and cv.W >= 2 and cv.kw <= 16
+            and cv.kh * cv.kw <= 64 and pattern)
+
+
+def conv_needs_scratch(cv, B: int, n: int, m: int) -> bool:
+    """Whether conv_forward needs an X scratch buffer (K x round_up(Ncol, 8) bf16) for this layer."""
+    Ho = (cv.H + 2 * cv.pad - cv.kh) // cv.stride + 1
+    Wo = (cv.W + 2 * cv.pad - cv.kw) // cv.stride + 1
+    pointwise = cv.kh == 1 and cv.kw == 1 and cv.stride == 1 and cv.pad == 0
+    if pointwise:
+        return (cv.batch * Ho * Wo) % 8 != 0      # act can serve as X only with an aligned row stride
+    return not fused_lowering_ok(cv, B, n, m)
+
+
+def conv_forward(layer: DeviceLayer, cv, act, Y, ldy, y_dtype=Y_F32, X_scratch=None):
+    """Product of a packed layer with a convolution input act [C][batch][H][W] on the current stream.
+    1x1 stride-1 with an aligned row stride: act is X.  Covered geometries: fused lowering.
+    Otherwise crisp_im2col into X_scratch (K x round_up(Ncol, 8), allocated by the caller) followed
+    by crisp_spmm.  Returns the path taken."""
+    d = layer.desc
+    Ho = (cv.H + 2 * cv.pad - cv.kh) // cv.stride + 1
+    Wo = (cv.W + 2 * cv.pad - cv.kw) // cv.stride + 1
+    Ncol = cv.batch * Ho * Wo
+    pointwise = cv.kh == 1 and cv.kw == 1 and cv.stride == 1 and cv.pad == 0
+    if pointwise and Ncol % 8 == 0:
+        crisp_spmm(d, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, act, Ncol, Ncol, Y, ldy, y_dtype)
+        return "none"
+    if not pointwise and fused_lowering_ok(cv, d.B, d.n, d.m):
+        crisp_conv_spmm(d, conv_desc_of(cv), layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, act, Y, ldy,
+                        y_dtype)
+        return "fused"
+    if X_scratch is None:
+        raise ValueError("this convolution needs an X scratch buffer of K x round_up(Ncol, 8) bf16")
+    ldx = (Ncol + 7) // 8 * 8
+    crisp_im2col(conv_desc_of(cv), act, X_scratch, ldx)
+    crisp_spmm(d, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, X_scratch, Ncol, ldx, Y, ldy, y_dtype)
+    return "im2col"

@@ -72,3 +72,22 @@ def check_product(Y, Yref, Aref, y_dtype, what=""):
     if y_dtype == crisp.Y_F32:
         assert fro <= 1e-5, (what, fro)
     return fro
+
+
+def lowering_gather_index(C, H, W, batch, kh, kw, stride, pad, cols):
+    """Flat indices into act[C][batch][H][W] of the X entries of the given output columns
+    (rows ordered (kh, kw, c), c fastest) and a mask of entries that fall into the zero padding.
+    Checked against the oracle's full lowering in a CPU test."""
+    Ho = (H + 2 * pad - kh) // stride + 1
+    Wo = (W + 2 * pad - kw) // stride + 1
+    cols = np.asarray(cols, dtype=np.int64)
+    img, rem = np.divmod(cols, Ho * Wo)
+    oh, ow = np.divmod(rem, Wo)
+    a = np.repeat(np.arange(kh), kw * C)[:, None]
+    b = np.tile(np.repeat(np.arange(kw), C), kh)[:, None]
+    c = np.tile(np.arange(C), kh * kw)[:, None]
+    ih = oh[None, :] * stride + a - pad
+    iw = ow[None, :] * stride + b - pad
+    inside = (ih >= 0) & (ih < H) & (iw >= 0) & (iw < W)
+    idx = ((c * batch + img[None, :]) * H + np.clip(ih, 0, H - 1)) * W + np.clip(iw, 0, W - 1)
+    return idx, inside

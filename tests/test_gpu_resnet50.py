@@ -1,0 +1,74 @@
+"""Config 5: all 53 ResNet-50 convolutions as hybrid-sparse GEMMs with on-device select+pack.
+Layer-wise mode: every layer gets a fresh ReLU(N(0,1)) input of its true shape (drawn on the
+device), and the oracle is fed exactly that input (teacher forcing), so errors do not compound.
+Batch 2: every output column is checked.  Batch 256: masks and packing in full, the product on
+sampled columns (each output column is an independent sum over K)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2311_14272_amd import crisp, synth
+
+from gpu_util import check_product, desc_of, dev, host, lowering_gather_index, run_select_pack
+
+pytestmark = pytest.mark.gpu
+
+
+def _device_activation(shape, gen):
+    a = torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32).clamp_(min=0).to(torch.bfloat16)
+    return a.view(torch.int16)
+
+
+def _run_layers(batch, sample_cols):
+    wl = synth.config(5, batch=batch)
+    assert len(wl.layers) == 53
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(wl.seed)
+    paths = {"none": 0, "fused": 0, "im2col": 0}
+    for li, L in enumerate(wl.layers):
+        cv = L.conv
+        t = synth.draw_layer(wl, li, with_x=False)
+        W, G = t["W"], t["G"]
+        sel = oracle.select(W, G, L.n, L.m, L.B, L.density, L.sal_kind, L.select_mode)
+        vals, idxw, flags = oracle.pack(W, sel.keep, L.n, L.m, L.B, sel.row_ptr, sel.col_idx)
+        layer, out = run_select_pack(L, W, G)
+        assert (out["nm_bits"] == sel.nm_bits).all() and (out["col_idx"] == sel.col_idx).all(), L.name
+        assert (out["score"].view(np.uint64) == sel.score.view(np.uint64)).all(), L.name
+        assert (out["vals"] == vals).all() and (out["idxw"] == idxw).all() and out["flags"][0] == flags[0], L.name
+        dact = _device_activation((cv.C, cv.batch, cv.H, cv.W), gen)
+        Ncol = L.Ncol
+        ld = (Ncol + 7) // 8 * 8
+        Y = torch.empty((L.S, ld), dtype=torch.float32, device="cuda")
+        need_x = crisp.conv_needs_scratch(cv, L.B, L.n, L.m)
+        Xs = torch.zeros((L.K, ld), dtype=torch.int16, device="cuda") if need_x else None
+        path = crisp.conv_forward(layer, cv, dact, Y, ld, crisp.Y_F32, Xs)
+        torch.cuda.synchronize()
+        paths[path] += 1
+        rng = np.random.default_rng(1000 + li)
+        if sample_cols is None or Ncol <= sample_cols:
+            cols = np.arange(Ncol)
+        else:
+            cols = np.unique(np.concatenate([np.arange(64), np.arange(Ncol - 64, Ncol),
+                                             rng.integers(0, Ncol, sample_cols)]))
+        idx, inside = lowering_gather_index(cv.C, cv.H, cv.W, cv.batch, cv.kh, cv.kw, cv.stride, cv.pad, cols)
+        g = torch.take(dact.view(-1), torch.from_numpy(idx).cuda()).cpu().numpy().view(np.uint16)
+        Xs_host = np.ascontiguousarray(np.where(inside, g, np.uint16(0)))
+        Yref, Aref = oracle.gemm_masked(W, sel.mask, Xs_host)
+        Yg = Y[:, torch.from_numpy(cols).cuda()].cpu().numpy().astype(np.float64)
+        check_product(Yg, Yref, Aref, crisp.Y_F32, "%s (%s)" % (L.name, path))
+        del dact, Y, Xs, layer
+        torch.cuda.empty_cache()
+        print("layer %2d %-8s %4dx%4dx%7d %d:%d d=%.2f path=%s ok" % (li, L.name, L.S, L.K, Ncol, L.n, L.m, L.density, path),
+              flush=True)
+    return paths
+
+
+def test_resnet50_batch2_all_columns():
+    paths = _run_layers(2, None)
+    assert paths["fused"] >= 10 and sum(paths.values()) == 53
+
+
+def test_resnet50_batch256_sampled_columns():
+    paths = _run_layers(256, 384)
+    assert sum(paths.values()) == 53
