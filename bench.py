@@ -33,7 +33,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, help="workload 1..4 (default 2: ResNet-50 stage-3 bottleneck)")
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2: ResNet-50 stage-3 bottleneck; 5: all 53 ResNet-50 convs, layer-wise)")
     ap.add_argument("--sets", type=int, default=0, help="independent input sets to rotate through (0 = enough for 600 MB)")
     ap.add_argument("--y-dtype", choices=["bf16", "f32"], default="bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -52,6 +52,84 @@ class LayerState:
     pass
 
 
+def resnet50_pass(args):
+    """Config 5, layer-wise: for each of the 53 convolutions select+pack on the device, then the
+    product on a fresh ReLU(N(0,1)) input of the layer's true shape (batch 256, 224x224).  One
+    layer is resident at a time; a "step" is the sum over the layers."""
+    import torch
+    from paper_2311_14272_amd import crisp, synth
+    dev = "cuda"
+    wl = synth.config(5)
+    y_dtype = crisp.Y_BF16 if args.y_dtype == "bf16" else crisp.Y_F32
+    ybytes = 2 if y_dtype == crisp.Y_BF16 else 4
+    ytorch = torch.bfloat16 if y_dtype == crisp.Y_BF16 else torch.float32
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(wl.seed)
+    reps = max(1, min(args.steps, 5))
+    rows, t_prune, t_fwd, useful, dense = [], 0.0, 0.0, 0.0, 0.0
+    for li, L in enumerate(wl.layers):
+        cv = L.conv
+        t = synth.draw_layer(wl, li, with_x=False)
+        W = torch.from_numpy(t["W"].view(np.int16)).to(dev)
+        G = torch.from_numpy(t["G"]).to(dev)
+        desc = crisp.layer_desc(L.S, L.K, L.n, L.m, L.B, L.density, L.sal_kind, L.select_mode)
+        dl = crisp.alloc_layer(desc, dev)
+        nbuf = 2
+        acts = [torch.randn((cv.C, cv.batch, cv.H, cv.W), generator=gen, device=dev).clamp_(min=0).to(torch.bfloat16).view(torch.int16)
+                for _ in range(nbuf)]
+        Ys = [torch.empty((L.S, L.Ncol), dtype=ytorch, device=dev) for _ in range(nbuf)]
+        Xs = torch.empty((L.K, L.Ncol), dtype=torch.int16, device=dev) if crisp.conv_needs_scratch(cv, L.B, L.n, L.m) else None
+
+        def timed(fn):
+            fn(0)
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for r in range(reps):
+                fn(r)
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / reps
+        tp = timed(lambda r: crisp.prune_and_pack(dl, W, G))
+        path = [None]
+
+        def fwd(r):
+            path[0] = crisp.conv_forward(dl, cv, acts[r % nbuf], Ys[r % nbuf], L.Ncol, y_dtype, Xs)
+        tf = timed(fwd)
+        sz = dl.sizes
+        ones = sz.nk * L.B * sz.slots_per_row if (L.S % L.B == 0 and L.K % L.B == 0) else None
+        if ones is None:   # ragged layer (conv1): count from the device mask
+            bits = dl.nm_mask.cpu().numpy().view(np.uint32)[: sz.mask_words].reshape(L.S, sz.mask_words_per_row)
+            keep = np.unpackbits(bits.view(np.uint8), axis=1, bitorder="little")[:, : L.K]
+            rp, ci = dl.row_ptr.cpu().numpy(), dl.col_idx.cpu().numpy()
+            ones = sum(int(keep[bi * L.B:(bi + 1) * L.B, bj * L.B:(bj + 1) * L.B].sum())
+                       for bi in range(sz.Sb) for bj in ci[rp[bi]:rp[bi + 1]])
+        uf = 2.0 * ones * L.Ncol
+        rows.append(dict(name=L.name, S=L.S, K=L.K, Ncol=L.Ncol, nm="%d:%d" % (L.n, L.m), density=round(L.density, 3),
+                         k_row=sz.k_row, lowering=path[0], prune_pack_ms=round(tp, 4), forward_ms=round(tf, 4),
+                         useful_tflops_forward=round(uf / (tf * 1e-3) / 1e12, 2)))
+        t_prune += tp
+        t_fwd += tf
+        useful += uf
+        dense += 2.0 * L.S * L.K * L.Ncol
+        del acts, Ys, Xs, dl, W, G
+        torch.cuda.empty_cache()
+    total = t_prune + t_fwd
+    out = {"metric": "effective TFLOP/s (nonzero FLOPs) of hybrid-sparse GEMM + % roofline",
+           "value": round(useful / (total * 1e-3) / 1e12, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": reps, "warmup": 1,
+           "ms_per_step": round(total, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": "c5: ResNet-50, 53 convs as GEMMs, batch 256, 224x224, layer-wise inputs, B=64, "
+                                  "per-layer n:m and block density drawn from the workload seed",
+                      "step": "per layer: select_mask+pack on device, lowering (fused, im2col or none), product; summed",
+                      "y_dtype": args.y_dtype},
+           "select_pack_ms": round(t_prune, 3), "forward_ms": round(t_fwd, 3),
+           "useful_tflops_forward_only": round(useful / (t_fwd * 1e-3) / 1e12, 2),
+           "dense_equivalent_tflops_forward_only": round(dense / (t_fwd * 1e-3) / 1e12, 1),
+           "roofline": None, "layers": rows}
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -64,6 +142,9 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(2)
     crisp.lib()
+    if args.config == 5:
+        resnet50_pass(args)
+        return
     dev = "cuda"
     wl = synth.config(args.config)
     y_dtype = crisp.Y_BF16 if args.y_dtype == "bf16" else crisp.Y_F32

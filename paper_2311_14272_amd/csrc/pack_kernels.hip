@@ -126,7 +126,8 @@ __global__ __launch_bounds__(256) void pack_block_kernel(int S, int K, int n, in
                 if (q < n) out[q] = v[q];
         }
     }
-    if (flag_mode == 0 && violates) atomicAnd(flags, 0);
+    // one atomic per wave at most, and none once the flag is already cleared
+    if (flag_mode == 0 && __any(violates) && (threadIdx.x & 63) == 0 && flags[0] != 0) atomicAnd(flags, 0);
 
     // ---- phase 2 -----------------------------------------------------------------------------
     uint64_t rb2[WITEMS];
