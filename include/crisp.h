@@ -198,6 +198,27 @@ CRISP_API crisp_status crisp_conv_spmm(const crisp_layer_desc *desc, const crisp
                                        int32_t y_dtype, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Global block budget across layers (Alg. 1 lines 6-9; Sec. 3.3): turns one overall target
+ * sparsity into kept blocks per block-row for every layer.
+ *   Per layer, each block-row's scores (output block_score of crisp_select_mask) are ordered
+ *   ascending (score ascending, on a tie the larger column first: the reverse of the keep order),
+ *   scores of equal rank position are added over the block-rows (rows ascending, fp64), all rank
+ *   columns of all layers are ordered ascending (ties: layer, then rank) and pruned in that order
+ *   until 1 - kept/total >= target_sparsity, where total = sum S*K and a block counts its in-range
+ *   elements times n/m.  A layer never loses its last rank column (no layer collapse).
+ *   descs, block_scores: HOST arrays of n_layers entries; block_scores[l] is a DEVICE pointer to
+ *   Sb x Kb fp64.  desc fields used: S, K, n, m, B.
+ *   k_row: DEVICE, n_layers int32 (kept blocks per block-row; a density k_row/Kb reproduces it in
+ *   crisp_select_mask).  achieved: DEVICE, 1 double, optional.  ws: DEVICE, sum Sb*Kb doubles.
+ * Limits: n_layers <= 64, sum of Kb <= 4096 (EUNSUPPORTED beyond).
+ * Errors: EINVAL, EALIGN, EBUFSIZE, EUNSUPPORTED, EDEVICE.
+ */
+CRISP_API crisp_status crisp_global_budget(int32_t n_layers, const crisp_layer_desc *descs,
+                                           const double *const *block_scores, double target_sparsity,
+                                           int32_t *k_row, double *achieved, void *ws, size_t ws_bytes,
+                                           void *stream);
+
+/*
  * The same product as crisp_spmm (conv == NULL, X_or_act = X) or crisp_conv_spmm (conv != NULL,
  * X_or_act = act; Ncol and ldx ignored), with two optional hipEvent_t (created by the caller with
  * timing enabled, passed as void*) that receive the time stamps of the product kernel's own start

@@ -185,3 +185,18 @@ def select(W: np.ndarray, G_or_T: Optional[np.ndarray], n: int, m: int, B: int, 
 
 def num_threads() -> int:
     return int(lib().oracle_num_threads())
+
+
+def global_budget(layers, scores, target: float):
+    """layers: list of (S, K, n, m, B); scores: list of fp64 Sb x Kb arrays.  Returns (k_row list, achieved sparsity)."""
+    L = len(layers)
+    arr = lambda i: (C.c_int * L)(*[int(x[i]) for x in layers])
+    sc = [np.ascontiguousarray(s, dtype=np.float64) for s in scores]
+    ptrs = (C.c_void_p * L)(*[s.ctypes.data for s in sc])
+    k_row = (C.c_int * L)()
+    ach = (C.c_double * 1)()
+    f = lib().oracle_global_budget
+    f.argtypes = [C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_double, C.c_void_p,
+                  C.c_void_p]
+    _chk(f(L, arr(0), arr(1), arr(2), arr(3), arr(4), ptrs, float(target), k_row, ach), "oracle_global_budget")
+    return list(k_row), float(ach[0])

@@ -447,3 +447,79 @@ int oracle_num_threads(void) { return omp_get_max_threads(); }
 #else
 int oracle_num_threads(void) { return 1; }
 #endif
+
+/* ------------------------------------------------------------------------
+ * Global block budget across layers (Alg. 1 lines 6-9; Sec. 3.3).
+ * For every layer: each block-row's scores are ordered ascending (the block
+ * that uniform pruning would drop first comes first; this is the exact reverse
+ * of the keep order of oracle_block_select: score ascending, on a tie the
+ * larger column first), and the scores at the same rank position o are added
+ * over the block-rows, rows ascending, in fp64: c_l[o].  All c_l[o] of all
+ * layers are then ordered ascending (ties: layer ascending, rank ascending)
+ * and rank columns are pruned in that order until the overall sparsity
+ * 1 - kept/total reaches `target`; one rank column of layer l removes that
+ * rank's block from every block-row of layer l, so rows stay uniform.  Within
+ * a layer c_l[o] is non-decreasing in o, hence a layer always loses a prefix of
+ * its ranks.  The last rank column of a layer is never pruned (no layer
+ * collapse, Sec. 3.3).  Weight counts: total = sum S*K; a block contributes
+ * its in-range elements times n/m (exact for full groups; the count is only
+ * used to decide when to stop).
+ * Inputs per layer l: S, K, n, m, B and score (Sb x Kb, fp64).
+ * Output: k_row[l] = kept blocks per block-row; achieved[0] = reached sparsity.
+ * ---------------------------------------------------------------------- */
+int oracle_global_budget(int L, const int *S, const int *K, const int *n, const int *m, const int *B,
+                         const double *const *score, double target, int *k_row, double *achieved)
+{
+    if (L < 1 || !S || !K || !n || !m || !B || !score || !k_row || !(target >= 0.0) || target > 1.0) return -1;
+    long ncols = 0;
+    double total = 0.0, kept = 0.0;
+    for (int l = 0; l < L; ++l) {
+        int Kb = ceil_div(K[l], B[l]);
+        ncols += Kb;
+        total += (double)S[l] * (double)K[l];
+        kept += (double)S[l] * (double)K[l] * (double)n[l] / (double)m[l];
+        k_row[l] = Kb;
+    }
+    double *c = (double *)malloc((size_t)ncols * sizeof(double));
+    double *w = (double *)malloc((size_t)ncols * sizeof(double)); /* kept weights a rank column holds */
+    int *lay = (int *)malloc((size_t)ncols * sizeof(int));
+    int *rk = (int *)malloc((size_t)ncols * sizeof(int));
+    if (!c || !w || !lay || !rk) return -2;
+    long pos = 0;
+    for (int l = 0; l < L; ++l) {
+        int Sb = ceil_div(S[l], B[l]), Kb = ceil_div(K[l], B[l]);
+        for (int o = 0; o < Kb; ++o) { c[pos + o] = 0.0; w[pos + o] = 0.0; lay[pos + o] = l; rk[pos + o] = o; }
+        for (int bi = 0; bi < Sb; ++bi) {
+            const double *sc = score[l] + (long)bi * Kb;
+            int rows = (S[l] - bi * B[l] < B[l]) ? S[l] - bi * B[l] : B[l];
+            for (int j = 0; j < Kb; ++j) {
+                /* ascending position of block j in its row: how many come before it */
+                int before = 0;
+                for (int o = 0; o < Kb; ++o)
+                    if (sc[o] < sc[j] || (sc[o] == sc[j] && o > j)) ++before;
+                int cols = (K[l] - j * B[l] < B[l]) ? K[l] - j * B[l] : B[l];
+                c[pos + before] += sc[j]; /* rows ascending: bi is the outer loop */
+                w[pos + before] += (double)rows * (double)cols * (double)n[l] / (double)m[l];
+            }
+        }
+        pos += Kb;
+    }
+    /* repeatedly take the smallest remaining column under (c, layer, rank) */
+    uint8_t *gone = (uint8_t *)calloc((size_t)ncols, 1);
+    if (!gone) return -2;
+    while (1.0 - kept / total < target) {
+        long best = -1;
+        for (long a = 0; a < ncols; ++a) {
+            if (gone[a]) continue;
+            if (k_row[lay[a]] <= 1) continue; /* keep the last rank column of every layer */
+            if (best < 0 || c[a] < c[best]) best = a; /* ascending scan keeps (layer, rank) order on ties */
+        }
+        if (best < 0) break;
+        gone[best] = 1;
+        kept -= w[best];
+        k_row[lay[best]] -= 1;
+    }
+    if (achieved) achieved[0] = 1.0 - kept / total;
+    free(c); free(w); free(lay); free(rk); free(gone);
+    return 0;
+}

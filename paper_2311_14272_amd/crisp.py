@@ -72,8 +72,9 @@ def lib():
                                       C.c_int32, vp, C.c_size_t, vp]
         L.crisp_spmm_timed.argtypes = [C.POINTER(LayerDesc), C.POINTER(ConvDesc), vp, vp, vp, vp, vp, C.c_int64,
                                        C.c_int64, vp, C.c_int64, C.c_int32, vp, vp, vp]
+        L.crisp_global_budget.argtypes = [C.c_int32, vp, vp, C.c_double, vp, vp, vp, C.c_size_t, vp]
         for f in (L.crisp_pack_sizes, L.crisp_select_mask, L.crisp_pack, L.crisp_im2col, L.crisp_spmm,
-                  L.crisp_conv_spmm, L.crisp_spmm_timed):
+                  L.crisp_conv_spmm, L.crisp_spmm_timed, L.crisp_global_budget):
             f.restype = C.c_int32
         _lib = L
     return _lib
@@ -154,6 +155,17 @@ def crisp_spmm_timed(desc, conv, row_ptr, col_idx, vals, idx_words, X_or_act, Nc
                                 y_dtype, start_event, stop_event, _stream() if stream == -1 else stream)
     if st != OK:
         raise CrispError("crisp_spmm_timed", st)
+
+
+def crisp_global_budget(descs, score_tensors, target_sparsity, k_row, achieved=None, ws=None, ws_bytes=0, stream=-1):
+    """descs: list of LayerDesc; score_tensors: list of device tensors (Sb x Kb fp64)."""
+    n = len(descs)
+    darr = (LayerDesc * n)(*descs)
+    parr = (C.c_void_p * n)(*[_ptr(t) for t in score_tensors])
+    st = lib().crisp_global_budget(n, darr, parr, float(target_sparsity), _ptr(k_row), _ptr(achieved), _ptr(ws),
+                                   ws_bytes, _stream() if stream == -1 else stream)
+    if st != OK:
+        raise CrispError("crisp_global_budget", st)
 
 
 class HipEvents:

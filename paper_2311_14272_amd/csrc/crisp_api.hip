@@ -218,6 +218,35 @@ crisp_status crisp_conv_spmm(const crisp_layer_desc* desc, const crisp_conv_desc
                           nullptr, nullptr);
 }
 
+crisp_status crisp_global_budget(int32_t n_layers, const crisp_layer_desc* descs, const double* const* block_scores,
+                                 double target_sparsity, int32_t* k_row, double* achieved, void* ws, size_t ws_bytes,
+                                 void* stream) {
+    if (!descs || !block_scores || !k_row) return CRISP_EINVAL;
+    if (n_layers < 1 || !(target_sparsity >= 0.0) || target_sparsity > 1.0) return CRISP_EINVAL;
+    if (n_layers > CRISP_BUDGET_MAX_LAYERS) return CRISP_EUNSUPPORTED;
+    BudgetArgs a;
+    a.L = n_layers;
+    a.target = target_sparsity;
+    int64_t cols = 0;
+    size_t need = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        Geometry g;
+        crisp_status st = make_geometry(&descs[l], false, &g);
+        if (st != CRISP_OK) return st;
+        if (!block_scores[l]) return CRISP_EINVAL;
+        if (misaligned(block_scores[l], 8)) return CRISP_EALIGN;
+        a.score[l] = block_scores[l];
+        a.S[l] = g.S; a.K[l] = g.K; a.n[l] = g.n; a.m[l] = g.m; a.B[l] = g.B; a.Sb[l] = g.Sb; a.Kb[l] = g.Kb;
+        cols += g.Kb;
+        need += (size_t)g.Sb * g.Kb * sizeof(double);
+    }
+    if (cols > CRISP_BUDGET_MAX_COLS) return CRISP_EUNSUPPORTED;
+    if (!ws || ws_bytes < need) return CRISP_EBUFSIZE;
+    if (misaligned(ws, 16) || misaligned(k_row, 4) || misaligned(achieved, 8)) return CRISP_EALIGN;
+    hipError_t e = launch_global_budget(a, (double*)ws, k_row, achieved, (hipStream_t)stream);
+    return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
+}
+
 crisp_status crisp_spmm_timed(const crisp_layer_desc* desc, const crisp_conv_desc* conv, const int32_t* row_ptr,
                               const int32_t* col_idx, const uint16_t* vals, const uint32_t* idx_words,
                               const uint16_t* X_or_act, int64_t Ncol, int64_t ldx, void* Y, int64_t ldy,

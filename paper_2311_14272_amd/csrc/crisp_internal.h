@@ -34,6 +34,17 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, int force_shape, 
                        const crisp_conv_desc* conv, int64_t Ncol, int64_t ldx, void* Y, int64_t ldy, int y_dtype,
                        hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st);
 
+#define CRISP_BUDGET_MAX_LAYERS 64
+#define CRISP_BUDGET_MAX_COLS 4096
+struct BudgetArgs {
+    int L;
+    double target;
+    const double* score[CRISP_BUDGET_MAX_LAYERS];
+    int S[CRISP_BUDGET_MAX_LAYERS], K[CRISP_BUDGET_MAX_LAYERS], n[CRISP_BUDGET_MAX_LAYERS], m[CRISP_BUDGET_MAX_LAYERS],
+        B[CRISP_BUDGET_MAX_LAYERS], Sb[CRISP_BUDGET_MAX_LAYERS], Kb[CRISP_BUDGET_MAX_LAYERS];
+};
+hipError_t launch_global_budget(const BudgetArgs& a, double* ws, int32_t* k_row, double* achieved, hipStream_t st);
+
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
 }  // namespace crisp

@@ -177,6 +177,41 @@ def test_conv_spmm_rejects_what_it_does_not_cover():
         assert e.value.status == status
 
 
+def test_global_budget_matches_oracle():
+    """crisp_global_budget on device block scores: kept blocks per row and reached sparsity equal
+    the oracle's, bit for bit, for several targets; feeding k_row/Kb back as the density reproduces
+    the oracle's block lists."""
+    cases = synth.small_cases()[:6] + synth.b16_cases()[:2]
+    descs, score_t, score_h, layers, Ws = [], [], [], [], []
+    for i, L in enumerate(cases):
+        W, G, _ = synth.draw_small(L, 40 + i)
+        L1 = synth.LayerSpec(L.name, L.S, L.K, L.Ncol, L.n, L.m, L.B, 1.0, L.sal_kind, L.w_sigma)
+        layer, out = run_select_pack(L1, W, G)
+        sel = oracle.select(W, G, L.n, L.m, L.B, 1.0, L.sal_kind)
+        assert (out["score"].view(np.uint64) == sel.score.view(np.uint64)).all()
+        descs.append(layer.desc)
+        score_t.append(layer.score)
+        score_h.append(sel.score)
+        layers.append((L.S, L.K, L.n, L.m, L.B))
+        Ws.append((L, W, G))
+    ws = torch.empty(sum(s.size for s in score_h), dtype=torch.float64, device="cuda")
+    k_dev = torch.zeros(len(cases), dtype=torch.int32, device="cuda")
+    ach = torch.zeros(1, dtype=torch.float64, device="cuda")
+    for target in (0.0, 0.55, 0.7, 0.8, 0.9, 0.97):
+        crisp.crisp_global_budget(descs, score_t, target, k_dev, ach, ws, ws.numel() * 8)
+        torch.cuda.synchronize()
+        k_ref, a_ref = oracle.global_budget(layers, score_h, target)
+        assert k_dev.cpu().tolist() == k_ref, target
+        assert ach.cpu().numpy().view(np.uint64)[0] == np.array([a_ref]).view(np.uint64)[0], target
+    # close the loop for the last target: density = k_row / Kb gives the same block lists
+    for (L, W, G), kr in zip(Ws, k_ref):
+        Kb = -(-L.K // L.B)
+        L2 = synth.LayerSpec(L.name, L.S, L.K, L.Ncol, L.n, L.m, L.B, kr / Kb, L.sal_kind, L.w_sigma)
+        _, out = run_select_pack(L2, W, G)
+        sel = oracle.select(W, G, L.n, L.m, L.B, kr / Kb, L.sal_kind)
+        assert sel.k_row == kr and (out["col_idx"] == sel.col_idx).all()
+
+
 def test_ties_and_zero_weights():
     """Constant saliency (every comparison is a tie) and weights with exact zeros / negative zeros."""
     L = synth.LayerSpec("ties", 64, 128, 64, 2, 4, 32, 0.5, synth.SAL_GIVEN, 1.0)
