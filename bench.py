@@ -284,7 +284,13 @@ def main():
             k_used = int(sum(min(L.K, (bj + 1) * L.B) - bj * L.B for bj in used_cols))
             x_bytes = 2 * k_used * L.Ncol
         alg_bytes = x_bytes + ybytes * L.S * L.Ncol + w_bytes
-        info.append(dict(name=L.name, S=L.S, K=L.K, Ncol=L.Ncol, nm="%d:%d" % (L.n, L.m), B=L.B, k_row=sz.k_row,
+        # metadata of the packed form next to the closed forms of Sec. 3.1 (K' = k_row*B kept columns per row)
+        Kp = sz.k_row * L.B
+        meta = dict(paper_block_bits=L.S * Kp * int(np.floor(np.log2(max(Kp / L.B, 1)))) // (L.B * L.B),
+                    paper_nm_bits=L.S * Kp * L.n * sz.idx_bits // L.m,
+                    stored_block_bytes=int(sz.nk * 4 + (sz.Sb + 1) * 4), stored_nm_bytes=int(sz.idx_words * 4),
+                    packed_value_bytes=int(kept_vals * 2), dense_bytes=int(L.S * L.K * 2))
+        info.append(dict(name=L.name, S=L.S, K=L.K, Ncol=L.Ncol, metadata=meta, nm="%d:%d" % (L.n, L.m), B=L.B, k_row=sz.k_row,
                          ones=ones, useful_flop=2.0 * ones * L.Ncol, dense_flop=2.0 * L.S * L.K * L.Ncol,
                          alg_bytes=alg_bytes, smfmac_ok=int(st.dl.flags.cpu()[0]),
                          lowering=("fused" if st.fused else ("im2col" if st.is_conv else "none"))))

@@ -175,7 +175,7 @@ CRISP_API crisp_status crisp_im2col(const crisp_conv_desc *conv, const uint16_t 
  *   Y: S x ldy, fp32 or bf16 per y_dtype (device), ldy >= Ncol, ldy % 8 == 0.
  *      Every element Y[0..S)[0..Ncol) is written (rows of empty block-rows get 0).
  *   desc->block_density and sal_kind are not used here.
- * Errors: EINVAL, ESHAPE, EALIGN, EUNSUPPORTED (B = 16, x_layout), EDEVICE.
+ * Errors: EINVAL, ESHAPE, EALIGN, EUNSUPPORTED (x_layout), EDEVICE.
  */
 CRISP_API crisp_status crisp_spmm(const crisp_layer_desc *desc, const int32_t *row_ptr, const int32_t *col_idx,
                         const uint16_t *vals, const uint32_t *idx_words, const uint16_t *X,

@@ -160,7 +160,6 @@ static crisp_status spmm_impl(const crisp_layer_desc* desc, const int32_t* row_p
         misaligned(X, 16) || misaligned(Y, 16))
         return CRISP_EALIGN;
     if (x_layout != CRISP_X_KN) return CRISP_EUNSUPPORTED;
-    if (g.B == 16) return CRISP_EUNSUPPORTED;
     // ws_bytes doubles as a tuning knob when ws is NULL: 0 = automatic launch shape, 1..5 force
     // shape (value - 1); results do not depend on it.
     const int force_shape = (!ws && ws_bytes >= 1 && ws_bytes <= 5) ? (int)ws_bytes - 1 : -1;

@@ -250,6 +250,100 @@ static hipError_t launch_one(const SpmmArgs& a, hipStream_t st) {
     return hipGetLastError();
 }
 
+// 16 x 16 blocks (the paper's smallest block size).  One wave per (block-row, strip of 64 output
+// columns); lane (j = lane % 16, q = lane / 16).  v_mfma_f32_16x16x16_bf16: A operand = row j of the
+// block, columns 4q..4q+3; B operand = one X column, K-rows 4q..4q+3; result = column j, rows
+// 4q..4q+3.  The lane loads 4 consecutive X columns (8 bytes) of each of its 4 K-rows and
+// transposes 16-bit halves as in the larger kernels, so its 4 accumulators are 4 consecutive
+// output columns.  Any n:m, any K and Ncol (rows past K and columns past Ncol are predicated).
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+__global__ __launch_bounds__(256) void spmm_b16_kernel(SpmmArgs p) {
+    const int id = blockIdx.x;
+    const int xcd = id & 7, slot = id >> 3;
+    const int bi = slot % p.Sb;
+    const int nt = (slot / p.Sb) * 8 + xcd;
+    if (nt >= p.NT) return;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int j = lane & 15, q = lane >> 4;
+    const int64_t wave_col = ((int64_t)nt * 4 + wave) * 64;
+    if (wave_col >= p.Ncol) return;
+    const int64_t col0 = wave_col + j * 4;
+    const bool col_ok = col0 < p.Ncol;          // chunk starts inside; ldx % 8 == 0 keeps the 8-byte load in the row
+    const uint16_t* xcol = p.X + (col_ok ? col0 : 0);
+    const int t_begin = p.row_ptr[bi], t_end = p.row_ptr[bi + 1];
+    f32x4 acc[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int t = t_begin; t < t_end; ++t) {
+        const int bj = p.col_idx[t];
+        // X: rows bj*16 + 4q + i; rows at or past K read as zero
+        uint2 xr[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int k = bj * 16 + 4 * q + i;
+            const int kc = min(k, p.K - 1);
+            const uint2 v = *reinterpret_cast<const uint2*>(xcol + (int64_t)kc * p.ldx);
+            xr[i] = (k < p.K) ? v : make_uint2(0u, 0u);
+        }
+        // A: row j of block t, columns 4q..4q+3, expanded from the packed slots
+        const size_t brow = (size_t)t * 16 + j;
+        const uint16_t* vrow = p.vals + brow * p.slots;
+        const uint32_t* irow = p.idxw + brow * p.wpr;
+        uint64_t stream = irow[0];
+        if (p.wpr > 1) stream |= (uint64_t)irow[1] << 32;
+        const int g = (p.m == 4) ? q : (q >> 1);        // group of this lane's 4 columns
+        const uint32_t half_sel = (uint32_t)(q & 1);     // m == 8: which half of the group
+        uint32_t a0 = 0u, a1 = 0u;
+        for (int s = 0; s < p.n; ++s) {
+            const int sl = g * p.n + s;
+            const uint32_t pos = (uint32_t)(stream >> (sl * p.w)) & (uint32_t)(p.m - 1);
+            const bool mine = (p.m == 4) || ((pos >> 2) == half_sel);
+            const uint32_t pl = pos & 3u;
+            const uint32_t v = mine ? ((uint32_t)vrow[sl] << ((pl & 1u) * 16u)) : 0u;
+            a0 |= (pl < 2u) ? v : 0u;
+            a1 |= (pl < 2u) ? 0u : v;
+        }
+        const uint2 av = make_uint2(a0, a1);
+        const s16x4 afrag = __builtin_bit_cast(s16x4, av);
+#pragma unroll
+        for (int pd = 0; pd < 2; ++pd) {
+            const uint32_t r0 = pd ? xr[0].y : xr[0].x, r1 = pd ? xr[1].y : xr[1].x;
+            const uint32_t r2 = pd ? xr[2].y : xr[2].x, r3 = pd ? xr[3].y : xr[3].x;
+            const uint2 lo = make_uint2(__builtin_amdgcn_perm(r1, r0, SEL_LO), __builtin_amdgcn_perm(r3, r2, SEL_LO));
+            const uint2 hi = make_uint2(__builtin_amdgcn_perm(r1, r0, SEL_HI), __builtin_amdgcn_perm(r3, r2, SEL_HI));
+            acc[2 * pd] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(afrag, __builtin_bit_cast(s16x4, lo), acc[2 * pd], 0, 0, 0);
+            acc[2 * pd + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(afrag, __builtin_bit_cast(s16x4, hi), acc[2 * pd + 1], 0, 0, 0);
+        }
+    }
+    if (!col_ok) return;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int row = bi * 16 + 4 * q + r;
+        if (row >= p.S) continue;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (col0 + c >= p.Ncol) continue;
+            const float v = acc[c][r];
+            if (p.y_bf16) reinterpret_cast<uint16_t*>(p.Y)[(int64_t)row * p.ldy + col0 + c] = float_to_bf16_rne(v);
+            else reinterpret_cast<float*>(p.Y)[(int64_t)row * p.ldy + col0 + c] = v;
+        }
+    }
+}
+
+static hipError_t launch_b16(const SpmmArgs& a, hipStream_t st) {
+    SpmmArgs p = a;
+    p.NT = (int)((a.Ncol + 255) / 256);
+    const int64_t groups = (int64_t)((p.NT + 7) / 8) * p.Sb * 8;
+    if (groups > INT32_MAX) return hipErrorInvalidValue;
+    if (a.ev_start || a.ev_stop)
+        hipExtLaunchKernelGGL(spmm_b16_kernel, dim3((unsigned)groups), dim3(256), 0, st, a.ev_start, a.ev_stop, 0, p);
+    else
+        spmm_b16_kernel<<<dim3((unsigned)groups), dim3(256), 0, st>>>(p);
+    return hipGetLastError();
+}
+
 template <> hipError_t launch_reg_nm<1, 4>(const SpmmArgs&, int, int, hipStream_t);
 template <> hipError_t launch_reg_nm<2, 4>(const SpmmArgs&, int, int, hipStream_t);
 template <> hipError_t launch_reg_nm<3, 4>(const SpmmArgs&, int, int, hipStream_t);
@@ -300,6 +394,7 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, int force_shape, 
         a.inv_Wo = 1.0 / a.Wo;
         a.inv_Ho = 1.0 / a.Ho;
     }
+    if (g.B == 16) return launch_b16(a, st);
     const int shape = (force_shape >= 0 && force_shape <= 3) ? force_shape : pick_shape(g, Ncol, density_hint);
     // the specialised kernels assume whole 16-row MFMA steps of X (K % 16 == 0) and whole groups
     // of four output columns per lane (Ncol % 4 == 0)

@@ -233,13 +233,14 @@ def small_cases() -> List[LayerSpec]:
 
 
 def b16_cases() -> List[LayerSpec]:
-    """16 x 16 blocks (the paper's smallest block size): selection and packing only."""
+    """16 x 16 blocks (the paper's smallest block size)."""
     mk = LayerSpec
     return [
-        mk("b16_2:4", 48, 80, 8, 2, 4, 16, 0.5, SAL_GRAD, 0.05),
-        mk("b16_1:4", 64, 48, 8, 1, 4, 16, 0.67, SAL_MAG, 0.05),
-        mk("b16_2:8_ragged", 40, 90, 8, 2, 8, 16, 0.5, SAL_MAG, 0.05),
-        mk("b16_3:4_uneven", 64, 128, 8, 3, 4, 16, 0.4, SAL_GRAD, 0.05, None, LAYER_TOPK),
+        mk("b16_2:4", 48, 80, 200, 2, 4, 16, 0.5, SAL_GRAD, 0.05),
+        mk("b16_1:4", 64, 48, 328, 1, 4, 16, 0.67, SAL_MAG, 0.05),
+        mk("b16_2:8_ragged", 40, 90, 77, 2, 8, 16, 0.5, SAL_MAG, 0.05),
+        mk("b16_4:8", 32, 64, 520, 4, 8, 16, 0.75, SAL_MAG, 0.05),
+        mk("b16_3:4_uneven", 64, 128, 136, 3, 4, 16, 0.4, SAL_GRAD, 0.05, None, LAYER_TOPK),
     ]
 
 

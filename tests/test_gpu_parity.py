@@ -85,16 +85,19 @@ def test_every_launch_shape(L, shape):
 
 
 @pytest.mark.parametrize("L", synth.b16_cases(), ids=lambda L: L.name)
-def test_select_pack_block16(L):
-    """16 x 16 blocks: selection and packing are bit-exact; the product reports EUNSUPPORTED."""
+def test_block16_end_to_end(L):
+    """16 x 16 blocks (the paper's smallest): selection and packing bit-exact, product in tolerance."""
     W, G, X = synth.draw_small(L, 24)
     sel, vals, idxw, flags = oracle_all(L, W, G)
     layer, out = run_select_pack(L, W, G)
     assert_select_pack_equal(L, out, sel, vals, idxw, flags)
-    with pytest.raises(crisp.CrispError) as e:
-        Y = torch.zeros((L.S, 8), dtype=torch.float32, device="cuda")
-        crisp.crisp_spmm(layer.desc, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dev(X), 8, 8, Y, 8)
-    assert e.value.status == crisp.EUNSUPPORTED
+    Yref, Aref = oracle.gemm_masked(W, sel.mask, X)
+    ldx = (L.Ncol + 7) // 8 * 8
+    Xp = np.zeros((L.K, ldx), dtype=np.uint16)
+    Xp[:, : L.Ncol] = X
+    for yd in (crisp.Y_F32, crisp.Y_BF16):
+        Y = run_spmm(layer, dev(Xp), L.Ncol, ldx, yd, L.S)
+        check_product(Y, Yref, Aref, yd, L.name)
 
 
 def test_bf16_output_is_rounded_fp32_output():
