@@ -43,6 +43,9 @@ def parse():
                          "cross-stream waits cost more than the overlap gains); default is one stream")
     ap.add_argument("--explicit-im2col", action="store_true",
                     help="materialise X with crisp_im2col for conv layers instead of the fused crisp_conv_spmm")
+    ap.add_argument("--sweep", action="store_true",
+                    help="block size x N:M sweep of the paper (B in 16/32/64, N in 1/2/3 of 4) on the layers of "
+                         "the chosen workload: product time per setting, one JSON line")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 512 MiB device copy a few times (known traffic, for scaling profiler counters)")
     return ap.parse_args()
@@ -130,6 +133,57 @@ def resnet50_pass(args):
     print(json.dumps(out))
 
 
+def block_sweep(args):
+    """The paper's hardware sweep (Sec. 4.2: N in {1,2,3} of 4, block sizes 16/32/64) on the
+    shapes of the chosen workload at equal block density: time of the product alone."""
+    import torch
+    from paper_2311_14272_amd import crisp, synth
+    dev = "cuda"
+    wl = synth.config(args.config)
+    y_dtype = crisp.Y_BF16 if args.y_dtype == "bf16" else crisp.Y_F32
+    ytorch = torch.bfloat16 if y_dtype == crisp.Y_BF16 else torch.float32
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(wl.seed)
+    rows = []
+    for li, L in enumerate(wl.layers):
+        t = synth.draw_layer(wl, li, with_x=False)
+        W = torch.from_numpy(t["W"].view(np.int16)).to(dev)
+        nsets = max(2, min(8, int(600e6 // (2 * L.K * L.Ncol + 2 * L.S * L.Ncol)) + 1))
+        Xs = [torch.randn((L.K, L.Ncol), generator=gen, device=dev).clamp_(min=0).to(torch.bfloat16).view(torch.int16)
+              for _ in range(nsets)]
+        Ys = [torch.empty((L.S, L.Ncol), dtype=ytorch, device=dev) for _ in range(nsets)]
+        for B in (16, 32, 64):
+            for n in (1, 2, 3):
+                desc = crisp.layer_desc(L.S, L.K, n, 4, B, L.density, crisp.SAL_MAG)
+                dl = crisp.alloc_layer(desc, dev)
+                crisp.prune_and_pack(dl, W, None)
+
+                def run(r):
+                    crisp.crisp_spmm(desc, dl.row_ptr, dl.col_idx, dl.vals, dl.idx_words, Xs[r % nsets], L.Ncol, L.Ncol,
+                                     Ys[r % nsets], L.Ncol, y_dtype)
+                for r in range(3):
+                    run(r)
+                torch.cuda.synchronize()
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                reps = 30
+                a.record()
+                for r in range(reps):
+                    run(r)
+                b.record()
+                torch.cuda.synchronize()
+                us = a.elapsed_time(b) * 1e3 / reps
+                sz = dl.sizes
+                kept = sz.nk * B * sz.slots_per_row
+                rows.append(dict(layer=L.name, B=B, nm="%d:4" % n, k_row=sz.k_row, us=round(us, 2),
+                                 useful_tflops=round(2.0 * kept * L.Ncol / us / 1e6, 2),
+                                 metadata_bytes=int(sz.idx_words * 4 + sz.nk * 4 + (sz.Sb + 1) * 4),
+                                 value_bytes=int(kept * 2)))
+        del Xs, Ys
+        torch.cuda.empty_cache()
+    print(json.dumps({"sweep": "block size x N:M at the workload's block density, product only (back-to-back launches, "
+                               "rotating input sets)", "workload": wl.name, "y_dtype": args.y_dtype, "rows": rows}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -142,6 +196,9 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(2)
     crisp.lib()
+    if args.sweep:
+        block_sweep(args)
+        return
     if args.config == 5:
         resnet50_pass(args)
         return

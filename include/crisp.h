@@ -174,7 +174,16 @@ CRISP_API crisp_status crisp_im2col(const crisp_conv_desc *conv, const uint16_t 
  *      allocation must cover K*ldx elements.  x_layout = CRISP_X_KN.
  *   Y: S x ldy, fp32 or bf16 per y_dtype (device), ldy >= Ncol, ldy % 8 == 0.
  *      Every element Y[0..S)[0..Ncol) is written (rows of empty block-rows get 0).
- *   desc->block_density and sal_kind are not used here.
+ *   desc->sal_kind is not used here.  desc->block_density and select_mode only
+ *   steer the choice of kernel (how many blocks a block-row holds, whether all
+ *   rows hold the same number); a wrong or out-of-range density costs speed, never
+ *   correctness.
+ *   ws is unused (spmm_ws_bytes is 0).  With ws == NULL, ws_bytes in 1..7 forces
+ *   launch shape ws_bytes - 1 (0..3 register-expansion kernels: wide strips, narrow
+ *   strips, 4- and 8-way split of the block list; 4 generic LDS-expansion kernel;
+ *   5 / 6 block-row resident in LDS with narrow / wide strips) for tests and
+ *   tuning; a shape that does not apply to the problem falls back to the automatic
+ *   choice.  Results agree across shapes within the summation-order tolerance.
  * Errors: EINVAL, ESHAPE, EALIGN, EUNSUPPORTED (x_layout), EDEVICE.
  */
 CRISP_API crisp_status crisp_spmm(const crisp_layer_desc *desc, const int32_t *row_ptr, const int32_t *col_idx,

@@ -10,7 +10,7 @@ LIB = os.path.join(HERE, "libcrisp.so")
 OBJDIR = os.path.join(HERE, "_build")
 
 SOURCES = ["spmm_nm_2_4.hip", "spmm_nm_4_8.hip", "spmm_nm_3_4.hip", "spmm_nm_4_4.hip", "spmm_nm_8_8.hip", "spmm_nm_1_4.hip",
-           "spmm_nm_2_8.hip", "spmm_nm_1_8.hip", "spmm_kernels.hip", "crisp_api.hip", "select_kernels.hip",
+           "spmm_nm_2_8.hip", "spmm_nm_1_8.hip", "spmm_lds.hip", "spmm_kernels.hip", "crisp_api.hip", "select_kernels.hip",
            "pack_kernels.hip", "im2col_kernels.hip", "budget_kernels.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-ffp-contract=off",

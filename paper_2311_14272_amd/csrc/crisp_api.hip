@@ -160,10 +160,11 @@ static crisp_status spmm_impl(const crisp_layer_desc* desc, const int32_t* row_p
         misaligned(X, 16) || misaligned(Y, 16))
         return CRISP_EALIGN;
     if (x_layout != CRISP_X_KN) return CRISP_EUNSUPPORTED;
-    // ws_bytes doubles as a tuning knob when ws is NULL: 0 = automatic launch shape, 1..5 force
+    // ws_bytes doubles as a tuning knob when ws is NULL: 0 = automatic launch shape, 1..7 force
     // shape (value - 1); results do not depend on it.
-    const int force_shape = (!ws && ws_bytes >= 1 && ws_bytes <= 5) ? (int)ws_bytes - 1 : -1;
-    hipError_t e = launch_spmm(g, desc->block_density, force_shape, row_ptr, col_idx, vals, idx_words, X, nullptr, Ncol,
+    const int force_shape = (!ws && ws_bytes >= 1 && ws_bytes <= 7) ? (int)ws_bytes - 1 : -1;
+    hipError_t e = launch_spmm(g, desc->block_density, desc->select_mode == CRISP_ROW_UNIFORM, force_shape, row_ptr, col_idx, vals,
+                               idx_words, X, nullptr, Ncol,
                                ldx, Y, ldy, y_dtype, (hipEvent_t)ev_start, (hipEvent_t)ev_stop, (hipStream_t)stream);
     return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
 }
@@ -196,7 +197,8 @@ static crisp_status conv_spmm_impl(const crisp_layer_desc* desc, const crisp_con
         conv->kh * conv->kw > 64 || plane > ((int64_t)1 << 27) || ldy > ((int64_t)1 << 23) || !pattern_ok)
         return CRISP_EUNSUPPORTED;
     const int force_shape = (!ws && ws_bytes >= 1 && ws_bytes <= 4) ? (int)ws_bytes - 1 : -1;
-    hipError_t e = launch_spmm(g, desc->block_density, force_shape, row_ptr, col_idx, vals, idx_words, act, conv,
+    hipError_t e = launch_spmm(g, desc->block_density, desc->select_mode == CRISP_ROW_UNIFORM, force_shape, row_ptr, col_idx, vals,
+                               idx_words, act, conv,
                                Ncol, Ncol, Y, ldy, y_dtype, (hipEvent_t)ev_start, (hipEvent_t)ev_stop, (hipStream_t)stream);
     return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
 }

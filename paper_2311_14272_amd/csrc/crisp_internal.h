@@ -27,9 +27,10 @@ hipError_t launch_pack(const Geometry& g, int select_mode, const uint16_t* W, co
                        const int32_t* row_ptr, const int32_t* col_idx, uint16_t* vals, uint32_t* idxw,
                        int32_t* flags, hipStream_t st);
 hipError_t launch_im2col(const crisp_conv_desc& c, const uint16_t* act, uint16_t* X, int64_t ldx, hipStream_t st);
-// density_hint only steers the launch shape; force_shape < 0 lets the library choose
-// (0..3 = shapes of the specialised kernels, 4 = generic LDS-expansion kernel).
-hipError_t launch_spmm(const Geometry& g, double density_hint, int force_shape, const int32_t* row_ptr,
+// density_hint and uniform_rows (every block-row keeps the same number of blocks) only steer the
+// choice of kernel; force_shape < 0 lets the library choose (0..3 = shapes of the specialised
+// kernels, 4 = generic LDS-expansion kernel, 5 / 6 = LDS-resident block-rows, narrow / wide).
+hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows, int force_shape, const int32_t* row_ptr,
                        const int32_t* col_idx, const uint16_t* vals, const uint32_t* idxw, const uint16_t* X,
                        const crisp_conv_desc* conv, int64_t Ncol, int64_t ldx, void* Y, int64_t ldy, int y_dtype,
                        hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st);

@@ -344,6 +344,9 @@ static hipError_t launch_b16(const SpmmArgs& a, hipStream_t st) {
     return hipGetLastError();
 }
 
+int lds_capacity(int B);
+hipError_t launch_spmm_lds(const SpmmArgs& a, int B, int max_blocks, bool wide, hipStream_t st);
+
 template <> hipError_t launch_reg_nm<1, 4>(const SpmmArgs&, int, int, hipStream_t);
 template <> hipError_t launch_reg_nm<2, 4>(const SpmmArgs&, int, int, hipStream_t);
 template <> hipError_t launch_reg_nm<3, 4>(const SpmmArgs&, int, int, hipStream_t);
@@ -353,24 +356,37 @@ template <> hipError_t launch_reg_nm<2, 8>(const SpmmArgs&, int, int, hipStream_
 template <> hipError_t launch_reg_nm<4, 8>(const SpmmArgs&, int, int, hipStream_t);
 template <> hipError_t launch_reg_nm<8, 8>(const SpmmArgs&, int, int, hipStream_t);
 
-// Launch shape from the problem size: wide strips once they alone give every SIMD several
-// waves; otherwise narrow strips, and when even those are few, 4 or 8 waves split each
-// block-row's list so that enough loads are in flight to cover the memory latency.
-static int pick_shape(const Geometry& g, int64_t Ncol, double density_hint) {
+// Launch shape of the register-expansion kernels from the problem size (thresholds from sweeps
+// over the layer shapes of ResNet-50 at batch 256 and the small single-layer workloads):
+// wide strips once they give every SIMD work or the block-rows are long (the expansion of A is
+// shared by twice the columns); otherwise narrow strips; and when even those are few, 4 or 8
+// waves split each block-row's list so that enough loads are in flight to cover the latency.
+static int pick_shape(const Geometry& g, int64_t Ncol, int blocks_per_row) {
     const int64_t wide = (int64_t)g.Sb * ((Ncol + 127) / 128);
     const int64_t narrow = (int64_t)g.Sb * ((Ncol + 63) / 64);
     if (wide >= 4096) return 0;
-    double d = (density_hint > 0.0 && density_hint <= 1.0) ? density_hint : 0.5;
-    const double blocks_per_row = d * g.Kb;
-    if (narrow >= 3072 || blocks_per_row < 3.0) return 1;
+    if (blocks_per_row >= 8 && wide >= 512) return 0;
+    if (narrow >= 3072 || blocks_per_row < 3) return 1;
+    if (wide >= 512) return 0;
     // the 8-way split keeps 8 partial tiles in LDS (128 KB for 64-row blocks: one workgroup per
     // CU), so it only pays when all workgroups are resident at once
     const int64_t resident8 = g.B == 64 ? 256 : 512;
-    if (blocks_per_row >= 8.0 && narrow <= resident8) return 3;
+    if (blocks_per_row >= 8 && narrow <= resident8) return 3;
     return 2;
 }
 
-hipError_t launch_spmm(const Geometry& g, double density_hint, int force_shape, const int32_t* row_ptr,
+// Whether the LDS-resident kernels are expected to beat the register-expansion ones: the rows
+// must fit, there must be several strips per wave to amortise the expansion, and the per-block
+// expansion in registers must be expensive (4 packed slots per operand: 2:4, 4:8, ...) or
+// repeated often (long block-rows).
+static bool prefer_lds(const Geometry& g, int64_t Ncol, int blocks_per_row) {
+    if (g.B != 64 || blocks_per_row > lds_capacity(g.B)) return false;
+    const int64_t narrow = (int64_t)g.Sb * ((Ncol + 63) / 64);
+    const int slots_per_operand = (8 / g.m) * g.n;
+    return narrow >= 2048 && (slots_per_operand >= 4 || blocks_per_row >= 6);
+}
+
+hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows, int force_shape, const int32_t* row_ptr,
                        const int32_t* col_idx, const uint16_t* vals, const uint32_t* idxw, const uint16_t* X,
                        const crisp_conv_desc* conv, int64_t Ncol, int64_t ldx, void* Y, int64_t ldy, int y_dtype,
                        hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st) {
@@ -395,7 +411,17 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, int force_shape, 
         a.inv_Ho = 1.0 / a.Ho;
     }
     if (g.B == 16) return launch_b16(a, st);
-    const int shape = (force_shape >= 0 && force_shape <= 3) ? force_shape : pick_shape(g, Ncol, density_hint);
+    // LDS-resident block-rows (forced shapes 5 = narrow strips, 6 = wide strips)
+    // kept blocks per block-row as the descriptor states them (a hint: only speed depends on it)
+    const bool hint = density_hint > 0.0 && density_hint <= 1.0;
+    int bpr = hint ? (int)(density_hint * g.Kb + 0.5) : (g.Kb + 1) / 2;
+    if (bpr < 1) bpr = 1;
+    // LDS-resident block-rows (forced shapes 5 = narrow strips, 6 = wide strips)
+    const bool lds_ok = !conv && (g.K % 16) == 0 && (Ncol % 4) == 0 && ldy <= ((int64_t)1 << 23);
+    if (lds_ok && (force_shape == 5 || force_shape == 6)) return launch_spmm_lds(a, g.B, bpr, force_shape == 6, st);
+    if (lds_ok && force_shape < 0 && hint && uniform_rows && prefer_lds(g, Ncol, bpr))
+        return launch_spmm_lds(a, g.B, bpr, bpr <= 3, st);
+    const int shape = (force_shape >= 0 && force_shape <= 3) ? force_shape : pick_shape(g, Ncol, bpr);
     // the specialised kernels assume whole 16-row MFMA steps of X (K % 16 == 0) and whole groups
     // of four output columns per lane (Ncol % 4 == 0)
     if (conv || (force_shape != 4 && (g.K % 16) == 0 && (Ncol % 4) == 0 && ldy <= ((int64_t)1 << 23))) {

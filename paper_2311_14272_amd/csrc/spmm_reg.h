@@ -320,8 +320,15 @@ struct BlockBody {
     }
 };
 
+// Two waves per SIMD (256 registers each) wherever the lane's slice of the packed block is small
+// enough to fit beside 128 accumulators and 64 X registers; the wide-strip kernels of the denser
+// patterns would spill there and run with one wave per SIMD instead.
+template <int N, int M, int B, int WD>
+constexpr int waves_per_simd() { return (WD == 2 && B == 64 && Fmt<N, M, B>::FS >= 4) ? 1 : 2; }
+
 template <int N, int M, int B, int WD, int NWK, int PF, bool CONV>
-__global__ __launch_bounds__(NWK > 1 ? 64 * NWK : 256) __attribute__((amdgpu_waves_per_eu(2)))
+__global__ __launch_bounds__(NWK > 1 ? 64 * NWK : 256)
+__attribute__((amdgpu_waves_per_eu(waves_per_simd<N, M, B, WD>(), 2)))
 void spmm_reg_kernel(SpmmArgs p) {
     static_assert(!CONV || WD == 1, "conv mode pairs two output columns per lane");
     typedef Fmt<N, M, B> F;

@@ -66,11 +66,12 @@ def test_spmm_from_oracle_pack(L):
     check_product(Y, Yref, Aref, crisp.Y_F32, L.name)
 
 
-@pytest.mark.parametrize("shape", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("shape", [0, 1, 2, 3, 4, 5, 6])
 @pytest.mark.parametrize("L", synth.small_cases(), ids=lambda L: L.name)
 def test_every_launch_shape(L, shape):
     """Each launch shape of the product (wide / narrow strips, 4- and 8-way split of the block
-    list, generic LDS-expansion kernel) must give the same result within tolerance."""
+    list, generic LDS-expansion kernel, LDS-resident block-rows with narrow / wide strips) must
+    give the same result within tolerance."""
     print("case", L.name, "shape", shape, flush=True)
     W, G, X = synth.draw_small(L, 23)
     sel, vals, idxw, flags = oracle_all(L, W, G)
@@ -82,6 +83,46 @@ def test_every_launch_shape(L, shape):
     for yd in (crisp.Y_F32, crisp.Y_BF16):
         Y = run_spmm(layer, dev(Xp), L.Ncol, ldx, yd, L.S, shape=shape)
         check_product(Y, Yref, Aref, yd, "%s shape %d" % (L.name, shape))
+
+
+LDS_CASES = [
+    # spec, density hint given to crisp_spmm (None = the layer's own)
+    # several strips per wave (the strip loop and its cross-strip prefetch)
+    (synth.LayerSpec("lds_iters_b64", 1024, 256, 20000, 2, 4, 64, 0.5, synth.SAL_MAG, 0.05), None),
+    (synth.LayerSpec("lds_iters_b32", 512, 128, 9000, 1, 4, 32, 0.5, synth.SAL_MAG, 0.05), None),
+    # 19-tile variant (more than 9 blocks per block-row), ragged S
+    (synth.LayerSpec("lds_big_b64", 100, 1024, 1032, 2, 8, 64, 0.75, synth.SAL_MAG, 0.05), None),
+    # block-rows longer than the variant the hint selects: chunked re-expansion
+    (synth.LayerSpec("lds_chunk_b64", 128, 768, 3000, 3, 4, 64, 1.0, synth.SAL_MAG, 0.05), 0.25),
+    (synth.LayerSpec("lds_chunk_b32", 64, 1280, 520, 2, 4, 32, 1.0, synth.SAL_MAG, 0.05), 0.1),
+    # more blocks per row than the largest variant holds (20 > 19)
+    (synth.LayerSpec("lds_chunk_big", 64, 1280, 2000, 1, 4, 64, 1.0, synth.SAL_MAG, 0.05), None),
+    # uneven rows, some empty or longer than the hint says
+    (synth.LayerSpec("lds_uneven", 256, 1024, 1200, 2, 4, 64, 0.3, synth.SAL_MAG, 0.05, None, synth.LAYER_TOPK), None),
+]
+
+
+@pytest.mark.parametrize("case", LDS_CASES, ids=lambda c: c[0].name)
+def test_lds_resident_block_rows(case):
+    """The kernels that keep a block-row's expanded tiles in LDS: strip loop, both tile capacities,
+    and the chunked fallback for block-rows that do not fit."""
+    L, hint = case
+    print("case", L.name, flush=True)
+    W, G, X = synth.draw_small(L, 27)
+    sel, vals, idxw, flags = oracle_all(L, W, G)
+    layer, out = run_select_pack(L, W, G)
+    assert_select_pack_equal(L, out, sel, vals, idxw, flags)
+    if hint is not None:
+        layer.desc = crisp.layer_desc(L.S, L.K, L.n, L.m, L.B, hint, L.sal_kind, L.select_mode)
+    ldx = (L.Ncol + 7) // 8 * 8
+    Xp = np.zeros((L.K, ldx), dtype=np.uint16)
+    Xp[:, : L.Ncol] = X
+    dX = dev(Xp)
+    Yref, Aref = oracle.gemm_masked(W, sel.mask, X)
+    for shape in (5, 6):
+        for yd in (crisp.Y_F32, crisp.Y_BF16):
+            Y = run_spmm(layer, dX, L.Ncol, ldx, yd, L.S, shape=shape)
+            check_product(Y, Yref, Aref, yd, "%s shape %d" % (L.name, shape))
 
 
 @pytest.mark.parametrize("L", synth.b16_cases(), ids=lambda L: L.name)
