@@ -442,9 +442,11 @@ def main():
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE,
 # scaled by the same counters on a plain copy of known size); filled in from profiles/.
 TRAFFIC = {
-    # (workload, layer, y dtype): bytes per launch = 2.0 * FETCH_SIZE + 1.0 * WRITE_SIZE (KiB -> bytes);
-    # profiles/bench_c2_kernels.txt: FETCH_SIZE 10295.7 KiB, WRITE_SIZE 3136.0 KiB for the 3x3 layer's product
-    ("c2", "c2b", "bf16"): int((2.0 * 10295.7 + 3136.0) * 1024),
+    # (workload, layer, y dtype): bytes per launch = 2.0 * FETCH_SIZE + 1.0 * WRITE_SIZE (KiB -> bytes); the factors come
+    # from the same counters on an elementwise add of known size in the same runs (profiles/bench_c*_kernels.txt)
+    ("c2", "c2c", "bf16"): int((2.0 * 1767.0 + 12544.0) * 1024),
+    ("c3", "c3", "bf16"): int((2.0 * 215427.7 + 50976.0) * 1024),
+    ("c4", "c4b", "bf16"): int((2.0 * 37682.0 + 18816.0) * 1024),
 }
 
 
