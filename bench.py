@@ -124,7 +124,7 @@ def resnet50_pass(args):
            "dtype": "bf16", "data": "synthetic",
            "config": {"workload": "c5: ResNet-50, 53 convs as GEMMs, batch 256, 224x224, layer-wise inputs, B=64, "
                                   "per-layer n:m and block density drawn from the workload seed",
-                      "step": "per layer: select_mask+pack on device, lowering (fused, im2col or none), product; summed",
+                      "step": "per layer: select+pack on device (crisp_select_pack), lowering (fused, im2col or none), product; summed",
                       "y_dtype": args.y_dtype},
            "select_pack_ms": round(t_prune, 3), "forward_ms": round(t_fwd, 3),
            "useful_tflops_forward_only": round(useful / (t_fwd * 1e-3) / 1e12, 2),
@@ -421,7 +421,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s: %s" % (wl.name, ", ".join("%s %dx%dx%d %s B%d k_row %d" % (
             x["name"], x["S"], x["K"], x["Ncol"], x["nm"], x["B"], x["k_row"]) for x in info)),
-                   "step": ("select_mask+pack+" if not args.spmm_only else "") + ("im2col+spmm" if args.explicit_im2col else "spmm with the 3x3 layer's lowering fused (crisp_conv_spmm)") + " per layer",
+                   "step": ("select+pack (crisp_select_pack)+" if not args.spmm_only else "") + ("im2col+spmm" if args.explicit_im2col else "spmm with the 3x3 layer's lowering fused (crisp_conv_spmm)") + " per layer",
                    "y_dtype": args.y_dtype, "x_layout": "KN", "input_sets": nsets,
                    "streams": "one" if (not args.side_streams or args.spmm_only) else "select+pack of each layer on its own side stream, products on the main stream"},
         "dense_equivalent_tflops": round(dense_eq / (ms_per_step * 1e-3) / 1e12, 3),

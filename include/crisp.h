@@ -89,6 +89,7 @@ typedef struct {
     size_t select_ws_bytes;    /* workspace of crisp_select_mask                                 */
     size_t pack_ws_bytes;      /* workspace of crisp_pack                                        */
     size_t spmm_ws_bytes;      /* workspace of crisp_spmm                                        */
+    size_t select_pack_ws_bytes; /* workspace of crisp_select_pack                               */
 } crisp_sizes;
 
 typedef struct {
@@ -151,6 +152,24 @@ CRISP_API crisp_status crisp_select_mask(const crisp_layer_desc *desc, const uin
 CRISP_API crisp_status crisp_pack(const crisp_layer_desc *desc, const uint16_t *W, const uint32_t *nm_mask,
                         const int32_t *row_ptr, const int32_t *col_idx, uint16_t *vals,
                         uint32_t *idx_words, int32_t *flags, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * crisp_select_mask followed by crisp_pack for the same layer, in fewer launches
+ * (Alg. 1 lines 2, 4-6, 10 and the storage format of Sec. 3.1 / 3.5): while a block's
+ * weights and keep bits are in registers for scoring, its packed form is written to
+ * the workspace; once the block choice is known the kept blocks are copied to their
+ * place.  Arguments, outputs and their contents are exactly those of the two calls
+ * (nm_mask, row_ptr, col_idx, optional block_score; vals, idx_words, flags); W is
+ * required for every sal_kind.
+ * ws: device workspace of select_pack_ws_bytes (scores + packed form of all Sb*Kb
+ * blocks), 16-byte aligned; contents on entry and exit are unspecified.
+ * LAYER_TOPK and grids wider than 512 block columns run the two steps one after the
+ * other internally.  Errors: as crisp_select_mask and crisp_pack.
+ */
+CRISP_API crisp_status crisp_select_pack(const crisp_layer_desc *desc, const uint16_t *W, const float *T_or_G,
+                               uint32_t *nm_mask, int32_t *row_ptr, int32_t *col_idx,
+                               double *block_score, uint16_t *vals, uint32_t *idx_words,
+                               int32_t *flags, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Convolution lowering (Sec. 3 "Notation": the kernel tensor is reshaped so that

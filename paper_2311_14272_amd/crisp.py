@@ -33,7 +33,7 @@ class Sizes(C.Structure):
                 ("mask_words_per_row", C.c_int32), ("mask_words", C.c_int64), ("row_ptr_elems", C.c_int64),
                 ("col_idx_elems", C.c_int64), ("score_elems", C.c_int64), ("vals_elems", C.c_int64),
                 ("idx_words", C.c_int64), ("flags_elems", C.c_int64), ("select_ws_bytes", C.c_size_t),
-                ("pack_ws_bytes", C.c_size_t), ("spmm_ws_bytes", C.c_size_t)]
+                ("pack_ws_bytes", C.c_size_t), ("spmm_ws_bytes", C.c_size_t), ("select_pack_ws_bytes", C.c_size_t)]
 
 
 class ConvDesc(C.Structure):
@@ -65,6 +65,7 @@ def lib():
         L.crisp_pack_sizes.argtypes = [C.POINTER(LayerDesc), C.POINTER(Sizes)]
         L.crisp_select_mask.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.crisp_pack.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.crisp_select_pack.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.crisp_im2col.argtypes = [C.POINTER(ConvDesc), vp, vp, C.c_int64, vp]
         L.crisp_spmm.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp, vp, C.c_int64, C.c_int64, C.c_int32, vp,
                                  C.c_int64, C.c_int32, vp, C.c_size_t, vp]
@@ -73,7 +74,7 @@ def lib():
         L.crisp_spmm_timed.argtypes = [C.POINTER(LayerDesc), C.POINTER(ConvDesc), vp, vp, vp, vp, vp, C.c_int64,
                                        C.c_int64, vp, C.c_int64, C.c_int32, vp, vp, vp]
         L.crisp_global_budget.argtypes = [C.c_int32, vp, vp, C.c_double, vp, vp, vp, C.c_size_t, vp]
-        for f in (L.crisp_pack_sizes, L.crisp_select_mask, L.crisp_pack, L.crisp_im2col, L.crisp_spmm,
+        for f in (L.crisp_pack_sizes, L.crisp_select_mask, L.crisp_pack, L.crisp_select_pack, L.crisp_im2col, L.crisp_spmm,
                   L.crisp_conv_spmm, L.crisp_spmm_timed, L.crisp_global_budget):
             f.restype = C.c_int32
         _lib = L
@@ -121,6 +122,15 @@ def crisp_pack(desc, W, nm_mask, row_ptr, col_idx, vals, idx_words, flags, ws=No
                           _ptr(idx_words), _ptr(flags), _ptr(ws), ws_bytes, _stream() if stream == -1 else stream)
     if st != OK:
         raise CrispError("crisp_pack", st)
+
+
+def crisp_select_pack(desc, W, T_or_G, nm_mask, row_ptr, col_idx, vals, idx_words, flags, ws, ws_bytes, block_score=None,
+                      stream=-1):
+    st = lib().crisp_select_pack(C.byref(desc), _ptr(W), _ptr(T_or_G), _ptr(nm_mask), _ptr(row_ptr), _ptr(col_idx),
+                                 _ptr(block_score), _ptr(vals), _ptr(idx_words), _ptr(flags), _ptr(ws), ws_bytes,
+                                 _stream() if stream == -1 else stream)
+    if st != OK:
+        raise CrispError("crisp_select_pack", st)
 
 
 def crisp_im2col(conv: ConvDesc, act, X, ldx, stream=-1):
@@ -207,6 +217,7 @@ class DeviceLayer:
     vals: object
     idx_words: object
     flags: object
+    ws: object = None          # workspace of crisp_select_pack (allocated on first use)
 
 
 def alloc_layer(desc: LayerDesc, device="cuda") -> DeviceLayer:
@@ -225,8 +236,16 @@ def alloc_layer(desc: LayerDesc, device="cuda") -> DeviceLayer:
         torch.empty(4, dtype=i32, device=dev))
 
 
-def prune_and_pack(layer: DeviceLayer, W, T_or_G=None):
-    """crisp_select_mask followed by crisp_pack on the current stream."""
+def prune_and_pack(layer: DeviceLayer, W, T_or_G=None, fused=True):
+    """Selection and packing on the current stream: crisp_select_pack, or (fused=False)
+    crisp_select_mask followed by crisp_pack.  Both leave the same bytes in the layer's buffers."""
+    if fused:
+        if layer.ws is None:
+            import torch
+            layer.ws = torch.empty(max(16, layer.sizes.select_pack_ws_bytes), dtype=torch.uint8, device=W.device)
+        crisp_select_pack(layer.desc, W, T_or_G, layer.nm_mask, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words,
+                          layer.flags, layer.ws, layer.ws.numel(), block_score=layer.score)
+        return
     crisp_select_mask(layer.desc, W, T_or_G, layer.nm_mask, layer.row_ptr, layer.col_idx, layer.score)
     crisp_pack(layer.desc, W, layer.nm_mask, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, layer.flags)
 

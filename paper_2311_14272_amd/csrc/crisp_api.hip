@@ -83,6 +83,8 @@ crisp_status crisp_pack_sizes(const crisp_layer_desc* desc, crisp_sizes* out) {
     out->select_ws_bytes = (size_t)g.Sb * g.Kb * sizeof(double);
     out->pack_ws_bytes = 0;
     out->spmm_ws_bytes = 0;
+    // fused selection + packing: scores, then the packed form of every block of the grid
+    out->select_pack_ws_bytes = ((size_t)g.Sb * g.Kb * sizeof(double) + 15) / 16 * 16 + select_pack_stage_bytes(g);
     return CRISP_OK;
 }
 
@@ -124,6 +126,38 @@ crisp_status crisp_pack(const crisp_layer_desc* desc, const uint16_t* W, const u
         return CRISP_EALIGN;
     hipError_t e = launch_pack(g, desc->select_mode, W, nm_mask, row_ptr, col_idx, vals, idx_words, flags,
                                (hipStream_t)stream);
+    return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
+}
+
+crisp_status crisp_select_pack(const crisp_layer_desc* desc, const uint16_t* W, const float* T_or_G,
+                               uint32_t* nm_mask, int32_t* row_ptr, int32_t* col_idx, double* block_score,
+                               uint16_t* vals, uint32_t* idx_words, int32_t* flags, void* ws, size_t ws_bytes,
+                               void* stream) {
+    Geometry g;
+    crisp_status st = make_geometry(desc, true, &g);
+    if (st != CRISP_OK) return st;
+    if (!W || !nm_mask || !row_ptr || !col_idx || !vals || !idx_words || !flags) return CRISP_EINVAL;
+    if (desc->sal_kind != CRISP_SAL_MAG && !T_or_G) return CRISP_EINVAL;
+    if (misaligned(W, 16) || misaligned(T_or_G, 16) || misaligned(nm_mask, 16) || misaligned(row_ptr, 4) ||
+        misaligned(col_idx, 4) || misaligned(block_score, 8) || misaligned(vals, 16) || misaligned(idx_words, 16) ||
+        misaligned(flags, 4) || misaligned(ws, 16))
+        return CRISP_EALIGN;
+    const size_t score_bytes = ((size_t)g.Sb * g.Kb * sizeof(double) + 15) / 16 * 16;
+    if (!ws || ws_bytes < score_bytes + select_pack_stage_bytes(g)) return CRISP_EBUFSIZE;
+    if (g.Kb > 4096) return CRISP_EUNSUPPORTED;
+    if (desc->select_mode == CRISP_LAYER_TOPK && ((int64_t)g.Sb * g.Kb > 8192 || g.Sb > 1024)) return CRISP_EUNSUPPORTED;
+    double* score = block_score ? block_score : (double*)ws;
+    hipError_t e;
+    if (select_pack_fusable(g, desc->select_mode)) {
+        e = launch_select_pack(g, desc->sal_kind, W, T_or_G, nm_mask, row_ptr, col_idx, score, vals, idx_words, flags,
+                               (unsigned char*)ws + score_bytes, (hipStream_t)stream);
+    } else {
+        // uneven rows or very wide grids: the two steps one after the other
+        e = launch_select(g, desc->sal_kind, desc->select_mode, W, T_or_G, nm_mask, row_ptr, col_idx, block_score, score,
+                          (hipStream_t)stream);
+        if (e == hipSuccess)
+            e = launch_pack(g, desc->select_mode, W, nm_mask, row_ptr, col_idx, vals, idx_words, flags, (hipStream_t)stream);
+    }
     return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
 }
 

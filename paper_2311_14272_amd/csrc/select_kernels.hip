@@ -25,22 +25,53 @@ __device__ __forceinline__ float saliency_of(uint16_t w, float tg) {
 // is part of the definition of the block score (a tree reduction would round differently;
 // adding +0.0 for a pruned element leaves the non-negative running sum unchanged bit for bit).
 // VEC: row segments are 16-byte aligned and lie wholly inside the matrix (K % B == 0).
-template <int B, int M, int KIND, bool VEC>
+// PACK: while the block's weights and keep bits are in registers, its packed form (compressed
+// values, position stream, 2-of-4 violation) is also written, to a staging area indexed by the
+// block's place in the grid; whether the block is kept is only known after the block choice,
+// which then just copies the kept blocks' packed forms to their final place (topk_gather_kernel).
+struct StageArgs {
+    int wbits, slots, wpr;      // bits per position, packed slots and position words per block row
+    uint16_t* vals;             // [Sb*Kb][B][slots]
+    uint32_t* idxw;             // [Sb*Kb][B][wpr]
+    int32_t* viol;              // [Sb*Kb]: an aligned group of four holds more than two kept elements
+    int32_t* flags;             // the layer's flags; preset here, cleared by topk_gather_kernel
+};
+
+__device__ __forceinline__ uint32_t slot_position_of(uint32_t bits, int j, bool outside) {
+    // j-th kept column of the group; 0 when the group holds fewer; j for a group outside the matrix
+    if (outside) return (uint32_t)j;
+    for (int i = 0; i < j; ++i) bits &= bits - 1u;
+    return bits ? (uint32_t)(__ffs(bits) - 1) : 0u;
+}
+
+template <int B, int M, int KIND, bool VEC, bool PACK>
 __global__ __launch_bounds__(B * (B / 16)) void score_select_kernel(int S, int K, int n, int Kb, int mwpr,
                                                                    const uint16_t* __restrict__ W,
                                                                    const float* __restrict__ TG,
                                                                    uint32_t* __restrict__ nm_mask,
-                                                                   double* __restrict__ score) {
+                                                                   double* __restrict__ score, StageArgs sa) {
     constexpr int CPT = 16;          // columns per lane
     constexpr int Q = B / CPT;       // lanes per block row (1, 2 or 4)
     constexpr int LDT = B + 4;       // padded LDS row stride in floats (keeps 16-byte alignment)
+    constexpr int WMAX = (B * 3 + 31) / 32;   // upper bound of position words per block row
+    constexpr int NTHR = B * (B / 16);
     __shared__ __attribute__((aligned(16))) float tkept[B * LDT];
     __shared__ double rowsum[B];
+    __shared__ uint32_t pos_lds[PACK ? B * WMAX : 1];
+    __shared__ int viol_lds;
     const int bj = blockIdx.x, bi = blockIdx.y;
     const int r = threadIdx.x / Q, q = threadIdx.x % Q;
     const int s = bi * B + r;
     const int c0 = q * CPT;                      // first column of this lane inside the block
     const int k0 = bj * B + c0;
+    if constexpr (PACK) {
+        for (int e = threadIdx.x; e < B * WMAX; e += NTHR) pos_lds[e] = 0u;
+        if (threadIdx.x == 0) {
+            viol_lds = 0;
+            if (bi == 0 && bj == 0) { sa.flags[0] = 1; sa.flags[1] = 0; sa.flags[2] = 0; sa.flags[3] = 0; }
+        }
+        __syncthreads();
+    }
     uint32_t bits = 0;
     {
         uint16_t w[CPT];
@@ -48,7 +79,7 @@ __global__ __launch_bounds__(B * (B / 16)) void score_select_kernel(int S, int K
         const int len = (s < S) ? min(CPT, K - k0) : 0;   // columns of this lane that exist (may be <= 0)
         const size_t e0 = (size_t)s * K + k0;
         if (VEC && s < S) {
-            if (KIND != CRISP_SAL_GIVEN) {
+            if (PACK || KIND != CRISP_SAL_GIVEN) {
 #pragma unroll
                 for (int i = 0; i < CPT / 8; ++i) {
                     const u32x4 v = *reinterpret_cast<const u32x4*>(W + e0 + 8 * i);
@@ -70,7 +101,7 @@ __global__ __launch_bounds__(B * (B / 16)) void score_select_kernel(int S, int K
         } else {
 #pragma unroll
             for (int i = 0; i < CPT; ++i) {
-                w[i] = (KIND != CRISP_SAL_GIVEN && i < len) ? W[e0 + i] : (uint16_t)0;
+                w[i] = ((PACK || KIND != CRISP_SAL_GIVEN) && i < len) ? W[e0 + i] : (uint16_t)0;
                 tg[i] = (KIND != CRISP_SAL_MAG && i < len) ? TG[e0 + i] : 0.0f;
             }
         }
@@ -95,6 +126,56 @@ __global__ __launch_bounds__(B * (B / 16)) void score_select_kernel(int S, int K
         for (int i = 0; i < CPT / 4; ++i) {
             const f32x4 v = {kept_t[4 * i], kept_t[4 * i + 1], kept_t[4 * i + 2], kept_t[4 * i + 3]};
             *reinterpret_cast<f32x4*>(&tkept[r * LDT + c0 + 4 * i]) = v;
+        }
+        if constexpr (PACK) {
+            // the lane's CPT / M groups: n slots each, kept values in ascending column order, then
+            // zeros; positions per the canonical rules (Sec. 3.1 / 3.5 storage format)
+            if (!VEC || s >= S) {
+#pragma unroll
+                for (int i = 0; i < CPT; ++i)
+                    if (i >= len) w[i] = 0;
+            }
+            const size_t blk = (size_t)bi * Kb + bj;
+            const int slot0 = (c0 / M) * n;
+            uint16_t* sv = sa.vals + (blk * B + r) * sa.slots + slot0;
+            uint64_t stream = 0;                 // at most 16 slots x 3 bits
+            int nb = 0;
+            bool violates = false;
+#pragma unroll
+            for (int g = 0; g < CPT / M; ++g) {
+                const uint32_t gb = (bits >> (g * M)) & ((1u << M) - 1u);
+                const bool outside = (s >= S) || (k0 + g * M >= K);
+                uint16_t v[M];
+#pragma unroll
+                for (int x = 0; x < M; ++x) v[x] = 0;
+                int filled = 0;
+#pragma unroll
+                for (int o = 0; o < M; ++o) {
+                    const bool on = (gb >> o) & 1u;
+#pragma unroll
+                    for (int x = 0; x < M; ++x)
+                        if (on && filled == x) v[x] = w[g * M + o];
+                    filled += on;
+                }
+#pragma unroll
+                for (int x = 0; x < M; ++x) {
+                    if (x < n) {
+                        sv[g * n + x] = v[x];
+                        stream |= (uint64_t)slot_position_of(gb, x, outside) << nb;
+                        nb += sa.wbits;
+                    }
+                }
+                violates = violates || __popc(gb & 0xFu) > 2 || __popc(gb >> 4) > 2;
+            }
+            const int bit0 = slot0 * sa.wbits, wi = bit0 >> 5, sh = bit0 & 31;
+            uint32_t* prow = pos_lds + r * WMAX;
+            const uint32_t p0 = (uint32_t)(stream << sh);
+            const uint32_t p1 = (uint32_t)(sh ? (stream >> (32 - sh)) : (stream >> 32));
+            const uint32_t p2 = (uint32_t)(sh ? (stream >> (64 - sh)) : 0u);
+            if (p0) atomicOr(prow + wi, p0);
+            if (p1 && wi + 1 < WMAX) atomicOr(prow + wi + 1, p1);
+            if (p2 && wi + 2 < WMAX) atomicOr(prow + wi + 2, p2);
+            if (violates) viol_lds = 1;
         }
     }
     // mask: the Q lanes of a row hold 16 bits each; pairs of lanes form one 32-bit word
@@ -134,6 +215,11 @@ __global__ __launch_bounds__(B * (B / 16)) void score_select_kernel(int S, int K
 #pragma unroll
         for (int i = 0; i < B; ++i) total = __dadd_rn(total, part[i]);
         score[(size_t)bi * Kb + bj] = total;
+        if constexpr (PACK) sa.viol[(size_t)bi * Kb + bj] = viol_lds;
+    }
+    if constexpr (PACK) {
+        uint32_t* dst = sa.idxw + ((size_t)bi * Kb + bj) * B * sa.wpr;
+        for (int e = threadIdx.x; e < B * sa.wpr; e += NTHR) dst[e] = pos_lds[(e / sa.wpr) * WMAX + e % sa.wpr];
     }
 }
 
@@ -219,29 +305,35 @@ __global__ __launch_bounds__(1024) void block_topk_layer_kernel(int Sb, int Kb, 
     for (int bi = wave; bi < Sb; bi += 16) wave_compact(kept + bi * Kb, Kb, col_idx + rowcnt[bi], lane);
 }
 
-template <int B, int M, int KIND>
+template <int B, int M, int KIND, bool PACK>
 static void launch_score_select(const Geometry& g, const uint16_t* W, const float* TG, uint32_t* nm_mask,
-                                double* score, hipStream_t st) {
+                                double* score, const StageArgs& sa, hipStream_t st) {
     const dim3 grd(g.Kb, g.Sb);
     if (g.K % B == 0)
-        score_select_kernel<B, M, KIND, true><<<grd, B * (B / 16), 0, st>>>(g.S, g.K, g.n, g.Kb, g.mwpr, W, TG, nm_mask, score);
+        score_select_kernel<B, M, KIND, true, PACK><<<grd, B * (B / 16), 0, st>>>(g.S, g.K, g.n, g.Kb, g.mwpr, W, TG, nm_mask, score, sa);
     else
-        score_select_kernel<B, M, KIND, false><<<grd, B * (B / 16), 0, st>>>(g.S, g.K, g.n, g.Kb, g.mwpr, W, TG, nm_mask, score);
+        score_select_kernel<B, M, KIND, false, PACK><<<grd, B * (B / 16), 0, st>>>(g.S, g.K, g.n, g.Kb, g.mwpr, W, TG, nm_mask, score, sa);
+}
+
+template <int KIND, bool PACK>
+static void launch_score_select_bm(const Geometry& g, const uint16_t* W, const float* TG, uint32_t* nm_mask,
+                                   double* score, const StageArgs& sa, hipStream_t st) {
+    const int key = g.B * 16 + g.m;
+    switch (key) {
+        case 64 * 16 + 4: launch_score_select<64, 4, KIND, PACK>(g, W, TG, nm_mask, score, sa, st); break;
+        case 64 * 16 + 8: launch_score_select<64, 8, KIND, PACK>(g, W, TG, nm_mask, score, sa, st); break;
+        case 32 * 16 + 4: launch_score_select<32, 4, KIND, PACK>(g, W, TG, nm_mask, score, sa, st); break;
+        case 32 * 16 + 8: launch_score_select<32, 8, KIND, PACK>(g, W, TG, nm_mask, score, sa, st); break;
+        case 16 * 16 + 4: launch_score_select<16, 4, KIND, PACK>(g, W, TG, nm_mask, score, sa, st); break;
+        default: launch_score_select<16, 8, KIND, PACK>(g, W, TG, nm_mask, score, sa, st); break;
+    }
 }
 
 template <int KIND>
 static hipError_t launch_select_kind(const Geometry& g, int select_mode, const uint16_t* W, const float* TG,
                                      uint32_t* nm_mask, int32_t* row_ptr, int32_t* col_idx, double* score,
                                      hipStream_t st) {
-    const int key = g.B * 16 + g.m;
-    switch (key) {
-        case 64 * 16 + 4: launch_score_select<64, 4, KIND>(g, W, TG, nm_mask, score, st); break;
-        case 64 * 16 + 8: launch_score_select<64, 8, KIND>(g, W, TG, nm_mask, score, st); break;
-        case 32 * 16 + 4: launch_score_select<32, 4, KIND>(g, W, TG, nm_mask, score, st); break;
-        case 32 * 16 + 8: launch_score_select<32, 8, KIND>(g, W, TG, nm_mask, score, st); break;
-        case 16 * 16 + 4: launch_score_select<16, 4, KIND>(g, W, TG, nm_mask, score, st); break;
-        default: launch_score_select<16, 8, KIND>(g, W, TG, nm_mask, score, st); break;
-    }
+    launch_score_select_bm<KIND, false>(g, W, TG, nm_mask, score, StageArgs{}, st);
     if (select_mode == CRISP_ROW_UNIFORM)
         block_topk_rows_kernel<<<g.Sb, 256, 0, st>>>(g.Sb, g.Kb, g.k_row, score, row_ptr, col_idx);
     else
@@ -258,6 +350,93 @@ hipError_t launch_select(const Geometry& g, int sal_kind, int select_mode, const
     if (sal_kind == CRISP_SAL_GRAD)
         return launch_select_kind<CRISP_SAL_GRAD>(g, select_mode, W, TG, nm_mask, row_ptr, col_idx, score, st);
     return launch_select_kind<CRISP_SAL_MAG>(g, select_mode, W, TG, nm_mask, row_ptr, col_idx, score, st);
+}
+
+// Second half of the fused select + pack (uniform rows): workgroup (t, bi) works out the block
+// choice of block-row bi on its own (k_row blocks first under score descending, column ascending;
+// the Kb scores are few, so doing this once per kept block costs less than a launch), takes the
+// t-th kept column in ascending order and copies that block's packed form from the staging area to
+// its final place.  Results are identical to crisp_select_mask followed by crisp_pack.
+__global__ __launch_bounds__(256) void topk_gather_kernel(int Sb, int Kb, int k_row, int vbytes, int ibytes,
+                                                          int clear_flag, const double* __restrict__ score,
+                                                          const uint16_t* __restrict__ st_vals,
+                                                          const uint32_t* __restrict__ st_idxw,
+                                                          const int32_t* __restrict__ st_viol,
+                                                          int32_t* __restrict__ row_ptr, int32_t* __restrict__ col_idx,
+                                                          uint16_t* __restrict__ vals, uint32_t* __restrict__ idxw,
+                                                          int32_t* __restrict__ flags) {
+    __shared__ double sc[512];
+    __shared__ uint8_t kept[512];
+    __shared__ int sel;
+    const int t = blockIdx.x, bi = blockIdx.y, tid = threadIdx.x;
+    for (int j = tid; j < Kb; j += 256) sc[j] = score[(size_t)bi * Kb + j];
+    __syncthreads();
+    for (int j = tid; j < Kb; j += 256) {
+        const double mine = sc[j];
+        int before = 0;
+        for (int o = 0; o < Kb; ++o) before += (sc[o] > mine) || (sc[o] == mine && o < j);
+        kept[j] = before < k_row;
+    }
+    __syncthreads();
+    for (int j = tid; j < Kb; j += 256) {
+        if (kept[j]) {
+            int pos = 0;
+            for (int o = 0; o < j; ++o) pos += kept[o];
+            if (pos == t) sel = j;
+        }
+    }
+    __syncthreads();
+    const int bj = sel;
+    const size_t src = (size_t)bi * Kb + bj, dst = (size_t)bi * k_row + t;
+    const u32x4* sv = reinterpret_cast<const u32x4*>(reinterpret_cast<const unsigned char*>(st_vals) + src * vbytes);
+    u32x4* dv = reinterpret_cast<u32x4*>(reinterpret_cast<unsigned char*>(vals) + dst * vbytes);
+    for (int e = tid; e < vbytes / 16; e += 256) dv[e] = sv[e];
+    const u32x4* si = reinterpret_cast<const u32x4*>(reinterpret_cast<const unsigned char*>(st_idxw) + src * ibytes);
+    u32x4* di = reinterpret_cast<u32x4*>(reinterpret_cast<unsigned char*>(idxw) + dst * ibytes);
+    for (int e = tid; e < ibytes / 16; e += 256) di[e] = si[e];
+    if (tid == 0) {
+        col_idx[dst] = bj;
+        if (t == 0) {
+            row_ptr[bi] = bi * k_row;
+            if (bi == Sb - 1) row_ptr[Sb] = Sb * k_row;
+        }
+        if (clear_flag && st_viol[src] && flags[0] != 0) atomicAnd(flags, 0);
+    }
+}
+
+bool select_pack_fusable(const Geometry& g, int select_mode) {
+    return select_mode == CRISP_ROW_UNIFORM && g.Kb <= 512 && g.nk > 0;
+}
+
+size_t select_pack_stage_bytes(const Geometry& g) {
+    const size_t blocks = (size_t)g.Sb * g.Kb;
+    const size_t viol = (blocks * sizeof(int32_t) + 15) / 16 * 16;
+    return viol + blocks * g.B * g.slots * 2 + blocks * g.B * g.wpr * 4;
+}
+
+// Fused selection + packing in two launches.  stage: select_pack_stage_bytes(g) bytes, 16-byte aligned.
+hipError_t launch_select_pack(const Geometry& g, int sal_kind, const uint16_t* W, const float* TG, uint32_t* nm_mask,
+                              int32_t* row_ptr, int32_t* col_idx, double* score, uint16_t* vals, uint32_t* idxw,
+                              int32_t* flags, void* stage, hipStream_t st) {
+    const size_t blocks = (size_t)g.Sb * g.Kb;
+    unsigned char* base = static_cast<unsigned char*>(stage);
+    StageArgs sa;
+    sa.wbits = g.w; sa.slots = g.slots; sa.wpr = g.wpr;
+    sa.viol = reinterpret_cast<int32_t*>(base);
+    base += (blocks * sizeof(int32_t) + 15) / 16 * 16;
+    sa.vals = reinterpret_cast<uint16_t*>(base);
+    base += blocks * g.B * g.slots * 2;
+    sa.idxw = reinterpret_cast<uint32_t*>(base);
+    sa.flags = flags;
+    if (sal_kind == CRISP_SAL_GIVEN) launch_score_select_bm<CRISP_SAL_GIVEN, true>(g, W, TG, nm_mask, score, sa, st);
+    else if (sal_kind == CRISP_SAL_GRAD) launch_score_select_bm<CRISP_SAL_GRAD, true>(g, W, TG, nm_mask, score, sa, st);
+    else launch_score_select_bm<CRISP_SAL_MAG, true>(g, W, TG, nm_mask, score, sa, st);
+    // n <= 2 can never put three kept elements into an aligned group of four
+    const int clear_flag = g.n > 2;
+    topk_gather_kernel<<<dim3(g.k_row, g.Sb), 256, 0, st>>>(g.Sb, g.Kb, g.k_row, g.B * g.slots * 2, g.B * g.wpr * 4,
+                                                           clear_flag, score, sa.vals, sa.idxw, sa.viol, row_ptr,
+                                                           col_idx, vals, idxw, flags);
+    return hipGetLastError();
 }
 
 }  // namespace crisp

@@ -24,12 +24,17 @@ def desc_of(L):
     return crisp.layer_desc(L.S, L.K, L.n, L.m, L.B, L.density, L.sal_kind, L.select_mode)
 
 
-def run_select_pack(L, W, G):
-    """crisp_select_mask + crisp_pack on the device; returns the DeviceLayer and host copies."""
-    layer = crisp.alloc_layer(desc_of(L))
+def run_select_pack(L, W, G, fused=True, desc=None):
+    """Selection + packing on the device (crisp_select_pack, or crisp_select_mask + crisp_pack when
+    fused is False); returns the DeviceLayer and host copies.  Outputs are poisoned first so that
+    anything the library leaves unwritten shows up."""
+    layer = crisp.alloc_layer(desc if desc is not None else desc_of(L))
+    for t in (layer.nm_mask, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, layer.flags):
+        t.fill_(-1)
+    layer.score.fill_(float("nan"))
     dW = dev(W)
     dG = dev(G) if G is not None else None
-    crisp.prune_and_pack(layer, dW, dG)
+    crisp.prune_and_pack(layer, dW, dG, fused=fused)
     torch.cuda.synchronize()
     sz = layer.sizes
     out = dict(

@@ -21,7 +21,7 @@ def declared_functions():
 def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert names == ["crisp_conv_spmm", "crisp_global_budget", "crisp_im2col", "crisp_pack", "crisp_pack_sizes", "crisp_select_mask",
-                     "crisp_spmm", "crisp_spmm_timed", "crisp_status_str"]
+                     "crisp_select_pack", "crisp_spmm", "crisp_spmm_timed", "crisp_status_str"]
     L = crisp.lib()
     for n in names:
         assert getattr(L, n) is not None
@@ -62,6 +62,8 @@ def test_pack_sizes_values():
     assert (sz.slots_per_row, sz.idx_bits, sz.idx_words_per_row) == (16, 2, 1)
     assert sz.vals_elems == 144 * 32 * 16 and sz.idx_words == 144 * 32
     assert sz.mask_words == 256 * 36 and sz.row_ptr_elems == 9 and sz.score_elems == 8 * 36
+    # scores + violation flags + packed values and positions of all 8 x 36 blocks
+    assert sz.select_pack_ws_bytes == 8 * 36 * 8 + 8 * 36 * 4 + 8 * 36 * 32 * (16 * 2 + 4)
     sz = crisp.crisp_pack_sizes(crisp.layer_desc(24, 144, 2, 4, 32, 0.6))
     assert (sz.Sb, sz.Kb, sz.k_row, sz.nk) == (1, 5, 3, 3)
     sz = crisp.crisp_pack_sizes(crisp.layer_desc(64, 147, 4, 8, 64, 0.5))
@@ -97,6 +99,13 @@ def test_entry_points_reject_bad_arguments_without_a_device():
     assert L.crisp_select_mask(C.byref(d), fake + 2, None, fake, fake, fake, fake, None, 0, None) == crisp.EALIGN
     dg = crisp.layer_desc(64, 128, 2, 4, 32, 0.5, sal_kind=crisp.SAL_GRAD)
     assert L.crisp_select_mask(C.byref(dg), fake, None, fake, fake, fake, fake, None, 0, None) == crisp.EINVAL
+    sp = lambda **k: L.crisp_select_pack(C.byref(k.get("d", d)), k.get("W", fake), k.get("T", None), fake, fake, fake, None,
+                                         k.get("vals", fake), fake, fake, k.get("ws", fake), k.get("wsb", 1 << 30), None)
+    assert sp(W=None) == crisp.EINVAL
+    assert sp(d=dg) == crisp.EINVAL            # gradient saliency without a gradient tensor
+    assert sp(vals=fake + 2) == crisp.EALIGN
+    assert sp(ws=None) == crisp.EBUFSIZE
+    assert sp(wsb=crisp.crisp_pack_sizes(d).select_pack_ws_bytes - 1) == crisp.EBUFSIZE
     assert L.crisp_pack(C.byref(d), fake, fake, fake, fake, None, fake, fake, None, 0, None) == crisp.EINVAL
     assert L.crisp_pack(C.byref(d), fake, fake, fake, fake, fake + 8, fake, fake, None, 0, None) == crisp.EALIGN
     spmm = lambda **k: L.crisp_spmm(C.byref(k.get("d", d)), fake, fake, fake, fake, k.get("X", fake), k.get("N", 64),

@@ -47,6 +47,48 @@ def test_small_cases_end_to_end(L):
         check_product(Y, Yref, Aref, yd, L.name)
 
 
+@pytest.mark.parametrize("L", synth.small_cases() + synth.b16_cases(), ids=lambda L: L.name)
+def test_select_then_pack_as_two_calls(L):
+    """crisp_select_mask followed by crisp_pack (the other tests go through crisp_select_pack):
+    the same bytes, bit for bit."""
+    W, G, X = synth.draw_small(L, 21)
+    sel, vals, idxw, flags = oracle_all(L, W, G)
+    layer, out = run_select_pack(L, W, G, fused=False)
+    assert_select_pack_equal(L, out, sel, vals, idxw, flags)
+
+
+FUSED_EXTRA = [
+    # patterns that can break the 2-of-4 flag, given saliency, ragged edges, wide grids
+    synth.LayerSpec("sp_3:4_b64", 128, 320, 8, 3, 4, 64, 0.6, synth.SAL_MAG, 0.05),
+    synth.LayerSpec("sp_4:8_b32", 96, 224, 8, 4, 8, 32, 0.5, synth.SAL_GRAD, 0.05),
+    synth.LayerSpec("sp_8:8_b64", 64, 192, 8, 8, 8, 64, 0.67, synth.SAL_MAG, 0.05),
+    synth.LayerSpec("sp_4:4_b16", 48, 80, 8, 4, 4, 16, 0.5, synth.SAL_MAG, 0.05),
+    synth.LayerSpec("sp_ragged_4:8", 70, 147, 8, 4, 8, 64, 0.67, synth.SAL_GRAD, 0.1),
+    synth.LayerSpec("sp_ragged_3:4_b32", 40, 150, 8, 3, 4, 32, 0.5, synth.SAL_GRAD, 0.1),
+    synth.LayerSpec("sp_wide_grid", 64, 4096, 8, 1, 8, 16, 0.1, synth.SAL_MAG, 0.05),
+    synth.LayerSpec("sp_1:8_b16", 40, 90, 8, 1, 8, 16, 0.5, synth.SAL_MAG, 0.05),
+    # more than 512 block columns: crisp_select_pack runs the two steps one after the other
+    synth.LayerSpec("sp_very_wide_grid", 16, 9600, 8, 2, 4, 16, 0.05, synth.SAL_MAG, 0.05),
+    synth.LayerSpec("sp_uneven_rows", 256, 512, 8, 3, 4, 64, 0.3, synth.SAL_GRAD, 0.05, None, synth.LAYER_TOPK),
+]
+
+
+@pytest.mark.parametrize("L", FUSED_EXTRA, ids=lambda L: L.name)
+def test_select_pack_extra_patterns(L):
+    """crisp_select_pack on the patterns the small cases do not reach, against the oracle and
+    against the two separate calls; also with the saliency handed in directly."""
+    W, G, X = synth.draw_small(L, 29)
+    sel, vals, idxw, flags = oracle_all(L, W, G)
+    for fused in (True, False):
+        layer, out = run_select_pack(L, W, G, fused=fused)
+        assert_select_pack_equal(L, out, sel, vals, idxw, flags)
+    # SAL_GIVEN: hand the oracle's saliency in; masks and packing must not change
+    T = np.abs(synth.bf16_bits_to_f32(W) * G).astype(np.float32) if G is not None else np.abs(synth.bf16_bits_to_f32(W))
+    d = crisp.layer_desc(L.S, L.K, L.n, L.m, L.B, L.density, crisp.SAL_GIVEN, L.select_mode)
+    layer, out = run_select_pack(L, W, T.astype(np.float32), fused=True, desc=d)
+    assert_select_pack_equal(L, out, sel, vals, idxw, flags)
+
+
 @pytest.mark.parametrize("L", synth.small_cases()[:6], ids=lambda L: L.name)
 def test_spmm_from_oracle_pack(L):
     """The product kernel alone, fed with the oracle's packed structure."""
