@@ -81,7 +81,7 @@ def resnet50_pass(args):
         acts = [torch.randn((cv.C, cv.batch, cv.H, cv.W), generator=gen, device=dev).clamp_(min=0).to(torch.bfloat16).view(torch.int16)
                 for _ in range(nbuf)]
         Ys = [torch.empty((L.S, L.Ncol), dtype=ytorch, device=dev) for _ in range(nbuf)]
-        Xs = torch.empty((L.K, L.Ncol), dtype=torch.int16, device=dev) if crisp.conv_needs_scratch(cv, L.B, L.n, L.m) else None
+        Xs = torch.empty((L.K, L.Ncol), dtype=torch.int16, device=dev) if crisp.conv_needs_scratch(cv, L.B, L.n, L.m, L.S) else None
 
         def timed(fn):
             fn(0)

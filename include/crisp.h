@@ -216,7 +216,13 @@ CRISP_API crisp_status crisp_spmm(const crisp_layer_desc *desc, const int32_t *r
  * from the convolution's input).  Same result, bit for bit, as crisp_im2col followed by
  * crisp_spmm.  act is [C][batch][H][W] bf16 (device); desc->K must equal kh*kw*C; Y is
  * S x ldy with Ncol = batch*Ho*Wo columns written.
- * Covered: stride 1, C % B == 0, Wo even, B in {32, 64}, n:m in {1..4}:4 or {1,2,4,8}:8.
+ * Covered: Ncol even, B in {32, 64}, n:m in {1..4}:4 or {1,2,4,8}:8, kw <= 16,
+ * kh*kw <= 64, stride <= 16, batch*H*W <= 2^27, ldy <= 2^23.  With C % B == 0 every block
+ * column belongs to one filter tap: for stride 1 and even Wo a lane's two output columns
+ * come from one 4-byte load, otherwise (strided, odd Wo, 1x1 with stride) each column is
+ * located and loaded on its own.  Other channel counts (the first layer of a network):
+ * every K-row is split into (tap, channel) on its own; needs K <= 65535 and an activation
+ * below 4 GiB.
  * Anything else returns CRISP_EUNSUPPORTED (use crisp_im2col + crisp_spmm).
  * Errors: EINVAL, ESHAPE, EALIGN, EUNSUPPORTED, EDEVICE.
  */

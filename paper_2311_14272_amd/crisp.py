@@ -257,20 +257,39 @@ def conv_desc_of(cv) -> ConvDesc:
 
 def fused_lowering_ok(cv, B: int, n: int, m: int) -> bool:
     """Whether crisp_conv_spmm covers this convolution (otherwise crisp_im2col + crisp_spmm)."""
-    Wo = cv.W + 2 * cv.pad - cv.kw + 1
+    Ho = (cv.H + 2 * cv.pad - cv.kh) // cv.stride + 1
+    Wo = (cv.W + 2 * cv.pad - cv.kw) // cv.stride + 1
     pattern = (m == 4 and n <= 4) or (m == 8 and n in (1, 2, 4, 8))
-    return (cv.stride == 1 and B in (32, 64) and cv.C % B == 0 and Wo % 2 == 0 and cv.W >= 2 and cv.kw <= 16
-            and cv.kh * cv.kw <= 64 and pattern)
+    plane = cv.batch * cv.H * cv.W
+    thin_ok = cv.C % B == 0 or (cv.C * plane * 2 < (1 << 32) - 16 and cv.kh * cv.kw * cv.C <= 65535)
+    return (B in (32, 64) and thin_ok and (cv.batch * Ho * Wo) % 2 == 0 and cv.kw <= 16 and cv.kh * cv.kw <= 64
+            and cv.stride <= 16 and plane <= (1 << 27) and pattern)
 
 
-def conv_needs_scratch(cv, B: int, n: int, m: int) -> bool:
-    """Whether conv_forward needs an X scratch buffer (K x round_up(Ncol, 8) bf16) for this layer."""
+def lowering_path(cv, B: int, n: int, m: int, S: int) -> str:
+    """How conv_forward runs this convolution: "none" (act is X), "fused" (crisp_conv_spmm) or
+    "im2col" (crisp_im2col into a scratch X, then crisp_spmm).  The fused kernels locate strided or
+    odd-width columns one by one with 2-byte loads; that beats writing X only where X would be an
+    inflated copy (more than one filter tap) that few block-rows read (measured on the ResNet-50
+    layers at batch 256)."""
     Ho = (cv.H + 2 * cv.pad - cv.kh) // cv.stride + 1
     Wo = (cv.W + 2 * cv.pad - cv.kw) // cv.stride + 1
     pointwise = cv.kh == 1 and cv.kw == 1 and cv.stride == 1 and cv.pad == 0
-    if pointwise:
-        return (cv.batch * Ho * Wo) % 8 != 0      # act can serve as X only with an aligned row stride
-    return not fused_lowering_ok(cv, B, n, m)
+    if pointwise and (cv.batch * Ho * Wo) % 8 == 0:
+        return "none"
+    if not pointwise and fused_lowering_ok(cv, B, n, m):
+        paired = cv.stride == 1 and Wo % 2 == 0 and cv.W >= 2 and cv.C % B == 0
+        if paired or (cv.kh * cv.kw > 1 and (S + B - 1) // B <= FUSED_GENERAL_MAX_BLOCK_ROWS):
+            return "fused"
+    return "im2col"
+
+
+FUSED_GENERAL_MAX_BLOCK_ROWS = 4
+
+
+def conv_needs_scratch(cv, B: int, n: int, m: int, S: int) -> bool:
+    """Whether conv_forward needs an X scratch buffer (K x round_up(Ncol, 8) bf16) for this layer."""
+    return lowering_path(cv, B, n, m, S) == "im2col"
 
 
 def conv_forward(layer: DeviceLayer, cv, act, Y, ldy, y_dtype=Y_F32, X_scratch=None):
@@ -282,14 +301,14 @@ def conv_forward(layer: DeviceLayer, cv, act, Y, ldy, y_dtype=Y_F32, X_scratch=N
     Ho = (cv.H + 2 * cv.pad - cv.kh) // cv.stride + 1
     Wo = (cv.W + 2 * cv.pad - cv.kw) // cv.stride + 1
     Ncol = cv.batch * Ho * Wo
-    pointwise = cv.kh == 1 and cv.kw == 1 and cv.stride == 1 and cv.pad == 0
-    if pointwise and Ncol % 8 == 0:
+    path = lowering_path(cv, d.B, d.n, d.m, d.S)
+    if path == "none":
         crisp_spmm(d, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, act, Ncol, Ncol, Y, ldy, y_dtype)
-        return "none"
-    if not pointwise and fused_lowering_ok(cv, d.B, d.n, d.m):
+        return path
+    if path == "fused":
         crisp_conv_spmm(d, conv_desc_of(cv), layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, act, Y, ldy,
                         y_dtype)
-        return "fused"
+        return path
     if X_scratch is None:
         raise ValueError("this convolution needs an X scratch buffer of K x round_up(Ncol, 8) bf16")
     ldx = (Ncol + 7) // 8 * 8

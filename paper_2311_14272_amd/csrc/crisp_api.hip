@@ -172,7 +172,7 @@ crisp_status crisp_im2col(const crisp_conv_desc* c, const uint16_t* act, uint16_
     int64_t Ncol = (int64_t)c->batch * Ho * Wo;
     int64_t K = (int64_t)c->kh * c->kw * c->C;
     if (ldx < Ncol || Ncol > INT32_MAX || K > INT32_MAX) return CRISP_ESHAPE;
-    if ((int64_t)c->batch * c->H * c->W >= ((int64_t)1 << 31) || K > 65535) return CRISP_EUNSUPPORTED;
+    if ((int64_t)c->batch * c->H * c->W >= ((int64_t)1 << 31) || c->C > (1 << 20)) return CRISP_EUNSUPPORTED;
     if (misaligned(act, 16) || misaligned(X, 16)) return CRISP_EALIGN;
     hipError_t e = launch_im2col(*c, act, X, ldx, (hipStream_t)stream);
     return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
@@ -217,8 +217,9 @@ static crisp_status conv_spmm_impl(const crisp_layer_desc* desc, const crisp_con
         return CRISP_ESHAPE;
     if (conv->act_layout != CRISP_ACT_CBHW) return CRISP_EUNSUPPORTED;
     if ((int64_t)conv->kh * conv->kw * conv->C != g.K) return CRISP_ESHAPE;
-    const int64_t Ho = (int64_t)conv->H + 2 * conv->pad - conv->kh + 1;
-    const int64_t Wo = (int64_t)conv->W + 2 * conv->pad - conv->kw + 1;
+    if (conv->H + 2 * conv->pad < conv->kh || conv->W + 2 * conv->pad < conv->kw) return CRISP_ESHAPE;
+    const int64_t Ho = ((int64_t)conv->H + 2 * conv->pad - conv->kh) / conv->stride + 1;
+    const int64_t Wo = ((int64_t)conv->W + 2 * conv->pad - conv->kw) / conv->stride + 1;
     if (Ho < 1 || Wo < 1) return CRISP_ESHAPE;
     const int64_t Ncol = (int64_t)conv->batch * Ho * Wo;
     const int64_t plane = (int64_t)conv->batch * conv->H * conv->W;
@@ -227,8 +228,11 @@ static crisp_status conv_spmm_impl(const crisp_layer_desc* desc, const crisp_con
         return CRISP_EALIGN;
     // what the fused kernels cover; everything else goes through crisp_im2col + crisp_spmm
     const bool pattern_ok = (g.m == 4 && g.n <= 4) || (g.m == 8 && (g.n == 1 || g.n == 2 || g.n == 4 || g.n == 8));
-    if (conv->stride != 1 || g.B == 16 || conv->C % g.B != 0 || (Wo & 1) || conv->W < 2 || conv->kw > 16 ||
-        conv->kh * conv->kw > 64 || plane > ((int64_t)1 << 27) || ldy > ((int64_t)1 << 23) || !pattern_ok)
+    if (g.B == 16 || (Ncol & 1) || conv->kw > 16 || conv->kh * conv->kw > 64 || conv->stride > 16 ||
+        plane > ((int64_t)1 << 27) || ldy > ((int64_t)1 << 23) || !pattern_ok)
+        return CRISP_EUNSUPPORTED;
+    // channel counts that are no multiple of B: rows are located one by one inside one buffer range
+    if (conv->C % g.B != 0 && ((int64_t)conv->C * plane * 2 >= ((int64_t)1 << 32) - 16 || g.K > 65535))
         return CRISP_EUNSUPPORTED;
     const int force_shape = (!ws && ws_bytes >= 1 && ws_bytes <= 4) ? (int)ws_bytes - 1 : -1;
     hipError_t e = launch_spmm(g, desc->block_density, desc->select_mode == CRISP_ROW_UNIFORM, force_shape, row_ptr, col_idx, vals,

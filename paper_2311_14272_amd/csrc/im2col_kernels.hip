@@ -7,73 +7,77 @@ namespace crisp {
 struct Im2colArgs {
     int C, H, W, batch, kh, kw, stride, pad, Ho, Wo;
     int Ncol;
+    int TG, CG;               // filter taps and channels handled by one thread
     double inv_Wo, inv_Ho;
-    int64_t ldx;
+    int64_t ldx, plane;       // row stride of X, elements of one channel plane (batch*H*W)
     const uint16_t* act;
     uint16_t* X;
 };
 
-// One thread produces 8 consecutive columns of one X row (one 16-byte store when aligned).
-// The row's tap (a, b) and channel c are uniform per workgroup; the thread splits its first
-// column into (image, oh, ow) once and then walks the 8 columns with incremental updates, all
-// in 32-bit arithmetic (a channel plane batch*H*W is below 2^31 elements).
-template <bool VEC>
+// One thread owns two neighbouring columns (output positions) and writes them, one 4-byte store
+// per row, for TG filter taps x CG channels: all rows of one tap share the source position, so
+// the split of the column number into (image, oh, ow) and the border tests are done once per
+// thread and tap, and the loop over channels is loads and stores only.  Neighbouring lanes own
+// neighbouring column pairs: a wave reads and writes contiguous runs.
+// PAIR: ldx is even, so the two columns of a thread are one aligned 32-bit word of X.
+template <bool PAIR>
 __global__ __launch_bounds__(256) void im2col_kernel(Im2colArgs p) {
-    const int row = blockIdx.y;
-    const int j0 = (blockIdx.x * 256 + threadIdx.x) * 8;
+    const int j0 = (blockIdx.x * 256 + threadIdx.x) * 2;
     if (j0 >= p.Ncol) return;
-    const int c = row % p.C;
-    const int tap = row / p.C;
-    const int a = tap / p.kw, b = tap % p.kw;
+    const bool has1 = j0 + 1 < p.Ncol;
     // exact unsigned division through fp64 reciprocals (operands are below 2^31)
     int t = (int)((double)j0 * p.inv_Wo);
     t -= (t * p.Wo > j0);
     t += ((t + 1) * p.Wo <= j0);
-    int ow = j0 - t * p.Wo;
-    int i = (int)((double)t * p.inv_Ho);
-    i -= (i * p.Ho > t);
-    i += ((i + 1) * p.Ho <= t);
-    int oh = t - i * p.Ho;
-    const uint16_t* plane = p.act + (size_t)c * p.batch * p.H * p.W;
-    int ih = oh * p.stride + a - p.pad;
-    int iw = ow * p.stride + b - p.pad;
-    int rowbase = (i * p.H + ih) * p.W;
-    // all 8 loads are issued unconditionally (index 0 stands in for positions outside the image)
-    // so that they are in flight together; the selection happens after they return
-    uint16_t v[8];
-    bool in[8];
+    const int ow0 = j0 - t * p.Wo;
+    int i0 = (int)((double)t * p.inv_Ho);
+    i0 -= (i0 * p.Ho > t);
+    i0 += ((i0 + 1) * p.Ho <= t);
+    const int oh0 = t - i0 * p.Ho;
+    int ow1 = ow0 + 1, oh1 = oh0, i1 = i0;
+    if (ow1 == p.Wo) { ow1 = 0; ++oh1; }
+    if (oh1 == p.Ho) { oh1 = 0; ++i1; }
+    if (!has1) { ow1 = ow0; oh1 = oh0; i1 = i0; }
+
+    const int tap_end = min(p.kh * p.kw, ((int)blockIdx.y + 1) * p.TG);
+    const int c_begin = blockIdx.z * p.CG, c_end = min(p.C, c_begin + p.CG);
+    for (int tap = blockIdx.y * p.TG; tap < tap_end; ++tap) {
+        const int a = tap / p.kw, b = tap - a * p.kw;
+        const int ih0 = oh0 * p.stride + a - p.pad, iw0 = ow0 * p.stride + b - p.pad;
+        const int ih1 = oh1 * p.stride + a - p.pad, iw1 = ow1 * p.stride + b - p.pad;
+        const bool v0 = (unsigned)ih0 < (unsigned)p.H && (unsigned)iw0 < (unsigned)p.W;
+        const bool v1 = has1 && (unsigned)ih1 < (unsigned)p.H && (unsigned)iw1 < (unsigned)p.W;
+        // positions outside the image read element 0 of the plane (always there) and are zeroed
+        const int off0 = v0 ? (i0 * p.H + ih0) * p.W + iw0 : 0;
+        const int off1 = v1 ? (i1 * p.H + ih1) * p.W + iw1 : 0;
+        const uint16_t* src = p.act + (int64_t)c_begin * p.plane;
+        uint16_t* dst = p.X + ((int64_t)tap * p.C + c_begin) * p.ldx + j0;
+        // eight channels at a time: all loads first (X may not alias act, but the compiler cannot
+        // know), then the stores, so that the loads are in flight together
+        for (int c = c_begin; c < c_end; c += 8) {
+            uint32_t e0[8], e1[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        in[e] = (j0 + e < p.Ncol) && ((unsigned)ih < (unsigned)p.H) && ((unsigned)iw < (unsigned)p.W);
-        v[e] = plane[in[e] ? rowbase + iw : 0];
-        iw += p.stride;
-        if (++ow == p.Wo) {
-            ow = 0;
-            iw = b - p.pad;
-            ih += p.stride;
-            rowbase += p.stride * p.W;
-            if (++oh == p.Ho) {
-                oh = 0;
-                ++i;
-                ih = a - p.pad;
-                rowbase = (i * p.H + ih) * p.W;
+            for (int u = 0; u < 8; ++u) {
+                const int64_t po = (int64_t)min(u, c_end - 1 - c) * p.plane;   // channels past the end re-read the last
+                e0[u] = src[po + off0];
+                e1[u] = src[po + off1];
             }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (c + u < c_end) {
+                    const uint32_t a0 = v0 ? e0[u] : 0u, a1 = v1 ? e1[u] : 0u;
+                    uint16_t* d = dst + (int64_t)u * p.ldx;
+                    if (PAIR && has1) {
+                        *reinterpret_cast<uint32_t*>(d) = a0 | (a1 << 16);
+                    } else {
+                        d[0] = (uint16_t)a0;
+                        if (has1) d[1] = (uint16_t)a1;
+                    }
+                }
+            }
+            src += 8 * p.plane;
+            dst += 8 * p.ldx;
         }
-    }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = in[e] ? v[e] : (uint16_t)0;
-    uint16_t* dst = p.X + (size_t)row * p.ldx + j0;
-    if (VEC && j0 + 8 <= p.Ncol) {
-        uint4 pk;
-        pk.x = v[0] | ((uint32_t)v[1] << 16);
-        pk.y = v[2] | ((uint32_t)v[3] << 16);
-        pk.z = v[4] | ((uint32_t)v[5] << 16);
-        pk.w = v[6] | ((uint32_t)v[7] << 16);
-        *reinterpret_cast<uint4*>(dst) = pk;
-    } else {
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-            if (j0 + e < p.Ncol) dst[e] = v[e];
     }
 }
 
@@ -86,13 +90,18 @@ hipError_t launch_im2col(const crisp_conv_desc& c, const uint16_t* act, uint16_t
     p.inv_Wo = 1.0 / p.Wo;
     p.inv_Ho = 1.0 / p.Ho;
     p.ldx = ldx;
+    p.plane = (int64_t)c.batch * c.H * c.W;
     p.act = act;
     p.X = X;
-    const int K = c.kh * c.kw * c.C;
-    const int chunks = (p.Ncol + 7) / 8;
-    dim3 grd((chunks + 255) / 256, K);
-    if (K > 65535) return hipErrorInvalidValue;
-    if ((ldx & 7) == 0)
+    // 16 to 32 rows per thread: whole channel runs of one tap, or for thin inputs (the first
+    // layer's 3 channels) a few taps with all their channels
+    p.CG = c.C < 16 ? c.C : 16;
+    p.TG = c.C < 16 ? (16 + c.C - 1) / c.C : 1;
+    const int taps = c.kh * c.kw;
+    const int pairs = (p.Ncol + 1) / 2;
+    const dim3 grd((pairs + 255) / 256, (taps + p.TG - 1) / p.TG, (c.C + p.CG - 1) / p.CG);
+    if (grd.y > 65535 || grd.z > 65535) return hipErrorInvalidValue;
+    if ((ldx & 1) == 0)
         im2col_kernel<true><<<grd, 256, 0, st>>>(p);
     else
         im2col_kernel<false><<<grd, 256, 0, st>>>(p);

@@ -401,11 +401,16 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
         // implicit lowering: X is the activation itself
         a.act = X;
         a.X = nullptr;
-        a.C = conv->C; a.H = conv->H; a.W = conv->W; a.kw = conv->kw; a.pad = conv->pad;
-        a.Ho = conv->H + 2 * conv->pad - conv->kh + 1;
-        a.Wo = conv->W + 2 * conv->pad - conv->kw + 1;
+        a.C = conv->C; a.H = conv->H; a.W = conv->W; a.kw = conv->kw; a.pad = conv->pad; a.stride = conv->stride;
+        a.Ho = (conv->H + 2 * conv->pad - conv->kh) / conv->stride + 1;
+        a.Wo = (conv->W + 2 * conv->pad - conv->kw) / conv->stride + 1;
+        // neighbours in a row from one dword when that is possible, else column by column
+        a.conv_mode = (conv->stride == 1 && (a.Wo & 1) == 0 && conv->W >= 2) ? 1 : 2;
+        if (conv->C % g.B != 0) a.conv_mode = 3;   // block columns span filter taps: every K-row on its own
         a.plane = (int64_t)conv->batch * conv->H * conv->W;
-        a.inv_cpb = 1.0f / (float)(conv->C / g.B);
+        a.act_bytes = a.conv_mode == 3 ? (uint32_t)((int64_t)conv->C * a.plane * 2) : 0u;
+        a.inv_C = 1.0f / (float)conv->C;
+        a.inv_cpb = conv->C >= g.B ? 1.0f / (float)(conv->C / g.B) : 1.0f;
         a.inv_kw = 1.0f / (float)conv->kw;
         a.inv_Wo = 1.0 / a.Wo;
         a.inv_Ho = 1.0 / a.Ho;

@@ -44,9 +44,17 @@ struct SpmmArgs {
     void* Y;
     int y_bf16;
     // implicit lowering (conv mode): X is not materialised; its rows are read from the activation
-    // [C][batch][H][W].  Stride 1, C % B == 0, Wo even.
+    // [C][batch][H][W], C % B == 0.  conv_mode 1: stride 1 and even Wo, a lane's two output columns
+    // are neighbours in a row and come from one dword.  conv_mode 2: any stride and Wo, the two
+    // columns are located independently and loaded with one 2-byte load each.  conv_mode 3: any C
+    // (a block column may span several filter taps): like 2, and in addition every K-row is split
+    // into (tap, channel) on its own; elements outside the image or past K are requested at an
+    // offset beyond the activation's buffer range, for which the hardware returns zero.
     const uint16_t* act;
-    int C, H, W, kw, pad, Ho, Wo;
+    int conv_mode;
+    uint32_t act_bytes;       // size of the activation (conv_mode 3: range of the buffer resource)
+    float inv_C;
+    int C, H, W, kw, pad, stride, Ho, Wo;
     int64_t plane;            // batch*H*W elements of one channel
     float inv_cpb, inv_kw;    // reciprocals of C/B (block columns per tap) and kw
     double inv_Wo, inv_Ho;
@@ -60,6 +68,7 @@ struct SpmmArgs {
 struct XCtx {
     uint32_t off;
     uint32_t sel_lo, sel_hi;
+    uint32_t off2;   // conv mode 2: address part of the lane's second column
 };
 constexpr uint32_t SEL_LO = 0x05040100u;    // r0.lo | r1.lo << 16
 constexpr uint32_t SEL_HI = 0x07060302u;    // r0.hi | r1.hi << 16
@@ -69,6 +78,7 @@ constexpr uint32_t SEL_ZERO = 0x0C0C0C0Cu;  // v_perm_b32: selector byte 0x0c yi
 struct ConvPos {
     int img, oh, ow;
     uint32_t half_off;   // hh * 8 channel planes, in bytes
+    int img1, oh1, ow1;  // conv mode 2: position of the lane's second column
 };
 
 __device__ __forceinline__ uint16_t float_to_bf16_rne(float f) {
@@ -176,10 +186,11 @@ __device__ __forceinline__ u32x4 expand_frag(const uint32_t (&v)[Fmt<N, M, B>::V
 // X rows of block column bj_next are requested into the same registers as soon as their
 // current contents have been turned into MFMA operands, and block t_next's compressed slice
 // after the last step; the body is straight-line code, so the compiler's wait counters stay exact.
-template <int N, int M, int B, int WD, bool PREFETCH, bool CONV>
+template <int N, int M, int B, int WD, bool PREFETCH, int CONV>
 struct BlockBody {
     typedef Fmt<N, M, B> F;
-    typedef typename XVec<WD>::type xvec_t;
+    static constexpr int XW = CONV >= 2 ? 2 : WD;    // registers per loaded X row
+    typedef typename XVec<XW>::type xvec_t;
     static constexpr int RT = F::RT, KS = F::KS, NACC = 2 * WD;
 
     // Conv mode: context of block column bj.  All B K-rows of the block column belong to one
@@ -193,6 +204,32 @@ struct BlockBody {
         const int tap = (int)(((float)bj + 0.5f) * p.inv_cpb);
         const int a = (int)(((float)tap + 0.5f) * p.inv_kw);
         const int b = tap - a * p.kw;
+        if constexpr (CONV == 3) {
+            // nothing depends on the block column: window origins of the two columns
+            XCtx c;
+            c.off = (uint32_t)((cp.img * p.H + cp.oh * p.stride - p.pad) * p.W + cp.ow * p.stride - p.pad);
+            c.off2 = (uint32_t)((cp.img1 * p.H + cp.oh1 * p.stride - p.pad) * p.W + cp.ow1 * p.stride - p.pad);
+            c.sel_lo = SEL_LO;
+            c.sel_hi = SEL_LO;
+            return c;
+        }
+        if constexpr (CONV == 2) {
+            // each column on its own: source act[c][img][oh*stride + a - pad][ow*stride + b - pad]
+            // or, outside the image, any valid address and a selector that yields zeros
+            const int ih0 = cp.oh * p.stride + a - p.pad, iw0 = cp.ow * p.stride + b - p.pad;
+            const int ih1 = cp.oh1 * p.stride + a - p.pad, iw1 = cp.ow1 * p.stride + b - p.pad;
+            const bool v0 = (unsigned)ih0 < (unsigned)p.H && (unsigned)iw0 < (unsigned)p.W;
+            const bool v1 = (unsigned)ih1 < (unsigned)p.H && (unsigned)iw1 < (unsigned)p.W;
+            const int safe = (cp.img * p.H + cp.oh * p.stride) * p.W + cp.ow * p.stride;   // inside the image
+            const int s0 = v0 ? (cp.img * p.H + ih0) * p.W + iw0 : safe;
+            const int s1 = v1 ? (cp.img1 * p.H + ih1) * p.W + iw1 : safe;
+            XCtx c;
+            c.off = cp.half_off + (uint32_t)s0 * 2u;
+            c.off2 = cp.half_off + (uint32_t)s1 * 2u;
+            c.sel_lo = v0 ? SEL_LO : SEL_ZERO;
+            c.sel_hi = v1 ? SEL_LO : SEL_ZERO;
+            return c;
+        }
         const int ih = cp.oh + a - p.pad, iw = cp.ow + b - p.pad;
         const bool vr = (unsigned)ih < (unsigned)p.H;
         const bool v0 = vr && (unsigned)iw < (unsigned)p.W;
@@ -207,22 +244,56 @@ struct BlockBody {
         else if (v1) { off = src + 1; c.sel_hi = SEL_LO; }   // loaded (e0, e1): column 1 <- e0
         else if (v0) { off = src - 1; c.sel_lo = SEL_HI; }   // loaded (e[W-2], e[W-1]): column 0 <- e[W-1]
         c.off = cp.half_off + (uint32_t)off * 2u;
+        c.off2 = 0u;
         return c;
     }
 
     // X rows of block column bj, MFMA step ks.  K is a multiple of 16 here, so a step lies either
     // wholly inside the matrix or wholly past its end; a step past the end re-reads the last 16
     // rows instead (finite values times the zero padding of the packed block).
-    __device__ static __forceinline__ void load_x(xvec_t (&dst)[8], const SpmmArgs& p, uint32_t lane_off, int bj,
-                                                   int ks) {
-        if constexpr (CONV) {
+    __device__ static __forceinline__ void load_x(xvec_t (&dst)[8], const SpmmArgs& p, const ConvPos& cp,
+                                                   uint32_t lane_off, uint32_t lane_off2, int bj, int ks) {
+        if constexpr (CONV == 3) {
+            // K-row k = tap*C + c with tap = a*kw + b, per row; lane_off / lane_off2 are the element
+            // offsets of the two columns' window origins (oh*stride - pad, ow*stride - pad) inside a
+            // channel plane, cp.half_off holds hh*8 here (rows, not bytes)
+            const rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.act), 0, p.act_bytes, 0x00020000);
+            const int ih0 = cp.oh * p.stride - p.pad, iw0 = cp.ow * p.stride - p.pad;
+            const int ih1 = cp.oh1 * p.stride - p.pad, iw1 = cp.ow1 * p.stride - p.pad;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int k = bj * B + ks * 16 + (int)cp.half_off + i;
+                const int tap = (int)(((float)k + 0.5f) * p.inv_C);
+                const int c = k - tap * p.C;
+                const int a = (int)(((float)tap + 0.5f) * p.inv_kw);
+                const int b = tap - a * p.kw;
+                const bool kin = k < p.K;
+                const bool v0 = kin && (unsigned)(ih0 + a) < (unsigned)p.H && (unsigned)(iw0 + b) < (unsigned)p.W;
+                const bool v1 = kin && (unsigned)(ih1 + a) < (unsigned)p.H && (unsigned)(iw1 + b) < (unsigned)p.W;
+                const uint32_t shift = (uint32_t)(c * (int)p.plane + a * p.W + b);
+                const uint32_t o0 = v0 ? (lane_off + shift) * 2u : 0xFFFFFFFEu;
+                const uint32_t o1 = v1 ? (lane_off2 + shift) * 2u : 0xFFFFFFFEu;
+                const uint32_t e0 = __builtin_amdgcn_raw_buffer_load_b16(r, o0, 0, 0);
+                const uint32_t e1 = __builtin_amdgcn_raw_buffer_load_b16(r, o1, 0, 0);
+                dst[i] = u32x2{e0, e1};
+            }
+        } else if constexpr (CONV != 0) {
             // K-row = tap*C + c: the 16 rows of the step are 16 consecutive channel planes
             const int tap = (int)(((float)bj + 0.5f) * p.inv_cpb);
             const int c0 = bj * B - tap * p.C + ks * 16;
             const rsrc_t r = make_rsrc(p.act + (int64_t)c0 * p.plane);
             const uint32_t row_bytes = (uint32_t)p.plane * 2u;
+            if constexpr (CONV == 2) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) dst[i] = buf_load_x<WD>(r, lane_off, (uint32_t)i * row_bytes);
+                for (int i = 0; i < 8; ++i) {
+                    const uint32_t e0 = __builtin_amdgcn_raw_buffer_load_b16(r, lane_off, (uint32_t)i * row_bytes, 0);
+                    const uint32_t e1 = __builtin_amdgcn_raw_buffer_load_b16(r, lane_off2, (uint32_t)i * row_bytes, 0);
+                    dst[i] = u32x2{e0, e1};
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) dst[i] = buf_load_x<WD>(r, lane_off, (uint32_t)i * row_bytes);
+            }
         } else {
             const int kb = min(bj * B + ks * 16, p.K - 16);
             const rsrc_t r = make_rsrc(p.X + (int64_t)kb * p.ldx);
@@ -257,9 +328,10 @@ struct BlockBody {
     template <int ks>
     __device__ static __forceinline__ void step(f32x16 (&acc)[RT][NACC], xvec_t (&xr)[KS][8],
                                                 const uint32_t (&av)[RT][KS][F::VW], const uint32_t (&ws)[RT][F::WPR],
-                                                const SpmmArgs& p, const XCtx& cur, uint32_t next_off, int bj_next) {
+                                                const SpmmArgs& p, const ConvPos& cp, const XCtx& cur, const XCtx& next,
+                                                int bj_next) {
         // 8 rows x 2*WD columns of 16-bit halves -> 2*WD operands of 8 K-values each
-        uint32_t xd[8][WD];
+        uint32_t xd[8][XW];
 #pragma unroll
         for (int r = 0; r < 8; ++r) xvec_unpack(xr[ks][r], xd[r]);
         bf16x8 bfrag[NACC];
@@ -269,14 +341,20 @@ struct BlockBody {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 // v_perm_b32: result bytes picked from {r1 (bytes 4..7), r0 (bytes 0..3)}
-                const uint32_t r0 = xd[2 * q][pd], r1 = xd[2 * q + 1][pd];
-                lo[q] = __builtin_amdgcn_perm(r1, r0, CONV ? cur.sel_lo : SEL_LO);  // first column of the pair
-                hi[q] = __builtin_amdgcn_perm(r1, r0, CONV ? cur.sel_hi : SEL_HI);  // second column
+                if constexpr (CONV >= 2) {
+                    // register 0 of a row holds the first column's element, register 1 the second's
+                    lo[q] = __builtin_amdgcn_perm(xd[2 * q + 1][0], xd[2 * q][0], cur.sel_lo);
+                    hi[q] = __builtin_amdgcn_perm(xd[2 * q + 1][1], xd[2 * q][1], cur.sel_hi);
+                } else {
+                    const uint32_t r0 = xd[2 * q][pd], r1 = xd[2 * q + 1][pd];
+                    lo[q] = __builtin_amdgcn_perm(r1, r0, CONV ? cur.sel_lo : SEL_LO);  // first column of the pair
+                    hi[q] = __builtin_amdgcn_perm(r1, r0, CONV ? cur.sel_hi : SEL_HI);  // second column
+                }
             }
             bfrag[2 * pd] = __builtin_bit_cast(bf16x8, lo);
             bfrag[2 * pd + 1] = __builtin_bit_cast(bf16x8, hi);
         }
-        if constexpr (PREFETCH) load_x(xr[ks], p, next_off, bj_next, ks);
+        if constexpr (PREFETCH) load_x(xr[ks], p, cp, next.off, next.off2, bj_next, ks);
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
             const u32x4 a4 = expand_frag<N, M, B, ks>(av[rt][ks], ws[rt]);
@@ -296,7 +374,7 @@ struct BlockBody {
         XCtx nx = cx;
         if constexpr (PREFETCH) {
             bj_next = p.col_idx[t_next];
-            if constexpr (CONV) nx = conv_ctx(p, cp, bj_next);
+            if constexpr (CONV != 0) nx = conv_ctx(p, cp, bj_next);
         }
         // drop the other half-wave's position bits: bit 0 of ws is this lane's first slot
         uint32_t ws[RT][F::WPR];
@@ -307,11 +385,11 @@ struct BlockBody {
                 for (int i = 0; i < F::WPR; ++i)
                     ws[rt][i] = __builtin_amdgcn_alignbit(i + 1 < F::WPR ? aw[rt][i + 1] : 0u, aw[rt][i], aw_sh);
         }
-        step<0>(acc, xr, av, ws, p, cx, nx.off, bj_next);
-        step<1>(acc, xr, av, ws, p, cx, nx.off, bj_next);
+        step<0>(acc, xr, av, ws, p, cp, cx, nx, bj_next);
+        step<1>(acc, xr, av, ws, p, cp, cx, nx, bj_next);
         if constexpr (KS == 4) {
-            step<2>(acc, xr, av, ws, p, cx, nx.off, bj_next);
-            step<3>(acc, xr, av, ws, p, cx, nx.off, bj_next);
+            step<2>(acc, xr, av, ws, p, cp, cx, nx, bj_next);
+            step<3>(acc, xr, av, ws, p, cp, cx, nx, bj_next);
         }
         if constexpr (PREFETCH) {
             load_a(av, aw, p, a_off, i_off, t_next);
@@ -326,7 +404,7 @@ struct BlockBody {
 template <int N, int M, int B, int WD>
 constexpr int waves_per_simd() { return (WD == 2 && B == 64 && Fmt<N, M, B>::FS >= 4) ? 1 : 2; }
 
-template <int N, int M, int B, int WD, int NWK, int PF, bool CONV>
+template <int N, int M, int B, int WD, int NWK, int PF, int CONV>
 __global__ __launch_bounds__(NWK > 1 ? 64 * NWK : 256)
 __attribute__((amdgpu_waves_per_eu(waves_per_simd<N, M, B, WD>(), 2)))
 void spmm_reg_kernel(SpmmArgs p) {
@@ -335,9 +413,9 @@ void spmm_reg_kernel(SpmmArgs p) {
     constexpr int RT = F::RT, KS = F::KS;
     constexpr int STRIPS = NWK > 1 ? 1 : 4;       // column strips per workgroup
     constexpr int NACC = 2 * WD;                   // accumulator tiles (consecutive columns) per lane
-    typedef typename XVec<WD>::type xvec_t;
     typedef BlockBody<N, M, B, WD, true, CONV> BodyP;
     typedef BlockBody<N, M, B, WD, false, CONV> BodyL;
+    typedef typename BodyP::xvec_t xvec_t;
 
     // Workgroup -> (block-row, strip group); ids are dealt round-robin to the 8 XCDs, and all
     // block-rows of a strip group get ids on the same XCD so they share its L2 for X.
@@ -356,9 +434,9 @@ void spmm_reg_kernel(SpmmArgs p) {
     // lane part of every X address (bytes): its 8-row half and its columns; lanes past the last
     // column read column 0 instead (in bounds) and never store
     const int64_t col_ld = col_ok ? col0 : 0;
-    ConvPos cp = {0, 0, 0, 0u};
+    ConvPos cp = {0, 0, 0, 0u, 0, 0, 0};
     uint32_t lane_off = 0;
-    if constexpr (CONV) {
+    if constexpr (CONV != 0) {
         // column -> (image, oh, ow); exact division through fp64 reciprocals (col < 2^31)
         const int j = (int)col_ld;
         int t = (int)((double)j * p.inv_Wo);
@@ -370,7 +448,12 @@ void spmm_reg_kernel(SpmmArgs p) {
         im += ((im + 1) * p.Ho <= t);
         cp.oh = t - im * p.Ho;
         cp.img = im;
-        cp.half_off = (uint32_t)((int64_t)hh * 8 * p.plane * 2);
+        cp.half_off = CONV == 3 ? (uint32_t)(hh * 8) : (uint32_t)((int64_t)hh * 8 * p.plane * 2);
+        // the next column (conv mode 2; Ncol is even, so it exists whenever the first one does)
+        cp.ow1 = cp.ow + 1; cp.oh1 = cp.oh; cp.img1 = cp.img;
+        if (cp.ow1 == p.Wo) { cp.ow1 = 0; cp.oh1 += 1; }
+        if (cp.oh1 == p.Ho) { cp.oh1 = 0; cp.img1 += 1; }
+        if (cp.img1 * p.Ho * p.Wo + cp.oh1 * p.Wo + cp.ow1 >= p.Ncol) { cp.img1 = cp.img; cp.oh1 = cp.oh; cp.ow1 = cp.ow; }
     } else {
         lane_off = (uint32_t)(((int64_t)hh * 8 * p.ldx + col_ld) * 2);
     }
@@ -401,10 +484,10 @@ void spmm_reg_kernel(SpmmArgs p) {
         if (d < cnt) {
             const int t = first + d * NWK;
             const int bj = p.col_idx[t];
-            if constexpr (CONV) cx[d] = BodyL::conv_ctx(p, cp, bj);
-            else cx[d] = XCtx{lane_off, SEL_LO, SEL_HI};
+            if constexpr (CONV != 0) cx[d] = BodyL::conv_ctx(p, cp, bj);
+            else cx[d] = XCtx{lane_off, SEL_LO, SEL_HI, 0u};
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) BodyL::load_x(xr[d][ks], p, cx[d].off, bj, ks);
+            for (int ks = 0; ks < KS; ++ks) BodyL::load_x(xr[d][ks], p, cp, cx[d].off, cx[d].off2, bj, ks);
             BodyL::load_a(av[d], aw[d], p, a_off, i_off, t);
         }
     }
@@ -505,7 +588,7 @@ void spmm_reg_kernel(SpmmArgs p) {
     }
 }
 
-template <int N, int M, int B, int WD, int NWK, int PF, bool CONV>
+template <int N, int M, int B, int WD, int NWK, int PF, int CONV>
 hipError_t launch_reg(const SpmmArgs& a, hipStream_t st) {
     SpmmArgs p = a;
     constexpr int STRIPS = NWK > 1 ? 1 : 4;
@@ -525,19 +608,35 @@ hipError_t launch_reg(const SpmmArgs& a, hipStream_t st) {
 // 2 / 3 = narrow strips, 4 / 8 waves split the block list.  Conv mode has the narrow shapes only.
 template <int N, int M, int B>
 hipError_t launch_reg_shape(const SpmmArgs& a, int shape, hipStream_t st) {
+    if (a.act != nullptr && a.conv_mode == 3) {
+        switch (shape) {
+            case 0:
+            case 1: return launch_reg<N, M, B, 1, 1, 1, 3>(a, st);
+            case 2: return launch_reg<N, M, B, 1, 4, 1, 3>(a, st);
+            default: return launch_reg<N, M, B, 1, 8, 1, 3>(a, st);
+        }
+    }
+    if (a.act != nullptr && a.conv_mode == 2) {
+        switch (shape) {
+            case 0:
+            case 1: return launch_reg<N, M, B, 1, 1, 1, 2>(a, st);
+            case 2: return launch_reg<N, M, B, 1, 4, 1, 2>(a, st);
+            default: return launch_reg<N, M, B, 1, 8, 1, 2>(a, st);
+        }
+    }
     if (a.act != nullptr) {
         switch (shape) {
             case 0:
-            case 1: return launch_reg<N, M, B, 1, 1, 1, true>(a, st);
-            case 2: return launch_reg<N, M, B, 1, 4, 1, true>(a, st);
-            default: return launch_reg<N, M, B, 1, 8, 1, true>(a, st);
+            case 1: return launch_reg<N, M, B, 1, 1, 1, 1>(a, st);
+            case 2: return launch_reg<N, M, B, 1, 4, 1, 1>(a, st);
+            default: return launch_reg<N, M, B, 1, 8, 1, 1>(a, st);
         }
     }
     switch (shape) {
-        case 0: return launch_reg<N, M, B, 2, 1, 1, false>(a, st);
-        case 1: return launch_reg<N, M, B, 1, 1, 1, false>(a, st);
-        case 2: return launch_reg<N, M, B, 1, 4, 1, false>(a, st);
-        default: return launch_reg<N, M, B, 1, 8, 1, false>(a, st);
+        case 0: return launch_reg<N, M, B, 2, 1, 1, 0>(a, st);
+        case 1: return launch_reg<N, M, B, 1, 1, 1, 0>(a, st);
+        case 2: return launch_reg<N, M, B, 1, 4, 1, 0>(a, st);
+        default: return launch_reg<N, M, B, 1, 8, 1, 0>(a, st);
     }
 }
 

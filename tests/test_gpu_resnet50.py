@@ -40,7 +40,7 @@ def _run_layers(batch, sample_cols):
         Ncol = L.Ncol
         ld = (Ncol + 7) // 8 * 8
         Y = torch.empty((L.S, ld), dtype=torch.float32, device="cuda")
-        need_x = crisp.conv_needs_scratch(cv, L.B, L.n, L.m)
+        need_x = crisp.conv_needs_scratch(cv, L.B, L.n, L.m, L.S)
         Xs = torch.zeros((L.K, ld), dtype=torch.int16, device="cuda") if need_x else None
         path = crisp.conv_forward(layer, cv, dact, Y, ld, crisp.Y_F32, Xs)
         torch.cuda.synchronize()
