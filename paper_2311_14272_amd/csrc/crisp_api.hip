@@ -196,7 +196,7 @@ static crisp_status spmm_impl(const crisp_layer_desc* desc, const int32_t* row_p
     if (x_layout != CRISP_X_KN) return CRISP_EUNSUPPORTED;
     // ws_bytes doubles as a tuning knob when ws is NULL: 0 = automatic launch shape, 1..7 force
     // shape (value - 1); results do not depend on it.
-    const int force_shape = (!ws && ws_bytes >= 1 && ws_bytes <= 7) ? (int)ws_bytes - 1 : -1;
+    const int force_shape = (!ws && ws_bytes >= 1 && ws_bytes <= 11) ? (int)ws_bytes - 1 : -1;
     hipError_t e = launch_spmm(g, desc->block_density, desc->select_mode == CRISP_ROW_UNIFORM, force_shape, row_ptr, col_idx, vals,
                                idx_words, X, nullptr, Ncol,
                                ldx, Y, ldy, y_dtype, (hipEvent_t)ev_start, (hipEvent_t)ev_stop, (hipStream_t)stream);
@@ -234,7 +234,8 @@ static crisp_status conv_spmm_impl(const crisp_layer_desc* desc, const crisp_con
     // channel counts that are no multiple of B: rows are located one by one inside one buffer range
     if (conv->C % g.B != 0 && ((int64_t)conv->C * plane * 2 >= ((int64_t)1 << 32) - 16 || g.K > 65535))
         return CRISP_EUNSUPPORTED;
-    const int force_shape = (!ws && ws_bytes >= 1 && ws_bytes <= 4) ? (int)ws_bytes - 1 : -1;
+    const int force_shape = (!ws && ws_bytes >= 1 && ws_bytes <= 4) ? (int)ws_bytes - 1
+                          : (!ws && ws_bytes >= 8 && ws_bytes <= 11) ? (int)ws_bytes - 1 : -1;
     hipError_t e = launch_spmm(g, desc->block_density, desc->select_mode == CRISP_ROW_UNIFORM, force_shape, row_ptr, col_idx, vals,
                                idx_words, act, conv,
                                Ncol, Ncol, Y, ldy, y_dtype, (hipEvent_t)ev_start, (hipEvent_t)ev_stop, (hipStream_t)stream);

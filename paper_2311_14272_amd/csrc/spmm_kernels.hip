@@ -361,9 +361,16 @@ template <> hipError_t launch_reg_nm<8, 8>(const SpmmArgs&, int, int, hipStream_
 // wide strips once they give every SIMD work or the block-rows are long (the expansion of A is
 // shared by twice the columns); otherwise narrow strips; and when even those are few, 4 or 8
 // waves split each block-row's list so that enough loads are in flight to cover the latency.
-static int pick_shape(const Geometry& g, int64_t Ncol, int blocks_per_row) {
+static int pick_shape(const Geometry& g, int64_t Ncol, int blocks_per_row, bool smf) {
     const int64_t wide = (int64_t)g.Sb * ((Ncol + 127) / 128);
     const int64_t narrow = (int64_t)g.Sb * ((Ncol + 63) / 64);
+    if (smf) {
+        // sparse matrix-core instantiations: no expansion work to share between columns, so narrow
+        // strips (more waves) win more often; 2:4 with wide strips is limited to one wave per SIMD
+        if (blocks_per_row <= 1) return wide >= 2048 ? 0 : 1;
+        if (narrow >= 1024) return ((g.n == 1 && blocks_per_row >= 7) || blocks_per_row >= 20) ? 0 : 1;
+        return (blocks_per_row >= 8 && g.B == 64) ? 2 : 1;
+    }
     if (wide >= 4096) return 0;
     if (blocks_per_row >= 8 && wide >= 512) return 0;
     if (narrow >= 3072 || blocks_per_row < 3) return 1;
@@ -381,6 +388,7 @@ static int pick_shape(const Geometry& g, int64_t Ncol, int blocks_per_row) {
 // repeated often (long block-rows).
 static bool prefer_lds(const Geometry& g, int64_t Ncol, int blocks_per_row) {
     if (g.B != 64 || blocks_per_row > lds_capacity(g.B)) return false;
+    if (g.m == 4 && g.n <= 2) return false;   // the sparse matrix-core path needs no expansion at all
     const int64_t narrow = (int64_t)g.Sb * ((Ncol + 63) / 64);
     const int slots_per_operand = (8 / g.m) * g.n;
     return narrow >= 2048 && (slots_per_operand >= 4 || blocks_per_row >= 6);
@@ -426,7 +434,13 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
     if (lds_ok && (force_shape == 5 || force_shape == 6)) return launch_spmm_lds(a, g.B, bpr, force_shape == 6, st);
     if (lds_ok && force_shape < 0 && hint && uniform_rows && prefer_lds(g, Ncol, bpr))
         return launch_spmm_lds(a, g.B, bpr, bpr <= 3, st);
-    const int shape = (force_shape >= 0 && force_shape <= 3) ? force_shape : pick_shape(g, Ncol, bpr);
+    // forced shapes 7..10: shapes 0..3 of the register kernels with the sparse matrix-core instruction
+    // (the automatic choice always takes it where the pattern is eligible: it was faster for every
+    // measured layer; shapes 0..3 force the dense-expansion instantiations)
+    a.use_smf = (force_shape < 0 || (force_shape >= 7 && force_shape <= 10)) ? 1 : 0;
+    const int shape = (force_shape >= 0 && force_shape <= 3) ? force_shape
+                    : (force_shape >= 7 && force_shape <= 10) ? force_shape - 7
+                    : pick_shape(g, Ncol, bpr, a.use_smf && g.m == 4 && g.n <= 2);
     // the specialised kernels assume whole 16-row MFMA steps of X (K % 16 == 0) and whole groups
     // of four output columns per lane (Ncol % 4 == 0)
     if (conv || (force_shape != 4 && (g.K % 16) == 0 && (Ncol % 4) == 0 && ldy <= ((int64_t)1 << 23))) {

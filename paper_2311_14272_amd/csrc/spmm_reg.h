@@ -28,6 +28,7 @@
 namespace crisp {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) __bf16 bf16x16;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
@@ -58,6 +59,7 @@ struct SpmmArgs {
     int64_t plane;            // batch*H*W elements of one channel
     float inv_cpb, inv_kw;    // reciprocals of C/B (block columns per tap) and kw
     double inv_Wo, inv_Ho;
+    int use_smf;              // host side only: sparse-MFMA instantiation wanted (eligible patterns)
     // host side only: optional events that receive the kernel's own start and stop time stamps
     hipEvent_t ev_start, ev_stop;
 };
@@ -186,7 +188,18 @@ __device__ __forceinline__ u32x4 expand_frag(const uint32_t (&v)[Fmt<N, M, B>::V
 // X rows of block column bj_next are requested into the same registers as soon as their
 // current contents have been turned into MFMA operands, and block t_next's compressed slice
 // after the last step; the body is straight-line code, so the compiler's wait counters stay exact.
-template <int N, int M, int B, int WD, bool PREFETCH, int CONV>
+// SMF: the A operand goes to the sparse matrix core instruction (v_smfmac_f32_32x32x32_bf16, "at
+// most 2 non-zeros in every aligned group of 4" along K) instead of being expanded to dense form.
+// Operand layout as measured on gfx950: lane (row l % 32, half h = l / 32) supplies the 8 stored
+// values of its row for the 16 dense columns 16h .. 16h+15 of the 32-deep step and, in bits 0..15 of
+// the index register, a 2-bit position per stored value; the B operand is the concatenation of the
+// two dense 32x32x16 operands of the step's two 16-deep halves (exactly what the X path builds);
+// two stored values of a group may name the same position when one of them is zero.  For 2:4 the
+// lane's slice of the canonical pack IS the operand: 16 bytes of values and 16 position bits.
+template <int N, int M>
+constexpr bool smf_pattern() { return M == 4 && N <= 2; }
+
+template <int N, int M, int B, int WD, bool PREFETCH, int CONV, bool SMF = false>
 struct BlockBody {
     typedef Fmt<N, M, B> F;
     static constexpr int XW = CONV >= 2 ? 2 : WD;    // registers per loaded X row
@@ -314,9 +327,20 @@ struct BlockBody {
         const uint32_t ib = (uint32_t)t * (B * F::WPR * 4);
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
+            if constexpr (SMF) {
+                // one request per 32-deep step: the 2*FS stored values behind the lane's 16 columns
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                load_vals<F::FS>(rv, a_off + (rt * 32 * F::SLOTS + ks * 2 * F::FS) * 2, vb, v[rt][ks]);
+                for (int s2 = 0; s2 < KS / 2; ++s2) {
+                    uint32_t t[F::VW * 2];
+                    load_vals<2 * F::FS>(rv, a_off + (rt * 32 * F::SLOTS + s2 * 4 * F::FS) * 2, vb, t);
+#pragma unroll
+                    for (int x = 0; x < F::VW; ++x) { v[rt][2 * s2][x] = t[x]; v[rt][2 * s2 + 1][x] = t[F::VW + x]; }
+                }
+            } else {
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+                    load_vals<F::FS>(rv, a_off + (rt * 32 * F::SLOTS + ks * 2 * F::FS) * 2, vb, v[rt][ks]);
+            }
             if constexpr (N != M) {
 #pragma unroll
                 for (int i = 0; i < F::WPR; ++i)
@@ -365,6 +389,68 @@ struct BlockBody {
         }
     }
 
+    // Sparse-MFMA version of two consecutive steps (one 32-deep step of the sparse instruction).
+    template <int s2>
+    __device__ static __forceinline__ void step_smf(f32x16 (&acc)[RT][NACC], xvec_t (&xr)[KS][8],
+                                                    const uint32_t (&av)[RT][KS][F::VW], const uint32_t (&ws)[RT][F::WPR],
+                                                    const SpmmArgs& p, const ConvPos& cp, const XCtx& cur, const XCtx& next,
+                                                    int bj_next) {
+        u32x4 half[2][NACC];
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2) {
+            const int ks = 2 * s2 + k2;
+            uint32_t xd[8][XW];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) xvec_unpack(xr[ks][r], xd[r]);
+#pragma unroll
+            for (int pd = 0; pd < WD; ++pd) {
+                u32x4 lo, hi;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if constexpr (CONV >= 2) {
+                        lo[q] = __builtin_amdgcn_perm(xd[2 * q + 1][0], xd[2 * q][0], cur.sel_lo);
+                        hi[q] = __builtin_amdgcn_perm(xd[2 * q + 1][1], xd[2 * q][1], cur.sel_hi);
+                    } else {
+                        const uint32_t r0 = xd[2 * q][pd], r1 = xd[2 * q + 1][pd];
+                        lo[q] = __builtin_amdgcn_perm(r1, r0, CONV ? cur.sel_lo : SEL_LO);
+                        hi[q] = __builtin_amdgcn_perm(r1, r0, CONV ? cur.sel_hi : SEL_HI);
+                    }
+                }
+                half[k2][2 * pd] = lo;
+                half[k2][2 * pd + 1] = hi;
+            }
+            if constexpr (PREFETCH) load_x(xr[ks], p, cp, next.off, next.off2, bj_next, ks);
+        }
+        constexpr int P = 4 * s2 * F::HB;   // first position bit of this step in the lane's (shifted) stream
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            u32x4 a4;
+            uint32_t idx;
+            if constexpr (N == 2) {
+                // 2:4: values and positions as packed
+                a4 = u32x4{av[rt][2 * s2][0], av[rt][2 * s2][1], av[rt][2 * s2 + 1][0], av[rt][2 * s2 + 1][1]};
+                idx = ws[rt][P >> 5] >> (P & 31);
+            } else {
+                // 1:4: each stored value gets a zero partner at the same position
+                const uint32_t w0 = av[rt][2 * s2][0], w1 = av[rt][2 * s2 + 1][0];
+                a4 = u32x4{w0 & 0xFFFFu, w0 >> 16, w1 & 0xFFFFu, w1 >> 16};
+                uint32_t y = (ws[rt][P >> 5] >> (P & 31)) & 0xFFu;   // p3 p2 p1 p0, two bits each
+                y = (y | (y << 4)) & 0x0F0Fu;
+                y = (y | (y << 2)) & 0x3333u;
+                idx = y | (y << 2);
+            }
+            const bf16x8 afrag = __builtin_bit_cast(bf16x8, a4);
+#pragma unroll
+            for (int c = 0; c < NACC; ++c) {
+                typedef __attribute__((ext_vector_type(8))) uint32_t u32x8;
+                const u32x8 b8 = {half[0][c][0], half[0][c][1], half[0][c][2], half[0][c][3],
+                                  half[1][c][0], half[1][c][1], half[1][c][2], half[1][c][3]};
+                acc[rt][c] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(afrag, __builtin_bit_cast(bf16x16, b8), acc[rt][c],
+                                                                       (int)idx, 0, 0);
+            }
+        }
+    }
+
     // cx: context of the block held in this ring slot; replaced by the next block's on prefetch.
     __device__ static __forceinline__ void run(f32x16 (&acc)[RT][NACC], xvec_t (&xr)[KS][8],
                                                uint32_t (&av)[RT][KS][F::VW], uint32_t (&aw)[RT][F::WPR], XCtx& cx,
@@ -385,11 +471,16 @@ struct BlockBody {
                 for (int i = 0; i < F::WPR; ++i)
                     ws[rt][i] = __builtin_amdgcn_alignbit(i + 1 < F::WPR ? aw[rt][i + 1] : 0u, aw[rt][i], aw_sh);
         }
-        step<0>(acc, xr, av, ws, p, cp, cx, nx, bj_next);
-        step<1>(acc, xr, av, ws, p, cp, cx, nx, bj_next);
-        if constexpr (KS == 4) {
-            step<2>(acc, xr, av, ws, p, cp, cx, nx, bj_next);
-            step<3>(acc, xr, av, ws, p, cp, cx, nx, bj_next);
+        if constexpr (SMF) {
+            step_smf<0>(acc, xr, av, ws, p, cp, cx, nx, bj_next);
+            if constexpr (KS == 4) step_smf<1>(acc, xr, av, ws, p, cp, cx, nx, bj_next);
+        } else {
+            step<0>(acc, xr, av, ws, p, cp, cx, nx, bj_next);
+            step<1>(acc, xr, av, ws, p, cp, cx, nx, bj_next);
+            if constexpr (KS == 4) {
+                step<2>(acc, xr, av, ws, p, cp, cx, nx, bj_next);
+                step<3>(acc, xr, av, ws, p, cp, cx, nx, bj_next);
+            }
         }
         if constexpr (PREFETCH) {
             load_a(av, aw, p, a_off, i_off, t_next);
@@ -404,7 +495,7 @@ struct BlockBody {
 template <int N, int M, int B, int WD>
 constexpr int waves_per_simd() { return (WD == 2 && B == 64 && Fmt<N, M, B>::FS >= 4) ? 1 : 2; }
 
-template <int N, int M, int B, int WD, int NWK, int PF, int CONV>
+template <int N, int M, int B, int WD, int NWK, int PF, int CONV, bool SMF = false>
 __global__ __launch_bounds__(NWK > 1 ? 64 * NWK : 256)
 __attribute__((amdgpu_waves_per_eu(waves_per_simd<N, M, B, WD>(), 2)))
 void spmm_reg_kernel(SpmmArgs p) {
@@ -413,8 +504,8 @@ void spmm_reg_kernel(SpmmArgs p) {
     constexpr int RT = F::RT, KS = F::KS;
     constexpr int STRIPS = NWK > 1 ? 1 : 4;       // column strips per workgroup
     constexpr int NACC = 2 * WD;                   // accumulator tiles (consecutive columns) per lane
-    typedef BlockBody<N, M, B, WD, true, CONV> BodyP;
-    typedef BlockBody<N, M, B, WD, false, CONV> BodyL;
+    typedef BlockBody<N, M, B, WD, true, CONV, SMF> BodyP;
+    typedef BlockBody<N, M, B, WD, false, CONV, SMF> BodyL;
     typedef typename BodyP::xvec_t xvec_t;
 
     // Workgroup -> (block-row, strip group); ids are dealt round-robin to the 8 XCDs, and all
@@ -457,9 +548,11 @@ void spmm_reg_kernel(SpmmArgs p) {
     } else {
         lane_off = (uint32_t)(((int64_t)hh * 8 * p.ldx + col_ld) * 2);
     }
-    const uint32_t a_off = (uint32_t)((jj * F::SLOTS + hh * F::FS) * 2);
+    // lane part of the packed block's addresses: its row, and the slots behind its half of a step
+    // (8 dense columns of a 16-deep step, 16 of a 32-deep sparse step)
+    const uint32_t a_off = (uint32_t)((jj * F::SLOTS + hh * F::FS * (SMF ? 2 : 1)) * 2);
     const uint32_t i_off = (uint32_t)(jj * F::WPR * 4);
-    const uint32_t aw_sh = (uint32_t)hh * F::HB;
+    const uint32_t aw_sh = (uint32_t)hh * F::HB * (SMF ? 2 : 1);
 
     const int t_begin = p.row_ptr[bi], t_end = p.row_ptr[bi + 1];
     const int first = t_begin + (NWK > 1 ? wave : 0);
@@ -588,8 +681,8 @@ void spmm_reg_kernel(SpmmArgs p) {
     }
 }
 
-template <int N, int M, int B, int WD, int NWK, int PF, int CONV>
-hipError_t launch_reg(const SpmmArgs& a, hipStream_t st) {
+template <int N, int M, int B, int WD, int NWK, int PF, int CONV, bool SMF = false>
+hipError_t launch_reg_k(const SpmmArgs& a, hipStream_t st) {
     SpmmArgs p = a;
     constexpr int STRIPS = NWK > 1 ? 1 : 4;
     const int64_t span = (int64_t)STRIPS * 64 * WD;
@@ -598,10 +691,18 @@ hipError_t launch_reg(const SpmmArgs& a, hipStream_t st) {
     if (groups > INT32_MAX) return hipErrorInvalidValue;
     const dim3 grd((unsigned)groups), blk(NWK > 1 ? 64 * NWK : 256);
     if (a.ev_start || a.ev_stop)
-        hipExtLaunchKernelGGL((spmm_reg_kernel<N, M, B, WD, NWK, PF, CONV>), grd, blk, 0, st, a.ev_start, a.ev_stop, 0, p);
+        hipExtLaunchKernelGGL((spmm_reg_kernel<N, M, B, WD, NWK, PF, CONV, SMF>), grd, blk, 0, st, a.ev_start, a.ev_stop, 0, p);
     else
-        spmm_reg_kernel<N, M, B, WD, NWK, PF, CONV><<<grd, blk, 0, st>>>(p);
+        spmm_reg_kernel<N, M, B, WD, NWK, PF, CONV, SMF><<<grd, blk, 0, st>>>(p);
     return hipGetLastError();
+}
+
+template <int N, int M, int B, int WD, int NWK, int PF, int CONV>
+hipError_t launch_reg(const SpmmArgs& a, hipStream_t st) {
+    if constexpr (smf_pattern<N, M>()) {
+        if (a.use_smf) return launch_reg_k<N, M, B, WD, NWK, PF, CONV, true>(a, st);
+    }
+    return launch_reg_k<N, M, B, WD, NWK, PF, CONV, false>(a, st);
 }
 
 // Launch shape: 0 = wide strips, waves own strips; 1 = narrow strips, waves own strips;

@@ -108,11 +108,12 @@ def test_spmm_from_oracle_pack(L):
     check_product(Y, Yref, Aref, crisp.Y_F32, L.name)
 
 
-@pytest.mark.parametrize("shape", [0, 1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("shape", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
 @pytest.mark.parametrize("L", synth.small_cases(), ids=lambda L: L.name)
 def test_every_launch_shape(L, shape):
     """Each launch shape of the product (wide / narrow strips, 4- and 8-way split of the block
-    list, generic LDS-expansion kernel, LDS-resident block-rows with narrow / wide strips) must
+    list, generic LDS-expansion kernel, LDS-resident block-rows with narrow / wide strips, and
+    shapes 0-3 again with the sparse matrix-core instruction where the pattern allows it) must
     give the same result within tolerance."""
     print("case", L.name, "shape", shape, flush=True)
     W, G, X = synth.draw_small(L, 23)
@@ -192,7 +193,7 @@ def test_bf16_output_is_rounded_fp32_output():
         Xp = np.zeros((L.K, ldx), dtype=np.uint16)
         Xp[:, : L.Ncol] = X
         dX = dev(Xp)
-        for shape in (0, 1, 2, 4):
+        for shape in (0, 1, 2, 4, 7, 9):
             y32 = run_spmm(layer, dX, L.Ncol, ldx, crisp.Y_F32, L.S, shape=shape).astype(np.float32)
             y16 = run_spmm(layer, dX, L.Ncol, ldx, crisp.Y_BF16, L.S, shape=shape).astype(np.float32)
             assert (synth.f32_to_bf16_bits(y16) == synth.f32_to_bf16_bits(y32)).all(), (L.name, shape)
@@ -251,7 +252,7 @@ def test_conv_spmm_implicit_lowering(case):
     dX = torch.zeros((L.K, ldx), dtype=torch.int16, device="cuda")
     crisp.crisp_im2col(conv, dact, dX, ldx)
     for yd, tdt in ((crisp.Y_F32, torch.float32), (crisp.Y_BF16, torch.bfloat16)):
-        for shape in (None, 1, 2, 3):
+        for shape in (None, 1, 2, 3, 8, 9, 10):
             Y = torch.full((S + 1, ldy), float("nan"), dtype=tdt, device="cuda")
             crisp.crisp_conv_spmm(layer.desc, conv, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dact, Y,
                                   ldy, yd, ws=None, ws_bytes=0 if shape is None else shape + 1)
