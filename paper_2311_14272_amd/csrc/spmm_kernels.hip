@@ -367,8 +367,9 @@ static int pick_shape(const Geometry& g, int64_t Ncol, int blocks_per_row, bool 
     if (smf) {
         // sparse matrix-core instantiations: no expansion work to share between columns, so narrow
         // strips (more waves) win more often; 2:4 with wide strips is limited to one wave per SIMD
-        if (blocks_per_row <= 1) return wide >= 2048 ? 0 : 1;
-        if (narrow >= 1024) return ((g.n == 1 && blocks_per_row >= 7) || blocks_per_row >= 20) ? 0 : 1;
+        const bool heavy = 8 * g.n / g.m >= 4;   // 2:4
+        if (blocks_per_row <= (heavy ? 1 : 2)) return wide >= 2048 ? 0 : 1;
+        if (narrow >= 1024) return ((!heavy && blocks_per_row >= 7) || blocks_per_row >= 20) ? 0 : 1;
         return (blocks_per_row >= 8 && g.B == 64) ? 2 : 1;
     }
     if (wide >= 4096) return 0;
@@ -388,7 +389,9 @@ static int pick_shape(const Geometry& g, int64_t Ncol, int blocks_per_row, bool 
 // repeated often (long block-rows).
 static bool prefer_lds(const Geometry& g, int64_t Ncol, int blocks_per_row) {
     if (g.B != 64 || blocks_per_row > lds_capacity(g.B)) return false;
-    if (g.m == 4 && g.n <= 2) return false;   // the sparse matrix-core path needs no expansion at all
+    // 1:4 and 2:4 feed the sparse matrix core without any expansion; 1:8 and 2:8 need a little per
+    // block, which the LDS kernels still beat by a few percent on long rows
+    if (g.n <= 2 && (g.m == 4 || blocks_per_row < 12)) return false;
     const int64_t narrow = (int64_t)g.Sb * ((Ncol + 63) / 64);
     const int slots_per_operand = (8 / g.m) * g.n;
     return narrow >= 2048 && (slots_per_operand >= 4 || blocks_per_row >= 6);
@@ -440,7 +443,7 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
     a.use_smf = (force_shape < 0 || (force_shape >= 7 && force_shape <= 10)) ? 1 : 0;
     const int shape = (force_shape >= 0 && force_shape <= 3) ? force_shape
                     : (force_shape >= 7 && force_shape <= 10) ? force_shape - 7
-                    : pick_shape(g, Ncol, bpr, a.use_smf && g.m == 4 && g.n <= 2);
+                    : pick_shape(g, Ncol, bpr, a.use_smf && g.n <= 2);
     // the specialised kernels assume whole 16-row MFMA steps of X (K % 16 == 0) and whole groups
     // of four output columns per lane (Ncol % 4 == 0)
     if (conv || (force_shape != 4 && (g.K % 16) == 0 && (Ncol % 4) == 0 && ldy <= ((int64_t)1 << 23))) {

@@ -196,8 +196,10 @@ __device__ __forceinline__ u32x4 expand_frag(const uint32_t (&v)[Fmt<N, M, B>::V
 // two dense 32x32x16 operands of the step's two 16-deep halves (exactly what the X path builds);
 // two stored values of a group may name the same position when one of them is zero.  For 2:4 the
 // lane's slice of the canonical pack IS the operand: 16 bytes of values and 16 position bits.
+// m = 8 with at most two kept per group also qualifies (any two of eight put at most two into each
+// aligned four): the 8-group's stored values go to the lower or the upper 4-group by position bit 2.
 template <int N, int M>
-constexpr bool smf_pattern() { return M == 4 && N <= 2; }
+constexpr bool smf_pattern() { return N <= 2; }
 
 template <int N, int M, int B, int WD, bool PREFETCH, int CONV, bool SMF = false>
 struct BlockBody {
@@ -331,10 +333,15 @@ struct BlockBody {
                 // one request per 32-deep step: the 2*FS stored values behind the lane's 16 columns
 #pragma unroll
                 for (int s2 = 0; s2 < KS / 2; ++s2) {
-                    uint32_t t[F::VW * 2];
+                    uint32_t t[(2 * F::FS + 1) / 2];
                     load_vals<2 * F::FS>(rv, a_off + (rt * 32 * F::SLOTS + s2 * 4 * F::FS) * 2, vb, t);
+                    if constexpr (F::FS == 1) {
+                        v[rt][2 * s2][0] = t[0] & 0xFFFFu;       // one stored value per 8 columns
+                        v[rt][2 * s2 + 1][0] = t[0] >> 16;
+                    } else {
 #pragma unroll
-                    for (int x = 0; x < F::VW; ++x) { v[rt][2 * s2][x] = t[x]; v[rt][2 * s2 + 1][x] = t[F::VW + x]; }
+                        for (int x = 0; x < F::VW; ++x) { v[rt][2 * s2][x] = t[x]; v[rt][2 * s2 + 1][x] = t[F::VW + x]; }
+                    }
                 }
             } else {
 #pragma unroll
@@ -426,7 +433,35 @@ struct BlockBody {
         for (int rt = 0; rt < RT; ++rt) {
             u32x4 a4;
             uint32_t idx;
-            if constexpr (N == 2) {
+            if constexpr (M == 8) {
+                // the lane's 16 columns are two groups of 8; position bits of both: 2 * HB bits from P
+                uint32_t field = ws[rt][P >> 5] >> (P & 31);
+                if constexpr ((P & 31) + 2 * F::HB > 32 && (P >> 5) + 1 < F::WPR) field |= ws[rt][(P >> 5) + 1] << (32 - (P & 31));
+                if constexpr (N == 2) {
+                    // group g: stored (v0, v1) at positions (p0, p1); the lower 4-group takes those with
+                    // position < 4, the upper the others, both with in-group positions (p0 & 3, p1 & 3)
+                    uint32_t d[4];
+                    idx = 0;
+#pragma unroll
+                    for (int g = 0; g < 2; ++g) {
+                        const uint32_t w = av[rt][2 * s2 + g][0];
+                        const uint32_t p0 = (field >> (6 * g)) & 7u, p1 = (field >> (6 * g + 3)) & 7u;
+                        const uint32_t lowmask = ((p0 & 4u) ? 0u : 0x0000FFFFu) | ((p1 & 4u) ? 0u : 0xFFFF0000u);
+                        d[2 * g] = w & lowmask;
+                        d[2 * g + 1] = w & ~lowmask;
+                        const uint32_t nib = (p0 & 3u) | ((p1 & 3u) << 2);
+                        idx |= (nib | (nib << 4)) << (8 * g);
+                    }
+                    a4 = u32x4{d[0], d[1], d[2], d[3]};
+                } else {
+                    // one stored value per group of 8, paired with a zero at the same position
+                    const uint32_t va = av[rt][2 * s2][0], vb2 = av[rt][2 * s2 + 1][0];
+                    const uint32_t pa = field & 7u, pb = (field >> 3) & 7u;
+                    a4 = u32x4{(pa & 4u) ? 0u : va, (pa & 4u) ? va : 0u, (pb & 4u) ? 0u : vb2, (pb & 4u) ? vb2 : 0u};
+                    const uint32_t na = (pa & 3u) * 5u, nb = (pb & 3u) * 5u;     // (p, p) as a nibble
+                    idx = (na | (na << 4)) | ((nb | (nb << 4)) << 8);
+                }
+            } else if constexpr (N == 2) {
                 // 2:4: values and positions as packed
                 a4 = u32x4{av[rt][2 * s2][0], av[rt][2 * s2][1], av[rt][2 * s2 + 1][0], av[rt][2 * s2 + 1][1]};
                 idx = ws[rt][P >> 5] >> (P & 31);

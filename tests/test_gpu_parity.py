@@ -393,6 +393,15 @@ def test_config_full_size(cid):
                 assert np.isfinite(Y).all()
                 dead = ~sel.mask.any(axis=1)
                 assert (Y[dead] == 0).all()
+            if t["X"] is None:
+                # the path bench.py times for convolution layers: lowering fused into the product
+                tdt = torch.float32 if yd == crisp.Y_F32 else torch.bfloat16
+                Yc = torch.full((L.S, L.Ncol), float("nan"), dtype=tdt, device="cuda")
+                path = crisp.conv_forward(layer, L.conv, dact, Yc, L.Ncol, yd, X_scratch=dX)
+                torch.cuda.synchronize()
+                assert path == "fused", path
+                Yh = Yc.float().cpu().numpy().astype(np.float64)
+                check_product(Yh[:, cols], Yref, Aref, yd, L.name + " fused lowering")
         del dX
         torch.cuda.empty_cache()
 
