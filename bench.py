@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--y-dtype", choices=["bf16", "f32"], default="bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--spmm-only", action="store_true", help="time only the products (selection and packing done once)")
+    ap.add_argument("--per-layer-prune", action="store_true",
+                    help="select+pack layer by layer (crisp_select_pack) instead of one crisp_select_pack_batch call")
     ap.add_argument("--side-streams", action="store_true",
                     help="issue each layer's select+pack on a side stream ordered by events (slower here: the "
                          "cross-stream waits cost more than the overlap gains); default is one stream")
@@ -70,30 +72,44 @@ def resnet50_pass(args):
     gen.manual_seed(wl.seed)
     reps = max(1, min(args.steps, 5))
     rows, t_prune, t_fwd, useful, dense = [], 0.0, 0.0, 0.0, 0.0
+
+    def timed(fn):
+        fn(0)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for r in range(reps):
+            fn(r)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    # weights, gradients and pack buffers of all 53 layers stay resident (about 0.3 GB); the model is
+    # pruned in one crisp_select_pack_batch call, as Alg. 1 does it
+    Wd, Gd, dls = [], [], []
+    for li, L in enumerate(wl.layers):
+        t = synth.draw_layer(wl, li, with_x=False)
+        Wd.append(torch.from_numpy(t["W"].view(np.int16)).to(dev))
+        Gd.append(torch.from_numpy(t["G"]).to(dev))
+        dls.append(crisp.alloc_layer(crisp.layer_desc(L.S, L.K, L.n, L.m, L.B, L.density, L.sal_kind, L.select_mode), dev))
+    if args.per_layer_prune:
+        per_layer_tp = [timed(lambda r, i=i: crisp.prune_and_pack(dls[i], Wd[i], Gd[i])) for i in range(len(dls))]
+        t_prune = sum(per_layer_tp)
+    else:
+        batch = crisp.make_batch(dls, Wd, Gd)
+        t_prune = timed(lambda r: crisp.crisp_select_pack_batch(*batch))
+        per_layer_tp = [None] * len(dls)
+
     for li, L in enumerate(wl.layers):
         cv = L.conv
-        t = synth.draw_layer(wl, li, with_x=False)
-        W = torch.from_numpy(t["W"].view(np.int16)).to(dev)
-        G = torch.from_numpy(t["G"]).to(dev)
-        desc = crisp.layer_desc(L.S, L.K, L.n, L.m, L.B, L.density, L.sal_kind, L.select_mode)
-        dl = crisp.alloc_layer(desc, dev)
+        W, G, dl = Wd[li], Gd[li], dls[li]
         nbuf = 2
         acts = [torch.randn((cv.C, cv.batch, cv.H, cv.W), generator=gen, device=dev).clamp_(min=0).to(torch.bfloat16).view(torch.int16)
                 for _ in range(nbuf)]
         Ys = [torch.empty((L.S, L.Ncol), dtype=ytorch, device=dev) for _ in range(nbuf)]
         Xs = torch.empty((L.K, L.Ncol), dtype=torch.int16, device=dev) if crisp.conv_needs_scratch(cv, L.B, L.n, L.m, L.S) else None
 
-        def timed(fn):
-            fn(0)
-            torch.cuda.synchronize()
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            for r in range(reps):
-                fn(r)
-            b.record()
-            torch.cuda.synchronize()
-            return a.elapsed_time(b) / reps
-        tp = timed(lambda r: crisp.prune_and_pack(dl, W, G))
+        tp = per_layer_tp[li]
         path = [None]
 
         def fwd(r):
@@ -109,13 +125,12 @@ def resnet50_pass(args):
                        for bi in range(sz.Sb) for bj in ci[rp[bi]:rp[bi + 1]])
         uf = 2.0 * ones * L.Ncol
         rows.append(dict(name=L.name, S=L.S, K=L.K, Ncol=L.Ncol, nm="%d:%d" % (L.n, L.m), density=round(L.density, 3),
-                         k_row=sz.k_row, lowering=path[0], prune_pack_ms=round(tp, 4), forward_ms=round(tf, 4),
+                         k_row=sz.k_row, lowering=path[0], prune_pack_ms=(round(tp, 4) if tp is not None else None), forward_ms=round(tf, 4),
                          useful_tflops_forward=round(uf / (tf * 1e-3) / 1e12, 2)))
-        t_prune += tp
         t_fwd += tf
         useful += uf
         dense += 2.0 * L.S * L.K * L.Ncol
-        del acts, Ys, Xs, dl, W, G
+        del acts, Ys, Xs
         torch.cuda.empty_cache()
     total = t_prune + t_fwd
     out = {"metric": "effective TFLOP/s (nonzero FLOPs) of hybrid-sparse GEMM + % roofline",
@@ -124,7 +139,7 @@ def resnet50_pass(args):
            "dtype": "bf16", "data": "synthetic",
            "config": {"workload": "c5: ResNet-50, 53 convs as GEMMs, batch 256, 224x224, layer-wise inputs, B=64, "
                                   "per-layer n:m and block density drawn from the workload seed",
-                      "step": "per layer: select+pack on device (crisp_select_pack), lowering (fused, im2col or none), product; summed",
+                      "step": ("select+pack layer by layer (crisp_select_pack)" if args.per_layer_prune else "select+pack of all layers in one crisp_select_pack_batch call") + "; then per layer: lowering (fused, im2col or none) and product; summed",
                       "y_dtype": args.y_dtype},
            "select_pack_ms": round(t_prune, 3), "forward_ms": round(t_fwd, 3),
            "useful_tflops_forward_only": round(useful / (t_fwd * 1e-3) / 1e12, 2),
@@ -287,11 +302,16 @@ def main():
     pdone = [None] * len(layers)                            # select+pack of layer i finished (side stream)
     fdone = [None] * len(layers)                            # product of layer i finished (main stream)
 
+    batch = crisp.make_batch([st.dl for st in layers], [st.W for st in layers], [st.G for st in layers])
+
     def step(k, dom=None, events=None):
         s = k % nsets
         if not args.side_streams or args.spmm_only:
+            # all layers are pruned in one call (the method prunes a model in one shot), then the products
+            if not args.spmm_only and not args.per_layer_prune:
+                crisp.crisp_select_pack_batch(*batch)
             for i, st in enumerate(layers):
-                if not args.spmm_only:
+                if not args.spmm_only and args.per_layer_prune:
                     prune(st)
                 forward(st, s, events if i == dom else None)
             return
@@ -421,7 +441,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s: %s" % (wl.name, ", ".join("%s %dx%dx%d %s B%d k_row %d" % (
             x["name"], x["S"], x["K"], x["Ncol"], x["nm"], x["B"], x["k_row"]) for x in info)),
-                   "step": ("select+pack (crisp_select_pack)+" if not args.spmm_only else "") + ("im2col+spmm" if args.explicit_im2col else "spmm with the 3x3 layer's lowering fused (crisp_conv_spmm)") + " per layer",
+                   "step": (("select+pack of all layers (crisp_select_pack_batch), then " if not args.per_layer_prune else "select+pack (crisp_select_pack)+") if not args.spmm_only else "") + ("im2col+spmm" if args.explicit_im2col else "spmm with the 3x3 layer's lowering fused (crisp_conv_spmm)") + " per layer",
                    "y_dtype": args.y_dtype, "x_layout": "KN", "input_sets": nsets,
                    "streams": "one" if (not args.side_streams or args.spmm_only) else "select+pack of each layer on its own side stream, products on the main stream"},
         "dense_equivalent_tflops": round(dense_eq / (ms_per_step * 1e-3) / 1e12, 3),

@@ -171,6 +171,33 @@ CRISP_API crisp_status crisp_select_pack(const crisp_layer_desc *desc, const uin
                                double *block_score, uint16_t *vals, uint32_t *idx_words,
                                int32_t *flags, void *ws, size_t ws_bytes, void *stream);
 
+/* The buffers of one layer for crisp_select_pack_batch: the arguments of crisp_select_pack. */
+typedef struct {
+    const uint16_t *W;
+    const float *T_or_G;
+    uint32_t *nm_mask;
+    int32_t *row_ptr;
+    int32_t *col_idx;
+    double *block_score;       /* optional */
+    uint16_t *vals;
+    uint32_t *idx_words;
+    int32_t *flags;
+    void *ws;                  /* select_pack_ws_bytes of this layer */
+    size_t ws_bytes;
+} crisp_layer_buffers;
+
+/*
+ * crisp_select_pack for n_layers layers at once (Alg. 1 prunes all layers of a model in one
+ * shot): layers that use the same kernel instantiation (block size, m, saliency kind, K a
+ * multiple of B or not) share launches, up to 8 layers per launch pair, so that the small block
+ * grids of single layers together fill the GPU.  Results per layer are exactly those of
+ * crisp_select_pack.  descs and bufs are host arrays of n_layers elements (1 <= n_layers <=
+ * 4096); the layers' buffers must not overlap.  All arguments are checked before anything is
+ * enqueued.  Errors: as crisp_select_pack (the first failing layer's status).
+ */
+CRISP_API crisp_status crisp_select_pack_batch(int32_t n_layers, const crisp_layer_desc *descs,
+                                     const crisp_layer_buffers *bufs, void *stream);
+
 /*
  * Convolution lowering (Sec. 3 "Notation": the kernel tensor is reshaped so that
  * the convolution becomes a matrix product).  act is [C][batch][H][W] bf16;

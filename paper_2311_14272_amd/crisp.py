@@ -42,6 +42,12 @@ class ConvDesc(C.Structure):
                 ("x_layout", C.c_int32)]
 
 
+class LayerBuffers(C.Structure):
+    _fields_ = [("W", C.c_void_p), ("T_or_G", C.c_void_p), ("nm_mask", C.c_void_p), ("row_ptr", C.c_void_p),
+                ("col_idx", C.c_void_p), ("block_score", C.c_void_p), ("vals", C.c_void_p), ("idx_words", C.c_void_p),
+                ("flags", C.c_void_p), ("ws", C.c_void_p), ("ws_bytes", C.c_size_t)]
+
+
 class CrispError(RuntimeError):
     def __init__(self, fn: str, status: int):
         self.status = status
@@ -66,6 +72,7 @@ def lib():
         L.crisp_select_mask.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.crisp_pack.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.crisp_select_pack.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.crisp_select_pack_batch.argtypes = [C.c_int32, C.POINTER(LayerDesc), C.POINTER(LayerBuffers), vp]
         L.crisp_im2col.argtypes = [C.POINTER(ConvDesc), vp, vp, C.c_int64, vp]
         L.crisp_spmm.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp, vp, C.c_int64, C.c_int64, C.c_int32, vp,
                                  C.c_int64, C.c_int32, vp, C.c_size_t, vp]
@@ -74,7 +81,8 @@ def lib():
         L.crisp_spmm_timed.argtypes = [C.POINTER(LayerDesc), C.POINTER(ConvDesc), vp, vp, vp, vp, vp, C.c_int64,
                                        C.c_int64, vp, C.c_int64, C.c_int32, vp, vp, vp]
         L.crisp_global_budget.argtypes = [C.c_int32, vp, vp, C.c_double, vp, vp, vp, C.c_size_t, vp]
-        for f in (L.crisp_pack_sizes, L.crisp_select_mask, L.crisp_pack, L.crisp_select_pack, L.crisp_im2col, L.crisp_spmm,
+        for f in (L.crisp_pack_sizes, L.crisp_select_mask, L.crisp_pack, L.crisp_select_pack, L.crisp_select_pack_batch,
+                  L.crisp_im2col, L.crisp_spmm,
                   L.crisp_conv_spmm, L.crisp_spmm_timed, L.crisp_global_budget):
             f.restype = C.c_int32
         _lib = L
@@ -131,6 +139,13 @@ def crisp_select_pack(desc, W, T_or_G, nm_mask, row_ptr, col_idx, vals, idx_word
                                  _stream() if stream == -1 else stream)
     if st != OK:
         raise CrispError("crisp_select_pack", st)
+
+
+def crisp_select_pack_batch(descs, buffers, stream=-1):
+    """descs: ctypes array of LayerDesc, buffers: ctypes array of LayerBuffers (see make_batch)."""
+    st = lib().crisp_select_pack_batch(len(descs), descs, buffers, _stream() if stream == -1 else stream)
+    if st != OK:
+        raise CrispError("crisp_select_pack_batch", st)
 
 
 def crisp_im2col(conv: ConvDesc, act, X, ldx, stream=-1):
@@ -248,6 +263,23 @@ def prune_and_pack(layer: DeviceLayer, W, T_or_G=None, fused=True):
         return
     crisp_select_mask(layer.desc, W, T_or_G, layer.nm_mask, layer.row_ptr, layer.col_idx, layer.score)
     crisp_pack(layer.desc, W, layer.nm_mask, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, layer.flags)
+
+
+def make_batch(layers, Ws, TGs):
+    """Argument arrays of crisp_select_pack_batch for DeviceLayers and their weight / saliency tensors
+    (built once; the arrays hold raw device pointers, so the tensors must stay alive)."""
+    import torch
+    n = len(layers)
+    descs = (LayerDesc * n)()
+    bufs = (LayerBuffers * n)()
+    for i, (layer, W, TG) in enumerate(zip(layers, Ws, TGs)):
+        if layer.ws is None:
+            layer.ws = torch.empty(max(16, layer.sizes.select_pack_ws_bytes), dtype=torch.uint8, device=W.device)
+        descs[i] = layer.desc
+        bufs[i] = LayerBuffers(_ptr(W), _ptr(TG), _ptr(layer.nm_mask), _ptr(layer.row_ptr), _ptr(layer.col_idx),
+                               _ptr(layer.score), _ptr(layer.vals), _ptr(layer.idx_words), _ptr(layer.flags),
+                               _ptr(layer.ws), layer.ws.numel())
+    return descs, bufs
 
 
 def conv_desc_of(cv) -> ConvDesc:

@@ -1,4 +1,6 @@
 // C ABI of libcrisp: argument validation on the host, size queries, dispatch to the launchers.
+#include <vector>
+
 #include "crisp_internal.h"
 
 #include <cmath>
@@ -129,36 +131,81 @@ crisp_status crisp_pack(const crisp_layer_desc* desc, const uint16_t* W, const u
     return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
 }
 
+// Argument checks of one layer of crisp_select_pack / crisp_select_pack_batch (host only).
+static crisp_status check_select_pack(const crisp_layer_desc* desc, const crisp_layer_buffers* b, Geometry* g) {
+    crisp_status st = make_geometry(desc, true, g);
+    if (st != CRISP_OK) return st;
+    if (!b->W || !b->nm_mask || !b->row_ptr || !b->col_idx || !b->vals || !b->idx_words || !b->flags) return CRISP_EINVAL;
+    if (desc->sal_kind != CRISP_SAL_MAG && !b->T_or_G) return CRISP_EINVAL;
+    if (misaligned(b->W, 16) || misaligned(b->T_or_G, 16) || misaligned(b->nm_mask, 16) || misaligned(b->row_ptr, 4) ||
+        misaligned(b->col_idx, 4) || misaligned(b->block_score, 8) || misaligned(b->vals, 16) ||
+        misaligned(b->idx_words, 16) || misaligned(b->flags, 4) || misaligned(b->ws, 16))
+        return CRISP_EALIGN;
+    const size_t score_bytes = ((size_t)g->Sb * g->Kb * sizeof(double) + 15) / 16 * 16;
+    if (!b->ws || b->ws_bytes < score_bytes + select_pack_stage_bytes(*g)) return CRISP_EBUFSIZE;
+    if (g->Kb > 4096) return CRISP_EUNSUPPORTED;
+    if (desc->select_mode == CRISP_LAYER_TOPK && ((int64_t)g->Sb * g->Kb > 8192 || g->Sb > 1024)) return CRISP_EUNSUPPORTED;
+    return CRISP_OK;
+}
+
+crisp_status crisp_select_pack_batch(int32_t n_layers, const crisp_layer_desc* descs, const crisp_layer_buffers* bufs,
+                                     void* stream) {
+    if (n_layers < 1 || n_layers > 4096 || !descs || !bufs) return CRISP_EINVAL;
+    std::vector<Geometry> geo((size_t)n_layers);
+    for (int i = 0; i < n_layers; ++i) {       // everything is checked before anything is enqueued
+        crisp_status st = check_select_pack(&descs[i], &bufs[i], &geo[i]);
+        if (st != CRISP_OK) return st;
+    }
+    std::vector<char> done((size_t)n_layers, 0);
+    hipError_t e = hipSuccess;
+    for (int i = 0; i < n_layers && e == hipSuccess; ++i) {
+        if (done[i]) continue;
+        const Geometry& g = geo[i];
+        const size_t score_bytes = ((size_t)g.Sb * g.Kb * sizeof(double) + 15) / 16 * 16;
+        double* score = bufs[i].block_score ? bufs[i].block_score : (double*)bufs[i].ws;
+        if (!select_pack_fusable(g, descs[i].select_mode)) {
+            // uneven rows or very wide grids: the two steps one after the other
+            done[i] = 1;
+            e = launch_select(g, descs[i].sal_kind, descs[i].select_mode, bufs[i].W, bufs[i].T_or_G, bufs[i].nm_mask,
+                              bufs[i].row_ptr, bufs[i].col_idx, bufs[i].block_score, score, (hipStream_t)stream);
+            if (e == hipSuccess)
+                e = launch_pack(g, descs[i].select_mode, bufs[i].W, bufs[i].nm_mask, bufs[i].row_ptr, bufs[i].col_idx,
+                                bufs[i].vals, bufs[i].idx_words, bufs[i].flags, (hipStream_t)stream);
+            continue;
+        }
+        // this layer and the later ones of the same kernel instantiation, CRISP_SELECT_BATCH per launch pair
+        Geometry gg[CRISP_SELECT_BATCH];
+        SelPackPtrs pp[CRISP_SELECT_BATCH];
+        int cnt = 0;
+        int64_t blocks = 0;
+        for (int j = i; j < n_layers && cnt < CRISP_SELECT_BATCH; ++j) {
+            const Geometry& h = geo[j];
+            if (done[j] || !select_pack_fusable(h, descs[j].select_mode)) continue;
+            if (h.B != g.B || h.m != g.m || descs[j].sal_kind != descs[i].sal_kind || (h.K % h.B == 0) != (g.K % g.B == 0))
+                continue;
+            if (blocks + (int64_t)h.Sb * h.Kb > (1 << 30)) break;
+            blocks += (int64_t)h.Sb * h.Kb;
+            const size_t sb = ((size_t)h.Sb * h.Kb * sizeof(double) + 15) / 16 * 16;
+            gg[cnt] = h;
+            pp[cnt] = SelPackPtrs{bufs[j].W, bufs[j].T_or_G, bufs[j].nm_mask, bufs[j].row_ptr, bufs[j].col_idx,
+                                  bufs[j].block_score ? bufs[j].block_score : (double*)bufs[j].ws, bufs[j].vals,
+                                  bufs[j].idx_words, bufs[j].flags, (unsigned char*)bufs[j].ws + sb};
+            done[j] = 1;
+            ++cnt;
+        }
+        (void)score_bytes;
+        e = launch_select_pack_batch(cnt, gg, descs[i].sal_kind, pp, (hipStream_t)stream);
+    }
+    return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
+}
+
 crisp_status crisp_select_pack(const crisp_layer_desc* desc, const uint16_t* W, const float* T_or_G,
                                uint32_t* nm_mask, int32_t* row_ptr, int32_t* col_idx, double* block_score,
                                uint16_t* vals, uint32_t* idx_words, int32_t* flags, void* ws, size_t ws_bytes,
                                void* stream) {
-    Geometry g;
-    crisp_status st = make_geometry(desc, true, &g);
-    if (st != CRISP_OK) return st;
-    if (!W || !nm_mask || !row_ptr || !col_idx || !vals || !idx_words || !flags) return CRISP_EINVAL;
-    if (desc->sal_kind != CRISP_SAL_MAG && !T_or_G) return CRISP_EINVAL;
-    if (misaligned(W, 16) || misaligned(T_or_G, 16) || misaligned(nm_mask, 16) || misaligned(row_ptr, 4) ||
-        misaligned(col_idx, 4) || misaligned(block_score, 8) || misaligned(vals, 16) || misaligned(idx_words, 16) ||
-        misaligned(flags, 4) || misaligned(ws, 16))
-        return CRISP_EALIGN;
-    const size_t score_bytes = ((size_t)g.Sb * g.Kb * sizeof(double) + 15) / 16 * 16;
-    if (!ws || ws_bytes < score_bytes + select_pack_stage_bytes(g)) return CRISP_EBUFSIZE;
-    if (g.Kb > 4096) return CRISP_EUNSUPPORTED;
-    if (desc->select_mode == CRISP_LAYER_TOPK && ((int64_t)g.Sb * g.Kb > 8192 || g.Sb > 1024)) return CRISP_EUNSUPPORTED;
-    double* score = block_score ? block_score : (double*)ws;
-    hipError_t e;
-    if (select_pack_fusable(g, desc->select_mode)) {
-        e = launch_select_pack(g, desc->sal_kind, W, T_or_G, nm_mask, row_ptr, col_idx, score, vals, idx_words, flags,
-                               (unsigned char*)ws + score_bytes, (hipStream_t)stream);
-    } else {
-        // uneven rows or very wide grids: the two steps one after the other
-        e = launch_select(g, desc->sal_kind, desc->select_mode, W, T_or_G, nm_mask, row_ptr, col_idx, block_score, score,
-                          (hipStream_t)stream);
-        if (e == hipSuccess)
-            e = launch_pack(g, desc->select_mode, W, nm_mask, row_ptr, col_idx, vals, idx_words, flags, (hipStream_t)stream);
-    }
-    return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
+    if (!desc) return CRISP_EINVAL;
+    const crisp_layer_buffers b = {W, T_or_G, nm_mask, row_ptr, col_idx, block_score, vals, idx_words, flags, ws, ws_bytes};
+    return crisp_select_pack_batch(1, desc, &b, stream);
 }
 
 crisp_status crisp_im2col(const crisp_conv_desc* c, const uint16_t* act, uint16_t* X, int64_t ldx, void* stream) {

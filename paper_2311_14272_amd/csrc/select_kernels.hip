@@ -29,12 +29,32 @@ __device__ __forceinline__ float saliency_of(uint16_t w, float tg) {
 // values, position stream, 2-of-4 violation) is also written, to a staging area indexed by the
 // block's place in the grid; whether the block is kept is only known after the block choice,
 // which then just copies the kept blocks' packed forms to their final place (topk_gather_kernel).
-struct StageArgs {
-    int wbits, slots, wpr;      // bits per position, packed slots and position words per block row
-    uint16_t* vals;             // [Sb*Kb][B][slots]
-    uint32_t* idxw;             // [Sb*Kb][B][wpr]
-    int32_t* viol;              // [Sb*Kb]: an aligned group of four holds more than two kept elements
-    int32_t* flags;             // the layer's flags; preset here, cleared by topk_gather_kernel
+// Up to SEL_BATCH layers of equal (B, m, saliency kind, alignment class) share one launch: a
+// model's layers have block grids of a few dozen to a few hundred workgroups each, far too few to
+// fill 256 compute units one layer at a time.  Workgroup ids are mapped to (layer, block) through
+// the prefix sums in `first`.
+#define SEL_BATCH CRISP_SELECT_BATCH
+struct SelLayer {
+    int S, K, n, Kb, Sb, mwpr, k_row, clear_flag;
+    int wbits, slots, wpr, pad_;  // bits per position, packed slots and position words per block row
+    const uint16_t* W;
+    const float* TG;
+    uint32_t* nm_mask;
+    double* score;
+    uint16_t* st_vals;            // staging [Sb*Kb][B][slots]
+    uint32_t* st_idxw;            // staging [Sb*Kb][B][wpr]
+    int32_t* st_viol;             // staging [Sb*Kb]: an aligned group of four holds more than two kept
+    int32_t* flags;               // the layer's flags; preset by the scoring kernel, cleared by the gather
+    int32_t* row_ptr;
+    int32_t* col_idx;
+    uint16_t* vals;
+    uint32_t* idxw;
+};
+struct SelBatch {
+    int n;
+    int first[SEL_BATCH + 1];     // first workgroup of each layer in the scoring launch (blocks of the grid)
+    int firstk[SEL_BATCH + 1];    // first workgroup of each layer in the gather launch (kept blocks)
+    SelLayer L[SEL_BATCH];
 };
 
 __device__ __forceinline__ uint32_t slot_position_of(uint32_t bits, int j, bool outside) {
@@ -45,11 +65,16 @@ __device__ __forceinline__ uint32_t slot_position_of(uint32_t bits, int j, bool 
 }
 
 template <int B, int M, int KIND, bool VEC, bool PACK>
-__global__ __launch_bounds__(B * (B / 16)) void score_select_kernel(int S, int K, int n, int Kb, int mwpr,
-                                                                   const uint16_t* __restrict__ W,
-                                                                   const float* __restrict__ TG,
-                                                                   uint32_t* __restrict__ nm_mask,
-                                                                   double* __restrict__ score, StageArgs sa) {
+__global__ __launch_bounds__(B * (B / 16)) void score_select_kernel(SelBatch bt) {
+    int li = 0;
+#pragma unroll
+    for (int i = 1; i < SEL_BATCH; ++i) li += (i < bt.n && (int)blockIdx.x >= bt.first[i]);
+    const SelLayer& sa = bt.L[li];
+    const int S = sa.S, K = sa.K, n = sa.n, Kb = sa.Kb, mwpr = sa.mwpr;
+    const uint16_t* __restrict__ W = sa.W;
+    const float* __restrict__ TG = sa.TG;
+    uint32_t* __restrict__ nm_mask = sa.nm_mask;
+    double* __restrict__ score = sa.score;
     constexpr int CPT = 16;          // columns per lane
     constexpr int Q = B / CPT;       // lanes per block row (1, 2 or 4)
     constexpr int LDT = B + 4;       // padded LDS row stride in floats (keeps 16-byte alignment)
@@ -59,7 +84,8 @@ __global__ __launch_bounds__(B * (B / 16)) void score_select_kernel(int S, int K
     __shared__ double rowsum[B];
     __shared__ uint32_t pos_lds[PACK ? B * WMAX : 1];
     __shared__ int viol_lds;
-    const int bj = blockIdx.x, bi = blockIdx.y;
+    const int local = (int)blockIdx.x - bt.first[li];
+    const int bi = local / Kb, bj = local - bi * Kb;
     const int r = threadIdx.x / Q, q = threadIdx.x % Q;
     const int s = bi * B + r;
     const int c0 = q * CPT;                      // first column of this lane inside the block
@@ -137,7 +163,7 @@ __global__ __launch_bounds__(B * (B / 16)) void score_select_kernel(int S, int K
             }
             const size_t blk = (size_t)bi * Kb + bj;
             const int slot0 = (c0 / M) * n;
-            uint16_t* sv = sa.vals + (blk * B + r) * sa.slots + slot0;
+            uint16_t* sv = sa.st_vals + (blk * B + r) * sa.slots + slot0;
             uint64_t stream = 0;                 // at most 16 slots x 3 bits
             int nb = 0;
             bool violates = false;
@@ -215,10 +241,10 @@ __global__ __launch_bounds__(B * (B / 16)) void score_select_kernel(int S, int K
 #pragma unroll
         for (int i = 0; i < B; ++i) total = __dadd_rn(total, part[i]);
         score[(size_t)bi * Kb + bj] = total;
-        if constexpr (PACK) sa.viol[(size_t)bi * Kb + bj] = viol_lds;
+        if constexpr (PACK) sa.st_viol[(size_t)bi * Kb + bj] = viol_lds;
     }
     if constexpr (PACK) {
-        uint32_t* dst = sa.idxw + ((size_t)bi * Kb + bj) * B * sa.wpr;
+        uint32_t* dst = sa.st_idxw + ((size_t)bi * Kb + bj) * B * sa.wpr;
         for (int e = threadIdx.x; e < B * sa.wpr; e += NTHR) dst[e] = pos_lds[(e / sa.wpr) * WMAX + e % sa.wpr];
     }
 }
@@ -305,35 +331,49 @@ __global__ __launch_bounds__(1024) void block_topk_layer_kernel(int Sb, int Kb, 
     for (int bi = wave; bi < Sb; bi += 16) wave_compact(kept + bi * Kb, Kb, col_idx + rowcnt[bi], lane);
 }
 
-template <int B, int M, int KIND, bool PACK>
-static void launch_score_select(const Geometry& g, const uint16_t* W, const float* TG, uint32_t* nm_mask,
-                                double* score, const StageArgs& sa, hipStream_t st) {
-    const dim3 grd(g.Kb, g.Sb);
-    if (g.K % B == 0)
-        score_select_kernel<B, M, KIND, true, PACK><<<grd, B * (B / 16), 0, st>>>(g.S, g.K, g.n, g.Kb, g.mwpr, W, TG, nm_mask, score, sa);
-    else
-        score_select_kernel<B, M, KIND, false, PACK><<<grd, B * (B / 16), 0, st>>>(g.S, g.K, g.n, g.Kb, g.mwpr, W, TG, nm_mask, score, sa);
-}
-
+// One launch of the scoring kernel for a batch whose layers share (B, m, kind, vec).
 template <int KIND, bool PACK>
-static void launch_score_select_bm(const Geometry& g, const uint16_t* W, const float* TG, uint32_t* nm_mask,
-                                   double* score, const StageArgs& sa, hipStream_t st) {
-    const int key = g.B * 16 + g.m;
-    switch (key) {
-        case 64 * 16 + 4: launch_score_select<64, 4, KIND, PACK>(g, W, TG, nm_mask, score, sa, st); break;
-        case 64 * 16 + 8: launch_score_select<64, 8, KIND, PACK>(g, W, TG, nm_mask, score, sa, st); break;
-        case 32 * 16 + 4: launch_score_select<32, 4, KIND, PACK>(g, W, TG, nm_mask, score, sa, st); break;
-        case 32 * 16 + 8: launch_score_select<32, 8, KIND, PACK>(g, W, TG, nm_mask, score, sa, st); break;
-        case 16 * 16 + 4: launch_score_select<16, 4, KIND, PACK>(g, W, TG, nm_mask, score, sa, st); break;
-        default: launch_score_select<16, 8, KIND, PACK>(g, W, TG, nm_mask, score, sa, st); break;
+static void launch_score_batch(int B, int m, bool vec, const SelBatch& bt, hipStream_t st) {
+    const unsigned grid = (unsigned)bt.first[bt.n];
+    if (grid == 0) return;
+#define CRISP_SCORE_CASE(BB, MM)                                                                       \
+    if (vec) score_select_kernel<BB, MM, KIND, true, PACK><<<grid, BB * (BB / 16), 0, st>>>(bt);          \
+    else score_select_kernel<BB, MM, KIND, false, PACK><<<grid, BB * (BB / 16), 0, st>>>(bt);
+    switch (B * 16 + m) {
+        case 64 * 16 + 4: CRISP_SCORE_CASE(64, 4) break;
+        case 64 * 16 + 8: CRISP_SCORE_CASE(64, 8) break;
+        case 32 * 16 + 4: CRISP_SCORE_CASE(32, 4) break;
+        case 32 * 16 + 8: CRISP_SCORE_CASE(32, 8) break;
+        case 16 * 16 + 4: CRISP_SCORE_CASE(16, 4) break;
+        default: CRISP_SCORE_CASE(16, 8) break;
     }
+#undef CRISP_SCORE_CASE
 }
 
-template <int KIND>
-static hipError_t launch_select_kind(const Geometry& g, int select_mode, const uint16_t* W, const float* TG,
-                                     uint32_t* nm_mask, int32_t* row_ptr, int32_t* col_idx, double* score,
-                                     hipStream_t st) {
-    launch_score_select_bm<KIND, false>(g, W, TG, nm_mask, score, StageArgs{}, st);
+template <bool PACK>
+static void launch_score_kind(int sal_kind, int B, int m, bool vec, const SelBatch& bt, hipStream_t st) {
+    if (sal_kind == CRISP_SAL_GIVEN) launch_score_batch<CRISP_SAL_GIVEN, PACK>(B, m, vec, bt, st);
+    else if (sal_kind == CRISP_SAL_GRAD) launch_score_batch<CRISP_SAL_GRAD, PACK>(B, m, vec, bt, st);
+    else launch_score_batch<CRISP_SAL_MAG, PACK>(B, m, vec, bt, st);
+}
+
+static SelLayer sel_layer_of(const Geometry& g, const uint16_t* W, const float* TG, uint32_t* nm_mask, double* score) {
+    SelLayer L = {};
+    L.S = g.S; L.K = g.K; L.n = g.n; L.Kb = g.Kb; L.Sb = g.Sb; L.mwpr = g.mwpr; L.k_row = g.k_row;
+    L.wbits = g.w; L.slots = g.slots; L.wpr = g.wpr;
+    L.W = W; L.TG = TG; L.nm_mask = nm_mask; L.score = score;
+    return L;
+}
+
+hipError_t launch_select(const Geometry& g, int sal_kind, int select_mode, const uint16_t* W, const float* TG,
+                         uint32_t* nm_mask, int32_t* row_ptr, int32_t* col_idx, double* score_out, double* score,
+                         hipStream_t st) {
+    (void)score_out;
+    SelBatch bt = {};
+    bt.n = 1;
+    bt.L[0] = sel_layer_of(g, W, TG, nm_mask, score);
+    bt.first[1] = g.Sb * g.Kb;
+    launch_score_kind<false>(sal_kind, g.B, g.m, g.K % g.B == 0, bt, st);
     if (select_mode == CRISP_ROW_UNIFORM)
         block_topk_rows_kernel<<<g.Sb, 256, 0, st>>>(g.Sb, g.Kb, g.k_row, score, row_ptr, col_idx);
     else
@@ -341,35 +381,25 @@ static hipError_t launch_select_kind(const Geometry& g, int select_mode, const u
     return hipGetLastError();
 }
 
-hipError_t launch_select(const Geometry& g, int sal_kind, int select_mode, const uint16_t* W, const float* TG,
-                         uint32_t* nm_mask, int32_t* row_ptr, int32_t* col_idx, double* score_out, double* score,
-                         hipStream_t st) {
-    (void)score_out;
-    if (sal_kind == CRISP_SAL_GIVEN)
-        return launch_select_kind<CRISP_SAL_GIVEN>(g, select_mode, W, TG, nm_mask, row_ptr, col_idx, score, st);
-    if (sal_kind == CRISP_SAL_GRAD)
-        return launch_select_kind<CRISP_SAL_GRAD>(g, select_mode, W, TG, nm_mask, row_ptr, col_idx, score, st);
-    return launch_select_kind<CRISP_SAL_MAG>(g, select_mode, W, TG, nm_mask, row_ptr, col_idx, score, st);
-}
-
-// Second half of the fused select + pack (uniform rows): workgroup (t, bi) works out the block
-// choice of block-row bi on its own (k_row blocks first under score descending, column ascending;
-// the Kb scores are few, so doing this once per kept block costs less than a launch), takes the
-// t-th kept column in ascending order and copies that block's packed form from the staging area to
-// its final place.  Results are identical to crisp_select_mask followed by crisp_pack.
-__global__ __launch_bounds__(256) void topk_gather_kernel(int Sb, int Kb, int k_row, int vbytes, int ibytes,
-                                                          int clear_flag, const double* __restrict__ score,
-                                                          const uint16_t* __restrict__ st_vals,
-                                                          const uint32_t* __restrict__ st_idxw,
-                                                          const int32_t* __restrict__ st_viol,
-                                                          int32_t* __restrict__ row_ptr, int32_t* __restrict__ col_idx,
-                                                          uint16_t* __restrict__ vals, uint32_t* __restrict__ idxw,
-                                                          int32_t* __restrict__ flags) {
+// Second half of the fused select + pack (uniform rows): the workgroup of kept block (bi, t)
+// works out the block choice of block-row bi on its own (k_row blocks first under score
+// descending, column ascending; the Kb scores are few, so doing this once per kept block costs
+// less than a launch), takes the t-th kept column in ascending order and copies that block's
+// packed form from the staging area to its final place.  Results are identical to
+// crisp_select_mask followed by crisp_pack.
+__global__ __launch_bounds__(256) void topk_gather_kernel(SelBatch bt, int B) {
     __shared__ double sc[512];
     __shared__ uint8_t kept[512];
     __shared__ int sel;
-    const int t = blockIdx.x, bi = blockIdx.y, tid = threadIdx.x;
-    for (int j = tid; j < Kb; j += 256) sc[j] = score[(size_t)bi * Kb + j];
+    int li = 0;
+#pragma unroll
+    for (int i = 1; i < SEL_BATCH; ++i) li += (i < bt.n && (int)blockIdx.x >= bt.firstk[i]);
+    const SelLayer& L = bt.L[li];
+    const int local = (int)blockIdx.x - bt.firstk[li];
+    const int Kb = L.Kb, k_row = L.k_row, Sb = L.Sb;
+    const int bi = local / k_row, t = local - bi * k_row, tid = threadIdx.x;
+    const int vbytes = B * L.slots * 2, ibytes = B * L.wpr * 4;
+    for (int j = tid; j < Kb; j += 256) sc[j] = L.score[(size_t)bi * Kb + j];
     __syncthreads();
     for (int j = tid; j < Kb; j += 256) {
         const double mine = sc[j];
@@ -388,19 +418,19 @@ __global__ __launch_bounds__(256) void topk_gather_kernel(int Sb, int Kb, int k_
     __syncthreads();
     const int bj = sel;
     const size_t src = (size_t)bi * Kb + bj, dst = (size_t)bi * k_row + t;
-    const u32x4* sv = reinterpret_cast<const u32x4*>(reinterpret_cast<const unsigned char*>(st_vals) + src * vbytes);
-    u32x4* dv = reinterpret_cast<u32x4*>(reinterpret_cast<unsigned char*>(vals) + dst * vbytes);
+    const u32x4* sv = reinterpret_cast<const u32x4*>(reinterpret_cast<const unsigned char*>(L.st_vals) + src * vbytes);
+    u32x4* dv = reinterpret_cast<u32x4*>(reinterpret_cast<unsigned char*>(L.vals) + dst * vbytes);
     for (int e = tid; e < vbytes / 16; e += 256) dv[e] = sv[e];
-    const u32x4* si = reinterpret_cast<const u32x4*>(reinterpret_cast<const unsigned char*>(st_idxw) + src * ibytes);
-    u32x4* di = reinterpret_cast<u32x4*>(reinterpret_cast<unsigned char*>(idxw) + dst * ibytes);
+    const u32x4* si = reinterpret_cast<const u32x4*>(reinterpret_cast<const unsigned char*>(L.st_idxw) + src * ibytes);
+    u32x4* di = reinterpret_cast<u32x4*>(reinterpret_cast<unsigned char*>(L.idxw) + dst * ibytes);
     for (int e = tid; e < ibytes / 16; e += 256) di[e] = si[e];
     if (tid == 0) {
-        col_idx[dst] = bj;
+        L.col_idx[dst] = bj;
         if (t == 0) {
-            row_ptr[bi] = bi * k_row;
-            if (bi == Sb - 1) row_ptr[Sb] = Sb * k_row;
+            L.row_ptr[bi] = bi * k_row;
+            if (bi == Sb - 1) L.row_ptr[Sb] = Sb * k_row;
         }
-        if (clear_flag && st_viol[src] && flags[0] != 0) atomicAnd(flags, 0);
+        if (L.clear_flag && L.st_viol[src] && L.flags[0] != 0) atomicAnd(L.flags, 0);
     }
 }
 
@@ -414,28 +444,29 @@ size_t select_pack_stage_bytes(const Geometry& g) {
     return viol + blocks * g.B * g.slots * 2 + blocks * g.B * g.wpr * 4;
 }
 
-// Fused selection + packing in two launches.  stage: select_pack_stage_bytes(g) bytes, 16-byte aligned.
-hipError_t launch_select_pack(const Geometry& g, int sal_kind, const uint16_t* W, const float* TG, uint32_t* nm_mask,
-                              int32_t* row_ptr, int32_t* col_idx, double* score, uint16_t* vals, uint32_t* idxw,
-                              int32_t* flags, void* stage, hipStream_t st) {
-    const size_t blocks = (size_t)g.Sb * g.Kb;
-    unsigned char* base = static_cast<unsigned char*>(stage);
-    StageArgs sa;
-    sa.wbits = g.w; sa.slots = g.slots; sa.wpr = g.wpr;
-    sa.viol = reinterpret_cast<int32_t*>(base);
-    base += (blocks * sizeof(int32_t) + 15) / 16 * 16;
-    sa.vals = reinterpret_cast<uint16_t*>(base);
-    base += blocks * g.B * g.slots * 2;
-    sa.idxw = reinterpret_cast<uint32_t*>(base);
-    sa.flags = flags;
-    if (sal_kind == CRISP_SAL_GIVEN) launch_score_select_bm<CRISP_SAL_GIVEN, true>(g, W, TG, nm_mask, score, sa, st);
-    else if (sal_kind == CRISP_SAL_GRAD) launch_score_select_bm<CRISP_SAL_GRAD, true>(g, W, TG, nm_mask, score, sa, st);
-    else launch_score_select_bm<CRISP_SAL_MAG, true>(g, W, TG, nm_mask, score, sa, st);
-    // n <= 2 can never put three kept elements into an aligned group of four
-    const int clear_flag = g.n > 2;
-    topk_gather_kernel<<<dim3(g.k_row, g.Sb), 256, 0, st>>>(g.Sb, g.Kb, g.k_row, g.B * g.slots * 2, g.B * g.wpr * 4,
-                                                           clear_flag, score, sa.vals, sa.idxw, sa.viol, row_ptr,
-                                                           col_idx, vals, idxw, flags);
+// Fused selection + packing of up to SEL_BATCH layers that share (B, m, saliency kind, alignment
+// class) in two launches.  stage[i]: select_pack_stage_bytes(g[i]) bytes, 16-byte aligned.
+hipError_t launch_select_pack_batch(int n, const Geometry* g, int sal_kind, const SelPackPtrs* pp, hipStream_t st) {
+    SelBatch bt = {};
+    bt.n = n;
+    for (int i = 0; i < n; ++i) {
+        const size_t blocks = (size_t)g[i].Sb * g[i].Kb;
+        unsigned char* base = static_cast<unsigned char*>(pp[i].stage);
+        SelLayer L = sel_layer_of(g[i], pp[i].W, pp[i].TG, pp[i].nm_mask, pp[i].score);
+        L.st_viol = reinterpret_cast<int32_t*>(base);
+        base += (blocks * sizeof(int32_t) + 15) / 16 * 16;
+        L.st_vals = reinterpret_cast<uint16_t*>(base);
+        base += blocks * g[i].B * g[i].slots * 2;
+        L.st_idxw = reinterpret_cast<uint32_t*>(base);
+        L.flags = pp[i].flags; L.row_ptr = pp[i].row_ptr; L.col_idx = pp[i].col_idx; L.vals = pp[i].vals; L.idxw = pp[i].idxw;
+        // n <= 2 can never put three kept elements into an aligned group of four
+        L.clear_flag = g[i].n > 2;
+        bt.L[i] = L;
+        bt.first[i + 1] = bt.first[i] + g[i].Sb * g[i].Kb;
+        bt.firstk[i + 1] = bt.firstk[i] + g[i].nk;
+    }
+    launch_score_kind<true>(sal_kind, g[0].B, g[0].m, g[0].K % g[0].B == 0, bt, st);
+    if (bt.firstk[n] > 0) topk_gather_kernel<<<(unsigned)bt.firstk[n], 256, 0, st>>>(bt, g[0].B);
     return hipGetLastError();
 }
 

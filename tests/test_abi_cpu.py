@@ -21,7 +21,7 @@ def declared_functions():
 def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert names == ["crisp_conv_spmm", "crisp_global_budget", "crisp_im2col", "crisp_pack", "crisp_pack_sizes", "crisp_select_mask",
-                     "crisp_select_pack", "crisp_spmm", "crisp_spmm_timed", "crisp_status_str"]
+                     "crisp_select_pack", "crisp_select_pack_batch", "crisp_spmm", "crisp_spmm_timed", "crisp_status_str"]
     L = crisp.lib()
     for n in names:
         assert getattr(L, n) is not None
@@ -106,6 +106,13 @@ def test_entry_points_reject_bad_arguments_without_a_device():
     assert sp(vals=fake + 2) == crisp.EALIGN
     assert sp(ws=None) == crisp.EBUFSIZE
     assert sp(wsb=crisp.crisp_pack_sizes(d).select_pack_ws_bytes - 1) == crisp.EBUFSIZE
+    # batch: every layer is checked before anything is enqueued
+    good = crisp.LayerBuffers(fake, None, fake, fake, fake, None, fake, fake, fake, fake, 1 << 30)
+    bad = crisp.LayerBuffers(fake, None, fake, fake, fake, None, None, fake, fake, fake, 1 << 30)
+    descs = (crisp.LayerDesc * 2)(d, d)
+    assert L.crisp_select_pack_batch(2, descs, (crisp.LayerBuffers * 2)(good, bad), None) == crisp.EINVAL
+    assert L.crisp_select_pack_batch(0, descs, (crisp.LayerBuffers * 2)(good, good), None) == crisp.EINVAL
+    assert L.crisp_select_pack_batch(2, None, (crisp.LayerBuffers * 2)(good, good), None) == crisp.EINVAL
     assert L.crisp_pack(C.byref(d), fake, fake, fake, fake, None, fake, fake, None, 0, None) == crisp.EINVAL
     assert L.crisp_pack(C.byref(d), fake, fake, fake, fake, fake + 8, fake, fake, None, 0, None) == crisp.EALIGN
     spmm = lambda **k: L.crisp_spmm(C.byref(k.get("d", d)), fake, fake, fake, fake, k.get("X", fake), k.get("N", 64),

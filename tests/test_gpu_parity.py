@@ -89,6 +89,36 @@ def test_select_pack_extra_patterns(L):
     assert_select_pack_equal(L, out, sel, vals, idxw, flags)
 
 
+def test_select_pack_batch_matches_single_calls():
+    """crisp_select_pack_batch over a mixed bag of layers (several kernel instantiations, more than
+    eight layers of one kind, uneven-row and very wide layers that fall back to separate steps):
+    every layer's outputs equal the oracle's, bit for bit."""
+    cases = synth.small_cases() + synth.b16_cases() + FUSED_EXTRA + synth.small_cases()[:5]
+    layers, Ws, TGs, keep, expect = [], [], [], [], []
+    for i, L in enumerate(cases):
+        W, G, _ = synth.draw_small(L, 60 + i)
+        expect.append(oracle_all(L, W, G))
+        layer = crisp.alloc_layer(desc_of(L))
+        for t in (layer.nm_mask, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, layer.flags):
+            t.fill_(-1)
+        layers.append(layer)
+        Ws.append(dev(W))
+        TGs.append(dev(G) if G is not None else None)
+    descs, bufs = crisp.make_batch(layers, Ws, TGs)
+    crisp.crisp_select_pack_batch(descs, bufs)
+    torch.cuda.synchronize()
+    for L, layer, (sel, vals, idxw, flags) in zip(cases, layers, expect):
+        sz = layer.sizes
+        out = dict(
+            nm_bits=host(layer.nm_mask, np.uint32)[: sz.mask_words].reshape(L.S, sz.mask_words_per_row),
+            row_ptr=host(layer.row_ptr, np.int32), col_idx=host(layer.col_idx, np.int32)[: sz.nk],
+            score=host(layer.score, np.float64).reshape(sz.Sb, sz.Kb),
+            vals=host(layer.vals, np.uint16)[: sz.vals_elems].reshape(sz.nk, L.B, sz.slots_per_row),
+            idxw=host(layer.idx_words, np.uint32)[: sz.idx_words].reshape(sz.nk, L.B, sz.idx_words_per_row),
+            flags=host(layer.flags, np.int32))
+        assert_select_pack_equal(L, out, sel, vals, idxw, flags)
+
+
 @pytest.mark.parametrize("L", synth.small_cases()[:6], ids=lambda L: L.name)
 def test_spmm_from_oracle_pack(L):
     """The product kernel alone, fed with the oracle's packed structure."""
