@@ -198,6 +198,60 @@ def test_lds_resident_block_rows(case):
             check_product(Y, Yref, Aref, yd, "%s shape %d" % (L.name, shape))
 
 
+TINY_CASES = [
+    # degenerate sizes: one row, one group, one column, fewer rows than a block, K below one block
+    synth.LayerSpec("tiny_1x4x1", 1, 4, 1, 1, 4, 16, 1.0, synth.SAL_MAG, 0.5),
+    synth.LayerSpec("tiny_1x8x3", 1, 8, 3, 2, 8, 32, 1.0, synth.SAL_MAG, 0.5),
+    synth.LayerSpec("tiny_3x5x2", 3, 5, 2, 1, 4, 64, 1.0, synth.SAL_MAG, 0.5),
+    synth.LayerSpec("tiny_2x16x4", 2, 16, 4, 2, 4, 16, 0.5, synth.SAL_GRAD, 0.5),
+    synth.LayerSpec("tiny_7x9x5", 7, 9, 5, 3, 4, 32, 0.5, synth.SAL_GRAD, 0.5),
+    synth.LayerSpec("tiny_1row_wide", 1, 256, 130, 2, 4, 64, 0.5, synth.SAL_MAG, 0.5),
+    synth.LayerSpec("tiny_1col", 200, 128, 1, 4, 8, 64, 0.5, synth.SAL_MAG, 0.5),
+    synth.LayerSpec("tiny_ncol4", 64, 64, 4, 2, 4, 64, 1.0, synth.SAL_MAG, 0.5),
+    synth.LayerSpec("tiny_all_kept_8:8", 32, 32, 8, 8, 8, 32, 1.0, synth.SAL_MAG, 0.5),
+]
+
+
+@pytest.mark.parametrize("L", TINY_CASES, ids=lambda L: L.name)
+def test_degenerate_sizes(L):
+    """The smallest shapes the interface admits, through both selection paths and every product kernel
+    family the shape can reach."""
+    W, G, X = synth.draw_small(L, 31)
+    sel, vals, idxw, flags = oracle_all(L, W, G)
+    for fused in (True, False):
+        layer, out = run_select_pack(L, W, G, fused=fused)
+        assert_select_pack_equal(L, out, sel, vals, idxw, flags)
+    Yref, Aref = oracle.gemm_masked(W, sel.mask, X)
+    ldx = (L.Ncol + 7) // 8 * 8
+    Xp = np.zeros((L.K, ldx), dtype=np.uint16)
+    Xp[:, : L.Ncol] = X
+    dX = dev(Xp)
+    for shape in (None, 1, 4, 5, 8):
+        Y = run_spmm(layer, dX, L.Ncol, ldx, crisp.Y_F32, L.S, shape=shape)
+        check_product(Y, Yref, Aref, crisp.Y_F32, "%s shape %s" % (L.name, shape))
+        # with a handful of outputs the Frobenius bound is no statistic of bf16 rounding any more:
+        # the bf16 result must be exactly the rounded fp32 result instead
+        Y16 = run_spmm(layer, dX, L.Ncol, ldx, crisp.Y_BF16, L.S, shape=shape)
+        assert (synth.f32_to_bf16_bits(Y16.astype(np.float32)) == synth.f32_to_bf16_bits(Y.astype(np.float32))).all()
+
+
+def test_zero_weights_and_zero_activations():
+    """All-zero W keeps exactly n per group by the tie rule and gives Y = 0; all-zero X gives Y = 0."""
+    L = synth.LayerSpec("zeros", 96, 160, 72, 2, 4, 32, 0.5, synth.SAL_MAG, 0.05)
+    W, G, X = synth.draw_small(L, 32)
+    Wz = np.zeros_like(W)
+    sel, vals, idxw, flags = oracle_all(L, Wz, None)
+    layer, out = run_select_pack(L, Wz, None)
+    assert_select_pack_equal(L, out, sel, vals, idxw, flags)
+    assert sel.nm_bits.any(), "the tie rule keeps the first n columns of every group"
+    ldx = (L.Ncol + 7) // 8 * 8
+    Xp = np.zeros((L.K, ldx), dtype=np.uint16)
+    Xp[:, : L.Ncol] = X
+    assert (run_spmm(layer, dev(Xp), L.Ncol, ldx, crisp.Y_F32, L.S) == 0).all()
+    layer, out = run_select_pack(L, W, None)
+    assert (run_spmm(layer, dev(np.zeros_like(Xp)), L.Ncol, ldx, crisp.Y_BF16, L.S) == 0).all()
+
+
 @pytest.mark.parametrize("L", synth.b16_cases(), ids=lambda L: L.name)
 def test_block16_end_to_end(L):
     """16 x 16 blocks (the paper's smallest): selection and packing bit-exact, product in tolerance."""
