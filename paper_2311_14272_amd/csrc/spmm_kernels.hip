@@ -365,10 +365,10 @@ static int pick_shape(const Geometry& g, int64_t Ncol, int blocks_per_row, bool 
     const int64_t wide = (int64_t)g.Sb * ((Ncol + 127) / 128);
     const int64_t narrow = (int64_t)g.Sb * ((Ncol + 63) / 64);
     if (smf) {
-        // sparse matrix-core instantiations: no expansion work to share between columns, so narrow
-        // strips (more waves) win more often; 2:4 with wide strips is limited to one wave per SIMD
+        // sparse matrix-core instantiations: no (or little) expansion work to share between
+        // columns, so narrow strips (more waves) win more often, most clearly for 2:4
         const bool heavy = 8 * g.n / g.m >= 4;   // 2:4
-        if (blocks_per_row <= (heavy ? 1 : 2)) return wide >= 2048 ? 0 : 1;
+        if (blocks_per_row <= 2) return wide >= 2048 ? 0 : 1;
         if (narrow >= 1024) return ((!heavy && blocks_per_row >= 7) || blocks_per_row >= 20) ? 0 : 1;
         return (blocks_per_row >= 8 && g.B == 64) ? 2 : 1;
     }

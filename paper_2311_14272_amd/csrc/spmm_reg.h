@@ -8,8 +8,12 @@
 //     MFMA B operands (8 K-values of one column each), so the accumulators of a lane are
 //     consecutive output columns and Y is written with wide stores;
 //   * the lane's slice of the compressed values and log2(m)-bit positions (canonical packed
-//     form, read as is) is expanded in registers into the dense 8-value A operand;
-//   * v_mfma_f32_32x32x16_bf16 accumulates in fp32.
+//     form, read as is) is expanded in registers into the dense 8-value A operand and fed to
+//     v_mfma_f32_32x32x16_bf16 -- or, for patterns with at most two kept per group (SMF), handed
+//     almost unchanged to the sparse matrix-core instruction v_smfmac_f32_32x32x32_bf16;
+//   * accumulation in fp32.
+// With CONV != 0 the X rows are not read from a materialised matrix but located inside the
+// convolution's input (three modes, see SpmmArgs).
 // Nothing goes through LDS in the loop and waves never wait for each other, so every wave keeps
 // PF blocks of X in flight.  Two ways to spread work:
 //   NWK == 1: the 4 waves of a workgroup own 4 neighbouring column strips (large Ncol);
@@ -527,14 +531,14 @@ struct BlockBody {
 // Two waves per SIMD (256 registers each) wherever the lane's slice of the packed block is small
 // enough to fit beside 128 accumulators and 64 X registers; the wide-strip kernels of the denser
 // patterns would spill there and run with one wave per SIMD instead.
-template <int N, int M, int B, int WD>
-constexpr int waves_per_simd() { return (WD == 2 && B == 64 && Fmt<N, M, B>::FS >= 4) ? 1 : 2; }
+template <int N, int M, int B, int WD, bool SMF>
+constexpr int waves_per_simd() { return (WD == 2 && B == 64 && Fmt<N, M, B>::FS >= 4 && !SMF) ? 1 : 2; }
 
 template <int N, int M, int B, int WD, int NWK, int PF, int CONV, bool SMF = false>
 __global__ __launch_bounds__(NWK > 1 ? 64 * NWK : 256)
-__attribute__((amdgpu_waves_per_eu(waves_per_simd<N, M, B, WD>(), 2)))
+__attribute__((amdgpu_waves_per_eu(waves_per_simd<N, M, B, WD, SMF>(), 2)))
 void spmm_reg_kernel(SpmmArgs p) {
-    static_assert(!CONV || WD == 1, "conv mode pairs two output columns per lane");
+    static_assert(!CONV || WD == 1, "conv modes work on two output columns per lane");
     typedef Fmt<N, M, B> F;
     constexpr int RT = F::RT, KS = F::KS;
     constexpr int STRIPS = NWK > 1 ? 1 : 4;       // column strips per workgroup
