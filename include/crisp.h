@@ -99,6 +99,22 @@ typedef struct {
     int32_t x_layout;          /* CRISP_X_KN                                                     */
 } crisp_conv_desc;
 
+/*
+ * Optional epilogue of the product entry points (the usual tail of a convolution layer once batch
+ * normalisation is folded into a per-channel scale and bias; not part of the paper's method):
+ *   y = sum;  y = y * scale[s]  (if scale);  y = y + bias[s]  (if bias);
+ *   y = y + residual[s][j]  (if residual);  y = max(y, 0)  (if relu);  Y[s][j] = round(y)
+ * in fp32 with one rounding per step, before the rounding to y_dtype.
+ */
+typedef struct {
+    const float *scale;        /* S values (device) or NULL                                      */
+    const float *bias;         /* S values (device) or NULL                                      */
+    const void *residual;      /* S x ldr elements of the output's type (device) or NULL         */
+    int64_t ldr;               /* >= Ncol, multiple of 8 (only read when residual != NULL)       */
+    int32_t relu;              /* 0 or 1                                                         */
+    int32_t reserved;          /* 0                                                              */
+} crisp_epilogue;
+
 /* Text for a status code (static storage, never NULL). */
 CRISP_API const char *crisp_status_str(crisp_status st);
 
@@ -257,6 +273,22 @@ CRISP_API crisp_status crisp_conv_spmm(const crisp_layer_desc *desc, const crisp
                                        const int32_t *row_ptr, const int32_t *col_idx, const uint16_t *vals,
                                        const uint32_t *idx_words, const uint16_t *act, void *Y, int64_t ldy,
                                        int32_t y_dtype, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * crisp_spmm / crisp_conv_spmm with an epilogue (see crisp_epilogue; ep == NULL: none).  The
+ * residual may not overlap Y.  Errors: those of the plain entry points, plus EALIGN / ESHAPE /
+ * EINVAL for a bad epilogue.
+ */
+CRISP_API crisp_status crisp_spmm_ep(const crisp_layer_desc *desc, const int32_t *row_ptr, const int32_t *col_idx,
+                           const uint16_t *vals, const uint32_t *idx_words, const uint16_t *X,
+                           int64_t Ncol, int64_t ldx, int32_t x_layout, void *Y, int64_t ldy,
+                           int32_t y_dtype, const crisp_epilogue *ep, void *ws, size_t ws_bytes,
+                           void *stream);
+CRISP_API crisp_status crisp_conv_spmm_ep(const crisp_layer_desc *desc, const crisp_conv_desc *conv,
+                                const int32_t *row_ptr, const int32_t *col_idx, const uint16_t *vals,
+                                const uint32_t *idx_words, const uint16_t *act, void *Y, int64_t ldy,
+                                int32_t y_dtype, const crisp_epilogue *ep, void *ws, size_t ws_bytes,
+                                void *stream);
 
 /*
  * Global block budget across layers (Alg. 1 lines 6-9; Sec. 3.3): turns one overall target

@@ -183,6 +183,27 @@ def select(W: np.ndarray, G_or_T: Optional[np.ndarray], n: int, m: int, B: int, 
     return Selection(T, keep, keep_to_bits(keep), sc, kr, row_ptr, col_idx, mask)
 
 
+def epilogue(Y: np.ndarray, A: Optional[np.ndarray], scale=None, bias=None, residual=None, relu=False):
+    """Tail of a layer on the exact product Y (fp64): y*scale[s] + bias[s] + residual[s][j], then
+    ReLU; absent parts are skipped.  A, the bound |W|.|X| that the element-wise tolerance uses, is
+    scaled by |scale| (bias and residual are exact inputs and add no error of their own).
+    Plain definition; not part of the paper's method (folded batch normalisation, ReLU, shortcut)."""
+    Y = np.array(Y, dtype=np.float64, copy=True)
+    A = None if A is None else np.array(A, dtype=np.float64, copy=True)
+    if scale is not None:
+        sc = np.asarray(scale, dtype=np.float64)[:, None]
+        Y *= sc
+        if A is not None:
+            A *= np.abs(sc)
+    if bias is not None:
+        Y += np.asarray(bias, dtype=np.float64)[:, None]
+    if residual is not None:
+        Y += np.asarray(residual, dtype=np.float64)
+    if relu:
+        Y = np.maximum(Y, 0.0)
+    return Y, A
+
+
 def num_threads() -> int:
     return int(lib().oracle_num_threads())
 

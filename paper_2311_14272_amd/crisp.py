@@ -48,6 +48,16 @@ class LayerBuffers(C.Structure):
                 ("flags", C.c_void_p), ("ws", C.c_void_p), ("ws_bytes", C.c_size_t)]
 
 
+class Epilogue(C.Structure):
+    _fields_ = [("scale", C.c_void_p), ("bias", C.c_void_p), ("residual", C.c_void_p), ("ldr", C.c_int64),
+                ("relu", C.c_int32), ("reserved", C.c_int32)]
+
+
+def epilogue(scale=None, bias=None, residual=None, ldr=0, relu=False) -> Epilogue:
+    """Epilogue descriptor from device tensors (kept alive by the caller)."""
+    return Epilogue(_ptr(scale), _ptr(bias), _ptr(residual), int(ldr), 1 if relu else 0, 0)
+
+
 class CrispError(RuntimeError):
     def __init__(self, fn: str, status: int):
         self.status = status
@@ -78,11 +88,15 @@ def lib():
                                  C.c_int64, C.c_int32, vp, C.c_size_t, vp]
         L.crisp_conv_spmm.argtypes = [C.POINTER(LayerDesc), C.POINTER(ConvDesc), vp, vp, vp, vp, vp, vp, C.c_int64,
                                       C.c_int32, vp, C.c_size_t, vp]
+        L.crisp_spmm_ep.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp, vp, C.c_int64, C.c_int64, C.c_int32, vp,
+                                    C.c_int64, C.c_int32, C.POINTER(Epilogue), vp, C.c_size_t, vp]
+        L.crisp_conv_spmm_ep.argtypes = [C.POINTER(LayerDesc), C.POINTER(ConvDesc), vp, vp, vp, vp, vp, vp, C.c_int64,
+                                         C.c_int32, C.POINTER(Epilogue), vp, C.c_size_t, vp]
         L.crisp_spmm_timed.argtypes = [C.POINTER(LayerDesc), C.POINTER(ConvDesc), vp, vp, vp, vp, vp, C.c_int64,
                                        C.c_int64, vp, C.c_int64, C.c_int32, vp, vp, vp]
         L.crisp_global_budget.argtypes = [C.c_int32, vp, vp, C.c_double, vp, vp, vp, C.c_size_t, vp]
         for f in (L.crisp_pack_sizes, L.crisp_select_mask, L.crisp_pack, L.crisp_select_pack, L.crisp_select_pack_batch,
-                  L.crisp_im2col, L.crisp_spmm,
+                  L.crisp_im2col, L.crisp_spmm, L.crisp_spmm_ep, L.crisp_conv_spmm_ep,
                   L.crisp_conv_spmm, L.crisp_spmm_timed, L.crisp_global_budget):
             f.restype = C.c_int32
         _lib = L
@@ -170,6 +184,25 @@ def crisp_conv_spmm(desc, conv: ConvDesc, row_ptr, col_idx, vals, idx_words, act
                                _stream() if stream == -1 else stream)
     if st != OK:
         raise CrispError("crisp_conv_spmm", st)
+
+
+def crisp_spmm_ep(desc, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, Y, ldy, y_dtype, ep: Epilogue, x_layout=X_KN,
+                  ws=None, ws_bytes=0, stream=-1):
+    st = lib().crisp_spmm_ep(C.byref(desc), _ptr(row_ptr), _ptr(col_idx), _ptr(vals), _ptr(idx_words), _ptr(X), Ncol,
+                             ldx, x_layout, _ptr(Y), ldy, y_dtype, C.byref(ep) if ep is not None else None, _ptr(ws),
+                             ws_bytes, _stream() if stream == -1 else stream)
+    if st != OK:
+        raise CrispError("crisp_spmm_ep", st)
+
+
+def crisp_conv_spmm_ep(desc, conv: ConvDesc, row_ptr, col_idx, vals, idx_words, act, Y, ldy, y_dtype, ep: Epilogue,
+                       ws=None, ws_bytes=0, stream=-1):
+    st = lib().crisp_conv_spmm_ep(C.byref(desc), C.byref(conv), _ptr(row_ptr), _ptr(col_idx), _ptr(vals),
+                                  _ptr(idx_words), _ptr(act), _ptr(Y), ldy, y_dtype,
+                                  C.byref(ep) if ep is not None else None, _ptr(ws), ws_bytes,
+                                  _stream() if stream == -1 else stream)
+    if st != OK:
+        raise CrispError("crisp_conv_spmm_ep", st)
 
 
 def crisp_spmm_timed(desc, conv, row_ptr, col_idx, vals, idx_words, X_or_act, Ncol, ldx, Y, ldy, y_dtype,

@@ -225,10 +225,20 @@ crisp_status crisp_im2col(const crisp_conv_desc* c, const uint16_t* act, uint16_
     return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
 }
 
+static crisp_status check_epilogue(const crisp_epilogue* ep, int64_t Ncol) {
+    if (!ep) return CRISP_OK;
+    if (misaligned(ep->scale, 4) || misaligned(ep->bias, 4) || misaligned(ep->residual, 16)) return CRISP_EALIGN;
+    if (ep->residual && (ep->ldr < Ncol || ep->ldr > ((int64_t)1 << 27))) return CRISP_ESHAPE;
+    if (ep->residual && (ep->ldr & 7)) return CRISP_EALIGN;
+    if (ep->relu != 0 && ep->relu != 1) return CRISP_EINVAL;
+    return CRISP_OK;
+}
+
 static crisp_status spmm_impl(const crisp_layer_desc* desc, const int32_t* row_ptr, const int32_t* col_idx,
                               const uint16_t* vals, const uint32_t* idx_words, const uint16_t* X, int64_t Ncol,
                               int64_t ldx, int32_t x_layout, void* Y, int64_t ldy, int32_t y_dtype, void* ws,
-                              size_t ws_bytes, void* stream, void* ev_start, void* ev_stop) {
+                              size_t ws_bytes, void* stream, void* ev_start, void* ev_stop,
+                              const crisp_epilogue* ep = nullptr) {
     Geometry g;
     crisp_status st = make_geometry(desc, false, &g);
     if (st != CRISP_OK) return st;
@@ -241,19 +251,21 @@ static crisp_status spmm_impl(const crisp_layer_desc* desc, const int32_t* row_p
         misaligned(X, 16) || misaligned(Y, 16))
         return CRISP_EALIGN;
     if (x_layout != CRISP_X_KN) return CRISP_EUNSUPPORTED;
+    { crisp_status es = check_epilogue(ep, Ncol); if (es != CRISP_OK) return es; }
     // ws_bytes doubles as a tuning knob when ws is NULL: 0 = automatic launch shape, 1..7 force
     // shape (value - 1); results do not depend on it.
     const int force_shape = (!ws && ws_bytes >= 1 && ws_bytes <= 11) ? (int)ws_bytes - 1 : -1;
     hipError_t e = launch_spmm(g, desc->block_density, desc->select_mode == CRISP_ROW_UNIFORM, force_shape, row_ptr, col_idx, vals,
                                idx_words, X, nullptr, Ncol,
-                               ldx, Y, ldy, y_dtype, (hipEvent_t)ev_start, (hipEvent_t)ev_stop, (hipStream_t)stream);
+                               ldx, Y, ldy, y_dtype, ep, (hipEvent_t)ev_start, (hipEvent_t)ev_stop, (hipStream_t)stream);
     return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
 }
 
 static crisp_status conv_spmm_impl(const crisp_layer_desc* desc, const crisp_conv_desc* conv, const int32_t* row_ptr,
                                    const int32_t* col_idx, const uint16_t* vals, const uint32_t* idx_words,
                                    const uint16_t* act, void* Y, int64_t ldy, int32_t y_dtype, void* ws,
-                                   size_t ws_bytes, void* stream, void* ev_start, void* ev_stop) {
+                                   size_t ws_bytes, void* stream, void* ev_start, void* ev_stop,
+                                   const crisp_epilogue* ep = nullptr) {
     Geometry g;
     crisp_status st = make_geometry(desc, false, &g);
     if (st != CRISP_OK) return st;
@@ -273,6 +285,7 @@ static crisp_status conv_spmm_impl(const crisp_layer_desc* desc, const crisp_con
     if (ldy < Ncol || Ncol > ((int64_t)1 << 27)) return CRISP_ESHAPE;
     if ((ldy & 7) || misaligned(act, 16) || misaligned(Y, 16) || misaligned(vals, 16) || misaligned(idx_words, 16))
         return CRISP_EALIGN;
+    { crisp_status es = check_epilogue(ep, Ncol); if (es != CRISP_OK) return es; }
     // what the fused kernels cover; everything else goes through crisp_im2col + crisp_spmm
     const bool pattern_ok = (g.m == 4 && g.n <= 4) || (g.m == 8 && (g.n == 1 || g.n == 2 || g.n == 4 || g.n == 8));
     if (g.B == 16 || (Ncol & 1) || conv->kw > 16 || conv->kh * conv->kw > 64 || conv->stride > 16 ||
@@ -285,7 +298,7 @@ static crisp_status conv_spmm_impl(const crisp_layer_desc* desc, const crisp_con
                           : (!ws && ws_bytes >= 8 && ws_bytes <= 11) ? (int)ws_bytes - 1 : -1;
     hipError_t e = launch_spmm(g, desc->block_density, desc->select_mode == CRISP_ROW_UNIFORM, force_shape, row_ptr, col_idx, vals,
                                idx_words, act, conv,
-                               Ncol, Ncol, Y, ldy, y_dtype, (hipEvent_t)ev_start, (hipEvent_t)ev_stop, (hipStream_t)stream);
+                               Ncol, Ncol, Y, ldy, y_dtype, ep, (hipEvent_t)ev_start, (hipEvent_t)ev_stop, (hipStream_t)stream);
     return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
 }
 
@@ -303,6 +316,22 @@ crisp_status crisp_conv_spmm(const crisp_layer_desc* desc, const crisp_conv_desc
                              void* stream) {
     return conv_spmm_impl(desc, conv, row_ptr, col_idx, vals, idx_words, act, Y, ldy, y_dtype, ws, ws_bytes, stream,
                           nullptr, nullptr);
+}
+
+crisp_status crisp_spmm_ep(const crisp_layer_desc* desc, const int32_t* row_ptr, const int32_t* col_idx,
+                           const uint16_t* vals, const uint32_t* idx_words, const uint16_t* X, int64_t Ncol,
+                           int64_t ldx, int32_t x_layout, void* Y, int64_t ldy, int32_t y_dtype,
+                           const crisp_epilogue* ep, void* ws, size_t ws_bytes, void* stream) {
+    return spmm_impl(desc, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, x_layout, Y, ldy, y_dtype, ws, ws_bytes,
+                     stream, nullptr, nullptr, ep);
+}
+
+crisp_status crisp_conv_spmm_ep(const crisp_layer_desc* desc, const crisp_conv_desc* conv, const int32_t* row_ptr,
+                                const int32_t* col_idx, const uint16_t* vals, const uint32_t* idx_words,
+                                const uint16_t* act, void* Y, int64_t ldy, int32_t y_dtype, const crisp_epilogue* ep,
+                                void* ws, size_t ws_bytes, void* stream) {
+    return conv_spmm_impl(desc, conv, row_ptr, col_idx, vals, idx_words, act, Y, ldy, y_dtype, ws, ws_bytes, stream,
+                          nullptr, nullptr, ep);
 }
 
 crisp_status crisp_global_budget(int32_t n_layers, const crisp_layer_desc* descs, const double* const* block_scores,

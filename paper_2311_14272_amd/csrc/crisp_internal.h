@@ -41,6 +41,7 @@ hipError_t launch_im2col(const crisp_conv_desc& c, const uint16_t* act, uint16_t
 hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows, int force_shape, const int32_t* row_ptr,
                        const int32_t* col_idx, const uint16_t* vals, const uint32_t* idxw, const uint16_t* X,
                        const crisp_conv_desc* conv, int64_t Ncol, int64_t ldx, void* Y, int64_t ldy, int y_dtype,
+                       const crisp_epilogue* ep,
                        hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st);
 
 #define CRISP_BUDGET_MAX_LAYERS 64

@@ -207,6 +207,16 @@ __global__ __launch_bounds__(64 * NW) void spmm_expand_mfma_kernel(SpmmArgs p) {
             float v[2 * WD];
 #pragma unroll
             for (int c = 0; c < 2 * WD; ++c) v[c] = acc[rt][c][r];
+            if (full) {
+                apply_epilogue<2 * WD>(p, row, col0, true, v);
+            } else {
+#pragma unroll
+                for (int c = 0; c < 2 * WD; ++c) {
+                    float one[1] = {v[c]};
+                    apply_epilogue<1>(p, row, col0 + c, col0 + c < p.Ncol, one);
+                    v[c] = one[0];
+                }
+            }
             if (p.y_bf16) {
                 uint16_t* y = reinterpret_cast<uint16_t*>(p.Y) + (int64_t)row * p.ldy + col0;
                 if (full) {
@@ -325,7 +335,9 @@ __global__ __launch_bounds__(256) void spmm_b16_kernel(SpmmArgs p) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             if (col0 + c >= p.Ncol) continue;
-            const float v = acc[c][r];
+            float one[1] = {acc[c][r]};
+            apply_epilogue<1>(p, row, col0 + c, true, one);
+            const float v = one[0];
             if (p.y_bf16) reinterpret_cast<uint16_t*>(p.Y)[(int64_t)row * p.ldy + col0 + c] = float_to_bf16_rne(v);
             else reinterpret_cast<float*>(p.Y)[(int64_t)row * p.ldy + col0 + c] = v;
         }
@@ -400,13 +412,17 @@ static bool prefer_lds(const Geometry& g, int64_t Ncol, int blocks_per_row) {
 hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows, int force_shape, const int32_t* row_ptr,
                        const int32_t* col_idx, const uint16_t* vals, const uint32_t* idxw, const uint16_t* X,
                        const crisp_conv_desc* conv, int64_t Ncol, int64_t ldx, void* Y, int64_t ldy, int y_dtype,
-                       hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st) {
+                       const crisp_epilogue* ep, hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st) {
     SpmmArgs a = {};
     a.ev_start = ev_start; a.ev_stop = ev_stop;
     a.S = g.S; a.K = g.K; a.n = g.n; a.m = g.m; a.w = g.w; a.slots = g.slots; a.wpr = g.wpr;
     a.Sb = g.Sb; a.NT = 0; a.Ncol = Ncol; a.ldx = ldx; a.ldy = ldy;
     a.row_ptr = row_ptr; a.col_idx = col_idx; a.vals = vals; a.idxw = idxw; a.X = X; a.Y = Y;
     a.y_bf16 = (y_dtype == CRISP_Y_BF16);
+    if (ep && (ep->scale || ep->bias || ep->residual || ep->relu)) {
+        a.ep_on = 1; a.ep_relu = ep->relu ? 1 : 0;
+        a.ep_scale = ep->scale; a.ep_bias = ep->bias; a.ep_res = ep->residual; a.ep_ldr = ep->ldr;
+    }
     a.act = nullptr;
     if (conv) {
         // implicit lowering: X is the activation itself

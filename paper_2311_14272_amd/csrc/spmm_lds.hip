@@ -203,11 +203,18 @@ void spmm_lds_kernel(SpmmArgs p, LdsSched sch) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const uint32_t off = y_off + (uint32_t)(rt * 32 + 8 * (r >> 2) + (r & 3)) * yrow_bytes;
+                float v[NACC];
+#pragma unroll
+                for (int c = 0; c < NACC; ++c) v[c] = acc[rt][c][r];
+                {
+                    const int row = bi * B + rt * 32 + 8 * (r >> 2) + (r & 3) + 4 * hh;
+                    apply_epilogue<NACC>(p, row, col0, col_ok && row < p.S, v);
+                }
                 if constexpr (decltype(as_bf16)::value) {
                     uint32_t pk[WD];
 #pragma unroll
                     for (int c = 0; c < WD; ++c) {
-                        const f32x2 two = {acc[rt][2 * c][r], acc[rt][2 * c + 1][r]};
+                        const f32x2 two = {v[2 * c], v[2 * c + 1]};
                         pk[c] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2));
                     }
                     if constexpr (WD == 1) {
@@ -218,11 +225,11 @@ void spmm_lds_kernel(SpmmArgs p, LdsSched sch) {
                     }
                 } else {
                     if constexpr (WD == 1) {
-                        const u32x2 two = {__float_as_uint(acc[rt][0][r]), __float_as_uint(acc[rt][1][r])};
+                        const u32x2 two = {__float_as_uint(v[0]), __float_as_uint(v[1])};
                         __builtin_amdgcn_raw_buffer_store_b64(two, ry, off, 0, 0);
                     } else {
-                        const u32x4 four = {__float_as_uint(acc[rt][0][r]), __float_as_uint(acc[rt][1][r]),
-                                            __float_as_uint(acc[rt][NACC - 2][r]), __float_as_uint(acc[rt][NACC - 1][r])};
+                        const u32x4 four = {__float_as_uint(v[0]), __float_as_uint(v[1]),
+                                            __float_as_uint(v[NACC - 2]), __float_as_uint(v[NACC - 1])};
                         __builtin_amdgcn_raw_buffer_store_b128(four, ry, off, 0, 0);
                     }
                 }

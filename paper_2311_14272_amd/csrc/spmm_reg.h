@@ -63,6 +63,13 @@ struct SpmmArgs {
     int64_t plane;            // batch*H*W elements of one channel
     float inv_cpb, inv_kw;    // reciprocals of C/B (block columns per tap) and kw
     double inv_Wo, inv_Ho;
+    // optional epilogue on the fp32 sums before the output rounding: y = relu(y * scale[row] +
+    // bias[row] + residual[row][col]), every step one fp32 rounding, absent parts skipped
+    int ep_on, ep_relu;
+    const float* ep_scale;
+    const float* ep_bias;
+    const void* ep_res;       // S x ep_ldr, same element type as Y
+    int64_t ep_ldr;
     int use_smf;              // host side only: sparse-MFMA instantiation wanted (eligible patterns)
     // host side only: optional events that receive the kernel's own start and stop time stamps
     hipEvent_t ev_start, ev_stop;
@@ -96,6 +103,7 @@ __device__ __forceinline__ uint16_t float_to_bf16_rne(float f) {
 
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4e;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 template <int WD> struct XVec;
 template <> struct XVec<1> { typedef uint32_t type; };
@@ -118,6 +126,48 @@ template <> __device__ __forceinline__ uint32_t buf_load_x<1>(rsrc_t r, uint32_t
 }
 template <> __device__ __forceinline__ u32x2 buf_load_x<2>(rsrc_t r, uint32_t voff, uint32_t soff) {
     return __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0));
+}
+
+// Epilogue on NV consecutive outputs (row, col .. col+NV-1) of a lane, all of which exist
+// (callers pass ok = false otherwise): per-row scale and bias (folded normalisation), residual
+// of the output's element type, ReLU.  fp32 throughout, one rounding per step.
+template <int NV>
+__device__ __forceinline__ void apply_epilogue(const SpmmArgs& p, int row, int64_t col, bool ok, float (&v)[NV]) {
+    if (!p.ep_on || !ok) return;
+    float res[NV];
+#pragma unroll
+    for (int c = 0; c < NV; ++c) res[c] = 0.0f;
+    if (p.ep_res) {
+        if (p.y_bf16) {
+            const uint16_t* r = reinterpret_cast<const uint16_t*>(p.ep_res) + (int64_t)row * p.ep_ldr + col;
+            if constexpr (NV == 4) {
+                const u32x2 t = *reinterpret_cast<const u32x2*>(r);
+                res[0] = __uint_as_float(t[0] << 16); res[1] = __uint_as_float(t[0] & 0xFFFF0000u);
+                res[2] = __uint_as_float(t[1] << 16); res[3] = __uint_as_float(t[1] & 0xFFFF0000u);
+            } else if constexpr (NV == 2) {
+                const uint32_t t = *reinterpret_cast<const uint32_t*>(r);
+                res[0] = __uint_as_float(t << 16); res[1] = __uint_as_float(t & 0xFFFF0000u);
+            } else {
+#pragma unroll
+                for (int c = 0; c < NV; ++c) res[c] = __uint_as_float((uint32_t)r[c] << 16);
+            }
+        } else {
+            const float* r = reinterpret_cast<const float*>(p.ep_res) + (int64_t)row * p.ep_ldr + col;
+#pragma unroll
+            for (int c = 0; c < NV; ++c) res[c] = r[c];
+        }
+    }
+    const float sc = p.ep_scale ? p.ep_scale[row] : 1.0f;
+    const float bi = p.ep_bias ? p.ep_bias[row] : 0.0f;
+#pragma unroll
+    for (int c = 0; c < NV; ++c) {
+        float y = v[c];
+        if (p.ep_scale) y = __fmul_rn(y, sc);
+        if (p.ep_bias) y = __fadd_rn(y, bi);
+        if (p.ep_res) y = __fadd_rn(y, res[c]);
+        if (p.ep_relu) y = fmaxf(y, 0.0f);
+        v[c] = y;
+    }
 }
 
 // Geometry of the canonical packed form as seen by one lane.
@@ -656,8 +706,15 @@ void spmm_reg_kernel(SpmmArgs p) {
     const rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(
         reinterpret_cast<char*>(p.Y) + (int64_t)bi * B * p.ldy * esz, 0, (uint32_t)rows_here * row_bytes, 0x00020000);
     const uint32_t y_off = col_ok ? (uint32_t)(4 * hh) * row_bytes + (uint32_t)col0 * esz : 0x80000000u;
-    auto store_row = [&](int tile_row, const float (&v)[NACC]) {
+    auto store_row = [&](int tile_row, const float (&vin)[NACC]) {
         const uint32_t off = y_off + (uint32_t)tile_row * row_bytes;
+        float v[NACC];
+#pragma unroll
+        for (int c = 0; c < NACC; ++c) v[c] = vin[c];
+        {
+            const int row = bi * B + tile_row + 4 * hh;
+            apply_epilogue<NACC>(p, row, col0, col_ok && row < p.S, v);
+        }
         if (p.y_bf16) {
             uint32_t pk[WD];
 #pragma unroll

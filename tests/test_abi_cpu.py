@@ -20,8 +20,8 @@ def declared_functions():
 
 def test_library_exports_every_declared_symbol():
     names = declared_functions()
-    assert names == ["crisp_conv_spmm", "crisp_global_budget", "crisp_im2col", "crisp_pack", "crisp_pack_sizes", "crisp_select_mask",
-                     "crisp_select_pack", "crisp_select_pack_batch", "crisp_spmm", "crisp_spmm_timed", "crisp_status_str"]
+    assert names == ["crisp_conv_spmm", "crisp_conv_spmm_ep", "crisp_global_budget", "crisp_im2col", "crisp_pack", "crisp_pack_sizes", "crisp_select_mask",
+                     "crisp_select_pack", "crisp_select_pack_batch", "crisp_spmm", "crisp_spmm_ep", "crisp_spmm_timed", "crisp_status_str"]
     L = crisp.lib()
     for n in names:
         assert getattr(L, n) is not None
@@ -126,6 +126,11 @@ def test_entry_points_reject_bad_arguments_without_a_device():
     assert spmm(yd=3) == crisp.EINVAL
     assert spmm(xl=1) == crisp.EUNSUPPORTED
     assert spmm(Y=fake + 4) == crisp.EALIGN
+    spmm_ep = lambda ep: L.crisp_spmm_ep(C.byref(d), fake, fake, fake, fake, fake, 64, 64, 0, fake, 64, 0, C.byref(ep), None, 0, None)
+    assert spmm_ep(crisp.Epilogue(fake + 2, None, None, 0, 0, 0)) == crisp.EALIGN
+    assert spmm_ep(crisp.Epilogue(None, None, fake, 56, 0, 0)) == crisp.ESHAPE
+    assert spmm_ep(crisp.Epilogue(None, None, fake, 68, 0, 0)) == crisp.EALIGN
+    assert spmm_ep(crisp.Epilogue(None, None, None, 0, 2, 0)) == crisp.EINVAL
     cv = crisp.ConvDesc(3, 8, 8, 1, 3, 3, 1, 1, 0, 0)
     assert L.crisp_im2col(C.byref(cv), None, fake, 64, None) == crisp.EINVAL
     assert L.crisp_im2col(C.byref(cv), fake, fake, 8, None) == crisp.ESHAPE

@@ -479,3 +479,24 @@ def test_config_shapes():
     assert abs(macs / 1e9 - 4.087) < 0.01                # ResNet-50 convs, GMAC per image
     assert {(L.n, L.m) for L in wl.layers} <= set(synth.NM_CHOICES)
     assert all(0.2 <= L.density <= 0.8 for L in wl.layers)
+
+
+def test_epilogue_closed_forms():
+    """oracle.epilogue against values worked out by hand: order of the steps (scale before bias
+    before residual before ReLU), per-row broadcasting, the scaled error bound."""
+    Y = np.array([[1.0, -2.0, 3.0], [-4.0, 5.0, -6.0]])
+    A = np.array([[1.0, 2.0, 3.0], [4.0, 5.0, 6.0]])
+    scale = np.array([2.0, -0.5], dtype=np.float32)
+    bias = np.array([1.0, -1.0], dtype=np.float32)
+    res = np.array([[0.0, 10.0, -10.0], [1.0, 1.0, 1.0]])
+    out, a = oracle.epilogue(Y, A, scale, bias, res, relu=False)
+    assert (out == np.array([[3.0, 7.0, -3.0], [2.0, -2.5, 3.0]])).all()
+    assert (a == np.array([[2.0, 4.0, 6.0], [2.0, 2.5, 3.0]])).all()
+    out, _ = oracle.epilogue(Y, A, scale, bias, res, relu=True)
+    assert (out == np.array([[3.0, 7.0, 0.0], [2.0, 0.0, 3.0]])).all()
+    out, a = oracle.epilogue(Y, A)
+    assert (out == Y).all() and (a == A).all() and out is not Y
+    out, _ = oracle.epilogue(Y, None, relu=True)
+    assert (out == np.maximum(Y, 0)).all()
+    out, _ = oracle.epilogue(Y, None, bias=bias)
+    assert (out == Y + np.array([[1.0], [-1.0]])).all()
