@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--y-dtype", choices=["bf16", "f32"], default="bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--spmm-only", action="store_true", help="time only the products (selection and packing done once)")
+    ap.add_argument("--chained", action="store_true",
+                    help="config 5: time the chained bf16 forward (epilogues fused, max-pool) instead of layer-wise products")
     ap.add_argument("--per-layer-prune", action="store_true",
                     help="select+pack layer by layer (crisp_select_pack) instead of one crisp_select_pack_batch call")
     ap.add_argument("--side-streams", action="store_true",
@@ -100,10 +102,44 @@ def resnet50_pass(args):
         t_prune = timed(lambda r: crisp.crisp_select_pack_batch(*batch))
         per_layer_tp = [None] * len(dls)
 
+    if args.chained:
+        # the network as a chain: every layer's bf16 output is the next layer's input, layer tails
+        # (folded-normalisation scale, shortcut, ReLU) fused into the products, one max-pool kernel
+        from paper_2311_14272_amd import resnet
+        if args.per_layer_prune:
+            crisp.crisp_select_pack_batch(*crisp.make_batch(dls, Wd, Gd))
+        scales = resnet.layer_scales(wl, dls)
+        need = max([L.K * L.Ncol for L in wl.layers if crisp.conv_needs_scratch(L.conv, L.B, L.n, L.m, L.S)] + [1])
+        xs = torch.empty(need, dtype=torch.int16, device=dev)
+        cv1 = wl.layers[0].conv
+        x = torch.randn((3, cv1.batch, 224, 224), generator=gen, device=dev).to(torch.bfloat16).view(torch.int16)
+        t_chain = timed(lambda r: resnet.forward(wl, dls, x, scales, xs))
+        for L, dl in zip(wl.layers, dls):
+            sz = dl.sizes
+            useful += 2.0 * sz.nk * L.B * sz.slots_per_row * L.Ncol if (L.S % L.B == 0 and L.K % L.B == 0) else 0.0
+            dense += 2.0 * L.S * L.K * L.Ncol
+        total = t_prune + t_chain
+        print(json.dumps({
+            "metric": "effective TFLOP/s (nonzero FLOPs) of hybrid-sparse GEMM + % roofline",
+            "value": round(useful / (total * 1e-3) / 1e12, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": reps, "warmup": 1,
+            "ms_per_step": round(total, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "c5: ResNet-50, 53 convs as GEMMs, batch 256, 224x224, chained bf16 forward "
+                                   "(scale / shortcut / ReLU epilogues, max-pool), B=64, per-layer n:m and block "
+                                   "density drawn from the workload seed",
+                       "step": "select+pack of all layers, then the chained forward", "y_dtype": "bf16",
+                       "note": "useful FLOPs exclude the ragged first layer"},
+            "select_pack_ms": round(t_prune, 3), "forward_ms": round(t_chain, 3),
+            "dense_equivalent_tflops_forward_only": round(dense / (t_chain * 1e-3) / 1e12, 1), "roofline": None}))
+        return
+
     for li, L in enumerate(wl.layers):
         cv = L.conv
         W, G, dl = Wd[li], Gd[li], dls[li]
-        nbuf = 2
+        # enough independent (input, output) pairs that a layer's working set is not served from the
+        # 256 MB last-level cache across repetitions
+        set_bytes = 2 * cv.C * cv.batch * cv.H * cv.W + ybytes * L.S * L.Ncol
+        nbuf = max(2, min(12, int(600e6 // set_bytes) + 1))
         acts = [torch.randn((cv.C, cv.batch, cv.H, cv.W), generator=gen, device=dev).clamp_(min=0).to(torch.bfloat16).view(torch.int16)
                 for _ in range(nbuf)]
         Ys = [torch.empty((L.S, L.Ncol), dtype=ytorch, device=dev) for _ in range(nbuf)]

@@ -275,6 +275,16 @@ CRISP_API crisp_status crisp_conv_spmm(const crisp_layer_desc *desc, const crisp
                                        int32_t y_dtype, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Max pooling of a channel-major activation (glue of the ResNet workload between the first
+ * convolution and the first residual stage; not part of the paper's method):
+ *   out[c][i][oh][ow] = max over a < kh, b < kw of act[c][i][oh*stride + a - pad][ow*stride + b - pad],
+ * positions outside the image excluded; Ho, Wo as for a convolution; pad < kh, kw.  The result is
+ * one of the inputs (no rounding).  act and out device, bf16, out holds C*batch*Ho*Wo elements.
+ * Errors: EINVAL, ESHAPE, EUNSUPPORTED (layout), EDEVICE.
+ */
+CRISP_API crisp_status crisp_maxpool(const crisp_conv_desc *pool, const uint16_t *act, uint16_t *out, void *stream);
+
+/*
  * crisp_spmm / crisp_conv_spmm with an epilogue (see crisp_epilogue; ep == NULL: none).  The
  * residual may not overlap Y.  Errors: those of the plain entry points, plus EALIGN / ESHAPE /
  * EINVAL for a bad epilogue.

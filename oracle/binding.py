@@ -204,6 +204,28 @@ def epilogue(Y: np.ndarray, A: Optional[np.ndarray], scale=None, bias=None, resi
     return Y, A
 
 
+def maxpool(act: np.ndarray, kh: int, kw: int, stride: int, pad: int) -> np.ndarray:
+    """Max over kh x kw windows of act [C][batch][H][W] (bf16 bits), positions outside the image
+    excluded; returns bf16 bits [C][batch][Ho][Wo].  Plain loops over the window."""
+    a = (np.ascontiguousarray(act, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+    C_, b, H, W = a.shape
+    Ho = (H + 2 * pad - kh) // stride + 1
+    Wo = (W + 2 * pad - kw) // stride + 1
+    out = np.full((C_, b, Ho, Wo), -np.inf, dtype=np.float32)
+    for oh in range(Ho):
+        for ow in range(Wo):
+            for da in range(kh):
+                ih = oh * stride + da - pad
+                if ih < 0 or ih >= H:
+                    continue
+                for db in range(kw):
+                    iw = ow * stride + db - pad
+                    if iw < 0 or iw >= W:
+                        continue
+                    out[:, :, oh, ow] = np.maximum(out[:, :, oh, ow], a[:, :, ih, iw])
+    return (out.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+
+
 def num_threads() -> int:
     return int(lib().oracle_num_threads())
 

@@ -88,6 +88,8 @@ def lib():
                                  C.c_int64, C.c_int32, vp, C.c_size_t, vp]
         L.crisp_conv_spmm.argtypes = [C.POINTER(LayerDesc), C.POINTER(ConvDesc), vp, vp, vp, vp, vp, vp, C.c_int64,
                                       C.c_int32, vp, C.c_size_t, vp]
+        L.crisp_maxpool.argtypes = [C.POINTER(ConvDesc), vp, vp, vp]
+        L.crisp_maxpool.restype = C.c_int32
         L.crisp_spmm_ep.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp, vp, C.c_int64, C.c_int64, C.c_int32, vp,
                                     C.c_int64, C.c_int32, C.POINTER(Epilogue), vp, C.c_size_t, vp]
         L.crisp_conv_spmm_ep.argtypes = [C.POINTER(LayerDesc), C.POINTER(ConvDesc), vp, vp, vp, vp, vp, vp, C.c_int64,
@@ -184,6 +186,12 @@ def crisp_conv_spmm(desc, conv: ConvDesc, row_ptr, col_idx, vals, idx_words, act
                                _stream() if stream == -1 else stream)
     if st != OK:
         raise CrispError("crisp_conv_spmm", st)
+
+
+def crisp_maxpool(pool: ConvDesc, act, out, stream=-1):
+    st = lib().crisp_maxpool(C.byref(pool), _ptr(act), _ptr(out), _stream() if stream == -1 else stream)
+    if st != OK:
+        raise CrispError("crisp_maxpool", st)
 
 
 def crisp_spmm_ep(desc, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, Y, ldy, y_dtype, ep: Epilogue, x_layout=X_KN,
@@ -357,7 +365,7 @@ def conv_needs_scratch(cv, B: int, n: int, m: int, S: int) -> bool:
     return lowering_path(cv, B, n, m, S) == "im2col"
 
 
-def conv_forward(layer: DeviceLayer, cv, act, Y, ldy, y_dtype=Y_F32, X_scratch=None):
+def conv_forward(layer: DeviceLayer, cv, act, Y, ldy, y_dtype=Y_F32, X_scratch=None, ep=None):
     """Product of a packed layer with a convolution input act [C][batch][H][W] on the current stream.
     1x1 stride-1 with an aligned row stride: act is X.  Covered geometries: fused lowering.
     Otherwise crisp_im2col into X_scratch (K x round_up(Ncol, 8), allocated by the caller) followed
@@ -368,15 +376,15 @@ def conv_forward(layer: DeviceLayer, cv, act, Y, ldy, y_dtype=Y_F32, X_scratch=N
     Ncol = cv.batch * Ho * Wo
     path = lowering_path(cv, d.B, d.n, d.m, d.S)
     if path == "none":
-        crisp_spmm(d, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, act, Ncol, Ncol, Y, ldy, y_dtype)
+        crisp_spmm_ep(d, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, act, Ncol, Ncol, Y, ldy, y_dtype, ep)
         return path
     if path == "fused":
-        crisp_conv_spmm(d, conv_desc_of(cv), layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, act, Y, ldy,
-                        y_dtype)
+        crisp_conv_spmm_ep(d, conv_desc_of(cv), layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, act, Y, ldy,
+                           y_dtype, ep)
         return path
     if X_scratch is None:
         raise ValueError("this convolution needs an X scratch buffer of K x round_up(Ncol, 8) bf16")
     ldx = (Ncol + 7) // 8 * 8
     crisp_im2col(conv_desc_of(cv), act, X_scratch, ldx)
-    crisp_spmm(d, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, X_scratch, Ncol, ldx, Y, ldy, y_dtype)
+    crisp_spmm_ep(d, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, X_scratch, Ncol, ldx, Y, ldy, y_dtype, ep)
     return "im2col"

@@ -225,6 +225,19 @@ crisp_status crisp_im2col(const crisp_conv_desc* c, const uint16_t* act, uint16_
     return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
 }
 
+crisp_status crisp_maxpool(const crisp_conv_desc* c, const uint16_t* act, uint16_t* out, void* stream) {
+    if (!c || !act || !out) return CRISP_EINVAL;
+    if (c->C < 1 || c->H < 1 || c->W < 1 || c->batch < 1 || c->kh < 1 || c->kw < 1 || c->stride < 1 || c->pad < 0)
+        return CRISP_ESHAPE;
+    if (c->pad >= c->kh || c->pad >= c->kw) return CRISP_ESHAPE;      // every window must touch the image
+    if (c->H + 2 * c->pad < c->kh || c->W + 2 * c->pad < c->kw) return CRISP_ESHAPE;
+    if (c->act_layout != CRISP_ACT_CBHW) return CRISP_EUNSUPPORTED;
+    if ((int64_t)c->H * c->W >= ((int64_t)1 << 31)) return CRISP_EUNSUPPORTED;
+    if (misaligned(act, 2) || misaligned(out, 2)) return CRISP_EALIGN;
+    hipError_t e = launch_maxpool(*c, act, out, (hipStream_t)stream);
+    return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
+}
+
 static crisp_status check_epilogue(const crisp_epilogue* ep, int64_t Ncol) {
     if (!ep) return CRISP_OK;
     if (misaligned(ep->scale, 4) || misaligned(ep->bias, 4) || misaligned(ep->residual, 16)) return CRISP_EALIGN;

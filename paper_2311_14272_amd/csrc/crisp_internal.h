@@ -35,6 +35,7 @@ hipError_t launch_pack(const Geometry& g, int select_mode, const uint16_t* W, co
                        const int32_t* row_ptr, const int32_t* col_idx, uint16_t* vals, uint32_t* idxw,
                        int32_t* flags, hipStream_t st);
 hipError_t launch_im2col(const crisp_conv_desc& c, const uint16_t* act, uint16_t* X, int64_t ldx, hipStream_t st);
+hipError_t launch_maxpool(const crisp_conv_desc& c, const uint16_t* act, uint16_t* out, hipStream_t st);
 // density_hint and uniform_rows (every block-row keeps the same number of blocks) only steer the
 // choice of kernel; force_shape < 0 lets the library choose (0..3 = shapes of the specialised
 // kernels, 4 = generic LDS-expansion kernel, 5 / 6 = LDS-resident block-rows, narrow / wide).

@@ -109,3 +109,49 @@ hipError_t launch_im2col(const crisp_conv_desc& c, const uint16_t* act, uint16_t
 }
 
 }  // namespace crisp
+
+namespace crisp {
+
+// Max pooling over kh x kw windows of a channel-major activation [C][batch][H][W] (the glue between
+// the first convolution and the first residual stage of the ResNet workload; not part of the paper's
+// method).  Positions outside the image do not take part.  bf16 values are compared as floats; the
+// result is one of the inputs, so no rounding occurs.  One thread per output element; a window that
+// lies wholly outside (cannot happen for pad < kernel size) would yield -inf.
+__global__ __launch_bounds__(256) void maxpool_kernel(Im2colArgs p, int64_t total) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    const int ow = (int)(e % p.Wo);
+    int64_t t = e / p.Wo;
+    const int oh = (int)(t % p.Ho);
+    t /= p.Ho;                      // t = c * batch + image
+    const uint16_t* src = p.act + t * (int64_t)p.H * p.W;
+    float best = -__builtin_inff();
+    uint16_t best_bits = 0xFF80u;   // -inf
+    for (int a = 0; a < p.kh; ++a) {
+        const int ih = oh * p.stride + a - p.pad;
+        if ((unsigned)ih >= (unsigned)p.H) continue;
+        for (int b = 0; b < p.kw; ++b) {
+            const int iw = ow * p.stride + b - p.pad;
+            if ((unsigned)iw >= (unsigned)p.W) continue;
+            const uint16_t bits = src[ih * p.W + iw];
+            const float v = bf16_bits_to_float(bits);
+            if (v > best) { best = v; best_bits = bits; }
+        }
+    }
+    p.X[e] = best_bits;
+}
+
+hipError_t launch_maxpool(const crisp_conv_desc& c, const uint16_t* act, uint16_t* out, hipStream_t st) {
+    Im2colArgs p = {};
+    p.C = c.C; p.H = c.H; p.W = c.W; p.batch = c.batch; p.kh = c.kh; p.kw = c.kw; p.stride = c.stride; p.pad = c.pad;
+    p.Ho = (c.H + 2 * c.pad - c.kh) / c.stride + 1;
+    p.Wo = (c.W + 2 * c.pad - c.kw) / c.stride + 1;
+    p.act = act;
+    p.X = out;
+    const int64_t total = (int64_t)c.C * c.batch * p.Ho * p.Wo;
+    if (total <= 0 || (total + 255) / 256 > INT32_MAX) return hipErrorInvalidValue;
+    maxpool_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(p, total);
+    return hipGetLastError();
+}
+
+}  // namespace crisp

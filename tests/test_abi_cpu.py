@@ -20,7 +20,7 @@ def declared_functions():
 
 def test_library_exports_every_declared_symbol():
     names = declared_functions()
-    assert names == ["crisp_conv_spmm", "crisp_conv_spmm_ep", "crisp_global_budget", "crisp_im2col", "crisp_pack", "crisp_pack_sizes", "crisp_select_mask",
+    assert names == ["crisp_conv_spmm", "crisp_conv_spmm_ep", "crisp_global_budget", "crisp_im2col", "crisp_maxpool", "crisp_pack", "crisp_pack_sizes", "crisp_select_mask",
                      "crisp_select_pack", "crisp_select_pack_batch", "crisp_spmm", "crisp_spmm_ep", "crisp_spmm_timed", "crisp_status_str"]
     L = crisp.lib()
     for n in names:

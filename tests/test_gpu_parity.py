@@ -432,6 +432,18 @@ def test_im2col_matches_oracle():
             assert (Xh[:, Ncol:] == 0xFFFF).all()
 
 
+@pytest.mark.parametrize("shape", [(3, 2, 9, 7, 3, 3, 2, 1), (4, 1, 8, 8, 2, 2, 2, 0), (2, 3, 5, 6, 3, 3, 1, 1), (64, 2, 112, 112, 3, 3, 2, 1)])
+def test_maxpool_matches_oracle(shape):
+    C_, b, H, Wd, kh, kw, stride, pad = shape
+    rng = np.random.default_rng(C_ * 100 + H)
+    act = synth.f32_to_bf16_bits(rng.standard_normal((C_, b, H, Wd), dtype=np.float32))
+    ref = oracle.maxpool(act, kh, kw, stride, pad)
+    out = torch.full(ref.shape, -1, dtype=torch.int16, device="cuda")
+    crisp.crisp_maxpool(crisp.ConvDesc(C_, H, Wd, b, kh, kw, stride, pad, crisp.ACT_CBHW, crisp.X_KN), dev(act), out)
+    torch.cuda.synchronize()
+    assert (synth.bf16_bits_to_f32(host(out, np.uint16)) == synth.bf16_bits_to_f32(ref)).all()
+
+
 def _sample_columns(Ncol, count, rng):
     """First strip, last (ragged) strip and random columns."""
     cols = set(range(min(Ncol, 96))) | set(range(max(0, Ncol - 96), Ncol))

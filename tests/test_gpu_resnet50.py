@@ -72,3 +72,72 @@ def test_resnet50_batch2_all_columns():
 def test_resnet50_batch256_sampled_columns():
     paths = _run_layers(256, 384)
     assert sum(paths.values()) == 53
+
+
+def _bf16_check(Y, Yref, Aref, what):
+    """bf16 outputs with added terms: products within 1e-2 of |W|.|X| (scaled), plus the final
+    rounding (unit roundoff 2^-8) of a value that may exceed that bound."""
+    assert np.isfinite(Y).all(), what
+    err = np.abs(Y - Yref)
+    fro = np.linalg.norm(Y - Yref) / max(np.linalg.norm(Yref), 1e-300)
+    assert fro <= 3e-3, (what, fro)
+    bound = 1e-2 * Aref + 4e-3 * np.abs(Yref) + 1e-30
+    assert (err <= bound).all(), (what, float((err - bound).max()))
+
+
+def test_resnet50_chained_forward_batch8():
+    """The chained bf16 forward (epilogues fused, max-pool, shortcuts) with teacher forcing: every
+    layer's actual device input (and shortcut) is handed to the oracle, which must reproduce that
+    layer's device output; all columns for small layers, sampled columns for the large ones."""
+    from paper_2311_14272_amd import resnet
+    wl = synth.config(5, batch=8)
+    layers, Ws, Gs, sels = [], [], [], []
+    for li, L in enumerate(wl.layers):
+        t = synth.draw_layer(wl, li, with_x=False)
+        sels.append((t["W"], oracle.select(t["W"], t["G"], L.n, L.m, L.B, L.density, L.sal_kind, L.select_mode)))
+        layers.append(crisp.alloc_layer(desc_of(L)))
+        Ws.append(dev(t["W"]))
+        Gs.append(dev(t["G"]))
+    crisp.crisp_select_pack_batch(*crisp.make_batch(layers, Ws, Gs))
+    scales = resnet.layer_scales(wl, layers)
+    need = max([L.K * L.Ncol for L in wl.layers if crisp.conv_needs_scratch(L.conv, L.B, L.n, L.m, L.S)] + [1])
+    xs = torch.empty(need, dtype=torch.int16, device="cuda")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(wl.seed)
+    x = torch.randn((3, 8, 224, 224), generator=gen, device="cuda").to(torch.bfloat16).view(torch.int16)
+    seen = []
+
+    def record(name, L, inp, residual, out):
+        torch.cuda.synchronize()
+        if name == "maxpool":
+            got = host(out, np.uint16).reshape(L.C, L.batch, 56, 56)
+            ref = oracle.maxpool(host(inp, np.uint16).reshape(L.C, L.batch, L.H, L.W), 3, 3, 2, 1)
+            assert (synth.bf16_bits_to_f32(got) == synth.bf16_bits_to_f32(ref)).all(), "maxpool"
+            seen.append(name)
+            return
+        li = [l.name for l in wl.layers].index(name)
+        W, sel = sels[li]
+        cv = L.conv
+        rng = np.random.default_rng(2000 + li)
+        cols = np.arange(L.Ncol) if L.S * L.K * L.Ncol <= 3e9 else np.unique(rng.integers(0, L.Ncol, 512))
+        idx, inside = lowering_gather_index(cv.C, cv.H, cv.W, cv.batch, cv.kh, cv.kw, cv.stride, cv.pad, cols)
+        g = torch.take(inp.view(-1), torch.from_numpy(idx).cuda()).cpu().numpy().view(np.uint16)
+        X = np.ascontiguousarray(np.where(inside, g, np.uint16(0)))
+        Y0, A0 = oracle.gemm_masked(W, sel.mask, X)
+        tcols = torch.from_numpy(cols).cuda()
+        res = None
+        if residual is not None:
+            res = synth.bf16_bits_to_f32(residual.view(L.S, L.Ncol)[:, tcols].cpu().numpy().view(np.uint16)).astype(np.float64)
+        scale = scales[li].cpu().numpy()
+        relu = not name.endswith(".ds")
+        Yref, Aref = oracle.epilogue(Y0, A0, scale, None, res, relu)
+        Yg = synth.bf16_bits_to_f32(out.view(L.S, L.Ncol)[:, tcols].cpu().numpy().view(np.uint16)).astype(np.float64)
+        _bf16_check(Yg, Yref, Aref, name)
+        seen.append(name)
+        print("chained %-8s ok (%d columns)" % (name, len(cols)), flush=True)
+
+    out = resnet.forward(wl, layers, x, scales, xs, record)
+    torch.cuda.synchronize()
+    assert len(seen) == 54 and out.shape == (2048, 8 * 7 * 7)
+    final = synth.bf16_bits_to_f32(host(out, np.uint16))
+    assert np.isfinite(final).all() and (final >= 0).all() and final.max() > 0

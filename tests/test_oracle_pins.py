@@ -500,3 +500,18 @@ def test_epilogue_closed_forms():
     assert (out == np.maximum(Y, 0)).all()
     out, _ = oracle.epilogue(Y, None, bias=bias)
     assert (out == Y + np.array([[1.0], [-1.0]])).all()
+
+
+def test_maxpool_hand_example():
+    """3x3 / stride 2 / pad 1 max-pool of a 4x4 image, worked out by hand (windows clipped at the border)."""
+    img = np.array([[1, 2, 3, 4], [5, 6, 7, 8], [-1, -2, -3, -4], [9, 0, 0, -9]], dtype=np.float32)
+    bits = synth.f32_to_bf16_bits(img).reshape(1, 1, 4, 4)
+    out = synth.bf16_bits_to_f32(oracle.maxpool(bits, 3, 3, 2, 1)).reshape(2, 2)
+    # windows: rows {0,1} x cols {0,1}; rows {0,1} x cols {1,2,3}; rows {1,2,3} x cols {0,1}; rows {1,2,3} x cols {1,2,3}
+    assert (out == np.array([[6, 8], [9, 8]], dtype=np.float32)).all()
+    # 2x2 / stride 2 without padding on an all-negative image: padding must not contribute zeros
+    neg = synth.f32_to_bf16_bits(-np.arange(1, 17, dtype=np.float32).reshape(4, 4)).reshape(1, 1, 4, 4)
+    out = synth.bf16_bits_to_f32(oracle.maxpool(neg, 2, 2, 2, 0)).reshape(2, 2)
+    assert (out == np.array([[-1, -3], [-9, -11]], dtype=np.float32)).all()
+    out = synth.bf16_bits_to_f32(oracle.maxpool(neg, 3, 3, 2, 1)).reshape(2, 2)
+    assert (out == np.array([[-1, -2], [-5, -6]], dtype=np.float32)).all()
