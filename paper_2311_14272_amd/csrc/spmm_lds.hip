@@ -196,7 +196,7 @@ void spmm_lds_kernel(SpmmArgs p, LdsSched sch) {
     };
     // accumulator register r of a 32x32 tile is row 8*(r/4) + 4*hh + r%4, column jj; rows past S
     // and lanes past the last column fall outside the store resource's range and are dropped
-    auto store_strip_t = [&](const f32x16 (&acc)[RT][NACC], bool col_ok, int64_t col0, auto as_bf16) __attribute__((always_inline)) {
+    auto store_strip_t = [&](const f32x16 (&acc)[RT][NACC], bool col_ok, int64_t col0, auto as_bf16, auto with_ep) __attribute__((always_inline)) {
         const uint32_t y_off = col_ok ? (uint32_t)(4 * hh) * yrow_bytes + (uint32_t)col0 * esz : 0x80000000u;
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt)
@@ -206,7 +206,7 @@ void spmm_lds_kernel(SpmmArgs p, LdsSched sch) {
                 float v[NACC];
 #pragma unroll
                 for (int c = 0; c < NACC; ++c) v[c] = acc[rt][c][r];
-                {
+                if constexpr (decltype(with_ep)::value) {
                     const int row = bi * B + rt * 32 + 8 * (r >> 2) + (r & 3) + 4 * hh;
                     apply_epilogue<NACC>(p, row, col0, col_ok && row < p.S, v);
                 }
@@ -236,8 +236,13 @@ void spmm_lds_kernel(SpmmArgs p, LdsSched sch) {
             }
     };
     auto store_strip = [&](const f32x16 (&acc)[RT][NACC], bool col_ok, int64_t col0) __attribute__((always_inline)) {
-        if (p.y_bf16) store_strip_t(acc, col_ok, col0, std::true_type{});
-        else store_strip_t(acc, col_ok, col0, std::false_type{});
+        if (p.ep_on) {
+            if (p.y_bf16) store_strip_t(acc, col_ok, col0, std::true_type{}, std::true_type{});
+            else store_strip_t(acc, col_ok, col0, std::false_type{}, std::true_type{});
+        } else {
+            if (p.y_bf16) store_strip_t(acc, col_ok, col0, std::true_type{}, std::false_type{});
+            else store_strip_t(acc, col_ok, col0, std::false_type{}, std::false_type{});
+        }
     };
     // lane part of the X addresses of a strip (bytes); lanes past the last column read column 0
     auto lane_offset = [&](int strip, bool& col_ok, int64_t& col0) __attribute__((always_inline)) {

@@ -706,50 +706,66 @@ void spmm_reg_kernel(SpmmArgs p) {
     const rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(
         reinterpret_cast<char*>(p.Y) + (int64_t)bi * B * p.ldy * esz, 0, (uint32_t)rows_here * row_bytes, 0x00020000);
     const uint32_t y_off = col_ok ? (uint32_t)(4 * hh) * row_bytes + (uint32_t)col0 * esz : 0x80000000u;
-    auto store_row = [&](int tile_row, const float (&vin)[NACC]) {
-        const uint32_t off = y_off + (uint32_t)tile_row * row_bytes;
-        float v[NACC];
+    // The four (epilogue yes/no) x (bf16/fp32 output) variants of the store loop are separate
+    // copies chosen once per wave, so the loop itself holds no branches.
+    auto emit = [&](auto with_ep, auto as_bf16, auto rows, auto row_source) __attribute__((always_inline)) {
+        constexpr int ROWS = decltype(rows)::value;
+        auto store_row = [&](int tile_row, const float (&vin)[NACC]) __attribute__((always_inline)) {
+            const uint32_t off = y_off + (uint32_t)tile_row * row_bytes;
+            float v[NACC];
 #pragma unroll
-        for (int c = 0; c < NACC; ++c) v[c] = vin[c];
-        {
-            const int row = bi * B + tile_row + 4 * hh;
-            apply_epilogue<NACC>(p, row, col0, col_ok && row < p.S, v);
-        }
-        if (p.y_bf16) {
-            uint32_t pk[WD];
+            for (int c = 0; c < NACC; ++c) v[c] = vin[c];
+            if constexpr (decltype(with_ep)::value) {
+                const int row = bi * B + tile_row + 4 * hh;
+                apply_epilogue<NACC>(p, row, col0, col_ok && row < p.S, v);
+            }
+            if constexpr (decltype(as_bf16)::value) {
+                uint32_t pk[WD];
 #pragma unroll
-            for (int c = 0; c < WD; ++c) {
-                const f32x2 two = {v[2 * c], v[2 * c + 1]};
-                pk[c] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2));  // v_cvt_pk_bf16_f32 (RNE)
-            }
-            if constexpr (WD == 1) {
-                __builtin_amdgcn_raw_buffer_store_b32(pk[0], ry, off, 0, 0);
+                for (int c = 0; c < WD; ++c) {
+                    const f32x2 two = {v[2 * c], v[2 * c + 1]};
+                    pk[c] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2));  // v_cvt_pk_bf16_f32 (RNE)
+                }
+                if constexpr (WD == 1) {
+                    __builtin_amdgcn_raw_buffer_store_b32(pk[0], ry, off, 0, 0);
+                } else {
+                    const u32x2 two = {pk[0], pk[WD - 1]};
+                    __builtin_amdgcn_raw_buffer_store_b64(two, ry, off, 0, 0);
+                }
             } else {
-                const u32x2 two = {pk[0], pk[WD - 1]};
-                __builtin_amdgcn_raw_buffer_store_b64(two, ry, off, 0, 0);
+                if constexpr (WD == 1) {
+                    const u32x2 two = {__float_as_uint(v[0]), __float_as_uint(v[1])};
+                    __builtin_amdgcn_raw_buffer_store_b64(two, ry, off, 0, 0);
+                } else {
+                    const u32x4 four = {__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[NACC - 2]),
+                                        __float_as_uint(v[NACC - 1])};
+                    __builtin_amdgcn_raw_buffer_store_b128(four, ry, off, 0, 0);
+                }
             }
-        } else {
-            if constexpr (WD == 1) {
-                const u32x2 two = {__float_as_uint(v[0]), __float_as_uint(v[1])};
-                __builtin_amdgcn_raw_buffer_store_b64(two, ry, off, 0, 0);
-            } else {
-                const u32x4 four = {__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[NACC - 2]),
-                                    __float_as_uint(v[NACC - 1])};
-                __builtin_amdgcn_raw_buffer_store_b128(four, ry, off, 0, 0);
-            }
+        };
+#pragma unroll
+        for (int q = 0; q < ROWS; ++q) {
+            float v[NACC];
+            const int pr = row_source(q, v);       // accumulator row index rt*16 + r
+            const int rt = pr >> 4, r = pr & 15;
+            store_row(rt * 32 + 8 * (r >> 2) + (r & 3), v);
         }
     };
-
+    auto finish = [&](auto rows, auto row_source) __attribute__((always_inline)) {
+        if (p.ep_on) {
+            if (p.y_bf16) emit(std::true_type{}, std::true_type{}, rows, row_source);
+            else emit(std::true_type{}, std::false_type{}, rows, row_source);
+        } else {
+            if (p.y_bf16) emit(std::false_type{}, std::true_type{}, rows, row_source);
+            else emit(std::false_type{}, std::false_type{}, rows, row_source);
+        }
+    };
     if constexpr (NWK == 1) {
+        finish(std::integral_constant<int, RT * 16>{}, [&](int q, float (&v)[NACC]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float v[NACC];
-#pragma unroll
-                for (int c = 0; c < NACC; ++c) v[c] = acc[rt][c][r];
-                store_row(rt * 32 + 8 * (r >> 2) + (r & 3), v);
-            }
+            for (int c = 0; c < NACC; ++c) v[c] = acc[q >> 4][c][q & 15];
+            return q;
+        });
     } else {
         // partial sums of the NWK waves -> LDS, then wave w adds up and stores every NWK-th row
         __shared__ float red[NWK][RT * 16][NACC][64];
@@ -760,10 +776,8 @@ void spmm_reg_kernel(SpmmArgs p) {
 #pragma unroll
                 for (int c = 0; c < NACC; ++c) red[wave][rt * 16 + r][c][lane] = acc[rt][c][r];
         __syncthreads();
-#pragma unroll
-        for (int q = 0; q < RT * 16 / NWK; ++q) {
+        finish(std::integral_constant<int, RT * 16 / NWK>{}, [&](int q, float (&v)[NACC]) __attribute__((always_inline)) {
             const int pr = q * NWK + wave;
-            float v[NACC];
 #pragma unroll
             for (int c = 0; c < NACC; ++c) {
                 float s = red[0][pr][c][lane];
@@ -771,9 +785,8 @@ void spmm_reg_kernel(SpmmArgs p) {
                 for (int w = 1; w < NWK; ++w) s += red[w][pr][c][lane];
                 v[c] = s;
             }
-            const int rt = pr >> 4, r = pr & 15;
-            store_row(rt * 32 + 8 * (r >> 2) + (r & 3), v);
-        }
+            return pr;
+        });
     }
 }
 
