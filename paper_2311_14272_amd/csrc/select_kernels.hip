@@ -1,22 +1,11 @@
 // Mask selection kernels: saliency -> N:M choice -> block scores -> block choice.
 // Alg. 1 lines 2, 4-6 and 10 of the CRISP paper; every ordering decision below is a total
 // order so that the result is unique and reproducible bit for bit.
-#include "crisp_internal.h"
+#include "select_lane.h"
 
 namespace crisp {
 
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-
-// Saliency of one element (Sec. 3.4, Eq. 1): one fp32 multiply, then the absolute value.
-template <int KIND>
-__device__ __forceinline__ float saliency_of(uint16_t w, float tg) {
-    if (KIND == CRISP_SAL_GIVEN) return tg;
-    if (KIND == CRISP_SAL_GRAD) return fabsf(__fmul_rn(bf16_bits_to_float(w), tg));
-    return fabsf(bf16_bits_to_float(w));
-}
-
-// One workgroup per B x B block, Q lanes per block row (Q * CPT = B columns, CPT = 16 or 8).
+// One workgroup per B x B block, Q lanes per block row (Q * CPT = B columns, CPT = 16).
 // Each lane loads its CPT weights (and gradient / saliency values) with 16-byte loads, ranks
 // every aligned group of M columns (keep the n first under: larger saliency first, on a tie the
 // smaller column first), and leaves "saliency if kept else +0" in LDS.  The Q lanes of a row
@@ -33,37 +22,6 @@ __device__ __forceinline__ float saliency_of(uint16_t w, float tg) {
 // model's layers have block grids of a few dozen to a few hundred workgroups each, far too few to
 // fill 256 compute units one layer at a time.  Workgroup ids are mapped to (layer, block) through
 // the prefix sums in `first`.
-#define SEL_BATCH CRISP_SELECT_BATCH
-struct SelLayer {
-    int S, K, n, Kb, Sb, mwpr, k_row, clear_flag;
-    int wbits, slots, wpr, pad_;  // bits per position, packed slots and position words per block row
-    const uint16_t* W;
-    const float* TG;
-    uint32_t* nm_mask;
-    double* score;
-    uint16_t* st_vals;            // staging [Sb*Kb][B][slots]
-    uint32_t* st_idxw;            // staging [Sb*Kb][B][wpr]
-    int32_t* st_viol;             // staging [Sb*Kb]: an aligned group of four holds more than two kept
-    int32_t* flags;               // the layer's flags; preset by the scoring kernel, cleared by the gather
-    int32_t* row_ptr;
-    int32_t* col_idx;
-    uint16_t* vals;
-    uint32_t* idxw;
-};
-struct SelBatch {
-    int n;
-    int first[SEL_BATCH + 1];     // first workgroup of each layer in the scoring launch (blocks of the grid)
-    int firstk[SEL_BATCH + 1];    // first workgroup of each layer in the gather launch (kept blocks)
-    SelLayer L[SEL_BATCH];
-};
-
-__device__ __forceinline__ uint32_t slot_position_of(uint32_t bits, int j, bool outside) {
-    // j-th kept column of the group; 0 when the group holds fewer; j for a group outside the matrix
-    if (outside) return (uint32_t)j;
-    for (int i = 0; i < j; ++i) bits &= bits - 1u;
-    return bits ? (uint32_t)(__ffs(bits) - 1) : 0u;
-}
-
 template <int B, int M, int KIND, bool VEC, bool PACK>
 __global__ __launch_bounds__(B * (B / 16)) void score_select_kernel(SelBatch bt) {
     int li = 0;
@@ -75,7 +33,7 @@ __global__ __launch_bounds__(B * (B / 16)) void score_select_kernel(SelBatch bt)
     const float* __restrict__ TG = sa.TG;
     uint32_t* __restrict__ nm_mask = sa.nm_mask;
     double* __restrict__ score = sa.score;
-    constexpr int CPT = 16;          // columns per lane
+    constexpr int CPT = LANE_COLS;   // columns per lane
     constexpr int Q = B / CPT;       // lanes per block row (1, 2 or 4)
     constexpr int LDT = B + 4;       // padded LDS row stride in floats (keeps 16-byte alignment)
     constexpr int WMAX = (B * 3 + 31) / 32;   // upper bound of position words per block row
@@ -98,110 +56,21 @@ __global__ __launch_bounds__(B * (B / 16)) void score_select_kernel(SelBatch bt)
         }
         __syncthreads();
     }
-    uint32_t bits = 0;
+    uint32_t bits;
     {
-        uint16_t w[CPT];
-        float tg[CPT];
+        constexpr bool NEEDW = PACK || KIND != CRISP_SAL_GIVEN;
         const int len = (s < S) ? min(CPT, K - k0) : 0;   // columns of this lane that exist (may be <= 0)
-        const size_t e0 = (size_t)s * K + k0;
-        if (VEC && s < S) {
-            if (PACK || KIND != CRISP_SAL_GIVEN) {
-#pragma unroll
-                for (int i = 0; i < CPT / 8; ++i) {
-                    const u32x4 v = *reinterpret_cast<const u32x4*>(W + e0 + 8 * i);
-#pragma unroll
-                    for (int x = 0; x < 4; ++x) {
-                        w[8 * i + 2 * x] = (uint16_t)(v[x] & 0xFFFFu);
-                        w[8 * i + 2 * x + 1] = (uint16_t)(v[x] >> 16);
-                    }
-                }
-            }
-            if (KIND != CRISP_SAL_MAG) {
-#pragma unroll
-                for (int i = 0; i < CPT / 4; ++i) {
-                    const f32x4 v = *reinterpret_cast<const f32x4*>(TG + e0 + 4 * i);
-#pragma unroll
-                    for (int x = 0; x < 4; ++x) tg[4 * i + x] = v[x];
-                }
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < CPT; ++i) {
-                w[i] = ((PACK || KIND != CRISP_SAL_GIVEN) && i < len) ? W[e0 + i] : (uint16_t)0;
-                tg[i] = (KIND != CRISP_SAL_MAG && i < len) ? TG[e0 + i] : 0.0f;
-            }
-        }
-        float kept_t[CPT];
-#pragma unroll
-        for (int g = 0; g < CPT / M; ++g) {
-            float t[M];
-#pragma unroll
-            for (int i = 0; i < M; ++i) t[i] = saliency_of<KIND>(w[g * M + i], tg[g * M + i]);
-            const int glen = len - g * M;
-#pragma unroll
-            for (int i = 0; i < M; ++i) {
-                int before = 0;
-#pragma unroll
-                for (int j = 0; j < M; ++j) before += (j < glen) && (t[j] > t[i] || (t[j] == t[i] && j < i));
-                const bool kept = (i < glen) && (before < n);
-                bits |= (kept ? 1u : 0u) << (g * M + i);
-                kept_t[g * M + i] = kept ? t[i] : 0.0f;
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < CPT / 4; ++i) {
-            const f32x4 v = {kept_t[4 * i], kept_t[4 * i + 1], kept_t[4 * i + 2], kept_t[4 * i + 3]};
-            *reinterpret_cast<f32x4*>(&tkept[r * LDT + c0 + 4 * i]) = v;
-        }
+        LaneRaw raw;
+        lane_load<KIND, VEC, NEEDW>(raw, W, TG, (size_t)min(s, S - 1) * K, k0, K);
+        bits = lane_select<M, KIND, NEEDW, true>(raw, n, len, &tkept[r * LDT + c0]);
         if constexpr (PACK) {
-            // the lane's CPT / M groups: n slots each, kept values in ascending column order, then
-            // zeros; positions per the canonical rules (Sec. 3.1 / 3.5 storage format)
-            if (!VEC || s >= S) {
-#pragma unroll
-                for (int i = 0; i < CPT; ++i)
-                    if (i >= len) w[i] = 0;
-            }
+            // packed form of the lane's groups, to the staging area of block (bi, bj)
             const size_t blk = (size_t)bi * Kb + bj;
             const int slot0 = (c0 / M) * n;
             uint16_t* sv = sa.st_vals + (blk * B + r) * sa.slots + slot0;
-            uint64_t stream = 0;                 // at most 16 slots x 3 bits
-            int nb = 0;
-            bool violates = false;
-#pragma unroll
-            for (int g = 0; g < CPT / M; ++g) {
-                const uint32_t gb = (bits >> (g * M)) & ((1u << M) - 1u);
-                const bool outside = (s >= S) || (k0 + g * M >= K);
-                uint16_t v[M];
-#pragma unroll
-                for (int x = 0; x < M; ++x) v[x] = 0;
-                int filled = 0;
-#pragma unroll
-                for (int o = 0; o < M; ++o) {
-                    const bool on = (gb >> o) & 1u;
-#pragma unroll
-                    for (int x = 0; x < M; ++x)
-                        if (on && filled == x) v[x] = w[g * M + o];
-                    filled += on;
-                }
-#pragma unroll
-                for (int x = 0; x < M; ++x) {
-                    if (x < n) {
-                        sv[g * n + x] = v[x];
-                        stream |= (uint64_t)slot_position_of(gb, x, outside) << nb;
-                        nb += sa.wbits;
-                    }
-                }
-                violates = violates || __popc(gb & 0xFu) > 2 || __popc(gb >> 4) > 2;
-            }
-            const int bit0 = slot0 * sa.wbits, wi = bit0 >> 5, sh = bit0 & 31;
-            uint32_t* prow = pos_lds + r * WMAX;
-            const uint32_t p0 = (uint32_t)(stream << sh);
-            const uint32_t p1 = (uint32_t)(sh ? (stream >> (32 - sh)) : (stream >> 32));
-            const uint32_t p2 = (uint32_t)(sh ? (stream >> (64 - sh)) : 0u);
-            if (p0) atomicOr(prow + wi, p0);
-            if (p1 && wi + 1 < WMAX) atomicOr(prow + wi + 1, p1);
-            if (p2 && wi + 2 < WMAX) atomicOr(prow + wi + 2, p2);
-            if (violates) viol_lds = 1;
+            uint16_t w[CPT];
+            lane_weights(raw, len, w);
+            if (lane_pack<M>(w, bits, n, sa.wbits, s >= S, k0, K, sv, pos_lds + r * WMAX, slot0, WMAX)) viol_lds = 1;
         }
     }
     // mask: the Q lanes of a row hold 16 bits each; pairs of lanes form one 32-bit word
