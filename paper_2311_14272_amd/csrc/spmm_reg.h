@@ -578,6 +578,75 @@ struct BlockBody {
     }
 };
 
+// Output of one wave: ROWS accumulator rows of a 64*WD-column strip of block-row bi.
+// Accumulator register r of a 32x32 tile is row 8*(r/4) + 4*hh + r%4 of the tile, column jj; the
+// NACC tiles of a lane are consecutive columns.  row_source(q, v) fills v with the lane's NACC
+// values of the q-th row to store and returns its accumulator row index rt*16 + r.  Y is written
+// through a buffer resource that spans the block-row's existing rows: rows past S and lanes past
+// the last column fall outside its range and the hardware drops them, so the stores need no
+// branches.  (Ncol is a multiple of 4 here, so a lane's columns are all inside or all outside.)
+// The four (epilogue yes/no) x (bf16/fp32 output) variants of the store loop are separate copies
+// chosen once per wave, so the loop itself holds no branches.
+template <int B, int WD, int ROWS, typename RowSource>
+__device__ __forceinline__ void store_rows(const SpmmArgs& p, int bi, int hh, int64_t col0, bool col_ok, RowSource row_source) {
+    constexpr int NACC = 2 * WD;
+    const uint32_t esz = p.y_bf16 ? 2u : 4u;
+    const uint32_t row_bytes = (uint32_t)p.ldy * esz;
+    const int rows_here = min(B, p.S - bi * B);
+    const rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(
+        reinterpret_cast<char*>(p.Y) + (int64_t)bi * B * p.ldy * esz, 0, (uint32_t)rows_here * row_bytes, 0x00020000);
+    const uint32_t y_off = col_ok ? (uint32_t)(4 * hh) * row_bytes + (uint32_t)col0 * esz : 0x80000000u;
+    auto emit = [&](auto with_ep, auto as_bf16) __attribute__((always_inline)) {
+        auto store_row = [&](int tile_row, const float (&vin)[NACC]) __attribute__((always_inline)) {
+            const uint32_t off = y_off + (uint32_t)tile_row * row_bytes;
+            float v[NACC];
+#pragma unroll
+            for (int c = 0; c < NACC; ++c) v[c] = vin[c];
+            if constexpr (decltype(with_ep)::value) {
+                const int row = bi * B + tile_row + 4 * hh;
+                apply_epilogue<NACC>(p, row, col0, col_ok && row < p.S, v);
+            }
+            if constexpr (decltype(as_bf16)::value) {
+                uint32_t pk[WD];
+#pragma unroll
+                for (int c = 0; c < WD; ++c) {
+                    const f32x2 two = {v[2 * c], v[2 * c + 1]};
+                    pk[c] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2));  // v_cvt_pk_bf16_f32 (RNE)
+                }
+                if constexpr (WD == 1) {
+                    __builtin_amdgcn_raw_buffer_store_b32(pk[0], ry, off, 0, 0);
+                } else {
+                    const u32x2 two = {pk[0], pk[WD - 1]};
+                    __builtin_amdgcn_raw_buffer_store_b64(two, ry, off, 0, 0);
+                }
+            } else {
+                if constexpr (WD == 1) {
+                    const u32x2 two = {__float_as_uint(v[0]), __float_as_uint(v[1])};
+                    __builtin_amdgcn_raw_buffer_store_b64(two, ry, off, 0, 0);
+                } else {
+                    const u32x4 four = {__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[NACC - 2]),
+                                        __float_as_uint(v[NACC - 1])};
+                    __builtin_amdgcn_raw_buffer_store_b128(four, ry, off, 0, 0);
+                }
+            }
+        };
+#pragma unroll
+        for (int q = 0; q < ROWS; ++q) {
+            float v[NACC];
+            const int pr = row_source(q, v);       // accumulator row index rt*16 + r
+            const int rt = pr >> 4, r = pr & 15;
+            store_row(rt * 32 + 8 * (r >> 2) + (r & 3), v);
+        }
+    };
+    if (p.ep_on) {
+        if (p.y_bf16) emit(std::true_type{}, std::true_type{});
+        else emit(std::true_type{}, std::false_type{});
+    } else {
+        if (p.y_bf16) emit(std::false_type{}, std::true_type{});
+        else emit(std::false_type{}, std::false_type{});
+    }
+}
+
 // Two waves per SIMD (256 registers each) wherever the lane's slice of the packed block is small
 // enough to fit beside 128 accumulators and 64 X registers; the wide-strip kernels of the denser
 // patterns would spill there and run with one wave per SIMD instead.
@@ -694,74 +763,9 @@ void spmm_reg_kernel(SpmmArgs p) {
         }
     }
 
-    // ---- epilogue: accumulator register r of a 32x32 tile is row 8*(r/4) + 4*hh + r%4 of the
-    //      tile, column jj; the NACC tiles of a lane are consecutive columns.  Y is written
-    //      through a buffer resource that spans the block-row's existing rows: rows past S and
-    //      lanes past the last column fall outside its range and the hardware drops them, so the
-    //      stores need no branches.  (Ncol is a multiple of 4 here, so a lane's columns are all
-    //      inside or all outside.)
-    const uint32_t esz = p.y_bf16 ? 2u : 4u;
-    const uint32_t row_bytes = (uint32_t)p.ldy * esz;
-    const int rows_here = min(B, p.S - bi * B);
-    const rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(
-        reinterpret_cast<char*>(p.Y) + (int64_t)bi * B * p.ldy * esz, 0, (uint32_t)rows_here * row_bytes, 0x00020000);
-    const uint32_t y_off = col_ok ? (uint32_t)(4 * hh) * row_bytes + (uint32_t)col0 * esz : 0x80000000u;
-    // The four (epilogue yes/no) x (bf16/fp32 output) variants of the store loop are separate
-    // copies chosen once per wave, so the loop itself holds no branches.
-    auto emit = [&](auto with_ep, auto as_bf16, auto rows, auto row_source) __attribute__((always_inline)) {
-        constexpr int ROWS = decltype(rows)::value;
-        auto store_row = [&](int tile_row, const float (&vin)[NACC]) __attribute__((always_inline)) {
-            const uint32_t off = y_off + (uint32_t)tile_row * row_bytes;
-            float v[NACC];
-#pragma unroll
-            for (int c = 0; c < NACC; ++c) v[c] = vin[c];
-            if constexpr (decltype(with_ep)::value) {
-                const int row = bi * B + tile_row + 4 * hh;
-                apply_epilogue<NACC>(p, row, col0, col_ok && row < p.S, v);
-            }
-            if constexpr (decltype(as_bf16)::value) {
-                uint32_t pk[WD];
-#pragma unroll
-                for (int c = 0; c < WD; ++c) {
-                    const f32x2 two = {v[2 * c], v[2 * c + 1]};
-                    pk[c] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2));  // v_cvt_pk_bf16_f32 (RNE)
-                }
-                if constexpr (WD == 1) {
-                    __builtin_amdgcn_raw_buffer_store_b32(pk[0], ry, off, 0, 0);
-                } else {
-                    const u32x2 two = {pk[0], pk[WD - 1]};
-                    __builtin_amdgcn_raw_buffer_store_b64(two, ry, off, 0, 0);
-                }
-            } else {
-                if constexpr (WD == 1) {
-                    const u32x2 two = {__float_as_uint(v[0]), __float_as_uint(v[1])};
-                    __builtin_amdgcn_raw_buffer_store_b64(two, ry, off, 0, 0);
-                } else {
-                    const u32x4 four = {__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[NACC - 2]),
-                                        __float_as_uint(v[NACC - 1])};
-                    __builtin_amdgcn_raw_buffer_store_b128(four, ry, off, 0, 0);
-                }
-            }
-        };
-#pragma unroll
-        for (int q = 0; q < ROWS; ++q) {
-            float v[NACC];
-            const int pr = row_source(q, v);       // accumulator row index rt*16 + r
-            const int rt = pr >> 4, r = pr & 15;
-            store_row(rt * 32 + 8 * (r >> 2) + (r & 3), v);
-        }
-    };
-    auto finish = [&](auto rows, auto row_source) __attribute__((always_inline)) {
-        if (p.ep_on) {
-            if (p.y_bf16) emit(std::true_type{}, std::true_type{}, rows, row_source);
-            else emit(std::true_type{}, std::false_type{}, rows, row_source);
-        } else {
-            if (p.y_bf16) emit(std::false_type{}, std::true_type{}, rows, row_source);
-            else emit(std::false_type{}, std::false_type{}, rows, row_source);
-        }
-    };
+    // ---- epilogue ---------------------------------------------------------------------------
     if constexpr (NWK == 1) {
-        finish(std::integral_constant<int, RT * 16>{}, [&](int q, float (&v)[NACC]) __attribute__((always_inline)) {
+        store_rows<B, WD, RT * 16>(p, bi, hh, col0, col_ok, [&](int q, float (&v)[NACC]) __attribute__((always_inline)) {
 #pragma unroll
             for (int c = 0; c < NACC; ++c) v[c] = acc[q >> 4][c][q & 15];
             return q;
@@ -776,7 +780,7 @@ void spmm_reg_kernel(SpmmArgs p) {
 #pragma unroll
                 for (int c = 0; c < NACC; ++c) red[wave][rt * 16 + r][c][lane] = acc[rt][c][r];
         __syncthreads();
-        finish(std::integral_constant<int, RT * 16 / NWK>{}, [&](int q, float (&v)[NACC]) __attribute__((always_inline)) {
+        store_rows<B, WD, RT * 16 / NWK>(p, bi, hh, col0, col_ok, [&](int q, float (&v)[NACC]) __attribute__((always_inline)) {
             const int pr = q * NWK + wave;
 #pragma unroll
             for (int c = 0; c < NACC; ++c) {
