@@ -240,10 +240,11 @@ CRISP_API crisp_status crisp_im2col(const crisp_conv_desc *conv, const uint16_t 
  *   steer the choice of kernel (how many blocks a block-row holds, whether all
  *   rows hold the same number); a wrong or out-of-range density costs speed, never
  *   correctness.
- *   ws is unused (spmm_ws_bytes is 0).  With ws == NULL, ws_bytes in 1..7 forces
+ *   ws is unused (spmm_ws_bytes is 0).  With ws == NULL, ws_bytes in 1..11 forces
  *   launch shape ws_bytes - 1 (0..3 register-expansion kernels: wide strips, narrow
  *   strips, 4- and 8-way split of the block list; 4 generic LDS-expansion kernel;
- *   5 / 6 block-row resident in LDS with narrow / wide strips) for tests and
+ *   5 / 6 block-row resident in LDS with narrow / wide strips; 7..10 shapes 0..3
+ *   with the sparse matrix-core instruction where the pattern allows it) for tests and
  *   tuning; a shape that does not apply to the problem falls back to the automatic
  *   choice.  Results agree across shapes within the summation-order tolerance.
  * Errors: EINVAL, ESHAPE, EALIGN, EUNSUPPORTED (x_layout), EDEVICE.

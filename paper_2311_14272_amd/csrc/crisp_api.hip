@@ -111,7 +111,7 @@ crisp_status crisp_select_mask(const crisp_layer_desc* desc, const uint16_t* W, 
     if (g.Kb > 4096) return CRISP_EUNSUPPORTED;
     if (desc->select_mode == CRISP_LAYER_TOPK && ((int64_t)g.Sb * g.Kb > 8192 || g.Sb > 1024)) return CRISP_EUNSUPPORTED;
     hipError_t e = launch_select(g, desc->sal_kind, desc->select_mode, W, T_or_G, nm_mask, row_ptr, col_idx,
-                                 block_score, score, (hipStream_t)stream);
+                                 score, (hipStream_t)stream);
     return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
 }
 
@@ -161,13 +161,12 @@ crisp_status crisp_select_pack_batch(int32_t n_layers, const crisp_layer_desc* d
     for (int i = 0; i < n_layers && e == hipSuccess; ++i) {
         if (done[i]) continue;
         const Geometry& g = geo[i];
-        const size_t score_bytes = ((size_t)g.Sb * g.Kb * sizeof(double) + 15) / 16 * 16;
         double* score = bufs[i].block_score ? bufs[i].block_score : (double*)bufs[i].ws;
         if (!select_pack_fusable(g, descs[i].select_mode)) {
             // uneven rows or very wide grids: the two steps one after the other
             done[i] = 1;
             e = launch_select(g, descs[i].sal_kind, descs[i].select_mode, bufs[i].W, bufs[i].T_or_G, bufs[i].nm_mask,
-                              bufs[i].row_ptr, bufs[i].col_idx, bufs[i].block_score, score, (hipStream_t)stream);
+                              bufs[i].row_ptr, bufs[i].col_idx, score, (hipStream_t)stream);
             if (e == hipSuccess)
                 e = launch_pack(g, descs[i].select_mode, bufs[i].W, bufs[i].nm_mask, bufs[i].row_ptr, bufs[i].col_idx,
                                 bufs[i].vals, bufs[i].idx_words, bufs[i].flags, (hipStream_t)stream);
@@ -193,7 +192,6 @@ crisp_status crisp_select_pack_batch(int32_t n_layers, const crisp_layer_desc* d
             done[j] = 1;
             ++cnt;
         }
-        (void)score_bytes;
         e = launch_select_pack_batch(cnt, gg, descs[i].sal_kind, pp, (hipStream_t)stream);
     }
     return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
@@ -265,7 +263,7 @@ static crisp_status spmm_impl(const crisp_layer_desc* desc, const int32_t* row_p
         return CRISP_EALIGN;
     if (x_layout != CRISP_X_KN) return CRISP_EUNSUPPORTED;
     { crisp_status es = check_epilogue(ep, Ncol); if (es != CRISP_OK) return es; }
-    // ws_bytes doubles as a tuning knob when ws is NULL: 0 = automatic launch shape, 1..7 force
+    // ws_bytes doubles as a tuning knob when ws is NULL: 0 = automatic launch shape, 1..11 force
     // shape (value - 1); results do not depend on it.
     const int force_shape = (!ws && ws_bytes >= 1 && ws_bytes <= 11) ? (int)ws_bytes - 1 : -1;
     hipError_t e = launch_spmm(g, desc->block_density, desc->select_mode == CRISP_ROW_UNIFORM, force_shape, row_ptr, col_idx, vals,

@@ -21,8 +21,7 @@ crisp_status make_geometry(const crisp_layer_desc* d, bool need_density, Geometr
 
 // Launchers (enqueue only).  Each returns hipGetLastError() of its launches.
 hipError_t launch_select(const Geometry& g, int sal_kind, int select_mode, const uint16_t* W, const float* TG,
-                         uint32_t* nm_mask, int32_t* row_ptr, int32_t* col_idx, double* score, double* score_ws,
-                         hipStream_t st);
+                         uint32_t* nm_mask, int32_t* row_ptr, int32_t* col_idx, double* score, hipStream_t st);
 bool select_pack_fusable(const Geometry& g, int select_mode);
 size_t select_pack_stage_bytes(const Geometry& g);
 struct SelPackPtrs {

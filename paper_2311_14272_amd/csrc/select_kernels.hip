@@ -235,9 +235,7 @@ static SelLayer sel_layer_of(const Geometry& g, const uint16_t* W, const float* 
 }
 
 hipError_t launch_select(const Geometry& g, int sal_kind, int select_mode, const uint16_t* W, const float* TG,
-                         uint32_t* nm_mask, int32_t* row_ptr, int32_t* col_idx, double* score_out, double* score,
-                         hipStream_t st) {
-    (void)score_out;
+                         uint32_t* nm_mask, int32_t* row_ptr, int32_t* col_idx, double* score, hipStream_t st) {
     SelBatch bt = {};
     bt.n = 1;
     bt.L[0] = sel_layer_of(g, W, TG, nm_mask, score);
