@@ -50,6 +50,8 @@ def parse():
     ap.add_argument("--sweep", action="store_true",
                     help="block size x N:M sweep of the paper (B in 16/32/64, N in 1/2/3 of 4) on the layers of "
                          "the chosen workload: product time per setting, one JSON line")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the step replayed from HIP graphs (one per input set) and check a replay against the eager step")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 512 MiB device copy a few times (known traffic, for scaling profiler counters)")
     return ap.parse_args()
@@ -463,6 +465,42 @@ def main():
         info[i]["useful_tflops_forward"] = round(info[i]["useful_flop"] / fw / 1e12, 3)
         info[i]["hbm_frac_forward"] = round(info[i]["alg_bytes"] / fw / 1e9 / HBM_PEAK_GBS, 4)
 
+    graph_info = None
+    if args.graph and not args.side_streams:
+        # the step of every input set captured once, replayed in turn: the launches of a step go to
+        # the GPU as one unit.  Nothing in the library allocates, synchronises or clears memory, so
+        # every call is capturable as it is.
+        step(0)
+        torch.cuda.synchronize()
+        eager = [st.Y[0].clone() for st in layers]
+        for st in layers:
+            st.Y[0].zero_()
+        graphs = []
+        for sidx in range(nsets):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                step(sidx)
+            graphs.append(g)
+        same = True
+        for rep in range(3):                       # replays with eager work in between, each checked
+            graphs[0].replay()
+            torch.cuda.synchronize()
+            same = same and all(torch.equal(st.Y[0], e) for st, e in zip(layers, eager))
+            step(1 % nsets)
+            for st in layers:
+                st.Y[0].zero_()
+            torch.cuda.synchronize()
+        for k in range(args.warmup):
+            graphs[k % nsets].replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            graphs[(args.warmup + k) % nsets].replay()
+        torch.cuda.synchronize()
+        g_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        graph_info = {"ms_per_step": round(g_ms, 5), "value": round(useful / (g_ms * 1e-3) / 1e12, 4),
+                      "replay_equals_eager": bool(same)}
+
     achieved = info[dom]["alg_bytes"] / (dom_ms * 1e-3) / 1e9
     out = {
         "metric": "effective TFLOP/s (nonzero FLOPs) of hybrid-sparse GEMM + % roofline",
@@ -492,6 +530,8 @@ def main():
                      "algorithmic_bytes": info[dom]["alg_bytes"]},
         "layers": info,
     }
+    if graph_info is not None:
+        out["graph_replay"] = graph_info
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, host_inputs, useful)
     print(json.dumps(out))
