@@ -452,7 +452,7 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
     const bool lds_ok = !conv && (g.K % 16) == 0 && (Ncol % 4) == 0 && ldy <= ((int64_t)1 << 23);
     if (lds_ok && (force_shape == 5 || force_shape == 6)) return launch_spmm_lds(a, g.B, bpr, force_shape == 6, st);
     if (lds_ok && force_shape < 0 && hint && uniform_rows && prefer_lds(g, Ncol, bpr))
-        return launch_spmm_lds(a, g.B, bpr, bpr <= 3, st);
+        return launch_spmm_lds(a, g.B, bpr, bpr <= 1, st);
     // forced shapes 7..10: shapes 0..3 of the register kernels with the sparse matrix-core instruction
     // (the automatic choice always takes it where the pattern is eligible: it was faster for every
     // measured layer; shapes 0..3 force the dense-expansion instantiations)
