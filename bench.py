@@ -111,7 +111,7 @@ def resnet50_pass(args):
         if args.per_layer_prune:
             crisp.crisp_select_pack_batch(*crisp.make_batch(dls, Wd, Gd))
         scales = resnet.layer_scales(wl, dls)
-        need = max([L.K * L.Ncol for L in wl.layers if crisp.conv_needs_scratch(L.conv, L.B, L.n, L.m, L.S)] + [1])
+        need = max([L.K * L.Ncol for L in wl.layers if crisp.conv_needs_scratch(L.conv, L.B, L.n, L.m, L.S, L.density)] + [1])
         xs = torch.empty(need, dtype=torch.int16, device=dev)
         cv1 = wl.layers[0].conv
         x = torch.randn((3, cv1.batch, 224, 224), generator=gen, device=dev).to(torch.bfloat16).view(torch.int16)
@@ -145,7 +145,7 @@ def resnet50_pass(args):
         acts = [torch.randn((cv.C, cv.batch, cv.H, cv.W), generator=gen, device=dev).clamp_(min=0).to(torch.bfloat16).view(torch.int16)
                 for _ in range(nbuf)]
         Ys = [torch.empty((L.S, L.Ncol), dtype=ytorch, device=dev) for _ in range(nbuf)]
-        Xs = torch.empty((L.K, L.Ncol), dtype=torch.int16, device=dev) if crisp.conv_needs_scratch(cv, L.B, L.n, L.m, L.S) else None
+        Xs = torch.empty((L.K, L.Ncol), dtype=torch.int16, device=dev) if crisp.conv_needs_scratch(cv, L.B, L.n, L.m, L.S, L.density) else None
 
         tp = per_layer_tp[li]
         path = [None]

@@ -339,12 +339,15 @@ def fused_lowering_ok(cv, B: int, n: int, m: int) -> bool:
             and cv.stride <= 16 and plane <= (1 << 27) and pattern)
 
 
-def lowering_path(cv, B: int, n: int, m: int, S: int) -> str:
+def lowering_path(cv, B: int, n: int, m: int, S: int, density: float) -> str:
     """How conv_forward runs this convolution: "none" (act is X), "fused" (crisp_conv_spmm) or
     "im2col" (crisp_im2col into a scratch X, then crisp_spmm).  The fused kernels locate strided or
-    odd-width columns one by one with 2-byte loads; that beats writing X only where X would be an
-    inflated copy (more than one filter tap) that few block-rows read (measured on the ResNet-50
-    layers at batch 256)."""
+    odd-width columns one by one with 2-byte loads, once per kept block; that beats writing X only
+    where X would be an inflated copy (more than one filter tap) and the kept blocks of all
+    block-rows together are not many more than X has block columns: block-rows x block density <=
+    FUSED_GENERAL_MAX_GATHER (measured on the strided 3x3 layers of ResNet-50 at batch 256: a
+    block gathered costs ~0.8 of a block column written and read back once, and the product over
+    a materialised X costs ~0.2 per kept block)."""
     Ho = (cv.H + 2 * cv.pad - cv.kh) // cv.stride + 1
     Wo = (cv.W + 2 * cv.pad - cv.kw) // cv.stride + 1
     pointwise = cv.kh == 1 and cv.kw == 1 and cv.stride == 1 and cv.pad == 0
@@ -352,17 +355,17 @@ def lowering_path(cv, B: int, n: int, m: int, S: int) -> str:
         return "none"
     if not pointwise and fused_lowering_ok(cv, B, n, m):
         paired = cv.stride == 1 and Wo % 2 == 0 and cv.W >= 2 and cv.C % B == 0
-        if paired or (cv.kh * cv.kw > 1 and (S + B - 1) // B <= FUSED_GENERAL_MAX_BLOCK_ROWS):
+        if paired or (cv.kh * cv.kw > 1 and ((S + B - 1) // B) * density <= FUSED_GENERAL_MAX_GATHER):
             return "fused"
     return "im2col"
 
 
-FUSED_GENERAL_MAX_BLOCK_ROWS = 4
+FUSED_GENERAL_MAX_GATHER = 1.6
 
 
-def conv_needs_scratch(cv, B: int, n: int, m: int, S: int) -> bool:
+def conv_needs_scratch(cv, B: int, n: int, m: int, S: int, density: float) -> bool:
     """Whether conv_forward needs an X scratch buffer (K x round_up(Ncol, 8) bf16) for this layer."""
-    return lowering_path(cv, B, n, m, S) == "im2col"
+    return lowering_path(cv, B, n, m, S, density) == "im2col"
 
 
 def conv_forward(layer: DeviceLayer, cv, act, Y, ldy, y_dtype=Y_F32, X_scratch=None, ep=None):
@@ -374,7 +377,7 @@ def conv_forward(layer: DeviceLayer, cv, act, Y, ldy, y_dtype=Y_F32, X_scratch=N
     Ho = (cv.H + 2 * cv.pad - cv.kh) // cv.stride + 1
     Wo = (cv.W + 2 * cv.pad - cv.kw) // cv.stride + 1
     Ncol = cv.batch * Ho * Wo
-    path = lowering_path(cv, d.B, d.n, d.m, d.S)
+    path = lowering_path(cv, d.B, d.n, d.m, d.S, d.block_density)
     if path == "none":
         crisp_spmm_ep(d, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, act, Ncol, Ncol, Y, ldy, y_dtype, ep)
         return path

@@ -40,7 +40,7 @@ def _run_layers(batch, sample_cols):
         Ncol = L.Ncol
         ld = (Ncol + 7) // 8 * 8
         Y = torch.empty((L.S, ld), dtype=torch.float32, device="cuda")
-        need_x = crisp.conv_needs_scratch(cv, L.B, L.n, L.m, L.S)
+        need_x = crisp.conv_needs_scratch(cv, L.B, L.n, L.m, L.S, L.density)
         Xs = torch.zeros((L.K, ld), dtype=torch.int16, device="cuda") if need_x else None
         path = crisp.conv_forward(layer, cv, dact, Y, ld, crisp.Y_F32, Xs)
         torch.cuda.synchronize()
@@ -100,7 +100,7 @@ def test_resnet50_chained_forward_batch8():
         Gs.append(dev(t["G"]))
     crisp.crisp_select_pack_batch(*crisp.make_batch(layers, Ws, Gs))
     scales = resnet.layer_scales(wl, layers)
-    need = max([L.K * L.Ncol for L in wl.layers if crisp.conv_needs_scratch(L.conv, L.B, L.n, L.m, L.S)] + [1])
+    need = max([L.K * L.Ncol for L in wl.layers if crisp.conv_needs_scratch(L.conv, L.B, L.n, L.m, L.S, L.density)] + [1])
     xs = torch.empty(need, dtype=torch.int16, device="cuda")
     gen = torch.Generator(device="cuda")
     gen.manual_seed(wl.seed)
