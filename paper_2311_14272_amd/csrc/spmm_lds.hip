@@ -38,6 +38,8 @@ void spmm_lds_kernel(SpmmArgs p, LdsSched sch) {
     // once the kernel has stored to Y the compiler no longer uses scalar loads for the list, and a
     // vector load would sit in the same in-order counter as the X requests and drain them.
     __shared__ int lds_bj[CAP];
+    // per-row terms of the optional epilogue for this block-row (0 where absent or past S)
+    __shared__ float lds_sc[B], lds_bs[B];
 
     // workgroup -> (block-row, column group); all block-rows of a column group get ids on the same
     // XCD so that the X strips they share are served by that XCD's L2
@@ -51,6 +53,11 @@ void spmm_lds_kernel(SpmmArgs p, LdsSched sch) {
     // block-list indices -- stays in scalar registers and scalar loads)
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int jj = lane & 31, hh = lane >> 5;
+    if (p.ep_on && tid < B) {          // visible after the first barrier of the expansion
+        const int row = bi * B + tid;
+        lds_sc[tid] = (p.ep_scale && row < p.S) ? p.ep_scale[row] : 0.0f;
+        lds_bs[tid] = (p.ep_bias && row < p.S) ? p.ep_bias[row] : 0.0f;
+    }
     const int t_begin = p.row_ptr[bi], t_end = p.row_ptr[bi + 1];
     const int cnt = t_end - t_begin;
     const int nchunks = (cnt + CAP - 1) / CAP;
@@ -196,44 +203,75 @@ void spmm_lds_kernel(SpmmArgs p, LdsSched sch) {
     };
     // accumulator register r of a 32x32 tile is row 8*(r/4) + 4*hh + r%4, column jj; rows past S
     // and lanes past the last column fall outside the store resource's range and are dropped
+    // With an epilogue the residual values of a batch of rows are requested together before the
+    // first of them is used (the requests share the in-order counter with the X rows in flight for
+    // the next strip, so every wait for them also waits for those: one wait per batch, not per row);
+    // scale and bias come from LDS.
     auto store_strip_t = [&](const f32x16 (&acc)[RT][NACC], bool col_ok, int64_t col0, auto as_bf16, auto with_ep) __attribute__((always_inline)) {
+        constexpr bool BF16 = decltype(as_bf16)::value;
         const uint32_t y_off = col_ok ? (uint32_t)(4 * hh) * yrow_bytes + (uint32_t)col0 * esz : 0x80000000u;
+        auto store_row = [&](int tile_row, const float (&v)[NACC]) __attribute__((always_inline)) {
+            const uint32_t off = y_off + (uint32_t)tile_row * yrow_bytes;
+            if constexpr (BF16) {
+                uint32_t pk[WD];
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const uint32_t off = y_off + (uint32_t)(rt * 32 + 8 * (r >> 2) + (r & 3)) * yrow_bytes;
-                float v[NACC];
-#pragma unroll
-                for (int c = 0; c < NACC; ++c) v[c] = acc[rt][c][r];
-                if constexpr (decltype(with_ep)::value) {
-                    const int row = bi * B + rt * 32 + 8 * (r >> 2) + (r & 3) + 4 * hh;
-                    apply_epilogue<NACC>(p, row, col0, col_ok && row < p.S, v);
+                for (int c = 0; c < WD; ++c) {
+                    const f32x2 two = {v[2 * c], v[2 * c + 1]};
+                    pk[c] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2));
                 }
-                if constexpr (decltype(as_bf16)::value) {
-                    uint32_t pk[WD];
-#pragma unroll
-                    for (int c = 0; c < WD; ++c) {
-                        const f32x2 two = {v[2 * c], v[2 * c + 1]};
-                        pk[c] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2));
-                    }
-                    if constexpr (WD == 1) {
-                        __builtin_amdgcn_raw_buffer_store_b32(pk[0], ry, off, 0, 0);
-                    } else {
-                        const u32x2 two = {pk[0], pk[WD - 1]};
-                        __builtin_amdgcn_raw_buffer_store_b64(two, ry, off, 0, 0);
-                    }
+                if constexpr (WD == 1) {
+                    __builtin_amdgcn_raw_buffer_store_b32(pk[0], ry, off, 0, 0);
                 } else {
-                    if constexpr (WD == 1) {
-                        const u32x2 two = {__float_as_uint(v[0]), __float_as_uint(v[1])};
-                        __builtin_amdgcn_raw_buffer_store_b64(two, ry, off, 0, 0);
-                    } else {
-                        const u32x4 four = {__float_as_uint(v[0]), __float_as_uint(v[1]),
-                                            __float_as_uint(v[NACC - 2]), __float_as_uint(v[NACC - 1])};
-                        __builtin_amdgcn_raw_buffer_store_b128(four, ry, off, 0, 0);
-                    }
+                    const u32x2 two = {pk[0], pk[WD - 1]};
+                    __builtin_amdgcn_raw_buffer_store_b64(two, ry, off, 0, 0);
+                }
+            } else {
+                if constexpr (WD == 1) {
+                    const u32x2 two = {__float_as_uint(v[0]), __float_as_uint(v[1])};
+                    __builtin_amdgcn_raw_buffer_store_b64(two, ry, off, 0, 0);
+                } else {
+                    const u32x4 four = {__float_as_uint(v[0]), __float_as_uint(v[1]),
+                                        __float_as_uint(v[NACC - 2]), __float_as_uint(v[NACC - 1])};
+                    __builtin_amdgcn_raw_buffer_store_b128(four, ry, off, 0, 0);
                 }
             }
+        };
+        if constexpr (decltype(with_ep)::value) {
+            constexpr int RW = BF16 ? WD : NACC;
+            constexpr int CH = 16 / WD;
+            const EpSource src = make_ep_source(p, bi, B, hh, col0, col_ok);
+#pragma unroll
+            for (int q0 = 0; q0 < RT * 16; q0 += CH) {
+                EpBatch<CH, RW> eb;
+#pragma unroll
+                for (int j = 0; j < CH; ++j) {
+                    const int rt = (q0 + j) >> 4, r = (q0 + j) & 15;
+                    const int tile_row = rt * 32 + 8 * (r >> 2) + (r & 3);
+                    ep_request_residual<RW>(src, tile_row, eb.res[j]);
+                    eb.sc[j] = lds_sc[tile_row + 4 * hh];
+                    eb.bs[j] = lds_bs[tile_row + 4 * hh];
+                }
+#pragma unroll
+                for (int j = 0; j < CH; ++j) {
+                    const int rt = (q0 + j) >> 4, r = (q0 + j) & 15;
+                    float v[NACC];
+#pragma unroll
+                    for (int c = 0; c < NACC; ++c) v[c] = acc[rt][c][r];
+                    ep_apply<NACC, BF16>(p, eb.res[j], eb.sc[j], eb.bs[j], v);
+                    store_row(rt * 32 + 8 * (r >> 2) + (r & 3), v);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float v[NACC];
+#pragma unroll
+                    for (int c = 0; c < NACC; ++c) v[c] = acc[rt][c][r];
+                    store_row(rt * 32 + 8 * (r >> 2) + (r & 3), v);
+                }
+        }
     };
     auto store_strip = [&](const f32x16 (&acc)[RT][NACC], bool col_ok, int64_t col0) __attribute__((always_inline)) {
         if (p.ep_on) {

@@ -170,6 +170,73 @@ __device__ __forceinline__ void apply_epilogue(const SpmmArgs& p, int row, int64
     }
 }
 
+// The epilogue's operands for CH output rows of a lane, requested together so that their
+// latencies overlap (one at a time, every row would wait out a memory round trip).  All requests
+// go through buffer resources whose range is the existing part of the operand -- zero for an
+// absent operand -- so they need no branches: out-of-range requests return 0 and are not used.
+// RW: dwords of residual per row and lane (bf16: one per column pair, fp32: one per column).
+template <int CH, int RW>
+struct EpBatch {
+    uint32_t res[CH][RW];
+    float sc[CH], bs[CH];
+};
+struct EpSource {
+    rsrc_t res, scale, bias;
+    uint32_t res_row_bytes;
+    uint32_t res_off;       // lane part of the residual address inside the block-row; out of range for lanes that store nothing
+    uint32_t row0_bytes;    // (first row of the lane in the block-row) * 4, for scale and bias
+};
+__device__ __forceinline__ EpSource make_ep_source(const SpmmArgs& p, int bi, int B, int hh, int64_t col0, bool col_ok) {
+    const uint32_t esz = p.y_bf16 ? 2u : 4u;
+    const int rows_here = min(B, p.S - bi * B);
+    EpSource e;
+    e.res_row_bytes = (uint32_t)p.ep_ldr * esz;
+    e.res = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char*>(reinterpret_cast<const char*>(p.ep_res)) + (p.ep_res ? (int64_t)bi * B * p.ep_ldr * esz : 0), 0,
+        p.ep_res ? (uint32_t)rows_here * e.res_row_bytes : 0u, 0x00020000);
+    e.scale = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.ep_scale), 0, p.ep_scale ? (uint32_t)p.S * 4u : 0u, 0x00020000);
+    e.bias = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.ep_bias), 0, p.ep_bias ? (uint32_t)p.S * 4u : 0u, 0x00020000);
+    e.res_off = col_ok ? (uint32_t)(4 * hh) * e.res_row_bytes + (uint32_t)col0 * esz : 0x80000000u;
+    e.row0_bytes = (uint32_t)(bi * B + 4 * hh) * 4u;
+    return e;
+}
+template <int RW>
+__device__ __forceinline__ void ep_request_residual(const EpSource& e, int tile_row, uint32_t (&dst)[RW]) {
+    const uint32_t off = e.res_off + (uint32_t)tile_row * e.res_row_bytes;
+    if constexpr (RW == 1) {
+        dst[0] = __builtin_amdgcn_raw_buffer_load_b32(e.res, off, 0, 0);
+    } else if constexpr (RW == 2) {
+        const u32x2 t = __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(e.res, off, 0, 0));
+        dst[0] = t[0]; dst[1] = t[1];
+    } else {
+        static_assert(RW == 4, "two or four columns per lane");
+        const u32x4 t = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(e.res, off, 0, 0));
+        dst[0] = t[0]; dst[1] = t[1]; dst[2] = t[2]; dst[3] = t[3];
+    }
+}
+__device__ __forceinline__ void ep_request_row_terms(const EpSource& e, int tile_row, float& sc, float& bs) {
+    const uint32_t off = e.row0_bytes + (uint32_t)tile_row * 4u;
+    sc = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(e.scale, off, 0, 0));
+    bs = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(e.bias, off, 0, 0));
+}
+// y = relu(y * scale + bias + residual) on the NV values of one row, every step one fp32 rounding,
+// absent parts skipped (same arithmetic as apply_epilogue).
+template <int NV, bool BF16>
+__device__ __forceinline__ void ep_apply(const SpmmArgs& p, const uint32_t (&res)[BF16 ? NV / 2 : NV], float sc, float bs, float (&v)[NV]) {
+#pragma unroll
+    for (int c = 0; c < NV; ++c) {
+        float r;
+        if constexpr (BF16) r = __uint_as_float((c & 1) ? (res[c / 2] & 0xFFFF0000u) : (res[c / 2] << 16));
+        else r = __uint_as_float(res[c]);
+        float y = v[c];
+        y = p.ep_scale ? __fmul_rn(y, sc) : y;
+        y = p.ep_bias ? __fadd_rn(y, bs) : y;
+        y = p.ep_res ? __fadd_rn(y, r) : y;
+        y = p.ep_relu ? fmaxf(y, 0.0f) : y;
+        v[c] = y;
+    }
+}
+
 // Geometry of the canonical packed form as seen by one lane.
 template <int N, int M, int B>
 struct Fmt {
@@ -578,17 +645,19 @@ struct BlockBody {
     }
 };
 
-// Output of one wave: ROWS accumulator rows of a 64*WD-column strip of block-row bi.
-// Accumulator register r of a 32x32 tile is row 8*(r/4) + 4*hh + r%4 of the tile, column jj; the
-// NACC tiles of a lane are consecutive columns.  row_source(q, v) fills v with the lane's NACC
-// values of the q-th row to store and returns its accumulator row index rt*16 + r.  Y is written
+// Output of one wave: ROWS accumulator rows of a 64*WD-column strip of block-row bi, namely the
+// rows with accumulator index pr = row_first + q * ROW_STEP (pr = rt*16 + r; register r of a 32x32
+// tile is row 8*(r/4) + 4*hh + r%4 of the tile, column jj; the NACC tiles of a lane are consecutive
+// columns).  row_source(pr, v) fills v with the lane's NACC values of that row.  Y is written
 // through a buffer resource that spans the block-row's existing rows: rows past S and lanes past
 // the last column fall outside its range and the hardware drops them, so the stores need no
 // branches.  (Ncol is a multiple of 4 here, so a lane's columns are all inside or all outside.)
 // The four (epilogue yes/no) x (bf16/fp32 output) variants of the store loop are separate copies
-// chosen once per wave, so the loop itself holds no branches.
-template <int B, int WD, int ROWS, typename RowSource>
-__device__ __forceinline__ void store_rows(const SpmmArgs& p, int bi, int hh, int64_t col0, bool col_ok, RowSource row_source) {
+// chosen once per wave, so the loop itself holds no branches; with an epilogue its operands are
+// requested for a batch of rows before the first of them is used.
+template <int B, int WD, int ROWS, int ROW_STEP, typename RowSource>
+__device__ __forceinline__ void store_rows(const SpmmArgs& p, int bi, int hh, int64_t col0, bool col_ok, int row_first,
+                                           RowSource row_source) {
     constexpr int NACC = 2 * WD;
     const uint32_t esz = p.y_bf16 ? 2u : 4u;
     const uint32_t row_bytes = (uint32_t)p.ldy * esz;
@@ -596,17 +665,15 @@ __device__ __forceinline__ void store_rows(const SpmmArgs& p, int bi, int hh, in
     const rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(
         reinterpret_cast<char*>(p.Y) + (int64_t)bi * B * p.ldy * esz, 0, (uint32_t)rows_here * row_bytes, 0x00020000);
     const uint32_t y_off = col_ok ? (uint32_t)(4 * hh) * row_bytes + (uint32_t)col0 * esz : 0x80000000u;
+    auto tile_row_of = [&](int q) __attribute__((always_inline)) {
+        const int pr = row_first + q * ROW_STEP;
+        return (pr >> 4) * 32 + 8 * ((pr & 15) >> 2) + (pr & 3);
+    };
     auto emit = [&](auto with_ep, auto as_bf16) __attribute__((always_inline)) {
-        auto store_row = [&](int tile_row, const float (&vin)[NACC]) __attribute__((always_inline)) {
+        constexpr bool BF16 = decltype(as_bf16)::value;
+        auto store_row = [&](int tile_row, const float (&v)[NACC]) __attribute__((always_inline)) {
             const uint32_t off = y_off + (uint32_t)tile_row * row_bytes;
-            float v[NACC];
-#pragma unroll
-            for (int c = 0; c < NACC; ++c) v[c] = vin[c];
-            if constexpr (decltype(with_ep)::value) {
-                const int row = bi * B + tile_row + 4 * hh;
-                apply_epilogue<NACC>(p, row, col0, col_ok && row < p.S, v);
-            }
-            if constexpr (decltype(as_bf16)::value) {
+            if constexpr (BF16) {
                 uint32_t pk[WD];
 #pragma unroll
                 for (int c = 0; c < WD; ++c) {
@@ -630,12 +697,35 @@ __device__ __forceinline__ void store_rows(const SpmmArgs& p, int bi, int hh, in
                 }
             }
         };
+        if constexpr (decltype(with_ep)::value) {
+            constexpr int RW = BF16 ? WD : NACC;
+            constexpr int CH = ROWS < 16 ? ROWS : 16;          // rows per batch of requests
+            static_assert(ROWS % CH == 0, "whole batches");
+            const EpSource src = make_ep_source(p, bi, B, hh, col0, col_ok);
 #pragma unroll
-        for (int q = 0; q < ROWS; ++q) {
-            float v[NACC];
-            const int pr = row_source(q, v);       // accumulator row index rt*16 + r
-            const int rt = pr >> 4, r = pr & 15;
-            store_row(rt * 32 + 8 * (r >> 2) + (r & 3), v);
+            for (int q0 = 0; q0 < ROWS; q0 += CH) {
+                EpBatch<CH, RW> eb;
+#pragma unroll
+                for (int j = 0; j < CH; ++j) {
+                    const int tile_row = tile_row_of(q0 + j);
+                    ep_request_residual<RW>(src, tile_row, eb.res[j]);
+                    ep_request_row_terms(src, tile_row, eb.sc[j], eb.bs[j]);
+                }
+#pragma unroll
+                for (int j = 0; j < CH; ++j) {
+                    float v[NACC];
+                    row_source(row_first + (q0 + j) * ROW_STEP, v);
+                    ep_apply<NACC, BF16>(p, eb.res[j], eb.sc[j], eb.bs[j], v);
+                    store_row(tile_row_of(q0 + j), v);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < ROWS; ++q) {
+                float v[NACC];
+                row_source(row_first + q * ROW_STEP, v);
+                store_row(tile_row_of(q), v);
+            }
         }
     };
     if (p.ep_on) {
@@ -765,10 +855,9 @@ void spmm_reg_kernel(SpmmArgs p) {
 
     // ---- epilogue ---------------------------------------------------------------------------
     if constexpr (NWK == 1) {
-        store_rows<B, WD, RT * 16>(p, bi, hh, col0, col_ok, [&](int q, float (&v)[NACC]) __attribute__((always_inline)) {
+        store_rows<B, WD, RT * 16, 1>(p, bi, hh, col0, col_ok, 0, [&](int pr, float (&v)[NACC]) __attribute__((always_inline)) {
 #pragma unroll
-            for (int c = 0; c < NACC; ++c) v[c] = acc[q >> 4][c][q & 15];
-            return q;
+            for (int c = 0; c < NACC; ++c) v[c] = acc[pr >> 4][c][pr & 15];
         });
     } else {
         // partial sums of the NWK waves -> LDS, then wave w adds up and stores every NWK-th row
@@ -780,8 +869,7 @@ void spmm_reg_kernel(SpmmArgs p) {
 #pragma unroll
                 for (int c = 0; c < NACC; ++c) red[wave][rt * 16 + r][c][lane] = acc[rt][c][r];
         __syncthreads();
-        store_rows<B, WD, RT * 16 / NWK>(p, bi, hh, col0, col_ok, [&](int q, float (&v)[NACC]) __attribute__((always_inline)) {
-            const int pr = q * NWK + wave;
+        store_rows<B, WD, RT * 16 / NWK, NWK>(p, bi, hh, col0, col_ok, wave, [&](int pr, float (&v)[NACC]) __attribute__((always_inline)) {
 #pragma unroll
             for (int c = 0; c < NACC; ++c) {
                 float s = red[0][pr][c][lane];
@@ -789,7 +877,6 @@ void spmm_reg_kernel(SpmmArgs p) {
                 for (int w = 1; w < NWK; ++w) s += red[w][pr][c][lane];
                 v[c] = s;
             }
-            return pr;
         });
     }
 }
