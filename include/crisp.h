@@ -280,8 +280,9 @@ CRISP_API crisp_status crisp_conv_spmm(const crisp_layer_desc *desc, const crisp
  * convolution and the first residual stage; not part of the paper's method):
  *   out[c][i][oh][ow] = max over a < kh, b < kw of act[c][i][oh*stride + a - pad][ow*stride + b - pad],
  * positions outside the image excluded; Ho, Wo as for a convolution; pad < kh, kw.  The result is
- * one of the inputs (no rounding).  act and out device, bf16, out holds C*batch*Ho*Wo elements.
- * Errors: EINVAL, ESHAPE, EUNSUPPORTED (layout), EDEVICE.
+ * one of the inputs (no rounding).  act and out device, bf16, out holds C*batch*Ho*Wo elements
+ * (fewer than 2^32).
+ * Errors: EINVAL, ESHAPE, EUNSUPPORTED (layout, size), EDEVICE.
  */
 CRISP_API crisp_status crisp_maxpool(const crisp_conv_desc *pool, const uint16_t *act, uint16_t *out, void *stream);
 

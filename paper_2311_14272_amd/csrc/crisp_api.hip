@@ -231,6 +231,10 @@ crisp_status crisp_maxpool(const crisp_conv_desc* c, const uint16_t* act, uint16
     if (c->H + 2 * c->pad < c->kh || c->W + 2 * c->pad < c->kw) return CRISP_ESHAPE;
     if (c->act_layout != CRISP_ACT_CBHW) return CRISP_EUNSUPPORTED;
     if ((int64_t)c->H * c->W >= ((int64_t)1 << 31)) return CRISP_EUNSUPPORTED;
+    {
+        const int64_t Ho = (c->H + 2 * c->pad - c->kh) / c->stride + 1, Wo = (c->W + 2 * c->pad - c->kw) / c->stride + 1;
+        if ((int64_t)c->C * c->batch * Ho * Wo >= ((int64_t)1 << 32) - 256) return CRISP_EUNSUPPORTED;   // 32-bit output index
+    }
     if (misaligned(act, 2) || misaligned(out, 2)) return CRISP_EALIGN;
     hipError_t e = launch_maxpool(*c, act, out, (hipStream_t)stream);
     return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;

@@ -117,28 +117,59 @@ namespace crisp {
 // method).  Positions outside the image do not take part.  bf16 values are compared as floats; the
 // result is one of the inputs, so no rounding occurs.  One thread per output element; a window that
 // lies wholly outside (cannot happen for pad < kernel size) would yield -inf.
-__global__ __launch_bounds__(256) void maxpool_kernel(Im2colArgs p, int64_t total) {
-    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+// KH, KW > 0: window size known at compile time.  Every tap is then loaded from a clamped (always
+// valid) position and masked afterwards, so the loop holds no branches and all loads of a thread
+// are in flight together; with the bounds tests as branches every tap waits for the one before.
+// KH == 0: any window size, taps outside the image skipped.
+template <int KH, int KW>
+__global__ __launch_bounds__(256) void maxpool_kernel(Im2colArgs p, uint32_t total) {
+    const uint32_t e = blockIdx.x * 256u + threadIdx.x;
     if (e >= total) return;
-    const int ow = (int)(e % p.Wo);
-    int64_t t = e / p.Wo;
-    const int oh = (int)(t % p.Ho);
-    t /= p.Ho;                      // t = c * batch + image
-    const uint16_t* src = p.act + t * (int64_t)p.H * p.W;
+    const uint32_t wo = (uint32_t)p.Wo, ho = (uint32_t)p.Ho;
+    const int ow = (int)(e % wo);
+    const uint32_t t = e / wo;
+    const int oh = (int)(t % ho);
+    const uint32_t plane = t / ho;              // c * batch + image
+    const uint16_t* src = p.act + (int64_t)plane * p.H * p.W;
     float best = -__builtin_inff();
-    uint16_t best_bits = 0xFF80u;   // -inf
-    for (int a = 0; a < p.kh; ++a) {
-        const int ih = oh * p.stride + a - p.pad;
-        if ((unsigned)ih >= (unsigned)p.H) continue;
-        for (int b = 0; b < p.kw; ++b) {
-            const int iw = ow * p.stride + b - p.pad;
-            if ((unsigned)iw >= (unsigned)p.W) continue;
-            const uint16_t bits = src[ih * p.W + iw];
-            const float v = bf16_bits_to_float(bits);
-            if (v > best) { best = v; best_bits = bits; }
+    uint32_t best_bits = 0xFF80u;               // -inf
+    if constexpr (KH > 0) {
+        uint32_t bits[KH][KW];
+#pragma unroll
+        for (int a = 0; a < KH; ++a) {
+            const int ih = min(max(oh * p.stride + a - p.pad, 0), p.H - 1);
+#pragma unroll
+            for (int b = 0; b < KW; ++b) {
+                const int iw = min(max(ow * p.stride + b - p.pad, 0), p.W - 1);
+                bits[a][b] = src[ih * p.W + iw];
+            }
+        }
+#pragma unroll
+        for (int a = 0; a < KH; ++a) {
+            const bool row_in = (unsigned)(oh * p.stride + a - p.pad) < (unsigned)p.H;
+#pragma unroll
+            for (int b = 0; b < KW; ++b) {
+                const bool in = row_in && (unsigned)(ow * p.stride + b - p.pad) < (unsigned)p.W;
+                const float v = in ? bf16_bits_to_float((uint16_t)bits[a][b]) : -__builtin_inff();
+                const bool better = v > best;
+                best = better ? v : best;
+                best_bits = better ? bits[a][b] : best_bits;
+            }
+        }
+    } else {
+        for (int a = 0; a < p.kh; ++a) {
+            const int ih = oh * p.stride + a - p.pad;
+            if ((unsigned)ih >= (unsigned)p.H) continue;
+            for (int b = 0; b < p.kw; ++b) {
+                const int iw = ow * p.stride + b - p.pad;
+                if ((unsigned)iw >= (unsigned)p.W) continue;
+                const uint32_t bits = src[ih * p.W + iw];
+                const float v = bf16_bits_to_float((uint16_t)bits);
+                if (v > best) { best = v; best_bits = bits; }
+            }
         }
     }
-    p.X[e] = best_bits;
+    p.X[e] = (uint16_t)best_bits;
 }
 
 hipError_t launch_maxpool(const crisp_conv_desc& c, const uint16_t* act, uint16_t* out, hipStream_t st) {
@@ -149,8 +180,11 @@ hipError_t launch_maxpool(const crisp_conv_desc& c, const uint16_t* act, uint16_
     p.act = act;
     p.X = out;
     const int64_t total = (int64_t)c.C * c.batch * p.Ho * p.Wo;
-    if (total <= 0 || (total + 255) / 256 > INT32_MAX) return hipErrorInvalidValue;
-    maxpool_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(p, total);
+    if (total <= 0 || total > (int64_t)0xFFFFFF00u) return hipErrorInvalidValue;
+    const unsigned grid = (unsigned)((total + 255) / 256);
+    if (c.kh == 3 && c.kw == 3) maxpool_kernel<3, 3><<<grid, 256, 0, st>>>(p, (uint32_t)total);
+    else if (c.kh == 2 && c.kw == 2) maxpool_kernel<2, 2><<<grid, 256, 0, st>>>(p, (uint32_t)total);
+    else maxpool_kernel<0, 0><<<grid, 256, 0, st>>>(p, (uint32_t)total);
     return hipGetLastError();
 }
 
