@@ -501,6 +501,16 @@ def main():
         graph_info = {"ms_per_step": round(g_ms, 5), "value": round(useful / (g_ms * 1e-3) / 1e12, 4),
                       "replay_equals_eager": bool(same)}
 
+    # a plain device-to-device copy that moves as many bytes as the dominant product (half read, half
+    # written), launched back to back over rotating buffers like forward_ms: what the memory system and
+    # the launch path give a kernel of this size that does nothing else
+    half = max(int(info[dom]["alg_bytes"]) // 4, 1)          # int16 elements per side
+    ncopy = max(2, min(16, int(600e6 // (4 * half)) + 1))
+    csrc = [torch.zeros(half, dtype=torch.int16, device=dev) for _ in range(ncopy)]
+    cdst = [torch.empty(half, dtype=torch.int16, device=dev) for _ in range(ncopy)]
+    copy_ms = timed(lambda r: cdst[r % ncopy].copy_(csrc[r % ncopy]))
+    del csrc, cdst
+
     achieved = info[dom]["alg_bytes"] / (dom_ms * 1e-3) / 1e9
     out = {
         "metric": "effective TFLOP/s (nonzero FLOPs) of hybrid-sparse GEMM + % roofline",
@@ -527,7 +537,9 @@ def main():
                      "avg_launch_ms": round(dom_ms, 5), "median_launch_ms": round(dom_med_ms, 5),
                      "timing": "event pair around the launch in every timed step, minus the calibrated cost of the pair",
                      "avg_bracket_ms": round(dom_raw_ms, 5), "event_pair_overhead_ms": round(pair_ms, 5),
-                     "algorithmic_bytes": info[dom]["alg_bytes"]},
+                     "algorithmic_bytes": info[dom]["alg_bytes"],
+                     "forward_ms_back_to_back": info[dom]["forward_ms"],
+                     "plain_copy_same_bytes_ms_back_to_back": round(copy_ms, 5)},
         "layers": info,
     }
     if graph_info is not None:
