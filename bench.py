@@ -75,7 +75,7 @@ def resnet50_pass(args):
     gen = torch.Generator(device=dev)
     gen.manual_seed(wl.seed)
     reps = max(1, min(args.steps, 5))
-    rows, t_prune, t_fwd, useful, dense = [], 0.0, 0.0, 0.0, 0.0
+    rows, t_prune, t_fwd, t_im2col, useful, dense = [], 0.0, 0.0, 0.0, 0.0, 0.0
 
     def timed(fn):
         fn(0)
@@ -153,6 +153,10 @@ def resnet50_pass(args):
         def fwd(r):
             path[0] = crisp.conv_forward(dl, cv, acts[r % nbuf], Ys[r % nbuf], L.Ncol, y_dtype, Xs)
         tf = timed(fwd)
+        ti = 0.0
+        if path[0] == "im2col":      # the lowering pass alone (part of forward_ms)
+            ldx = (L.Ncol + 7) // 8 * 8
+            ti = timed(lambda r: crisp.crisp_im2col(crisp.conv_desc_of(cv), acts[r % nbuf], Xs, ldx))
         sz = dl.sizes
         ones = sz.nk * L.B * sz.slots_per_row if (L.S % L.B == 0 and L.K % L.B == 0) else None
         if ones is None:   # ragged layer (conv1): count from the device mask
@@ -164,8 +168,10 @@ def resnet50_pass(args):
         uf = 2.0 * ones * L.Ncol
         rows.append(dict(name=L.name, S=L.S, K=L.K, Ncol=L.Ncol, nm="%d:%d" % (L.n, L.m), density=round(L.density, 3),
                          k_row=sz.k_row, lowering=path[0], prune_pack_ms=(round(tp, 4) if tp is not None else None), forward_ms=round(tf, 4),
+                         im2col_ms=round(ti, 4),
                          useful_tflops_forward=round(uf / (tf * 1e-3) / 1e12, 2)))
         t_fwd += tf
+        t_im2col += ti
         useful += uf
         dense += 2.0 * L.S * L.K * L.Ncol
         del acts, Ys, Xs
@@ -180,6 +186,7 @@ def resnet50_pass(args):
                       "step": ("select+pack layer by layer (crisp_select_pack)" if args.per_layer_prune else "select+pack of all layers in one crisp_select_pack_batch call") + "; then per layer: lowering (fused, im2col or none) and product; summed",
                       "y_dtype": args.y_dtype},
            "select_pack_ms": round(t_prune, 3), "forward_ms": round(t_fwd, 3),
+           "im2col_ms": round(t_im2col, 3), "product_ms": round(t_fwd - t_im2col, 3),
            "useful_tflops_forward_only": round(useful / (t_fwd * 1e-3) / 1e12, 2),
            "dense_equivalent_tflops_forward_only": round(dense / (t_fwd * 1e-3) / 1e12, 1),
            "roofline": None, "layers": rows}
