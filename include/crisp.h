@@ -257,8 +257,9 @@ CRISP_API crisp_status crisp_spmm(const crisp_layer_desc *desc, const int32_t *r
 /*
  * Product with implicit lowering: Y = W_hybrid * im2col(act) without materialising X
  * (Sec. 3.5, first step: only the activations that kept blocks need are fetched, here straight
- * from the convolution's input).  Same result, bit for bit, as crisp_im2col followed by
- * crisp_spmm.  act is [C][batch][H][W] bf16 (device); desc->K must equal kh*kw*C; Y is
+ * from the convolution's input).  Same result as crisp_im2col followed by crisp_spmm up to
+ * the fp32 summation order (bit for bit when both are forced into the same launch shape of the
+ * register kernels).  act is [C][batch][H][W] bf16 (device); desc->K must equal kh*kw*C; Y is
  * S x ldy with Ncol = batch*Ho*Wo columns written.
  * Covered: Ncol even, B in {32, 64}, n:m in {1..4}:4 or {1,2,4,8}:8, kw <= 16,
  * kh*kw <= 64, stride <= 16, batch*H*W <= 2^27, ldy <= 2^23.  With C % B == 0 every block
@@ -266,7 +267,10 @@ CRISP_API crisp_status crisp_spmm(const crisp_layer_desc *desc, const int32_t *r
  * come from one 4-byte load, otherwise (strided, odd Wo, 1x1 with stride) each column is
  * located and loaded on its own.  Other channel counts (the first layer of a network):
  * every K-row is split into (tap, channel) on its own; needs K <= 65535 and an activation
- * below 4 GiB.
+ * below 4 GiB.  For stride 1, C % 64 == 0, 64x64 blocks and an even Wo <= 64 there is also
+ * a kernel that stages the input patch of a tile of output rows in LDS once for all filter
+ * taps and up to four block-rows (chosen for dense multi-row layers; ws == NULL with
+ * ws_bytes == 13 forces it, 1..4 and 8..11 force the shapes of crisp_spmm).
  * Anything else returns CRISP_EUNSUPPORTED (use crisp_im2col + crisp_spmm).
  * Errors: EINVAL, ESHAPE, EALIGN, EUNSUPPORTED, EDEVICE.
  */

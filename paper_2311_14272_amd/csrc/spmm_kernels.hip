@@ -7,7 +7,7 @@
 // multiplies it with its own strip of X (loaded as in spmm_reg.h).  The patterns the paper and
 // the benchmark workloads use have register-resident specialisations (spmm_reg.h), which the
 // dispatcher prefers.
-#include "spmm_reg.h"
+#include "conv_lds.h"
 
 namespace crisp {
 
@@ -367,6 +367,14 @@ template <> hipError_t launch_reg_nm<1, 8>(const SpmmArgs&, int, int, hipStream_
 template <> hipError_t launch_reg_nm<2, 8>(const SpmmArgs&, int, int, hipStream_t);
 template <> hipError_t launch_reg_nm<4, 8>(const SpmmArgs&, int, int, hipStream_t);
 template <> hipError_t launch_reg_nm<8, 8>(const SpmmArgs&, int, int, hipStream_t);
+template <> hipError_t launch_conv_lds_nm<1, 4>(const SpmmArgs&, const ConvLdsSched&, int, hipStream_t);
+template <> hipError_t launch_conv_lds_nm<2, 4>(const SpmmArgs&, const ConvLdsSched&, int, hipStream_t);
+template <> hipError_t launch_conv_lds_nm<3, 4>(const SpmmArgs&, const ConvLdsSched&, int, hipStream_t);
+template <> hipError_t launch_conv_lds_nm<4, 4>(const SpmmArgs&, const ConvLdsSched&, int, hipStream_t);
+template <> hipError_t launch_conv_lds_nm<1, 8>(const SpmmArgs&, const ConvLdsSched&, int, hipStream_t);
+template <> hipError_t launch_conv_lds_nm<2, 8>(const SpmmArgs&, const ConvLdsSched&, int, hipStream_t);
+template <> hipError_t launch_conv_lds_nm<4, 8>(const SpmmArgs&, const ConvLdsSched&, int, hipStream_t);
+template <> hipError_t launch_conv_lds_nm<8, 8>(const SpmmArgs&, const ConvLdsSched&, int, hipStream_t);
 
 // Launch shape of the register-expansion kernels from the problem size (thresholds from sweeps
 // over the layer shapes of ResNet-50 at batch 256 and the small single-layer workloads):
@@ -443,6 +451,27 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
         a.inv_Ho = 1.0 / a.Ho;
     }
     if (g.B == 16) return launch_b16(a, st);
+    // convolution with the input patch staged in LDS (forced shape 12).  Chosen automatically for
+    // filters with several taps where at least two block-rows keep at least half of their blocks:
+    // there the patch is reused often enough to pay for bringing it in (measured on the 3x3 layers
+    // of ResNet-50: 1.1-1.25x at those densities, slower below)
+    ConvLdsSched cs;
+    const bool conv_lds_wanted = force_shape == 12 ||
+        (force_shape < 0 && conv && conv->kh * conv->kw > 1 && g.Sb >= 2 && density_hint >= 0.5 && density_hint <= 1.0);
+    if (conv && conv_lds_wanted && (Ncol % 4) == 0 && ldy <= ((int64_t)1 << 23) && conv_lds_plan(a, g.B, conv->kh, &cs)) {
+        a.use_smf = 1;
+        switch (g.n * 16 + g.m) {
+            case 1 * 16 + 4: return launch_conv_lds_nm<1, 4>(a, cs, conv->batch, st);
+            case 2 * 16 + 4: return launch_conv_lds_nm<2, 4>(a, cs, conv->batch, st);
+            case 3 * 16 + 4: return launch_conv_lds_nm<3, 4>(a, cs, conv->batch, st);
+            case 4 * 16 + 4: return launch_conv_lds_nm<4, 4>(a, cs, conv->batch, st);
+            case 1 * 16 + 8: return launch_conv_lds_nm<1, 8>(a, cs, conv->batch, st);
+            case 2 * 16 + 8: return launch_conv_lds_nm<2, 8>(a, cs, conv->batch, st);
+            case 4 * 16 + 8: return launch_conv_lds_nm<4, 8>(a, cs, conv->batch, st);
+            case 8 * 16 + 8: return launch_conv_lds_nm<8, 8>(a, cs, conv->batch, st);
+            default: break;
+        }
+    }
     // LDS-resident block-rows (forced shapes 5 = narrow strips, 6 = wide strips)
     // kept blocks per block-row as the descriptor states them (a hint: only speed depends on it)
     const bool hint = density_hint > 0.0 && density_hint <= 1.0;

@@ -305,6 +305,57 @@ __device__ __forceinline__ u32x4 expand_frag(const uint32_t (&v)[Fmt<N, M, B>::V
     return out;
 }
 
+// A operand and index register of the sparse matrix-core instruction for 32-row tile values `av`
+// (the lane's stored values per 16-deep step) and position stream `ws` (shifted so that bit 0 is
+// the lane's half), 32-deep step s2.
+template <int N, int M, int B, int s2>
+__device__ __forceinline__ void smf_operand(const uint32_t (&av)[Fmt<N, M, B>::KS][Fmt<N, M, B>::VW],
+                                            const uint32_t (&ws)[Fmt<N, M, B>::WPR], u32x4& a4, uint32_t& idx) {
+    typedef Fmt<N, M, B> F;
+    constexpr int P = 4 * s2 * F::HB;   // first position bit of this step in the lane's (shifted) stream
+    if constexpr (M == 8) {
+        // the lane's 16 columns are two groups of 8; position bits of both: 2 * HB bits from P
+        uint32_t field = ws[P >> 5] >> (P & 31);
+        if constexpr ((P & 31) + 2 * F::HB > 32 && (P >> 5) + 1 < F::WPR) field |= ws[(P >> 5) + 1] << (32 - (P & 31));
+        if constexpr (N == 2) {
+            // group g: stored (v0, v1) at positions (p0, p1); the lower 4-group takes those with
+            // position < 4, the upper the others, both with in-group positions (p0 & 3, p1 & 3)
+            uint32_t d[4];
+            idx = 0;
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+                const uint32_t w = av[2 * s2 + g][0];
+                const uint32_t p0 = (field >> (6 * g)) & 7u, p1 = (field >> (6 * g + 3)) & 7u;
+                const uint32_t lowmask = ((p0 & 4u) ? 0u : 0x0000FFFFu) | ((p1 & 4u) ? 0u : 0xFFFF0000u);
+                d[2 * g] = w & lowmask;
+                d[2 * g + 1] = w & ~lowmask;
+                const uint32_t nib = (p0 & 3u) | ((p1 & 3u) << 2);
+                idx |= (nib | (nib << 4)) << (8 * g);
+            }
+            a4 = u32x4{d[0], d[1], d[2], d[3]};
+        } else {
+            // one stored value per group of 8, paired with a zero at the same position
+            const uint32_t va = av[2 * s2][0], vb2 = av[2 * s2 + 1][0];
+            const uint32_t pa = field & 7u, pb = (field >> 3) & 7u;
+            a4 = u32x4{(pa & 4u) ? 0u : va, (pa & 4u) ? va : 0u, (pb & 4u) ? 0u : vb2, (pb & 4u) ? vb2 : 0u};
+            const uint32_t na = (pa & 3u) * 5u, nb = (pb & 3u) * 5u;     // (p, p) as a nibble
+            idx = (na | (na << 4)) | ((nb | (nb << 4)) << 8);
+        }
+    } else if constexpr (N == 2) {
+        // 2:4: values and positions as packed
+        a4 = u32x4{av[2 * s2][0], av[2 * s2][1], av[2 * s2 + 1][0], av[2 * s2 + 1][1]};
+        idx = ws[P >> 5] >> (P & 31);
+    } else {
+        // 1:4: each stored value gets a zero partner at the same position
+        const uint32_t w0 = av[2 * s2][0], w1 = av[2 * s2 + 1][0];
+        a4 = u32x4{w0 & 0xFFFFu, w0 >> 16, w1 & 0xFFFFu, w1 >> 16};
+        uint32_t y = (ws[P >> 5] >> (P & 31)) & 0xFFu;   // p3 p2 p1 p0, two bits each
+        y = (y | (y << 4)) & 0x0F0Fu;
+        y = (y | (y << 2)) & 0x3333u;
+        idx = y | (y << 2);
+    }
+}
+
 // One kept block: multiply the block held in ring slot (xr, av, aw) into acc.  With PREFETCH the
 // X rows of block column bj_next are requested into the same registers as soon as their
 // current contents have been turned into MFMA operands, and block t_next's compressed slice
@@ -549,52 +600,11 @@ struct BlockBody {
             }
             if constexpr (PREFETCH) load_x(xr[ks], p, cp, next.off, next.off2, bj_next, ks);
         }
-        constexpr int P = 4 * s2 * F::HB;   // first position bit of this step in the lane's (shifted) stream
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
             u32x4 a4;
             uint32_t idx;
-            if constexpr (M == 8) {
-                // the lane's 16 columns are two groups of 8; position bits of both: 2 * HB bits from P
-                uint32_t field = ws[rt][P >> 5] >> (P & 31);
-                if constexpr ((P & 31) + 2 * F::HB > 32 && (P >> 5) + 1 < F::WPR) field |= ws[rt][(P >> 5) + 1] << (32 - (P & 31));
-                if constexpr (N == 2) {
-                    // group g: stored (v0, v1) at positions (p0, p1); the lower 4-group takes those with
-                    // position < 4, the upper the others, both with in-group positions (p0 & 3, p1 & 3)
-                    uint32_t d[4];
-                    idx = 0;
-#pragma unroll
-                    for (int g = 0; g < 2; ++g) {
-                        const uint32_t w = av[rt][2 * s2 + g][0];
-                        const uint32_t p0 = (field >> (6 * g)) & 7u, p1 = (field >> (6 * g + 3)) & 7u;
-                        const uint32_t lowmask = ((p0 & 4u) ? 0u : 0x0000FFFFu) | ((p1 & 4u) ? 0u : 0xFFFF0000u);
-                        d[2 * g] = w & lowmask;
-                        d[2 * g + 1] = w & ~lowmask;
-                        const uint32_t nib = (p0 & 3u) | ((p1 & 3u) << 2);
-                        idx |= (nib | (nib << 4)) << (8 * g);
-                    }
-                    a4 = u32x4{d[0], d[1], d[2], d[3]};
-                } else {
-                    // one stored value per group of 8, paired with a zero at the same position
-                    const uint32_t va = av[rt][2 * s2][0], vb2 = av[rt][2 * s2 + 1][0];
-                    const uint32_t pa = field & 7u, pb = (field >> 3) & 7u;
-                    a4 = u32x4{(pa & 4u) ? 0u : va, (pa & 4u) ? va : 0u, (pb & 4u) ? 0u : vb2, (pb & 4u) ? vb2 : 0u};
-                    const uint32_t na = (pa & 3u) * 5u, nb = (pb & 3u) * 5u;     // (p, p) as a nibble
-                    idx = (na | (na << 4)) | ((nb | (nb << 4)) << 8);
-                }
-            } else if constexpr (N == 2) {
-                // 2:4: values and positions as packed
-                a4 = u32x4{av[rt][2 * s2][0], av[rt][2 * s2][1], av[rt][2 * s2 + 1][0], av[rt][2 * s2 + 1][1]};
-                idx = ws[rt][P >> 5] >> (P & 31);
-            } else {
-                // 1:4: each stored value gets a zero partner at the same position
-                const uint32_t w0 = av[rt][2 * s2][0], w1 = av[rt][2 * s2 + 1][0];
-                a4 = u32x4{w0 & 0xFFFFu, w0 >> 16, w1 & 0xFFFFu, w1 >> 16};
-                uint32_t y = (ws[rt][P >> 5] >> (P & 31)) & 0xFFu;   // p3 p2 p1 p0, two bits each
-                y = (y | (y << 4)) & 0x0F0Fu;
-                y = (y | (y << 2)) & 0x3333u;
-                idx = y | (y << 2);
-            }
+            smf_operand<N, M, B, s2>(av[rt], ws[rt], a4, idx);
             const bf16x8 afrag = __builtin_bit_cast(bf16x8, a4);
 #pragma unroll
             for (int c = 0; c < NACC; ++c) {
@@ -940,15 +950,5 @@ hipError_t launch_reg_shape(const SpmmArgs& a, int shape, hipStream_t st) {
         default: return launch_reg<N, M, B, 1, 8, 1, 0>(a, st);
     }
 }
-
-// One translation unit per N:M pattern provides this.
-template <int N, int M>
-hipError_t launch_reg_nm(const SpmmArgs& a, int B, int shape, hipStream_t st);
-
-#define CRISP_INSTANTIATE_NM(N, M)                                                           \
-    template <>                                                                              \
-    hipError_t launch_reg_nm<N, M>(const SpmmArgs& a, int B, int shape, hipStream_t st) {    \
-        return B == 64 ? launch_reg_shape<N, M, 64>(a, shape, st) : launch_reg_shape<N, M, 32>(a, shape, st); \
-    }
 
 }  // namespace crisp
