@@ -43,9 +43,11 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(SpmmArgs p, ConvLdsSched 
     constexpr int RT = F::RT, KS = F::KS, NACC = 2;
     typedef BlockBody<N, M, B, 1, false, 0, SMF> Body;
     constexpr int PB = CONV_LDS_POS_BYTES;
-    // packed slices in flight per wave (ring; as many as fit beside the accumulators)
+    // packed slices in flight per wave (ring).  Two, and six staging loads at a time: with longer
+    // rings the kernel needs more than 170 registers and only two workgroups fit a compute unit,
+    // which costs more than the deeper prefetch gains
     constexpr int AREGS = RT * KS * F::VW + RT * F::WPR;
-    constexpr int R = AREGS <= 12 ? 4 : AREGS <= 22 ? 2 : 1;
+    constexpr int R = AREGS <= 22 ? 2 : 1;
     extern __shared__ __attribute__((aligned(16))) unsigned char patch[];      // [PR][PC][PB]
     __shared__ uint32_t kept_bits[4][CONV_LDS_MAX_KB / 32];
     // per wave: its kept blocks in (channel block, tap) order, each channel block's run padded with
@@ -232,7 +234,7 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(SpmmArgs p, ConvLdsSched 
         const uint16_t* src_cb = p.act + (int64_t)cb * 64 * p.plane + (int64_t)img * p.H * p.W;
         // UN loads per lane are requested before the first is used: taken one at a time, every unit
         // would wait out a memory round trip
-        constexpr int UN = 12;
+        constexpr int UN = 6;
         for (int u0 = wave * rows_per_half; u0 < units; u0 += 4 * rows_per_half * UN) {
             uint32_t got[UN];
 #pragma unroll

@@ -454,7 +454,7 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
     // convolution with the input patch staged in LDS (forced shape 12).  Chosen automatically for
     // filters with several taps where at least two block-rows keep at least half of their blocks:
     // there the patch is reused often enough to pay for bringing it in (measured on the 3x3 layers
-    // of ResNet-50: 1.1-1.25x at those densities, slower below)
+    // of ResNet-50: 1.1-1.4x at those densities, slower or equal below)
     ConvLdsSched cs;
     const bool conv_lds_wanted = force_shape == 12 ||
         (force_shape < 0 && conv && conv->kh * conv->kw > 1 && g.Sb >= 2 && density_hint >= 0.5 && density_hint <= 1.0);
