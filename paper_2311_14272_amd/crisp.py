@@ -339,6 +339,27 @@ def fused_lowering_ok(cv, B: int, n: int, m: int) -> bool:
             and cv.stride <= 16 and plane <= (1 << 27) and pattern)
 
 
+def conv_lds_chosen(cv, B: int, S: int, density: float) -> bool:
+    """Whether crisp_conv_spmm runs this convolution with the input patch staged in LDS (the
+    library's own rule, restated here because the choice between the fused path and im2col below
+    depends on it): 64x64 blocks, C a multiple of 64, even W and Wo <= 64, a patch of at most 60 KB,
+    several taps (a strided 1x1 filter would stage every input column for a single use), and at
+    least two block-rows that keep at least half of their blocks."""
+    Ho = (cv.H + 2 * cv.pad - cv.kh) // cv.stride + 1
+    Wo = (cv.W + 2 * cv.pad - cv.kw) // cv.stride + 1
+    Sb = (S + B - 1) // B
+    taps = cv.kh * cv.kw
+    if B != 64 or cv.C % 64 or Wo % 2 or Wo > 64 or cv.W % 2 or cv.stride > 4 or taps > 64:
+        return False
+    if cv.C // 64 > 64 or taps * (cv.C // 64) > 128 or taps == 1:
+        return False
+    RG = 4 if Sb >= 4 else 2 if Sb >= 2 else 1
+    R = min(64 // Wo, Ho)
+    rows = ((4 // RG) * R - 1) * (1 if cv.kh == 1 else cv.stride) + cv.kh
+    cols = max((Wo - 1) * cv.stride + cv.kw, cv.W + cv.pad)
+    return rows * cols * 144 <= 60 * 1024 and Sb >= 2 and 0.5 <= density <= 1.0
+
+
 def lowering_path(cv, B: int, n: int, m: int, S: int, density: float) -> str:
     """How conv_forward runs this convolution: "none" (act is X), "fused" (crisp_conv_spmm) or
     "im2col" (crisp_im2col into a scratch X, then crisp_spmm).  The fused kernels locate strided or
@@ -355,7 +376,7 @@ def lowering_path(cv, B: int, n: int, m: int, S: int, density: float) -> str:
         return "none"
     if not pointwise and fused_lowering_ok(cv, B, n, m):
         paired = cv.stride == 1 and Wo % 2 == 0 and cv.W >= 2 and cv.C % B == 0
-        if paired or (cv.kh * cv.kw > 1 and ((S + B - 1) // B) * density <= FUSED_GENERAL_MAX_GATHER):
+        if paired or conv_lds_chosen(cv, B, S, density) or (cv.kh * cv.kw > 1 and ((S + B - 1) // B) * density <= FUSED_GENERAL_MAX_GATHER):
             return "fused"
     return "im2col"
 

@@ -1,4 +1,4 @@
-// Hybrid-sparse convolution with the input staged in LDS (stride 1, C a multiple of 64, 64x64 blocks).
+// Hybrid-sparse convolution with the input staged in LDS (C a multiple of 64, 64x64 blocks).
 //
 // The fused lowering of spmm_reg.h fetches the X rows of every kept block straight from the
 // convolution's input: for a kh x kw filter the same input element is then fetched up to kh*kw
@@ -33,11 +33,13 @@ struct ConvLdsSched {
     int row_groups;         // groups of RG block-rows
     int CB, kh, taps;       // channel blocks, filter height, kh * kw
     int PR, PC;             // patch rows and columns
+    int row_mul, ih_step;   // patch rows per output row; input rows per patch row (a 1-row filter with a stride
+                            // skips the input rows in between: row_mul 1, ih_step = stride; else stride, 1)
     int Kb;
 };
 
 template <int N, int M, bool SMF>
-__global__ __launch_bounds__(256) void conv_lds_kernel(SpmmArgs p, ConvLdsSched sc) {
+__global__ __launch_bounds__(256, 3) void conv_lds_kernel(SpmmArgs p, ConvLdsSched sc) {
     constexpr int B = 64;
     typedef Fmt<N, M, B> F;
     constexpr int RT = F::RT, KS = F::KS, NACC = 2;
@@ -130,7 +132,8 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(SpmmArgs p, ConvLdsSched 
     const bool col_ok = n0 < TP;
     const int n_ld = col_ok ? n0 : 0;
     const int r_local = n_ld / p.Wo, ow = n_ld - r_local * p.Wo;
-    const uint32_t lane_pos = (uint32_t)(((pt * sc.R + r_local) * sc.PC + ow) * PB + hh * 16);
+    const uint32_t lane_pos = (uint32_t)(((pt * sc.R + r_local) * sc.row_mul * sc.PC + ow * p.stride) * PB + hh * 16);
+    const uint32_t col_step = (uint32_t)(p.stride * PB);       // from a lane's first output column to its second
     const uint32_t a_off = (uint32_t)((jj * F::SLOTS + hh * F::FS * (SMF ? 2 : 1)) * 2);
     const uint32_t i_off = (uint32_t)(jj * F::WPR * 4);
     const uint32_t aw_sh = (uint32_t)hh * F::HB * (SMF ? 2 : 1);
@@ -177,8 +180,8 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(SpmmArgs p, ConvLdsSched 
                 u32x8 b8[NACC];
 #pragma unroll
                 for (int c = 0; c < NACC; ++c) {
-                    const u32x4 lo = *reinterpret_cast<const u32x4*>(base + c * PB + (2 * s2) * 32);
-                    const u32x4 hi = *reinterpret_cast<const u32x4*>(base + c * PB + (2 * s2 + 1) * 32);
+                    const u32x4 lo = *reinterpret_cast<const u32x4*>(base + c * col_step + (2 * s2) * 32);
+                    const u32x4 hi = *reinterpret_cast<const u32x4*>(base + c * col_step + (2 * s2 + 1) * 32);
                     b8[c] = u32x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
                 }
 #pragma unroll
@@ -200,7 +203,7 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(SpmmArgs p, ConvLdsSched 
                 bf16x8 bfrag[NACC];
 #pragma unroll
                 for (int c = 0; c < NACC; ++c)
-                    bfrag[c] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(base + c * PB + ks * 32));
+                    bfrag[c] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(base + c * col_step + ks * 32));
 #pragma unroll
                 for (int rt = 0; rt < RT; ++rt) {
                     const u32x4 a4 = expand_frag<N, M, B, ks>(av[rt][ks], ws[rt]);
@@ -241,7 +244,7 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(SpmmArgs p, ConvLdsSched 
             for (int k = 0; k < UN; ++k) {
                 const int unit = min(u0 + k * 4 * rows_per_half + sub, units - 1);
                 const int pr = unit >> 5, q = unit & 31;       // patch row, channel pair
-                const int ih = oh_base - p.pad + pr;
+                const int ih = (oh_base * sc.row_mul + pr) * sc.ih_step - p.pad;
                 const int ihc = min(max(ih, 0), p.H - 1);
                 const uint32_t mine = *reinterpret_cast<const uint32_t*>(src_cb + (int64_t)(2 * q + upper) * p.plane + ihc * p.W +
                                                                          2 * min(seg, segs - 1));
@@ -300,7 +303,7 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(SpmmArgs p, ConvLdsSched 
 
 // Geometry of the LDS-staged convolution for this problem; false if it does not apply.
 inline bool conv_lds_plan(const SpmmArgs& a, int B, int kh, ConvLdsSched* out) {
-    if (a.act == nullptr || B != 64 || a.stride != 1 || a.C % 64 != 0 || (a.Wo & 1) || a.Wo > 64 || (a.W & 1)) return false;
+    if (a.act == nullptr || B != 64 || a.stride > 4 || a.C % 64 != 0 || (a.Wo & 1) || a.Wo > 64 || (a.W & 1)) return false;
     const int taps = kh * a.kw;
     ConvLdsSched s;
     s.CB = a.C / 64; s.kh = kh; s.taps = taps; s.Kb = taps * s.CB;
@@ -311,9 +314,11 @@ inline bool conv_lds_plan(const SpmmArgs& a, int B, int kh, ConvLdsSched* out) {
     if (s.R > a.Ho) s.R = a.Ho;
     s.tiles_per_img = (a.Ho + s.PT * s.R - 1) / (s.PT * s.R);
     s.row_groups = (a.Sb + s.RG - 1) / s.RG;
-    s.PR = s.PT * s.R + kh - 1;
-    s.PC = a.Wo + a.kw - 1;
-    if (s.PC < a.W + a.pad) return false;              // every input column must have a place in the patch
+    s.row_mul = kh == 1 ? 1 : a.stride;
+    s.ih_step = kh == 1 ? a.stride : 1;
+    s.PR = (s.PT * s.R - 1) * s.row_mul + kh;
+    s.PC = (a.Wo - 1) * a.stride + a.kw;
+    if (s.PC < a.W + a.pad) s.PC = a.W + a.pad;        // every input column has a place in the patch
     if ((int64_t)s.PR * s.PC * CONV_LDS_POS_BYTES > CONV_LDS_MAX_PATCH) return false;
     *out = s;
     return true;

@@ -309,6 +309,12 @@ CONV_CASES = [
     (32, 11, 10, 2, 5, 5, 2, 64, 3, 4, 32, 0.5, 3),
     (128, 14, 14, 4, 3, 3, 1, 128, 2, 4, 64, 0.4, 2),
     (64, 14, 14, 6, 1, 1, 0, 128, 1, 8, 64, 0.5, 2),
+    # strided shapes of the LDS-staged convolution (3x3, 5x5, 1x1 that skips input rows, stride 3)
+    (128, 28, 28, 2, 3, 3, 1, 256, 2, 4, 64, 0.6, 2),
+    (256, 28, 28, 2, 1, 1, 0, 256, 2, 4, 64, 0.6, 2),
+    (64, 56, 56, 1, 1, 1, 0, 128, 1, 4, 64, 0.7, 2),
+    (64, 12, 16, 2, 3, 3, 1, 128, 2, 8, 64, 0.5, 3),
+    (64, 20, 20, 1, 5, 5, 2, 64, 1, 4, 64, 0.5, 2),
     # channel counts that are no multiple of B (first layers): every K-row located on its own
     (3, 20, 20, 2, 7, 7, 3, 64, 1, 8, 64, 0.7, 2),
     (3, 12, 12, 2, 3, 3, 1, 32, 2, 4, 32, 0.6, 1),
