@@ -342,22 +342,30 @@ def fused_lowering_ok(cv, B: int, n: int, m: int) -> bool:
 def conv_lds_chosen(cv, B: int, S: int, density: float) -> bool:
     """Whether crisp_conv_spmm runs this convolution with the input patch staged in LDS (the
     library's own rule, restated here because the choice between the fused path and im2col below
-    depends on it): 64x64 blocks, C a multiple of 64, even W and Wo <= 64, a patch of at most 60 KB,
-    several taps (a strided 1x1 filter would stage every input column for a single use), and at
-    least two block-rows that keep at least half of their blocks."""
+    depends on it).  Covered: 64x64 blocks, C a multiple of 64, even W and Wo <= 64, stride <= 4, a
+    patch of at most 60 KB, a channel plane below 2^25 elements.  Chosen: several taps (a strided
+    1x1 filter would stage every input column for a single use) and at least two block-rows, when
+    half of the blocks are kept; below that only where a staged patch still serves about six kept
+    blocks, Wo <= 28, at most four block-rows and at least 256 workgroups."""
     Ho = (cv.H + 2 * cv.pad - cv.kh) // cv.stride + 1
     Wo = (cv.W + 2 * cv.pad - cv.kw) // cv.stride + 1
     Sb = (S + B - 1) // B
     taps = cv.kh * cv.kw
     if B != 64 or cv.C % 64 or Wo % 2 or Wo > 64 or cv.W % 2 or cv.stride > 4 or taps > 64:
         return False
-    if cv.C // 64 > 64 or taps * (cv.C // 64) > 128 or taps == 1:
+    if cv.C // 64 > 64 or taps * (cv.C // 64) > 128 or cv.batch * cv.H * cv.W >= 1 << 25:
         return False
     RG = 4 if Sb >= 4 else 2 if Sb >= 2 else 1
+    PT = 4 // RG
     R = min(64 // Wo, Ho)
-    rows = ((4 // RG) * R - 1) * (1 if cv.kh == 1 else cv.stride) + cv.kh
+    rows = (PT * R - 1) * (1 if cv.kh == 1 else cv.stride) + cv.kh
     cols = max((Wo - 1) * cv.stride + cv.kw, cv.W + cv.pad)
-    return rows * cols * 144 <= 60 * 1024 and Sb >= 2 and 0.5 <= density <= 1.0
+    if rows * cols * 144 > 60 * 1024 or taps == 1 or Sb < 2 or not density <= 1.0:
+        return False
+    if density >= 0.5:
+        return True
+    wgs = cv.batch * ((Ho + PT * R - 1) // (PT * R)) * ((Sb + RG - 1) // RG)
+    return RG * density * taps >= 6.0 and Sb <= 4 and Wo <= 28 and wgs >= 256
 
 
 def lowering_path(cv, B: int, n: int, m: int, S: int, density: float) -> str:

@@ -39,17 +39,17 @@ struct ConvLdsSched {
 };
 
 template <int N, int M, bool SMF>
-__global__ __launch_bounds__(256, 3) void conv_lds_kernel(SpmmArgs p, ConvLdsSched sc) {
+__global__ __launch_bounds__(256, 4) void conv_lds_kernel(SpmmArgs p, ConvLdsSched sc) {
     constexpr int B = 64;
     typedef Fmt<N, M, B> F;
     constexpr int RT = F::RT, KS = F::KS, NACC = 2;
     typedef BlockBody<N, M, B, 1, false, 0, SMF> Body;
     constexpr int PB = CONV_LDS_POS_BYTES;
-    // packed slices in flight per wave (ring).  Two, and six staging loads at a time: with longer
-    // rings the kernel needs more than 170 registers and only two workgroups fit a compute unit,
-    // which costs more than the deeper prefetch gains
-    constexpr int AREGS = RT * KS * F::VW + RT * F::WPR;
-    constexpr int R = AREGS <= 22 ? 2 : 1;
+    // packed slices in flight per wave (ring).  One: the kernel then fits 128 registers and four
+    // workgroups share a compute unit, which gains more than a deeper prefetch of the slices (a ring
+    // of two at three workgroups per compute unit was 1.2-1.3x slower on the 14x14 layers of
+    // ResNet-50, whose 1024 workgroups are exactly four per compute unit)
+    constexpr int R = 1;
     extern __shared__ __attribute__((aligned(16))) unsigned char patch[];      // [PR][PC][PB]
     __shared__ uint32_t kept_bits[4][CONV_LDS_MAX_KB / 32];
     // per wave: its kept blocks in (channel block, tap) order, each channel block's run padded with
@@ -221,52 +221,63 @@ __global__ __launch_bounds__(256, 3) void conv_lds_kernel(SpmmArgs p, ConvLdsSch
     };
 
     // Staging: a lane loads one dword (two neighbouring input positions) of one channel; lanes 0..31
-    // of a wave walk along the row(s) of an even channel, lanes 32..63 along the same positions of
-    // the next channel.  The two halves swap their dwords, so that the lower half can write the
-    // channel pair of the first position and the upper half that of the second as one dword each
-    // (patch[pos][channel]).  No divisions, coalesced loads, one LDS write per load.
+    // of a wave walk along a row of an even channel, lanes 32..63 along the same positions of the
+    // next channel.  One lane-swap instruction hands every lane both dwords; the lower half then
+    // writes the channel pair of the first position and the upper half that of the second as one
+    // dword each (patch[pos][channel]).  A lane keeps its place in the row and its channel pair(s)
+    // for the whole kernel and walks down the patch rows: the row is the scalar offset of a buffer
+    // load, so a load costs no address arithmetic (coalesced loads, one LDS write per load).
     const int segs = p.W >> 1;                                 // dwords of one input row of one channel
     const int segw_log = segs > 16 ? 5 : segs > 8 ? 4 : segs > 4 ? 3 : segs > 2 ? 2 : segs > 1 ? 1 : 0;   // lanes per row: 2^segw_log >= segs
-    const int rows_per_half = 32 >> segw_log;                  // (channel pair, patch row) units per half-wave
+    const int pairs_per_half = 32 >> segw_log;                 // channel pairs a half-wave covers at a time
     const int l32 = lane & 31, upper = lane >> 5;
-    const int seg = l32 & ((1 << segw_log) - 1), sub = l32 >> segw_log;
-    const int units = sc.PR * 32;                              // (patch row, channel pair) units per channel block
-    const int halo_cols = sc.PC - p.W;                         // zero columns of the patch
+    const int seg = l32 & ((1 << segw_log) - 1);
+    const int q0 = wave * pairs_per_half + (l32 >> segw_log);  // the lane's first channel pair
+    const int q_step = 4 * pairs_per_half;                     // from one of its channel pairs to the next
+    const int q_turns = q_step >= 32 ? 1 : 32 / q_step;        // (32 is a multiple of a smaller q_step)
+    const bool lane_writes = seg < segs && wave * pairs_per_half < 32;
+    const uint32_t pair_sel = upper ? SEL_HI : SEL_LO;
+    const uint32_t write0 = (uint32_t)((2 * seg + upper + p.pad) * PB);
+    {
+        // zero columns of the patch left and right of the image: staging never touches them
+        const int halo_cols = sc.PC - p.W;
+        for (int i = tid; i < sc.PR * halo_cols * 8; i += 256) {
+            const int part = i & 7, pos = i >> 3;
+            const int pr = pos / halo_cols, hcol = pos - pr * halo_cols;
+            const int pc = hcol < p.pad ? hcol : p.W + hcol;   // left halo, then right halo
+            *reinterpret_cast<u32x4*>(patch + ((pr * sc.PC + pc) * PB + part * 16)) = u32x4{0u, 0u, 0u, 0u};
+        }
+    }
     for (int cb = 0; cb < sc.CB; ++cb) {
         __syncthreads();                                       // everybody is done with the previous patch
-        const uint16_t* src_cb = p.act + (int64_t)cb * 64 * p.plane + (int64_t)img * p.H * p.W;
-        // UN loads per lane are requested before the first is used: taken one at a time, every unit
+        const rsrc_t ract = make_rsrc(p.act + (int64_t)cb * 64 * p.plane + (int64_t)img * p.H * p.W);
+        // UN loads per lane are requested before the first is used: taken one at a time, every row
         // would wait out a memory round trip
         constexpr int UN = 6;
-        for (int u0 = wave * rows_per_half; u0 < units; u0 += 4 * rows_per_half * UN) {
-            uint32_t got[UN];
+        for (int turn = 0; turn < q_turns; ++turn) {
+            const int q = q0 + turn * q_step;                  // < 32 for every lane of a wave that writes
+            const uint32_t lane_off = ((uint32_t)(2 * min(q, 31) + upper) * (uint32_t)p.plane + (uint32_t)(2 * min(seg, segs - 1))) * 2u;
+            const uint32_t write_q = write0 + (uint32_t)(q * 4);
+            for (int pr0 = 0; pr0 < sc.PR; pr0 += UN) {
+                uint32_t got[UN];
 #pragma unroll
-            for (int k = 0; k < UN; ++k) {
-                const int unit = min(u0 + k * 4 * rows_per_half + sub, units - 1);
-                const int pr = unit >> 5, q = unit & 31;       // patch row, channel pair
-                const int ih = (oh_base * sc.row_mul + pr) * sc.ih_step - p.pad;
-                const int ihc = min(max(ih, 0), p.H - 1);
-                const uint32_t mine = *reinterpret_cast<const uint32_t*>(src_cb + (int64_t)(2 * q + upper) * p.plane + ihc * p.W +
-                                                                         2 * min(seg, segs - 1));
-                got[k] = ((unsigned)ih < (unsigned)p.H) ? mine : 0u;
-            }
+                for (int k = 0; k < UN; ++k) {
+                    const int pr = min(pr0 + k, sc.PR - 1);
+                    const int ih = (oh_base * sc.row_mul + pr) * sc.ih_step - p.pad;
+                    const int ihc = min(max(ih, 0), p.H - 1);
+                    const uint32_t mine = __builtin_amdgcn_raw_buffer_load_b32(ract, lane_off, (uint32_t)(ihc * p.W * 2), 0);
+                    got[k] = ((unsigned)ih < (unsigned)p.H) ? mine : 0u;
+                }
 #pragma unroll
-            for (int k = 0; k < UN; ++k) {
-                const int unit = u0 + k * 4 * rows_per_half + sub;
-                const int pr = unit >> 5, q = unit & 31;
-                const uint32_t other = (uint32_t)__shfl_xor((int)got[k], 32, 64);
-                // lower half: first position, (even channel, odd channel) = (mine.lo, other.lo);
-                // upper half: second position, (other.hi, mine.hi)
-                const uint32_t pair = upper ? __builtin_amdgcn_perm(got[k], other, SEL_HI) : __builtin_amdgcn_perm(other, got[k], SEL_LO);
-                if (unit < units && seg < segs)
-                    *reinterpret_cast<uint32_t*>(patch + ((pr * sc.PC + 2 * seg + upper + p.pad) * PB + q * 4)) = pair;
+                for (int k = 0; k < UN; ++k) {
+                    // [0]: the even channel's dword in every lane, [1]: the odd channel's
+                    const auto both = __builtin_amdgcn_permlane32_swap(got[k], got[k], false, false);
+                    // lower half: first position, (even.lo, odd.lo); upper half: second position, (even.hi, odd.hi)
+                    const uint32_t pair = __builtin_amdgcn_perm(both[1], both[0], pair_sel);
+                    if (lane_writes && pr0 + k < sc.PR)
+                        *reinterpret_cast<uint32_t*>(patch + write_q + (uint32_t)((pr0 + k) * sc.PC * PB)) = pair;
+                }
             }
-        }
-        for (int i = tid; i < 64 * sc.PR * halo_cols; i += 256) {
-            const int c = i & 63, rest = i >> 6;
-            const int pr = rest / halo_cols, hcol = rest - pr * halo_cols;
-            const int pc = hcol < p.pad ? hcol : p.W + hcol;   // left halo, then right halo
-            *reinterpret_cast<uint16_t*>(patch + ((pr * sc.PC + pc) * PB + c * 2)) = 0;
         }
         __syncthreads();
         // ---- the wave's kept blocks of this channel block, all taps --------------------------------
@@ -308,6 +319,7 @@ inline bool conv_lds_plan(const SpmmArgs& a, int B, int kh, ConvLdsSched* out) {
     ConvLdsSched s;
     s.CB = a.C / 64; s.kh = kh; s.taps = taps; s.Kb = taps * s.CB;
     if (taps > 64 || s.CB > 64 || s.Kb > CONV_LDS_MAX_KB || a.K != taps * a.C) return false;
+    if (a.plane >= ((int64_t)1 << 25)) return false;    // staging addresses 64 channel planes with 32-bit byte offsets
     s.RG = a.Sb >= 4 ? 4 : a.Sb >= 2 ? 2 : 1;
     s.PT = 4 / s.RG;
     s.R = 64 / a.Wo;

@@ -381,6 +381,22 @@ template <> hipError_t launch_conv_lds_nm<8, 8>(const SpmmArgs&, const ConvLdsSc
 // wide strips once they give every SIMD work or the block-rows are long (the expansion of A is
 // shared by twice the columns); otherwise narrow strips; and when even those are few, 4 or 8
 // waves split each block-row's list so that enough loads are in flight to cover the latency.
+static int pick_shape(const Geometry& g, int64_t Ncol, int blocks_per_row, bool smf);
+
+// Whether the LDS-staged convolution is the faster choice (measured on 3x3 layers of the ResNet-50
+// shapes, all patterns, block densities 0.25 .. 1): with at least half of the blocks kept the patch
+// is reused often enough in every shape (1.1-1.4x over the register kernels); below that only where
+// a staged patch still serves about six kept blocks, the tiles are small (output width <= 28) and
+// one group of block-rows covers the layer (1.1-1.7x there, 0.7-0.9x elsewhere), and the grid
+// gives every compute unit a workgroup.
+static bool conv_lds_pays(const ConvLdsSched& s, int Sb, double density, int batch, int Wo) {
+    if (s.taps <= 1 || Sb < 2 || !(density <= 1.0)) return false;
+    if (density >= 0.5) return true;
+    const double blocks_per_patch = s.RG * density * s.taps;
+    const int64_t wgs = (int64_t)batch * s.tiles_per_img * s.row_groups;
+    return blocks_per_patch >= 6.0 && Sb <= 4 && Wo <= 28 && wgs >= 256;
+}
+
 static int pick_shape(const Geometry& g, int64_t Ncol, int blocks_per_row, bool smf) {
     const int64_t wide = (int64_t)g.Sb * ((Ncol + 127) / 128);
     const int64_t narrow = (int64_t)g.Sb * ((Ncol + 63) / 64);
@@ -451,14 +467,11 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
         a.inv_Ho = 1.0 / a.Ho;
     }
     if (g.B == 16) return launch_b16(a, st);
-    // convolution with the input patch staged in LDS (forced shape 12).  Chosen automatically for
-    // filters with several taps where at least two block-rows keep at least half of their blocks:
-    // there the patch is reused often enough to pay for bringing it in (measured on the 3x3 layers
-    // of ResNet-50: 1.1-1.4x at those densities, slower or equal below)
+    // convolution with the input patch staged in LDS (forced shape 12)
     ConvLdsSched cs;
-    const bool conv_lds_wanted = force_shape == 12 ||
-        (force_shape < 0 && conv && conv->kh * conv->kw > 1 && g.Sb >= 2 && density_hint >= 0.5 && density_hint <= 1.0);
-    if (conv && conv_lds_wanted && (Ncol % 4) == 0 && ldy <= ((int64_t)1 << 23) && conv_lds_plan(a, g.B, conv->kh, &cs)) {
+    const bool conv_lds_wanted = force_shape == 12 || force_shape < 0;
+    if (conv && conv_lds_wanted && (Ncol % 4) == 0 && ldy <= ((int64_t)1 << 23) && conv_lds_plan(a, g.B, conv->kh, &cs) &&
+        (force_shape == 12 || conv_lds_pays(cs, g.Sb, density_hint, conv->batch, a.Wo))) {
         a.use_smf = 1;
         switch (g.n * 16 + g.m) {
             case 1 * 16 + 4: return launch_conv_lds_nm<1, 4>(a, cs, conv->batch, st);
