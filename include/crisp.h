@@ -267,7 +267,7 @@ CRISP_API crisp_status crisp_spmm(const crisp_layer_desc *desc, const int32_t *r
  * come from one 4-byte load, otherwise (strided, odd Wo, 1x1 with stride) each column is
  * located and loaded on its own.  Other channel counts (the first layer of a network):
  * every K-row is split into (tap, channel) on its own; needs K <= 65535 and an activation
- * below 4 GiB.  For stride <= 4, C % 64 == 0, 64x64 blocks, even W and Wo <= 64 there is also
+ * below 4 GiB.  For stride <= 4, C % 64 == 0, 64x64 blocks, even W <= 64 and even Wo there is also
  * a kernel that stages the input patch of a tile of output rows in LDS once for all filter
  * taps and up to four block-rows (chosen for dense multi-row layers; ws == NULL with
  * ws_bytes == 13 forces it, 1..4 and 8..11 force the shapes of crisp_spmm).

@@ -342,7 +342,7 @@ def fused_lowering_ok(cv, B: int, n: int, m: int) -> bool:
 def conv_lds_chosen(cv, B: int, S: int, density: float) -> bool:
     """Whether crisp_conv_spmm runs this convolution with the input patch staged in LDS (the
     library's own rule, restated here because the choice between the fused path and im2col below
-    depends on it).  Covered: 64x64 blocks, C a multiple of 64, even W and Wo <= 64, stride <= 4, a
+    depends on it).  Covered: 64x64 blocks, C a multiple of 64, even W <= 64 and Wo, stride <= 4, a
     patch of at most 60 KB, a channel plane below 2^25 elements.  Chosen: several taps (a strided
     1x1 filter would stage every input column for a single use) and at least two block-rows, when
     half of the blocks are kept; below that only where a staged patch still serves about six kept
@@ -351,7 +351,7 @@ def conv_lds_chosen(cv, B: int, S: int, density: float) -> bool:
     Wo = (cv.W + 2 * cv.pad - cv.kw) // cv.stride + 1
     Sb = (S + B - 1) // B
     taps = cv.kh * cv.kw
-    if B != 64 or cv.C % 64 or Wo % 2 or Wo > 64 or cv.W % 2 or cv.stride > 4 or taps > 64:
+    if B != 64 or cv.C % 64 or Wo % 2 or Wo > 64 or cv.W % 2 or cv.W > 64 or cv.stride > 4 or taps > 64:
         return False
     if cv.C // 64 > 64 or taps * (cv.C // 64) > 128 or cv.batch * cv.H * cv.W >= 1 << 25:
         return False

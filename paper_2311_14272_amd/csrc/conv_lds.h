@@ -314,7 +314,8 @@ __global__ __launch_bounds__(256, 4) void conv_lds_kernel(SpmmArgs p, ConvLdsSch
 
 // Geometry of the LDS-staged convolution for this problem; false if it does not apply.
 inline bool conv_lds_plan(const SpmmArgs& a, int B, int kh, ConvLdsSched* out) {
-    if (a.act == nullptr || B != 64 || a.stride > 4 || a.C % 64 != 0 || (a.Wo & 1) || a.Wo > 64 || (a.W & 1)) return false;
+    if (a.act == nullptr || B != 64 || a.stride > 4 || a.C % 64 != 0 || (a.Wo & 1) || a.Wo > 64 || (a.W & 1) || a.W > 64)
+        return false;    // (32 lanes stage one input row as dwords)
     const int taps = kh * a.kw;
     ConvLdsSched s;
     s.CB = a.C / 64; s.kh = kh; s.taps = taps; s.Kb = taps * s.CB;

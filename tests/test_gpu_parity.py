@@ -315,6 +315,9 @@ CONV_CASES = [
     (64, 56, 56, 1, 1, 1, 0, 128, 1, 4, 64, 0.7, 2),
     (64, 12, 16, 2, 3, 3, 1, 128, 2, 8, 64, 0.5, 3),
     (64, 20, 20, 1, 5, 5, 2, 64, 1, 4, 64, 0.5, 2),
+    # input rows wider than the LDS-staged kernel takes (64): it must hand over to the register kernels
+    (64, 3, 66, 1, 3, 3, 0, 128, 2, 4, 64, 0.6, 1),
+    (64, 5, 128, 1, 3, 3, 1, 128, 2, 4, 64, 0.6, 2),
     # channel counts that are no multiple of B (first layers): every K-row located on its own
     (3, 20, 20, 2, 7, 7, 3, 64, 1, 8, 64, 0.7, 2),
     (3, 12, 12, 2, 3, 3, 1, 32, 2, 4, 32, 0.6, 1),
