@@ -237,7 +237,10 @@ __global__ __launch_bounds__(256, 4) void conv_lds_kernel(SpmmArgs p, ConvLdsSch
     const int q_turns = q_step >= 32 ? 1 : 32 / q_step;        // (32 is a multiple of a smaller q_step)
     const bool lane_writes = seg < segs && wave * pairs_per_half < 32;
     const uint32_t pair_sel = upper ? SEL_HI : SEL_LO;
-    const uint32_t write0 = (uint32_t)((2 * seg + upper + p.pad) * PB);
+    const uint32_t write0 = (uint32_t)((2 * seg + upper + p.pad) * PB + q0 * 4);
+    const uint32_t lane_off = ((uint32_t)(2 * min(q0, 31) + upper) * (uint32_t)p.plane + (uint32_t)(2 * min(seg, segs - 1))) * 2u;
+    const uint32_t turn_bytes = (uint32_t)(2 * q_step) * (uint32_t)p.plane * 2u;   // from one channel pair of a lane to its next
+    const uint32_t pr_inv = (65536u + (uint32_t)sc.PR - 1u) / (uint32_t)sc.PR;     // u / PR = (u * pr_inv) >> 16 for the few hundred units
     {
         // zero columns of the patch left and right of the image: staging never touches them
         const int halo_cols = sc.PC - p.W;
@@ -252,31 +255,33 @@ __global__ __launch_bounds__(256, 4) void conv_lds_kernel(SpmmArgs p, ConvLdsSch
         __syncthreads();                                       // everybody is done with the previous patch
         const rsrc_t ract = make_rsrc(p.act + (int64_t)cb * 64 * p.plane + (int64_t)img * p.H * p.W);
         // UN loads per lane are requested before the first is used: taken one at a time, every row
-        // would wait out a memory round trip
-        constexpr int UN = 6;
-        for (int turn = 0; turn < q_turns; ++turn) {
-            const int q = q0 + turn * q_step;                  // < 32 for every lane of a wave that writes
-            const uint32_t lane_off = ((uint32_t)(2 * min(q, 31) + upper) * (uint32_t)p.plane + (uint32_t)(2 * min(seg, segs - 1))) * 2u;
-            const uint32_t write_q = write0 + (uint32_t)(q * 4);
-            for (int pr0 = 0; pr0 < sc.PR; pr0 += UN) {
-                uint32_t got[UN];
+        // would wait out a memory round trip.  The lane's (channel pair, patch row) units are numbered
+        // u = turn * PR + pr; what depends on the unit is uniform and goes into the scalar offset of
+        // the load and one scalar addend of the LDS address.
+        constexpr int UN = 12;
+        const int units = q_turns * sc.PR;
+        for (int u0 = 0; u0 < units; u0 += UN) {
+            uint32_t got[UN];
 #pragma unroll
-                for (int k = 0; k < UN; ++k) {
-                    const int pr = min(pr0 + k, sc.PR - 1);
-                    const int ih = (oh_base * sc.row_mul + pr) * sc.ih_step - p.pad;
-                    const int ihc = min(max(ih, 0), p.H - 1);
-                    const uint32_t mine = __builtin_amdgcn_raw_buffer_load_b32(ract, lane_off, (uint32_t)(ihc * p.W * 2), 0);
-                    got[k] = ((unsigned)ih < (unsigned)p.H) ? mine : 0u;
-                }
+            for (int k = 0; k < UN; ++k) {
+                const int u = min(u0 + k, units - 1);
+                const int turn = (int)(((uint32_t)u * pr_inv) >> 16), pr = u - turn * sc.PR;
+                const int ih = (oh_base * sc.row_mul + pr) * sc.ih_step - p.pad;
+                const int ihc = min(max(ih, 0), p.H - 1);
+                const uint32_t soff = (uint32_t)turn * turn_bytes + (uint32_t)(ihc * p.W * 2);
+                const uint32_t mine = __builtin_amdgcn_raw_buffer_load_b32(ract, lane_off, soff, 0);
+                got[k] = ((unsigned)ih < (unsigned)p.H) ? mine : 0u;
+            }
 #pragma unroll
-                for (int k = 0; k < UN; ++k) {
-                    // [0]: the even channel's dword in every lane, [1]: the odd channel's
-                    const auto both = __builtin_amdgcn_permlane32_swap(got[k], got[k], false, false);
-                    // lower half: first position, (even.lo, odd.lo); upper half: second position, (even.hi, odd.hi)
-                    const uint32_t pair = __builtin_amdgcn_perm(both[1], both[0], pair_sel);
-                    if (lane_writes && pr0 + k < sc.PR)
-                        *reinterpret_cast<uint32_t*>(patch + write_q + (uint32_t)((pr0 + k) * sc.PC * PB)) = pair;
-                }
+            for (int k = 0; k < UN; ++k) {
+                const int u = u0 + k;
+                const int turn = (int)(((uint32_t)u * pr_inv) >> 16), pr = u - turn * sc.PR;
+                // [0]: the even channel's dword in every lane, [1]: the odd channel's
+                const auto both = __builtin_amdgcn_permlane32_swap(got[k], got[k], false, false);
+                // lower half: first position, (even.lo, odd.lo); upper half: second position, (even.hi, odd.hi)
+                const uint32_t pair = __builtin_amdgcn_perm(both[1], both[0], pair_sel);
+                if (lane_writes && u < units)
+                    *reinterpret_cast<uint32_t*>(patch + write0 + (uint32_t)(turn * q_step * 4 + pr * sc.PC * PB)) = pair;
             }
         }
         __syncthreads();
