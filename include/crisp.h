@@ -244,8 +244,9 @@ CRISP_API crisp_status crisp_im2col(const crisp_conv_desc *conv, const uint16_t 
  *   launch shape ws_bytes - 1 (0..3 register-expansion kernels: wide strips, narrow
  *   strips, 4- and 8-way split of the block list; 4 generic LDS-expansion kernel;
  *   5 / 6 block-row resident in LDS with narrow / wide strips; 7..10 shapes 0..3
- *   with the sparse matrix-core instruction where the pattern allows it) for tests and
- *   tuning; a shape that does not apply to the problem falls back to the automatic
+ *   with the sparse matrix-core instruction where the pattern allows it) and ws_bytes
+ *   == 14 the kernel that keeps a strip of X in registers for all block-rows (K <= 128,
+ *   64x64 blocks), for tests and tuning; a shape that does not apply to the problem falls back to the automatic
  *   choice.  Results agree across shapes within the summation-order tolerance.
  * Errors: EINVAL, ESHAPE, EALIGN, EUNSUPPORTED (x_layout), EDEVICE.
  */

@@ -18,6 +18,7 @@
 // next block is requested while the current one is multiplied.
 #pragma once
 #include "spmm_reg.h"
+#include "spmm_xres.h"
 
 namespace crisp {
 
@@ -372,6 +373,7 @@ hipError_t launch_conv_lds_nm(const SpmmArgs& a, const ConvLdsSched& s, int batc
 #define CRISP_INSTANTIATE_NM(N, M)                                                           \
     template <>                                                                              \
     hipError_t launch_reg_nm<N, M>(const SpmmArgs& a, int B, int shape, hipStream_t st) {    \
+        if (shape == XRES_SHAPE) return launch_xres<N, M>(a, st);                            \
         return B == 64 ? launch_reg_shape<N, M, 64>(a, shape, st) : launch_reg_shape<N, M, 32>(a, shape, st); \
     }                                                                                        \
     template <>                                                                              \

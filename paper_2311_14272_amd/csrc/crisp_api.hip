@@ -269,7 +269,7 @@ static crisp_status spmm_impl(const crisp_layer_desc* desc, const int32_t* row_p
     { crisp_status es = check_epilogue(ep, Ncol); if (es != CRISP_OK) return es; }
     // ws_bytes doubles as a tuning knob when ws is NULL: 0 = automatic launch shape, 1..11 force
     // shape (value - 1); results do not depend on it.
-    const int force_shape = (!ws && ws_bytes >= 1 && ws_bytes <= 11) ? (int)ws_bytes - 1 : -1;
+    const int force_shape = (!ws && ws_bytes >= 1 && ws_bytes <= 11) ? (int)ws_bytes - 1 : (!ws && ws_bytes == 14) ? 13 : -1;
     hipError_t e = launch_spmm(g, desc->block_density, desc->select_mode == CRISP_ROW_UNIFORM, force_shape, row_ptr, col_idx, vals,
                                idx_words, X, nullptr, Ncol,
                                ldx, Y, ldy, y_dtype, ep, (hipEvent_t)ev_start, (hipEvent_t)ev_stop, (hipStream_t)stream);

@@ -498,8 +498,16 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
     // forced shapes 7..10: shapes 0..3 of the register kernels with the sparse matrix-core instruction
     // (the automatic choice always takes it where the pattern is eligible: it was faster for every
     // measured layer; shapes 0..3 force the dense-expansion instantiations)
-    a.use_smf = (force_shape < 0 || (force_shape >= 7 && force_shape <= 10)) ? 1 : 0;
-    const int shape = (force_shape >= 0 && force_shape <= 3) ? force_shape
+    a.use_smf = (force_shape < 0 || force_shape == 13 || (force_shape >= 7 && force_shape <= 10)) ? 1 : 0;
+    // X-resident kernel for short K (forced shape 13).  Chosen for one block column, several
+    // block-rows, patterns that go to the sparse matrix-core instruction and long X rows: 1.12x on the
+    // 64 -> 256 channel layers of ResNet-50 at batch 256 (107 vs 120 us for 103 MB read and 411 MB
+    // written; a plain fill of 411 MB takes 61 us, a copy of 257 + 257 MB 97 us); equal within
+    // 6 % either way for two block columns or the dense-expansion patterns
+    const bool xres = xres_covers(a, g.B) &&
+        (force_shape == 13 || (force_shape < 0 && g.Kb == 1 && g.Sb >= 2 && g.n <= 2 && Ncol >= ((int64_t)1 << 18)));
+    const int shape = xres ? XRES_SHAPE
+                    : (force_shape >= 0 && force_shape <= 3) ? force_shape
                     : (force_shape >= 7 && force_shape <= 10) ? force_shape - 7
                     : pick_shape(g, Ncol, bpr, a.use_smf && g.n <= 2);
     // the specialised kernels assume whole 16-row MFMA steps of X (K % 16 == 0) and whole groups

@@ -10,7 +10,10 @@ from gpu_util import dev, run_select_pack
 
 pytestmark = pytest.mark.gpu
 
-CASES = [synth.small_cases()[i] for i in (0, 1, 2, 5, 7, 9, 13)] + synth.b16_cases()[:2]
+CASES = [synth.small_cases()[i] for i in (0, 1, 2, 5, 7, 9, 13)] + synth.b16_cases()[:2] + [
+    # short K: the kernel that keeps X in registers (forced shape 13) stores block-row by block-row
+    synth.LayerSpec("ep_k128_2:8", 200, 128, 520, 2, 8, 64, 0.5, synth.SAL_MAG, 0.05),
+    synth.LayerSpec("ep_k64_4:8", 256, 64, 264, 4, 8, 64, 1.0, synth.SAL_MAG, 0.05)]
 
 
 def _check(Y, Yref, Aref, bf16, what):
@@ -65,7 +68,7 @@ def test_spmm_epilogue(L):
                                          res if cb["res"] else None, cb["relu"])
             ep = crisp.epilogue(dscale if cb["scale"] else None, dbias if cb["bias"] else None,
                                 dres if cb["res"] else None, ldr, cb["relu"])
-            for shape in (None, 0, 1, 2, 4, 5, 6, 8):
+            for shape in (None, 0, 1, 2, 4, 5, 6, 8, 13):
                 Y = torch.full((L.S + 1, ldy), float("nan"), dtype=tdt, device="cuda")
                 crisp.crisp_spmm_ep(layer.desc, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dX, L.Ncol, ldx,
                                     Y, ldy, yd, ep, ws=None, ws_bytes=0 if shape is None else shape + 1)

@@ -198,6 +198,40 @@ def test_lds_resident_block_rows(case):
             check_product(Y, Yref, Aref, yd, "%s shape %d" % (L.name, shape))
 
 
+XRES_CASES = [
+    # short K (one or two 64-wide block columns): the kernel that keeps the strip of X in registers.
+    # One and two block columns, ragged S, a last strip group with idle waves, more block-rows than
+    # one group holds, patterns with and without the sparse matrix-core instruction, uneven rows
+    synth.LayerSpec("xres_k64_2:8", 256, 64, 1000, 2, 8, 64, 1.0, synth.SAL_MAG, 0.05),
+    synth.LayerSpec("xres_k128_1:4", 200, 128, 520, 1, 4, 64, 0.5, synth.SAL_MAG, 0.05),
+    synth.LayerSpec("xres_k128_2:4_full", 512, 128, 264, 2, 4, 64, 1.0, synth.SAL_GRAD, 0.05),
+    synth.LayerSpec("xres_k96_4:8", 320, 96, 136, 4, 8, 64, 0.5, synth.SAL_MAG, 0.05),
+    synth.LayerSpec("xres_k48_3:4", 64, 48, 72, 3, 4, 64, 1.0, synth.SAL_MAG, 0.05),
+    synth.LayerSpec("xres_k128_1:8_rows40", 2560, 128, 68, 1, 8, 64, 0.5, synth.SAL_MAG, 0.05),
+    synth.LayerSpec("xres_k128_4:4_uneven", 384, 128, 300, 4, 4, 64, 0.4, synth.SAL_MAG, 0.05, None, synth.LAYER_TOPK),
+    synth.LayerSpec("xres_k64_8:8", 128, 64, 260, 8, 8, 64, 1.0, synth.SAL_MAG, 0.05),
+]
+
+
+@pytest.mark.parametrize("L", XRES_CASES, ids=lambda L: L.name)
+def test_x_resident_short_k(L):
+    """The short-K product kernel (forced, and whatever the library picks) against the oracle."""
+    print("case", L.name, flush=True)
+    W, G, X = synth.draw_small(L, 29)
+    sel, vals, idxw, flags = oracle_all(L, W, G)
+    layer, out = run_select_pack(L, W, G)
+    assert_select_pack_equal(L, out, sel, vals, idxw, flags)
+    ldx = (L.Ncol + 7) // 8 * 8
+    Xp = np.zeros((L.K, ldx), dtype=np.uint16)
+    Xp[:, : L.Ncol] = X
+    dX = dev(Xp)
+    Yref, Aref = oracle.gemm_masked(W, sel.mask, X)
+    for shape in (13, None):
+        for yd in (crisp.Y_F32, crisp.Y_BF16):
+            Y = run_spmm(layer, dX, L.Ncol, ldx, yd, L.S, shape=shape)
+            check_product(Y, Yref, Aref, yd, "%s shape %s" % (L.name, shape))
+
+
 TINY_CASES = [
     # degenerate sizes: one row, one group, one column, fewer rows than a block, K below one block
     synth.LayerSpec("tiny_1x4x1", 1, 4, 1, 1, 4, 16, 1.0, synth.SAL_MAG, 0.5),
