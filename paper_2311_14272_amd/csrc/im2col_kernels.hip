@@ -172,6 +172,58 @@ __global__ __launch_bounds__(256) void maxpool_kernel(Im2colArgs p, uint32_t tot
     p.X[e] = (uint16_t)best_bits;
 }
 
+// 3x3 window, stride 2, padding 1, W a multiple of 8 (the pooling layer of ResNet-like networks):
+// a thread produces four neighbouring outputs from, per input row, one 16-byte load (input columns
+// 8j .. 8j+7) and one 2-byte load (column 8j-1): 6 loads for 4 outputs instead of 36, which takes
+// the kernel from the load units' instruction rate to the memory rate.  Same comparison order as
+// maxpool_kernel (rows outer, columns inner, strict >), so the results are the same bits.
+__global__ __launch_bounds__(256) void maxpool_3x3s2_kernel(Im2colArgs p, uint32_t quads) {
+    typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+    const uint32_t e = blockIdx.x * 256u + threadIdx.x;
+    if (e >= quads) return;
+    const uint32_t wq = (uint32_t)p.Wo / 4u, ho = (uint32_t)p.Ho;
+    const int j = (int)(e % wq);
+    const uint32_t t = e / wq;
+    const int oh = (int)(t % ho);
+    const uint32_t plane = t / ho;              // c * batch + image
+    const uint16_t* src = p.act + (int64_t)plane * p.H * p.W;
+    u32x4 main_[3];
+    uint32_t left[3];
+#pragma unroll
+    for (int a = 0; a < 3; ++a) {
+        const int ih = min(max(oh * 2 + a - 1, 0), p.H - 1);
+        main_[a] = *reinterpret_cast<const u32x4*>(src + ih * p.W + 8 * j);
+        left[a] = src[ih * p.W + max(8 * j - 1, 0)];
+    }
+    float best[4];
+    uint32_t best_bits[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) { best[k] = -__builtin_inff(); best_bits[k] = 0xFF80u; }
+#pragma unroll
+    for (int a = 0; a < 3; ++a) {
+        const bool row_in = (unsigned)(oh * 2 + a - 1) < (unsigned)p.H;
+        uint32_t el[9];                         // columns 8j-1 .. 8j+7
+        el[0] = left[a];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { el[1 + 2 * i] = main_[a][i] & 0xFFFFu; el[2 + 2 * i] = main_[a][i] >> 16; }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+#pragma unroll
+            for (int b = 0; b < 3; ++b) {
+                const bool in = row_in && (k > 0 || b > 0 || j > 0);      // column 8j-1 of the first quad is padding
+                const uint32_t bits = el[2 * k + b];
+                const float v = in ? bf16_bits_to_float((uint16_t)bits) : -__builtin_inff();
+                const bool better = v > best[k];
+                best[k] = better ? v : best[k];
+                best_bits[k] = better ? bits : best_bits[k];
+            }
+        }
+    }
+    typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+    const u32x2 out = {best_bits[0] | (best_bits[1] << 16), best_bits[2] | (best_bits[3] << 16)};
+    *reinterpret_cast<u32x2*>(p.X + (size_t)e * 4u) = out;
+}
+
 hipError_t launch_maxpool(const crisp_conv_desc& c, const uint16_t* act, uint16_t* out, hipStream_t st) {
     Im2colArgs p = {};
     p.C = c.C; p.H = c.H; p.W = c.W; p.batch = c.batch; p.kh = c.kh; p.kw = c.kw; p.stride = c.stride; p.pad = c.pad;
@@ -181,6 +233,13 @@ hipError_t launch_maxpool(const crisp_conv_desc& c, const uint16_t* act, uint16_
     p.X = out;
     const int64_t total = (int64_t)c.C * c.batch * p.Ho * p.Wo;
     if (total <= 0 || total > (int64_t)0xFFFFFF00u) return hipErrorInvalidValue;
+    if (c.kh == 3 && c.kw == 3 && c.stride == 2 && c.pad == 1 && c.W % 8 == 0 && (reinterpret_cast<uintptr_t>(act) & 15) == 0 &&
+        (reinterpret_cast<uintptr_t>(out) & 7) == 0) {
+        // (then Wo = W / 2 is a multiple of 4 and every row of act starts 16-byte aligned)
+        const int64_t quads = total / 4;
+        maxpool_3x3s2_kernel<<<(unsigned)((quads + 255) / 256), 256, 0, st>>>(p, (uint32_t)quads);
+        return hipGetLastError();
+    }
     const unsigned grid = (unsigned)((total + 255) / 256);
     if (c.kh == 3 && c.kw == 3) maxpool_kernel<3, 3><<<grid, 256, 0, st>>>(p, (uint32_t)total);
     else if (c.kh == 2 && c.kw == 2) maxpool_kernel<2, 2><<<grid, 256, 0, st>>>(p, (uint32_t)total);

@@ -484,7 +484,9 @@ def test_im2col_matches_oracle():
 
 
 @pytest.mark.parametrize("shape", [(3, 2, 9, 7, 3, 3, 2, 1), (4, 1, 8, 8, 2, 2, 2, 0), (2, 3, 5, 6, 3, 3, 1, 1), (64, 2, 112, 112, 3, 3, 2, 1),
-                                   (2, 2, 7, 9, 5, 3, 2, 2), (1, 1, 4, 4, 1, 1, 1, 0), (3, 1, 6, 5, 3, 3, 3, 2)])
+                                   (2, 2, 7, 9, 5, 3, 2, 2), (1, 1, 4, 4, 1, 1, 1, 0), (3, 1, 6, 5, 3, 3, 3, 2),
+                                   # 3x3 / 2 / 1 with W % 8 == 0: four outputs per thread (one quad per row, odd H, several quads)
+                                   (3, 2, 7, 8, 3, 3, 2, 1), (2, 1, 10, 24, 3, 3, 2, 1), (5, 3, 16, 16, 3, 3, 2, 1)])
 def test_maxpool_matches_oracle(shape):
     C_, b, H, Wd, kh, kw, stride, pad = shape
     rng = np.random.default_rng(C_ * 100 + H)
