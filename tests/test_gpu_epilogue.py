@@ -102,8 +102,11 @@ def test_epilogue_none_equals_plain_product():
 
 def test_conv_spmm_epilogue():
     """Fused lowering + epilogue (the tail of a residual block: scale, bias, shortcut, ReLU)."""
+    # the last three run in the kernel that stages the input patch in LDS (also forced: shape 12): stride 1
+    # and 2, with the sparse matrix-core instruction and with dense expansion, ragged S
     for (C_, H, Wd, b, k, pad, stride, S, n, m, B) in ((64, 8, 8, 2, 3, 1, 1, 64, 2, 4, 64), (32, 9, 7, 2, 3, 1, 2, 32, 4, 8, 32),
-                                                       (3, 12, 12, 2, 3, 1, 1, 32, 2, 4, 32)):
+                                                       (3, 12, 12, 2, 3, 1, 1, 32, 2, 4, 32), (128, 14, 14, 2, 3, 1, 1, 256, 2, 8, 64),
+                                                       (64, 28, 28, 1, 3, 1, 2, 200, 4, 8, 64), (64, 12, 12, 2, 3, 1, 1, 128, 1, 4, 64)):
         cv = synth.ConvShape(C_, H, Wd, b, k, k, stride, pad)
         L = synth.LayerSpec("convep", S, cv.K, cv.Ncol, n, m, B, 0.6, synth.SAL_MAG, 0.05, conv=cv)
         rng = np.random.default_rng(C_ + H)
@@ -119,9 +122,11 @@ def test_conv_spmm_epilogue():
             Yref, Aref = oracle.epilogue(Y0, A0, scale, bias, res, True)
             dscale, dbias, dres = dev(scale), dev(bias), dev(respad)     # the descriptor holds raw pointers
             ep = crisp.epilogue(dscale, dbias, dres, ld, True)
-            Y = torch.full((S, ld), float("nan"), dtype=torch.bfloat16 if bf16 else torch.float32, device="cuda")
-            crisp.crisp_conv_spmm_ep(layer.desc, crisp.conv_desc_of(cv), layer.row_ptr, layer.col_idx, layer.vals,
-                                     layer.idx_words, dev(act), Y, ld, crisp.Y_BF16 if bf16 else crisp.Y_F32, ep)
-            torch.cuda.synchronize()
-            Yh = Y.float().cpu().numpy().astype(np.float64)
-            _check(Yh[:, :Ncol], Yref, Aref, bf16, "conv epilogue C=%d bf16=%s" % (C_, bf16))
+            for shape in (None, 12):
+                Y = torch.full((S, ld), float("nan"), dtype=torch.bfloat16 if bf16 else torch.float32, device="cuda")
+                crisp.crisp_conv_spmm_ep(layer.desc, crisp.conv_desc_of(cv), layer.row_ptr, layer.col_idx, layer.vals,
+                                         layer.idx_words, dev(act), Y, ld, crisp.Y_BF16 if bf16 else crisp.Y_F32, ep,
+                                         ws=None, ws_bytes=0 if shape is None else shape + 1)
+                torch.cuda.synchronize()
+                Yh = Y.float().cpu().numpy().astype(np.float64)
+                _check(Yh[:, :Ncol], Yref, Aref, bf16, "conv epilogue C=%d bf16=%s shape %s" % (C_, bf16, shape))
