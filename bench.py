@@ -284,7 +284,8 @@ def main():
             per_set += 2 * L.conv.C * L.conv.batch * L.conv.H * L.conv.W
         if not is_conv or args.explicit_im2col:
             per_set += 2 * L.K * L.Ncol
-    nsets = args.sets if args.sets > 0 else max(2, min(16, int(600e6 // per_set) + 1))
+    # enough independent input sets that a rotation exceeds the 256 MB last-level cache more than twice
+    nsets = args.sets if args.sets > 0 else max(2, min(80, int(600e6 // per_set) + 1))
     gen = torch.Generator(device=dev)
     gen.manual_seed(wl.seed)
     layers = []
