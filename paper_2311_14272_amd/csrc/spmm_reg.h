@@ -262,9 +262,31 @@ __device__ __forceinline__ void load_vals(rsrc_t r, uint32_t voff, uint32_t soff
     } else if constexpr (FS == 8) {
         const u32x4 t = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0));
         v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
+    } else if constexpr (FS == 6) {
+        // 12 bytes, 4-byte aligned: one request (three dword requests would each touch the lines of all
+        // 32 rows again, and the address unit's time per request goes with the lines touched)
+        typedef __attribute__((ext_vector_type(3))) uint32_t u32x3;
+        const u32x3 t = __builtin_bit_cast(u32x3, __builtin_amdgcn_raw_buffer_load_b96(r, voff, soff, 0));
+        v[0] = t[0]; v[1] = t[1]; v[2] = t[2];
     } else {
 #pragma unroll
         for (int i = 0; i < (FS + 1) / 2; ++i) v[i] = __builtin_amdgcn_raw_buffer_load_b32(r, voff + 4 * i, soff, 0);
+    }
+}
+
+// The WPR position words of one block row (consecutive, 4-byte aligned; 8-byte aligned for WPR == 2).
+template <int WPR>
+__device__ __forceinline__ void load_positions(rsrc_t r, uint32_t voff, uint32_t soff, uint32_t (&w)[WPR]) {
+    if constexpr (WPR == 2) {
+        const u32x2 t = __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0));
+        w[0] = t[0]; w[1] = t[1];
+    } else if constexpr (WPR == 3) {
+        typedef __attribute__((ext_vector_type(3))) uint32_t u32x3;
+        const u32x3 t = __builtin_bit_cast(u32x3, __builtin_amdgcn_raw_buffer_load_b96(r, voff, soff, 0));
+        w[0] = t[0]; w[1] = t[1]; w[2] = t[2];
+    } else {
+#pragma unroll
+        for (int i = 0; i < WPR; ++i) w[i] = __builtin_amdgcn_raw_buffer_load_b32(r, voff + 4 * i, soff, 0);
     }
 }
 
@@ -279,6 +301,26 @@ __device__ __forceinline__ u32x4 expand_frag(const uint32_t (&v)[Fmt<N, M, B>::V
         // every column kept: slot s is column s
 #pragma unroll
         for (int x = 0; x < 4; ++x) out[x] = v[x];
+    } else if constexpr (M == 4) {
+        // the 8 columns are two groups of four; a group's four 16-bit places are one 64-bit word, and a
+        // stored value goes to place `pos` by a 64-bit shift of 16 * pos.  The two position bits are moved
+        // to bits 4..5 of the shift amount straight from the stream (2-bit fields never straddle words)
+        constexpr int P0 = KSTEP * 2 * F::HB;
+#pragma unroll
+        for (int gi = 0; gi < 2; ++gi) {
+            uint64_t places = 0;
+#pragma unroll
+            for (int j = 0; j < N; ++j) {
+                const int s = gi * N + j;
+                const int P = P0 + s * F::WB;
+                const int wi = P >> 5, sh = P & 31;
+                const uint32_t by = (sh >= 4 ? (ws[wi] >> (sh >= 4 ? sh - 4 : 0)) : (ws[wi] << (sh >= 4 ? 0 : 4 - sh))) & 0x30u;
+                const uint32_t val = (s & 1) ? (v[s >> 1] >> 16) : (v[s >> 1] & 0xFFFFu);
+                places |= (uint64_t)val << by;
+            }
+            out[2 * gi] = (uint32_t)places;
+            out[2 * gi + 1] = (uint32_t)(places >> 32);
+        }
     } else {
 #pragma unroll
         for (int s = 0; s < F::FS; ++s) {
@@ -290,16 +332,9 @@ __device__ __forceinline__ u32x4 expand_frag(const uint32_t (&v)[Fmt<N, M, B>::V
             const uint32_t pos = field & (uint32_t)(M - 1);
             const uint32_t val = (s & 1) ? (v[s >> 1] >> 16) : (v[s >> 1] & 0xFFFFu);
             const uint32_t vv = val << ((pos & 1u) << 4);
-            if constexpr (M == 4) {
-                const int gi = s / N;  // which of the two groups of four behind these 8 columns
-                const bool upper = (pos & 2u) != 0u;
-                out[2 * gi] |= upper ? 0u : vv;
-                out[2 * gi + 1] |= upper ? vv : 0u;
-            } else {
-                const uint32_t dw = pos >> 1;
+            const uint32_t dw = pos >> 1;
 #pragma unroll
-                for (int x = 0; x < 4; ++x) out[x] |= (dw == (uint32_t)x) ? vv : 0u;
-            }
+            for (int x = 0; x < 4; ++x) out[x] |= (dw == (uint32_t)x) ? vv : 0u;
         }
     }
     return out;
@@ -520,11 +555,7 @@ struct BlockBody {
                 for (int ks = 0; ks < KS; ++ks)
                     load_vals<F::FS>(rv, a_off + (rt * 32 * F::SLOTS + ks * 2 * F::FS) * 2, vb, v[rt][ks]);
             }
-            if constexpr (N != M) {
-#pragma unroll
-                for (int i = 0; i < F::WPR; ++i)
-                    w[rt][i] = __builtin_amdgcn_raw_buffer_load_b32(ri, i_off + (rt * 32 * F::WPR + i) * 4, ib, 0);
-            }
+            if constexpr (N != M) load_positions<F::WPR>(ri, i_off + rt * 32 * F::WPR * 4, ib, w[rt]);
         }
     }
 
