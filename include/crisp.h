@@ -271,7 +271,9 @@ CRISP_API crisp_status crisp_spmm(const crisp_layer_desc *desc, const int32_t *r
  * below 4 GiB.  For stride <= 4, C % 64 == 0, 64x64 blocks, even W <= 64 and even Wo there is also
  * a kernel that stages the input patch of a tile of output rows in LDS once for all filter
  * taps and up to four block-rows (chosen for dense multi-row layers; ws == NULL with
- * ws_bytes == 13 forces it, 1..4 and 8..11 force the shapes of crisp_spmm).
+ * ws_bytes == 13 forces it, 1..4 and 8..11 force the shapes of crisp_spmm).  Channel
+ * counts that are no multiple of 64 with 64x64 blocks, even W and even Ho*Wo run in a kernel
+ * that keeps the input patch of 1024 output positions in LDS (ws_bytes == 15 forces it).
  * Anything else returns CRISP_EUNSUPPORTED (use crisp_im2col + crisp_spmm).
  * Errors: EINVAL, ESHAPE, EALIGN, EUNSUPPORTED, EDEVICE.
  */

@@ -19,6 +19,7 @@
 #pragma once
 #include "spmm_reg.h"
 #include "spmm_xres.h"
+#include "conv_patch.h"
 
 namespace crisp {
 
@@ -369,6 +370,8 @@ template <int N, int M>
 hipError_t launch_reg_nm(const SpmmArgs& a, int B, int shape, hipStream_t st);
 template <int N, int M>
 hipError_t launch_conv_lds_nm(const SpmmArgs& a, const ConvLdsSched& s, int batch, hipStream_t st);
+template <int N, int M>
+hipError_t launch_conv_patch_nm(const SpmmArgs& a, const ConvPatchSched& s, int batch, hipStream_t st);
 
 #define CRISP_INSTANTIATE_NM(N, M)                                                           \
     template <>                                                                              \
@@ -379,6 +382,10 @@ hipError_t launch_conv_lds_nm(const SpmmArgs& a, const ConvLdsSched& s, int batc
     template <>                                                                              \
     hipError_t launch_conv_lds_nm<N, M>(const SpmmArgs& a, const ConvLdsSched& s, int batch, hipStream_t st) { \
         return launch_conv_lds<N, M>(a, s, batch, st);                                      \
+    }                                                                                        \
+    template <>                                                                              \
+    hipError_t launch_conv_patch_nm<N, M>(const SpmmArgs& a, const ConvPatchSched& s, int batch, hipStream_t st) { \
+        return launch_conv_patch<N, M>(a, s, batch, st);                                    \
     }
 
 }  // namespace crisp

@@ -311,7 +311,7 @@ static crisp_status conv_spmm_impl(const crisp_layer_desc* desc, const crisp_con
         return CRISP_EUNSUPPORTED;
     const int force_shape = (!ws && ws_bytes >= 1 && ws_bytes <= 4) ? (int)ws_bytes - 1
                           : (!ws && ws_bytes >= 8 && ws_bytes <= 11) ? (int)ws_bytes - 1
-                          : (!ws && ws_bytes == 13) ? 12 : -1;
+                          : (!ws && ws_bytes == 13) ? 12 : (!ws && ws_bytes == 15) ? 14 : -1;
     hipError_t e = launch_spmm(g, desc->block_density, desc->select_mode == CRISP_ROW_UNIFORM, force_shape, row_ptr, col_idx, vals,
                                idx_words, act, conv,
                                Ncol, Ncol, Y, ldy, y_dtype, ep, (hipEvent_t)ev_start, (hipEvent_t)ev_stop, (hipStream_t)stream);

@@ -367,6 +367,14 @@ template <> hipError_t launch_reg_nm<1, 8>(const SpmmArgs&, int, int, hipStream_
 template <> hipError_t launch_reg_nm<2, 8>(const SpmmArgs&, int, int, hipStream_t);
 template <> hipError_t launch_reg_nm<4, 8>(const SpmmArgs&, int, int, hipStream_t);
 template <> hipError_t launch_reg_nm<8, 8>(const SpmmArgs&, int, int, hipStream_t);
+template <> hipError_t launch_conv_patch_nm<1, 4>(const SpmmArgs&, const ConvPatchSched&, int, hipStream_t);
+template <> hipError_t launch_conv_patch_nm<2, 4>(const SpmmArgs&, const ConvPatchSched&, int, hipStream_t);
+template <> hipError_t launch_conv_patch_nm<3, 4>(const SpmmArgs&, const ConvPatchSched&, int, hipStream_t);
+template <> hipError_t launch_conv_patch_nm<4, 4>(const SpmmArgs&, const ConvPatchSched&, int, hipStream_t);
+template <> hipError_t launch_conv_patch_nm<1, 8>(const SpmmArgs&, const ConvPatchSched&, int, hipStream_t);
+template <> hipError_t launch_conv_patch_nm<2, 8>(const SpmmArgs&, const ConvPatchSched&, int, hipStream_t);
+template <> hipError_t launch_conv_patch_nm<4, 8>(const SpmmArgs&, const ConvPatchSched&, int, hipStream_t);
+template <> hipError_t launch_conv_patch_nm<8, 8>(const SpmmArgs&, const ConvPatchSched&, int, hipStream_t);
 template <> hipError_t launch_conv_lds_nm<1, 4>(const SpmmArgs&, const ConvLdsSched&, int, hipStream_t);
 template <> hipError_t launch_conv_lds_nm<2, 4>(const SpmmArgs&, const ConvLdsSched&, int, hipStream_t);
 template <> hipError_t launch_conv_lds_nm<3, 4>(const SpmmArgs&, const ConvLdsSched&, int, hipStream_t);
@@ -484,6 +492,24 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
             case 2 * 16 + 8: return launch_conv_lds_nm<2, 8>(a, cs, conv->batch, st);
             case 4 * 16 + 8: return launch_conv_lds_nm<4, 8>(a, cs, conv->batch, st);
             case 8 * 16 + 8: return launch_conv_lds_nm<8, 8>(a, cs, conv->batch, st);
+            default: break;
+        }
+    }
+    // channel counts that are no multiple of the block size (first layers): input patch in LDS in its
+    // own layout (forced shape 14)
+    ConvPatchSched ps;
+    if (conv && (force_shape == 14 || force_shape < 0) && ldy <= ((int64_t)1 << 23) &&
+        conv_patch_plan(a, g.B, conv->kh, g.Kb, g.nk, &ps)) {
+        a.use_smf = 1;
+        switch (g.n * 16 + g.m) {
+            case 1 * 16 + 4: return launch_conv_patch_nm<1, 4>(a, ps, conv->batch, st);
+            case 2 * 16 + 4: return launch_conv_patch_nm<2, 4>(a, ps, conv->batch, st);
+            case 3 * 16 + 4: return launch_conv_patch_nm<3, 4>(a, ps, conv->batch, st);
+            case 4 * 16 + 4: return launch_conv_patch_nm<4, 4>(a, ps, conv->batch, st);
+            case 1 * 16 + 8: return launch_conv_patch_nm<1, 8>(a, ps, conv->batch, st);
+            case 2 * 16 + 8: return launch_conv_patch_nm<2, 8>(a, ps, conv->batch, st);
+            case 4 * 16 + 8: return launch_conv_patch_nm<4, 8>(a, ps, conv->batch, st);
+            case 8 * 16 + 8: return launch_conv_patch_nm<8, 8>(a, ps, conv->batch, st);
             default: break;
         }
     }

@@ -106,7 +106,9 @@ def test_conv_spmm_epilogue():
     # and 2, with the sparse matrix-core instruction and with dense expansion, ragged S
     for (C_, H, Wd, b, k, pad, stride, S, n, m, B) in ((64, 8, 8, 2, 3, 1, 1, 64, 2, 4, 64), (32, 9, 7, 2, 3, 1, 2, 32, 4, 8, 32),
                                                        (3, 12, 12, 2, 3, 1, 1, 32, 2, 4, 32), (128, 14, 14, 2, 3, 1, 1, 256, 2, 8, 64),
-                                                       (64, 28, 28, 1, 3, 1, 2, 200, 4, 8, 64), (64, 12, 12, 2, 3, 1, 1, 128, 1, 4, 64)):
+                                                       (64, 28, 28, 1, 3, 1, 2, 200, 4, 8, 64), (64, 12, 12, 2, 3, 1, 1, 128, 1, 4, 64),
+                                                       # few channels, 64x64 blocks: the kernel with the patch in its own layout (shape 14)
+                                                       (3, 16, 16, 2, 3, 1, 1, 100, 2, 4, 64), (12, 20, 20, 1, 5, 2, 2, 64, 4, 8, 64)):
         cv = synth.ConvShape(C_, H, Wd, b, k, k, stride, pad)
         L = synth.LayerSpec("convep", S, cv.K, cv.Ncol, n, m, B, 0.6, synth.SAL_MAG, 0.05, conv=cv)
         rng = np.random.default_rng(C_ + H)
@@ -122,7 +124,7 @@ def test_conv_spmm_epilogue():
             Yref, Aref = oracle.epilogue(Y0, A0, scale, bias, res, True)
             dscale, dbias, dres = dev(scale), dev(bias), dev(respad)     # the descriptor holds raw pointers
             ep = crisp.epilogue(dscale, dbias, dres, ld, True)
-            for shape in (None, 12):
+            for shape in (None, 12, 14):
                 Y = torch.full((S, ld), float("nan"), dtype=torch.bfloat16 if bf16 else torch.float32, device="cuda")
                 crisp.crisp_conv_spmm_ep(layer.desc, crisp.conv_desc_of(cv), layer.row_ptr, layer.col_idx, layer.vals,
                                          layer.idx_words, dev(act), Y, ld, crisp.Y_BF16 if bf16 else crisp.Y_F32, ep,

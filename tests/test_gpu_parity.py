@@ -358,6 +358,13 @@ CONV_CASES = [
     (24, 9, 8, 2, 3, 3, 1, 64, 2, 4, 64, 0.5, 1),
     (48, 7, 7, 2, 3, 3, 1, 96, 1, 4, 32, 0.5, 2),
     (5, 8, 8, 4, 5, 5, 2, 32, 4, 8, 32, 1.0, 1),
+    # the same with 64x64 blocks and even W and Ho*Wo: the kernel that keeps the input patch in LDS in its own
+    # layout (exactly one tile, a ragged second tile, two block-rows, ragged S, ragged last block column)
+    (3, 32, 32, 2, 7, 7, 3, 64, 1, 8, 64, 0.7, 2),
+    (3, 40, 40, 1, 7, 7, 3, 128, 2, 4, 64, 0.7, 2),
+    (16, 12, 12, 2, 3, 3, 1, 64, 4, 8, 64, 0.67, 1),
+    (3, 18, 14, 2, 5, 5, 2, 96, 3, 4, 64, 1.0, 1),
+    (40, 10, 10, 3, 3, 3, 1, 200, 2, 8, 64, 0.5, 1),
 ]
 
 
@@ -387,7 +394,7 @@ def test_conv_spmm_implicit_lowering(case):
     dX = torch.zeros((L.K, ldx), dtype=torch.int16, device="cuda")
     crisp.crisp_im2col(conv, dact, dX, ldx)
     for yd, tdt in ((crisp.Y_F32, torch.float32), (crisp.Y_BF16, torch.bfloat16)):
-        for shape in (None, 1, 2, 3, 8, 9, 10, 12):        # 12: input staged in LDS (where it applies)
+        for shape in (None, 1, 2, 3, 8, 9, 10, 12, 14):    # 12 / 14: input staged in LDS (where they apply)
             Y = torch.full((S + 1, ldy), float("nan"), dtype=tdt, device="cuda")
             crisp.crisp_conv_spmm(layer.desc, conv, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dact, Y,
                                   ldy, yd, ws=None, ws_bytes=0 if shape is None else shape + 1)
@@ -395,7 +402,7 @@ def test_conv_spmm_implicit_lowering(case):
             Yh = Y.float().cpu().numpy().astype(np.float64)
             assert np.isnan(Yh[:S, Ncol:]).all() and np.isnan(Yh[S]).all()
             check_product(Yh[:S, :Ncol], Yref, Aref, yd, "conv %s shape %s" % (case, shape))
-            if shape is not None and shape != 12 and Ncol % 4 == 0 and L.K % 16 == 0:
+            if shape is not None and shape not in (12, 14) and Ncol % 4 == 0 and L.K % 16 == 0:
                 # (other K or Ncol: the explicit path runs the generic kernel, a different summation order)
                 Ye = run_spmm(layer, dX, Ncol, ldx, yd, S, ldy=ldy, shape=shape)
                 assert (Ye == Yh[:S, :Ncol]).all(), "implicit and explicit lowering differ"
