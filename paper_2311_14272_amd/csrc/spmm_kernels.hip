@@ -467,6 +467,8 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
         a.Wo = (conv->W + 2 * conv->pad - conv->kw) / conv->stride + 1;
         // neighbours in a row from one dword when that is possible, else column by column
         a.conv_mode = (conv->stride == 1 && (a.Wo & 1) == 0 && conv->W >= 2) ? 1 : 2;
+        if (conv->kh == 1 && conv->kw == 1 && conv->stride == 2 && conv->pad == 0 && (conv->W & 1) == 0 && (a.Wo & 1) == 0)
+            a.conv_mode = 4;                       // strided 1x1: both columns from one 8-byte piece of the input row
         if (conv->C % g.B != 0) a.conv_mode = 3;   // block columns span filter taps: every K-row on its own
         a.plane = (int64_t)conv->batch * conv->H * conv->W;
         a.act_bytes = a.conv_mode == 3 ? (uint32_t)((int64_t)conv->C * a.plane * 2) : 0u;

@@ -51,7 +51,8 @@ struct SpmmArgs {
     // implicit lowering (conv mode): X is not materialised; its rows are read from the activation
     // [C][batch][H][W], C % B == 0.  conv_mode 1: stride 1 and even Wo, a lane's two output columns
     // are neighbours in a row and come from one dword.  conv_mode 2: any stride and Wo, the two
-    // columns are located independently and loaded with one 2-byte load each.  conv_mode 3: any C
+    // columns are located independently and loaded with one 2-byte load each.  conv_mode 4: 1x1 filter
+    // with stride 2 (no padding, even W and Wo): the two columns come from one 8-byte load.  conv_mode 3: any C
     // (a block column may span several filter taps): like 2, and in addition every K-row is split
     // into (tap, channel) on its own; elements outside the image or past K are requested at an
     // offset beyond the activation's buffer range, for which the hardware returns zero.
@@ -435,6 +436,16 @@ struct BlockBody {
             c.sel_hi = SEL_LO;
             return c;
         }
+        if constexpr (CONV == 4) {
+            // 1x1 filter, stride 2, no padding, even W and Wo: the lane's two columns are the elements 0
+            // and 2 of one 8-byte piece of input row 2*oh (always inside the image)
+            XCtx c;
+            c.off = cp.half_off + (uint32_t)((cp.img * p.H + cp.oh * 2) * p.W + cp.ow * 2) * 2u;
+            c.off2 = 0u;
+            c.sel_lo = SEL_LO;
+            c.sel_hi = SEL_LO;
+            return c;
+        }
         if constexpr (CONV == 2) {
             // each column on its own: source act[c][img][oh*stride + a - pad][ow*stride + b - pad]
             // or, outside the image, any valid address and a selector that yields zeros
@@ -505,7 +516,10 @@ struct BlockBody {
             const int c0 = bj * B - tap * p.C + ks * 16;
             const rsrc_t r = make_rsrc(p.act + (int64_t)c0 * p.plane);
             const uint32_t row_bytes = (uint32_t)p.plane * 2u;
-            if constexpr (CONV == 2) {
+            if constexpr (CONV == 4) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) dst[i] = buf_load_x<2>(r, lane_off, (uint32_t)i * row_bytes);
+            } else if constexpr (CONV == 2) {
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     const uint32_t e0 = __builtin_amdgcn_raw_buffer_load_b16(r, lane_off, (uint32_t)i * row_bytes, 0);
@@ -956,6 +970,14 @@ hipError_t launch_reg_shape(const SpmmArgs& a, int shape, hipStream_t st) {
             case 1: return launch_reg<N, M, B, 1, 1, 1, 3>(a, st);
             case 2: return launch_reg<N, M, B, 1, 4, 1, 3>(a, st);
             default: return launch_reg<N, M, B, 1, 8, 1, 3>(a, st);
+        }
+    }
+    if (a.act != nullptr && a.conv_mode == 4) {
+        switch (shape) {
+            case 0:
+            case 1: return launch_reg<N, M, B, 1, 1, 1, 4>(a, st);
+            case 2: return launch_reg<N, M, B, 1, 4, 1, 4>(a, st);
+            default: return launch_reg<N, M, B, 1, 8, 1, 4>(a, st);
         }
     }
     if (a.act != nullptr && a.conv_mode == 2) {

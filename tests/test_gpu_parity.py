@@ -343,6 +343,9 @@ CONV_CASES = [
     (32, 11, 10, 2, 5, 5, 2, 64, 3, 4, 32, 0.5, 3),
     (128, 14, 14, 4, 3, 3, 1, 128, 2, 4, 64, 0.4, 2),
     (64, 14, 14, 6, 1, 1, 0, 128, 1, 8, 64, 0.5, 2),
+    # strided 1x1 with even W and Wo: both columns of a lane from one 8-byte piece of the input row
+    (128, 12, 12, 3, 1, 1, 0, 192, 2, 8, 64, 0.5, 2),
+    (64, 8, 16, 2, 1, 1, 0, 96, 4, 8, 32, 0.6, 2),
     # strided shapes of the LDS-staged convolution (3x3, 5x5, 1x1 that skips input rows, stride 3)
     (128, 28, 28, 2, 3, 3, 1, 256, 2, 4, 64, 0.6, 2),
     (256, 28, 28, 2, 1, 1, 0, 256, 2, 4, 64, 0.6, 2),
