@@ -798,9 +798,15 @@ __device__ __forceinline__ void store_rows(const SpmmArgs& p, int bi, int hh, in
 template <int N, int M, int B, int WD, bool SMF>
 constexpr int waves_per_simd() { return (WD == 2 && B == 64 && Fmt<N, M, B>::FS >= 4 && !SMF) ? 1 : 2; }
 
+// (upper limit: three for the narrow-strip kernels of the sparse matrix-core patterns on plain X, whose
+// registers allow it)
+template <int N, int M, int B, int WD, int NWK, int CONV, bool SMF>
+constexpr int waves_per_simd_max() { return (WD == 1 && SMF && NWK == 1 && CONV == 0 && B == 64) ? 3 : 2; }
+
 template <int N, int M, int B, int WD, int NWK, int PF, int CONV, bool SMF = false>
 __global__ __launch_bounds__(NWK > 1 ? 64 * NWK : 256)
-__attribute__((amdgpu_waves_per_eu(waves_per_simd<N, M, B, WD, SMF>(), 2)))
+__attribute__((amdgpu_waves_per_eu(waves_per_simd_max<N, M, B, WD, NWK, CONV, SMF>() == 3 ? 3 : waves_per_simd<N, M, B, WD, SMF>(),
+                                   waves_per_simd_max<N, M, B, WD, NWK, CONV, SMF>())))
 void spmm_reg_kernel(SpmmArgs p) {
     static_assert(!CONV || WD == 1, "conv modes work on two output columns per lane");
     typedef Fmt<N, M, B> F;
