@@ -411,6 +411,46 @@ def test_conv_spmm_implicit_lowering(case):
                 assert (Ye == Yh[:S, :Ncol]).all(), "implicit and explicit lowering differ"
 
 
+@pytest.mark.parametrize("case", [
+    # uneven block-rows (whole-grid block choice: some rows long, some empty) through the kernels that keep
+    # the input in LDS: staged patch (shape 12) and few-channel patch (shape 14), and the library's own choice
+    (64, 14, 14, 2, 3, 3, 1, 256, 2, 4, 64, 0.35, 1, 12),
+    (128, 12, 12, 2, 3, 3, 1, 320, 1, 8, 64, 0.3, 2, 12),
+    (3, 24, 24, 2, 7, 7, 3, 192, 2, 8, 64, 0.4, 2, 14),
+    (20, 12, 12, 2, 3, 3, 1, 256, 4, 8, 64, 0.3, 1, 14),
+], ids=lambda c: "C%d_S%d_shape%d" % (c[0], c[7], c[13]))
+def test_conv_spmm_uneven_block_rows(case):
+    C_, H, Wd, b, kh, kw, pad, S, n, m, B, dens, stride, forced = case
+    cv = synth.ConvShape(C_, H, Wd, b, kh, kw, stride, pad)
+    L = synth.LayerSpec("conv_uneven", S, cv.K, cv.Ncol, n, m, B, dens, synth.SAL_MAG, 0.05, conv=cv, select_mode=synth.LAYER_TOPK)
+    rng = np.random.default_rng(C_ * 11 + S)
+    W = synth.draw_weight(rng, L)
+    # make the block scores very uneven so that the whole-grid choice empties some block-rows
+    Wf = synth.bf16_bits_to_f32(W).reshape(S, cv.K)
+    Wf[: B] *= 8.0
+    if S > 2 * B:
+        Wf[2 * B: 3 * B] *= 0.01
+    W = synth.f32_to_bf16_bits(Wf.astype(np.float32))
+    act = synth.draw_relu_normal(rng, (C_, b, H, Wd))
+    sel, vals, idxw, flags = oracle_all(L, W, None)
+    counts = np.diff(sel.row_ptr)
+    assert counts.min() == 0 or counts.max() > counts.min(), "the case is meant to have uneven rows"
+    layer, out = run_select_pack(L, W, None)
+    assert_select_pack_equal(L, out, sel, vals, idxw, flags)
+    Yref, Aref = oracle.gemm_masked(W, sel.mask, oracle.im2col(act, kh, kw, stride, pad))
+    conv = crisp.ConvDesc(C_, H, Wd, b, kh, kw, stride, pad, crisp.ACT_CBHW, crisp.X_KN)
+    Ncol = cv.Ncol
+    ldy = (Ncol + 7) // 8 * 8
+    for shape in (forced, None):
+        for yd, tdt in ((crisp.Y_F32, torch.float32), (crisp.Y_BF16, torch.bfloat16)):
+            Y = torch.full((S, ldy), float("nan"), dtype=tdt, device="cuda")
+            crisp.crisp_conv_spmm(layer.desc, conv, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dev(act), Y, ldy, yd,
+                                  ws=None, ws_bytes=0 if shape is None else shape + 1)
+            torch.cuda.synchronize()
+            Yh = Y.float().cpu().numpy().astype(np.float64)
+            check_product(Yh[:, :Ncol], Yref, Aref, yd, "uneven %s shape %s" % (case, shape))
+
+
 def test_conv_spmm_rejects_what_it_does_not_cover():
     d = crisp.layer_desc(64, 9 * 64, 2, 4, 64, 0.5)
     z = torch.zeros(1 << 16, dtype=torch.int16, device="cuda")
