@@ -515,6 +515,27 @@ def test_ties_and_zero_weights():
         assert_select_pack_equal(L, out, sel, vals, idxw, flags)
 
 
+@pytest.mark.parametrize("B", [16, 32, 64])
+def test_two_of_four_flag_on_4_of_8(B):
+    """4:8 patterns whose kept values fall two per aligned quad set the 2-of-4 flag; one row with three
+    in a quad clears it.  Random 4:8 layers practically never hit the first case."""
+    L = synth.LayerSpec("quads_B%d" % B, 2 * B, 3 * B, 64, 4, 8, B, 1.0, synth.SAL_MAG, 1.0)
+    rng = np.random.default_rng(41 + B)
+    mag = np.tile(np.array([2.0, 0.5, 0.5, 2.0, 0.5, 2.0, 2.0, 0.5], dtype=np.float32), (L.S, L.K // 8))
+    Wf = (mag * rng.uniform(1.0, 1.5, mag.shape) * rng.choice([-1.0, 1.0], mag.shape)).astype(np.float32)
+    seen = []
+    for skew in (False, True):
+        if skew:
+            Wf[:, :8] = np.abs(Wf[:, :8])
+            Wf[B + 3, :8] = [3.0, 3.0, 3.0, 0.1, 0.1, 0.1, 0.1, 3.0]
+        W = synth.f32_to_bf16_bits(Wf)
+        sel, vals, idxw, flags = oracle_all(L, W, None)
+        layer, out = run_select_pack(L, W, None)
+        assert_select_pack_equal(L, out, sel, vals, idxw, flags)
+        seen.append(int(out["flags"][0]))
+    assert seen == [1, 0]
+
+
 def test_im2col_matches_oracle():
     rng = np.random.default_rng(5)
     for (C_, H, Wd, b, kh, kw, st, pad) in [(3, 9, 8, 2, 3, 3, 1, 1), (4, 8, 8, 1, 1, 1, 2, 0), (2, 11, 11, 2, 7, 7, 2, 3),

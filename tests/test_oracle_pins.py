@@ -361,6 +361,24 @@ def test_pack_hand_written_bits():
     assert int(i8[0, r, 0]) == expect
 
 
+def test_two_of_four_flag_counts_aligned_quads():
+    # 4:8 is eligible for the 2-of-4 hardware form exactly when no aligned quad of columns holds more
+    # than two kept values; the count runs over quads, not over the whole group of eight.
+    B, n, m = 8, 4, 8
+    big, small = 2.0, 0.5
+    even = np.tile(np.array([big, small, small, big, small, big, big, small], dtype=np.float32), (8, 1))
+    W = synth.f32_to_bf16_bits(even)                              # two large values in either quad
+    sel = oracle.select(W, None, n, m, B, 1.0, synth.SAL_MAG)
+    assert sel.keep[0].tolist() == [1, 0, 0, 1, 0, 1, 1, 0]
+    assert int(oracle.pack(W, sel.keep, n, m, B, sel.row_ptr, sel.col_idx)[2][0]) == 1
+    skew = even.copy()
+    skew[5] = [big, big, big, small, small, small, small, big]  # one row with three in its first quad
+    W = synth.f32_to_bf16_bits(skew)
+    sel = oracle.select(W, None, n, m, B, 1.0, synth.SAL_MAG)
+    assert sel.keep[5].tolist() == [1, 1, 1, 0, 0, 0, 0, 1]
+    assert int(oracle.pack(W, sel.keep, n, m, B, sel.row_ptr, sel.col_idx)[2][0]) == 0
+
+
 def test_pack_padding_rules():
     # S=3 < B=4 and K=6: block column 1 has columns 4,5 only (short group), row 3 is outside.
     B, n, m = 4, 2, 4
