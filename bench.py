@@ -14,6 +14,7 @@ timed on the host cores as a reported baseline.
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -552,6 +553,13 @@ def main():
     }
     if graph_info is not None:
         out["graph_replay"] = graph_info
+    # the bytes both the device path and the oracle were given (first input set), for reproduction
+    digests = {}
+    for h, x in zip(host_inputs, info):
+        for key in ("W", "G", "X", "act"):
+            if h.get(key) is not None:
+                digests["%s.%s" % (x["name"], key)] = hashlib.sha256(np.ascontiguousarray(h[key]).view(np.uint8)).hexdigest()[:16]
+    out["inputs"] = {"generator": "numpy %s PCG64, seed %d" % (np.__version__, wl.seed), "sha256_prefix": digests}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, host_inputs, useful)
     print(json.dumps(out))
