@@ -52,7 +52,9 @@ __global__ __launch_bounds__(256, 3) void conv_patch_kernel(SpmmArgs p, ConvPatc
     const int ih_first = oh_first * p.stride - p.pad;
     const int rows_here = (oh_last - oh_first) * p.stride + sc.kh;                  // <= sc.PR
 
-    // the block list, read before anything is stored (lane l: row_ptr[l], and the l-th block's column)
+    // the block list, read before anything is stored (lane l: row_ptr[l], and the l-th block's column;
+    // the number of kept blocks is only known on the device: blocks from the 64th on are looked up in
+    // memory as they come)
     const int my_ptr = p.row_ptr[min(lane, p.Sb)];
     const int t_last = __builtin_amdgcn_readlane(my_ptr, p.Sb) - 1;
     const int my_bj = p.col_idx[max(min(lane, t_last), 0)];
@@ -156,7 +158,7 @@ __global__ __launch_bounds__(256, 3) void conv_patch_kernel(SpmmArgs p, ConvPatc
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[rt][c][r] = 0.0f;
         for (; t < t_end; ++t) {
-            const int bj = __builtin_amdgcn_readlane(my_bj, t);
+            const int bj = t < 64 ? __builtin_amdgcn_readlane(my_bj, t) : p.col_idx[t];
             uint32_t ws[RT][F::WPR];
             if constexpr (N != M) {
 #pragma unroll
@@ -222,10 +224,10 @@ __global__ __launch_bounds__(256, 3) void conv_patch_kernel(SpmmArgs p, ConvPatc
     }
 }
 
-// Covered: C % 64 != 0 (conv mode 3), 64 x 64 blocks, even W and Ho * Wo, at most 64 blocks in all,
+// Covered: C % 64 != 0 (conv mode 3), 64 x 64 blocks, even W and Ho * Wo, at most 63 block-rows,
 // K-row table and patch within 64 KB of LDS.
-inline bool conv_patch_plan(const SpmmArgs& a, int B, int kh, int Kb, int nk, ConvPatchSched* out) {
-    if (a.act == nullptr || a.conv_mode != 3 || B != 64 || (a.W & 1) || ((a.Ho * a.Wo) & 1) || a.Sb > 63 || nk > 64) return false;
+inline bool conv_patch_plan(const SpmmArgs& a, int B, int kh, int Kb, ConvPatchSched* out) {
+    if (a.act == nullptr || a.conv_mode != 3 || B != 64 || (a.W & 1) || ((a.Ho * a.Wo) & 1) || a.Sb > 63) return false;
     ConvPatchSched s;
     s.kh = kh; s.taps = kh * a.kw;
     if (a.K != s.taps * a.C || (int64_t)a.C * a.plane * 2 >= ((int64_t)1 << 32)) return false;

@@ -501,7 +501,7 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
     // own layout (forced shape 14)
     ConvPatchSched ps;
     if (conv && (force_shape == 14 || force_shape < 0) && ldy <= ((int64_t)1 << 23) &&
-        conv_patch_plan(a, g.B, conv->kh, g.Kb, g.nk, &ps)) {
+        conv_patch_plan(a, g.B, conv->kh, g.Kb, &ps)) {
         a.use_smf = 1;
         switch (g.n * 16 + g.m) {
             case 1 * 16 + 4: return launch_conv_patch_nm<1, 4>(a, ps, conv->batch, st);

@@ -368,6 +368,9 @@ CONV_CASES = [
     (16, 12, 12, 2, 3, 3, 1, 64, 4, 8, 64, 0.67, 1),
     (3, 18, 14, 2, 5, 5, 2, 96, 3, 4, 64, 1.0, 1),
     (40, 10, 10, 3, 3, 3, 1, 200, 2, 8, 64, 0.5, 1),
+    # more than 64 kept blocks in all (the kernel holds the first 64 block columns in a register)
+    (16, 13, 48, 1, 7, 7, 3, 320, 2, 4, 64, 1.0, 1),
+    (16, 8, 12, 2, 5, 5, 2, 448, 1, 8, 64, 0.8, 1),
 ]
 
 
