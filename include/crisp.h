@@ -236,6 +236,8 @@ CRISP_API crisp_status crisp_im2col(const crisp_conv_desc *conv, const uint16_t 
  *      allocation must cover K*ldx elements.  x_layout = CRISP_X_KN.
  *   Y: S x ldy, fp32 or bf16 per y_dtype (device), ldy >= Ncol, ldy % 8 == 0.
  *      Every element Y[0..S)[0..Ncol) is written (rows of empty block-rows get 0).
+ *   Ncol, ldx and ldy may be up to 2^27 (ESHAPE beyond); with ldy above 2^23 the
+ *   generic kernel runs whatever the pattern.
  *   desc->sal_kind is not used here.  desc->block_density and select_mode only
  *   steer the choice of kernel (how many blocks a block-row holds, whether all
  *   rows hold the same number); a wrong or out-of-range density costs speed, never

@@ -7,7 +7,7 @@ import torch
 import oracle
 from paper_2311_14272_amd import crisp, synth
 
-from gpu_util import check_product, desc_of, dev, host, run_select_pack, run_spmm
+from gpu_util import check_product, desc_of, dev, host, lowering_gather_index, run_select_pack, run_spmm
 
 pytestmark = pytest.mark.gpu
 
@@ -627,6 +627,89 @@ def test_config_full_size(cid):
                 Yh = Yc.float().cpu().numpy().astype(np.float64)
                 check_product(Yh[:, cols], Yref, Aref, yd, L.name + " fused lowering")
         del dX
+        torch.cuda.empty_cache()
+
+
+def _device_relu_normal_bits(shape, seed):
+    """ReLU(N(0,1)) rounded to bf16, drawn on the device (too large to draw on the host in reasonable time)."""
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    out = torch.empty(shape, dtype=torch.bfloat16, device="cuda")
+    rows = max(1, (1 << 26) // shape[-1])
+    flat = out.view(-1, shape[-1])
+    for r0 in range(0, flat.shape[0], rows):
+        part = flat[r0:r0 + rows]
+        part.copy_(torch.randn(part.shape, generator=gen, device="cuda").clamp_(min=0).to(torch.bfloat16))
+    return out.view(torch.int16)
+
+
+@pytest.mark.parametrize("case", [
+    # S, K, n, m, B, density, Ncol (= ldx = ldy), forced shapes
+    # the widest Y the specialised kernels take (ldy = 2^23): X-resident kernel (the library's own choice
+    # here), narrow and wide strips of the register kernels
+    (128, 64, 2, 4, 64, 1.0, 1 << 23, (None, 1, 7)),
+    # one step beyond: handed to the generic kernel
+    (64, 64, 1, 4, 32, 0.5, (1 << 23) + 8, (None,)),
+    # the largest column count the entry point accepts (2^27)
+    (32, 32, 2, 8, 32, 1.0, 1 << 27, (None,)),
+], ids=lambda c: "S%d_K%d_N%d" % (c[0], c[1], c[6]))
+def test_maximum_column_counts(case):
+    """Products at the documented column limits, bf16 output, checked on sampled columns (first and last
+    strips plus random ones) against the oracle; untouched guard rows below Y."""
+    S, K, n, m, B, dens, Ncol, shapes = case
+    L = synth.LayerSpec("wide", S, K, Ncol, n, m, B, dens, synth.SAL_MAG, 0.05)
+    rng = np.random.default_rng(S + K)
+    W = synth.draw_weight(rng, L)
+    sel = oracle.select(W, None, n, m, B, dens, synth.SAL_MAG)
+    layer, _ = run_select_pack(L, W, None)
+    dX = _device_relu_normal_bits((K, Ncol), 77)
+    cols = _sample_columns(Ncol, 2000, rng)
+    tcols = torch.from_numpy(cols).cuda()
+    Xs = np.ascontiguousarray(host(dX[:, tcols], np.uint16))
+    Yref, Aref = oracle.gemm_masked(W, sel.mask, Xs)
+    for shape in shapes:
+        print("wide case", case[:7], "shape", shape, flush=True)
+        Y = torch.full((S + 1, Ncol), float("nan"), dtype=torch.bfloat16, device="cuda")
+        crisp.crisp_spmm(layer.desc, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dX, Ncol, Ncol, Y, Ncol,
+                         crisp.Y_BF16, ws=None, ws_bytes=0 if shape is None else shape + 1)
+        torch.cuda.synchronize()
+        assert bool(torch.isnan(Y[S]).all()), "row beyond S was written"
+        assert bool(torch.isfinite(Y[:S]).all())
+        Yh = Y[:S][:, tcols].float().cpu().numpy().astype(np.float64)
+        check_product(Yh, Yref, Aref, crisp.Y_BF16, "wide %s shape %s" % (case[:7], shape))
+        del Y
+        torch.cuda.empty_cache()
+
+
+def test_maximum_convolution_plane():
+    """Fused lowering with 2^23 output columns (the widest Y the fused kernels take): the kernel that
+    stages the input in LDS (the library's own choice) and the register kernels, sampled columns."""
+    C_, H, Wd, b, k, pad, S, n, m, B, dens = 64, 64, 64, 2048, 3, 1, 128, 2, 4, 64, 0.5
+    cv = synth.ConvShape(C_, H, Wd, b, k, k, 1, pad)
+    assert cv.Ncol == 1 << 23
+    L = synth.LayerSpec("wide_conv", S, cv.K, cv.Ncol, n, m, B, dens, synth.SAL_MAG, 0.05, conv=cv)
+    rng = np.random.default_rng(5)
+    W = synth.draw_weight(rng, L)
+    sel = oracle.select(W, None, n, m, B, dens, synth.SAL_MAG)
+    layer, _ = run_select_pack(L, W, None)
+    dact = _device_relu_normal_bits((C_, b, H, Wd), 78)
+    cols = _sample_columns(cv.Ncol, 1500, rng)
+    idx, inside = lowering_gather_index(C_, H, Wd, b, k, k, 1, pad, cols)
+    g = torch.take(dact.view(-1), torch.from_numpy(idx).cuda()).cpu().numpy().view(np.uint16)
+    Xs = np.ascontiguousarray(np.where(inside, g, np.uint16(0)))
+    Yref, Aref = oracle.gemm_masked(W, sel.mask, Xs)
+    tcols = torch.from_numpy(cols).cuda()
+    conv = crisp.conv_desc_of(cv)
+    for shape in (None, 12, 1, 8):
+        print("wide conv shape", shape, flush=True)
+        Y = torch.full((S + 1, cv.Ncol), float("nan"), dtype=torch.bfloat16, device="cuda")
+        crisp.crisp_conv_spmm(layer.desc, conv, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dact, Y, cv.Ncol,
+                              crisp.Y_BF16, ws=None, ws_bytes=0 if shape is None else shape + 1)
+        torch.cuda.synchronize()
+        assert bool(torch.isnan(Y[S]).all()) and bool(torch.isfinite(Y[:S]).all())
+        Yh = Y[:S][:, tcols].float().cpu().numpy().astype(np.float64)
+        check_product(Yh, Yref, Aref, crisp.Y_BF16, "wide conv shape %s" % shape)
+        del Y
         torch.cuda.empty_cache()
 
 
