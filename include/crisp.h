@@ -63,7 +63,9 @@ enum { CRISP_ACT_CBHW = 0 };           /* activation layout: [C][batch][H][W], W
 
 typedef struct {
     double block_density;  /* (0,1]; kept blocks per block-row k_row = clamp(floor(d*Kb+0.5),1,Kb) */
-    int32_t S, K;          /* weight rows (output channels) and reduction length, >= 1            */
+    int32_t S, K;          /* weight rows (output channels) and reduction length, >= 1; the packed
+                              values of the whole block grid, Sb*Kb*B*(B*n/m)*2 bytes, must stay
+                              below 4 GiB (ESHAPE otherwise)                                       */
     int32_t n, m;          /* 1 <= n <= m, m in {4,8}; n == m switches the fine-grained part off   */
     int32_t B;             /* block edge, 16 | 32 | 64, B % m == 0                                 */
     int32_t sal_kind;      /* CRISP_SAL_*                                                          */

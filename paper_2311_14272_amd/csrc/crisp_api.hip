@@ -28,6 +28,9 @@ crisp_status make_geometry(const crisp_layer_desc* d, bool need_density, Geometr
     g->mwpr = ceil_div(d->K, 32);
     g->k_row = 0;
     g->nk = 0;
+    // the kernels address a layer's packed values with 32-bit byte offsets: even with every block kept
+    // they must stay below 4 GiB
+    if ((int64_t)g->Sb * g->Kb * g->B * g->slots * 2 >= ((int64_t)1 << 32)) return CRISP_ESHAPE;
     if (need_density) {
         // Kept blocks per block-row for the layer's block density; at least one so that a
         // layer cannot collapse (Sec. 3.3, last paragraph).

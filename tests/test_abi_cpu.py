@@ -77,7 +77,9 @@ def test_pack_sizes_values():
     (dict(m=5), crisp.EINVAL), (dict(n=0), crisp.EINVAL), (dict(n=5), crisp.EINVAL), (dict(B=48), crisp.EINVAL),
     (dict(B=16, m=8, n=2), None), (dict(block_density=0.0), crisp.EINVAL), (dict(block_density=1.5), crisp.EINVAL),
     (dict(block_density=float("nan")), crisp.EINVAL), (dict(S=0), crisp.ESHAPE), (dict(K=-3), crisp.ESHAPE),
-    (dict(sal_kind=7), crisp.EINVAL), (dict(select_mode=2), crisp.EINVAL)])
+    (dict(sal_kind=7), crisp.EINVAL), (dict(select_mode=2), crisp.EINVAL),
+    # packed values of the whole grid: 4 GiB and one block column less
+    (dict(S=32768, K=65536, n=4, m=4, B=64), crisp.ESHAPE), (dict(S=32768, K=65536 - 64, n=4, m=4, B=64), None)])
 def test_descriptor_validation(kw, status):
     base = dict(S=64, K=128, n=2, m=4, B=32, block_density=0.5)
     base.update(kw)
