@@ -112,7 +112,8 @@ typedef struct {
     const float *scale;        /* S values (device) or NULL                                      */
     const float *bias;         /* S values (device) or NULL                                      */
     const void *residual;      /* S x ldr elements of the output's type (device) or NULL         */
-    int64_t ldr;               /* >= Ncol, multiple of 8 (only read when residual != NULL)       */
+    int64_t ldr;               /* >= Ncol, multiple of 8, <= 2^27 (only read when residual != NULL);
+                                  above 2^23 the generic kernel runs (fused lowering: EUNSUPPORTED)  */
     int32_t relu;              /* 0 or 1                                                         */
     int32_t reserved;          /* 0                                                              */
 } crisp_epilogue;

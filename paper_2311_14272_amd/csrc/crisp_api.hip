@@ -307,7 +307,8 @@ static crisp_status conv_spmm_impl(const crisp_layer_desc* desc, const crisp_con
     // what the fused kernels cover; everything else goes through crisp_im2col + crisp_spmm
     const bool pattern_ok = (g.m == 4 && g.n <= 4) || (g.m == 8 && (g.n == 1 || g.n == 2 || g.n == 4 || g.n == 8));
     if (g.B == 16 || (Ncol & 1) || conv->kw > 16 || conv->kh * conv->kw > 64 || conv->stride > 16 ||
-        plane > ((int64_t)1 << 27) || ldy > ((int64_t)1 << 23) || !pattern_ok)
+        plane > ((int64_t)1 << 27) || ldy > ((int64_t)1 << 23) || (ep && ep->residual && ep->ldr > ((int64_t)1 << 23)) ||
+        !pattern_ok)
         return CRISP_EUNSUPPORTED;
     // channel counts that are no multiple of B: rows are located one by one inside one buffer range
     if (conv->C % g.B != 0 && ((int64_t)conv->C * plane * 2 >= ((int64_t)1 << 32) - 16 || g.K > 65535))

@@ -457,6 +457,9 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
         a.ep_on = 1; a.ep_relu = ep->relu ? 1 : 0;
         a.ep_scale = ep->scale; a.ep_bias = ep->bias; a.ep_res = ep->residual; a.ep_ldr = ep->ldr;
     }
+    // the specialised kernels address a block-row of Y, and of the residual, with 32-bit byte offsets:
+    // both row strides must stay within 2^23 elements there (beyond that the generic kernel runs)
+    const int64_t ld_wide = (a.ep_on && a.ep_res && a.ep_ldr > ldy) ? a.ep_ldr : ldy;
     a.act = nullptr;
     if (conv) {
         // implicit lowering: X is the activation itself
@@ -482,7 +485,7 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
     // convolution with the input patch staged in LDS (forced shape 12)
     ConvLdsSched cs;
     const bool conv_lds_wanted = force_shape == 12 || force_shape < 0;
-    if (conv && conv_lds_wanted && (Ncol % 4) == 0 && ldy <= ((int64_t)1 << 23) && conv_lds_plan(a, g.B, conv->kh, &cs) &&
+    if (conv && conv_lds_wanted && (Ncol % 4) == 0 && ld_wide <= ((int64_t)1 << 23) && conv_lds_plan(a, g.B, conv->kh, &cs) &&
         (force_shape == 12 || conv_lds_pays(cs, g.Sb, density_hint, conv->batch, a.Wo))) {
         a.use_smf = 1;
         switch (g.n * 16 + g.m) {
@@ -500,7 +503,7 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
     // channel counts that are no multiple of the block size (first layers): input patch in LDS in its
     // own layout (forced shape 14)
     ConvPatchSched ps;
-    if (conv && (force_shape == 14 || force_shape < 0) && ldy <= ((int64_t)1 << 23) &&
+    if (conv && (force_shape == 14 || force_shape < 0) && ld_wide <= ((int64_t)1 << 23) &&
         conv_patch_plan(a, g.B, conv->kh, g.Kb, &ps)) {
         a.use_smf = 1;
         switch (g.n * 16 + g.m) {
@@ -521,7 +524,7 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
     int bpr = hint ? (int)(density_hint * g.Kb + 0.5) : (g.Kb + 1) / 2;
     if (bpr < 1) bpr = 1;
     // LDS-resident block-rows (forced shapes 5 = narrow strips, 6 = wide strips)
-    const bool lds_ok = !conv && (g.K % 16) == 0 && (Ncol % 4) == 0 && ldy <= ((int64_t)1 << 23);
+    const bool lds_ok = !conv && (g.K % 16) == 0 && (Ncol % 4) == 0 && ld_wide <= ((int64_t)1 << 23);
     if (lds_ok && (force_shape == 5 || force_shape == 6)) return launch_spmm_lds(a, g.B, bpr, force_shape == 6, st);
     if (lds_ok && force_shape < 0 && hint && uniform_rows && prefer_lds(g, Ncol, bpr))
         return launch_spmm_lds(a, g.B, bpr, bpr <= 1, st);
@@ -542,7 +545,7 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
                     : pick_shape(g, Ncol, bpr, a.use_smf && g.n <= 2);
     // the specialised kernels assume whole 16-row MFMA steps of X (K % 16 == 0) and whole groups
     // of four output columns per lane (Ncol % 4 == 0)
-    if (conv || (force_shape != 4 && (g.K % 16) == 0 && (Ncol % 4) == 0 && ldy <= ((int64_t)1 << 23))) {
+    if (conv || (force_shape != 4 && (g.K % 16) == 0 && (Ncol % 4) == 0 && ld_wide <= ((int64_t)1 << 23))) {
         const int key = g.n * 16 + g.m;
         switch (key) {
             case 1 * 16 + 4: return launch_reg_nm<1, 4>(a, g.B, shape, st);

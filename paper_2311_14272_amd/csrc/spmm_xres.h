@@ -160,7 +160,8 @@ __global__ __launch_bounds__(256, 2) void spmm_xres_kernel(SpmmArgs p, int rows_
 
 // Covered: plain X (no lowering), 64 x 64 blocks, K <= 128 and a multiple of 16, Ncol a multiple of 4.
 inline bool xres_covers(const SpmmArgs& a, int B) {
-    return a.act == nullptr && B == 64 && a.K <= 128 && (a.K % 16) == 0 && (a.Ncol % 4) == 0 && a.ldy <= ((int64_t)1 << 23);
+    return a.act == nullptr && B == 64 && a.K <= 128 && (a.K % 16) == 0 && (a.Ncol % 4) == 0 && a.ldy <= ((int64_t)1 << 23) &&
+           !(a.ep_on && a.ep_res && a.ep_ldr > ((int64_t)1 << 23));
 }
 
 template <int N, int M, bool SMF, int KB>

@@ -78,6 +78,39 @@ def test_spmm_epilogue(L):
                 _check(Yh[: L.S, : L.Ncol], Yref, Aref, bf16, "%s %s shape %s bf16=%s" % (L.name, cb, shape, bf16))
 
 
+def test_residual_with_a_very_wide_row_stride():
+    """A residual whose row stride exceeds 2^23 elements (a view into a much wider tensor) while Y is
+    narrow: the kernels that address a block-row with 32-bit offsets must not be used for it."""
+    L = synth.LayerSpec("ep_wide_ldr", 96, 128, 264, 2, 4, 32, 0.5, synth.SAL_MAG, 0.05)
+    W, G, X = synth.draw_small(L, 73)
+    sel = oracle.select(W, G, L.n, L.m, L.B, L.density, L.sal_kind, L.select_mode)
+    layer, _ = run_select_pack(L, W, G)
+    Y0, A0 = oracle.gemm_masked(W, sel.mask, X)
+    ldx = (L.Ncol + 7) // 8 * 8
+    Xp = np.zeros((L.K, ldx), dtype=np.uint16)
+    Xp[:, : L.Ncol] = X
+    dX = dev(Xp)
+    ldr = (1 << 23) + 8
+    rng = np.random.default_rng(5)
+    res = synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(rng.normal(0.0, 1.0, size=(L.S, L.Ncol)).astype(np.float32)))
+    dres = torch.zeros((L.S, ldr), dtype=torch.bfloat16, device="cuda")
+    dres[:, : L.Ncol] = torch.from_numpy(res).cuda().to(torch.bfloat16)
+    Yref, Aref = oracle.epilogue(Y0, A0, None, None, res, True)
+    ep = crisp.epilogue(None, None, dres.view(torch.int16), ldr, True)
+    for shape in (None, 1, 8):
+        Y = torch.full((L.S, ldx), float("nan"), dtype=torch.bfloat16, device="cuda")
+        crisp.crisp_spmm_ep(layer.desc, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dX, L.Ncol, ldx, Y, ldx,
+                            crisp.Y_BF16, ep, ws=None, ws_bytes=0 if shape is None else shape + 1)
+        torch.cuda.synchronize()
+        _check(Y.float().cpu().numpy().astype(np.float64)[:, : L.Ncol], Yref, Aref, True, "wide ldr shape %s" % shape)
+    # the fused lowering has no generic kernel to hand over to
+    conv = crisp.ConvDesc(128, 12, 22, 1, 1, 1, 1, 0, crisp.ACT_CBHW, crisp.X_KN)
+    with pytest.raises(crisp.CrispError) as e:
+        crisp.crisp_conv_spmm_ep(layer.desc, conv, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dX, Y, ldx,
+                                 crisp.Y_BF16, ep)
+    assert e.value.status == crisp.EUNSUPPORTED
+
+
 def test_epilogue_none_equals_plain_product():
     """ep == NULL and an epilogue with nothing switched on give the plain product, bit for bit."""
     L = synth.small_cases()[0]
