@@ -681,6 +681,23 @@ def test_maximum_column_counts(case):
         torch.cuda.empty_cache()
 
 
+def test_maximum_row_stride_of_x():
+    """X handed over as the first columns of a tensor with the largest accepted row stride (2^27)."""
+    L = synth.LayerSpec("wide_ldx", 128, 128, 520, 2, 4, 64, 1.0, synth.SAL_MAG, 0.05)
+    W, G, X = synth.draw_small(L, 31)
+    sel = oracle.select(W, G, L.n, L.m, L.B, L.density, L.sal_kind)
+    layer, _ = run_select_pack(L, W, G)
+    Yref, Aref = oracle.gemm_masked(W, sel.mask, X)
+    ldx = 1 << 27
+    dX = torch.zeros((L.K, ldx), dtype=torch.int16, device="cuda")
+    dX[:, : L.Ncol] = dev(X)
+    for shape in (None, 0, 1, 2, 4, 5, 6, 8, 13):
+        print("wide ldx shape", shape, flush=True)
+        for yd in (crisp.Y_F32, crisp.Y_BF16):
+            Y = run_spmm(layer, dX, L.Ncol, ldx, yd, L.S, shape=shape)
+            check_product(Y, Yref, Aref, yd, "wide ldx shape %s" % shape)
+
+
 def test_maximum_convolution_plane():
     """Fused lowering with 2^23 output columns (the widest Y the fused kernels take): the kernel that
     stages the input in LDS (the library's own choice) and the register kernels, sampled columns."""
