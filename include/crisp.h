@@ -224,7 +224,9 @@ CRISP_API crisp_status crisp_select_pack_batch(int32_t n_layers, const crisp_lay
  * and zero outside the image.  X is K x ldx with K = kh*kw*C, Ncol = batch*Ho*Wo
  * columns written, ldx >= Ncol.  For kh = kw = stride = 1, pad = 0 the result equals
  * act viewed as C x (batch*H*W); callers may skip the call and pass act as X.
- * All pointers device.  Errors: EINVAL, ESHAPE, EUNSUPPORTED (layouts), EDEVICE.
+ * Limits: kh, kw <= 255, stride, pad <= 65535, C < 2^20 - 16, batch*H*W < 2^31 (EUNSUPPORTED beyond),
+ * Ncol < 2^31 - 1024 (ESHAPE beyond).
+ * All pointers device.  Errors: EINVAL, ESHAPE, EUNSUPPORTED (layouts, limits), EDEVICE.
  */
 CRISP_API crisp_status crisp_im2col(const crisp_conv_desc *conv, const uint16_t *act, uint16_t *X, int64_t ldx,
                           void *stream);
@@ -294,7 +296,7 @@ CRISP_API crisp_status crisp_conv_spmm(const crisp_layer_desc *desc, const crisp
  *   out[c][i][oh][ow] = max over a < kh, b < kw of act[c][i][oh*stride + a - pad][ow*stride + b - pad],
  * positions outside the image excluded; Ho, Wo as for a convolution; pad < kh, kw.  The result is
  * one of the inputs (no rounding).  act and out device, bf16, out holds C*batch*Ho*Wo elements
- * (fewer than 2^32).
+ * (fewer than 2^32); kh, kw <= 255, stride <= 65535.
  * Errors: EINVAL, ESHAPE, EUNSUPPORTED (layout, size), EDEVICE.
  */
 CRISP_API crisp_status crisp_maxpool(const crisp_conv_desc *pool, const uint16_t *act, uint16_t *out, void *stream);

@@ -214,13 +214,16 @@ crisp_status crisp_im2col(const crisp_conv_desc* c, const uint16_t* act, uint16_
     if (c->C < 1 || c->H < 1 || c->W < 1 || c->batch < 1 || c->kh < 1 || c->kw < 1 || c->stride < 1 || c->pad < 0)
         return CRISP_ESHAPE;
     if (c->act_layout != CRISP_ACT_CBHW || c->x_layout != CRISP_X_KN) return CRISP_EUNSUPPORTED;
+    // (filter and step sizes far beyond any layer; they keep the 32-bit index arithmetic below exact)
+    if (c->kh > 255 || c->kw > 255 || c->stride > 65535 || c->pad > 65535) return CRISP_EUNSUPPORTED;
     int64_t Ho = ((int64_t)c->H + 2 * c->pad - c->kh) / c->stride + 1;
     int64_t Wo = ((int64_t)c->W + 2 * c->pad - c->kw) / c->stride + 1;
     if (c->H + 2 * c->pad < c->kh || c->W + 2 * c->pad < c->kw || Ho < 1 || Wo < 1) return CRISP_ESHAPE;
     int64_t Ncol = (int64_t)c->batch * Ho * Wo;
     int64_t K = (int64_t)c->kh * c->kw * c->C;
-    if (ldx < Ncol || Ncol > INT32_MAX || K > INT32_MAX) return CRISP_ESHAPE;
-    if ((int64_t)c->batch * c->H * c->W >= ((int64_t)1 << 31) || c->C > (1 << 20)) return CRISP_EUNSUPPORTED;
+    if (ldx < Ncol || Ncol > INT32_MAX - 1024 || K > INT32_MAX) return CRISP_ESHAPE;   // (column index of a thread: int)
+    // (one grid slice per 16 channels: at most 65535 of them)
+    if ((int64_t)c->batch * c->H * c->W >= ((int64_t)1 << 31) || c->C > (1 << 20) - 16) return CRISP_EUNSUPPORTED;
     if (misaligned(act, 16) || misaligned(X, 16)) return CRISP_EALIGN;
     hipError_t e = launch_im2col(*c, act, X, ldx, (hipStream_t)stream);
     return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
@@ -230,6 +233,7 @@ crisp_status crisp_maxpool(const crisp_conv_desc* c, const uint16_t* act, uint16
     if (!c || !act || !out) return CRISP_EINVAL;
     if (c->C < 1 || c->H < 1 || c->W < 1 || c->batch < 1 || c->kh < 1 || c->kw < 1 || c->stride < 1 || c->pad < 0)
         return CRISP_ESHAPE;
+    if (c->kh > 255 || c->kw > 255 || c->stride > 65535) return CRISP_EUNSUPPORTED;
     if (c->pad >= c->kh || c->pad >= c->kw) return CRISP_ESHAPE;      // every window must touch the image
     if (c->H + 2 * c->pad < c->kh || c->W + 2 * c->pad < c->kw) return CRISP_ESHAPE;
     if (c->act_layout != CRISP_ACT_CBHW) return CRISP_EUNSUPPORTED;

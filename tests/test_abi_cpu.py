@@ -140,6 +140,11 @@ def test_entry_points_reject_bad_arguments_without_a_device():
     assert L.crisp_im2col(C.byref(cv2), fake, fake, 64, None) == crisp.ESHAPE
     cv3 = crisp.ConvDesc(3, 8, 8, 1, 3, 3, 1, 1, 1, 0)
     assert L.crisp_im2col(C.byref(cv3), fake, fake, 64, None) == crisp.EUNSUPPORTED
+    # sizes beyond the stated limits: a filter edge of 256, a million channels, 2^31 - 1024 columns
+    assert L.crisp_im2col(C.byref(crisp.ConvDesc(3, 300, 300, 1, 256, 3, 1, 0, 0, 0)), fake, fake, 1 << 20, None) == crisp.EUNSUPPORTED
+    assert L.crisp_im2col(C.byref(crisp.ConvDesc(1 << 20, 2, 2, 1, 1, 1, 1, 0, 0, 0)), fake, fake, 64, None) == crisp.EUNSUPPORTED
+    assert L.crisp_im2col(C.byref(crisp.ConvDesc(1, 1, (1 << 31) - 512, 1, 1, 1, 1, 0, 0, 0)), fake, fake, 1 << 31, None) == crisp.ESHAPE
+    assert L.crisp_maxpool(C.byref(crisp.ConvDesc(3, 600, 600, 1, 256, 256, 1, 0, 0, 0)), fake, fake, None) == crisp.EUNSUPPORTED
     assert crisp.status_str(crisp.EALIGN).startswith("misaligned")
 
 
