@@ -318,6 +318,32 @@ CRISP_API crisp_status crisp_conv_spmm_ep(const crisp_layer_desc *desc, const cr
                                 void *stream);
 
 /*
+ * A whole convolution layer (Sec. 3 "Notation" + Sec. 3.5): the product of a packed layer with the
+ * lowering of act [C][batch][H][W], by whichever of three ways is fastest for the geometry:
+ *   CRISP_CONV_DIRECT  1x1 filter, stride 1, no padding, batch*H*W a multiple of 8: act is X as it stands;
+ *   CRISP_CONV_FUSED   crisp_conv_spmm_ep (X never materialised);
+ *   CRISP_CONV_IM2COL  crisp_im2col into x_scratch, K x round_up(Ncol, 8) bf16, then crisp_spmm_ep.
+ * The fused kernels that locate strided or odd-width columns one by one repeat that for every kept block;
+ * they are chosen where desc->block_density (used here, unlike in the product calls: it must be the
+ * layer's) says the kept blocks of all block-rows are not many more than X has block columns, where the
+ * kernel that stages the input in LDS applies, or where column pairs come from one aligned piece of
+ * an input row; everything the fused entry point does not cover is materialised.
+ * crisp_conv_plan (host only, pure) reports the way and the scratch bytes it needs (0 unless IM2COL).
+ * crisp_conv_forward enqueues it; x_scratch may be NULL when no scratch is needed; with Y or residual
+ * row strides above 2^23 a FUSED plan is run as IM2COL (then scratch of K x round_up(Ncol, 8) is needed
+ * after all); *path_taken (optional, host) receives the way taken.
+ * Errors: those of the entry points named above; EBUFSIZE when the scratch is missing or too small.
+ */
+enum { CRISP_CONV_DIRECT = 0, CRISP_CONV_FUSED = 1, CRISP_CONV_IM2COL = 2 };
+CRISP_API crisp_status crisp_conv_plan(const crisp_layer_desc *desc, const crisp_conv_desc *conv, int32_t *path,
+                             size_t *scratch_bytes);
+CRISP_API crisp_status crisp_conv_forward(const crisp_layer_desc *desc, const crisp_conv_desc *conv,
+                                const int32_t *row_ptr, const int32_t *col_idx, const uint16_t *vals,
+                                const uint32_t *idx_words, const uint16_t *act, void *Y, int64_t ldy,
+                                int32_t y_dtype, const crisp_epilogue *ep, uint16_t *x_scratch,
+                                size_t scratch_bytes, int32_t *path_taken, void *stream);
+
+/*
  * Global block budget across layers (Alg. 1 lines 6-9; Sec. 3.3): turns one overall target
  * sparsity into kept blocks per block-row for every layer.
  *   Per layer, each block-row's scores (output block_score of crisp_select_mask) are ordered

@@ -97,9 +97,12 @@ def lib():
         L.crisp_spmm_timed.argtypes = [C.POINTER(LayerDesc), C.POINTER(ConvDesc), vp, vp, vp, vp, vp, C.c_int64,
                                        C.c_int64, vp, C.c_int64, C.c_int32, vp, vp, vp]
         L.crisp_global_budget.argtypes = [C.c_int32, vp, vp, C.c_double, vp, vp, vp, C.c_size_t, vp]
+        L.crisp_conv_plan.argtypes = [C.POINTER(LayerDesc), C.POINTER(ConvDesc), C.POINTER(C.c_int32), C.POINTER(C.c_size_t)]
+        L.crisp_conv_forward.argtypes = [C.POINTER(LayerDesc), C.POINTER(ConvDesc), vp, vp, vp, vp, vp, vp, C.c_int64, C.c_int32,
+                                         C.POINTER(Epilogue), vp, C.c_size_t, C.POINTER(C.c_int32), vp]
         for f in (L.crisp_pack_sizes, L.crisp_select_mask, L.crisp_pack, L.crisp_select_pack, L.crisp_select_pack_batch,
                   L.crisp_im2col, L.crisp_spmm, L.crisp_spmm_ep, L.crisp_conv_spmm_ep,
-                  L.crisp_conv_spmm, L.crisp_spmm_timed, L.crisp_global_budget):
+                  L.crisp_conv_spmm, L.crisp_spmm_timed, L.crisp_global_budget, L.crisp_conv_plan, L.crisp_conv_forward):
             f.restype = C.c_int32
         _lib = L
     return _lib
@@ -328,75 +331,24 @@ def conv_desc_of(cv) -> ConvDesc:
     return ConvDesc(cv.C, cv.H, cv.W, cv.batch, cv.kh, cv.kw, cv.stride, cv.pad, ACT_CBHW, X_KN)
 
 
-def fused_lowering_ok(cv, B: int, n: int, m: int) -> bool:
-    """Whether crisp_conv_spmm covers this convolution (otherwise crisp_im2col + crisp_spmm)."""
-    Ho = (cv.H + 2 * cv.pad - cv.kh) // cv.stride + 1
-    Wo = (cv.W + 2 * cv.pad - cv.kw) // cv.stride + 1
-    pattern = (m == 4 and n <= 4) or (m == 8 and n in (1, 2, 4, 8))
-    plane = cv.batch * cv.H * cv.W
-    thin_ok = cv.C % B == 0 or (cv.C * plane * 2 < (1 << 32) - 16 and cv.kh * cv.kw * cv.C <= 65535)
-    return (B in (32, 64) and thin_ok and (cv.batch * Ho * Wo) % 2 == 0 and cv.kw <= 16 and cv.kh * cv.kw <= 64
-            and cv.stride <= 16 and plane <= (1 << 27) and pattern)
+CONV_PATHS = ("none", "fused", "im2col")     # CRISP_CONV_DIRECT, CRISP_CONV_FUSED, CRISP_CONV_IM2COL
 
 
-def conv_lds_chosen(cv, B: int, S: int, density: float) -> bool:
-    """Whether crisp_conv_spmm runs this convolution with the input patch staged in LDS (the
-    library's own rule, restated here because the choice between the fused path and im2col below
-    depends on it).  Covered: 64x64 blocks, C a multiple of 64, even W <= 64 and Wo, stride <= 4, a
-    patch of at most 60 KB, a channel plane below 2^25 elements.  Chosen: several taps (a strided
-    1x1 filter would stage every input column for a single use) and at least two block-rows, when
-    half of the blocks are kept; below that only where a staged patch still serves about six kept
-    blocks, Wo <= 28, at most four block-rows and at least 256 workgroups."""
-    Ho = (cv.H + 2 * cv.pad - cv.kh) // cv.stride + 1
-    Wo = (cv.W + 2 * cv.pad - cv.kw) // cv.stride + 1
-    Sb = (S + B - 1) // B
-    taps = cv.kh * cv.kw
-    if B != 64 or cv.C % 64 or Wo % 2 or Wo > 64 or cv.W % 2 or cv.W > 64 or cv.stride > 4 or taps > 64:
-        return False
-    if cv.C // 64 > 64 or taps * (cv.C // 64) > 128 or cv.batch * cv.H * cv.W >= 1 << 25:
-        return False
-    RG = 4 if Sb >= 4 else 2 if Sb >= 2 else 1
-    PT = 4 // RG
-    R = min(64 // Wo, Ho)
-    rows = (PT * R - 1) * (1 if cv.kh == 1 else cv.stride) + cv.kh
-    cols = max((Wo - 1) * cv.stride + cv.kw, cv.W + cv.pad)
-    if rows * cols * 144 > 60 * 1024 or taps == 1 or Sb < 2 or not density <= 1.0:
-        return False
-    if density >= 0.5:
-        return True
-    wgs = cv.batch * ((Ho + PT * R - 1) // (PT * R)) * ((Sb + RG - 1) // RG)
-    return RG * density * taps >= 6.0 and Sb <= 4 and Wo <= 28 and wgs >= 256
+def conv_plan(desc: LayerDesc, cv):
+    """crisp_conv_plan: (path, scratch bytes) for a layer descriptor and a ConvShape-like geometry."""
+    path = C.c_int32(-1)
+    nbytes = C.c_size_t(0)
+    conv = conv_desc_of(cv)
+    st = lib().crisp_conv_plan(C.byref(desc), C.byref(conv), C.byref(path), C.byref(nbytes))
+    if st != OK:
+        raise CrispError("crisp_conv_plan", st)
+    return CONV_PATHS[path.value], nbytes.value
 
 
 def lowering_path(cv, B: int, n: int, m: int, S: int, density: float) -> str:
-    """How conv_forward runs this convolution: "none" (act is X), "fused" (crisp_conv_spmm) or
-    "im2col" (crisp_im2col into a scratch X, then crisp_spmm).  The fused kernels locate strided or
-    odd-width columns one by one with 2-byte loads, once per kept block; that beats writing X only
-    where X would be an inflated copy (more than one filter tap) and the kept blocks of all
-    block-rows together are not many more than X has block columns: block-rows x block density <=
-    FUSED_GENERAL_MAX_GATHER (measured on the strided 3x3 layers of ResNet-50 at batch 256: a
-    block gathered costs ~0.8 of a block column written and read back once, and the product over
-    a materialised X costs ~0.2 per kept block)."""
-    Ho = (cv.H + 2 * cv.pad - cv.kh) // cv.stride + 1
-    Wo = (cv.W + 2 * cv.pad - cv.kw) // cv.stride + 1
-    pointwise = cv.kh == 1 and cv.kw == 1 and cv.stride == 1 and cv.pad == 0
-    if pointwise and (cv.batch * Ho * Wo) % 8 == 0:
-        return "none"
-    if not pointwise and fused_lowering_ok(cv, B, n, m):
-        paired = cv.stride == 1 and Wo % 2 == 0 and cv.W >= 2 and cv.C % B == 0
-        # strided 1x1 filter whose column pairs come from one 8-byte piece of an input row: X is not inflated,
-        # the fused path only saves writing and re-reading it, and pays with wider loads per kept block
-        # (ResNet-50 shortcuts at batch 256: 161 vs 186 us with 4 gathers per block column, 148 vs 115 with 11)
-        if (cv.kh == 1 and cv.kw == 1 and cv.stride == 2 and cv.pad == 0 and cv.W % 2 == 0 and Wo % 2 == 0 and cv.C % B == 0
-                and ((S + B - 1) // B) * density <= STRIDED_1X1_MAX_GATHER):
-            return "fused"
-        if paired or conv_lds_chosen(cv, B, S, density) or (cv.kh * cv.kw > 1 and ((S + B - 1) // B) * density <= FUSED_GENERAL_MAX_GATHER):
-            return "fused"
-    return "im2col"
-
-
-FUSED_GENERAL_MAX_GATHER = 1.6
-STRIDED_1X1_MAX_GATHER = 6.0
+    """How the library runs this convolution: "none" (act is X), "fused" (crisp_conv_spmm) or "im2col"
+    (crisp_im2col into a scratch X, then crisp_spmm); the rule itself lives in crisp_conv_plan."""
+    return conv_plan(layer_desc(S, cv.kh * cv.kw * cv.C, n, m, B, density), cv)[0]
 
 
 def conv_needs_scratch(cv, B: int, n: int, m: int, S: int, density: float) -> bool:
@@ -404,26 +356,21 @@ def conv_needs_scratch(cv, B: int, n: int, m: int, S: int, density: float) -> bo
     return lowering_path(cv, B, n, m, S, density) == "im2col"
 
 
-def conv_forward(layer: DeviceLayer, cv, act, Y, ldy, y_dtype=Y_F32, X_scratch=None, ep=None):
-    """Product of a packed layer with a convolution input act [C][batch][H][W] on the current stream.
-    1x1 stride-1 with an aligned row stride: act is X.  Covered geometries: fused lowering.
-    Otherwise crisp_im2col into X_scratch (K x round_up(Ncol, 8), allocated by the caller) followed
-    by crisp_spmm.  Returns the path taken."""
-    d = layer.desc
-    Ho = (cv.H + 2 * cv.pad - cv.kh) // cv.stride + 1
-    Wo = (cv.W + 2 * cv.pad - cv.kw) // cv.stride + 1
-    Ncol = cv.batch * Ho * Wo
-    path = lowering_path(cv, d.B, d.n, d.m, d.S, d.block_density)
-    if path == "none":
-        crisp_spmm_ep(d, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, act, Ncol, Ncol, Y, ldy, y_dtype, ep)
-        return path
-    if path == "fused":
-        crisp_conv_spmm_ep(d, conv_desc_of(cv), layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, act, Y, ldy,
-                           y_dtype, ep)
-        return path
-    if X_scratch is None:
+def conv_forward(layer: DeviceLayer, cv, act, Y, ldy, y_dtype=Y_F32, X_scratch=None, ep=None, stream=-1):
+    """crisp_conv_forward on the current stream: the product of a packed layer with a convolution input
+    act [C][batch][H][W].  X_scratch (K x round_up(Ncol, 8) bf16, allocated by the caller) is needed where
+    crisp_conv_plan says so.  Returns the path taken."""
+    taken = C.c_int32(-1)
+    conv = conv_desc_of(cv)
+    nbytes = 0 if X_scratch is None else X_scratch.numel() * X_scratch.element_size()
+    st = lib().crisp_conv_forward(C.byref(layer.desc), C.byref(conv), _ptr(layer.row_ptr), _ptr(layer.col_idx), _ptr(layer.vals),
+                                  _ptr(layer.idx_words), _ptr(act), _ptr(Y), ldy, y_dtype,
+                                  C.byref(ep) if ep is not None else None, _ptr(X_scratch), nbytes, C.byref(taken),
+                                  _stream() if stream == -1 else stream)
+    if st == EBUFSIZE and X_scratch is None:
         raise ValueError("this convolution needs an X scratch buffer of K x round_up(Ncol, 8) bf16")
-    ldx = (Ncol + 7) // 8 * 8
-    crisp_im2col(conv_desc_of(cv), act, X_scratch, ldx)
-    crisp_spmm_ep(d, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, X_scratch, Ncol, ldx, Y, ldy, y_dtype, ep)
-    return "im2col"
+    if st != OK:
+        raise CrispError("crisp_conv_forward", st)
+    return CONV_PATHS[taken.value]
+
+

@@ -283,6 +283,17 @@ static crisp_status spmm_impl(const crisp_layer_desc* desc, const int32_t* row_p
     return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
 }
 
+// The geometries the fused lowering covers (row strides of Y and of a residual are checked by the caller).
+static bool fused_lowering_covers(const Geometry& g, const crisp_conv_desc& conv, int64_t Ncol, int64_t plane) {
+    const bool pattern_ok = (g.m == 4 && g.n <= 4) || (g.m == 8 && (g.n == 1 || g.n == 2 || g.n == 4 || g.n == 8));
+    if (g.B == 16 || (Ncol & 1) || conv.kw > 16 || conv.kh * conv.kw > 64 || conv.stride > 16 ||
+        plane > ((int64_t)1 << 27) || !pattern_ok)
+        return false;
+    // channel counts that are no multiple of B: rows are located one by one inside one buffer range
+    if (conv.C % g.B != 0 && ((int64_t)conv.C * plane * 2 >= ((int64_t)1 << 32) - 16 || g.K > 65535)) return false;
+    return true;
+}
+
 static crisp_status conv_spmm_impl(const crisp_layer_desc* desc, const crisp_conv_desc* conv, const int32_t* row_ptr,
                                    const int32_t* col_idx, const uint16_t* vals, const uint32_t* idx_words,
                                    const uint16_t* act, void* Y, int64_t ldy, int32_t y_dtype, void* ws,
@@ -309,13 +320,8 @@ static crisp_status conv_spmm_impl(const crisp_layer_desc* desc, const crisp_con
         return CRISP_EALIGN;
     { crisp_status es = check_epilogue(ep, Ncol); if (es != CRISP_OK) return es; }
     // what the fused kernels cover; everything else goes through crisp_im2col + crisp_spmm
-    const bool pattern_ok = (g.m == 4 && g.n <= 4) || (g.m == 8 && (g.n == 1 || g.n == 2 || g.n == 4 || g.n == 8));
-    if (g.B == 16 || (Ncol & 1) || conv->kw > 16 || conv->kh * conv->kw > 64 || conv->stride > 16 ||
-        plane > ((int64_t)1 << 27) || ldy > ((int64_t)1 << 23) || (ep && ep->residual && ep->ldr > ((int64_t)1 << 23)) ||
-        !pattern_ok)
-        return CRISP_EUNSUPPORTED;
-    // channel counts that are no multiple of B: rows are located one by one inside one buffer range
-    if (conv->C % g.B != 0 && ((int64_t)conv->C * plane * 2 >= ((int64_t)1 << 32) - 16 || g.K > 65535))
+    if (!fused_lowering_covers(g, *conv, Ncol, plane) || ldy > ((int64_t)1 << 23) ||
+        (ep && ep->residual && ep->ldr > ((int64_t)1 << 23)))
         return CRISP_EUNSUPPORTED;
     const int force_shape = (!ws && ws_bytes >= 1 && ws_bytes <= 4) ? (int)ws_bytes - 1
                           : (!ws && ws_bytes >= 8 && ws_bytes <= 11) ? (int)ws_bytes - 1
@@ -356,6 +362,93 @@ crisp_status crisp_conv_spmm_ep(const crisp_layer_desc* desc, const crisp_conv_d
                                 void* ws, size_t ws_bytes, void* stream) {
     return conv_spmm_impl(desc, conv, row_ptr, col_idx, vals, idx_words, act, Y, ldy, y_dtype, ws, ws_bytes, stream,
                           nullptr, nullptr, ep);
+}
+
+// Thresholds of crisp_conv_plan, measured on the ResNet-50 shapes at batch 256.  A kept block gathered
+// with 2-byte loads costs about 0.8 of a block column of X written and read back once, the product over a
+// materialised X about 0.2 per kept block: the fused register kernels pay while block-rows x density (kept
+// blocks per block column of X) stays below 1.6.  For a strided 1x1 filter (8-byte pieces, X not inflated)
+// the break-even is near 6 (the stride-2 shortcuts: 161 vs 186 us with 4 gathers per block column, 148 vs
+// 115 us with 11).
+static const double FUSED_GENERAL_MAX_GATHER = 1.6;
+static const double STRIDED_1X1_MAX_GATHER = 6.0;
+
+static crisp_status conv_plan_impl(const crisp_layer_desc* desc, const crisp_conv_desc* conv, Geometry* g, int32_t* path,
+                                   int64_t* Ncol_out, int64_t* scratch_elems) {
+    crisp_status st = make_geometry(desc, true, g);
+    if (st != CRISP_OK) return st;
+    if (conv->C < 1 || conv->H < 1 || conv->W < 1 || conv->batch < 1 || conv->kh < 1 || conv->kw < 1 ||
+        conv->stride < 1 || conv->pad < 0)
+        return CRISP_ESHAPE;
+    if (conv->act_layout != CRISP_ACT_CBHW || conv->x_layout != CRISP_X_KN) return CRISP_EUNSUPPORTED;
+    if (conv->kh > 255 || conv->kw > 255 || conv->stride > 65535 || conv->pad > 65535) return CRISP_EUNSUPPORTED;
+    if ((int64_t)conv->kh * conv->kw * conv->C != g->K) return CRISP_ESHAPE;
+    if (conv->H + 2 * conv->pad < conv->kh || conv->W + 2 * conv->pad < conv->kw) return CRISP_ESHAPE;
+    const int64_t Ho = ((int64_t)conv->H + 2 * conv->pad - conv->kh) / conv->stride + 1;
+    const int64_t Wo = ((int64_t)conv->W + 2 * conv->pad - conv->kw) / conv->stride + 1;
+    const int64_t Ncol = (int64_t)conv->batch * Ho * Wo;
+    const int64_t plane = (int64_t)conv->batch * conv->H * conv->W;
+    if (Ncol > ((int64_t)1 << 27)) return CRISP_ESHAPE;
+    *Ncol_out = Ncol;
+    *scratch_elems = 0;
+    const bool pointwise = conv->kh == 1 && conv->kw == 1 && conv->stride == 1 && conv->pad == 0;
+    if (pointwise && (Ncol & 7) == 0) { *path = CRISP_CONV_DIRECT; return CRISP_OK; }
+    if (!pointwise && fused_lowering_covers(*g, *conv, Ncol, plane)) {
+        const double gathers = (double)g->Sb * desc->block_density;   // kept blocks per block column of X
+        const bool aligned = conv->C % g->B == 0;
+        const bool paired = conv->stride == 1 && (Wo & 1) == 0 && conv->W >= 2 && aligned;
+        const bool strided_1x1 = conv->kh == 1 && conv->kw == 1 && conv->stride == 2 && conv->pad == 0 && (conv->W & 1) == 0 &&
+                                 (Wo & 1) == 0 && aligned;
+        if ((strided_1x1 && gathers <= STRIDED_1X1_MAX_GATHER) || paired ||
+            conv_lds_would_run(*g, desc->block_density, *conv, Ncol) ||
+            (conv->kh * conv->kw > 1 && gathers <= FUSED_GENERAL_MAX_GATHER)) {
+            *path = CRISP_CONV_FUSED;
+            return CRISP_OK;
+        }
+    }
+    *path = CRISP_CONV_IM2COL;
+    *scratch_elems = (int64_t)g->K * ((Ncol + 7) / 8 * 8);
+    return CRISP_OK;
+}
+
+crisp_status crisp_conv_plan(const crisp_layer_desc* desc, const crisp_conv_desc* conv, int32_t* path, size_t* scratch_bytes) {
+    if (!desc || !conv || !path) return CRISP_EINVAL;
+    Geometry g;
+    int64_t Ncol = 0, elems = 0;
+    crisp_status st = conv_plan_impl(desc, conv, &g, path, &Ncol, &elems);
+    if (st == CRISP_OK && scratch_bytes) *scratch_bytes = (size_t)elems * 2;
+    return st;
+}
+
+crisp_status crisp_conv_forward(const crisp_layer_desc* desc, const crisp_conv_desc* conv, const int32_t* row_ptr,
+                                const int32_t* col_idx, const uint16_t* vals, const uint32_t* idx_words,
+                                const uint16_t* act, void* Y, int64_t ldy, int32_t y_dtype, const crisp_epilogue* ep,
+                                uint16_t* x_scratch, size_t scratch_bytes, int32_t* path_taken, void* stream) {
+    if (!desc || !conv) return CRISP_EINVAL;
+    Geometry g;
+    int32_t path = 0;
+    int64_t Ncol = 0, elems = 0;
+    crisp_status st = conv_plan_impl(desc, conv, &g, &path, &Ncol, &elems);
+    if (st != CRISP_OK) return st;
+    // the fused kernels address a block-row of Y and of the residual with 32-bit offsets: wider row strides
+    // go through a materialised X and the generic product kernel
+    if (path == CRISP_CONV_FUSED && (ldy > ((int64_t)1 << 23) || (ep && ep->residual && ep->ldr > ((int64_t)1 << 23)))) {
+        path = CRISP_CONV_IM2COL;
+        elems = (int64_t)g.K * ((Ncol + 7) / 8 * 8);
+    }
+    if (path_taken) *path_taken = path;
+    if (path == CRISP_CONV_DIRECT)
+        return spmm_impl(desc, row_ptr, col_idx, vals, idx_words, act, Ncol, Ncol, CRISP_X_KN, Y, ldy, y_dtype, nullptr, 0, stream,
+                         nullptr, nullptr, ep);
+    if (path == CRISP_CONV_FUSED)
+        return conv_spmm_impl(desc, conv, row_ptr, col_idx, vals, idx_words, act, Y, ldy, y_dtype, nullptr, 0, stream, nullptr,
+                              nullptr, ep);
+    if (!x_scratch || scratch_bytes < (size_t)elems * 2) return CRISP_EBUFSIZE;
+    const int64_t ldx = (Ncol + 7) / 8 * 8;
+    st = crisp_im2col(conv, act, x_scratch, ldx, stream);
+    if (st != CRISP_OK) return st;
+    return spmm_impl(desc, row_ptr, col_idx, vals, idx_words, x_scratch, Ncol, ldx, CRISP_X_KN, Y, ldy, y_dtype, nullptr, 0,
+                     stream, nullptr, nullptr, ep);
 }
 
 crisp_status crisp_global_budget(int32_t n_layers, const crisp_layer_desc* descs, const double* const* block_scores,

@@ -44,6 +44,9 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
                        const crisp_epilogue* ep,
                        hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st);
 
+// Whether launch_spmm would run this convolution with the input patch staged in LDS (host only).
+bool conv_lds_would_run(const Geometry& g, double density_hint, const crisp_conv_desc& conv, int64_t Ncol);
+
 #define CRISP_BUDGET_MAX_LAYERS 64
 #define CRISP_BUDGET_MAX_COLS 4096
 struct BudgetArgs {

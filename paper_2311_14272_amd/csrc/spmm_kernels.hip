@@ -443,6 +443,38 @@ static bool prefer_lds(const Geometry& g, int64_t Ncol, int blocks_per_row) {
     return narrow >= 2048 && (slots_per_operand >= 4 || blocks_per_row >= 6);
 }
 
+// Geometry of an implicitly lowered convolution as the product kernels want it (everything but the
+// activation pointer).
+static void fill_conv_args(SpmmArgs& a, const Geometry& g, const crisp_conv_desc& conv) {
+    a.C = conv.C; a.H = conv.H; a.W = conv.W; a.kw = conv.kw; a.pad = conv.pad; a.stride = conv.stride;
+    a.Ho = (conv.H + 2 * conv.pad - conv.kh) / conv.stride + 1;
+    a.Wo = (conv.W + 2 * conv.pad - conv.kw) / conv.stride + 1;
+    // neighbours in a row from one dword when that is possible, else column by column
+    a.conv_mode = (conv.stride == 1 && (a.Wo & 1) == 0 && conv.W >= 2) ? 1 : 2;
+    if (conv.kh == 1 && conv.kw == 1 && conv.stride == 2 && conv.pad == 0 && (conv.W & 1) == 0 && (a.Wo & 1) == 0)
+        a.conv_mode = 4;                       // strided 1x1: both columns from one 8-byte piece of the input row
+    if (conv.C % g.B != 0) a.conv_mode = 3;   // block columns span filter taps: every K-row on its own
+    a.plane = (int64_t)conv.batch * conv.H * conv.W;
+    a.act_bytes = a.conv_mode == 3 ? (uint32_t)((int64_t)conv.C * a.plane * 2) : 0u;
+    a.inv_C = 1.0f / (float)conv.C;
+    a.inv_cpb = conv.C >= g.B ? 1.0f / (float)(conv.C / g.B) : 1.0f;
+    a.inv_kw = 1.0f / (float)conv.kw;
+    a.inv_Wo = 1.0 / a.Wo;
+    a.inv_Ho = 1.0 / a.Ho;
+}
+
+// Whether launch_spmm, left to its own choice, runs this convolution in the kernel that stages the
+// input patch in LDS (the callers that choose between the fused lowering and a materialised X ask).
+bool conv_lds_would_run(const Geometry& g, double density_hint, const crisp_conv_desc& conv, int64_t Ncol) {
+    if (g.B == 16) return false;
+    SpmmArgs a = {};
+    a.S = g.S; a.K = g.K; a.Sb = g.Sb; a.Ncol = Ncol;
+    a.act = reinterpret_cast<const uint16_t*>(&a);      // any non-null value: never dereferenced on the host
+    fill_conv_args(a, g, conv);
+    ConvLdsSched cs;
+    return (Ncol % 4) == 0 && conv_lds_plan(a, g.B, conv.kh, &cs) && conv_lds_pays(cs, g.Sb, density_hint, conv.batch, a.Wo);
+}
+
 hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows, int force_shape, const int32_t* row_ptr,
                        const int32_t* col_idx, const uint16_t* vals, const uint32_t* idxw, const uint16_t* X,
                        const crisp_conv_desc* conv, int64_t Ncol, int64_t ldx, void* Y, int64_t ldy, int y_dtype,
@@ -465,21 +497,7 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
         // implicit lowering: X is the activation itself
         a.act = X;
         a.X = nullptr;
-        a.C = conv->C; a.H = conv->H; a.W = conv->W; a.kw = conv->kw; a.pad = conv->pad; a.stride = conv->stride;
-        a.Ho = (conv->H + 2 * conv->pad - conv->kh) / conv->stride + 1;
-        a.Wo = (conv->W + 2 * conv->pad - conv->kw) / conv->stride + 1;
-        // neighbours in a row from one dword when that is possible, else column by column
-        a.conv_mode = (conv->stride == 1 && (a.Wo & 1) == 0 && conv->W >= 2) ? 1 : 2;
-        if (conv->kh == 1 && conv->kw == 1 && conv->stride == 2 && conv->pad == 0 && (conv->W & 1) == 0 && (a.Wo & 1) == 0)
-            a.conv_mode = 4;                       // strided 1x1: both columns from one 8-byte piece of the input row
-        if (conv->C % g.B != 0) a.conv_mode = 3;   // block columns span filter taps: every K-row on its own
-        a.plane = (int64_t)conv->batch * conv->H * conv->W;
-        a.act_bytes = a.conv_mode == 3 ? (uint32_t)((int64_t)conv->C * a.plane * 2) : 0u;
-        a.inv_C = 1.0f / (float)conv->C;
-        a.inv_cpb = conv->C >= g.B ? 1.0f / (float)(conv->C / g.B) : 1.0f;
-        a.inv_kw = 1.0f / (float)conv->kw;
-        a.inv_Wo = 1.0 / a.Wo;
-        a.inv_Ho = 1.0 / a.Ho;
+        fill_conv_args(a, g, *conv);
     }
     if (g.B == 16) return launch_b16(a, st);
     // convolution with the input patch staged in LDS (forced shape 12)

@@ -20,7 +20,7 @@ def declared_functions():
 
 def test_library_exports_every_declared_symbol():
     names = declared_functions()
-    assert names == ["crisp_conv_spmm", "crisp_conv_spmm_ep", "crisp_global_budget", "crisp_im2col", "crisp_maxpool", "crisp_pack", "crisp_pack_sizes", "crisp_select_mask",
+    assert names == ["crisp_conv_forward", "crisp_conv_plan", "crisp_conv_spmm", "crisp_conv_spmm_ep", "crisp_global_budget", "crisp_im2col", "crisp_maxpool", "crisp_pack", "crisp_pack_sizes", "crisp_select_mask",
                      "crisp_select_pack", "crisp_select_pack_batch", "crisp_spmm", "crisp_spmm_ep", "crisp_spmm_timed", "crisp_status_str"]
     L = crisp.lib()
     for n in names:
@@ -170,3 +170,18 @@ def test_lowering_choice_on_resnet50_shapes():
     assert pick(cs(3, 224, 224, 8, 7, 7, 2, 3), 64, 0.5) == "fused"           # first layer: one block-row
     assert crisp.conv_needs_scratch(cs(512, 14, 14, 8, 3, 3, 2, 1), 64, 2, 4, 512, 0.70)
     assert not crisp.conv_needs_scratch(cs(256, 14, 14, 8, 3, 3, 1, 1), 64, 2, 4, 256, 0.9)
+    # scratch size of the materialised path: K x round_up(Ncol, 8) bf16; argument checks on the host
+    cv = cs(512, 14, 14, 3, 3, 3, 2, 1)
+    path, nbytes = crisp.conv_plan(crisp.layer_desc(512, 9 * 512, 2, 4, 64, 0.7), cv)
+    assert path == "im2col" and nbytes == 9 * 512 * ((3 * 49 + 7) // 8 * 8) * 2
+    assert crisp.conv_plan(crisp.layer_desc(256, 9 * 256, 2, 4, 64, 0.9), cs(256, 14, 14, 8, 3, 3, 1, 1)) == ("fused", 0)
+    with pytest.raises(crisp.CrispError) as e:
+        crisp.conv_plan(crisp.layer_desc(256, 9 * 128, 2, 4, 64, 0.9), cs(256, 14, 14, 8, 3, 3, 1, 1))   # K mismatch
+    assert e.value.status == crisp.ESHAPE
+    L = crisp.lib()
+    d = crisp.layer_desc(512, 9 * 512, 2, 4, 64, 0.7)
+    conv = crisp.conv_desc_of(cv)
+    fake = 0x1000
+    fwd = lambda scratch, nb: L.crisp_conv_forward(C.byref(d), C.byref(conv), fake, fake, fake, fake, fake, fake, 152, 0, None,
+                                                   scratch, nb, None, None)
+    assert fwd(None, 0) == crisp.EBUFSIZE and fwd(fake, nbytes - 2) == crisp.EBUFSIZE

@@ -454,6 +454,36 @@ def test_conv_spmm_uneven_block_rows(case):
             check_product(Yh[:, :Ncol], Yref, Aref, yd, "uneven %s shape %s" % (case, shape))
 
 
+def test_conv_forward_takes_each_of_its_three_ways():
+    """crisp_conv_forward: the activation as X, the fused lowering, a materialised X (also when a fused plan
+    meets a Y row stride beyond the fused kernels' range), and the error for a missing scratch buffer."""
+    for (cvt, S, dens, expect, ldy_extra) in (((64, 6, 8, 2, 1, 1, 1, 0), 128, 0.5, "none", 0),
+                                              ((64, 8, 8, 2, 3, 3, 1, 1), 128, 0.5, "fused", 0),
+                                              ((64, 9, 7, 2, 3, 3, 2, 1), 256, 1.0, "im2col", 0),
+                                              ((64, 8, 8, 2, 3, 3, 1, 1), 64, 0.5, "im2col", (1 << 23) + 8)):
+        cv = synth.ConvShape(*cvt)
+        L = synth.LayerSpec("fw", S, cv.K, cv.Ncol, 2, 4, 64, dens, synth.SAL_MAG, 0.05, conv=cv)
+        rng = np.random.default_rng(S + cv.H)
+        W = synth.draw_weight(rng, L)
+        act = synth.draw_relu_normal(rng, (cv.C, cv.batch, cv.H, cv.W))
+        sel = oracle.select(W, None, L.n, L.m, L.B, dens, synth.SAL_MAG)
+        layer, _ = run_select_pack(L, W, None)
+        Yref, Aref = oracle.gemm_masked(W, sel.mask, oracle.im2col(act, cv.kh, cv.kw, cv.stride, cv.pad))
+        planned, nbytes = crisp.conv_plan(layer.desc, cv)
+        assert planned == (expect if not ldy_extra else "fused")
+        ld = (cv.Ncol + 7) // 8 * 8
+        ldy = ldy_extra or ld
+        Y = torch.full((S, ldy), float("nan"), dtype=torch.float32, device="cuda")
+        if expect == "im2col":
+            with pytest.raises(ValueError):
+                crisp.conv_forward(layer, cv, dev(act), Y, ldy, crisp.Y_F32, None)
+        Xs = torch.empty((cv.K, ld), dtype=torch.int16, device="cuda") if expect == "im2col" else None
+        assert crisp.conv_forward(layer, cv, dev(act), Y, ldy, crisp.Y_F32, Xs) == expect
+        torch.cuda.synchronize()
+        check_product(Y[:, : cv.Ncol].cpu().numpy().astype(np.float64), Yref, Aref, crisp.Y_F32, "forward %s" % (cvt,))
+        assert bool(torch.isnan(Y[:, cv.Ncol:]).all())
+
+
 def test_conv_spmm_rejects_what_it_does_not_cover():
     d = crisp.layer_desc(64, 9 * 64, 2, 4, 64, 0.5)
     z = torch.zeros(1 << 16, dtype=torch.int16, device="cuda")
