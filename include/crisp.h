@@ -37,7 +37,8 @@ enum {
     CRISP_OK = 0,
     CRISP_EINVAL = 1,       /* null pointer, n/m/B/density/kind out of range       */
     CRISP_ESHAPE = 2,       /* S, K, Ncol, ld*, conv geometry inconsistent         */
-    CRISP_EBUFSIZE = 3,     /* workspace smaller than crisp_pack_sizes reports     */
+    CRISP_EBUFSIZE = 3,     /* workspace or scratch smaller than crisp_pack_sizes /
+                               crisp_conv_plan report                              */
     CRISP_EALIGN = 4,       /* pointer or leading dimension alignment              */
     CRISP_EUNSUPPORTED = 5, /* valid request this build has no kernel for          */
     CRISP_EDEVICE = 6       /* a HIP launch reported an error                      */
