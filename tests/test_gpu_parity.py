@@ -760,6 +760,40 @@ def test_maximum_convolution_plane():
         torch.cuda.empty_cache()
 
 
+def test_calls_on_two_streams_do_not_disturb_each_other():
+    """The library keeps no state between calls: selection, packing and products of two layers enqueued
+    alternately on two streams give the bytes each layer gives on its own."""
+    cases = [synth.small_cases()[1], synth.small_cases()[3]]
+    work = []
+    for i, L in enumerate(cases):
+        W, G, X = synth.draw_small(L, 90 + i)
+        ldx = (L.Ncol + 7) // 8 * 8
+        Xp = np.zeros((L.K, ldx), dtype=np.uint16)
+        Xp[:, : L.Ncol] = X
+        layer, out = run_select_pack(L, W, G)
+        Yalone = run_spmm(layer, dev(Xp), L.Ncol, ldx, crisp.Y_F32, L.S, ldy=ldx)
+        fresh = crisp.alloc_layer(desc_of(L))
+        work.append(dict(L=L, W=dev(W), G=dev(G) if G is not None else None, X=dev(Xp), ldx=ldx, layer=fresh, alone=(out, Yalone),
+                         Y=torch.zeros((L.S, ldx), dtype=torch.float32, device="cuda"), stream=torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    for it in range(10):
+        for w in work:
+            with torch.cuda.stream(w["stream"]):
+                for t in (w["layer"].vals, w["layer"].idx_words, w["layer"].col_idx):
+                    t.fill_(-1)
+                crisp.prune_and_pack(w["layer"], w["W"], w["G"])
+                crisp.crisp_spmm(w["layer"].desc, w["layer"].row_ptr, w["layer"].col_idx, w["layer"].vals, w["layer"].idx_words,
+                                 w["X"], w["L"].Ncol, w["ldx"], w["Y"], w["ldx"])
+    torch.cuda.synchronize()
+    for w in work:
+        out, Yalone = w["alone"]
+        sz = w["layer"].sizes
+        assert (host(w["layer"].col_idx, np.int32)[: sz.nk] == out["col_idx"]).all()
+        assert (host(w["layer"].vals, np.uint16)[: sz.vals_elems] == out["vals"].reshape(-1)).all()
+        assert (host(w["layer"].idx_words, np.uint32)[: sz.idx_words] == out["idxw"].reshape(-1)).all()
+        assert (w["Y"].cpu().numpy().astype(np.float64)[:, : w["L"].Ncol] == Yalone).all()
+
+
 def test_determinism():
     L = synth.small_cases()[1]
     W, G, X = synth.draw_small(L, 30)
