@@ -760,6 +760,35 @@ def test_maximum_convolution_plane():
         torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("L", [synth.small_cases()[0], synth.small_cases()[13], synth.b16_cases()[2]], ids=lambda L: L.name)
+def test_block_scores_are_an_optional_output(L):
+    """Without a block_score buffer the scores live in the caller's workspace; masks, block lists and packing
+    stay the same bytes (separate calls and the fused call)."""
+    W, G, _ = synth.draw_small(L, 95)
+    sel, vals, idxw, flags = oracle_all(L, W, G)
+    layer = crisp.alloc_layer(desc_of(L))
+    sz = layer.sizes
+    dW, dG = dev(W), dev(G) if G is not None else None
+    for fused in (False, True):
+        for t in (layer.nm_mask, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, layer.flags):
+            t.fill_(-1)
+        if fused:
+            ws = torch.empty(max(16, sz.select_pack_ws_bytes), dtype=torch.uint8, device="cuda")
+            crisp.crisp_select_pack(layer.desc, dW, dG, layer.nm_mask, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words,
+                                    layer.flags, ws, ws.numel(), block_score=None)
+        else:
+            ws = torch.empty(max(16, sz.select_ws_bytes), dtype=torch.uint8, device="cuda")
+            crisp.crisp_select_mask(layer.desc, dW, dG, layer.nm_mask, layer.row_ptr, layer.col_idx, None, ws, ws.numel())
+            crisp.crisp_pack(layer.desc, dW, layer.nm_mask, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, layer.flags)
+        torch.cuda.synchronize()
+        assert (host(layer.nm_mask, np.uint32)[: sz.mask_words].reshape(L.S, sz.mask_words_per_row) == sel.nm_bits).all()
+        assert (host(layer.row_ptr, np.int32) == sel.row_ptr).all()
+        assert (host(layer.col_idx, np.int32)[: int(sel.row_ptr[-1])] == sel.col_idx).all()
+        assert (host(layer.vals, np.uint16)[: vals.size] == vals.reshape(-1)).all()
+        assert (host(layer.idx_words, np.uint32)[: idxw.size] == idxw.reshape(-1)).all()
+        assert host(layer.flags, np.int32)[0] == flags[0]
+
+
 def test_calls_on_two_streams_do_not_disturb_each_other():
     """The library keeps no state between calls: selection, packing and products of two layers enqueued
     alternately on two streams give the bytes each layer gives on its own."""
