@@ -141,3 +141,33 @@ def test_resnet50_chained_forward_batch8():
     assert len(seen) == 54 and out.shape == (2048, 8 * 7 * 7)
     final = synth.bf16_bits_to_f32(host(out, np.uint16))
     assert np.isfinite(final).all() and (final >= 0).all() and final.max() > 0
+
+
+def test_resnet50_global_budget():
+    """One overall sparsity target for the whole network (Alg. 1 lines 6-9): block scores of all 53 layers
+    from the device, kept blocks per row and reached sparsity equal to the oracle's, bit for bit."""
+    wl = synth.config(5, batch=8)
+    layers, Ws, Gs, shapes, scores_h = [], [], [], [], []
+    for li, L in enumerate(wl.layers):
+        t = synth.draw_layer(wl, li, with_x=False)
+        sel = oracle.select(t["W"], t["G"], L.n, L.m, L.B, 1.0, L.sal_kind)
+        scores_h.append(sel.score)
+        shapes.append((L.S, L.K, L.n, L.m, L.B))
+        layers.append(crisp.alloc_layer(crisp.layer_desc(L.S, L.K, L.n, L.m, L.B, 1.0, L.sal_kind)))
+        Ws.append(dev(t["W"]))
+        Gs.append(dev(t["G"]))
+    crisp.crisp_select_pack_batch(*crisp.make_batch(layers, Ws, Gs))
+    torch.cuda.synchronize()
+    for layer, sc in zip(layers, scores_h):
+        assert (host(layer.score, np.float64).reshape(sc.shape).view(np.uint64) == sc.view(np.uint64)).all()
+    ws = torch.empty(sum(s.size for s in scores_h), dtype=torch.float64, device="cuda")
+    k_dev = torch.zeros(len(layers), dtype=torch.int32, device="cuda")
+    ach = torch.zeros(1, dtype=torch.float64, device="cuda")
+    for target in (0.75, 0.9, 0.95):
+        crisp.crisp_global_budget([l.desc for l in layers], [l.score for l in layers], target, k_dev, ach, ws, ws.numel() * 8)
+        torch.cuda.synchronize()
+        k_ref, a_ref = oracle.global_budget(shapes, scores_h, target)
+        assert k_dev.cpu().tolist() == k_ref, target
+        assert ach.cpu().numpy().view(np.uint64)[0] == np.array([a_ref]).view(np.uint64)[0], target
+        assert a_ref >= target and min(k_ref) >= 1
+        print("target %.2f: reached %.4f, kept blocks per row %s ..." % (target, a_ref, k_ref[:8]), flush=True)
