@@ -571,7 +571,7 @@ TRAFFIC = {
     # (workload, layer, y dtype): bytes per launch = 2.0 * FETCH_SIZE + 1.0 * WRITE_SIZE (KiB -> bytes); the factors come
     # from the same counters on an elementwise add of known size in the same runs (profiles/bench_c*_kernels.txt)
     ("c1", "c1", "bf16"): int((2.0 * 4230.1 + 1568.0) * 1024),
-    ("c2", "c2c", "bf16"): int((2.0 * 1757.5 + 12544.0) * 1024),
+    ("c2", "c2c", "bf16"): int((2.0 * 1762.5 + 12544.0) * 1024),
     ("c3", "c3", "bf16"): int((2.0 * 215781.7 + 50976.0) * 1024),
     ("c4", "c4b", "bf16"): int((2.0 * 37684.9 + 18816.0) * 1024),
 }
