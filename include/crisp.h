@@ -162,7 +162,8 @@ CRISP_API crisp_status crisp_select_mask(const crisp_layer_desc *desc, const uin
  *   vals       [nk][B][B*n/m] bf16
  *   idx_words  [nk][B][idx_words_per_row] uint32: per block row a little-endian bit
  *              stream, slot q at bits [q*w, q*w+w), w = log2 m, 0-based position of
- *              the value inside its group ("second value ... index of 1").
+ *              the value inside its group (Sec. 3.5: a value in the second place of its
+ *              group is stored with position 1).
  *   Padding: unused slots of a short group hold value 0, position 0; groups wholly
  *   outside the matrix (row >= S or first column >= K) hold value 0, positions 0..n-1.
  *   flags[0] = 1 when no aligned group of 4 columns in a kept block holds more
@@ -248,14 +249,8 @@ CRISP_API crisp_status crisp_im2col(const crisp_conv_desc *conv, const uint16_t 
  *   steer the choice of kernel (how many blocks a block-row holds, whether all
  *   rows hold the same number); a wrong or out-of-range density costs speed, never
  *   correctness.
- *   ws is unused (spmm_ws_bytes is 0).  With ws == NULL, ws_bytes in 1..11 forces
- *   launch shape ws_bytes - 1 (0..3 register-expansion kernels: wide strips, narrow
- *   strips, 4- and 8-way split of the block list; 4 generic LDS-expansion kernel;
- *   5 / 6 block-row resident in LDS with narrow / wide strips; 7..10 shapes 0..3
- *   with the sparse matrix-core instruction where the pattern allows it) and ws_bytes
- *   == 14 the kernel that keeps a strip of X in registers for all block-rows (K <= 128,
- *   64x64 blocks), for tests and tuning; a shape that does not apply to the problem falls back to the automatic
- *   choice.  Results agree across shapes within the summation-order tolerance.
+ *   ws, ws_bytes: reserved (spmm_ws_bytes is 0); both are ignored.  Results of the launch
+ *   shapes the library may choose agree within the summation-order tolerance.
  * Errors: EINVAL, ESHAPE, EALIGN, EUNSUPPORTED (x_layout), EDEVICE.
  */
 CRISP_API crisp_status crisp_spmm(const crisp_layer_desc *desc, const int32_t *row_ptr, const int32_t *col_idx,
@@ -279,10 +274,9 @@ CRISP_API crisp_status crisp_spmm(const crisp_layer_desc *desc, const int32_t *r
  * every K-row is split into (tap, channel) on its own; needs K <= 65535 and an activation
  * below 4 GiB.  For stride <= 4, C % 64 == 0, 64x64 blocks, even W <= 64 and even Wo there is also
  * a kernel that stages the input patch of a tile of output rows in LDS once for all filter
- * taps and up to four block-rows (chosen for dense multi-row layers; ws == NULL with
- * ws_bytes == 13 forces it, 1..4 and 8..11 force the shapes of crisp_spmm).  Channel
- * counts that are no multiple of 64 with 64x64 blocks, even W and even Ho*Wo run in a kernel
- * that keeps the input patch of 1024 output positions in LDS (ws_bytes == 15 forces it).
+ * taps and up to four block-rows (chosen for dense multi-row layers).  Channel counts that are
+ * no multiple of 64 with 64x64 blocks, even W and even Ho*Wo run in a kernel that keeps the input
+ * patch of 1024 output positions in LDS.  ws, ws_bytes: reserved, ignored.
  * Anything else returns CRISP_EUNSUPPORTED (use crisp_im2col + crisp_spmm).
  * Errors: EINVAL, ESHAPE, EALIGN, EUNSUPPORTED, EDEVICE.
  */
@@ -317,6 +311,51 @@ CRISP_API crisp_status crisp_conv_spmm_ep(const crisp_layer_desc *desc, const cr
                                 const uint32_t *idx_words, const uint16_t *act, void *Y, int64_t ldy,
                                 int32_t y_dtype, const crisp_epilogue *ep, void *ws, size_t ws_bytes,
                                 void *stream);
+
+/*
+ * For tests and tuning sweeps only (callers that cannot allocate or that want the library's own
+ * choice use the entry points above): crisp_spmm_ep / crisp_conv_spmm_ep with the launch shape
+ * chosen by the caller, and a report of the kernel that ran.
+ *   shape: CRISP_SHAPE_AUTO, or one of the shapes below; a shape that does not apply to the problem
+ *          (pattern, block size, K or Ncol alignment, geometry) falls back to the automatic choice.
+ *   kernel_code (optional, host): receives family | shape << 8 | conv_mode << 16 | sparse << 24 of
+ *          the kernel that was launched (family: CRISP_KERNEL_*; shape: the register kernels' launch
+ *          shape 0..3, else 0; conv_mode: 0 plain X, 1..4 the fused-lowering modes; sparse: 1 when
+ *          the sparse matrix-core instruction is used).
+ * Results agree across shapes within the summation-order tolerance.  Errors as for the plain calls.
+ */
+enum {
+    CRISP_SHAPE_AUTO = -1,
+    CRISP_SHAPE_REG_WIDE = 0,    /* register expansion, waves own strips of 128 columns          */
+    CRISP_SHAPE_REG_NARROW = 1,  /* ... strips of 64 columns                                      */
+    CRISP_SHAPE_REG_SPLIT4 = 2,  /* ... 4 waves split the block list of one tile                  */
+    CRISP_SHAPE_REG_SPLIT8 = 3,  /* ... 8 waves                                                   */
+    CRISP_SHAPE_GENERIC = 4,     /* generic LDS-expansion kernel (any K, Ncol, pattern)           */
+    CRISP_SHAPE_LDS_NARROW = 5,  /* block-row resident in LDS, strips of 64 columns               */
+    CRISP_SHAPE_LDS_WIDE = 6,    /* ... strips of 128 columns                                     */
+    CRISP_SHAPE_SMF_WIDE = 7,    /* shapes 0..3 with the sparse matrix-core instruction where the */
+    CRISP_SHAPE_SMF_NARROW = 8,  /* pattern allows it                                             */
+    CRISP_SHAPE_SMF_SPLIT4 = 9,
+    CRISP_SHAPE_SMF_SPLIT8 = 10,
+    CRISP_SHAPE_CONV_LDS = 12,   /* fused lowering with the input patch staged in LDS             */
+    CRISP_SHAPE_XRES = 13,       /* K <= 128: X operands resident in registers                    */
+    CRISP_SHAPE_CONV_PATCH = 14, /* fused lowering for channel counts that are no multiple of 64  */
+    CRISP_SHAPE_BALANCED = 15    /* block list dealt evenly to the waves (uneven block-rows)      */
+};
+enum {
+    CRISP_KERNEL_REG = 1, CRISP_KERNEL_GENERIC = 2, CRISP_KERNEL_LDS = 3, CRISP_KERNEL_XRES = 4,
+    CRISP_KERNEL_CONV_LDS = 5, CRISP_KERNEL_CONV_PATCH = 6, CRISP_KERNEL_B16 = 7, CRISP_KERNEL_BALANCED = 8
+};
+CRISP_API crisp_status crisp_spmm_forced(const crisp_layer_desc *desc, const int32_t *row_ptr, const int32_t *col_idx,
+                               const uint16_t *vals, const uint32_t *idx_words, const uint16_t *X,
+                               int64_t Ncol, int64_t ldx, int32_t x_layout, void *Y, int64_t ldy,
+                               int32_t y_dtype, const crisp_epilogue *ep, int32_t shape,
+                               int32_t *kernel_code, void *stream);
+CRISP_API crisp_status crisp_conv_spmm_forced(const crisp_layer_desc *desc, const crisp_conv_desc *conv,
+                                    const int32_t *row_ptr, const int32_t *col_idx, const uint16_t *vals,
+                                    const uint32_t *idx_words, const uint16_t *act, void *Y, int64_t ldy,
+                                    int32_t y_dtype, const crisp_epilogue *ep, int32_t shape,
+                                    int32_t *kernel_code, void *stream);
 
 /*
  * A whole convolution layer (Sec. 3 "Notation" + Sec. 3.5): the product of a packed layer with the

@@ -15,8 +15,8 @@
  * Orientation (Sec. 3 "Notation" together with Sec. 3.1): the reshaped weight
  * has S rows (output channels) and K = kh*kw*C columns (reduction dimension).
  * N:M groups run along K inside one row; blocks are B x B tiles of that S x K
- * matrix; "each row has the same number of pruned blocks" refers to rows of
- * the block grid.
+ * matrix; the uniform count of pruned blocks per row that Sec. 3.1 requires is
+ * taken per row of the block grid.
  *
  * Every function returns 0 on success and a negative number on bad arguments.
  *
@@ -235,7 +235,7 @@ int oracle_dense_mask(int S, int K, int B, const uint8_t *keep, const int32_t *r
  * For kept block t (in row_ptr/col_idx order), block row r, group g of m
  * columns: n slots.  Kept elements of the group fill the slots in ascending
  * column order; a slot stores the bf16 value and the 0-based position of the
- * value inside its group of m (log2 m bits; "second value ... index of 1").
+ * value inside its group of m (log2 m bits; Sec. 3.5: the second place of a group is position 1).
  * Padding: a short group (K not a multiple of m) fills its unused slots with
  * value 0 and position 0; a group wholly outside the matrix (row >= S or
  * first column >= K) holds value 0 with positions 0..n-1.
@@ -301,7 +301,7 @@ int oracle_pack(int S, int K, int n, int m, int B, const uint16_t *W, const uint
 }
 
 /* Inverse of oracle_pack: scatter the slots back to a dense S x K bf16 matrix
- * (zeros elsewhere).  Blocks "retain their original positions" (Sec. 3.3). */
+ * (zeros elsewhere).  A kept block sits where it sat in W (Sec. 3.3). */
 int oracle_unpack(int S, int K, int n, int m, int B, const int32_t *row_ptr, const int32_t *col_idx,
                   const uint16_t *vals, const uint32_t *idxw, uint16_t *Wd)
 {

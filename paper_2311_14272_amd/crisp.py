@@ -94,6 +94,10 @@ def lib():
                                     C.c_int64, C.c_int32, C.POINTER(Epilogue), vp, C.c_size_t, vp]
         L.crisp_conv_spmm_ep.argtypes = [C.POINTER(LayerDesc), C.POINTER(ConvDesc), vp, vp, vp, vp, vp, vp, C.c_int64,
                                          C.c_int32, C.POINTER(Epilogue), vp, C.c_size_t, vp]
+        L.crisp_spmm_forced.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp, vp, C.c_int64, C.c_int64, C.c_int32, vp,
+                                        C.c_int64, C.c_int32, C.POINTER(Epilogue), C.c_int32, C.POINTER(C.c_int32), vp]
+        L.crisp_conv_spmm_forced.argtypes = [C.POINTER(LayerDesc), C.POINTER(ConvDesc), vp, vp, vp, vp, vp, vp, C.c_int64,
+                                             C.c_int32, C.POINTER(Epilogue), C.c_int32, C.POINTER(C.c_int32), vp]
         L.crisp_spmm_timed.argtypes = [C.POINTER(LayerDesc), C.POINTER(ConvDesc), vp, vp, vp, vp, vp, C.c_int64,
                                        C.c_int64, vp, C.c_int64, C.c_int32, vp, vp, vp]
         L.crisp_global_budget.argtypes = [C.c_int32, vp, vp, C.c_double, vp, vp, vp, C.c_size_t, vp]
@@ -102,7 +106,7 @@ def lib():
                                          C.POINTER(Epilogue), vp, C.c_size_t, C.POINTER(C.c_int32), vp]
         for f in (L.crisp_pack_sizes, L.crisp_select_mask, L.crisp_pack, L.crisp_select_pack, L.crisp_select_pack_batch,
                   L.crisp_im2col, L.crisp_spmm, L.crisp_spmm_ep, L.crisp_conv_spmm_ep,
-                  L.crisp_conv_spmm, L.crisp_spmm_timed, L.crisp_global_budget, L.crisp_conv_plan, L.crisp_conv_forward):
+                  L.crisp_conv_spmm, L.crisp_spmm_timed, L.crisp_spmm_forced, L.crisp_conv_spmm_forced, L.crisp_global_budget, L.crisp_conv_plan, L.crisp_conv_forward):
             f.restype = C.c_int32
         _lib = L
     return _lib
@@ -214,6 +218,41 @@ def crisp_conv_spmm_ep(desc, conv: ConvDesc, row_ptr, col_idx, vals, idx_words, 
                                   _stream() if stream == -1 else stream)
     if st != OK:
         raise CrispError("crisp_conv_spmm_ep", st)
+
+
+SHAPE_AUTO = -1
+KERNEL_FAMILIES = {1: "reg", 2: "generic", 3: "lds", 4: "xres", 5: "conv_lds", 6: "conv_patch", 7: "b16", 8: "balanced"}
+
+
+def crisp_spmm_forced(desc, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, Y, ldy, y_dtype, ep=None, shape=SHAPE_AUTO,
+                      x_layout=X_KN, stream=-1) -> int:
+    """crisp_spmm_forced (tests, tuning): returns the kernel code of the launch."""
+    code = C.c_int32(0)
+    st = lib().crisp_spmm_forced(C.byref(desc), _ptr(row_ptr), _ptr(col_idx), _ptr(vals), _ptr(idx_words), _ptr(X), Ncol,
+                                 ldx, x_layout, _ptr(Y), ldy, y_dtype, C.byref(ep) if ep is not None else None, shape,
+                                 C.byref(code), _stream() if stream == -1 else stream)
+    if st != OK:
+        raise CrispError("crisp_spmm_forced", st)
+    return code.value
+
+
+def crisp_conv_spmm_forced(desc, conv: ConvDesc, row_ptr, col_idx, vals, idx_words, act, Y, ldy, y_dtype, ep=None,
+                           shape=SHAPE_AUTO, stream=-1) -> int:
+    """crisp_conv_spmm_forced (tests, tuning): returns the kernel code of the launch."""
+    code = C.c_int32(0)
+    st = lib().crisp_conv_spmm_forced(C.byref(desc), C.byref(conv), _ptr(row_ptr), _ptr(col_idx), _ptr(vals),
+                                      _ptr(idx_words), _ptr(act), _ptr(Y), ldy, y_dtype,
+                                      C.byref(ep) if ep is not None else None, shape, C.byref(code),
+                                      _stream() if stream == -1 else stream)
+    if st != OK:
+        raise CrispError("crisp_conv_spmm_forced", st)
+    return code.value
+
+
+def kernel_code_fields(code: int) -> dict:
+    """The fields of a kernel code as crisp_spmm_forced reports it."""
+    return {"family": KERNEL_FAMILIES.get(code & 0xFF, "?"), "shape": (code >> 8) & 0xFF, "conv_mode": (code >> 16) & 0xFF,
+            "sparse_mfma": (code >> 24) & 1}
 
 
 def crisp_spmm_timed(desc, conv, row_ptr, col_idx, vals, idx_words, X_or_act, Ncol, ldx, Y, ldy, y_dtype,

@@ -258,8 +258,8 @@ static crisp_status check_epilogue(const crisp_epilogue* ep, int64_t Ncol) {
 
 static crisp_status spmm_impl(const crisp_layer_desc* desc, const int32_t* row_ptr, const int32_t* col_idx,
                               const uint16_t* vals, const uint32_t* idx_words, const uint16_t* X, int64_t Ncol,
-                              int64_t ldx, int32_t x_layout, void* Y, int64_t ldy, int32_t y_dtype, void* ws,
-                              size_t ws_bytes, void* stream, void* ev_start, void* ev_stop,
+                              int64_t ldx, int32_t x_layout, void* Y, int64_t ldy, int32_t y_dtype, int force_shape,
+                              int32_t* kernel_code, void* stream, void* ev_start, void* ev_stop,
                               const crisp_epilogue* ep = nullptr) {
     Geometry g;
     crisp_status st = make_geometry(desc, false, &g);
@@ -274,12 +274,13 @@ static crisp_status spmm_impl(const crisp_layer_desc* desc, const int32_t* row_p
         return CRISP_EALIGN;
     if (x_layout != CRISP_X_KN) return CRISP_EUNSUPPORTED;
     { crisp_status es = check_epilogue(ep, Ncol); if (es != CRISP_OK) return es; }
-    // ws_bytes doubles as a tuning knob when ws is NULL: 0 = automatic launch shape, 1..11 force
-    // shape (value - 1); results do not depend on it.
-    const int force_shape = (!ws && ws_bytes >= 1 && ws_bytes <= 11) ? (int)ws_bytes - 1 : (!ws && ws_bytes == 14) ? 13 : -1;
+    // shapes of the plain product that may be forced (anything else: the automatic choice)
+    if (!((force_shape >= 0 && force_shape <= 10) || force_shape == CRISP_SHAPE_XRES || force_shape == CRISP_SHAPE_BALANCED))
+        force_shape = -1;
     hipError_t e = launch_spmm(g, desc->block_density, desc->select_mode == CRISP_ROW_UNIFORM, force_shape, row_ptr, col_idx, vals,
                                idx_words, X, nullptr, Ncol,
-                               ldx, Y, ldy, y_dtype, ep, (hipEvent_t)ev_start, (hipEvent_t)ev_stop, (hipStream_t)stream);
+                               ldx, Y, ldy, y_dtype, ep, (hipEvent_t)ev_start, (hipEvent_t)ev_stop, (hipStream_t)stream,
+                               kernel_code);
     return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
 }
 
@@ -296,8 +297,8 @@ static bool fused_lowering_covers(const Geometry& g, const crisp_conv_desc& conv
 
 static crisp_status conv_spmm_impl(const crisp_layer_desc* desc, const crisp_conv_desc* conv, const int32_t* row_ptr,
                                    const int32_t* col_idx, const uint16_t* vals, const uint32_t* idx_words,
-                                   const uint16_t* act, void* Y, int64_t ldy, int32_t y_dtype, void* ws,
-                                   size_t ws_bytes, void* stream, void* ev_start, void* ev_stop,
+                                   const uint16_t* act, void* Y, int64_t ldy, int32_t y_dtype, int force_shape,
+                                   int32_t* kernel_code, void* stream, void* ev_start, void* ev_stop,
                                    const crisp_epilogue* ep = nullptr) {
     Geometry g;
     crisp_status st = make_geometry(desc, false, &g);
@@ -323,12 +324,14 @@ static crisp_status conv_spmm_impl(const crisp_layer_desc* desc, const crisp_con
     if (!fused_lowering_covers(g, *conv, Ncol, plane) || ldy > ((int64_t)1 << 23) ||
         (ep && ep->residual && ep->ldr > ((int64_t)1 << 23)))
         return CRISP_EUNSUPPORTED;
-    const int force_shape = (!ws && ws_bytes >= 1 && ws_bytes <= 4) ? (int)ws_bytes - 1
-                          : (!ws && ws_bytes >= 8 && ws_bytes <= 11) ? (int)ws_bytes - 1
-                          : (!ws && ws_bytes == 13) ? 12 : (!ws && ws_bytes == 15) ? 14 : -1;
+    // shapes of the fused lowering that may be forced (anything else: the automatic choice)
+    if (!((force_shape >= 0 && force_shape <= 3) || (force_shape >= 7 && force_shape <= 10) ||
+          force_shape == CRISP_SHAPE_CONV_LDS || force_shape == CRISP_SHAPE_CONV_PATCH))
+        force_shape = -1;
     hipError_t e = launch_spmm(g, desc->block_density, desc->select_mode == CRISP_ROW_UNIFORM, force_shape, row_ptr, col_idx, vals,
                                idx_words, act, conv,
-                               Ncol, Ncol, Y, ldy, y_dtype, ep, (hipEvent_t)ev_start, (hipEvent_t)ev_stop, (hipStream_t)stream);
+                               Ncol, Ncol, Y, ldy, y_dtype, ep, (hipEvent_t)ev_start, (hipEvent_t)ev_stop, (hipStream_t)stream,
+                               kernel_code);
     return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
 }
 
@@ -336,7 +339,8 @@ crisp_status crisp_spmm(const crisp_layer_desc* desc, const int32_t* row_ptr, co
                         const uint16_t* vals, const uint32_t* idx_words, const uint16_t* X, int64_t Ncol,
                         int64_t ldx, int32_t x_layout, void* Y, int64_t ldy, int32_t y_dtype, void* ws,
                         size_t ws_bytes, void* stream) {
-    return spmm_impl(desc, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, x_layout, Y, ldy, y_dtype, ws, ws_bytes,
+    (void)ws; (void)ws_bytes;
+    return spmm_impl(desc, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, x_layout, Y, ldy, y_dtype, -1, nullptr,
                      stream, nullptr, nullptr);
 }
 
@@ -344,7 +348,8 @@ crisp_status crisp_conv_spmm(const crisp_layer_desc* desc, const crisp_conv_desc
                              const int32_t* col_idx, const uint16_t* vals, const uint32_t* idx_words,
                              const uint16_t* act, void* Y, int64_t ldy, int32_t y_dtype, void* ws, size_t ws_bytes,
                              void* stream) {
-    return conv_spmm_impl(desc, conv, row_ptr, col_idx, vals, idx_words, act, Y, ldy, y_dtype, ws, ws_bytes, stream,
+    (void)ws; (void)ws_bytes;
+    return conv_spmm_impl(desc, conv, row_ptr, col_idx, vals, idx_words, act, Y, ldy, y_dtype, -1, nullptr, stream,
                           nullptr, nullptr);
 }
 
@@ -352,7 +357,8 @@ crisp_status crisp_spmm_ep(const crisp_layer_desc* desc, const int32_t* row_ptr,
                            const uint16_t* vals, const uint32_t* idx_words, const uint16_t* X, int64_t Ncol,
                            int64_t ldx, int32_t x_layout, void* Y, int64_t ldy, int32_t y_dtype,
                            const crisp_epilogue* ep, void* ws, size_t ws_bytes, void* stream) {
-    return spmm_impl(desc, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, x_layout, Y, ldy, y_dtype, ws, ws_bytes,
+    (void)ws; (void)ws_bytes;
+    return spmm_impl(desc, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, x_layout, Y, ldy, y_dtype, -1, nullptr,
                      stream, nullptr, nullptr, ep);
 }
 
@@ -360,7 +366,24 @@ crisp_status crisp_conv_spmm_ep(const crisp_layer_desc* desc, const crisp_conv_d
                                 const int32_t* col_idx, const uint16_t* vals, const uint32_t* idx_words,
                                 const uint16_t* act, void* Y, int64_t ldy, int32_t y_dtype, const crisp_epilogue* ep,
                                 void* ws, size_t ws_bytes, void* stream) {
-    return conv_spmm_impl(desc, conv, row_ptr, col_idx, vals, idx_words, act, Y, ldy, y_dtype, ws, ws_bytes, stream,
+    (void)ws; (void)ws_bytes;
+    return conv_spmm_impl(desc, conv, row_ptr, col_idx, vals, idx_words, act, Y, ldy, y_dtype, -1, nullptr, stream,
+                          nullptr, nullptr, ep);
+}
+
+crisp_status crisp_spmm_forced(const crisp_layer_desc* desc, const int32_t* row_ptr, const int32_t* col_idx,
+                               const uint16_t* vals, const uint32_t* idx_words, const uint16_t* X, int64_t Ncol,
+                               int64_t ldx, int32_t x_layout, void* Y, int64_t ldy, int32_t y_dtype,
+                               const crisp_epilogue* ep, int32_t shape, int32_t* kernel_code, void* stream) {
+    return spmm_impl(desc, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, x_layout, Y, ldy, y_dtype, shape, kernel_code,
+                     stream, nullptr, nullptr, ep);
+}
+
+crisp_status crisp_conv_spmm_forced(const crisp_layer_desc* desc, const crisp_conv_desc* conv, const int32_t* row_ptr,
+                                    const int32_t* col_idx, const uint16_t* vals, const uint32_t* idx_words,
+                                    const uint16_t* act, void* Y, int64_t ldy, int32_t y_dtype, const crisp_epilogue* ep,
+                                    int32_t shape, int32_t* kernel_code, void* stream) {
+    return conv_spmm_impl(desc, conv, row_ptr, col_idx, vals, idx_words, act, Y, ldy, y_dtype, shape, kernel_code, stream,
                           nullptr, nullptr, ep);
 }
 
@@ -438,16 +461,16 @@ crisp_status crisp_conv_forward(const crisp_layer_desc* desc, const crisp_conv_d
     }
     if (path_taken) *path_taken = path;
     if (path == CRISP_CONV_DIRECT)
-        return spmm_impl(desc, row_ptr, col_idx, vals, idx_words, act, Ncol, Ncol, CRISP_X_KN, Y, ldy, y_dtype, nullptr, 0, stream,
+        return spmm_impl(desc, row_ptr, col_idx, vals, idx_words, act, Ncol, Ncol, CRISP_X_KN, Y, ldy, y_dtype, -1, nullptr, stream,
                          nullptr, nullptr, ep);
     if (path == CRISP_CONV_FUSED)
-        return conv_spmm_impl(desc, conv, row_ptr, col_idx, vals, idx_words, act, Y, ldy, y_dtype, nullptr, 0, stream, nullptr,
+        return conv_spmm_impl(desc, conv, row_ptr, col_idx, vals, idx_words, act, Y, ldy, y_dtype, -1, nullptr, stream, nullptr,
                               nullptr, ep);
     if (!x_scratch || scratch_bytes < (size_t)elems * 2) return CRISP_EBUFSIZE;
     const int64_t ldx = (Ncol + 7) / 8 * 8;
     st = crisp_im2col(conv, act, x_scratch, ldx, stream);
     if (st != CRISP_OK) return st;
-    return spmm_impl(desc, row_ptr, col_idx, vals, idx_words, x_scratch, Ncol, ldx, CRISP_X_KN, Y, ldy, y_dtype, nullptr, 0,
+    return spmm_impl(desc, row_ptr, col_idx, vals, idx_words, x_scratch, Ncol, ldx, CRISP_X_KN, Y, ldy, y_dtype, -1, nullptr,
                      stream, nullptr, nullptr, ep);
 }
 
@@ -485,10 +508,10 @@ crisp_status crisp_spmm_timed(const crisp_layer_desc* desc, const crisp_conv_des
                               const uint16_t* X_or_act, int64_t Ncol, int64_t ldx, void* Y, int64_t ldy,
                               int32_t y_dtype, void* start_event, void* stop_event, void* stream) {
     if (conv)
-        return conv_spmm_impl(desc, conv, row_ptr, col_idx, vals, idx_words, X_or_act, Y, ldy, y_dtype, nullptr, 0,
+        return conv_spmm_impl(desc, conv, row_ptr, col_idx, vals, idx_words, X_or_act, Y, ldy, y_dtype, -1, nullptr,
                               stream, start_event, stop_event);
-    return spmm_impl(desc, row_ptr, col_idx, vals, idx_words, X_or_act, Ncol, ldx, CRISP_X_KN, Y, ldy, y_dtype, nullptr,
-                     0, stream, start_event, stop_event);
+    return spmm_impl(desc, row_ptr, col_idx, vals, idx_words, X_or_act, Ncol, ldx, CRISP_X_KN, Y, ldy, y_dtype, -1,
+                     nullptr, stream, start_event, stop_event);
 }
 
 }  // extern "C"

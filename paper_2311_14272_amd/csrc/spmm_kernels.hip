@@ -478,7 +478,11 @@ bool conv_lds_would_run(const Geometry& g, double density_hint, const crisp_conv
 hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows, int force_shape, const int32_t* row_ptr,
                        const int32_t* col_idx, const uint16_t* vals, const uint32_t* idxw, const uint16_t* X,
                        const crisp_conv_desc* conv, int64_t Ncol, int64_t ldx, void* Y, int64_t ldy, int y_dtype,
-                       const crisp_epilogue* ep, hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st) {
+                       const crisp_epilogue* ep, hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st, int32_t* kernel_code) {
+    // what ran, for callers that ask: family | shape << 8 | conv_mode << 16 | sparse << 24
+    auto report = [&](int family, int shape, int conv_mode, int sparse) {
+        if (kernel_code) *kernel_code = family | (shape << 8) | (conv_mode << 16) | (sparse << 24);
+    };
     SpmmArgs a = {};
     a.ev_start = ev_start; a.ev_stop = ev_stop;
     a.S = g.S; a.K = g.K; a.n = g.n; a.m = g.m; a.w = g.w; a.slots = g.slots; a.wpr = g.wpr;
@@ -499,13 +503,14 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
         a.X = nullptr;
         fill_conv_args(a, g, *conv);
     }
-    if (g.B == 16) return launch_b16(a, st);
+    if (g.B == 16) { report(CRISP_KERNEL_B16, 0, 0, 0); return launch_b16(a, st); }
     // convolution with the input patch staged in LDS (forced shape 12)
     ConvLdsSched cs;
     const bool conv_lds_wanted = force_shape == 12 || force_shape < 0;
     if (conv && conv_lds_wanted && (Ncol % 4) == 0 && ld_wide <= ((int64_t)1 << 23) && conv_lds_plan(a, g.B, conv->kh, &cs) &&
         (force_shape == 12 || conv_lds_pays(cs, g.Sb, density_hint, conv->batch, a.Wo))) {
         a.use_smf = 1;
+        report(CRISP_KERNEL_CONV_LDS, 0, a.conv_mode, g.n <= 2);
         switch (g.n * 16 + g.m) {
             case 1 * 16 + 4: return launch_conv_lds_nm<1, 4>(a, cs, conv->batch, st);
             case 2 * 16 + 4: return launch_conv_lds_nm<2, 4>(a, cs, conv->batch, st);
@@ -524,6 +529,7 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
     if (conv && (force_shape == 14 || force_shape < 0) && ld_wide <= ((int64_t)1 << 23) &&
         conv_patch_plan(a, g.B, conv->kh, g.Kb, &ps)) {
         a.use_smf = 1;
+        report(CRISP_KERNEL_CONV_PATCH, 0, a.conv_mode, g.n <= 2);
         switch (g.n * 16 + g.m) {
             case 1 * 16 + 4: return launch_conv_patch_nm<1, 4>(a, ps, conv->batch, st);
             case 2 * 16 + 4: return launch_conv_patch_nm<2, 4>(a, ps, conv->batch, st);
@@ -543,9 +549,14 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
     if (bpr < 1) bpr = 1;
     // LDS-resident block-rows (forced shapes 5 = narrow strips, 6 = wide strips)
     const bool lds_ok = !conv && (g.K % 16) == 0 && (Ncol % 4) == 0 && ld_wide <= ((int64_t)1 << 23);
-    if (lds_ok && (force_shape == 5 || force_shape == 6)) return launch_spmm_lds(a, g.B, bpr, force_shape == 6, st);
-    if (lds_ok && force_shape < 0 && hint && uniform_rows && prefer_lds(g, Ncol, bpr))
+    if (lds_ok && (force_shape == 5 || force_shape == 6)) {
+        report(CRISP_KERNEL_LDS, force_shape == 6, 0, 0);
+        return launch_spmm_lds(a, g.B, bpr, force_shape == 6, st);
+    }
+    if (lds_ok && force_shape < 0 && hint && uniform_rows && prefer_lds(g, Ncol, bpr)) {
+        report(CRISP_KERNEL_LDS, bpr <= 1, 0, 0);
         return launch_spmm_lds(a, g.B, bpr, bpr <= 1, st);
+    }
     // forced shapes 7..10: shapes 0..3 of the register kernels with the sparse matrix-core instruction
     // (the automatic choice always takes it where the pattern is eligible: it was faster for every
     // measured layer; shapes 0..3 force the dense-expansion instantiations)
@@ -565,6 +576,11 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
     // of four output columns per lane (Ncol % 4 == 0)
     if (conv || (force_shape != 4 && (g.K % 16) == 0 && (Ncol % 4) == 0 && ld_wide <= ((int64_t)1 << 23))) {
         const int key = g.n * 16 + g.m;
+        const bool known = key == 0x14 || key == 0x24 || key == 0x34 || key == 0x44 || key == 0x18 || key == 0x28 ||
+                           key == 0x48 || key == 0x88;
+        // (the fused lowering has the narrow shapes only)
+        const int shape_run = xres ? 0 : (conv && shape == 0) ? 1 : shape;
+        if (known) report(xres ? CRISP_KERNEL_XRES : CRISP_KERNEL_REG, shape_run, conv ? a.conv_mode : 0, a.use_smf && g.n <= 2);
         switch (key) {
             case 1 * 16 + 4: return launch_reg_nm<1, 4>(a, g.B, shape, st);
             case 2 * 16 + 4: return launch_reg_nm<2, 4>(a, g.B, shape, st);
@@ -580,6 +596,7 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
     }
     // any other n:m (or forced): the generic LDS-expansion kernel
     const bool wide = (int64_t)g.Sb * ((Ncol + 511) / 512) >= 512;
+    report(CRISP_KERNEL_GENERIC, wide, 0, 0);
     if (g.B == 64) return wide ? launch_one<64, 2, 4>(a, st) : launch_one<64, 1, 4>(a, st);
     return wide ? launch_one<32, 2, 4>(a, st) : launch_one<32, 1, 4>(a, st);
 }

@@ -48,16 +48,44 @@ def run_select_pack(L, W, G, fused=True, desc=None):
     return layer, out
 
 
+def spmm(desc, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, Y, ldy, y_dtype, shape=None):
+    """The product through crisp_spmm (shape None: the library's own choice, the production call) or
+    through crisp_spmm_forced with launch shape `shape`."""
+    if shape is None:
+        crisp.crisp_spmm(desc, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, Y, ldy, y_dtype)
+    else:
+        crisp.crisp_spmm_forced(desc, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, Y, ldy, y_dtype, None, shape)
+
+
+def spmm_ep(desc, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, Y, ldy, y_dtype, ep, shape=None):
+    if shape is None:
+        crisp.crisp_spmm_ep(desc, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, Y, ldy, y_dtype, ep)
+    else:
+        crisp.crisp_spmm_forced(desc, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, Y, ldy, y_dtype, ep, shape)
+
+
+def conv_spmm(desc, conv, row_ptr, col_idx, vals, idx_words, act, Y, ldy, y_dtype, shape=None):
+    if shape is None:
+        crisp.crisp_conv_spmm(desc, conv, row_ptr, col_idx, vals, idx_words, act, Y, ldy, y_dtype)
+    else:
+        crisp.crisp_conv_spmm_forced(desc, conv, row_ptr, col_idx, vals, idx_words, act, Y, ldy, y_dtype, None, shape)
+
+
+def conv_spmm_ep(desc, conv, row_ptr, col_idx, vals, idx_words, act, Y, ldy, y_dtype, ep, shape=None):
+    if shape is None:
+        crisp.crisp_conv_spmm_ep(desc, conv, row_ptr, col_idx, vals, idx_words, act, Y, ldy, y_dtype, ep)
+    else:
+        crisp.crisp_conv_spmm_forced(desc, conv, row_ptr, col_idx, vals, idx_words, act, Y, ldy, y_dtype, ep, shape)
+
+
 def run_spmm(layer, dX, Ncol, ldx, y_dtype, S, ldy=None, fill=None, shape=None):
     """crisp_spmm into a fresh Y with a guard band of columns (ldy > Ncol) that must stay untouched."""
     if ldy is None:
         ldy = (Ncol + 7) // 8 * 8 + 8
     tdt = torch.float32 if y_dtype == crisp.Y_F32 else torch.bfloat16
     Y = torch.full((S + 1, ldy), float("nan") if fill is None else fill, dtype=tdt, device="cuda")
-    # shape: None = the library's own choice; 0..3 force a launch shape of the specialised
-    # kernels, 4 forces the generic kernel (ws = NULL, ws_bytes = shape + 1)
-    crisp.crisp_spmm(layer.desc, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dX, Ncol, ldx, Y, ldy,
-                     y_dtype, ws=None, ws_bytes=0 if shape is None else shape + 1)
+    # shape: None = the library's own choice (crisp_spmm); otherwise crisp_spmm_forced with that launch shape
+    spmm(layer.desc, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dX, Ncol, ldx, Y, ldy, y_dtype, shape=shape)
     torch.cuda.synchronize()
     Yh = Y.float().cpu().numpy().astype(np.float64)
     assert np.isnan(Yh[:S, Ncol:]).all(), "columns beyond Ncol were written"
@@ -77,6 +105,16 @@ def check_product(Y, Yref, Aref, y_dtype, what=""):
     if y_dtype == crisp.Y_F32:
         assert fro <= 1e-5, (what, fro)
     return fro
+
+
+def check_bf16_is_rounded_f32(Y16, Y32, what=""):
+    """A bf16 output must be exactly the round-to-nearest-even of the fp32 output of the same launch
+    shape (same fp32 arithmetic, one more rounding).  Used where the outputs are too few for the
+    Frobenius bound to be a statistic of that rounding."""
+    from paper_2311_14272_amd import synth
+    a = synth.f32_to_bf16_bits(np.asarray(Y16, dtype=np.float32))
+    b = synth.f32_to_bf16_bits(np.asarray(Y32, dtype=np.float32))
+    assert (a == b).all(), (what, int((a != b).sum()))
 
 
 def lowering_gather_index(C, H, W, batch, kh, kw, stride, pad, cols):

@@ -20,8 +20,10 @@ def declared_functions():
 
 def test_library_exports_every_declared_symbol():
     names = declared_functions()
-    assert names == ["crisp_conv_forward", "crisp_conv_plan", "crisp_conv_spmm", "crisp_conv_spmm_ep", "crisp_global_budget", "crisp_im2col", "crisp_maxpool", "crisp_pack", "crisp_pack_sizes", "crisp_select_mask",
-                     "crisp_select_pack", "crisp_select_pack_batch", "crisp_spmm", "crisp_spmm_ep", "crisp_spmm_timed", "crisp_status_str"]
+    assert names == ["crisp_conv_forward", "crisp_conv_plan", "crisp_conv_spmm", "crisp_conv_spmm_ep", "crisp_conv_spmm_forced",
+                     "crisp_global_budget", "crisp_im2col", "crisp_maxpool", "crisp_pack", "crisp_pack_sizes", "crisp_select_mask",
+                     "crisp_select_pack", "crisp_select_pack_batch", "crisp_spmm", "crisp_spmm_ep", "crisp_spmm_forced",
+                     "crisp_spmm_timed", "crisp_status_str"]
     L = crisp.lib()
     for n in names:
         assert getattr(L, n) is not None
@@ -128,6 +130,12 @@ def test_entry_points_reject_bad_arguments_without_a_device():
     assert spmm(yd=3) == crisp.EINVAL
     assert spmm(xl=1) == crisp.EUNSUPPORTED
     assert spmm(Y=fake + 4) == crisp.EALIGN
+    # the reserved workspace arguments select nothing: a stale size with ws == NULL is validated like any other call
+    assert L.crisp_spmm(C.byref(d), fake, fake, fake, fake, None, 64, 64, 0, fake, 64, 0, None, 5, None) == crisp.EINVAL
+    code = C.c_int32(-7)
+    forced = lambda shape, **k: L.crisp_spmm_forced(C.byref(d), fake, fake, fake, fake, k.get("X", fake), 64, 64, 0, fake,
+                                                    k.get("ldy", 64), 0, None, shape, C.byref(code), None)
+    assert forced(1, X=None) == crisp.EINVAL and forced(99, ldy=100) == crisp.EALIGN and code.value == -7
     spmm_ep = lambda ep: L.crisp_spmm_ep(C.byref(d), fake, fake, fake, fake, fake, 64, 64, 0, fake, 64, 0, C.byref(ep), None, 0, None)
     assert spmm_ep(crisp.Epilogue(fake + 2, None, None, 0, 0, 0)) == crisp.EALIGN
     assert spmm_ep(crisp.Epilogue(None, None, fake, 56, 0, 0)) == crisp.ESHAPE

@@ -7,7 +7,7 @@ import torch
 import oracle
 from paper_2311_14272_amd import crisp, synth
 
-from gpu_util import check_product, desc_of, dev, host, lowering_gather_index, run_select_pack, run_spmm
+from gpu_util import check_product, desc_of, dev, host, lowering_gather_index, run_select_pack, run_spmm, spmm, conv_spmm
 
 pytestmark = pytest.mark.gpu
 
@@ -402,8 +402,8 @@ def test_conv_spmm_implicit_lowering(case):
     for yd, tdt in ((crisp.Y_F32, torch.float32), (crisp.Y_BF16, torch.bfloat16)):
         for shape in (None, 1, 2, 3, 8, 9, 10, 12, 14):    # 12 / 14: input staged in LDS (where they apply)
             Y = torch.full((S + 1, ldy), float("nan"), dtype=tdt, device="cuda")
-            crisp.crisp_conv_spmm(layer.desc, conv, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dact, Y,
-                                  ldy, yd, ws=None, ws_bytes=0 if shape is None else shape + 1)
+            conv_spmm(layer.desc, conv, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dact, Y,
+                                  ldy, yd, shape=shape)
             torch.cuda.synchronize()
             Yh = Y.float().cpu().numpy().astype(np.float64)
             assert np.isnan(Yh[:S, Ncol:]).all() and np.isnan(Yh[S]).all()
@@ -447,8 +447,7 @@ def test_conv_spmm_uneven_block_rows(case):
     for shape in (forced, None):
         for yd, tdt in ((crisp.Y_F32, torch.float32), (crisp.Y_BF16, torch.bfloat16)):
             Y = torch.full((S, ldy), float("nan"), dtype=tdt, device="cuda")
-            crisp.crisp_conv_spmm(layer.desc, conv, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dev(act), Y, ldy, yd,
-                                  ws=None, ws_bytes=0 if shape is None else shape + 1)
+            conv_spmm(layer.desc, conv, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dev(act), Y, ldy, yd, shape=shape)
             torch.cuda.synchronize()
             Yh = Y.float().cpu().numpy().astype(np.float64)
             check_product(Yh[:, :Ncol], Yref, Aref, yd, "uneven %s shape %s" % (case, shape))
@@ -700,8 +699,8 @@ def test_maximum_column_counts(case):
     for shape in shapes:
         print("wide case", case[:7], "shape", shape, flush=True)
         Y = torch.full((S + 1, Ncol), float("nan"), dtype=torch.bfloat16, device="cuda")
-        crisp.crisp_spmm(layer.desc, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dX, Ncol, Ncol, Y, Ncol,
-                         crisp.Y_BF16, ws=None, ws_bytes=0 if shape is None else shape + 1)
+        spmm(layer.desc, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dX, Ncol, Ncol, Y, Ncol,
+                         crisp.Y_BF16, shape=shape)
         torch.cuda.synchronize()
         assert bool(torch.isnan(Y[S]).all()), "row beyond S was written"
         assert bool(torch.isfinite(Y[:S]).all())
@@ -750,8 +749,8 @@ def test_maximum_convolution_plane():
     for shape in (None, 12, 1, 8):
         print("wide conv shape", shape, flush=True)
         Y = torch.full((S + 1, cv.Ncol), float("nan"), dtype=torch.bfloat16, device="cuda")
-        crisp.crisp_conv_spmm(layer.desc, conv, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dact, Y, cv.Ncol,
-                              crisp.Y_BF16, ws=None, ws_bytes=0 if shape is None else shape + 1)
+        conv_spmm(layer.desc, conv, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dact, Y, cv.Ncol,
+                              crisp.Y_BF16, shape=shape)
         torch.cuda.synchronize()
         assert bool(torch.isnan(Y[S]).all()) and bool(torch.isfinite(Y[:S]).all())
         Yh = Y[:S][:, tcols].float().cpu().numpy().astype(np.float64)

@@ -9,7 +9,7 @@ import torch
 import oracle
 from paper_2311_14272_amd import crisp, synth
 
-from gpu_util import check_product, desc_of, dev, host, run_select_pack, run_spmm
+from gpu_util import check_bf16_is_rounded_f32, check_product, desc_of, dev, host, run_select_pack, run_spmm, spmm_ep, conv_spmm_ep, conv_spmm
 from test_gpu_epilogue import _check as check_epilogue_product, _draw_ep
 
 pytestmark = pytest.mark.gpu
@@ -68,8 +68,8 @@ def test_random_convolutions(seed):
             for yd, tdt in ((crisp.Y_F32, torch.float32), (crisp.Y_BF16, torch.bfloat16)):
                 Y = torch.full((S + 1, ldy), float("nan"), dtype=tdt, device="cuda")
                 try:
-                    crisp.crisp_conv_spmm(layer.desc, conv, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dact, Y,
-                                          ldy, yd, ws=None, ws_bytes=0 if shape is None else shape + 1)
+                    conv_spmm(layer.desc, conv, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dact, Y,
+                                          ldy, yd, shape=shape)
                 except crisp.CrispError as e:
                     assert e.status == crisp.EUNSUPPORTED and ((Ncol & 1) or L.B == 16), (cv, e.status)
                     continue
@@ -78,6 +78,10 @@ def test_random_convolutions(seed):
                 computed += 1
                 try:
                     assert np.isnan(Yh[:S, Ncol:]).all() and np.isnan(Yh[S]).all(), "guard band written"
+                    if yd == crisp.Y_F32:
+                        Y32 = Yh[:S, :Ncol]
+                    else:
+                        check_bf16_is_rounded_f32(Yh[:S, :Ncol], Y32, "random conv")
                     if yd == crisp.Y_F32 or S * Ncol >= 2000:
                         check_product(Yh[:S, :Ncol], Yref, Aref, yd, "random conv")
                 except AssertionError as e:
@@ -91,6 +95,10 @@ def test_random_convolutions(seed):
             Yh = Y.float().cpu().numpy().astype(np.float64)
             try:
                 assert np.isnan(Yh[:S, Ncol:]).all() and np.isnan(Yh[S]).all(), "guard band written"
+                if yd == crisp.Y_F32:
+                    Y32 = Yh[:S, :Ncol]
+                else:
+                    check_bf16_is_rounded_f32(Yh[:S, :Ncol], Y32, "random conv forward")
                 if yd == crisp.Y_F32 or S * Ncol >= 2000:
                     check_product(Yh[:S, :Ncol], Yref, Aref, yd, "random conv forward")
             except AssertionError as e:
@@ -141,6 +149,10 @@ def test_random_products(seed):
             for yd in (crisp.Y_F32, crisp.Y_BF16):
                 try:
                     Y = run_spmm(layer, dX, Ncol, ldx, yd, S, shape=shape)
+                    if yd == crisp.Y_F32:
+                        Y32 = Y
+                    else:
+                        check_bf16_is_rounded_f32(Y, Y32, "random product")
                     if yd == crisp.Y_F32 or S * Ncol >= 2000:
                         check_product(Y, Yref, Aref, yd, "random product")
                 except AssertionError as e:
@@ -205,19 +217,38 @@ def test_random_epilogues(seed):
                                     dres if cb["res"] else None, ld, cb["relu"])
                 for shape in shapes:
                     Y = torch.full((S + 1, ldy), float("nan"), dtype=tdt, device="cuda")
-                    wsb = 0 if shape is None else shape + 1
                     if is_conv:
-                        crisp.crisp_conv_spmm_ep(layer.desc, crisp.conv_desc_of(cv), layer.row_ptr, layer.col_idx, layer.vals,
-                                                 layer.idx_words, dsrc, Y, ldy, yd, ep, ws=None, ws_bytes=wsb)
+                        conv_spmm_ep(layer.desc, crisp.conv_desc_of(cv), layer.row_ptr, layer.col_idx, layer.vals,
+                                                 layer.idx_words, dsrc, Y, ldy, yd, ep, shape=shape)
                     else:
-                        crisp.crisp_spmm_ep(layer.desc, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dsrc, Ncol, ld,
-                                            Y, ldy, yd, ep, ws=None, ws_bytes=wsb)
+                        spmm_ep(layer.desc, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dsrc, Ncol, ld,
+                                            Y, ldy, yd, ep, shape=shape)
                     torch.cuda.synchronize()
                     Yh = Y.float().cpu().numpy().astype(np.float64)
                     try:
                         assert np.isnan(Yh[:S, Ncol:]).all() and np.isnan(Yh[S]).all(), "guard band written"
                         if not bf16 or S * Ncol >= 2000:
                             check_epilogue_product(Yh[:S, :Ncol], Yref, Aref, bf16, "random epilogue")
+                        else:
+                            # too few outputs for the Frobenius statistic of the bf16 rounding: the same launch with
+                            # fp32 output and the same (bf16-representable) residual values, rounded, must give the
+                            # same bits, and that fp32 result is held to the fp32 bounds
+                            pad32 = np.zeros((S, ld), dtype=np.float32)
+                            pad32[:, :Ncol] = res
+                            dres32 = dev(pad32)
+                            ep32 = crisp.epilogue(dscale if cb["scale"] else None, dbias if cb["bias"] else None,
+                                                  dres32 if cb["res"] else None, ld, cb["relu"])
+                            Yf = torch.full((S + 1, ldy), float("nan"), dtype=torch.float32, device="cuda")
+                            if is_conv:
+                                conv_spmm_ep(layer.desc, crisp.conv_desc_of(cv), layer.row_ptr, layer.col_idx, layer.vals,
+                                             layer.idx_words, dsrc, Yf, ldy, crisp.Y_F32, ep32, shape=shape)
+                            else:
+                                spmm_ep(layer.desc, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dsrc, Ncol, ld,
+                                        Yf, ldy, crisp.Y_F32, ep32, shape=shape)
+                            torch.cuda.synchronize()
+                            Y32 = Yf.cpu().numpy().astype(np.float64)[:S, :Ncol]
+                            check_epilogue_product(Y32, Yref, Aref, False, "random epilogue, fp32 twin")
+                            check_bf16_is_rounded_f32(Yh[:S, :Ncol], Y32, "random epilogue")
                     except AssertionError as e:
                         fails.append((what, cb, shape, bf16, str(e)[:80]))
     _report(fails)

@@ -75,13 +75,13 @@ def test_resnet50_batch256_sampled_columns():
 
 
 def _bf16_check(Y, Yref, Aref, what):
-    """bf16 outputs with added terms: products within 1e-2 of |W|.|X| (scaled), plus the final
-    rounding (unit roundoff 2^-8) of a value that may exceed that bound."""
+    """bf16 outputs with added terms: the stated 2e-3 in the Frobenius norm; element-wise the product's
+    1e-2 |W|.|X| (scaled) plus the final rounding, unit roundoff 2^-8, of a value within that of Y*."""
     assert np.isfinite(Y).all(), what
     err = np.abs(Y - Yref)
     fro = np.linalg.norm(Y - Yref) / max(np.linalg.norm(Yref), 1e-300)
-    assert fro <= 3e-3, (what, fro)
-    bound = 1e-2 * Aref + 4e-3 * np.abs(Yref) + 1e-30
+    assert fro <= 2e-3, (what, fro)
+    bound = 1e-2 * Aref + 2.0 ** -8 * (np.abs(Yref) + 1e-2 * Aref) + 1e-30
     assert (err <= bound).all(), (what, float((err - bound).max()))
 
 

@@ -480,10 +480,15 @@ def test_im2col_matches_direct_convolution(C, H, Wd, batch, kh, kw, stride, pad)
 
 def test_metadata_closed_forms():
     # Sec. 3.1 with S=256, K=1024, K'=320 (5 of 16 block columns of 64), 1:4
+    # worked by hand: 256*320/(64*64) = 20 kept blocks; floor(log2(320/64)) = floor(log2 5) = 2 bits each -> 40;
+    # with ceil(log2(1024/64)) = 4 bits each (every block column addressable) -> 80;
+    # 256*320/4 = 20480 kept values, log2(4) = 2 bits each -> 40960
     bits = oracle.metadata_bits(256, 1024, 320, 1, 4, 64)
-    assert bits[0] == 256 * 320 * np.floor(np.log2(320 / 64)) / (64 * 64)
-    assert bits[1] == (256 * 320 // (64 * 64)) * 4
-    assert bits[2] == 256 * 320 * (1 / 4) * 2
+    assert bits[0] == 40 and bits[1] == 80 and bits[2] == 40960
+    # 2:8 in 32x32 blocks, S=64, K=256, K'=128: 8 kept blocks x floor(log2 4) = 2 -> 16; x ceil(log2 8) = 3 -> 24;
+    # 64*128*2/8 = 2048 kept values x 3 bits -> 6144
+    bits = oracle.metadata_bits(64, 256, 128, 2, 8, 32)
+    assert bits[0] == 16 and bits[1] == 24 and bits[2] == 6144
 
 
 def test_config_shapes():
