@@ -192,6 +192,24 @@ CRISP_API crisp_status crisp_select_pack(const crisp_layer_desc *desc, const uin
                                double *block_score, uint16_t *vals, uint32_t *idx_words,
                                int32_t *flags, void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * crisp_select_pack for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): same arguments, outputs and results, but
+ * the workspace is a device array of CRISP_STATIC_SCRATCH_BYTES built into the library (each GPU the
+ * library runs on holds one until the process ends).  The call allocates nothing, on the host or on
+ * the device; the first call on a device looks the array's address up.  Layers whose
+ * select_pack_ws_bytes exceed CRISP_STATIC_SCRATCH_BYTES are rejected with CRISP_EBUFSIZE (nothing
+ * is enqueued).  All calls on one GPU share the array: calls that may run at the same time there
+ * (different streams, threads) race; calls ordered on one stream are fine.  Nothing in the array
+ * needs clearing between calls: every part that is read has been written by the same call.
+ * Errors: as crisp_select_pack; EDEVICE when the array's address cannot be obtained.
+ */
+#define CRISP_STATIC_SCRATCH_BYTES (8u << 20)
+CRISP_API crisp_status crisp_select_pack_noalloc(const crisp_layer_desc *desc, const uint16_t *W, const float *T_or_G,
+                                       uint32_t *nm_mask, int32_t *row_ptr, int32_t *col_idx,
+                                       double *block_score, uint16_t *vals, uint32_t *idx_words,
+                                       int32_t *flags, void *stream);
+
 /* The buffers of one layer for crisp_select_pack_batch: the arguments of crisp_select_pack. */
 typedef struct {
     const uint16_t *W;

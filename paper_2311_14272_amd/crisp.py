@@ -82,6 +82,7 @@ def lib():
         L.crisp_select_mask.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.crisp_pack.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.crisp_select_pack.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.crisp_select_pack_noalloc.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.crisp_select_pack_batch.argtypes = [C.c_int32, C.POINTER(LayerDesc), C.POINTER(LayerBuffers), vp]
         L.crisp_im2col.argtypes = [C.POINTER(ConvDesc), vp, vp, C.c_int64, vp]
         L.crisp_spmm.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp, vp, C.c_int64, C.c_int64, C.c_int32, vp,
@@ -105,6 +106,7 @@ def lib():
         L.crisp_conv_forward.argtypes = [C.POINTER(LayerDesc), C.POINTER(ConvDesc), vp, vp, vp, vp, vp, vp, C.c_int64, C.c_int32,
                                          C.POINTER(Epilogue), vp, C.c_size_t, C.POINTER(C.c_int32), vp]
         for f in (L.crisp_pack_sizes, L.crisp_select_mask, L.crisp_pack, L.crisp_select_pack, L.crisp_select_pack_batch,
+                  L.crisp_select_pack_noalloc,
                   L.crisp_im2col, L.crisp_spmm, L.crisp_spmm_ep, L.crisp_conv_spmm_ep,
                   L.crisp_conv_spmm, L.crisp_spmm_timed, L.crisp_spmm_forced, L.crisp_conv_spmm_forced, L.crisp_global_budget, L.crisp_conv_plan, L.crisp_conv_forward):
             f.restype = C.c_int32
@@ -162,6 +164,17 @@ def crisp_select_pack(desc, W, T_or_G, nm_mask, row_ptr, col_idx, vals, idx_word
                                  _stream() if stream == -1 else stream)
     if st != OK:
         raise CrispError("crisp_select_pack", st)
+
+
+STATIC_SCRATCH_BYTES = 8 << 20
+
+
+def crisp_select_pack_noalloc(desc, W, T_or_G, nm_mask, row_ptr, col_idx, vals, idx_words, flags, block_score=None, stream=-1):
+    st = lib().crisp_select_pack_noalloc(C.byref(desc), _ptr(W), _ptr(T_or_G), _ptr(nm_mask), _ptr(row_ptr), _ptr(col_idx),
+                                         _ptr(block_score), _ptr(vals), _ptr(idx_words), _ptr(flags),
+                                         _stream() if stream == -1 else stream)
+    if st != OK:
+        raise CrispError("crisp_select_pack_noalloc", st)
 
 
 def crisp_select_pack_batch(descs, buffers, stream=-1):

@@ -1,4 +1,5 @@
 // C ABI of libcrisp: argument validation on the host, size queries, dispatch to the launchers.
+#include <mutex>
 #include <vector>
 
 #include "crisp_internal.h"
@@ -151,15 +152,11 @@ static crisp_status check_select_pack(const crisp_layer_desc* desc, const crisp_
     return CRISP_OK;
 }
 
-crisp_status crisp_select_pack_batch(int32_t n_layers, const crisp_layer_desc* descs, const crisp_layer_buffers* bufs,
-                                     void* stream) {
-    if (n_layers < 1 || n_layers > 4096 || !descs || !bufs) return CRISP_EINVAL;
-    std::vector<Geometry> geo((size_t)n_layers);
-    for (int i = 0; i < n_layers; ++i) {       // everything is checked before anything is enqueued
-        crisp_status st = check_select_pack(&descs[i], &bufs[i], &geo[i]);
-        if (st != CRISP_OK) return st;
-    }
-    std::vector<char> done((size_t)n_layers, 0);
+// Enqueues the fused selection + packing of layers whose arguments have been checked (geo[i] filled by
+// check_select_pack); done: n_layers bytes of scratch.
+static crisp_status select_pack_run(int32_t n_layers, const crisp_layer_desc* descs, const crisp_layer_buffers* bufs,
+                                    const Geometry* geo, char* done, void* stream) {
+    for (int i = 0; i < n_layers; ++i) done[i] = 0;
     hipError_t e = hipSuccess;
     for (int i = 0; i < n_layers && e == hipSuccess; ++i) {
         if (done[i]) continue;
@@ -200,13 +197,74 @@ crisp_status crisp_select_pack_batch(int32_t n_layers, const crisp_layer_desc* d
     return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
 }
 
+crisp_status crisp_select_pack_batch(int32_t n_layers, const crisp_layer_desc* descs, const crisp_layer_buffers* bufs,
+                                     void* stream) {
+    if (n_layers < 1 || n_layers > 4096 || !descs || !bufs) return CRISP_EINVAL;
+    std::vector<Geometry> geo((size_t)n_layers);
+    for (int i = 0; i < n_layers; ++i) {       // everything is checked before anything is enqueued
+        crisp_status st = check_select_pack(&descs[i], &bufs[i], &geo[i]);
+        if (st != CRISP_OK) return st;
+    }
+    std::vector<char> done((size_t)n_layers, 0);
+    return select_pack_run(n_layers, descs, bufs, geo.data(), done.data(), stream);
+}
+
 crisp_status crisp_select_pack(const crisp_layer_desc* desc, const uint16_t* W, const float* T_or_G,
                                uint32_t* nm_mask, int32_t* row_ptr, int32_t* col_idx, double* block_score,
                                uint16_t* vals, uint32_t* idx_words, int32_t* flags, void* ws, size_t ws_bytes,
                                void* stream) {
     if (!desc) return CRISP_EINVAL;
     const crisp_layer_buffers b = {W, T_or_G, nm_mask, row_ptr, col_idx, block_score, vals, idx_words, flags, ws, ws_bytes};
-    return crisp_select_pack_batch(1, desc, &b, stream);
+    Geometry geo;
+    crisp_status st = check_select_pack(desc, &b, &geo);
+    if (st != CRISP_OK) return st;
+    char done = 0;
+    return select_pack_run(1, desc, &b, &geo, &done, stream);
+}
+
+// ---- crisp_select_pack for callers that cannot allocate ------------------------------------------
+// The workspace of crisp_select_pack (block scores + packed form of every block of the grid) lives in
+// a file-scope device array.  In host code the array's name is only a stand-in: its device address is
+// looked up once per device with hipGetSymbolAddress (each GPU holds its own copy of the array at its
+// own address) and that pointer is what the kernels are given.
+static __device__ __align__(256) unsigned char scratch[CRISP_STATIC_SCRATCH_BYTES];
+
+static const int MAX_DEVICES = 64;
+static std::mutex scratch_mutex;
+static void* scratch_ptr[MAX_DEVICES];     // per device, filled on the first call there
+
+static crisp_status static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return CRISP_EDEVICE;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return CRISP_EDEVICE;
+        scratch_ptr[dev] = p;
+    }
+    *out = scratch_ptr[dev];
+    return CRISP_OK;
+}
+
+crisp_status crisp_select_pack_noalloc(const crisp_layer_desc* desc, const uint16_t* W, const float* T_or_G,
+                                       uint32_t* nm_mask, int32_t* row_ptr, int32_t* col_idx, double* block_score,
+                                       uint16_t* vals, uint32_t* idx_words, int32_t* flags, void* stream) {
+    if (!desc) return CRISP_EINVAL;
+    // every argument is checked first, with a stand-in for the workspace (aligned, never dereferenced)
+    crisp_layer_buffers b = {W, T_or_G, nm_mask, row_ptr, col_idx, block_score, vals, idx_words, flags,
+                             reinterpret_cast<void*>(uintptr_t(256)), ~size_t(0)};
+    Geometry geo;
+    crisp_status st = check_select_pack(desc, &b, &geo);
+    if (st != CRISP_OK) return st;
+    const size_t need = ((size_t)geo.Sb * geo.Kb * sizeof(double) + 15) / 16 * 16 + select_pack_stage_bytes(geo);
+    if (need > (size_t)CRISP_STATIC_SCRATCH_BYTES) return CRISP_EBUFSIZE;   // the layer does not fit the built-in scratch
+    void* ws = nullptr;
+    st = static_scratch(&ws);
+    if (st != CRISP_OK) return st;
+    b.ws = ws;
+    b.ws_bytes = CRISP_STATIC_SCRATCH_BYTES;
+    char done = 0;
+    return select_pack_run(1, desc, &b, &geo, &done, stream);
 }
 
 crisp_status crisp_im2col(const crisp_conv_desc* c, const uint16_t* act, uint16_t* X, int64_t ldx, void* stream) {

@@ -22,7 +22,7 @@ def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert names == ["crisp_conv_forward", "crisp_conv_plan", "crisp_conv_spmm", "crisp_conv_spmm_ep", "crisp_conv_spmm_forced",
                      "crisp_global_budget", "crisp_im2col", "crisp_maxpool", "crisp_pack", "crisp_pack_sizes", "crisp_select_mask",
-                     "crisp_select_pack", "crisp_select_pack_batch", "crisp_spmm", "crisp_spmm_ep", "crisp_spmm_forced",
+                     "crisp_select_pack", "crisp_select_pack_batch", "crisp_select_pack_noalloc", "crisp_spmm", "crisp_spmm_ep", "crisp_spmm_forced",
                      "crisp_spmm_timed", "crisp_status_str"]
     L = crisp.lib()
     for n in names:
@@ -110,6 +110,12 @@ def test_entry_points_reject_bad_arguments_without_a_device():
     assert sp(vals=fake + 2) == crisp.EALIGN
     assert sp(ws=None) == crisp.EBUFSIZE
     assert sp(wsb=crisp.crisp_pack_sizes(d).select_pack_ws_bytes - 1) == crisp.EBUFSIZE
+    # the variant with the built-in workspace: same checks, and a layer beyond the built-in array is refused
+    na = lambda **k: L.crisp_select_pack_noalloc(C.byref(k.get("d", d)), k.get("W", fake), None, fake, fake, fake, None,
+                                                 k.get("vals", fake), fake, fake, None)
+    assert na(W=None) == crisp.EINVAL and na(vals=fake + 2) == crisp.EALIGN and na(d=dg) == crisp.EINVAL
+    big = crisp.layer_desc(4096, 4096, 4, 4, 64, 0.5)
+    assert crisp.crisp_pack_sizes(big).select_pack_ws_bytes > crisp.STATIC_SCRATCH_BYTES and na(d=big) == crisp.EBUFSIZE
     # batch: every layer is checked before anything is enqueued
     good = crisp.LayerBuffers(fake, None, fake, fake, fake, None, fake, fake, fake, fake, 1 << 30)
     bad = crisp.LayerBuffers(fake, None, fake, fake, fake, None, None, fake, fake, fake, 1 << 30)
