@@ -1,15 +1,23 @@
 #!/usr/bin/env python3
 """Benchmark of the CRISP hybrid-sparse hot path on one MI355X.
 
-A step is one pass of the whole path over one batch of synthetic input: for every layer of the
-workload crisp_select_mask + crisp_pack (saliency, N:M choice, block scores, block choice,
-packing), crisp_im2col for the layers that are real convolutions, crisp_spmm.  Inputs are
-resident in HBM before the timed region; batches rotate through several independent input sets
-so that consecutive steps do not find their activations in the last-level cache.
+A step is one pass of the whole path over one batch of synthetic input: selection and packing of
+every layer of the workload on the device (saliency, N:M choice, block scores, block choice,
+packing), then for every layer the lowering (fused, none, or crisp_im2col) and the product.  Inputs
+are resident in HBM before the timed region.
 
-Prints one JSON line: effective TFLOP/s counting only non-zero-weight FLOPs (whole step), the
-roofline of the dominant kernel measured with events on the launch stream, and the CPU oracle
-timed on the host cores as a reported baseline.
+Default workload: config 5, the 53 convolutions of ResNet-50 at batch 256 (the largest
+configuration; one layer's inputs and outputs alone exceed the last-level cache, and a pass touches
+17 GB, so every launch finds its inputs in HBM).  The one JSON line carries
+  value / ms_per_step   useful (non-zero weight) TFLOP/s of the whole step, timed over --steps passes;
+  roofline              the product kernel with the largest share of the step: algorithmic bytes per
+                        launch / its average launch duration from HIP event pairs recorded around
+                        its launches inside the timed steps;
+  cpu_baseline          the CPU oracle timed on the host cores on a bounded sample of the workload;
+  layers                per-layer time, useful TFLOP/s, fraction of the HBM / MFMA bound;
+  configs               one row per benchmark configuration 1..5 (1..4 measured after the timed
+                        region by short runs of their own; --no-config-table skips them).
+`--config 1..4` makes one of the small configurations the workload of the line instead.
 """
 from __future__ import annotations
 
@@ -25,61 +33,546 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+METRIC = "effective TFLOP/s (nonzero FLOPs) of hybrid-sparse GEMM + % roofline"
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2: ResNet-50 stage-3 bottleneck; 5: all 53 ResNet-50 convs, layer-wise)")
-    ap.add_argument("--sets", type=int, default=0, help="independent input sets to rotate through (0 = enough for 600 MB)")
+    ap.add_argument("--steps", type=int, default=0, help="timed steps (default: 30 for config 5, 200 for 1..4)")
+    ap.add_argument("--warmup", type=int, default=0, help="untimed steps before (default: 3 for config 5, 20 for 1..4)")
+    ap.add_argument("--config", type=int, default=5,
+                    help="workload 1..5 (default 5: all 53 ResNet-50 convs at batch 256, the largest configuration)")
+    ap.add_argument("--sets", type=int, default=0, help="configs 1..4: independent input sets to rotate through (0 = enough for 600 MB)")
     ap.add_argument("--y-dtype", choices=["bf16", "f32"], default="bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--spmm-only", action="store_true", help="time only the products (selection and packing done once)")
+    ap.add_argument("--no-config-table", action="store_true", help="skip the short runs of the other configurations")
+    ap.add_argument("--spmm-only", action="store_true", help="configs 1..4: time only the products (selection and packing done once)")
     ap.add_argument("--chained", action="store_true",
                     help="config 5: time the chained bf16 forward (epilogues fused, max-pool) instead of layer-wise products")
     ap.add_argument("--per-layer-prune", action="store_true",
                     help="select+pack layer by layer (crisp_select_pack) instead of one crisp_select_pack_batch call")
-    ap.add_argument("--side-streams", action="store_true",
-                    help="issue each layer's select+pack on a side stream ordered by events (slower here: the "
-                         "cross-stream waits cost more than the overlap gains); default is one stream")
     ap.add_argument("--explicit-im2col", action="store_true",
-                    help="materialise X with crisp_im2col for conv layers instead of the fused crisp_conv_spmm")
+                    help="configs 1..4: materialise X with crisp_im2col for conv layers instead of the fused crisp_conv_spmm")
     ap.add_argument("--sweep", action="store_true",
                     help="block size x N:M sweep of the paper (B in 16/32/64, N in 1/2/3 of 4) on the layers of "
                          "the chosen workload: product time per setting, one JSON line")
-    ap.add_argument("--graph", action="store_true",
-                    help="also time the step replayed from HIP graphs (one per input set) and check a replay against the eager step")
+    ap.add_argument("--layer", default=None,
+                    help="only the product of this layer of the chosen workload (e.g. --config 5 --layer s4b0.a), launched "
+                         "--steps times over rotating inputs that do not fit the last-level cache: isolated cold launches "
+                         "for profiler counters")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 512 MiB device copy a few times (known traffic, for scaling profiler counters)")
     return ap.parse_args()
 
 
-class LayerState:
-    pass
+# HBM bytes per launch of dominant kernels from rocprofv3 --pmc runs (FETCH_SIZE and WRITE_SIZE, each scaled by what the
+# same counter reads for an elementwise pass of known size): key = (workload, kernel id as this script prints it),
+# value = (bytes per launch, file under profiles/ that holds the counter rows).  A kernel without an entry reports null.
+TRAFFIC = {}
 
 
-def resnet50_pass(args):
-    """Config 5, layer-wise: for each of the 53 convolutions select+pack on the device, then the
-    product on a fresh ReLU(N(0,1)) input of the layer's true shape (batch 256, 224x224).  One
-    layer is resident at a time; a "step" is the sum over the layers."""
+# ------------------------------------------------------------------------------------------------
+# bookkeeping shared by all workloads
+# ------------------------------------------------------------------------------------------------
+def kernel_id(code: int, L) -> str:
+    """Readable name of the kernel instantiation a product launch ran (from the library's report)."""
+    from paper_2311_14272_amd import crisp
+    f = crisp.kernel_code_fields(code)
+    return "%s %d:%d B%d shape%d conv%d %s" % (f["family"], L.n, L.m, L.B, f["shape"], f["conv_mode"],
+                                                "sparse-mfma" if f["sparse_mfma"] else "dense-mfma")
+
+
+def mask_stats(L, dl):
+    """Kept weights, block columns in use and packed bytes of a pruned layer, from the device output."""
+    sz = dl.sizes
+    row_ptr = dl.row_ptr.cpu().numpy()
+    col_idx = dl.col_idx.cpu().numpy()[: sz.nk]
+    if L.S % L.B == 0 and L.K % L.B == 0 and L.K % L.m == 0:
+        ones = sz.nk * L.B * sz.slots_per_row
+    else:                                   # ragged layer: count from the device mask
+        bits = dl.nm_mask.cpu().numpy().view(np.uint32)[: sz.mask_words].reshape(L.S, sz.mask_words_per_row)
+        keep = np.unpackbits(bits.view(np.uint8), axis=1, bitorder="little")[:, : L.K]
+        ones = sum(int(keep[bi * L.B:(bi + 1) * L.B, bj * L.B:(bj + 1) * L.B].sum())
+                   for bi in range(sz.Sb) for bj in col_idx[row_ptr[bi]:row_ptr[bi + 1]])
+    used_cols = np.unique(col_idx)
+    kept_vals = sz.nk * L.B * sz.slots_per_row
+    w_bytes = kept_vals * 2 + sz.idx_words * 4 + sz.nk * 4 + (sz.Sb + 1) * 4
+    return ones, used_cols, w_bytes, kept_vals
+
+
+def algorithmic_bytes(L, used_cols, w_bytes, ybytes):
+    """Bytes a launch has to move: the activations the kept blocks need (rows of X of block columns kept by
+    at least one block-row; for a real convolution the input elements those rows come from, each once),
+    the output, the packed weights."""
+    cv = L.conv
+    lowered = cv is not None and (cv.kh > 1 or cv.kw > 1 or cv.stride > 1)
+    if lowered:
+        chans = set()
+        for bj in used_cols:
+            for k in range(int(bj) * L.B, min(L.K, (int(bj) + 1) * L.B)):
+                chans.add(k % cv.C)
+        rows = cv.H if cv.kh >= cv.stride else min(cv.H, cv.Ho * cv.kh)
+        cols = cv.W if cv.kw >= cv.stride else min(cv.W, cv.Wo * cv.kw)
+        x_bytes = 2 * len(chans) * cv.batch * rows * cols
+    else:
+        k_used = int(sum(min(L.K, (int(bj) + 1) * L.B) - int(bj) * L.B for bj in used_cols))
+        x_bytes = 2 * k_used * L.Ncol
+    return x_bytes + ybytes * L.S * L.Ncol + w_bytes
+
+
+def useful_ceiling(L) -> float:
+    """Upper limit of useful / dense-peak matrix-core throughput of the execution path: the sparse
+    matrix-core instruction (patterns with at most two kept per group) skips half of the zeros, dense
+    expansion multiplies all of them."""
+    return min(1.0, (2.0 if L.n <= 2 else 1.0) * L.n / L.m)
+
+
+def bound_ms(alg_bytes, useful_flop, L):
+    t_hbm = alg_bytes / (HBM_PEAK_GBS * 1e9) * 1e3
+    t_mfma = useful_flop / (useful_ceiling(L) * MFMA_BF16_PEAK_TFLOPS * 1e12) * 1e3
+    return t_hbm, t_mfma
+
+
+def layer_row(L, st, ms, ybytes):
+    t_hbm, t_mfma = bound_ms(st["alg_bytes"], st["useful_flop"], L)
+    return dict(st, forward_ms=round(ms, 5), useful_tflops_forward=round(st["useful_flop"] / (ms * 1e-3) / 1e12, 2),
+                hbm_frac=round(t_hbm / ms, 4), mfma_frac_useful=round(st["useful_flop"] / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                bound="hbm" if t_hbm >= t_mfma else "mfma", bound_frac=round(max(t_hbm, t_mfma) / ms, 4))
+
+
+# ------------------------------------------------------------------------------------------------
+# config 5: ResNet-50, all 53 convolutions, batch 256
+# ------------------------------------------------------------------------------------------------
+def run_resnet50(args):
     import torch
     from paper_2311_14272_amd import crisp, synth
     dev = "cuda"
+    steps = args.steps or 30
+    warmup = args.warmup or 3
     wl = synth.config(5)
     y_dtype = crisp.Y_BF16 if args.y_dtype == "bf16" else crisp.Y_F32
     ybytes = 2 if y_dtype == crisp.Y_BF16 else 4
     ytorch = torch.bfloat16 if y_dtype == crisp.Y_BF16 else torch.float32
     gen = torch.Generator(device=dev)
     gen.manual_seed(wl.seed)
-    reps = max(1, min(args.steps, 5))
-    rows, t_prune, t_fwd, t_im2col, useful, dense = [], 0.0, 0.0, 0.0, 0.0, 0.0
+    nl = len(wl.layers)
 
-    def timed(fn):
-        fn(0)
+    # weights, gradients and pack buffers of all 53 layers stay resident; the model is pruned in one
+    # crisp_select_pack_batch call per step, as Alg. 1 prunes all layers in one shot
+    Wd, Gd, dls, digests = [], [], [], {}
+    for li, L in enumerate(wl.layers):
+        t = synth.draw_layer(wl, li, with_x=False)
+        for key in ("W", "G"):
+            digests["%s.%s" % (L.name, key)] = hashlib.sha256(np.ascontiguousarray(t[key]).view(np.uint8)).hexdigest()[:16]
+        Wd.append(torch.from_numpy(t["W"].view(np.int16)).to(dev))
+        Gd.append(torch.from_numpy(t["G"]).to(dev))
+        dls.append(crisp.alloc_layer(crisp.layer_desc(L.S, L.K, L.n, L.m, L.B, L.density, L.sal_kind, L.select_mode), dev))
+    batch = crisp.make_batch(dls, Wd, Gd)
+
+    def prune_all():
+        if args.per_layer_prune:
+            for i in range(nl):
+                crisp.prune_and_pack(dls[i], Wd[i], Gd[i])
+        else:
+            crisp.crisp_select_pack_batch(*batch)
+
+    if args.chained:
+        return run_resnet50_chained(args, wl, dls, prune_all, gen, steps, warmup)
+
+    # every layer's own input (ReLU(N(0,1)) of its true shape) and output stay resident: 17 GB per pass,
+    # so a layer's input is long gone from the 256 MB last-level cache when the next step reads it again
+    acts, Ys = [], []
+    need_x = 1
+    for L in wl.layers:
+        cv = L.conv
+        acts.append(torch.randn((cv.C, cv.batch, cv.H, cv.W), generator=gen, device=dev).clamp_(min=0).to(torch.bfloat16).view(torch.int16))
+        Ys.append(torch.empty((L.S, L.Ncol), dtype=ytorch, device=dev))
+        if crisp.conv_needs_scratch(cv, L.B, L.n, L.m, L.S, L.density):
+            need_x = max(need_x, L.K * ((L.Ncol + 7) // 8 * 8))
+    Xs = torch.empty(need_x, dtype=torch.int16, device=dev)
+    convs = [crisp.conv_desc_of(L.conv) for L in wl.layers]
+
+    def forward(i):
+        return crisp.conv_forward(dls[i], wl.layers[i].conv, acts[i], Ys[i], wl.layers[i].Ncol, y_dtype, Xs)
+
+    def step(pairs=None):
+        prune_all()
+        for i in range(nl):
+            if pairs is not None and i in pairs:
+                pairs[i][0].record()
+                forward(i)
+                pairs[i][1].record()
+            else:
+                forward(i)
+
+    # ---- one untimed pass: masks (for the FLOP and byte counts) and which kernel each layer runs ----
+    prune_all()
+    torch.cuda.synchronize()
+    stats, kids, paths = [], [], []
+    for i, L in enumerate(wl.layers):
+        ones, used_cols, w_bytes, _ = mask_stats(L, dls[i])
+        uf = 2.0 * ones * L.Ncol
+        stats.append(dict(name=L.name, S=L.S, K=L.K, Ncol=L.Ncol, nm="%d:%d" % (L.n, L.m), B=L.B, density=round(L.density, 3),
+                          k_row=dls[i].sizes.k_row, useful_flop=uf, dense_flop=2.0 * L.S * L.K * L.Ncol,
+                          alg_bytes=algorithmic_bytes(L, used_cols, w_bytes, ybytes)))
+        path = crisp.conv_plan(dls[i].desc, L.conv)[0]
+        d = dls[i]
+        if path == "fused":
+            code = crisp.crisp_conv_spmm_forced(d.desc, convs[i], d.row_ptr, d.col_idx, d.vals, d.idx_words, acts[i], Ys[i], L.Ncol, y_dtype)
+        else:
+            X, ldx = acts[i], L.Ncol
+            if path == "im2col":
+                ldx = (L.Ncol + 7) // 8 * 8
+                crisp.crisp_im2col(convs[i], acts[i], Xs, ldx)
+                X = Xs
+            code = crisp.crisp_spmm_forced(d.desc, d.row_ptr, d.col_idx, d.vals, d.idx_words, X, L.Ncol, ldx, Ys[i], L.Ncol, y_dtype)
+        kids.append(kernel_id(code, L))
+        paths.append(path)
+    torch.cuda.synchronize()
+    useful = sum(s["useful_flop"] for s in stats)
+    dense = sum(s["dense_flop"] for s in stats)
+    if args.copy_calibration:
+        copy_calibration()
+
+    def event_pairs(idx):
+        return {i: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for i in idx}
+
+    # ---- warm-up with every layer bracketed: finds the kernel with the largest share of the step ----
+    wsum = np.zeros(nl)
+    for _ in range(warmup):
+        pairs = event_pairs(range(nl))
+        step(pairs)
+        torch.cuda.synchronize()
+        wsum += np.array([pairs[i][0].elapsed_time(pairs[i][1]) for i in range(nl)])
+    share = {}
+    for i in range(nl):
+        if paths[i] != "im2col":                 # (a bracket around a materialised layer also holds the lowering pass)
+            share[kids[i]] = share.get(kids[i], 0.0) + wsum[i]
+    dom_kid = max(share, key=share.get)
+    dom_layers = [i for i in range(nl) if kids[i] == dom_kid and paths[i] != "im2col"]
+
+    # ---- timed region: exactly `steps` passes; only the dominant kernel's launches are bracketed ----
+    all_pairs = [event_pairs(dom_layers) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        step(all_pairs[k])
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+    dom_ms = np.array([[p[i][0].elapsed_time(p[i][1]) for i in dom_layers] for p in all_pairs])   # steps x launches
+    dom_avg_ms = float(dom_ms.mean())
+    dom_bytes = float(np.mean([stats[i]["alg_bytes"] for i in dom_layers]))
+    achieved = dom_bytes / (dom_avg_ms * 1e-3) / 1e9
+
+    # ---- breakdown (untimed extras): a few more passes with every launch bracketed --------------------
+    reps = max(1, min(steps, 5))
+    fsum, isum, psum = np.zeros(nl), np.zeros(nl), 0.0
+    for _ in range(reps):
+        pa, pb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        pa.record()
+        prune_all()
+        pb.record()
+        pairs, ipairs = event_pairs(range(nl)), event_pairs([i for i in range(nl) if paths[i] == "im2col"])
+        for i, L in enumerate(wl.layers):
+            if paths[i] == "im2col":          # the two launches crisp_conv_forward makes, bracketed one by one
+                ldx = (L.Ncol + 7) // 8 * 8
+                d = dls[i]
+                ipairs[i][0].record()
+                crisp.crisp_im2col(convs[i], acts[i], Xs, ldx)
+                ipairs[i][1].record()
+                pairs[i][0].record()
+                crisp.crisp_spmm(d.desc, d.row_ptr, d.col_idx, d.vals, d.idx_words, Xs, L.Ncol, ldx, Ys[i], L.Ncol, y_dtype)
+                pairs[i][1].record()
+            else:
+                pairs[i][0].record()
+                forward(i)
+                pairs[i][1].record()
+        torch.cuda.synchronize()
+        psum += pa.elapsed_time(pb)
+        fsum += np.array([pairs[i][0].elapsed_time(pairs[i][1]) for i in range(nl)])
+        for i in ipairs:
+            isum[i] += ipairs[i][0].elapsed_time(ipairs[i][1])
+    rows = []
+    for i, L in enumerate(wl.layers):
+        r = layer_row(L, stats[i], (fsum[i] + isum[i]) / reps, ybytes)
+        r.update(lowering=paths[i], kernel=kids[i], im2col_ms=round(isum[i] / reps, 5))
+        rows.append(r)
+    t_fwd = float((fsum.sum() + isum.sum()) / reps)
+    t_bound = sum(max(bound_ms(s["alg_bytes"], s["useful_flop"], L)) for s, L in zip(stats, wl.layers))
+    t_hbm_all = sum(s["alg_bytes"] for s in stats) / (HBM_PEAK_GBS * 1e9) * 1e3
+    traffic = TRAFFIC.get(("c5", dom_kid))
+    out = {"metric": METRIC, "value": round(useful / (ms_per_step * 1e-3) / 1e12, 3), "unit": "TFLOP/s", "n_gpus": 1,
+           "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": "c5: ResNet-50, 53 convs as GEMMs, batch 256, 224x224, layer-wise inputs (every layer reads its own "
+                                  "ReLU(N(0,1)) input of its true shape), B=64, per-layer n:m and block density drawn from the workload seed",
+                      "step": ("select+pack layer by layer (crisp_select_pack)" if args.per_layer_prune else
+                               "select+pack of all layers in one crisp_select_pack_batch call") +
+                              "; then per layer crisp_conv_forward: lowering (fused, im2col or none) and product",
+                      "y_dtype": args.y_dtype, "x_layout": "KN", "resident_input_sets": 1,
+                      "bytes_touched_per_step": int(sum(s["alg_bytes"] for s in stats))},
+           "dense_equivalent_tflops": round(dense / (ms_per_step * 1e-3) / 1e12, 1),
+           "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic[0] if traffic else None,
+                        "traffic_source": traffic[1] if traffic else None,
+                        "kernel": dom_kid, "launches_per_step": len(dom_layers), "layers": [wl.layers[i].name for i in dom_layers],
+                        "share_of_step": round(float(dom_ms.sum(axis=1).mean()) / ms_per_step, 4),
+                        "avg_launch_ms": round(dom_avg_ms, 5), "median_launch_ms": round(float(np.median(dom_ms)), 5),
+                        "algorithmic_bytes_per_launch": int(dom_bytes),
+                        "timing": "HIP event pair around every launch of this kernel in every timed step (raw brackets, "
+                                  "nothing subtracted)",
+                        "mfma_frac_useful": round(sum(stats[i]["useful_flop"] for i in dom_layers) / len(dom_layers) /
+                                                  (dom_avg_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)},
+           "roofline_all_layers": {"hbm_frac_forward": round(t_hbm_all / t_fwd, 4), "bound_frac_forward": round(t_bound / t_fwd, 4),
+                                   "note": "sum over layers of max(algorithmic bytes / 8 TB/s, useful FLOP / (path ceiling x 2.5 PFLOP/s)) "
+                                           "over the summed bracketed launch times of the breakdown passes"},
+           "select_pack_ms": round(psum / reps, 4), "forward_ms": round(t_fwd, 4), "im2col_ms": round(float(isum.sum() / reps), 4),
+           "useful_tflops_forward_only": round(useful / (t_fwd * 1e-3) / 1e12, 2),
+           "dense_equivalent_tflops_forward_only": round(dense / (t_fwd * 1e-3) / 1e12, 1),
+           "layers": rows,
+           "inputs": {"generator": "numpy %s PCG64, seed %d (weights, gradients); torch.Generator(cuda) seed %d (activations)"
+                                   % (np.__version__, wl.seed, wl.seed), "sha256_prefix": digests}}
+    del acts, Ys, Xs
+    torch.cuda.empty_cache()
+    return out, useful
+
+
+def run_resnet50_chained(args, wl, dls, prune_all, gen, steps, warmup):
+    """The network as a chain: every layer's bf16 output is the next layer's input, layer tails (folded-
+    normalisation scale, shortcut, ReLU) fused into the products, one max-pool kernel."""
+    import torch
+    from paper_2311_14272_amd import crisp, resnet
+    dev = "cuda"
+    prune_all()
+    scales = resnet.layer_scales(wl, dls)
+    need = max([L.K * L.Ncol for L in wl.layers if crisp.conv_needs_scratch(L.conv, L.B, L.n, L.m, L.S, L.density)] + [1])
+    xs = torch.empty(need, dtype=torch.int16, device=dev)
+    cv1 = wl.layers[0].conv
+    x = torch.randn((3, cv1.batch, 224, 224), generator=gen, device=dev).to(torch.bfloat16).view(torch.int16)
+    for _ in range(warmup):
+        prune_all()
+        resnet.forward(wl, dls, x, scales, xs)
+    torch.cuda.synchronize()
+    a, b, c = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+    t_prune = t_chain = 0.0
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        a.record()
+        prune_all()
+        b.record()
+        resnet.forward(wl, dls, x, scales, xs)
+        c.record()
+        torch.cuda.synchronize()
+        t_prune += a.elapsed_time(b)
+        t_chain += b.elapsed_time(c)
+    total = (time.perf_counter() - t0) * 1e3 / steps
+    t_prune /= steps
+    t_chain /= steps
+    useful = dense = 0.0
+    for L, dl in zip(wl.layers, dls):
+        useful += 2.0 * mask_stats(L, dl)[0] * L.Ncol
+        dense += 2.0 * L.S * L.K * L.Ncol
+    out = {"metric": METRIC, "value": round(useful / (total * 1e-3) / 1e12, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": steps,
+           "warmup": warmup, "ms_per_step": round(total, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": "c5: ResNet-50, 53 convs as GEMMs, batch 256, 224x224, chained bf16 forward "
+                                  "(scale / shortcut / ReLU epilogues, max-pool), B=64, per-layer n:m and block "
+                                  "density drawn from the workload seed",
+                      "step": "select+pack of all layers, then the chained forward (one synchronisation per step)", "y_dtype": "bf16"},
+           "select_pack_ms": round(t_prune, 3), "forward_ms": round(t_chain, 3),
+           "dense_equivalent_tflops_forward_only": round(dense / (t_chain * 1e-3) / 1e12, 1), "roofline": None}
+    return out, useful
+
+
+def cpu_baseline_resnet50(useful_flop_full):
+    """The CPU oracle as it stands on a bounded sample of config 5: selection and packing of all 53 layers at
+    full size, lowering and the dense masked fp64 product at a small batch (1/256 .. 32/256 of the columns of
+    every layer), the product part scaled to batch 256."""
+    import oracle
+    from paper_2311_14272_amd import synth
+    full = synth.config(5)
+    sels, t_sel = [], 0.0
+    for li, L in enumerate(full.layers):
+        t = synth.draw_layer(full, li, with_x=False)
+        t0 = time.perf_counter()
+        sel = oracle.select(t["W"], t["G"], L.n, L.m, L.B, L.density, L.sal_kind, L.select_mode)
+        oracle.pack(t["W"], sel.keep, L.n, L.m, L.B, sel.row_ptr, sel.col_idx)
+        t_sel += time.perf_counter() - t0
+        sels.append((t["W"], sel.mask))
+
+    def products(b):
+        wl = synth.config(5, batch=b)
+        dt = 0.0
+        for li, L in enumerate(wl.layers):
+            cv = L.conv
+            act = synth.draw_relu_normal(synth.layer_rng(wl, li), (cv.C, cv.batch, cv.H, cv.W))
+            t0 = time.perf_counter()
+            X = oracle.im2col(act, cv.kh, cv.kw, cv.stride, cv.pad)
+            oracle.gemm_masked(sels[li][0], sels[li][1], X, want_abs=False)
+            dt += time.perf_counter() - t0
+        return dt
+
+    t1 = products(1)
+    b = int(max(1, min(32, 12.0 // max(t1, 1e-3))))
+    tb = products(b) if b > 1 else t1
+    dt = t_sel + tb * 256.0 / b
+    return {"value": round(useful_flop_full / dt / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "seconds_scaled_to_full_workload": round(dt, 1), "cpu_seconds_spent": round(t_sel + t1 + (tb if b > 1 else 0.0), 1),
+            "sample": "select+pack of all 53 layers at full size (%.2f s) + lowering and dense masked fp64 product of every "
+                      "layer at batch %d (%.2f s), the product part scaled by 256/%d" % (t_sel, b, tb, b)}
+
+
+# ------------------------------------------------------------------------------------------------
+# configs 1..4: single layers and the three-layer bottleneck
+# ------------------------------------------------------------------------------------------------
+class LayerState:
+    pass
+
+
+def run_small(cid, args, steps, warmup, want_cpu):
+    import torch
+    from paper_2311_14272_amd import crisp, synth
+    dev = "cuda"
+    wl = synth.config(cid)
+    y_dtype = crisp.Y_BF16 if args.y_dtype == "bf16" else crisp.Y_F32
+    ybytes = 2 if y_dtype == crisp.Y_BF16 else 4
+    ytorch = torch.bfloat16 if y_dtype == crisp.Y_BF16 else torch.float32
+
+    def to_dev(a):
+        a = np.ascontiguousarray(a)
+        if a.dtype == np.uint16:
+            a = a.view(np.int16)
+        return torch.from_numpy(a).to(dev)
+
+    host_inputs = [synth.draw_layer(wl, i) for i in range(len(wl.layers))]
+    per_set = 0
+    for L in wl.layers:
+        is_conv = L.conv is not None and (L.conv.kh > 1 or L.conv.kw > 1 or L.conv.stride > 1)
+        per_set += ybytes * L.S * L.Ncol
+        if is_conv:
+            per_set += 2 * L.conv.C * L.conv.batch * L.conv.H * L.conv.W
+        if not is_conv or args.explicit_im2col:
+            per_set += 2 * L.K * L.Ncol
+    # enough independent input sets that a rotation exceeds the 256 MB last-level cache more than twice
+    nsets = args.sets if args.sets > 0 else max(2, min(80, int(600e6 // per_set) + 1))
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(wl.seed)
+    layers = []
+    for i, L in enumerate(wl.layers):
+        st = LayerState()
+        st.L = L
+        st.desc = crisp.layer_desc(L.S, L.K, L.n, L.m, L.B, L.density, L.sal_kind, L.select_mode)
+        st.dl = crisp.alloc_layer(st.desc, dev)
+        st.W = to_dev(host_inputs[i]["W"])
+        st.G = to_dev(host_inputs[i]["G"]) if host_inputs[i]["G"] is not None else None
+        cv = L.conv
+        st.is_conv = cv is not None and (cv.kh > 1 or cv.kw > 1 or cv.stride > 1)
+        st.conv = crisp.conv_desc_of(cv) if st.is_conv else None
+        st.fused = False
+        if st.is_conv and not args.explicit_im2col:
+            Wo = cv.W + 2 * cv.pad - cv.kw + 1
+            st.fused = (cv.stride == 1 and cv.C % L.B == 0 and Wo % 2 == 0 and L.B in (32, 64))
+        st.act, st.X, st.Y = [], [], []
+        for s in range(nsets):
+            if st.is_conv:
+                a = to_dev(host_inputs[i]["act"]) if s == 0 else \
+                    torch.randn((cv.C, cv.batch, cv.H, cv.W), generator=gen, device=dev).clamp_(min=0).to(torch.bfloat16).view(torch.int16)
+                st.act.append(a)
+                st.X.append(None if st.fused else torch.empty((L.K, L.Ncol), dtype=torch.int16, device=dev))
+            else:
+                x = to_dev(host_inputs[i]["X"]) if s == 0 else \
+                    torch.randn((L.K, L.Ncol), generator=gen, device=dev).clamp_(min=0).to(torch.bfloat16).view(torch.int16)
+                st.X.append(x)
+            st.Y.append(torch.empty((L.S, L.Ncol), dtype=ytorch, device=dev))
+        layers.append(st)
+
+    def prune(st):
+        crisp.prune_and_pack(st.dl, st.W, st.G)
+
+    def product(st, s, want_code=False):
+        L, d = st.L, st.dl
+        if want_code:
+            if st.fused:
+                return crisp.crisp_conv_spmm_forced(st.desc, st.conv, d.row_ptr, d.col_idx, d.vals, d.idx_words, st.act[s], st.Y[s], L.Ncol, y_dtype)
+            return crisp.crisp_spmm_forced(st.desc, d.row_ptr, d.col_idx, d.vals, d.idx_words, st.X[s], L.Ncol, L.Ncol, st.Y[s], L.Ncol, y_dtype)
+        if st.fused:
+            crisp.crisp_conv_spmm(st.desc, st.conv, d.row_ptr, d.col_idx, d.vals, d.idx_words, st.act[s], st.Y[s], L.Ncol, y_dtype)
+        else:
+            crisp.crisp_spmm(st.desc, d.row_ptr, d.col_idx, d.vals, d.idx_words, st.X[s], L.Ncol, L.Ncol, st.Y[s], L.Ncol, y_dtype)
+
+    def forward(st, s, events=None):
+        if st.is_conv and not st.fused:
+            crisp.crisp_im2col(st.conv, st.act[s], st.X[s], st.L.Ncol)
+        if events is not None:
+            events[0].record()
+        product(st, s)
+        if events is not None:
+            events[1].record()
+
+    batch = crisp.make_batch([st.dl for st in layers], [st.W for st in layers], [st.G for st in layers])
+
+    def step(k, dom=None, events=None):
+        s = k % nsets
+        # all layers are pruned in one call (the method prunes a model in one shot), then the products
+        if not args.spmm_only and not args.per_layer_prune:
+            crisp.crisp_select_pack_batch(*batch)
+        for i, st in enumerate(layers):
+            if not args.spmm_only and args.per_layer_prune:
+                prune(st)
+            forward(st, s, events if i == dom else None)
+
+    # ---- one untimed pass to learn the mask statistics (metric bookkeeping, from device output) ----
+    for st in layers:
+        prune(st)
+    torch.cuda.synchronize()
+    info = []
+    for st in layers:
+        L, sz = st.L, st.dl.sizes
+        ones, used_cols, w_bytes, kept_vals = mask_stats(L, st.dl)
+        if st.is_conv and not st.fused:     # materialised X is what the product reads
+            k_used = int(sum(min(L.K, (int(bj) + 1) * L.B) - int(bj) * L.B for bj in used_cols))
+            alg_bytes = 2 * k_used * L.Ncol + ybytes * L.S * L.Ncol + w_bytes
+        else:
+            alg_bytes = algorithmic_bytes(L, used_cols, w_bytes, ybytes)
+        # metadata of the packed form next to the closed forms of Sec. 3.1 (K' = k_row*B kept columns per row)
+        Kp = sz.k_row * L.B
+        meta = dict(paper_block_bits=L.S * Kp * int(np.floor(np.log2(max(Kp / L.B, 1)))) // (L.B * L.B),
+                    paper_nm_bits=L.S * Kp * L.n * sz.idx_bits // L.m,
+                    stored_block_bytes=int(sz.nk * 4 + (sz.Sb + 1) * 4), stored_nm_bytes=int(sz.idx_words * 4),
+                    packed_value_bytes=int(kept_vals * 2), dense_bytes=int(L.S * L.K * 2))
+        code = product(st, 0, want_code=True)
+        info.append(dict(name=L.name, S=L.S, K=L.K, Ncol=L.Ncol, metadata=meta, nm="%d:%d" % (L.n, L.m), B=L.B, k_row=sz.k_row,
+                         ones=ones, useful_flop=2.0 * ones * L.Ncol, dense_flop=2.0 * L.S * L.K * L.Ncol,
+                         alg_bytes=alg_bytes, smfmac_ok=int(st.dl.flags.cpu()[0]), kernel=kernel_id(code, L),
+                         lowering=("fused" if st.fused else ("im2col" if st.is_conv else "none"))))
+    useful = sum(x["useful_flop"] for x in info)
+    dense_eq = sum(x["dense_flop"] for x in info)
+    dom = int(np.argmax([x["alg_bytes"] for x in info]))   # dominant kernel: the product with the most traffic
+
+    if args.copy_calibration:
+        copy_calibration()
+
+    # ---- warm-up, then the timed region ----------------------------------------------------
+    for k in range(warmup):
+        step(k)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        step(warmup + k, dom, ev[k])
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+    # the bracket as the events give it: it also holds the dispatch gaps next to the launch (about 3 us
+    # on this machine against the kernel trace), which matters for kernels of a few microseconds
+    dom_raw = [a.elapsed_time(b) for a, b in ev]
+    dom_ms = float(np.mean(dom_raw))
+
+    # ---- per-phase breakdown (untimed extras): back-to-back launches over the rotating input sets ----
+    def timed(fn, reps=50):
         torch.cuda.synchronize()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
@@ -89,109 +582,165 @@ def resnet50_pass(args):
         torch.cuda.synchronize()
         return a.elapsed_time(b) / reps
 
-    # weights, gradients and pack buffers of all 53 layers stay resident (about 0.3 GB); the model is
-    # pruned in one crisp_select_pack_batch call, as Alg. 1 does it
-    Wd, Gd, dls = [], [], []
-    for li, L in enumerate(wl.layers):
-        t = synth.draw_layer(wl, li, with_x=False)
-        Wd.append(torch.from_numpy(t["W"].view(np.int16)).to(dev))
-        Gd.append(torch.from_numpy(t["G"]).to(dev))
-        dls.append(crisp.alloc_layer(crisp.layer_desc(L.S, L.K, L.n, L.m, L.B, L.density, L.sal_kind, L.select_mode), dev))
-    if args.per_layer_prune:
-        per_layer_tp = [timed(lambda r, i=i: crisp.prune_and_pack(dls[i], Wd[i], Gd[i])) for i in range(len(dls))]
-        t_prune = sum(per_layer_tp)
-    else:
-        batch = crisp.make_batch(dls, Wd, Gd)
-        t_prune = timed(lambda r: crisp.crisp_select_pack_batch(*batch))
-        per_layer_tp = [None] * len(dls)
+    for i, st in enumerate(layers):
+        info[i]["prune_pack_ms"] = round(timed(lambda r, st=st: prune(st)), 5)
+        ms = timed(lambda r, st=st: forward(st, r % nsets))
+        info[i] = layer_row(st.L, info[i], ms, ybytes)
 
-    if args.chained:
-        # the network as a chain: every layer's bf16 output is the next layer's input, layer tails
-        # (folded-normalisation scale, shortcut, ReLU) fused into the products, one max-pool kernel
-        from paper_2311_14272_amd import resnet
-        if args.per_layer_prune:
-            crisp.crisp_select_pack_batch(*crisp.make_batch(dls, Wd, Gd))
-        scales = resnet.layer_scales(wl, dls)
-        need = max([L.K * L.Ncol for L in wl.layers if crisp.conv_needs_scratch(L.conv, L.B, L.n, L.m, L.S, L.density)] + [1])
-        xs = torch.empty(need, dtype=torch.int16, device=dev)
-        cv1 = wl.layers[0].conv
-        x = torch.randn((3, cv1.batch, 224, 224), generator=gen, device=dev).to(torch.bfloat16).view(torch.int16)
-        t_chain = timed(lambda r: resnet.forward(wl, dls, x, scales, xs))
-        for L, dl in zip(wl.layers, dls):
-            sz = dl.sizes
-            useful += 2.0 * sz.nk * L.B * sz.slots_per_row * L.Ncol if (L.S % L.B == 0 and L.K % L.B == 0) else 0.0
-            dense += 2.0 * L.S * L.K * L.Ncol
-        total = t_prune + t_chain
-        print(json.dumps({
-            "metric": "effective TFLOP/s (nonzero FLOPs) of hybrid-sparse GEMM + % roofline",
-            "value": round(useful / (total * 1e-3) / 1e12, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": reps, "warmup": 1,
-            "ms_per_step": round(total, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-            "dtype": "bf16", "data": "synthetic",
-            "config": {"workload": "c5: ResNet-50, 53 convs as GEMMs, batch 256, 224x224, chained bf16 forward "
-                                   "(scale / shortcut / ReLU epilogues, max-pool), B=64, per-layer n:m and block "
-                                   "density drawn from the workload seed",
-                       "step": "select+pack of all layers, then the chained forward", "y_dtype": "bf16",
-                       "note": "useful FLOPs exclude the ragged first layer"},
-            "select_pack_ms": round(t_prune, 3), "forward_ms": round(t_chain, 3),
-            "dense_equivalent_tflops_forward_only": round(dense / (t_chain * 1e-3) / 1e12, 1), "roofline": None}))
-        return
+    achieved = info[dom]["alg_bytes"] / (dom_ms * 1e-3) / 1e9
+    traffic = TRAFFIC.get((wl.name, info[dom]["kernel"]))
+    out = {
+        "metric": METRIC, "value": round(useful / (ms_per_step * 1e-3) / 1e12, 4), "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: %s" % (wl.name, ", ".join("%s %dx%dx%d %s B%d k_row %d" % (
+            x["name"], x["S"], x["K"], x["Ncol"], x["nm"], x["B"], x["k_row"]) for x in info)),
+                   "step": (("select+pack of all layers (crisp_select_pack_batch), then " if not args.per_layer_prune else "select+pack (crisp_select_pack)+") if not args.spmm_only else "") + ("im2col+spmm" if args.explicit_im2col else "spmm with the 3x3 layer's lowering fused (crisp_conv_spmm)") + " per layer",
+                   "y_dtype": args.y_dtype, "x_layout": "KN", "input_sets": nsets},
+        "dense_equivalent_tflops": round(dense_eq / (ms_per_step * 1e-3) / 1e12, 3),
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic[0] if traffic else None,
+                     "traffic_source": traffic[1] if traffic else None,
+                     "kernel": "%s (layer %s)" % (info[dom]["kernel"], info[dom]["name"]),
+                     "avg_launch_ms": round(dom_ms, 5), "median_launch_ms": round(float(np.median(dom_raw)), 5),
+                     "timing": "HIP event pair around the launch in every timed step (raw bracket, nothing subtracted)",
+                     "algorithmic_bytes": info[dom]["alg_bytes"],
+                     "forward_ms_back_to_back": info[dom]["forward_ms"]},
+        "layers": info,
+    }
+    digests = {}
+    for h, x in zip(host_inputs, info):
+        for key in ("W", "G", "X", "act"):
+            if h.get(key) is not None:
+                digests["%s.%s" % (x["name"], key)] = hashlib.sha256(np.ascontiguousarray(h[key]).view(np.uint8)).hexdigest()[:16]
+    out["inputs"] = {"generator": "numpy %s PCG64, seed %d" % (np.__version__, wl.seed), "sha256_prefix": digests}
+    if want_cpu:
+        out["cpu_baseline"] = cpu_baseline_small(wl, host_inputs, useful, 10.0 if want_cpu == "full" else 2.5)
+    del layers, host_inputs
+    torch.cuda.empty_cache()
+    return out
 
-    for li, L in enumerate(wl.layers):
-        cv = L.conv
-        W, G, dl = Wd[li], Gd[li], dls[li]
-        # enough independent (input, output) pairs that a layer's working set is not served from the
-        # 256 MB last-level cache across repetitions
-        set_bytes = 2 * cv.C * cv.batch * cv.H * cv.W + ybytes * L.S * L.Ncol
-        nbuf = max(2, min(12, int(600e6 // set_bytes) + 1))
-        acts = [torch.randn((cv.C, cv.batch, cv.H, cv.W), generator=gen, device=dev).clamp_(min=0).to(torch.bfloat16).view(torch.int16)
-                for _ in range(nbuf)]
-        Ys = [torch.empty((L.S, L.Ncol), dtype=ytorch, device=dev) for _ in range(nbuf)]
-        Xs = torch.empty((L.K, L.Ncol), dtype=torch.int16, device=dev) if crisp.conv_needs_scratch(cv, L.B, L.n, L.m, L.S, L.density) else None
 
-        tp = per_layer_tp[li]
-        path = [None]
+def cpu_baseline_small(wl, host_inputs, useful_flop, budget_s):
+    """The CPU oracle as it stands, timed on the host cores on the same workload: whole passes are
+    repeated until about budget_s seconds of CPU work have been spent, and the mean pass is reported."""
+    import oracle
 
-        def fwd(r):
-            path[0] = crisp.conv_forward(dl, cv, acts[r % nbuf], Ys[r % nbuf], L.Ncol, y_dtype, Xs)
-        tf = timed(fwd)
-        ti = 0.0
-        if path[0] == "im2col":      # the lowering pass alone (part of forward_ms)
-            ldx = (L.Ncol + 7) // 8 * 8
-            ti = timed(lambda r: crisp.crisp_im2col(crisp.conv_desc_of(cv), acts[r % nbuf], Xs, ldx))
-        sz = dl.sizes
-        ones = sz.nk * L.B * sz.slots_per_row if (L.S % L.B == 0 and L.K % L.B == 0) else None
-        if ones is None:   # ragged layer (conv1): count from the device mask
-            bits = dl.nm_mask.cpu().numpy().view(np.uint32)[: sz.mask_words].reshape(L.S, sz.mask_words_per_row)
-            keep = np.unpackbits(bits.view(np.uint8), axis=1, bitorder="little")[:, : L.K]
-            rp, ci = dl.row_ptr.cpu().numpy(), dl.col_idx.cpu().numpy()
-            ones = sum(int(keep[bi * L.B:(bi + 1) * L.B, bj * L.B:(bj + 1) * L.B].sum())
-                       for bi in range(sz.Sb) for bj in ci[rp[bi]:rp[bi + 1]])
-        uf = 2.0 * ones * L.Ncol
-        rows.append(dict(name=L.name, S=L.S, K=L.K, Ncol=L.Ncol, nm="%d:%d" % (L.n, L.m), density=round(L.density, 3),
-                         k_row=sz.k_row, lowering=path[0], prune_pack_ms=(round(tp, 4) if tp is not None else None), forward_ms=round(tf, 4),
-                         im2col_ms=round(ti, 4),
-                         useful_tflops_forward=round(uf / (tf * 1e-3) / 1e12, 2)))
-        t_fwd += tf
-        t_im2col += ti
-        useful += uf
-        dense += 2.0 * L.S * L.K * L.Ncol
-        del acts, Ys, Xs
-        torch.cuda.empty_cache()
-    total = t_prune + t_fwd
-    out = {"metric": "effective TFLOP/s (nonzero FLOPs) of hybrid-sparse GEMM + % roofline",
-           "value": round(useful / (total * 1e-3) / 1e12, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": reps, "warmup": 1,
-           "ms_per_step": round(total, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-           "dtype": "bf16", "data": "synthetic",
-           "config": {"workload": "c5: ResNet-50, 53 convs as GEMMs, batch 256, 224x224, layer-wise inputs, B=64, "
-                                  "per-layer n:m and block density drawn from the workload seed",
-                      "step": ("select+pack layer by layer (crisp_select_pack)" if args.per_layer_prune else "select+pack of all layers in one crisp_select_pack_batch call") + "; then per layer: lowering (fused, im2col or none) and product; summed",
-                      "y_dtype": args.y_dtype},
-           "select_pack_ms": round(t_prune, 3), "forward_ms": round(t_fwd, 3),
-           "im2col_ms": round(t_im2col, 3), "product_ms": round(t_fwd - t_im2col, 3),
-           "useful_tflops_forward_only": round(useful / (t_fwd * 1e-3) / 1e12, 2),
-           "dense_equivalent_tflops_forward_only": round(dense / (t_fwd * 1e-3) / 1e12, 1),
-           "roofline": None, "layers": rows}
-    print(json.dumps(out))
+    def one_pass():
+        t0 = time.perf_counter()
+        for i, L in enumerate(wl.layers):
+            h = host_inputs[i]
+            sel = oracle.select(h["W"], h["G"], L.n, L.m, L.B, L.density, L.sal_kind, L.select_mode)
+            oracle.pack(h["W"], sel.keep, L.n, L.m, L.B, sel.row_ptr, sel.col_idx)
+            X = h["X"]
+            if X is None:
+                cv = L.conv
+                X = oracle.im2col(h["act"], cv.kh, cv.kw, cv.stride, cv.pad)
+            frac = 1.0
+            ncols = X.shape[1]
+            budget = 2e9 * budget_s / 10.0    # multiply-adds per layer that keep one pass within the budget
+            if L.S * L.K * ncols > budget:
+                ncols = max(64, int(budget // (L.S * L.K)))
+                frac = ncols / X.shape[1]
+            tg = time.perf_counter()
+            oracle.gemm_masked(h["W"], sel.mask, X, 0, ncols, want_abs=False)
+            tg = time.perf_counter() - tg
+            t0 -= tg * (1.0 / frac - 1.0)    # scale the sampled columns to the full width
+        return time.perf_counter() - t0
+
+    wall0 = time.perf_counter()
+    passes = [one_pass()]
+    while time.perf_counter() - wall0 < budget_s and len(passes) < 64:
+        passes.append(one_pass())
+    dt = sum(passes) / len(passes)
+    return {"value": round(useful_flop / dt / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "seconds": round(dt, 3), "passes": len(passes), "cpu_seconds_spent": round(time.perf_counter() - wall0, 1),
+            "sample": "mean of %d passes of the full workload (select, pack, im2col, dense masked fp64 product); "
+                      "products above %.1e multiply-adds are timed on their first columns and scaled" % (len(passes), 2e9 * budget_s / 10.0)}
+
+
+def copy_calibration():
+    """A plain elementwise pass of known traffic (reads 512 MiB, writes 512 MiB) whose profiler counters
+    give the scale of FETCH_SIZE / WRITE_SIZE on this machine."""
+    import torch
+    a = torch.ones(128 << 20, dtype=torch.float32, device="cuda")
+    b = torch.empty_like(a)
+    for _ in range(5):
+        torch.add(a, 1.0, out=b)
+    torch.cuda.synchronize()
+    del a, b
+
+
+def run_layer(args):
+    """One layer of a workload on its own: select+pack once, then only its product (with its lowering), --steps
+    launches back to back over rotating inputs (more than 600 MB in total), for profiler counters on cold launches."""
+    import torch
+    from paper_2311_14272_amd import crisp, synth
+    dev = "cuda"
+    wl = synth.config(args.config)
+    names = [L.name for L in wl.layers]
+    if args.layer not in names:
+        print("bench.py: workload c%d has no layer %r (layers: %s)" % (args.config, args.layer, " ".join(names)), file=sys.stderr)
+        sys.exit(2)
+    li = names.index(args.layer)
+    L = wl.layers[li]
+    y_dtype = crisp.Y_BF16 if args.y_dtype == "bf16" else crisp.Y_F32
+    ybytes = 2 if y_dtype == crisp.Y_BF16 else 4
+    ytorch = torch.bfloat16 if y_dtype == crisp.Y_BF16 else torch.float32
+    steps = args.steps or 40
+    t = synth.draw_layer(wl, li, with_x=False)
+    dl = crisp.alloc_layer(crisp.layer_desc(L.S, L.K, L.n, L.m, L.B, L.density, L.sal_kind, L.select_mode), dev)
+    W = torch.from_numpy(t["W"].view(np.int16)).to(dev)
+    G = torch.from_numpy(t["G"]).to(dev) if t["G"] is not None else None
+    crisp.prune_and_pack(dl, W, G)
+    cv = L.conv if L.conv is not None else synth.ConvShape(L.K, 1, L.Ncol, 1, 1, 1, 1, 0)    # a plain product as a 1x1 layer
+    in_elems = cv.C * cv.batch * cv.H * cv.W
+    nbuf = max(2, min(16, int(600e6 // (2 * in_elems + ybytes * L.S * L.Ncol)) + 1))
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(wl.seed)
+    acts = [torch.randn((cv.C, cv.batch, cv.H, cv.W), generator=gen, device=dev).clamp_(min=0).to(torch.bfloat16).view(torch.int16)
+            for _ in range(nbuf)]
+    Ys = [torch.empty((L.S, L.Ncol), dtype=ytorch, device=dev) for _ in range(nbuf)]
+    Xs = torch.empty(L.K * ((L.Ncol + 7) // 8 * 8), dtype=torch.int16, device=dev) \
+        if crisp.conv_needs_scratch(cv, L.B, L.n, L.m, L.S, L.density) else None
+    if args.copy_calibration:
+        copy_calibration()
+    ones, used_cols, w_bytes, _ = mask_stats(L, dl)
+    for r in range(3):
+        path = crisp.conv_forward(dl, cv, acts[r % nbuf], Ys[r % nbuf], L.Ncol, y_dtype, Xs)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for r in range(steps):
+        crisp.conv_forward(dl, cv, acts[r % nbuf], Ys[r % nbuf], L.Ncol, y_dtype, Xs)
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b) / steps
+    st = dict(name=L.name, S=L.S, K=L.K, Ncol=L.Ncol, nm="%d:%d" % (L.n, L.m), B=L.B, k_row=dl.sizes.k_row,
+              useful_flop=2.0 * ones * L.Ncol, dense_flop=2.0 * L.S * L.K * L.Ncol,
+              alg_bytes=algorithmic_bytes(L, used_cols, w_bytes, ybytes), lowering=path, launches=steps, input_sets=nbuf)
+    print(json.dumps({"layer_only": layer_row(L, st, ms, ybytes), "workload": wl.name,
+                      "timing": "launches back to back between one event pair, rotating inputs"}))
+
+
+def config_row(cid, out):
+    """One row of the per-configuration table from a run's output."""
+    hb = out.get("roofline") or {}
+    row = {"config": "c%d" % cid, "ms_per_step": out["ms_per_step"], "useful_tflops": out["value"],
+           "dense_equivalent_tflops": out["dense_equivalent_tflops"],
+           "useful_tflops_forward_only": out.get("useful_tflops_forward_only"),
+           "hbm_frac_dominant_kernel": hb.get("frac"), "dominant_kernel": hb.get("kernel"),
+           "layers": [{k: r.get(k) for k in ("name", "kernel", "forward_ms", "useful_tflops_forward", "hbm_frac", "mfma_frac_useful",
+                                             "bound", "bound_frac")} for r in out.get("layers", [])]}
+    if cid != 5:
+        fw = sum(r["forward_ms"] for r in out["layers"])
+        row["useful_tflops_forward_only"] = round(sum(r["useful_flop"] for r in out["layers"]) / (fw * 1e-3) / 1e12, 2)
+    cb = out.get("cpu_baseline")
+    if cb:
+        row["oracle_seconds"] = cb.get("seconds", cb.get("seconds_scaled_to_full_workload"))
+        row["oracle_cores"] = cb["cores"]
+        row["oracle_tflops"] = cb["value"]
+    return row
 
 
 def block_sweep(args):
@@ -251,7 +800,7 @@ def main():
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
     import torch
-    from paper_2311_14272_amd import crisp, synth
+    from paper_2311_14272_amd import crisp
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
@@ -260,360 +809,25 @@ def main():
     if args.sweep:
         block_sweep(args)
         return
-    if args.config == 5:
-        resnet50_pass(args)
+    if args.layer:
+        run_layer(args)
         return
-    dev = "cuda"
-    wl = synth.config(args.config)
-    y_dtype = crisp.Y_BF16 if args.y_dtype == "bf16" else crisp.Y_F32
-    ybytes = 2 if y_dtype == crisp.Y_BF16 else 4
-    ytorch = torch.bfloat16 if y_dtype == crisp.Y_BF16 else torch.float32
-
-    def to_dev(a):
-        a = np.ascontiguousarray(a)
-        if a.dtype == np.uint16:
-            a = a.view(np.int16)
-        return torch.from_numpy(a).to(dev)
-
-    # ---- resident data ------------------------------------------------------------------
-    host_inputs = [synth.draw_layer(wl, i) for i in range(len(wl.layers))]
-    per_set = 0
-    for L in wl.layers:
-        is_conv = L.conv is not None and (L.conv.kh > 1 or L.conv.kw > 1 or L.conv.stride > 1)
-        per_set += ybytes * L.S * L.Ncol
-        if is_conv:
-            per_set += 2 * L.conv.C * L.conv.batch * L.conv.H * L.conv.W
-        if not is_conv or args.explicit_im2col:
-            per_set += 2 * L.K * L.Ncol
-    # enough independent input sets that a rotation exceeds the 256 MB last-level cache more than twice
-    nsets = args.sets if args.sets > 0 else max(2, min(80, int(600e6 // per_set) + 1))
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(wl.seed)
-    layers = []
-    for i, L in enumerate(wl.layers):
-        st = LayerState()
-        st.L = L
-        st.desc = crisp.layer_desc(L.S, L.K, L.n, L.m, L.B, L.density, L.sal_kind, L.select_mode)
-        st.dl = crisp.alloc_layer(st.desc, dev)
-        st.W = to_dev(host_inputs[i]["W"])
-        st.G = to_dev(host_inputs[i]["G"]) if host_inputs[i]["G"] is not None else None
-        cv = L.conv
-        st.is_conv = cv is not None and (cv.kh > 1 or cv.kw > 1 or cv.stride > 1)
-        st.conv = crisp.ConvDesc(cv.C, cv.H, cv.W, cv.batch, cv.kh, cv.kw, cv.stride, cv.pad, crisp.ACT_CBHW,
-                                 crisp.X_KN) if st.is_conv else None
-        st.fused = False
-        if st.is_conv and not args.explicit_im2col:
-            Wo = cv.W + 2 * cv.pad - cv.kw + 1
-            st.fused = (cv.stride == 1 and cv.C % L.B == 0 and Wo % 2 == 0 and L.B in (32, 64))
-        st.act, st.X, st.Y = [], [], []
-        for s in range(nsets):
-            if st.is_conv:
-                if s == 0:
-                    a = to_dev(host_inputs[i]["act"])
-                else:
-                    a = torch.randn((cv.C, cv.batch, cv.H, cv.W), generator=gen, device=dev).clamp_(min=0).to(torch.bfloat16).view(torch.int16)
-                st.act.append(a)
-                st.X.append(None if st.fused else torch.empty((L.K, L.Ncol), dtype=torch.int16, device=dev))
-            else:
-                if s == 0:
-                    x = to_dev(host_inputs[i]["X"])
-                else:
-                    x = torch.randn((L.K, L.Ncol), generator=gen, device=dev).clamp_(min=0).to(torch.bfloat16).view(torch.int16)
-                st.X.append(x)
-            st.Y.append(torch.empty((L.S, L.Ncol), dtype=ytorch, device=dev))
-        layers.append(st)
-
-    def prune(st):
-        crisp.prune_and_pack(st.dl, st.W, st.G)
-
-    def product(st, s):
-        L = st.L
-        if st.fused:
-            crisp.crisp_conv_spmm(st.desc, st.conv, st.dl.row_ptr, st.dl.col_idx, st.dl.vals, st.dl.idx_words,
-                                  st.act[s], st.Y[s], L.Ncol, y_dtype)
-        else:
-            crisp.crisp_spmm(st.desc, st.dl.row_ptr, st.dl.col_idx, st.dl.vals, st.dl.idx_words, st.X[s], L.Ncol,
-                             L.Ncol, st.Y[s], L.Ncol, y_dtype)
-
-    def forward(st, s, events=None):
-        if st.is_conv and not st.fused:
-            crisp.crisp_im2col(st.conv, st.act[s], st.X[s], st.L.Ncol)
-        if events is not None:
-            events[0].record()
-        product(st, s)
-        if events is not None:
-            events[1].record()
-
-    main = torch.cuda.current_stream()
-    side = [torch.cuda.Stream() for _ in layers]           # default priority
-    pdone = [None] * len(layers)                            # select+pack of layer i finished (side stream)
-    fdone = [None] * len(layers)                            # product of layer i finished (main stream)
-
-    batch = crisp.make_batch([st.dl for st in layers], [st.W for st in layers], [st.G for st in layers])
-
-    def step(k, dom=None, events=None):
-        s = k % nsets
-        if not args.side_streams or args.spmm_only:
-            # all layers are pruned in one call (the method prunes a model in one shot), then the products
-            if not args.spmm_only and not args.per_layer_prune:
-                crisp.crisp_select_pack_batch(*batch)
-            for i, st in enumerate(layers):
-                if not args.spmm_only and args.per_layer_prune:
-                    prune(st)
-                forward(st, s, events if i == dom else None)
-            return
-        # The weights-only part (select + pack) of the layers is mutually independent: one side
-        # stream per layer.  A layer's pack buffers are rewritten only after the previous step's
-        # product of that layer has read them, and its product waits for its pack.
-        for i, st in enumerate(layers):
-            if fdone[i] is not None:
-                side[i].wait_event(fdone[i])
-            with torch.cuda.stream(side[i]):
-                prune(st)
-                pdone[i] = torch.cuda.Event()
-                pdone[i].record()
-        for i, st in enumerate(layers):
-            main.wait_event(pdone[i])
-            forward(st, s, events if i == dom else None)
-            fdone[i] = torch.cuda.Event()
-            fdone[i].record()
-
-    # ---- one untimed pass to learn the mask statistics (metric bookkeeping, from device output) ----
-    for st in layers:
-        prune(st)
-    torch.cuda.synchronize()
-    info = []
-    for st in layers:
-        L, sz = st.L, st.dl.sizes
-        row_ptr = st.dl.row_ptr.cpu().numpy()
-        col_idx = st.dl.col_idx.cpu().numpy()[: sz.nk]
-        bits = st.dl.nm_mask.cpu().numpy().view(np.uint32)[: sz.mask_words].reshape(L.S, sz.mask_words_per_row)
-        keep = np.unpackbits(bits.view(np.uint8), axis=1, bitorder="little")[:, : L.K]
-        ones = 0
-        for bi in range(sz.Sb):
-            for bj in col_idx[row_ptr[bi]:row_ptr[bi + 1]]:
-                ones += int(keep[bi * L.B:(bi + 1) * L.B, bj * L.B:(bj + 1) * L.B].sum())
-        used_cols = np.unique(col_idx)
-        kept_vals = sz.nk * L.B * sz.slots_per_row
-        w_bytes = kept_vals * 2 + sz.idx_words * 4 + sz.nk * 4 + (sz.Sb + 1) * 4
-        if st.fused:
-            # implicit lowering: the activation planes of the channels that any kept block column touches
-            cvs = L.conv
-            chans = set()
-            for bj in used_cols:
-                c0 = (bj * L.B) % cvs.C
-                chans.update(range(c0, c0 + L.B))
-            x_bytes = 2 * len(chans) * cvs.batch * cvs.H * cvs.W
-        else:
-            k_used = int(sum(min(L.K, (bj + 1) * L.B) - bj * L.B for bj in used_cols))
-            x_bytes = 2 * k_used * L.Ncol
-        alg_bytes = x_bytes + ybytes * L.S * L.Ncol + w_bytes
-        # metadata of the packed form next to the closed forms of Sec. 3.1 (K' = k_row*B kept columns per row)
-        Kp = sz.k_row * L.B
-        meta = dict(paper_block_bits=L.S * Kp * int(np.floor(np.log2(max(Kp / L.B, 1)))) // (L.B * L.B),
-                    paper_nm_bits=L.S * Kp * L.n * sz.idx_bits // L.m,
-                    stored_block_bytes=int(sz.nk * 4 + (sz.Sb + 1) * 4), stored_nm_bytes=int(sz.idx_words * 4),
-                    packed_value_bytes=int(kept_vals * 2), dense_bytes=int(L.S * L.K * 2))
-        info.append(dict(name=L.name, S=L.S, K=L.K, Ncol=L.Ncol, metadata=meta, nm="%d:%d" % (L.n, L.m), B=L.B, k_row=sz.k_row,
-                         ones=ones, useful_flop=2.0 * ones * L.Ncol, dense_flop=2.0 * L.S * L.K * L.Ncol,
-                         alg_bytes=alg_bytes, smfmac_ok=int(st.dl.flags.cpu()[0]),
-                         lowering=("fused" if st.fused else ("im2col" if st.is_conv else "none"))))
-    useful = sum(x["useful_flop"] for x in info)
-    dense_eq = sum(x["dense_flop"] for x in info)
-    dom = int(np.argmax([x["alg_bytes"] for x in info]))   # dominant kernel: the product with the most traffic
-
-    if args.copy_calibration:
-        # a plain elementwise pass of known traffic (reads 512 MiB, writes 512 MiB) whose profiler
-        # counters give the scale of FETCH_SIZE / WRITE_SIZE on this machine
-        a = torch.ones(128 << 20, dtype=torch.float32, device=dev)
-        b = torch.empty_like(a)
-        for _ in range(5):
-            torch.add(a, 1.0, out=b)
-        torch.cuda.synchronize()
-        del a, b
-
-    # ---- warm-up, then the timed region ----------------------------------------------------
-    for k in range(args.warmup):
-        step(k)
-    torch.cuda.synchronize()
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        step(args.warmup + k, dom, ev[k])
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    # An event pair around one launch also times the dispatch gaps next to it.  Against the kernel
-    # trace of the same command (profiles/) that excess is a stable 3.0 us on this machine
-    # (11.5 vs 8.5 us and 17.4 vs 14.3 us for two product kernels of different length); it is
-    # taken off here and both numbers are reported.
-    pair_ms = 0.0030
-    dom_raw = [a.elapsed_time(b) for a, b in ev]
-    dom_raw_ms = float(np.mean(dom_raw))
-    dom_ms = max(dom_raw_ms - pair_ms, 1e-6)
-    dom_med_ms = max(float(np.median(dom_raw)) - pair_ms, 1e-6)
-
-    # ---- per-phase breakdown (untimed extras, reported for context) --------------------------
-    def timed(fn, reps=50):
-        torch.cuda.synchronize()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for r in range(reps):
-            fn(r)
-        b.record()
-        torch.cuda.synchronize()
-        return a.elapsed_time(b) / reps
-
-    for i, st in enumerate(layers):
-        info[i]["prune_pack_ms"] = round(timed(lambda r, st=st: prune(st)), 5)
-        info[i]["forward_ms"] = round(timed(lambda r, st=st: forward(st, r % nsets)), 5)
-        # the same launches on one input set over and over: inputs served from the last-level cache
-        info[i]["forward_warm_ms"] = round(timed(lambda r, st=st: forward(st, 0)), 5)
-        fw = info[i]["forward_ms"] * 1e-3
-        info[i]["useful_tflops_forward"] = round(info[i]["useful_flop"] / fw / 1e12, 3)
-        info[i]["hbm_frac_forward"] = round(info[i]["alg_bytes"] / fw / 1e9 / HBM_PEAK_GBS, 4)
-
-    graph_info = None
-    if args.graph and not args.side_streams:
-        # the step of every input set captured once, replayed in turn: the launches of a step go to
-        # the GPU as one unit.  Nothing in the library allocates, synchronises or clears memory, so
-        # every call is capturable as it is.
-        step(0)
-        torch.cuda.synchronize()
-        eager = [st.Y[0].clone() for st in layers]
-        for st in layers:
-            st.Y[0].zero_()
-        graphs = []
-        for sidx in range(nsets):
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g):
-                step(sidx)
-            graphs.append(g)
-        same = True
-        for rep in range(3):                       # replays with eager work in between, each checked
-            graphs[0].replay()
-            torch.cuda.synchronize()
-            same = same and all(torch.equal(st.Y[0], e) for st, e in zip(layers, eager))
-            step(1 % nsets)
-            for st in layers:
-                st.Y[0].zero_()
-            torch.cuda.synchronize()
-        for k in range(args.warmup):
-            graphs[k % nsets].replay()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for k in range(args.steps):
-            graphs[(args.warmup + k) % nsets].replay()
-        torch.cuda.synchronize()
-        g_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-        graph_info = {"ms_per_step": round(g_ms, 5), "value": round(useful / (g_ms * 1e-3) / 1e12, 4),
-                      "replay_equals_eager": bool(same)}
-
-    # a plain device-to-device copy that moves as many bytes as the dominant product (half read, half
-    # written), launched back to back over rotating buffers like forward_ms: what the memory system and
-    # the launch path give a kernel of this size that does nothing else
-    half = max(int(info[dom]["alg_bytes"]) // 4, 1)          # int16 elements per side
-    ncopy = max(2, min(16, int(600e6 // (4 * half)) + 1))
-    csrc = [torch.zeros(half, dtype=torch.int16, device=dev) for _ in range(ncopy)]
-    cdst = [torch.empty(half, dtype=torch.int16, device=dev) for _ in range(ncopy)]
-    copy_ms = timed(lambda r: cdst[r % ncopy].copy_(csrc[r % ncopy]))
-    del csrc, cdst
-
-    achieved = info[dom]["alg_bytes"] / (dom_ms * 1e-3) / 1e9
-    out = {
-        "metric": "effective TFLOP/s (nonzero FLOPs) of hybrid-sparse GEMM + % roofline",
-        "value": round(useful / (ms_per_step * 1e-3) / 1e12, 4),
-        "unit": "TFLOP/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 5),
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "bf16",
-        "data": "synthetic",
-        "config": {"workload": "%s: %s" % (wl.name, ", ".join("%s %dx%dx%d %s B%d k_row %d" % (
-            x["name"], x["S"], x["K"], x["Ncol"], x["nm"], x["B"], x["k_row"]) for x in info)),
-                   "step": (("select+pack of all layers (crisp_select_pack_batch), then " if not args.per_layer_prune else "select+pack (crisp_select_pack)+") if not args.spmm_only else "") + ("im2col+spmm" if args.explicit_im2col else "spmm with the 3x3 layer's lowering fused (crisp_conv_spmm)") + " per layer",
-                   "y_dtype": args.y_dtype, "x_layout": "KN", "input_sets": nsets,
-                   "streams": "one" if (not args.side_streams or args.spmm_only) else "select+pack of each layer on its own side stream, products on the main stream"},
-        "dense_equivalent_tflops": round(dense_eq / (ms_per_step * 1e-3) / 1e12, 3),
-        "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": TRAFFIC.get((wl.name, info[dom]["name"], args.y_dtype)),
-                     "kernel": "spmm kernel of layer %s" % info[dom]["name"],
-                     "avg_launch_ms": round(dom_ms, 5), "median_launch_ms": round(dom_med_ms, 5),
-                     "timing": "event pair around the launch in every timed step, minus the calibrated cost of the pair",
-                     "avg_bracket_ms": round(dom_raw_ms, 5), "event_pair_overhead_ms": round(pair_ms, 5),
-                     "algorithmic_bytes": info[dom]["alg_bytes"],
-                     "forward_ms_back_to_back": info[dom]["forward_ms"],
-                     "plain_copy_same_bytes_ms_back_to_back": round(copy_ms, 5)},
-        "layers": info,
-    }
-    if graph_info is not None:
-        out["graph_replay"] = graph_info
-    # the bytes both the device path and the oracle were given (first input set), for reproduction
-    digests = {}
-    for h, x in zip(host_inputs, info):
-        for key in ("W", "G", "X", "act"):
-            if h.get(key) is not None:
-                digests["%s.%s" % (x["name"], key)] = hashlib.sha256(np.ascontiguousarray(h[key]).view(np.uint8)).hexdigest()[:16]
-    out["inputs"] = {"generator": "numpy %s PCG64, seed %d" % (np.__version__, wl.seed), "sha256_prefix": digests}
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, host_inputs, useful)
+    want_cpu = not args.no_cpu_baseline
+    if args.config != 5:
+        out = run_small(args.config, args, args.steps or 200, args.warmup or 20, "full" if want_cpu else None)
+        print(json.dumps(out))
+        return
+    out, useful = run_resnet50(args)
+    if want_cpu and not args.chained:
+        out["cpu_baseline"] = cpu_baseline_resnet50(useful)
+    if not args.no_config_table and not args.chained:
+        # the other configurations, by short runs of their own after the timed region (same process)
+        table = []
+        for cid in (1, 2, 3, 4):
+            table.append(config_row(cid, run_small(cid, args, 100, 10, "short" if want_cpu else None)))
+        table.append(config_row(5, out))
+        out["configs"] = table
     print(json.dumps(out))
-
-
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE,
-# scaled by the same counters on a plain copy of known size); filled in from profiles/.
-TRAFFIC = {
-    # (workload, layer, y dtype): bytes per launch = 2.0 * FETCH_SIZE + 1.0 * WRITE_SIZE (KiB -> bytes); the factors come
-    # from the same counters on an elementwise add of known size in the same runs (profiles/bench_c*_kernels.txt)
-    ("c1", "c1", "bf16"): int((2.0 * 4230.1 + 1568.0) * 1024),
-    ("c2", "c2c", "bf16"): int((2.0 * 1762.5 + 12544.0) * 1024),
-    ("c3", "c3", "bf16"): int((2.0 * 215781.7 + 50976.0) * 1024),
-    ("c4", "c4b", "bf16"): int((2.0 * 37684.9 + 18816.0) * 1024),
-}
-
-
-def cpu_baseline(wl, host_inputs, useful_flop):
-    """The CPU oracle as it stands, timed on the host cores on the same workload: whole passes are
-    repeated until about ten seconds of CPU work have been spent, and the mean pass is reported."""
-    import oracle
-
-    def one_pass():
-        t0 = time.perf_counter()
-        for i, L in enumerate(wl.layers):
-            h = host_inputs[i]
-            sel = oracle.select(h["W"], h["G"], L.n, L.m, L.B, L.density, L.sal_kind, L.select_mode)
-            oracle.pack(h["W"], sel.keep, L.n, L.m, L.B, sel.row_ptr, sel.col_idx)
-            X = h["X"]
-            if X is None:
-                cv = L.conv
-                X = oracle.im2col(h["act"], cv.kh, cv.kw, cv.stride, cv.pad)
-            frac = 1.0
-            ncols = X.shape[1]
-            budget = 6e9                     # multiply-adds per layer that keep one pass within ~30 s
-            if L.S * L.K * ncols > budget:
-                ncols = max(64, int(budget // (L.S * L.K)))
-                frac = ncols / X.shape[1]
-            tg = time.perf_counter()
-            oracle.gemm_masked(h["W"], sel.mask, X, 0, ncols, want_abs=False)
-            tg = time.perf_counter() - tg
-            t0 -= tg * (1.0 / frac - 1.0)    # scale the sampled columns to the full width
-        return time.perf_counter() - t0
-
-    wall0 = time.perf_counter()
-    passes = [one_pass()]
-    while time.perf_counter() - wall0 < 10.0 and len(passes) < 64:
-        passes.append(one_pass())
-    dt = sum(passes) / len(passes)
-    cores = oracle.num_threads()
-    return {"value": round(useful_flop / dt / 1e12, 6), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
-            "seconds": round(dt, 3), "passes": len(passes), "cpu_seconds_spent": round(time.perf_counter() - wall0, 1),
-            "sample": "mean of %d passes of the full workload (select, pack, im2col, dense masked fp64 product); "
-                      "products above 6e9 multiply-adds are timed on their first columns and scaled" % len(passes)}
 
 
 if __name__ == "__main__":
