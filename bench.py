@@ -63,6 +63,13 @@ def parse():
                     help="only the product of this layer of the chosen workload (e.g. --config 5 --layer s4b0.a), launched "
                          "--steps times over rotating inputs that do not fit the last-level cache: isolated cold launches "
                          "for profiler counters")
+    ap.add_argument("--topk", action="store_true",
+                    help="--layer mode: plain block pruning over the whole grid (CRISP_LAYER_TOPK) instead of uniform rows")
+    ap.add_argument("--row-skew", type=float, default=0.0,
+                    help="--layer mode: saliency |W| scaled per block-row by skew^(-row), handed in as CRISP_SAL_GIVEN, so that "
+                         "whole-grid block pruning leaves block-rows of very different length (e.g. 1.6)")
+    ap.add_argument("--shape", type=int, default=None,
+                    help="--layer mode, plain products: force this launch shape (crisp_spmm_forced) instead of the library's choice")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 512 MiB device copy a few times (known traffic, for scaling profiler counters)")
     return ap.parse_args()
@@ -81,8 +88,10 @@ def kernel_id(code: int, L) -> str:
     """Readable name of the kernel instantiation a product launch ran (from the library's report)."""
     from paper_2311_14272_amd import crisp
     f = crisp.kernel_code_fields(code)
-    return "%s %d:%d B%d shape%d conv%d %s" % (f["family"], L.n, L.m, L.B, f["shape"], f["conv_mode"],
-                                                "sparse-mfma" if f["sparse_mfma"] else "dense-mfma")
+    # (the LDS-resident, generic and 16 x 16 families are one compiled kernel for every pattern)
+    pattern = "any n:m" if f["family"] in ("lds", "generic", "b16") else "%d:%d" % (L.n, L.m)
+    return "%s %s B%d shape%d conv%d %s" % (f["family"], pattern, L.B, f["shape"], f["conv_mode"],
+                                             "sparse-mfma" if f["sparse_mfma"] else "dense-mfma")
 
 
 def mask_stats(L, dl):
@@ -689,9 +698,17 @@ def run_layer(args):
     ytorch = torch.bfloat16 if y_dtype == crisp.Y_BF16 else torch.float32
     steps = args.steps or 40
     t = synth.draw_layer(wl, li, with_x=False)
-    dl = crisp.alloc_layer(crisp.layer_desc(L.S, L.K, L.n, L.m, L.B, L.density, L.sal_kind, L.select_mode), dev)
+    sal_kind, TG = L.sal_kind, t["G"]
+    if args.row_skew > 0.0:
+        # input generation only: a saliency tensor whose block-rows differ in scale
+        Sb = (L.S + L.B - 1) // L.B
+        scale = np.repeat(np.float32(args.row_skew) ** -np.arange(Sb, dtype=np.float32), L.B)[: L.S, None]
+        TG = (np.abs(synth.bf16_bits_to_f32(t["W"])) * scale).astype(np.float32)
+        sal_kind = crisp.SAL_GIVEN
+    desc = crisp.layer_desc(L.S, L.K, L.n, L.m, L.B, L.density, sal_kind, crisp.LAYER_TOPK if args.topk else L.select_mode)
+    dl = crisp.alloc_layer(desc, dev)
     W = torch.from_numpy(t["W"].view(np.int16)).to(dev)
-    G = torch.from_numpy(t["G"]).to(dev) if t["G"] is not None else None
+    G = torch.from_numpy(TG).to(dev) if TG is not None else None
     crisp.prune_and_pack(dl, W, G)
     cv = L.conv if L.conv is not None else synth.ConvShape(L.K, 1, L.Ncol, 1, 1, 1, 1, 0)    # a plain product as a 1x1 layer
     in_elems = cv.C * cv.batch * cv.H * cv.W
@@ -706,19 +723,32 @@ def run_layer(args):
     if args.copy_calibration:
         copy_calibration()
     ones, used_cols, w_bytes, _ = mask_stats(L, dl)
+    code = [0]
+
+    def launch(r):
+        if args.shape is None:
+            return crisp.conv_forward(dl, cv, acts[r % nbuf], Ys[r % nbuf], L.Ncol, y_dtype, Xs)
+        code[0] = crisp.crisp_spmm_forced(desc, dl.row_ptr, dl.col_idx, dl.vals, dl.idx_words, acts[r % nbuf], L.Ncol, L.Ncol,
+                                          Ys[r % nbuf], L.Ncol, y_dtype, None, args.shape)
+        return "none"
+    if args.shape is not None and (cv.kh > 1 or cv.kw > 1 or cv.stride > 1):
+        print("bench.py: --shape applies to plain products (1x1, stride 1) only", file=sys.stderr)
+        sys.exit(2)
     for r in range(3):
-        path = crisp.conv_forward(dl, cv, acts[r % nbuf], Ys[r % nbuf], L.Ncol, y_dtype, Xs)
+        path = launch(r)
     torch.cuda.synchronize()
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     a.record()
     for r in range(steps):
-        crisp.conv_forward(dl, cv, acts[r % nbuf], Ys[r % nbuf], L.Ncol, y_dtype, Xs)
+        launch(r)
     b.record()
     torch.cuda.synchronize()
     ms = a.elapsed_time(b) / steps
     st = dict(name=L.name, S=L.S, K=L.K, Ncol=L.Ncol, nm="%d:%d" % (L.n, L.m), B=L.B, k_row=dl.sizes.k_row,
               useful_flop=2.0 * ones * L.Ncol, dense_flop=2.0 * L.S * L.K * L.Ncol,
-              alg_bytes=algorithmic_bytes(L, used_cols, w_bytes, ybytes), lowering=path, launches=steps, input_sets=nbuf)
+              alg_bytes=algorithmic_bytes(L, used_cols, w_bytes, ybytes), lowering=path, launches=steps, input_sets=nbuf,
+              blocks_per_row=np.diff(dl.row_ptr.cpu().numpy()).tolist()[:64],
+              kernel=kernel_id(code[0], L) if args.shape is not None else None)
     print(json.dumps({"layer_only": layer_row(L, st, ms, ybytes), "workload": wl.name,
                       "timing": "launches back to back between one event pair, rotating inputs"}))
 

@@ -20,6 +20,7 @@
 #include "spmm_reg.h"
 #include "spmm_xres.h"
 #include "conv_patch.h"
+#include "spmm_balanced.h"
 
 namespace crisp {
 
@@ -372,6 +373,8 @@ template <int N, int M>
 hipError_t launch_conv_lds_nm(const SpmmArgs& a, const ConvLdsSched& s, int batch, hipStream_t st);
 template <int N, int M>
 hipError_t launch_conv_patch_nm(const SpmmArgs& a, const ConvPatchSched& s, int batch, hipStream_t st);
+template <int N, int M>
+hipError_t launch_balanced_nm(const SpmmArgs& a, int B, hipStream_t st);
 
 #define CRISP_INSTANTIATE_NM(N, M)                                                           \
     template <>                                                                              \
@@ -386,6 +389,10 @@ hipError_t launch_conv_patch_nm(const SpmmArgs& a, const ConvPatchSched& s, int 
     template <>                                                                              \
     hipError_t launch_conv_patch_nm<N, M>(const SpmmArgs& a, const ConvPatchSched& s, int batch, hipStream_t st) { \
         return launch_conv_patch<N, M>(a, s, batch, st);                                    \
+    }                                                                                        \
+    template <>                                                                              \
+    hipError_t launch_balanced_nm<N, M>(const SpmmArgs& a, int B, hipStream_t st) {          \
+        return launch_balanced<N, M>(a, B, st);                                              \
     }
 
 }  // namespace crisp

@@ -375,6 +375,14 @@ template <> hipError_t launch_conv_patch_nm<1, 8>(const SpmmArgs&, const ConvPat
 template <> hipError_t launch_conv_patch_nm<2, 8>(const SpmmArgs&, const ConvPatchSched&, int, hipStream_t);
 template <> hipError_t launch_conv_patch_nm<4, 8>(const SpmmArgs&, const ConvPatchSched&, int, hipStream_t);
 template <> hipError_t launch_conv_patch_nm<8, 8>(const SpmmArgs&, const ConvPatchSched&, int, hipStream_t);
+template <> hipError_t launch_balanced_nm<1, 4>(const SpmmArgs&, int, hipStream_t);
+template <> hipError_t launch_balanced_nm<2, 4>(const SpmmArgs&, int, hipStream_t);
+template <> hipError_t launch_balanced_nm<3, 4>(const SpmmArgs&, int, hipStream_t);
+template <> hipError_t launch_balanced_nm<4, 4>(const SpmmArgs&, int, hipStream_t);
+template <> hipError_t launch_balanced_nm<1, 8>(const SpmmArgs&, int, hipStream_t);
+template <> hipError_t launch_balanced_nm<2, 8>(const SpmmArgs&, int, hipStream_t);
+template <> hipError_t launch_balanced_nm<4, 8>(const SpmmArgs&, int, hipStream_t);
+template <> hipError_t launch_balanced_nm<8, 8>(const SpmmArgs&, int, hipStream_t);
 template <> hipError_t launch_conv_lds_nm<1, 4>(const SpmmArgs&, const ConvLdsSched&, int, hipStream_t);
 template <> hipError_t launch_conv_lds_nm<2, 4>(const SpmmArgs&, const ConvLdsSched&, int, hipStream_t);
 template <> hipError_t launch_conv_lds_nm<3, 4>(const SpmmArgs&, const ConvLdsSched&, int, hipStream_t);
@@ -549,13 +557,35 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
     if (bpr < 1) bpr = 1;
     // LDS-resident block-rows (forced shapes 5 = narrow strips, 6 = wide strips)
     const bool lds_ok = !conv && (g.K % 16) == 0 && (Ncol % 4) == 0 && ld_wide <= ((int64_t)1 << 23);
+    // (reported shape of this family: bit 0 = wide strips, bit 1 = the instantiation with the larger tile capacity
+    // where the block size has two; the kernels are not specialised by pattern)
+    auto lds_variant = [&](bool wide) { return (wide ? 1 : 0) | ((g.B == 64 ? (wide && bpr > 9) : bpr > 36) ? 2 : 0); };
     if (lds_ok && (force_shape == 5 || force_shape == 6)) {
-        report(CRISP_KERNEL_LDS, force_shape == 6, 0, 0);
+        report(CRISP_KERNEL_LDS, lds_variant(force_shape == 6), 0, 0);
         return launch_spmm_lds(a, g.B, bpr, force_shape == 6, st);
     }
     if (lds_ok && force_shape < 0 && hint && uniform_rows && prefer_lds(g, Ncol, bpr)) {
-        report(CRISP_KERNEL_LDS, bpr <= 1, 0, 0);
+        report(CRISP_KERNEL_LDS, lds_variant(bpr <= 1), 0, 0);
         return launch_spmm_lds(a, g.B, bpr, bpr <= 1, st);
+    }
+    // Block-rows of uneven length (forced shape 15; chosen for plain block pruning over the whole grid): the
+    // block list is dealt evenly to the waves
+    const bool bal_ok = !conv && (g.K % 16) == 0 && (Ncol % 4) == 0 && ld_wide <= ((int64_t)1 << 23) && g.Sb <= BAL_MAX_ROWS;
+    if (bal_ok && (force_shape == CRISP_SHAPE_BALANCED || (force_shape < 0 && !uniform_rows && g.Sb >= 2))) {
+        a.use_smf = 1;
+        const int key = g.n * 16 + g.m;
+        report(CRISP_KERNEL_BALANCED, 0, 0, g.n <= 2);
+        switch (key) {
+            case 1 * 16 + 4: return launch_balanced_nm<1, 4>(a, g.B, st);
+            case 2 * 16 + 4: return launch_balanced_nm<2, 4>(a, g.B, st);
+            case 3 * 16 + 4: return launch_balanced_nm<3, 4>(a, g.B, st);
+            case 4 * 16 + 4: return launch_balanced_nm<4, 4>(a, g.B, st);
+            case 1 * 16 + 8: return launch_balanced_nm<1, 8>(a, g.B, st);
+            case 2 * 16 + 8: return launch_balanced_nm<2, 8>(a, g.B, st);
+            case 4 * 16 + 8: return launch_balanced_nm<4, 8>(a, g.B, st);
+            case 8 * 16 + 8: return launch_balanced_nm<8, 8>(a, g.B, st);
+            default: break;
+        }
     }
     // forced shapes 7..10: shapes 0..3 of the register kernels with the sparse matrix-core instruction
     // (the automatic choice always takes it where the pattern is eligible: it was faster for every

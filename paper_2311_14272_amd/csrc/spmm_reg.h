@@ -666,11 +666,12 @@ struct BlockBody {
     __device__ static __forceinline__ void run(f32x16 (&acc)[RT][NACC], xvec_t (&xr)[KS][8],
                                                uint32_t (&av)[RT][KS][F::VW], uint32_t (&aw)[RT][F::WPR], XCtx& cx,
                                                const SpmmArgs& p, const ConvPos& cp, uint32_t a_off, uint32_t i_off,
-                                               uint32_t aw_sh, int t_next) {
+                                               uint32_t aw_sh, int t_next, int bj_known = -1) {
+        // bj_known: block column of block t_next when the caller already holds it (else it is read here)
         int bj_next = 0;
         XCtx nx = cx;
         if constexpr (PREFETCH) {
-            bj_next = p.col_idx[t_next];
+            bj_next = bj_known >= 0 ? bj_known : p.col_idx[t_next];
             if constexpr (CONV != 0) nx = conv_ctx(p, cp, bj_next);
         }
         // drop the other half-wave's position bits: bit 0 of ws is this lane's first slot

@@ -138,7 +138,7 @@ def test_spmm_from_oracle_pack(L):
     check_product(Y, Yref, Aref, crisp.Y_F32, L.name)
 
 
-@pytest.mark.parametrize("shape", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
+@pytest.mark.parametrize("shape", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 15])
 @pytest.mark.parametrize("L", synth.small_cases(), ids=lambda L: L.name)
 def test_every_launch_shape(L, shape):
     """Each launch shape of the product (wide / narrow strips, 4- and 8-way split of the block
@@ -311,7 +311,7 @@ def test_bf16_output_is_rounded_fp32_output():
         Xp = np.zeros((L.K, ldx), dtype=np.uint16)
         Xp[:, : L.Ncol] = X
         dX = dev(Xp)
-        for shape in (0, 1, 2, 4, 7, 9):
+        for shape in (0, 1, 2, 4, 7, 9, 15):
             y32 = run_spmm(layer, dX, L.Ncol, ldx, crisp.Y_F32, L.S, shape=shape).astype(np.float32)
             y16 = run_spmm(layer, dX, L.Ncol, ldx, crisp.Y_BF16, L.S, shape=shape).astype(np.float32)
             assert (synth.f32_to_bf16_bits(y16) == synth.f32_to_bf16_bits(y32)).all(), (L.name, shape)
@@ -720,7 +720,7 @@ def test_maximum_row_stride_of_x():
     ldx = 1 << 27
     dX = torch.zeros((L.K, ldx), dtype=torch.int16, device="cuda")
     dX[:, : L.Ncol] = dev(X)
-    for shape in (None, 0, 1, 2, 4, 5, 6, 8, 13):
+    for shape in (None, 0, 1, 2, 4, 5, 6, 8, 13, 15):
         print("wide ldx shape", shape, flush=True)
         for yd in (crisp.Y_F32, crisp.Y_BF16):
             Y = run_spmm(layer, dX, L.Ncol, ldx, yd, L.S, shape=shape)
