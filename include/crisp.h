@@ -58,7 +58,11 @@ enum {
     CRISP_LAYER_TOPK = 1   /* plain block pruning over the whole grid; rows may be uneven   */
 };
 
-enum { CRISP_X_KN = 0 };               /* X layout: K rows, columns contiguous              */
+enum {
+    CRISP_X_KN = 0,   /* X is K x ldx, columns contiguous; Y is S x ldy                                       */
+    CRISP_X_K8 = 1    /* octet-interleaved: X is [K/8][ldx][8] (X8[k/8][j][k%8] = X[k][j]) and Y is written
+                         the same way, [S/8][ldy][8], so that a layer's output is the next layer's operand   */
+};
 enum { CRISP_Y_F32 = 0, CRISP_Y_BF16 = 1 };
 enum { CRISP_ACT_CBHW = 0 };           /* activation layout: [C][batch][H][W], W contiguous */
 
@@ -258,7 +262,12 @@ CRISP_API crisp_status crisp_im2col(const crisp_conv_desc *conv, const uint16_t 
  * touched, neither their weights nor the X rows only they would need.
  *   row_ptr/col_idx/vals/idx_words: output of crisp_pack (device).
  *   X: K x ldx bf16 (device), Ncol used columns, ldx >= Ncol, ldx % 8 == 0; the
- *      allocation must cover K*ldx elements.  x_layout = CRISP_X_KN.
+ *      allocation must cover K*ldx elements.  x_layout = CRISP_X_KN, or CRISP_X_K8 for
+ *      operands interleaved in octets of rows: X as [K/8][ldx][8], Y (and an epilogue's
+ *      residual) as [S/8][ld][8], which makes every matrix-core operand one 16-byte load
+ *      and every store of a wave 512 contiguous bytes.  CRISP_X_K8 needs K % 16 == 0,
+ *      S % 8 == 0, B in {32, 64}, n:m in {1..4}:4 or {1,2,4,8}:8, ldx <= 2^26, ldy and a
+ *      residual's stride <= 2^23 (EUNSUPPORTED otherwise: there is no other kernel for it).
  *   Y: S x ldy, fp32 or bf16 per y_dtype (device), ldy >= Ncol, ldy % 8 == 0.
  *      Every element Y[0..S)[0..Ncol) is written (rows of empty block-rows get 0).
  *   Ncol, ldx and ldy may be up to 2^27 (ESHAPE beyond); with ldy above 2^23 the
@@ -269,7 +278,7 @@ CRISP_API crisp_status crisp_im2col(const crisp_conv_desc *conv, const uint16_t 
  *   correctness.
  *   ws, ws_bytes: reserved (spmm_ws_bytes is 0); both are ignored.  Results of the launch
  *   shapes the library may choose agree within the summation-order tolerance.
- * Errors: EINVAL, ESHAPE, EALIGN, EUNSUPPORTED (x_layout), EDEVICE.
+ * Errors: EINVAL, ESHAPE, EALIGN, EUNSUPPORTED (x_layout and what it covers), EDEVICE.
  */
 CRISP_API crisp_status crisp_spmm(const crisp_layer_desc *desc, const int32_t *row_ptr, const int32_t *col_idx,
                         const uint16_t *vals, const uint32_t *idx_words, const uint16_t *X,
@@ -365,7 +374,8 @@ enum {
 };
 enum {
     CRISP_KERNEL_REG = 1, CRISP_KERNEL_GENERIC = 2, CRISP_KERNEL_LDS = 3, CRISP_KERNEL_XRES = 4,
-    CRISP_KERNEL_CONV_LDS = 5, CRISP_KERNEL_CONV_PATCH = 6, CRISP_KERNEL_B16 = 7, CRISP_KERNEL_BALANCED = 8
+    CRISP_KERNEL_CONV_LDS = 5, CRISP_KERNEL_CONV_PATCH = 6, CRISP_KERNEL_B16 = 7, CRISP_KERNEL_BALANCED = 8,
+    CRISP_KERNEL_K8 = 9
 };
 CRISP_API crisp_status crisp_spmm_forced(const crisp_layer_desc *desc, const int32_t *row_ptr, const int32_t *col_idx,
                                const uint16_t *vals, const uint32_t *idx_words, const uint16_t *X,

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(HERE, "libcrisp.so")
 OK, EINVAL, ESHAPE, EBUFSIZE, EALIGN, EUNSUPPORTED, EDEVICE = range(7)
 SAL_GIVEN, SAL_GRAD, SAL_MAG = 0, 1, 2
 ROW_UNIFORM, LAYER_TOPK = 0, 1
-X_KN = 0
+X_KN, X_K8 = 0, 1
 Y_F32, Y_BF16 = 0, 1
 ACT_CBHW = 0
 
@@ -234,7 +234,7 @@ def crisp_conv_spmm_ep(desc, conv: ConvDesc, row_ptr, col_idx, vals, idx_words, 
 
 
 SHAPE_AUTO = -1
-KERNEL_FAMILIES = {1: "reg", 2: "generic", 3: "lds", 4: "xres", 5: "conv_lds", 6: "conv_patch", 7: "b16", 8: "balanced"}
+KERNEL_FAMILIES = {1: "reg", 2: "generic", 3: "lds", 4: "xres", 5: "conv_lds", 6: "conv_patch", 7: "b16", 8: "balanced", 9: "k8"}
 
 
 def crisp_spmm_forced(desc, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, Y, ldy, y_dtype, ep=None, shape=SHAPE_AUTO,

@@ -21,6 +21,7 @@
 #include "spmm_xres.h"
 #include "conv_patch.h"
 #include "spmm_balanced.h"
+#include "spmm_k8.h"
 
 namespace crisp {
 
@@ -375,6 +376,8 @@ template <int N, int M>
 hipError_t launch_conv_patch_nm(const SpmmArgs& a, const ConvPatchSched& s, int batch, hipStream_t st);
 template <int N, int M>
 hipError_t launch_balanced_nm(const SpmmArgs& a, int B, hipStream_t st);
+template <int N, int M>
+hipError_t launch_k8_nm(const SpmmArgs& a, int B, hipStream_t st);
 
 #define CRISP_INSTANTIATE_NM(N, M)                                                           \
     template <>                                                                              \
@@ -393,6 +396,10 @@ hipError_t launch_balanced_nm(const SpmmArgs& a, int B, hipStream_t st);
     template <>                                                                              \
     hipError_t launch_balanced_nm<N, M>(const SpmmArgs& a, int B, hipStream_t st) {          \
         return launch_balanced<N, M>(a, B, st);                                              \
+    }                                                                                        \
+    template <>                                                                              \
+    hipError_t launch_k8_nm<N, M>(const SpmmArgs& a, int B, hipStream_t st) {                \
+        return launch_k8<N, M>(a, B, st);                                                    \
     }
 
 }  // namespace crisp

@@ -330,15 +330,22 @@ static crisp_status spmm_impl(const crisp_layer_desc* desc, const int32_t* row_p
     if (misaligned(row_ptr, 4) || misaligned(col_idx, 4) || misaligned(vals, 16) || misaligned(idx_words, 16) ||
         misaligned(X, 16) || misaligned(Y, 16))
         return CRISP_EALIGN;
-    if (x_layout != CRISP_X_KN) return CRISP_EUNSUPPORTED;
+    if (x_layout != CRISP_X_KN && x_layout != CRISP_X_K8) return CRISP_EUNSUPPORTED;
     { crisp_status es = check_epilogue(ep, Ncol); if (es != CRISP_OK) return es; }
+    if (x_layout == CRISP_X_K8) {
+        // what the octet-interleaved kernels cover (there is no other path for this layout)
+        const bool pattern_ok = (g.m == 4 && g.n <= 4) || (g.m == 8 && (g.n == 1 || g.n == 2 || g.n == 4 || g.n == 8));
+        if (g.B == 16 || (g.K % 16) != 0 || (g.S % 8) != 0 || !pattern_ok || ldx > ((int64_t)1 << 26) || ldy > ((int64_t)1 << 23) ||
+            (ep && ep->residual && ep->ldr > ((int64_t)1 << 23)))
+            return CRISP_EUNSUPPORTED;
+    }
     // shapes of the plain product that may be forced (anything else: the automatic choice)
     if (!((force_shape >= 0 && force_shape <= 10) || force_shape == CRISP_SHAPE_XRES || force_shape == CRISP_SHAPE_BALANCED))
         force_shape = -1;
     hipError_t e = launch_spmm(g, desc->block_density, desc->select_mode == CRISP_ROW_UNIFORM, force_shape, row_ptr, col_idx, vals,
                                idx_words, X, nullptr, Ncol,
                                ldx, Y, ldy, y_dtype, ep, (hipEvent_t)ev_start, (hipEvent_t)ev_stop, (hipStream_t)stream,
-                               kernel_code);
+                               kernel_code, x_layout);
     return e == hipSuccess ? CRISP_OK : CRISP_EDEVICE;
 }
 

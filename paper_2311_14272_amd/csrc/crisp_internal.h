@@ -42,7 +42,8 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
                        const int32_t* col_idx, const uint16_t* vals, const uint32_t* idxw, const uint16_t* X,
                        const crisp_conv_desc* conv, int64_t Ncol, int64_t ldx, void* Y, int64_t ldy, int y_dtype,
                        const crisp_epilogue* ep,
-                       hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st, int32_t* kernel_code = nullptr);
+                       hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st, int32_t* kernel_code = nullptr,
+                       int x_layout = CRISP_X_KN);
 
 // Whether launch_spmm would run this convolution with the input patch staged in LDS (host only).
 bool conv_lds_would_run(const Geometry& g, double density_hint, const crisp_conv_desc& conv, int64_t Ncol);

@@ -375,6 +375,14 @@ template <> hipError_t launch_conv_patch_nm<1, 8>(const SpmmArgs&, const ConvPat
 template <> hipError_t launch_conv_patch_nm<2, 8>(const SpmmArgs&, const ConvPatchSched&, int, hipStream_t);
 template <> hipError_t launch_conv_patch_nm<4, 8>(const SpmmArgs&, const ConvPatchSched&, int, hipStream_t);
 template <> hipError_t launch_conv_patch_nm<8, 8>(const SpmmArgs&, const ConvPatchSched&, int, hipStream_t);
+template <> hipError_t launch_k8_nm<1, 4>(const SpmmArgs&, int, hipStream_t);
+template <> hipError_t launch_k8_nm<2, 4>(const SpmmArgs&, int, hipStream_t);
+template <> hipError_t launch_k8_nm<3, 4>(const SpmmArgs&, int, hipStream_t);
+template <> hipError_t launch_k8_nm<4, 4>(const SpmmArgs&, int, hipStream_t);
+template <> hipError_t launch_k8_nm<1, 8>(const SpmmArgs&, int, hipStream_t);
+template <> hipError_t launch_k8_nm<2, 8>(const SpmmArgs&, int, hipStream_t);
+template <> hipError_t launch_k8_nm<4, 8>(const SpmmArgs&, int, hipStream_t);
+template <> hipError_t launch_k8_nm<8, 8>(const SpmmArgs&, int, hipStream_t);
 template <> hipError_t launch_balanced_nm<1, 4>(const SpmmArgs&, int, hipStream_t);
 template <> hipError_t launch_balanced_nm<2, 4>(const SpmmArgs&, int, hipStream_t);
 template <> hipError_t launch_balanced_nm<3, 4>(const SpmmArgs&, int, hipStream_t);
@@ -486,7 +494,8 @@ bool conv_lds_would_run(const Geometry& g, double density_hint, const crisp_conv
 hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows, int force_shape, const int32_t* row_ptr,
                        const int32_t* col_idx, const uint16_t* vals, const uint32_t* idxw, const uint16_t* X,
                        const crisp_conv_desc* conv, int64_t Ncol, int64_t ldx, void* Y, int64_t ldy, int y_dtype,
-                       const crisp_epilogue* ep, hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st, int32_t* kernel_code) {
+                       const crisp_epilogue* ep, hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st, int32_t* kernel_code,
+                       int x_layout) {
     // what ran, for callers that ask: family | shape << 8 | conv_mode << 16 | sparse << 24
     auto report = [&](int family, int shape, int conv_mode, int sparse) {
         if (kernel_code) *kernel_code = family | (shape << 8) | (conv_mode << 16) | (sparse << 24);
@@ -510,6 +519,22 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
         a.act = X;
         a.X = nullptr;
         fill_conv_args(a, g, *conv);
+    }
+    if (x_layout == CRISP_X_K8) {
+        // octet-interleaved operands: one kernel family (the caller has checked what it covers)
+        a.use_smf = 1;
+        report(CRISP_KERNEL_K8, 1, 0, g.n <= 2);
+        switch (g.n * 16 + g.m) {
+            case 1 * 16 + 4: return launch_k8_nm<1, 4>(a, g.B, st);
+            case 2 * 16 + 4: return launch_k8_nm<2, 4>(a, g.B, st);
+            case 3 * 16 + 4: return launch_k8_nm<3, 4>(a, g.B, st);
+            case 4 * 16 + 4: return launch_k8_nm<4, 4>(a, g.B, st);
+            case 1 * 16 + 8: return launch_k8_nm<1, 8>(a, g.B, st);
+            case 2 * 16 + 8: return launch_k8_nm<2, 8>(a, g.B, st);
+            case 4 * 16 + 8: return launch_k8_nm<4, 8>(a, g.B, st);
+            case 8 * 16 + 8: return launch_k8_nm<8, 8>(a, g.B, st);
+            default: return hipErrorInvalidValue;
+        }
     }
     if (g.B == 16) { report(CRISP_KERNEL_B16, 0, 0, 0); return launch_b16(a, st); }
     // convolution with the input patch staged in LDS (forced shape 12)

@@ -412,7 +412,7 @@ constexpr bool smf_pattern() { return N <= 2; }
 template <int N, int M, int B, int WD, bool PREFETCH, int CONV, bool SMF = false>
 struct BlockBody {
     typedef Fmt<N, M, B> F;
-    static constexpr int XW = CONV >= 2 ? 2 : WD;    // registers per loaded X row
+    static constexpr int XW = (CONV >= 2 && CONV <= 4) ? 2 : WD;    // registers per loaded X row
     typedef typename XVec<XW>::type xvec_t;
     static constexpr int RT = F::RT, KS = F::KS, NACC = 2 * WD;
 
@@ -486,7 +486,18 @@ struct BlockBody {
     // rows instead (finite values times the zero padding of the packed block).
     __device__ static __forceinline__ void load_x(xvec_t (&dst)[8], const SpmmArgs& p, const ConvPos& cp,
                                                    uint32_t lane_off, uint32_t lane_off2, int bj, int ks) {
-        if constexpr (CONV == 3) {
+        if constexpr (CONV == 5) {
+            // octet-interleaved X, [K/8][ldx][8]: the 8 K-values a lane feeds to the matrix core for one column
+            // are 16 consecutive bytes.  dst[0..3] = operand of the lane's first column (offset lane_off),
+            // dst[4..7] = of its second (lane_off2); the lane's half hh is part of both offsets.
+            static_assert(WD == 1, "two columns per lane");
+            const int kb = min(bj * B + ks * 16, p.K - 16);
+            const rsrc_t r = make_rsrc(p.X + (int64_t)(kb >> 3) * p.ldx * 8);
+            const u32x4 t0 = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(r, lane_off, 0, 0));
+            const u32x4 t1 = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(r, lane_off2, 0, 0));
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { dst[i] = t0[i]; dst[4 + i] = t1[i]; }
+        } else if constexpr (CONV == 3) {
             // K-row k = tap*C + c with tap = a*kw + b, per row; lane_off / lane_off2 are the element
             // offsets of the two columns' window origins (oh*stride - pad, ow*stride - pad) inside a
             // channel plane, cp.half_off holds hh*8 here (rows, not bytes)
@@ -589,7 +600,10 @@ struct BlockBody {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 // v_perm_b32: result bytes picked from {r1 (bytes 4..7), r0 (bytes 0..3)}
-                if constexpr (CONV >= 2) {
+                if constexpr (CONV == 5) {
+                    lo[q] = xd[q][0];           // loaded in operand form
+                    hi[q] = xd[4 + q][0];
+                } else if constexpr (CONV >= 2) {
                     // register 0 of a row holds the first column's element, register 1 the second's
                     lo[q] = __builtin_amdgcn_perm(xd[2 * q + 1][0], xd[2 * q][0], cur.sel_lo);
                     hi[q] = __builtin_amdgcn_perm(xd[2 * q + 1][1], xd[2 * q][1], cur.sel_hi);
@@ -631,7 +645,10 @@ struct BlockBody {
                 u32x4 lo, hi;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    if constexpr (CONV >= 2) {
+                    if constexpr (CONV == 5) {
+                        lo[q] = xd[q][0];
+                        hi[q] = xd[4 + q][0];
+                    } else if constexpr (CONV >= 2) {
                         lo[q] = __builtin_amdgcn_perm(xd[2 * q + 1][0], xd[2 * q][0], cur.sel_lo);
                         hi[q] = __builtin_amdgcn_perm(xd[2 * q + 1][1], xd[2 * q][1], cur.sel_hi);
                     } else {
@@ -672,7 +689,7 @@ struct BlockBody {
         XCtx nx = cx;
         if constexpr (PREFETCH) {
             bj_next = bj_known >= 0 ? bj_known : p.col_idx[t_next];
-            if constexpr (CONV != 0) nx = conv_ctx(p, cp, bj_next);
+            if constexpr (CONV != 0 && CONV != 5) nx = conv_ctx(p, cp, bj_next);
         }
         // drop the other half-wave's position bits: bit 0 of ws is this lane's first slot
         uint32_t ws[RT][F::WPR];

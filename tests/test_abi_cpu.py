@@ -134,7 +134,11 @@ def test_entry_points_reject_bad_arguments_without_a_device():
     assert spmm(N=60, ldx=60, ldy=64) == crisp.EALIGN
     assert spmm(ldy=100, N=64) == crisp.EALIGN
     assert spmm(yd=3) == crisp.EINVAL
-    assert spmm(xl=1) == crisp.EUNSUPPORTED
+    assert spmm(xl=2) == crisp.EUNSUPPORTED
+    # octet-interleaved operands: S must be a multiple of 8, K of 16, no 16 x 16 blocks
+    assert spmm(xl=1, d=crisp.layer_desc(60, 128, 2, 4, 32, 0.5)) == crisp.EUNSUPPORTED
+    assert spmm(xl=1, d=crisp.layer_desc(64, 136, 2, 4, 32, 0.5)) == crisp.EUNSUPPORTED
+    assert spmm(xl=1, d=crisp.layer_desc(64, 128, 2, 4, 16, 0.5)) == crisp.EUNSUPPORTED
     assert spmm(Y=fake + 4) == crisp.EALIGN
     # the reserved workspace arguments select nothing: a stale size with ws == NULL is validated like any other call
     assert L.crisp_spmm(C.byref(d), fake, fake, fake, fake, None, 64, 64, 0, fake, 64, 0, None, 5, None) == crisp.EINVAL
