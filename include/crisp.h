@@ -294,10 +294,10 @@ CRISP_API crisp_status crisp_spmm(const crisp_layer_desc *desc, const int32_t *r
  * S x ldy with Ncol = batch*Ho*Wo columns written.
  * Covered: Ncol even, B in {32, 64}, n:m in {1..4}:4 or {1,2,4,8}:8, kw <= 16,
  * kh*kw <= 64, stride <= 16, batch*H*W <= 2^27, ldy <= 2^23.  With C % B == 0 every block
- * column belongs to one filter tap: for stride 1 and even Wo a lane's two output columns
- * come from one 4-byte load, for a 1x1 filter with stride 2, no padding and even W and Wo
- * from one 8-byte load, otherwise (strided, odd Wo) each column is located and loaded on
- * its own.  Other channel counts (the first layer of a network):
+ * column belongs to one filter tap: for stride 1 and either an even Wo or padding (k-1)/2
+ * in both directions a lane's two output columns come from one 4-byte load, for a 1x1 filter
+ * with stride 2, no padding and even W and Wo from one 8-byte load, otherwise each column is
+ * located and loaded on its own.  Other channel counts (the first layer of a network):
  * every K-row is split into (tap, channel) on its own; needs K <= 65535 and an activation
  * below 4 GiB.  For stride <= 4, C % 64 == 0, 64x64 blocks, even W <= 64 and even Wo there is also
  * a kernel that stages the input patch of a tile of output rows in LDS once for all filter

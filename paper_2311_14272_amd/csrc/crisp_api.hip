@@ -484,7 +484,8 @@ static crisp_status conv_plan_impl(const crisp_layer_desc* desc, const crisp_con
     if (!pointwise && fused_lowering_covers(*g, *conv, Ncol, plane)) {
         const double gathers = (double)g->Sb * desc->block_density;   // kept blocks per block column of X
         const bool aligned = conv->C % g->B == 0;
-        const bool paired = conv->stride == 1 && (Wo & 1) == 0 && conv->W >= 2 && aligned;
+        const bool same_pad = conv->kh == 2 * conv->pad + 1 && conv->kw == 2 * conv->pad + 1;
+        const bool paired = conv->stride == 1 && ((Wo & 1) == 0 || same_pad) && conv->W >= 2 && Wo >= 2 && aligned;
         const bool strided_1x1 = conv->kh == 1 && conv->kw == 1 && conv->stride == 2 && conv->pad == 0 && (conv->W & 1) == 0 &&
                                  (Wo & 1) == 0 && aligned;
         if ((strided_1x1 && gathers <= STRIDED_1X1_MAX_GATHER) || paired ||

@@ -465,8 +465,12 @@ static void fill_conv_args(SpmmArgs& a, const Geometry& g, const crisp_conv_desc
     a.C = conv.C; a.H = conv.H; a.W = conv.W; a.kw = conv.kw; a.pad = conv.pad; a.stride = conv.stride;
     a.Ho = (conv.H + 2 * conv.pad - conv.kh) / conv.stride + 1;
     a.Wo = (conv.W + 2 * conv.pad - conv.kw) / conv.stride + 1;
-    // neighbours in a row from one dword when that is possible, else column by column
-    a.conv_mode = (conv.stride == 1 && (a.Wo & 1) == 0 && conv.W >= 2) ? 1 : 2;
+    // a lane's two columns from one dword when their sources are neighbours in memory (stride 1 and either an
+    // even output width, so that a pair never leaves its output row, or padding (k - 1) / 2 in both directions,
+    // so that consecutive output positions read consecutive input elements even across rows and images), else
+    // column by column
+    const bool same_pad = conv.kh == 2 * conv.pad + 1 && conv.kw == 2 * conv.pad + 1;
+    a.conv_mode = (conv.stride == 1 && ((a.Wo & 1) == 0 || same_pad) && conv.W >= 2 && a.Wo >= 2) ? 1 : 2;
     if (conv.kh == 1 && conv.kw == 1 && conv.stride == 2 && conv.pad == 0 && (conv.W & 1) == 0 && (a.Wo & 1) == 0)
         a.conv_mode = 4;                       // strided 1x1: both columns from one 8-byte piece of the input row
     if (conv.C % g.B != 0) a.conv_mode = 3;   // block columns span filter taps: every K-row on its own

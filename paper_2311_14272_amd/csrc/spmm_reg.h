@@ -49,8 +49,8 @@ struct SpmmArgs {
     void* Y;
     int y_bf16;
     // implicit lowering (conv mode): X is not materialised; its rows are read from the activation
-    // [C][batch][H][W], C % B == 0.  conv_mode 1: stride 1 and even Wo, a lane's two output columns
-    // are neighbours in a row and come from one dword.  conv_mode 2: any stride and Wo, the two
+    // [C][batch][H][W], C % B == 0.  conv_mode 1: stride 1 and (even Wo, or padding (k-1)/2 in both
+    // directions): the sources of a lane's two output columns are neighbours in memory and come from one dword.  conv_mode 2: any stride and Wo, the two
     // columns are located independently and loaded with one 2-byte load each.  conv_mode 4: 1x1 filter
     // with stride 2 (no padding, even W and Wo): the two columns come from one 8-byte load.  conv_mode 3: any C
     // (a block column may span several filter taps): like 2, and in addition every K-row is split
@@ -463,19 +463,31 @@ struct BlockBody {
             c.sel_hi = v1 ? SEL_LO : SEL_ZERO;
             return c;
         }
+        // The lane's second column is the next output position, which may lie in the next output row or
+        // image (odd Wo).  The host picks this mode only where the two sources are then still neighbours in
+        // memory when both are inside the image: always inside one output row, and across rows and images
+        // when the padding is (k - 1) / 2 in both directions (then consecutive output positions read
+        // consecutive input elements for every tap).
         const int ih = cp.oh + a - p.pad, iw = cp.ow + b - p.pad;
-        const bool vr = (unsigned)ih < (unsigned)p.H;
-        const bool v0 = vr && (unsigned)iw < (unsigned)p.W;
-        const bool v1 = vr && (unsigned)(iw + 1) < (unsigned)p.W;
+        const int ih1 = cp.oh1 + a - p.pad, iw1 = cp.ow1 + b - p.pad;
+        const bool v0 = (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
+        const bool v1 = (unsigned)ih1 < (unsigned)p.H && (unsigned)iw1 < (unsigned)p.W;
         const int centre = (cp.img * p.H + cp.oh) * p.W + cp.ow;
         const int src = (cp.img * p.H + ih) * p.W + iw;
+        const int src1 = (cp.img1 * p.H + ih1) * p.W + iw1;
         XCtx c;
         int off = centre;
         c.sel_lo = SEL_ZERO;
         c.sel_hi = SEL_ZERO;
         if (v0 && v1) { off = src; c.sel_lo = SEL_LO; c.sel_hi = SEL_HI; }
-        else if (v1) { off = src + 1; c.sel_hi = SEL_LO; }   // loaded (e0, e1): column 1 <- e0
-        else if (v0) { off = src - 1; c.sel_lo = SEL_HI; }   // loaded (e[W-2], e[W-1]): column 0 <- e[W-1]
+        else if (v1) {
+            // loaded (e0, e1) at the second column's source: column 1 <- e0; at the very end of a channel
+            // plane the dword one element earlier is loaded instead and column 1 <- e1
+            const bool last = (int64_t)src1 + 1 >= p.plane;
+            off = last ? src1 - 1 : src1;
+            c.sel_hi = last ? SEL_HI : SEL_LO;
+        }
+        else if (v0) { off = src - 1; c.sel_lo = SEL_HI; }   // loaded (e[src-1], e[src]): column 0 <- e[src]
         c.off = cp.half_off + (uint32_t)off * 2u;
         c.off2 = 0u;
         return c;

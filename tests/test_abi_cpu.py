@@ -182,7 +182,9 @@ def test_lowering_choice_on_resnet50_shapes():
     assert pick(cs(256, 14, 14, 8, 3, 3, 1, 1), 256, 0.9) == "fused"          # stride 1, even width: paired loads
     assert pick(cs(128, 56, 56, 8, 3, 3, 2, 1), 128, 0.25) == "fused"         # strided, few gathers per block column
     assert pick(cs(256, 28, 28, 8, 3, 3, 2, 1), 256, 0.70) == "fused"         # strided, dense block-rows: staged in LDS
-    assert pick(cs(512, 14, 14, 8, 3, 3, 2, 1), 512, 0.70) == "im2col"        # odd output width, many gathers per block column
+    assert pick(cs(512, 14, 14, 8, 3, 3, 2, 1), 512, 0.70) == "im2col"        # strided, odd output width, many gathers per block column
+    assert pick(cs(512, 7, 7, 8, 3, 3, 1, 1), 512, 0.70) == "fused"           # stride 1, odd width, padding (k-1)/2: paired loads
+    assert pick(cs(512, 9, 9, 8, 3, 3, 1, 0), 512, 0.70) == "im2col"          # stride 1, odd width, no padding: column by column
     assert pick(cs(256, 56, 56, 8, 1, 1, 2, 0), 512, 0.5) == "fused"          # 1x1 stride 2, few gathers per block column
     assert pick(cs(512, 28, 28, 8, 1, 1, 2, 0), 1024, 0.66) == "im2col"       # 1x1 stride 2, many: nothing inflated to save
     assert pick(cs(3, 224, 224, 8, 7, 7, 2, 3), 64, 0.5) == "fused"           # first layer: one block-row

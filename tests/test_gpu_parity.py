@@ -343,6 +343,18 @@ CONV_CASES = [
     (32, 11, 10, 2, 5, 5, 2, 64, 3, 4, 32, 0.5, 3),
     (128, 14, 14, 4, 3, 3, 1, 128, 2, 4, 64, 0.4, 2),
     (64, 14, 14, 6, 1, 1, 0, 128, 1, 8, 64, 0.5, 2),
+    # stride 1, odd output width, padding (k-1)/2: a lane's column pair may straddle output rows and images, yet
+    # its two sources stay neighbours in memory (one dword); all-border images, 5x5 and 1x1 filters, last pair at
+    # the very end of the channel plane
+    (128, 7, 7, 4, 3, 3, 1, 128, 2, 4, 64, 0.5, 1),
+    (64, 3, 3, 6, 3, 3, 1, 64, 4, 8, 64, 1.0, 1),
+    (64, 5, 5, 2, 5, 5, 2, 64, 1, 4, 64, 0.6, 1),
+    (64, 7, 9, 2, 1, 1, 0, 128, 2, 4, 64, 0.7, 1),
+    (32, 5, 7, 2, 3, 3, 1, 64, 3, 4, 32, 0.6, 1),
+    (512, 7, 7, 8, 3, 3, 1, 128, 1, 4, 64, 0.3, 1),
+    # stride 1, odd output width, other paddings: the pair's sources are not neighbours across rows
+    (64, 9, 9, 2, 3, 3, 0, 64, 2, 4, 64, 0.6, 1),
+    (64, 7, 7, 2, 3, 3, 2, 64, 2, 8, 64, 0.6, 1),
     # strided 1x1 with even W and Wo: both columns of a lane from one 8-byte piece of the input row
     (128, 12, 12, 3, 1, 1, 0, 192, 2, 8, 64, 0.5, 2),
     (64, 8, 16, 2, 1, 1, 0, 96, 4, 8, 32, 0.6, 2),
