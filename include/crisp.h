@@ -232,7 +232,7 @@ typedef struct {
 /*
  * crisp_select_pack for n_layers layers at once (Alg. 1 prunes all layers of a model in one
  * shot): layers that use the same kernel instantiation (block size, m, saliency kind, K a
- * multiple of B or not) share launches, up to 8 layers per launch pair, so that the small block
+ * multiple of B or not) share launches, up to 24 layers per launch pair, so that the small block
  * grids of single layers together fill the GPU.  Results per layer are exactly those of
  * crisp_select_pack.  descs and bufs are host arrays of n_layers elements (1 <= n_layers <=
  * 4096); the layers' buffers must not overlap.  All arguments are checked before anything is

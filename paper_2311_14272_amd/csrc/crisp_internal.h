@@ -28,7 +28,7 @@ struct SelPackPtrs {
     const uint16_t* W; const float* TG; uint32_t* nm_mask; int32_t* row_ptr; int32_t* col_idx; double* score;
     uint16_t* vals; uint32_t* idxw; int32_t* flags; void* stage;
 };
-#define CRISP_SELECT_BATCH 8   // layers per launch pair of launch_select_pack_batch
+#define CRISP_SELECT_BATCH 24  // layers per launch pair of launch_select_pack_batch (the batch travels in the kernel arguments: 3.7 of 4 KB)
 hipError_t launch_select_pack_batch(int n, const Geometry* g, int sal_kind, const SelPackPtrs* pp, hipStream_t st);
 hipError_t launch_pack(const Geometry& g, int select_mode, const uint16_t* W, const uint32_t* nm_mask,
                        const int32_t* row_ptr, const int32_t* col_idx, uint16_t* vals, uint32_t* idxw,
