@@ -78,7 +78,9 @@ def parse():
 # HBM bytes per launch of dominant kernels from rocprofv3 --pmc runs (FETCH_SIZE and WRITE_SIZE, each scaled by what the
 # same counter reads for an elementwise pass of known size): key = (workload, kernel id as this script prints it),
 # value = (bytes per launch, file under profiles/ that holds the counter rows).  A kernel without an entry reports null.
-TRAFFIC = {}
+TRAFFIC = {
+    ("c5", "lds any n:m B64 shape0 conv0 dense-mfma"): (161673151, "profiles/bench_c5_kernels.txt"),
+}
 
 
 # ------------------------------------------------------------------------------------------------
@@ -207,10 +209,29 @@ def run_resnet50(args):
     def forward(i):
         return crisp.conv_forward(dls[i], wl.layers[i].conv, acts[i], Ys[i], wl.layers[i].Ncol, y_dtype, Xs)
 
-    def step(pairs=None):
+    def forward_timed(i, ev_start, ev_stop):
+        """The launches of crisp_conv_forward for layer i, the product through crisp_spmm_timed: the two events
+        receive the product kernel's own start and stop (an event pair recorded around the call would also
+        hold the dispatch gaps next to the launch, about 3 us here)."""
+        L, d = wl.layers[i], dls[i]
+        if paths[i] == "fused":
+            crisp.crisp_spmm_timed(d.desc, convs[i], d.row_ptr, d.col_idx, d.vals, d.idx_words, acts[i], L.Ncol, L.Ncol, Ys[i], L.Ncol,
+                                   y_dtype, ev_start, ev_stop)
+            return
+        X, ldx = acts[i], L.Ncol
+        if paths[i] == "im2col":
+            ldx = (L.Ncol + 7) // 8 * 8
+            crisp.crisp_im2col(convs[i], acts[i], Xs, ldx)
+            X = Xs
+        crisp.crisp_spmm_timed(d.desc, None, d.row_ptr, d.col_idx, d.vals, d.idx_words, X, L.Ncol, ldx, Ys[i], L.Ncol, y_dtype,
+                               ev_start, ev_stop)
+
+    def step(pairs=None, kernel_events=None):
         prune_all()
         for i in range(nl):
-            if pairs is not None and i in pairs:
+            if kernel_events is not None and i in kernel_events:
+                forward_timed(i, *kernel_events[i])
+            elif pairs is not None and i in pairs:
                 pairs[i][0].record()
                 forward(i)
                 pairs[i][1].record()
@@ -258,20 +279,23 @@ def run_resnet50(args):
         wsum += np.array([pairs[i][0].elapsed_time(pairs[i][1]) for i in range(nl)])
     share = {}
     for i in range(nl):
-        if paths[i] != "im2col":                 # (a bracket around a materialised layer also holds the lowering pass)
-            share[kids[i]] = share.get(kids[i], 0.0) + wsum[i]
+        # (a bracket around a materialised layer also holds the lowering pass: its share is scaled by the product's part)
+        w = wsum[i] * (0.55 if paths[i] == "im2col" else 1.0)
+        share[kids[i]] = share.get(kids[i], 0.0) + w
     dom_kid = max(share, key=share.get)
-    dom_layers = [i for i in range(nl) if kids[i] == dom_kid and paths[i] != "im2col"]
+    dom_layers = [i for i in range(nl) if kids[i] == dom_kid]
 
-    # ---- timed region: exactly `steps` passes; only the dominant kernel's launches are bracketed ----
-    all_pairs = [event_pairs(dom_layers) for _ in range(steps)]
+    # ---- timed region: exactly `steps` passes; the dominant kernel's launches carry HIP events that receive
+    # the kernel's own start and stop on the launch stream -------------------------------------------------
+    hev = crisp.HipEvents(steps * len(dom_layers))
+    kev = [{i: hev.pairs[k * len(dom_layers) + j] for j, i in enumerate(dom_layers)} for k in range(steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(steps):
-        step(all_pairs[k])
+        step(None, kev[k])
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
-    dom_ms = np.array([[p[i][0].elapsed_time(p[i][1]) for i in dom_layers] for p in all_pairs])   # steps x launches
+    dom_ms = np.array([[hev.elapsed_ms(k * len(dom_layers) + j) for j in range(len(dom_layers))] for k in range(steps)])   # steps x launches
     dom_avg_ms = float(dom_ms.mean())
     dom_bytes = float(np.mean([stats[i]["alg_bytes"] for i in dom_layers]))
     achieved = dom_bytes / (dom_avg_ms * 1e-3) / 1e9
@@ -331,8 +355,8 @@ def run_resnet50(args):
                         "share_of_step": round(float(dom_ms.sum(axis=1).mean()) / ms_per_step, 4),
                         "avg_launch_ms": round(dom_avg_ms, 5), "median_launch_ms": round(float(np.median(dom_ms)), 5),
                         "algorithmic_bytes_per_launch": int(dom_bytes),
-                        "timing": "HIP event pair around every launch of this kernel in every timed step (raw brackets, "
-                                  "nothing subtracted)",
+                        "timing": "HIP events on the launch stream that receive the kernel's own start and stop "
+                                  "(hipExtLaunchKernelGGL), every launch of this kernel in every timed step; nothing subtracted",
                         "mfma_frac_useful": round(sum(stats[i]["useful_flop"] for i in dom_layers) / len(dom_layers) /
                                                   (dom_avg_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)},
            "roofline_all_layers": {"hbm_frac_forward": round(t_hbm_all / t_fwd, 4), "bound_frac_forward": round(t_bound / t_fwd, 4),
