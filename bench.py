@@ -95,8 +95,10 @@ def kernel_id(code: int, L) -> str:
     """Readable name of the kernel instantiation a product launch ran (from the library's report)."""
     from paper_2311_14272_amd import crisp
     f = crisp.kernel_code_fields(code)
-    # (the LDS-resident, generic and 16 x 16 families are one compiled kernel for every pattern)
-    pattern = "any n:m" if f["family"] in ("lds", "generic", "b16") else "%d:%d" % (L.n, L.m)
+    # (the LDS-resident family with dense tiles, the generic and the 16 x 16 families are one compiled kernel for
+    # every pattern)
+    one_for_all = f["family"] in ("generic", "b16") or (f["family"] == "lds" and not f["sparse_mfma"])
+    pattern = "any n:m" if one_for_all else "%d:%d" % (L.n, L.m)
     return "%s %s B%d shape%d conv%d %s" % (f["family"], pattern, L.B, f["shape"], f["conv_mode"],
                                              "sparse-mfma" if f["sparse_mfma"] else "dense-mfma")
 

@@ -370,7 +370,9 @@ enum {
     CRISP_SHAPE_CONV_LDS = 12,   /* fused lowering with the input patch staged in LDS             */
     CRISP_SHAPE_XRES = 13,       /* K <= 128: X operands resident in registers                    */
     CRISP_SHAPE_CONV_PATCH = 14, /* fused lowering for channel counts that are no multiple of 64  */
-    CRISP_SHAPE_BALANCED = 15    /* block list dealt evenly to the waves (uneven block-rows)      */
+    CRISP_SHAPE_BALANCED = 15,   /* block list dealt evenly to the waves (uneven block-rows)      */
+    CRISP_SHAPE_LDS_SMF = 16,    /* block-row resident in LDS as sparse matrix-core operands      */
+    CRISP_SHAPE_LDS_SMF_30 = 17  /* ... always the instantiation that holds 30 blocks             */
 };
 enum {
     CRISP_KERNEL_REG = 1, CRISP_KERNEL_GENERIC = 2, CRISP_KERNEL_LDS = 3, CRISP_KERNEL_XRES = 4,

@@ -358,6 +358,8 @@ static hipError_t launch_b16(const SpmmArgs& a, hipStream_t st) {
 
 int lds_capacity(int B);
 hipError_t launch_spmm_lds(const SpmmArgs& a, int B, int max_blocks, bool wide, hipStream_t st);
+int lds_smf_capacity();
+hipError_t launch_spmm_lds_smf(const SpmmArgs& a, int max_blocks, int variant, hipStream_t st);
 
 template <> hipError_t launch_reg_nm<1, 4>(const SpmmArgs&, int, int, hipStream_t);
 template <> hipError_t launch_reg_nm<2, 4>(const SpmmArgs&, int, int, hipStream_t);
@@ -451,12 +453,24 @@ static int pick_shape(const Geometry& g, int64_t Ncol, int blocks_per_row, bool 
 // repeated often (long block-rows).
 static bool prefer_lds(const Geometry& g, int64_t Ncol, int blocks_per_row) {
     if (g.B != 64 || blocks_per_row > lds_capacity(g.B)) return false;
-    // 1:4 and 2:4 feed the sparse matrix core without any expansion; 1:8 and 2:8 need a little per
-    // block, which the LDS kernels still beat by a few percent on long rows
-    if (g.n <= 2 && (g.m == 4 || blocks_per_row < 12)) return false;
+    // patterns that feed the sparse matrix core need no (or little) expansion: the register kernels, or
+    // residency in that operand form (prefer_lds_smf), are faster
+    if (g.n <= 2) return false;
     const int64_t narrow = (int64_t)g.Sb * ((Ncol + 63) / 64);
     const int slots_per_operand = (8 / g.m) * g.n;
     return narrow >= 2048 && (slots_per_operand >= 4 || blocks_per_row >= 6);
+}
+
+// Block-rows resident in LDS as sparse matrix-core operands: a wave's loop then holds no requests for packed
+// slices at all.  Measured on the 1x1 layers of ResNet-50 at batch 256 and on the 512 x 4608 x 50176 2:8 layer
+// against the register kernels: 1.03-1.12x from six blocks per block-row on (1.15x on the latter, 18 blocks:
+// 117 vs 132-138 us), 0.85-1.0x for rows of one to three blocks (the expansion is not amortised); always the
+// 30-tile instantiation (one workgroup of eight waves per compute unit), which beat the 15-tile one (two
+// workgroups of four) on every layer with six or more blocks.
+static bool prefer_lds_smf(const Geometry& g, int64_t Ncol, int blocks_per_row) {
+    if (g.B != 64 || g.n > 2 || blocks_per_row < 6 || blocks_per_row > lds_smf_capacity()) return false;
+    const int64_t narrow = (int64_t)g.Sb * ((Ncol + 63) / 64);
+    return narrow >= 2048;
 }
 
 // Geometry of an implicitly lowered convolution as the product kernels want it (everything but the
@@ -592,6 +606,18 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
     if (lds_ok && (force_shape == 5 || force_shape == 6)) {
         report(CRISP_KERNEL_LDS, lds_variant(force_shape == 6), 0, 0);
         return launch_spmm_lds(a, g.B, bpr, force_shape == 6, st);
+    }
+    // the same with the blocks resident as sparse matrix-core operands (forced shapes 16 and 17, the latter
+    // always the 30-tile instantiation): 64 x 64 blocks, at most two kept values per group
+    const bool lds_smf_ok = lds_ok && g.B == 64 && g.n <= 2;
+    if (lds_smf_ok && (force_shape == CRISP_SHAPE_LDS_SMF || force_shape == CRISP_SHAPE_LDS_SMF_30)) {
+        const int variant = force_shape == CRISP_SHAPE_LDS_SMF ? 0 : 2;
+        report(CRISP_KERNEL_LDS, (variant == 2 || bpr > 14) ? 2 : 0, 0, 1);
+        return launch_spmm_lds_smf(a, bpr, variant, st);
+    }
+    if (lds_smf_ok && force_shape < 0 && hint && uniform_rows && prefer_lds_smf(g, Ncol, bpr)) {
+        report(CRISP_KERNEL_LDS, 2, 0, 1);
+        return launch_spmm_lds_smf(a, bpr, 2, st);
     }
     if (lds_ok && force_shape < 0 && hint && uniform_rows && prefer_lds(g, Ncol, bpr)) {
         report(CRISP_KERNEL_LDS, lds_variant(bpr <= 1), 0, 0);

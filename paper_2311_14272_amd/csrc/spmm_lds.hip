@@ -27,11 +27,20 @@ struct LdsSched {
     int SW;      // columns per strip: a multiple of 4, at most 64 * WD (lanes past it stay idle)
 };
 
-template <int B, int WD, int NW, int CAP, int PF, int WPS>
+// SN:SM != 0:0 -- the resident form of a block is the operand of the sparse matrix-core instruction
+// (patterns with at most two kept values per aligned four, 64 x 64 blocks): per lane, 32-row tile and
+// 32-deep step 16 bytes of stored values and one index word, 5 KB per block instead of 8, so that 30
+// blocks fit, each step reads 20 bytes per lane from LDS instead of 32 and issues half the matrix-core
+// instructions.  The kernel is then specialised by pattern, because the operand is built by the same
+// code as in the register kernels (smf_operand).
+template <int B, int WD, int NW, int CAP, int PF, int WPS, int SN = 0, int SM = 0>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(WPS, WPS)))
 void spmm_lds_kernel(SpmmArgs p, LdsSched sch) {
     constexpr int RT = B / 32, KS = B / 16, NACC = 2 * WD;
-    constexpr int A_BYTES = B * B * 2;
+    constexpr bool SMF = SN > 0;
+    static_assert(!SMF || B == 64, "sparse-operand tiles are laid out for 64 x 64 blocks");
+    constexpr int SMF_IDX = RT * (KS / 2) * 1024;            // index words behind the value operands
+    constexpr int A_BYTES = SMF ? SMF_IDX + RT * (KS / 2) * 256 : B * B * 2;
     typedef typename XVec<WD>::type xvec_t;
     __shared__ __attribute__((aligned(16))) unsigned char lds_a[CAP * A_BYTES];
     // block columns of the resident tiles.  Read back through LDS rather than from global memory:
@@ -82,6 +91,46 @@ void spmm_lds_kernel(SpmmArgs p, LdsSched sch) {
         const int nq = (8 / p.m) * p.n;            // slots behind one operand
         const int vbytes = B * p.slots * 2;
         const uint32_t pmask = (uint32_t)p.m - 1u;
+        if constexpr (SMF) {
+            constexpr int EN = SMF ? SN : 1, EM = SMF ? SM : 4;   // (the dense instantiation never gets here)
+            typedef Fmt<EN, EM, B> F;
+            typedef BlockBody<EN, EM, B, 1, false, 0, true> Body;
+            const uint32_t a_off = (uint32_t)((jj * F::SLOTS + hh * F::FS * 2) * 2);
+            const uint32_t i_off = (uint32_t)(jj * F::WPR * 4);
+            const uint32_t aw_sh = (uint32_t)hh * F::HB * 2;
+            for (int t = c_begin + wave; t < c_end; t += NW) {
+                unsigned char* tile = lds_a + (t - c_begin) * A_BYTES;
+                uint32_t av[RT][KS][F::VW], aw[RT][F::WPR], ws[RT][F::WPR];
+                Body::load_a(av, aw, p, a_off, i_off, t);
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) {
+#pragma unroll
+                    for (int i = 0; i < F::WPR; ++i)
+                        ws[rt][i] = __builtin_amdgcn_alignbit(i + 1 < F::WPR ? aw[rt][i + 1] : 0u, aw[rt][i], aw_sh);
+                    u32x4 a4[2];
+                    uint32_t idx[2];
+                    smf_operand<EN, EM, B, 0>(av[rt], ws[rt], a4[0], idx[0]);
+                    smf_operand<EN, EM, B, 1>(av[rt], ws[rt], a4[1], idx[1]);
+#pragma unroll
+                    for (int s2 = 0; s2 < 2; ++s2) {
+                        *reinterpret_cast<u32x4*>(tile + ((rt * 2 + s2) * 64 + lane) * 16) = a4[s2];
+                        *reinterpret_cast<uint32_t*>(tile + SMF_IDX + ((rt * 2 + s2) * 64 + lane) * 4) = idx[s2];
+                    }
+                }
+            }
+            if constexpr (!decltype(lean)::value) {
+                for (int t = c_end + wave; t < c_begin + cnt_pad; t += NW) {
+                    unsigned char* tile = lds_a + (t - c_begin) * A_BYTES;
+#pragma unroll
+                    for (int q = 0; q < RT * 2; ++q) {
+                        *reinterpret_cast<u32x4*>(tile + (q * 64 + lane) * 16) = u32x4{0u, 0u, 0u, 0u};
+                        *reinterpret_cast<uint32_t*>(tile + SMF_IDX + (q * 64 + lane) * 4) = 0u;
+                    }
+                }
+            }
+            __syncthreads();
+            return;
+        }
         for (int t = c_begin + wave; t < c_end; t += NW) {
             unsigned char* tile = lds_a + (t - c_begin) * A_BYTES;
             u32x4 frag[RT * KS];
@@ -170,6 +219,46 @@ void spmm_lds_kernel(SpmmArgs p, LdsSched sch) {
     // their place (block column bj_next at lane offset off_next), A operands from LDS, MFMA
     auto mma_block = [&](f32x16 (&acc)[RT][NACC], xvec_t (&xr)[KS][8], const unsigned char* abase,
                          uint32_t off_next, int bj_next) __attribute__((always_inline)) {
+        if constexpr (SMF) {
+            // abase: the tile + lane * 16; the lane's index words sit at a quarter of that offset behind the values
+            const unsigned char* ibase = abase + SMF_IDX - (lane * 16) + lane * 4;
+#pragma unroll
+            for (int s2 = 0; s2 < KS / 2; ++s2) {
+                u32x4 half[2][NACC];
+#pragma unroll
+                for (int k2 = 0; k2 < 2; ++k2) {
+                    const int ks = 2 * s2 + k2;
+                    uint32_t xd[8][WD];
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) xvec_unpack(xr[ks][r], xd[r]);
+#pragma unroll
+                    for (int pd = 0; pd < WD; ++pd) {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            half[k2][2 * pd][q] = __builtin_amdgcn_perm(xd[2 * q + 1][pd], xd[2 * q][pd], SEL_LO);
+                            half[k2][2 * pd + 1][q] = __builtin_amdgcn_perm(xd[2 * q + 1][pd], xd[2 * q][pd], SEL_HI);
+                        }
+                    }
+                    load_x(xr[ks], off_next, bj_next, ks);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) {
+                    const u32x4 a4 = *reinterpret_cast<const u32x4*>(abase + (rt * 2 + s2) * 1024);
+                    const uint32_t idx = *reinterpret_cast<const uint32_t*>(ibase + (rt * 2 + s2) * 256);
+                    const bf16x8 afrag = __builtin_bit_cast(bf16x8, a4);
+#pragma unroll
+                    for (int c = 0; c < NACC; ++c) {
+                        typedef __attribute__((ext_vector_type(8))) uint32_t u32x8;
+                        const u32x8 b8 = {half[0][c][0], half[0][c][1], half[0][c][2], half[0][c][3],
+                                          half[1][c][0], half[1][c][1], half[1][c][2], half[1][c][3]};
+                        acc[rt][c] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(afrag, __builtin_bit_cast(bf16x16, b8), acc[rt][c],
+                                                                               (int)idx, 0, 0);
+                    }
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             uint32_t xd[8][WD];
@@ -383,9 +472,10 @@ void spmm_lds_kernel(SpmmArgs p, LdsSched sch) {
     }
 }
 
-template <int B, int WD, int NW, int CAP, int PF>
+template <int B, int WD, int NW, int CAP, int PF, int SN = 0, int SM = 0>
 static hipError_t launch_lds(const SpmmArgs& a, int wgs_per_cu, hipStream_t st) {
-    constexpr int WPS = NW / 4 * (CAP * B * B * 2 > 80 * 1024 ? 1 : 2);   // waves per SIMD
+    constexpr int TILE = SN > 0 ? 5 * 1024 : B * B * 2;
+    constexpr int WPS = NW / 4 * (CAP * TILE > 80 * 1024 ? 1 : 2);   // waves per SIMD
     // With W waves per block-row resident at once the columns take
     // iters = ceil(strips / W) strips per wave.  (Shrinking the strips so that the last round is
     // as full as the others was measured to be slower: the time per block step does not shrink
@@ -401,9 +491,9 @@ static hipError_t launch_lds(const SpmmArgs& a, int wgs_per_cu, hipStream_t st) 
     const int64_t groups = (int64_t)((s.G + 7) / 8) * a.Sb * 8;
     const dim3 grd((unsigned)groups), blk(64 * NW);
     if (a.ev_start || a.ev_stop)
-        hipExtLaunchKernelGGL((spmm_lds_kernel<B, WD, NW, CAP, PF, WPS>), grd, blk, 0, st, a.ev_start, a.ev_stop, 0, a, s);
+        hipExtLaunchKernelGGL((spmm_lds_kernel<B, WD, NW, CAP, PF, WPS, SN, SM>), grd, blk, 0, st, a.ev_start, a.ev_stop, 0, a, s);
     else
-        spmm_lds_kernel<B, WD, NW, CAP, PF, WPS><<<grd, blk, 0, st>>>(a, s);
+        spmm_lds_kernel<B, WD, NW, CAP, PF, WPS, SN, SM><<<grd, blk, 0, st>>>(a, s);
     return hipGetLastError();
 }
 
@@ -413,6 +503,29 @@ static hipError_t launch_lds(const SpmmArgs& a, int wgs_per_cu, hipStream_t st) 
 // Narrow strips (64 columns per wave) run with a two-block request ring, wide strips (128 columns)
 // with one block ahead: both keep the wave near the limit of 63 outstanding vector loads.
 int lds_capacity(int B) { return B == 64 ? 19 : 76; }
+
+// Blocks in the sparse-operand form (64 x 64 blocks, n <= 2): narrow strips, 15 tiles with two
+// workgroups of four waves per compute unit or 30 tiles with one workgroup of eight waves (the block count
+// is padded to a multiple of the request ring's two slots: 14 and 30 blocks are what fits).
+int lds_smf_capacity() { return 30; }
+
+template <int N, int M>
+static hipError_t launch_lds_smf_nm(const SpmmArgs& a, int max_blocks, int variant, hipStream_t st) {
+    const bool small = variant == 1 || (variant == 0 && max_blocks <= 14);
+    return small ? launch_lds<64, 1, 4, 15, 2, N, M>(a, 2, st) : launch_lds<64, 1, 8, 30, 2, N, M>(a, 1, st);
+}
+
+// variant: 0 = by max_blocks, 1 = the 15-tile instantiation, 2 = the 30-tile one (rows that do not fit are
+// computed chunk by chunk)
+hipError_t launch_spmm_lds_smf(const SpmmArgs& a, int max_blocks, int variant, hipStream_t st) {
+    switch (a.n * 16 + a.m) {
+        case 1 * 16 + 4: return launch_lds_smf_nm<1, 4>(a, max_blocks, variant, st);
+        case 2 * 16 + 4: return launch_lds_smf_nm<2, 4>(a, max_blocks, variant, st);
+        case 1 * 16 + 8: return launch_lds_smf_nm<1, 8>(a, max_blocks, variant, st);
+        case 2 * 16 + 8: return launch_lds_smf_nm<2, 8>(a, max_blocks, variant, st);
+        default: return hipErrorInvalidValue;
+    }
+}
 
 hipError_t launch_spmm_lds(const SpmmArgs& a, int B, int max_blocks, bool wide, hipStream_t st) {
     if (B == 64) {

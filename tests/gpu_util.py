@@ -50,11 +50,11 @@ def run_select_pack(L, W, G, fused=True, desc=None):
 
 def spmm(desc, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, Y, ldy, y_dtype, shape=None):
     """The product through crisp_spmm (shape None: the library's own choice, the production call) or
-    through crisp_spmm_forced with launch shape `shape`."""
+    through crisp_spmm_forced with launch shape `shape` (returns the code of the kernel that ran)."""
     if shape is None:
         crisp.crisp_spmm(desc, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, Y, ldy, y_dtype)
-    else:
-        crisp.crisp_spmm_forced(desc, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, Y, ldy, y_dtype, None, shape)
+        return None
+    return crisp.crisp_spmm_forced(desc, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, Y, ldy, y_dtype, None, shape)
 
 
 def spmm_ep(desc, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, Y, ldy, y_dtype, ep, shape=None):
@@ -78,19 +78,19 @@ def conv_spmm_ep(desc, conv, row_ptr, col_idx, vals, idx_words, act, Y, ldy, y_d
         crisp.crisp_conv_spmm_forced(desc, conv, row_ptr, col_idx, vals, idx_words, act, Y, ldy, y_dtype, ep, shape)
 
 
-def run_spmm(layer, dX, Ncol, ldx, y_dtype, S, ldy=None, fill=None, shape=None):
+def run_spmm(layer, dX, Ncol, ldx, y_dtype, S, ldy=None, fill=None, shape=None, with_code=False):
     """crisp_spmm into a fresh Y with a guard band of columns (ldy > Ncol) that must stay untouched."""
     if ldy is None:
         ldy = (Ncol + 7) // 8 * 8 + 8
     tdt = torch.float32 if y_dtype == crisp.Y_F32 else torch.bfloat16
     Y = torch.full((S + 1, ldy), float("nan") if fill is None else fill, dtype=tdt, device="cuda")
     # shape: None = the library's own choice (crisp_spmm); otherwise crisp_spmm_forced with that launch shape
-    spmm(layer.desc, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dX, Ncol, ldx, Y, ldy, y_dtype, shape=shape)
+    code = spmm(layer.desc, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dX, Ncol, ldx, Y, ldy, y_dtype, shape=shape)
     torch.cuda.synchronize()
     Yh = Y.float().cpu().numpy().astype(np.float64)
     assert np.isnan(Yh[:S, Ncol:]).all(), "columns beyond Ncol were written"
     assert np.isnan(Yh[S]).all(), "row beyond S was written"
-    return Yh[:S, :Ncol]
+    return (Yh[:S, :Ncol], code) if with_code else Yh[:S, :Ncol]
 
 
 def check_product(Y, Yref, Aref, y_dtype, what=""):

@@ -138,13 +138,13 @@ def test_spmm_from_oracle_pack(L):
     check_product(Y, Yref, Aref, crisp.Y_F32, L.name)
 
 
-@pytest.mark.parametrize("shape", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 15])
+@pytest.mark.parametrize("shape", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 15, 16, 17])
 @pytest.mark.parametrize("L", synth.small_cases(), ids=lambda L: L.name)
 def test_every_launch_shape(L, shape):
     """Each launch shape of the product (wide / narrow strips, 4- and 8-way split of the block
-    list, generic LDS-expansion kernel, LDS-resident block-rows with narrow / wide strips, and
-    shapes 0-3 again with the sparse matrix-core instruction where the pattern allows it) must
-    give the same result within tolerance."""
+    list, generic LDS-expansion kernel, LDS-resident block-rows with narrow / wide strips, shapes 0-3 again
+    with the sparse matrix-core instruction where the pattern allows it, the uneven-row kernel, block-rows
+    resident as sparse matrix-core operands) must give the same result within tolerance."""
     print("case", L.name, "shape", shape, flush=True)
     W, G, X = synth.draw_small(L, 23)
     sel, vals, idxw, flags = oracle_all(L, W, G)
@@ -173,6 +173,68 @@ LDS_CASES = [
     # uneven rows, some empty or longer than the hint says
     (synth.LayerSpec("lds_uneven", 256, 1024, 1200, 2, 4, 64, 0.3, synth.SAL_MAG, 0.05, None, synth.LAYER_TOPK), None),
 ]
+
+
+LDS_SMF_CASES = [
+    # all four patterns the sparse matrix-core instruction takes, several strips per wave, ragged S and Ncol
+    (synth.LayerSpec("ldss_1:4", 200, 512, 20004, 1, 4, 64, 0.5, synth.SAL_MAG, 0.05), None),
+    (synth.LayerSpec("ldss_2:4", 1024, 256, 20000, 2, 4, 64, 0.5, synth.SAL_MAG, 0.05), None),
+    (synth.LayerSpec("ldss_1:8", 128, 448, 9000, 1, 8, 64, 0.6, synth.SAL_MAG, 0.05), None),
+    (synth.LayerSpec("ldss_2:8", 100, 320, 5128, 2, 8, 64, 0.8, synth.SAL_GRAD, 0.05), None),
+    # more than 15 blocks per block-row: the 30-tile instantiation
+    (synth.LayerSpec("ldss_big", 100, 1536, 1032, 2, 8, 64, 0.75, synth.SAL_MAG, 0.05), None),
+    # block-rows longer than the variant the hint selects (24 > 15) and than the largest holds (32 > 30)
+    (synth.LayerSpec("ldss_chunk15", 128, 1536, 3000, 2, 4, 64, 1.0, synth.SAL_MAG, 0.05), 0.25),
+    (synth.LayerSpec("ldss_chunk30", 64, 2048, 2000, 1, 4, 64, 1.0, synth.SAL_MAG, 0.05), None),
+    # uneven rows, some empty or longer than the hint says
+    (synth.LayerSpec("ldss_uneven", 256, 1024, 1200, 2, 4, 64, 0.3, synth.SAL_MAG, 0.05, None, synth.LAYER_TOPK), None),
+    # a single block per row and an odd block count (the padding tile of the two-block request ring)
+    (synth.LayerSpec("ldss_one", 192, 64, 4100, 2, 8, 64, 1.0, synth.SAL_MAG, 0.05), None),
+    (synth.LayerSpec("ldss_three", 64, 256, 4100, 1, 8, 64, 0.75, synth.SAL_MAG, 0.05), None),
+]
+
+
+@pytest.mark.parametrize("case", LDS_SMF_CASES, ids=lambda c: c[0].name)
+def test_lds_resident_sparse_operands(case):
+    """Block-rows resident in LDS in the operand form of the sparse matrix-core instruction (forced shapes 16:
+    capacity by the descriptor's density, 17: always the 30-tile instantiation)."""
+    L, hint = case
+    print("case", L.name, flush=True)
+    W, G, X = synth.draw_small(L, 29)
+    sel, vals, idxw, flags = oracle_all(L, W, G)
+    layer, out = run_select_pack(L, W, G)
+    assert_select_pack_equal(L, out, sel, vals, idxw, flags)
+    if hint is not None:
+        layer.desc = crisp.layer_desc(L.S, L.K, L.n, L.m, L.B, hint, L.sal_kind, L.select_mode)
+    ldx = (L.Ncol + 7) // 8 * 8
+    Xp = np.zeros((L.K, ldx), dtype=np.uint16)
+    Xp[:, : L.Ncol] = X
+    dX = dev(Xp)
+    Yref, Aref = oracle.gemm_masked(W, sel.mask, X)
+    for shape in (16, 17):
+        for yd in (crisp.Y_F32, crisp.Y_BF16):
+            Y, code = run_spmm(layer, dX, L.Ncol, ldx, yd, L.S, shape=shape, with_code=True)
+            f = crisp.kernel_code_fields(code)
+            assert f["family"] == "lds" and f["sparse_mfma"] == 1, (L.name, shape, f)
+            check_product(Y, Yref, Aref, yd, "%s shape %d" % (L.name, shape))
+
+
+def test_lds_sparse_operands_are_the_choice_for_long_rows():
+    """Six or more kept blocks per block-row, 64 x 64 blocks, n <= 2, many columns: the library's own choice is
+    the kernel with the block-row resident as sparse matrix-core operands, and its result is within tolerance."""
+    L = synth.LayerSpec("ldss_auto", 128, 512, 65544, 2, 8, 64, 0.75, synth.SAL_MAG, 0.05)
+    W, G, X = synth.draw_small(L, 31)
+    sel, vals, idxw, flags = oracle_all(L, W, G)
+    layer, out = run_select_pack(L, W, G)
+    dX = dev(X)
+    Yref, Aref = oracle.gemm_masked(W, sel.mask, X)
+    for yd in (crisp.Y_F32, crisp.Y_BF16):
+        Y, code = run_spmm(layer, dX, L.Ncol, L.Ncol, yd, L.S, shape=crisp.SHAPE_AUTO, with_code=True)
+        f = crisp.kernel_code_fields(code)
+        assert f["family"] == "lds" and f["sparse_mfma"] == 1, f
+        check_product(Y, Yref, Aref, yd, L.name)
+        Yp = run_spmm(layer, dX, L.Ncol, L.Ncol, yd, L.S)          # crisp_spmm itself: the same launch
+        assert np.array_equal(Y, Yp)
 
 
 @pytest.mark.parametrize("case", LDS_CASES, ids=lambda c: c[0].name)
