@@ -350,8 +350,8 @@ CRISP_API crisp_status crisp_conv_spmm_ep(const crisp_layer_desc *desc, const cr
  *          shape 0..3; for the LDS-resident family bit 0 = wide strips, bit 1 = the instantiation with
  *          the larger tile capacity; else 0; conv_mode: 0 plain X, 1..4 the fused-lowering modes;
  *          sparse: 1 when the sparse matrix-core instruction is used).  Together with (n, m, B) --
- *          B alone for the LDS-resident, generic and 16 x 16 families, which are not specialised by
- *          pattern -- the code names one compiled kernel.
+ *          B alone for the generic and 16 x 16 families and for the LDS-resident family with sparse = 0,
+ *          which are not specialised by pattern -- the code names one compiled kernel.
  * Results agree across shapes within the summation-order tolerance.  Errors as for the plain calls.
  */
 enum {

@@ -373,7 +373,7 @@ def test_bf16_output_is_rounded_fp32_output():
         Xp = np.zeros((L.K, ldx), dtype=np.uint16)
         Xp[:, : L.Ncol] = X
         dX = dev(Xp)
-        for shape in (0, 1, 2, 4, 7, 9, 15):
+        for shape in (0, 1, 2, 4, 7, 9, 15, 16):
             y32 = run_spmm(layer, dX, L.Ncol, ldx, crisp.Y_F32, L.S, shape=shape).astype(np.float32)
             y16 = run_spmm(layer, dX, L.Ncol, ldx, crisp.Y_BF16, L.S, shape=shape).astype(np.float32)
             assert (synth.f32_to_bf16_bits(y16) == synth.f32_to_bf16_bits(y32)).all(), (L.name, shape)
@@ -794,7 +794,7 @@ def test_maximum_row_stride_of_x():
     ldx = 1 << 27
     dX = torch.zeros((L.K, ldx), dtype=torch.int16, device="cuda")
     dX[:, : L.Ncol] = dev(X)
-    for shape in (None, 0, 1, 2, 4, 5, 6, 8, 13, 15):
+    for shape in (None, 0, 1, 2, 4, 5, 6, 8, 13, 15, 16):
         print("wide ldx shape", shape, flush=True)
         for yd in (crisp.Y_F32, crisp.Y_BF16):
             Y = run_spmm(layer, dX, L.Ncol, ldx, yd, L.S, shape=shape)
