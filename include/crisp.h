@@ -372,12 +372,13 @@ enum {
     CRISP_SHAPE_CONV_PATCH = 14, /* fused lowering for channel counts that are no multiple of 64  */
     CRISP_SHAPE_BALANCED = 15,   /* block list dealt evenly to the waves (uneven block-rows)      */
     CRISP_SHAPE_LDS_SMF = 16,    /* block-row resident in LDS as sparse matrix-core operands      */
-    CRISP_SHAPE_LDS_SMF_30 = 17  /* ... always the instantiation that holds 30 blocks             */
+    CRISP_SHAPE_LDS_SMF_30 = 17, /* ... always the instantiation that holds 30 blocks             */
+    CRISP_SHAPE_XLDS = 18        /* K <= 512: a strip of X resident in LDS for all block-rows     */
 };
 enum {
     CRISP_KERNEL_REG = 1, CRISP_KERNEL_GENERIC = 2, CRISP_KERNEL_LDS = 3, CRISP_KERNEL_XRES = 4,
     CRISP_KERNEL_CONV_LDS = 5, CRISP_KERNEL_CONV_PATCH = 6, CRISP_KERNEL_B16 = 7, CRISP_KERNEL_BALANCED = 8,
-    CRISP_KERNEL_K8 = 9
+    CRISP_KERNEL_K8 = 9, CRISP_KERNEL_XLDS = 10
 };
 CRISP_API crisp_status crisp_spmm_forced(const crisp_layer_desc *desc, const int32_t *row_ptr, const int32_t *col_idx,
                                const uint16_t *vals, const uint32_t *idx_words, const uint16_t *X,

@@ -234,7 +234,7 @@ def crisp_conv_spmm_ep(desc, conv: ConvDesc, row_ptr, col_idx, vals, idx_words, 
 
 
 SHAPE_AUTO = -1
-KERNEL_FAMILIES = {1: "reg", 2: "generic", 3: "lds", 4: "xres", 5: "conv_lds", 6: "conv_patch", 7: "b16", 8: "balanced", 9: "k8"}
+KERNEL_FAMILIES = {1: "reg", 2: "generic", 3: "lds", 4: "xres", 5: "conv_lds", 6: "conv_patch", 7: "b16", 8: "balanced", 9: "k8", 10: "xlds"}
 
 
 def crisp_spmm_forced(desc, row_ptr, col_idx, vals, idx_words, X, Ncol, ldx, Y, ldy, y_dtype, ep=None, shape=SHAPE_AUTO,

@@ -19,6 +19,7 @@
 #pragma once
 #include "spmm_reg.h"
 #include "spmm_xres.h"
+#include "spmm_xlds.h"
 #include "conv_patch.h"
 #include "spmm_balanced.h"
 #include "spmm_k8.h"
@@ -383,6 +384,7 @@ hipError_t launch_k8_nm(const SpmmArgs& a, int B, hipStream_t st);
     template <>                                                                              \
     hipError_t launch_reg_nm<N, M>(const SpmmArgs& a, int B, int shape, hipStream_t st) {    \
         if (shape == XRES_SHAPE) return launch_xres<N, M>(a, st);                            \
+        if (shape == XLDS_SHAPE) return launch_xlds<N, M>(a, st);                            \
         return B == 64 ? launch_reg_shape<N, M, 64>(a, shape, st) : launch_reg_shape<N, M, 32>(a, shape, st); \
     }                                                                                        \
     template <>                                                                              \

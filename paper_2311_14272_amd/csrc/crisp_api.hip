@@ -341,7 +341,7 @@ static crisp_status spmm_impl(const crisp_layer_desc* desc, const int32_t* row_p
     }
     // shapes of the plain product that may be forced (anything else: the automatic choice)
     if (!((force_shape >= 0 && force_shape <= 10) || force_shape == CRISP_SHAPE_XRES ||
-          (force_shape >= CRISP_SHAPE_BALANCED && force_shape <= CRISP_SHAPE_LDS_SMF_30)))
+          (force_shape >= CRISP_SHAPE_BALANCED && force_shape <= CRISP_SHAPE_XLDS)))
         force_shape = -1;
     hipError_t e = launch_spmm(g, desc->block_density, desc->select_mode == CRISP_ROW_UNIFORM, force_shape, row_ptr, col_idx, vals,
                                idx_words, X, nullptr, Ncol,

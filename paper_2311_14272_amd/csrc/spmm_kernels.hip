@@ -645,7 +645,7 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
     // forced shapes 7..10: shapes 0..3 of the register kernels with the sparse matrix-core instruction
     // (the automatic choice always takes it where the pattern is eligible: it was faster for every
     // measured layer; shapes 0..3 force the dense-expansion instantiations)
-    a.use_smf = (force_shape < 0 || force_shape == 13 || (force_shape >= 7 && force_shape <= 10)) ? 1 : 0;
+    a.use_smf = (force_shape < 0 || force_shape == 13 || force_shape == CRISP_SHAPE_XLDS || (force_shape >= 7 && force_shape <= 10)) ? 1 : 0;
     // X-resident kernel for short K (forced shape 13).  Chosen for one block column, several
     // block-rows, patterns that go to the sparse matrix-core instruction and long X rows: 1.12x on the
     // 64 -> 256 channel layers of ResNet-50 at batch 256 (107 vs 120 us for 103 MB read and 411 MB
@@ -653,7 +653,16 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
     // 6 % either way for two block columns or the dense-expansion patterns
     const bool xres = xres_covers(a, g.B) &&
         (force_shape == 13 || (force_shape < 0 && g.Kb == 1 && g.Sb >= 2 && g.n <= 2 && Ncol >= ((int64_t)1 << 18)));
-    const int shape = xres ? XRES_SHAPE
+    // X strip resident in LDS as operands for all block-rows (forced shape 18)
+    // Chosen for patterns that go to the sparse matrix-core instruction when at least 16 block-rows share
+    // two to eight block columns and there are enough columns for a workgroup per compute unit: 1.2-1.45x on
+    // the 256 -> 1024 and 512 -> 2048 channel layers of ResNet-50 at batch 256 (rows of one to three blocks:
+    // 29-37 us against 37-52 us, 20-23 us against 23-28 us); 0.75-1.0x with 8 block-rows or fewer, with one
+    // block column (the register-resident kernel above is for those) and for the dense-expansion patterns.
+    const bool xlds = !xres && !conv && xlds_covers(a, g.B) &&
+        (force_shape == CRISP_SHAPE_XLDS ||
+         (force_shape < 0 && g.n <= 2 && g.Kb >= 2 && g.Sb >= 16 && Ncol >= 8192));
+    const int shape = xres ? XRES_SHAPE : xlds ? XLDS_SHAPE
                     : (force_shape >= 0 && force_shape <= 3) ? force_shape
                     : (force_shape >= 7 && force_shape <= 10) ? force_shape - 7
                     : pick_shape(g, Ncol, bpr, a.use_smf && g.n <= 2);
@@ -664,8 +673,9 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
         const bool known = key == 0x14 || key == 0x24 || key == 0x34 || key == 0x44 || key == 0x18 || key == 0x28 ||
                            key == 0x48 || key == 0x88;
         // (the fused lowering has the narrow shapes only)
-        const int shape_run = xres ? 0 : (conv && shape == 0) ? 1 : shape;
-        if (known) report(xres ? CRISP_KERNEL_XRES : CRISP_KERNEL_REG, shape_run, conv ? a.conv_mode : 0, a.use_smf && g.n <= 2);
+        const int shape_run = (xres || xlds) ? 0 : (conv && shape == 0) ? 1 : shape;
+        if (known) report(xres ? CRISP_KERNEL_XRES : xlds ? CRISP_KERNEL_XLDS : CRISP_KERNEL_REG, shape_run, conv ? a.conv_mode : 0,
+                          a.use_smf && g.n <= 2);
         switch (key) {
             case 1 * 16 + 4: return launch_reg_nm<1, 4>(a, g.B, shape, st);
             case 2 * 16 + 4: return launch_reg_nm<2, 4>(a, g.B, shape, st);

@@ -73,7 +73,7 @@ def test_spmm_epilogue(L):
                                          res if cb["res"] else None, cb["relu"])
             ep = crisp.epilogue(dscale if cb["scale"] else None, dbias if cb["bias"] else None,
                                 dres if cb["res"] else None, ldr, cb["relu"])
-            for shape in (None, 0, 1, 2, 4, 5, 6, 8, 13, 15, 16, 17):
+            for shape in (None, 0, 1, 2, 4, 5, 6, 8, 13, 15, 16, 17, 18):
                 Y = torch.full((L.S + 1, ldy), float("nan"), dtype=tdt, device="cuda")
                 spmm_ep(layer.desc, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dX, L.Ncol, ldx,
                                     Y, ldy, yd, ep, shape=shape)

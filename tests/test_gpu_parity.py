@@ -138,7 +138,7 @@ def test_spmm_from_oracle_pack(L):
     check_product(Y, Yref, Aref, crisp.Y_F32, L.name)
 
 
-@pytest.mark.parametrize("shape", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 15, 16, 17])
+@pytest.mark.parametrize("shape", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 15, 16, 17, 18])
 @pytest.mark.parametrize("L", synth.small_cases(), ids=lambda L: L.name)
 def test_every_launch_shape(L, shape):
     """Each launch shape of the product (wide / narrow strips, 4- and 8-way split of the block
@@ -260,6 +260,61 @@ def test_lds_resident_block_rows(case):
             check_product(Y, Yref, Aref, yd, "%s shape %d" % (L.name, shape))
 
 
+XLDS_CASES = [
+    # K of up to eight 64-wide block columns: the kernel that keeps a strip of X in LDS as operands for all
+    # block-rows.  Full and partial last block column, ragged S, more block-rows than a group holds (> 60),
+    # fewer block-rows than waves, patterns with and without the sparse matrix-core instruction, uneven rows
+    # with empty ones, a block list longer than the part staged in LDS (> 512 entries), the largest K
+    synth.LayerSpec("xlds_k256_2:4", 1024, 256, 1000, 2, 4, 64, 0.5, synth.SAL_MAG, 0.05),
+    synth.LayerSpec("xlds_k512_1:8", 520, 512, 264, 1, 8, 64, 0.4, synth.SAL_GRAD, 0.05),
+    synth.LayerSpec("xlds_k208_4:8", 300, 208, 520, 4, 8, 64, 0.75, synth.SAL_MAG, 0.05),
+    synth.LayerSpec("xlds_k320_3:4", 128, 320, 72, 3, 4, 64, 0.6, synth.SAL_MAG, 0.05),
+    synth.LayerSpec("xlds_k192_2:8_rows70", 4480, 192, 68, 2, 8, 64, 0.67, synth.SAL_MAG, 0.05),
+    synth.LayerSpec("xlds_k512_1:4_rows60", 3840, 512, 132, 1, 4, 64, 1.0, synth.SAL_MAG, 0.05),
+    synth.LayerSpec("xlds_one_group", 1280, 128, 32776, 2, 8, 64, 0.5, synth.SAL_MAG, 0.05),
+    synth.LayerSpec("xlds_k384_2:4_uneven", 640, 384, 300, 2, 4, 64, 0.3, synth.SAL_MAG, 0.05, None, synth.LAYER_TOPK),
+    synth.LayerSpec("xlds_k128_8:8", 192, 128, 260, 8, 8, 64, 1.0, synth.SAL_MAG, 0.05),
+    synth.LayerSpec("xlds_k64_4:4", 64, 64, 64, 4, 4, 64, 1.0, synth.SAL_MAG, 0.05),
+]
+
+
+@pytest.mark.parametrize("L", XLDS_CASES, ids=lambda L: L.name)
+def test_x_strip_resident_in_lds(L):
+    """Forced shape 18: the strip's operands staged once per workgroup in LDS, waves walk the block-rows."""
+    print("case", L.name, flush=True)
+    W, G, X = synth.draw_small(L, 33)
+    sel, vals, idxw, flags = oracle_all(L, W, G)
+    layer, out = run_select_pack(L, W, G)
+    assert_select_pack_equal(L, out, sel, vals, idxw, flags)
+    ldx = (L.Ncol + 7) // 8 * 8
+    Xp = np.zeros((L.K, ldx), dtype=np.uint16)
+    Xp[:, : L.Ncol] = X
+    dX = dev(Xp)
+    Yref, Aref = oracle.gemm_masked(W, sel.mask, X)
+    for yd in (crisp.Y_F32, crisp.Y_BF16):
+        Y, code = run_spmm(layer, dX, L.Ncol, ldx, yd, L.S, shape=18, with_code=True)
+        assert crisp.kernel_code_fields(code)["family"] == "xlds", (L.name, crisp.kernel_code_fields(code))
+        check_product(Y, Yref, Aref, yd, "%s shape 18" % L.name)
+
+
+def test_x_strip_in_lds_is_the_choice_for_many_short_block_rows():
+    """16 or more block-rows over two to eight block columns, n <= 2, enough columns: the library's own choice is
+    the kernel with the strip of X resident in LDS."""
+    L = synth.LayerSpec("xlds_auto", 1024, 256, 8200, 2, 4, 64, 0.5, synth.SAL_MAG, 0.05)
+    W, G, X = synth.draw_small(L, 35)
+    sel, vals, idxw, flags = oracle_all(L, W, G)
+    layer, out = run_select_pack(L, W, G)
+    dX = dev(X)
+    Yref, Aref = oracle.gemm_masked(W, sel.mask, X)
+    for yd in (crisp.Y_F32, crisp.Y_BF16):
+        Y, code = run_spmm(layer, dX, L.Ncol, L.Ncol, yd, L.S, shape=crisp.SHAPE_AUTO, with_code=True)
+        f = crisp.kernel_code_fields(code)
+        assert f["family"] == "xlds" and f["sparse_mfma"] == 1, f
+        check_product(Y, Yref, Aref, yd, L.name)
+        Yp = run_spmm(layer, dX, L.Ncol, L.Ncol, yd, L.S)          # crisp_spmm itself: the same launch
+        assert np.array_equal(Y, Yp)
+
+
 XRES_CASES = [
     # short K (one or two 64-wide block columns): the kernel that keeps the strip of X in registers.
     # One and two block columns, ragged S, a last strip group with idle waves, more block-rows than
@@ -373,7 +428,7 @@ def test_bf16_output_is_rounded_fp32_output():
         Xp = np.zeros((L.K, ldx), dtype=np.uint16)
         Xp[:, : L.Ncol] = X
         dX = dev(Xp)
-        for shape in (0, 1, 2, 4, 7, 9, 15, 16):
+        for shape in (0, 1, 2, 4, 7, 9, 15, 16, 18):
             y32 = run_spmm(layer, dX, L.Ncol, ldx, crisp.Y_F32, L.S, shape=shape).astype(np.float32)
             y16 = run_spmm(layer, dX, L.Ncol, ldx, crisp.Y_BF16, L.S, shape=shape).astype(np.float32)
             assert (synth.f32_to_bf16_bits(y16) == synth.f32_to_bf16_bits(y32)).all(), (L.name, shape)

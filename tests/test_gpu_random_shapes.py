@@ -145,7 +145,7 @@ def test_random_products(seed):
         Xp = np.full((K, ldx), 0x7FC0, dtype=np.uint16)     # NaN in the padding columns: must not leak
         Xp[:, :Ncol] = X
         dX = dev(Xp)
-        for shape in (None, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 13, 15, 16, 17):
+        for shape in (None, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 13, 15, 16, 17, 18):
             for yd in (crisp.Y_F32, crisp.Y_BF16):
                 try:
                     Y = run_spmm(layer, dX, Ncol, ldx, yd, S, shape=shape)
@@ -189,7 +189,7 @@ def test_random_epilogues(seed):
                 continue
             L = synth.LayerSpec("re", S, K, Ncol, n, m, B, dens, synth.SAL_MAG, 0.05, None, mode)
             W, G, X = synth.draw_small(L, int(rng.integers(1, 1 << 30)))
-            shapes = (None, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 13, 15, 16, 17)
+            shapes = (None, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 13, 15, 16, 17, 18)
         what = ("conv", cv) if is_conv else "plain", (L.S, L.K, L.Ncol, n, m, L.B, dens, mode)
         print("epilogue case", case, what, flush=True)
         case += 1
