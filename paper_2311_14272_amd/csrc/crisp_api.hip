@@ -392,7 +392,7 @@ static crisp_status conv_spmm_impl(const crisp_layer_desc* desc, const crisp_con
         return CRISP_EUNSUPPORTED;
     // shapes of the fused lowering that may be forced (anything else: the automatic choice)
     if (!((force_shape >= 0 && force_shape <= 3) || (force_shape >= 7 && force_shape <= 10) ||
-          force_shape == CRISP_SHAPE_CONV_LDS || force_shape == CRISP_SHAPE_CONV_PATCH))
+          force_shape == CRISP_SHAPE_CONV_LDS || force_shape == CRISP_SHAPE_CONV_PATCH || force_shape == CRISP_SHAPE_XLDS))
         force_shape = -1;
     hipError_t e = launch_spmm(g, desc->block_density, desc->select_mode == CRISP_ROW_UNIFORM, force_shape, row_ptr, col_idx, vals,
                                idx_words, act, conv,
@@ -489,7 +489,7 @@ static crisp_status conv_plan_impl(const crisp_layer_desc* desc, const crisp_con
         const bool paired = conv->stride == 1 && ((Wo & 1) == 0 || same_pad) && conv->W >= 2 && Wo >= 2 && aligned;
         const bool strided_1x1 = conv->kh == 1 && conv->kw == 1 && conv->stride == 2 && conv->pad == 0 && (conv->W & 1) == 0 &&
                                  (Wo & 1) == 0 && aligned;
-        if ((strided_1x1 && gathers <= STRIDED_1X1_MAX_GATHER) || paired ||
+        if ((strided_1x1 && gathers <= STRIDED_1X1_MAX_GATHER) || paired || xlds_conv_would_run(*g, *conv, Ncol) ||
             conv_lds_would_run(*g, desc->block_density, *conv, Ncol) ||
             (conv->kh * conv->kw > 1 && gathers <= FUSED_GENERAL_MAX_GATHER)) {
             *path = CRISP_CONV_FUSED;

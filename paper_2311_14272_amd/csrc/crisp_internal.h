@@ -47,6 +47,7 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
 
 // Whether launch_spmm would run this convolution with the input patch staged in LDS (host only).
 bool conv_lds_would_run(const Geometry& g, double density_hint, const crisp_conv_desc& conv, int64_t Ncol);
+bool xlds_conv_would_run(const Geometry& g, const crisp_conv_desc& conv, int64_t Ncol);
 
 #define CRISP_BUDGET_MAX_LAYERS 64
 #define CRISP_BUDGET_MAX_COLS 4096

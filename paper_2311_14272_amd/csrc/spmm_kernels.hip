@@ -497,6 +497,21 @@ static void fill_conv_args(SpmmArgs& a, const Geometry& g, const crisp_conv_desc
     a.inv_Ho = 1.0 / a.Ho;
 }
 
+// Where the kernel that keeps a strip of X in LDS for all block-rows is the automatic choice (patterns with
+// n <= 2; the caller checks that and xlds_covers).
+static bool xlds_pays(int Sb, int Kb, int64_t Ncol, bool strided_1x1) {
+    return Kb >= 2 && Sb >= (strided_1x1 ? 8 : 16) && Ncol >= 8192;
+}
+
+// Whether launch_spmm, left to its own choice, runs this strided 1 x 1 convolution in that kernel (asked by the
+// callers that choose between the fused lowering and a materialised X).
+bool xlds_conv_would_run(const Geometry& g, const crisp_conv_desc& conv, int64_t Ncol) {
+    const int64_t Wo = ((int64_t)conv.W + 2 * conv.pad - conv.kw) / conv.stride + 1;
+    const bool strided_1x1 = conv.kh == 1 && conv.kw == 1 && conv.stride == 2 && conv.pad == 0 && (conv.W & 1) == 0 &&
+                             (Wo & 1) == 0 && conv.C % 64 == 0;
+    return strided_1x1 && g.B == 64 && g.n <= 2 && g.K <= XLDS_MAX_KB * 64 && (Ncol % 4) == 0 && xlds_pays(g.Sb, g.Kb, Ncol, true);
+}
+
 // Whether launch_spmm, left to its own choice, runs this convolution in the kernel that stages the
 // input patch in LDS (the callers that choose between the fused lowering and a materialised X ask).
 bool conv_lds_would_run(const Geometry& g, double density_hint, const crisp_conv_desc& conv, int64_t Ncol) {
@@ -659,9 +674,12 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
     // the 256 -> 1024 and 512 -> 2048 channel layers of ResNet-50 at batch 256 (rows of one to three blocks:
     // 29-37 us against 37-52 us, 20-23 us against 23-28 us); 0.75-1.0x with 8 block-rows or fewer, with one
     // block column (the register-resident kernel above is for those) and for the dense-expansion patterns.
-    const bool xlds = !xres && !conv && xlds_covers(a, g.B) &&
+    // With the lowering of a strided 1 x 1 filter fused in, the strided gather is done once per strip instead of
+    // once per block-row: chosen from 8 block-rows on (512 x 256 x 200704 1:8: 134 against 165 us; the input
+    // alone is 411 MB there, of which every line is touched).
+    const bool xlds = !xres && xlds_covers(a, g.B) &&
         (force_shape == CRISP_SHAPE_XLDS ||
-         (force_shape < 0 && g.n <= 2 && g.Kb >= 2 && g.Sb >= 16 && Ncol >= 8192));
+         (force_shape < 0 && g.n <= 2 && xlds_pays(g.Sb, g.Kb, Ncol, conv != nullptr)));
     const int shape = xres ? XRES_SHAPE : xlds ? XLDS_SHAPE
                     : (force_shape >= 0 && force_shape <= 3) ? force_shape
                     : (force_shape >= 7 && force_shape <= 10) ? force_shape - 7

@@ -26,8 +26,13 @@ constexpr int XLDS_MAX_KB = 8;          // block columns held at most (64 KB of 
 constexpr int XLDS_MAX_GROUP = 60;      // block-rows per workgroup at most (row_ptr of the group sits in one register per lane)
 constexpr int XLDS_LIST = 512;          // block-list entries of a group staged in LDS at most
 
-template <int N, int M, bool SMF>
+// CONV == 4: X is the implicit lowering of a 1 x 1 filter with stride 2 (no padding, even W and Wo) over the
+// activation [C][batch][H][W]: K-row c is channel c, and the lane's two columns are elements 0 and 2 of one
+// 8-byte piece of input row 2 * oh, so the strided gather is done once per strip here instead of once per
+// block-row.
+template <int N, int M, bool SMF, int CONV>
 __global__ __launch_bounds__(256, 4) void spmm_xlds_kernel(SpmmArgs p, int rows_per_group, int row_groups, int Kb) {
+    static_assert(CONV == 0 || CONV == 4, "plain X or the strided 1 x 1 lowering");
     constexpr int B = 64;
     typedef Fmt<N, M, B> F;
     constexpr int RT = F::RT, KS = F::KS, NACC = 2;
@@ -43,7 +48,22 @@ __global__ __launch_bounds__(256, 4) void spmm_xlds_kernel(SpmmArgs p, int rows_
     const int64_t col0 = (int64_t)nt * 64 + jj * NACC;
     const bool col_ok = col0 < p.Ncol;
     const int64_t col_ld = col_ok ? col0 : 0;     // lanes past the last column read column 0 and never store
-    const uint32_t lane_off = (uint32_t)(((int64_t)hh * 8 * p.ldx + col_ld) * 2);
+    uint32_t lane_off;
+    if constexpr (CONV == 4) {
+        // column -> (image, oh, ow); exact division through fp64 reciprocals (col < 2^31)
+        const int j = (int)col_ld;
+        int t = (int)((double)j * p.inv_Wo);
+        t -= (t * p.Wo > j);
+        t += ((t + 1) * p.Wo <= j);
+        const int ow = j - t * p.Wo;
+        int im = (int)((double)t * p.inv_Ho);
+        im -= (im * p.Ho > t);
+        im += ((im + 1) * p.Ho <= t);
+        const int oh = t - im * p.Ho;
+        lane_off = (uint32_t)((int64_t)hh * 8 * p.plane * 2) + (uint32_t)((im * p.H + oh * 2) * p.W + ow * 2) * 2u;
+    } else {
+        lane_off = (uint32_t)(((int64_t)hh * 8 * p.ldx + col_ld) * 2);
+    }
     const uint32_t a_off = (uint32_t)((jj * F::SLOTS + hh * F::FS * (SMF ? 2 : 1)) * 2);
     const uint32_t i_off = (uint32_t)(jj * F::WPR * 4);
     const uint32_t aw_sh = (uint32_t)hh * F::HB * (SMF ? 2 : 1);
@@ -60,17 +80,18 @@ __global__ __launch_bounds__(256, 4) void spmm_xlds_kernel(SpmmArgs p, int rows_
     // every fourth unit, four units (32 requests) in flight before the first is transposed ----
     {
         const int units = Kb * KS;
-        const uint32_t row_bytes = (uint32_t)p.ldx * 2u;
+        const uint32_t row_bytes = CONV == 4 ? (uint32_t)p.plane * 2u : (uint32_t)p.ldx * 2u;
+        typedef typename XVec<CONV == 4 ? 2 : 1>::type xv_t;
         for (int u0 = wave; u0 < units; u0 += 16) {
-            uint32_t xr[4][8];
+            xv_t xr[4][8];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const int u = min(u0 + 4 * k, units - 1);
                 // a step past the end of K re-reads the last 16 rows (finite values times stored zeros)
                 const int k_first = min(u * 16, p.K - 16);
-                const rsrc_t r = make_rsrc(p.X + (int64_t)k_first * p.ldx);
+                const rsrc_t r = CONV == 4 ? make_rsrc(p.act + (int64_t)k_first * p.plane) : make_rsrc(p.X + (int64_t)k_first * p.ldx);
 #pragma unroll
-                for (int i = 0; i < 8; ++i) xr[k][i] = __builtin_amdgcn_raw_buffer_load_b32(r, lane_off, (uint32_t)i * row_bytes, 0);
+                for (int i = 0; i < 8; ++i) xr[k][i] = buf_load_x<CONV == 4 ? 2 : 1>(r, lane_off, (uint32_t)i * row_bytes);
             }
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -79,8 +100,19 @@ __global__ __launch_bounds__(256, 4) void spmm_xlds_kernel(SpmmArgs p, int rows_
                     u32x4 lo, hi;
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
-                        lo[q] = __builtin_amdgcn_perm(xr[k][2 * q + 1], xr[k][2 * q], SEL_LO);   // first column of the pair
-                        hi[q] = __builtin_amdgcn_perm(xr[k][2 * q + 1], xr[k][2 * q], SEL_HI);   // second column
+                        if constexpr (CONV == 4) {
+                            uint32_t r0[2], r1[2];
+                            xvec_unpack(xr[k][2 * q], r0);
+                            xvec_unpack(xr[k][2 * q + 1], r1);
+                            lo[q] = __builtin_amdgcn_perm(r1[0], r0[0], SEL_LO);   // element 0 of the piece: first column
+                            hi[q] = __builtin_amdgcn_perm(r1[1], r0[1], SEL_LO);   // element 2: second column
+                        } else {
+                            uint32_t r0[1], r1[1];
+                            xvec_unpack(xr[k][2 * q], r0);
+                            xvec_unpack(xr[k][2 * q + 1], r1);
+                            lo[q] = __builtin_amdgcn_perm(r1[0], r0[0], SEL_LO);   // first column of the pair
+                            hi[q] = __builtin_amdgcn_perm(r1[0], r0[0], SEL_HI);   // second column
+                        }
                     }
                     *reinterpret_cast<u32x4*>(xl + ((u * NACC + 0) * 64 + lane) * 16) = lo;
                     *reinterpret_cast<u32x4*>(xl + ((u * NACC + 1) * 64 + lane) * 16) = hi;
@@ -197,13 +229,16 @@ __global__ __launch_bounds__(256, 4) void spmm_xlds_kernel(SpmmArgs p, int rows_
     }
 }
 
-// Covered: plain X (no lowering), 64 x 64 blocks, K <= 512 and a multiple of 16, Ncol a multiple of 4.
+// Covered: 64 x 64 blocks, K <= 512 and a multiple of 16, Ncol a multiple of 4; plain X, or the fused
+// lowering of a strided 1 x 1 filter (conv mode 4; channel planes of at most 2^27 elements as for every fused
+// lowering).
 inline bool xlds_covers(const SpmmArgs& a, int B) {
-    return a.act == nullptr && B == 64 && a.K <= XLDS_MAX_KB * 64 && (a.K % 16) == 0 && (a.Ncol % 4) == 0 &&
-           a.ldy <= ((int64_t)1 << 23) && a.ldx <= ((int64_t)1 << 23) && !(a.ep_on && a.ep_res && a.ep_ldr > ((int64_t)1 << 23));
+    const bool x_ok = a.act == nullptr ? a.ldx <= ((int64_t)1 << 23) : a.conv_mode == 4;
+    return x_ok && B == 64 && a.K <= XLDS_MAX_KB * 64 && (a.K % 16) == 0 && (a.Ncol % 4) == 0 &&
+           a.ldy <= ((int64_t)1 << 23) && !(a.ep_on && a.ep_res && a.ep_ldr > ((int64_t)1 << 23));
 }
 
-template <int N, int M, bool SMF>
+template <int N, int M, bool SMF, int CONV>
 hipError_t launch_xlds_k(const SpmmArgs& a, hipStream_t st) {
     const int Kb = (a.K + 63) / 64;
     const int64_t strips = (a.Ncol + 63) / 64;
@@ -223,7 +258,7 @@ hipError_t launch_xlds_k(const SpmmArgs& a, hipStream_t st) {
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
         if (!(raised.load() >> dev & 1)) {
-            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&spmm_xlds_kernel<N, M, SMF>),
+            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&spmm_xlds_kernel<N, M, SMF, CONV>),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, XLDS_MAX_KB * 8192 + XLDS_LIST * 4);
             if (e != hipSuccess) return e;
             raised.fetch_or((uint64_t)1 << dev);
@@ -231,18 +266,19 @@ hipError_t launch_xlds_k(const SpmmArgs& a, hipStream_t st) {
     }
     const dim3 grd((unsigned)wgs), blk(256);
     if (a.ev_start || a.ev_stop)
-        hipExtLaunchKernelGGL((spmm_xlds_kernel<N, M, SMF>), grd, blk, lds, st, a.ev_start, a.ev_stop, 0, a, rpg, row_groups, Kb);
+        hipExtLaunchKernelGGL((spmm_xlds_kernel<N, M, SMF, CONV>), grd, blk, lds, st, a.ev_start, a.ev_stop, 0, a, rpg, row_groups, Kb);
     else
-        spmm_xlds_kernel<N, M, SMF><<<grd, blk, lds, st>>>(a, rpg, row_groups, Kb);
+        spmm_xlds_kernel<N, M, SMF, CONV><<<grd, blk, lds, st>>>(a, rpg, row_groups, Kb);
     return hipGetLastError();
 }
 
 template <int N, int M>
 hipError_t launch_xlds(const SpmmArgs& a, hipStream_t st) {
+    const bool strided = a.act != nullptr;
     if constexpr (smf_pattern<N, M>()) {
-        if (a.use_smf) return launch_xlds_k<N, M, true>(a, st);
+        if (a.use_smf) return strided ? launch_xlds_k<N, M, true, 4>(a, st) : launch_xlds_k<N, M, true, 0>(a, st);
     }
-    return launch_xlds_k<N, M, false>(a, st);
+    return strided ? launch_xlds_k<N, M, false, 4>(a, st) : launch_xlds_k<N, M, false, 0>(a, st);
 }
 
 }  // namespace crisp

@@ -188,6 +188,11 @@ def test_lowering_choice_on_resnet50_shapes():
     assert pick(cs(256, 56, 56, 8, 1, 1, 2, 0), 512, 0.5) == "fused"          # 1x1 stride 2, few gathers per block column
     assert pick(cs(512, 28, 28, 8, 1, 1, 2, 0), 1024, 0.66) == "im2col"       # 1x1 stride 2, many: nothing inflated to save
     assert pick(cs(3, 224, 224, 8, 7, 7, 2, 3), 64, 0.5) == "fused"           # first layer: one block-row
+    # 1x1 stride 2, many gathers, but at most 512 channels, 8 or more block-rows, n <= 2 and many columns: the strided
+    # gather is staged once per strip in LDS for all block-rows
+    assert pick(cs(256, 56, 56, 64, 1, 1, 2, 0), 512, 0.9) == "fused"
+    assert crisp.lowering_path(cs(256, 56, 56, 64, 1, 1, 2, 0), 64, 4, 8, 512, 0.9) == "im2col"    # dense-expansion pattern
+    assert pick(cs(1024, 14, 14, 64, 1, 1, 2, 0), 2048, 0.9) == "im2col"      # more channels than that kernel holds
     assert crisp.conv_needs_scratch(cs(512, 14, 14, 8, 3, 3, 2, 1), 64, 2, 4, 512, 0.70)
     assert not crisp.conv_needs_scratch(cs(256, 14, 14, 8, 3, 3, 1, 1), 64, 2, 4, 256, 0.9)
     # scratch size of the materialised path: K x round_up(Ncol, 8) bf16; argument checks on the host

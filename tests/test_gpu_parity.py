@@ -475,6 +475,11 @@ CONV_CASES = [
     # strided 1x1 with even W and Wo: both columns of a lane from one 8-byte piece of the input row
     (128, 12, 12, 3, 1, 1, 0, 192, 2, 8, 64, 0.5, 2),
     (64, 8, 16, 2, 1, 1, 0, 96, 4, 8, 32, 0.6, 2),
+    # the same with many block-rows (forced shape 18: the gathered strip staged once in LDS for all of them),
+    # sparse and dense matrix-core patterns, the largest channel count that kernel takes
+    (256, 8, 12, 3, 1, 1, 0, 1100, 1, 8, 64, 0.5, 2),
+    (512, 4, 8, 5, 1, 1, 0, 320, 4, 8, 64, 0.6, 2),
+    (128, 28, 28, 2, 1, 1, 0, 512, 2, 4, 64, 0.5, 2),
     # strided shapes of the LDS-staged convolution (3x3, 5x5, 1x1 that skips input rows, stride 3)
     (128, 28, 28, 2, 3, 3, 1, 256, 2, 4, 64, 0.6, 2),
     (256, 28, 28, 2, 1, 1, 0, 256, 2, 4, 64, 0.6, 2),
@@ -529,7 +534,7 @@ def test_conv_spmm_implicit_lowering(case):
     dX = torch.zeros((L.K, ldx), dtype=torch.int16, device="cuda")
     crisp.crisp_im2col(conv, dact, dX, ldx)
     for yd, tdt in ((crisp.Y_F32, torch.float32), (crisp.Y_BF16, torch.bfloat16)):
-        for shape in (None, 1, 2, 3, 8, 9, 10, 12, 14):    # 12 / 14: input staged in LDS (where they apply)
+        for shape in (None, 1, 2, 3, 8, 9, 10, 12, 14, 18):    # 12 / 14 / 18: input staged in LDS (where they apply)
             Y = torch.full((S + 1, ldy), float("nan"), dtype=tdt, device="cuda")
             conv_spmm(layer.desc, conv, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dact, Y,
                                   ldy, yd, shape=shape)
@@ -537,7 +542,7 @@ def test_conv_spmm_implicit_lowering(case):
             Yh = Y.float().cpu().numpy().astype(np.float64)
             assert np.isnan(Yh[:S, Ncol:]).all() and np.isnan(Yh[S]).all()
             check_product(Yh[:S, :Ncol], Yref, Aref, yd, "conv %s shape %s" % (case, shape))
-            if shape is not None and shape not in (12, 14) and Ncol % 4 == 0 and L.K % 16 == 0:
+            if shape is not None and shape not in (12, 14, 18) and Ncol % 4 == 0 and L.K % 16 == 0:
                 # (other K or Ncol: the explicit path runs the generic kernel, a different summation order)
                 Ye = run_spmm(layer, dX, Ncol, ldx, yd, S, ldy=ldy, shape=shape)
                 assert (Ye == Yh[:S, :Ncol]).all(), "implicit and explicit lowering differ"
