@@ -70,6 +70,9 @@ def parse():
                          "whole-grid block pruning leaves block-rows of very different length (e.g. 1.6)")
     ap.add_argument("--shape", type=int, default=None,
                     help="--layer mode, plain products: force this launch shape (crisp_spmm_forced) instead of the library's choice")
+    ap.add_argument("--two-of-four", action="store_true",
+                    help="--layer mode, 4:8 layers: weights whose kept values fall two per aligned four (magnitude saliency), and the "
+                         "product told so (CRISP_HINT_TWO_OF_FOUR) once the pack's flag has been read back as 1")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 512 MiB device copy a few times (known traffic, for scaling profiler counters)")
     return ap.parse_args()
@@ -736,11 +739,24 @@ def run_layer(args):
         scale = np.repeat(np.float32(args.row_skew) ** -np.arange(Sb, dtype=np.float32), L.B)[: L.S, None]
         TG = (np.abs(synth.bf16_bits_to_f32(t["W"])) * scale).astype(np.float32)
         sal_kind = crisp.SAL_GIVEN
+    if args.two_of_four:
+        if (L.n, L.m) != (4, 8) or args.row_skew > 0.0:
+            print("bench.py: --two-of-four applies to 4:8 layers (without --row-skew)", file=sys.stderr)
+            sys.exit(2)
+        t["W"] = synth.draw_two_per_quad_weight(np.random.Generator(np.random.PCG64([wl.seed, li])), L.S, L.K)
+        sal_kind, TG = crisp.SAL_MAG, None
     desc = crisp.layer_desc(L.S, L.K, L.n, L.m, L.B, L.density, sal_kind, crisp.LAYER_TOPK if args.topk else L.select_mode)
     dl = crisp.alloc_layer(desc, dev)
     W = torch.from_numpy(t["W"].view(np.int16)).to(dev)
     G = torch.from_numpy(TG).to(dev) if TG is not None else None
     crisp.prune_and_pack(dl, W, G)
+    if args.two_of_four:
+        if int(dl.flags.cpu()[0]) != 1:
+            print("bench.py: the pack did not report the 2-of-4 property", file=sys.stderr)
+            sys.exit(1)
+        desc = crisp.layer_desc(L.S, L.K, L.n, L.m, L.B, L.density, sal_kind, crisp.LAYER_TOPK if args.topk else L.select_mode,
+                                hints=crisp.HINT_TWO_OF_FOUR)
+        dl.desc = desc
     cv = L.conv if L.conv is not None else synth.ConvShape(L.K, 1, L.Ncol, 1, 1, 1, 1, 0)    # a plain product as a 1x1 layer
     in_elems = cv.C * cv.batch * cv.H * cv.W
     nbuf = max(2, min(16, int(600e6 // (2 * in_elems + ybytes * L.S * L.Ncol)) + 1))

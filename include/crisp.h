@@ -75,8 +75,18 @@ typedef struct {
     int32_t B;             /* block edge, 16 | 32 | 64, B % m == 0                                 */
     int32_t sal_kind;      /* CRISP_SAL_*                                                          */
     int32_t select_mode;   /* CRISP_ROW_UNIFORM | CRISP_LAYER_TOPK                                 */
-    int32_t reserved;      /* must be 0                                                            */
+    int32_t hints;         /* CRISP_HINT_* bits, read by the product calls only; other bits must be 0 */
 } crisp_layer_desc;
+
+/*
+ * CRISP_HINT_TWO_OF_FOUR: the caller has read flags[0] == 1 from the crisp_pack / crisp_select_pack call
+ * that produced the vals / idx_words it passes to the product: no aligned group of four columns holds more
+ * than two kept values.  A 4:8 layer may then go to the sparse matrix-core instruction like a 2:4 layer
+ * (Sec. 3.5 keeps the weights compressed next to the multipliers).  The flag lives on the device and the
+ * kernel is chosen on the host, hence a hint; unlike block_density it is an assertion: with the bit set
+ * for a pack whose flag is 0 the product is wrong.  Ignored for every pattern other than 4:8.
+ */
+enum { CRISP_HINT_TWO_OF_FOUR = 1 };
 
 typedef struct {
     int32_t Sb, Kb;            /* block grid: ceil(S/B) x ceil(K/B)                              */

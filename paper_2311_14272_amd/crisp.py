@@ -17,6 +17,7 @@ OK, EINVAL, ESHAPE, EBUFSIZE, EALIGN, EUNSUPPORTED, EDEVICE = range(7)
 SAL_GIVEN, SAL_GRAD, SAL_MAG = 0, 1, 2
 ROW_UNIFORM, LAYER_TOPK = 0, 1
 X_KN, X_K8 = 0, 1
+HINT_TWO_OF_FOUR = 1
 Y_F32, Y_BF16 = 0, 1
 ACT_CBHW = 0
 
@@ -24,7 +25,7 @@ ACT_CBHW = 0
 class LayerDesc(C.Structure):
     _fields_ = [("block_density", C.c_double), ("S", C.c_int32), ("K", C.c_int32), ("n", C.c_int32),
                 ("m", C.c_int32), ("B", C.c_int32), ("sal_kind", C.c_int32), ("select_mode", C.c_int32),
-                ("reserved", C.c_int32)]
+                ("hints", C.c_int32)]
 
 
 class Sizes(C.Structure):
@@ -131,8 +132,8 @@ def _stream() -> Optional[int]:
     return torch.cuda.current_stream().cuda_stream or None
 
 
-def layer_desc(S, K, n, m, B, block_density=1.0, sal_kind=SAL_MAG, select_mode=ROW_UNIFORM) -> LayerDesc:
-    return LayerDesc(float(block_density), S, K, n, m, B, sal_kind, select_mode, 0)
+def layer_desc(S, K, n, m, B, block_density=1.0, sal_kind=SAL_MAG, select_mode=ROW_UNIFORM, hints=0) -> LayerDesc:
+    return LayerDesc(float(block_density), S, K, n, m, B, sal_kind, select_mode, hints)
 
 
 def crisp_pack_sizes(desc: LayerDesc) -> Sizes:

@@ -19,8 +19,9 @@ crisp_status make_geometry(const crisp_layer_desc* d, bool need_density, Geometr
     if (d->B % d->m != 0) return CRISP_EINVAL;
     if (d->sal_kind < CRISP_SAL_GIVEN || d->sal_kind > CRISP_SAL_MAG) return CRISP_EINVAL;
     if (d->select_mode != CRISP_ROW_UNIFORM && d->select_mode != CRISP_LAYER_TOPK) return CRISP_EINVAL;
-    if (d->reserved != 0) return CRISP_EINVAL;
+    if (d->hints & ~CRISP_HINT_TWO_OF_FOUR) return CRISP_EINVAL;
     g->S = d->S; g->K = d->K; g->n = d->n; g->m = d->m; g->B = d->B;
+    g->two_of_four = (d->hints & CRISP_HINT_TWO_OF_FOUR) && d->n == 4 && d->m == 8;
     g->Sb = ceil_div(d->S, d->B);
     g->Kb = ceil_div(d->K, d->B);
     g->w = d->m == 4 ? 2 : 3;

@@ -14,6 +14,7 @@ struct Geometry {
     int slots;  // value slots per block row
     int wpr;    // index words per block row
     int mwpr;   // mask words per weight row
+    int two_of_four;   // 4:8 whose pack the caller asserts to hold at most two values per aligned four (products only)
 };
 
 // Host-side validation + derived sizes; no device calls.

@@ -455,7 +455,7 @@ static bool prefer_lds(const Geometry& g, int64_t Ncol, int blocks_per_row) {
     if (g.B != 64 || blocks_per_row > lds_capacity(g.B)) return false;
     // patterns that feed the sparse matrix core need no (or little) expansion: the register kernels, or
     // residency in that operand form (prefer_lds_smf), are faster
-    if (g.n <= 2) return false;
+    if (g.n <= 2 || g.two_of_four) return false;
     const int64_t narrow = (int64_t)g.Sb * ((Ncol + 63) / 64);
     const int slots_per_operand = (8 / g.m) * g.n;
     return narrow >= 2048 && (slots_per_operand >= 4 || blocks_per_row >= 6);
@@ -468,7 +468,7 @@ static bool prefer_lds(const Geometry& g, int64_t Ncol, int blocks_per_row) {
 // 30-tile instantiation (one workgroup of eight waves per compute unit), which beat the 15-tile one (two
 // workgroups of four) on every layer with six or more blocks.
 static bool prefer_lds_smf(const Geometry& g, int64_t Ncol, int blocks_per_row) {
-    if (g.B != 64 || g.n > 2 || blocks_per_row < 6 || blocks_per_row > lds_smf_capacity()) return false;
+    if (g.B != 64 || !(g.n <= 2 || g.two_of_four) || blocks_per_row < 6 || blocks_per_row > lds_smf_capacity()) return false;
     const int64_t narrow = (int64_t)g.Sb * ((Ncol + 63) / 64);
     return narrow >= 2048;
 }
@@ -509,7 +509,7 @@ bool xlds_conv_would_run(const Geometry& g, const crisp_conv_desc& conv, int64_t
     const int64_t Wo = ((int64_t)conv.W + 2 * conv.pad - conv.kw) / conv.stride + 1;
     const bool strided_1x1 = conv.kh == 1 && conv.kw == 1 && conv.stride == 2 && conv.pad == 0 && (conv.W & 1) == 0 &&
                              (Wo & 1) == 0 && conv.C % 64 == 0;
-    return strided_1x1 && g.B == 64 && g.n <= 2 && g.K <= XLDS_MAX_KB * 64 && (Ncol % 4) == 0 && xlds_pays(g.Sb, g.Kb, Ncol, true);
+    return strided_1x1 && g.B == 64 && (g.n <= 2 || g.two_of_four) && g.K <= XLDS_MAX_KB * 64 && (Ncol % 4) == 0 && xlds_pays(g.Sb, g.Kb, Ncol, true);
 }
 
 // Whether launch_spmm, left to its own choice, runs this convolution in the kernel that stages the
@@ -539,6 +539,10 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
     a.Sb = g.Sb; a.NT = 0; a.Ncol = Ncol; a.ldx = ldx; a.ldy = ldy;
     a.row_ptr = row_ptr; a.col_idx = col_idx; a.vals = vals; a.idxw = idxw; a.X = X; a.Y = Y;
     a.y_bf16 = (y_dtype == CRISP_Y_BF16);
+    // patterns that may go to the sparse matrix-core instruction: at most two kept per group, or 4:8 whose pack
+    // the caller asserts to hold at most two values per aligned four (kernel families for plain X only)
+    const bool smf_ok = g.n <= 2 || g.two_of_four;
+    a.two_of_four = g.two_of_four;
     if (ep && (ep->scale || ep->bias || ep->residual || ep->relu)) {
         a.ep_on = 1; a.ep_relu = ep->relu ? 1 : 0;
         a.ep_scale = ep->scale; a.ep_bias = ep->bias; a.ep_res = ep->residual; a.ep_ldr = ep->ldr;
@@ -624,7 +628,7 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
     }
     // the same with the blocks resident as sparse matrix-core operands (forced shapes 16 and 17, the latter
     // always the 30-tile instantiation): 64 x 64 blocks, at most two kept values per group
-    const bool lds_smf_ok = lds_ok && g.B == 64 && g.n <= 2;
+    const bool lds_smf_ok = lds_ok && g.B == 64 && smf_ok;
     if (lds_smf_ok && (force_shape == CRISP_SHAPE_LDS_SMF || force_shape == CRISP_SHAPE_LDS_SMF_30)) {
         const int variant = force_shape == CRISP_SHAPE_LDS_SMF ? 0 : 2;
         report(CRISP_KERNEL_LDS, (variant == 2 || bpr > 14) ? 2 : 0, 0, 1);
@@ -667,7 +671,7 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
     // written; a plain fill of 411 MB takes 61 us, a copy of 257 + 257 MB 97 us); equal within
     // 6 % either way for two block columns or the dense-expansion patterns
     const bool xres = xres_covers(a, g.B) &&
-        (force_shape == 13 || (force_shape < 0 && g.Kb == 1 && g.Sb >= 2 && g.n <= 2 && Ncol >= ((int64_t)1 << 18)));
+        (force_shape == 13 || (force_shape < 0 && g.Kb == 1 && g.Sb >= 2 && smf_ok && Ncol >= ((int64_t)1 << 18)));
     // X strip resident in LDS as operands for all block-rows (forced shape 18)
     // Chosen for patterns that go to the sparse matrix-core instruction when at least 16 block-rows share
     // two to eight block columns and there are enough columns for a workgroup per compute unit: 1.2-1.45x on
@@ -679,11 +683,11 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
     // alone is 411 MB there, of which every line is touched).
     const bool xlds = !xres && xlds_covers(a, g.B) &&
         (force_shape == CRISP_SHAPE_XLDS ||
-         (force_shape < 0 && g.n <= 2 && xlds_pays(g.Sb, g.Kb, Ncol, conv != nullptr)));
+         (force_shape < 0 && smf_ok && xlds_pays(g.Sb, g.Kb, Ncol, conv != nullptr)));
     const int shape = xres ? XRES_SHAPE : xlds ? XLDS_SHAPE
                     : (force_shape >= 0 && force_shape <= 3) ? force_shape
                     : (force_shape >= 7 && force_shape <= 10) ? force_shape - 7
-                    : pick_shape(g, Ncol, bpr, a.use_smf && g.n <= 2);
+                    : pick_shape(g, Ncol, bpr, a.use_smf && smf_ok);
     // the specialised kernels assume whole 16-row MFMA steps of X (K % 16 == 0) and whole groups
     // of four output columns per lane (Ncol % 4 == 0)
     if (conv || (force_shape != 4 && (g.K % 16) == 0 && (Ncol % 4) == 0 && ld_wide <= ((int64_t)1 << 23))) {
@@ -693,7 +697,7 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
         // (the fused lowering has the narrow shapes only)
         const int shape_run = (xres || xlds) ? 0 : (conv && shape == 0) ? 1 : shape;
         if (known) report(xres ? CRISP_KERNEL_XRES : xlds ? CRISP_KERNEL_XLDS : CRISP_KERNEL_REG, shape_run, conv ? a.conv_mode : 0,
-                          a.use_smf && g.n <= 2);
+                          a.use_smf && (g.n <= 2 || (g.two_of_four && (!conv || xlds))));
         switch (key) {
             case 1 * 16 + 4: return launch_reg_nm<1, 4>(a, g.B, shape, st);
             case 2 * 16 + 4: return launch_reg_nm<2, 4>(a, g.B, shape, st);

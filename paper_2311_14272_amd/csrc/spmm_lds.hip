@@ -523,6 +523,7 @@ hipError_t launch_spmm_lds_smf(const SpmmArgs& a, int max_blocks, int variant, h
         case 2 * 16 + 4: return launch_lds_smf_nm<2, 4>(a, max_blocks, variant, st);
         case 1 * 16 + 8: return launch_lds_smf_nm<1, 8>(a, max_blocks, variant, st);
         case 2 * 16 + 8: return launch_lds_smf_nm<2, 8>(a, max_blocks, variant, st);
+        case 4 * 16 + 8: return a.two_of_four ? launch_lds_smf_nm<4, 8>(a, max_blocks, variant, st) : hipErrorInvalidValue;
         default: return hipErrorInvalidValue;
     }
 }

@@ -72,6 +72,7 @@ struct SpmmArgs {
     const void* ep_res;       // S x ep_ldr, same element type as Y
     int64_t ep_ldr;
     int use_smf;              // host side only: sparse-MFMA instantiation wanted (eligible patterns)
+    int two_of_four;          // host side only: 4:8 pack with at most two values per aligned four (caller's assertion)
     // host side only: optional events that receive the kernel's own start and stop time stamps
     hipEvent_t ev_start, ev_stop;
 };
@@ -353,7 +354,17 @@ __device__ __forceinline__ void smf_operand(const uint32_t (&av)[Fmt<N, M, B>::K
         // the lane's 16 columns are two groups of 8; position bits of both: 2 * HB bits from P
         uint32_t field = ws[P >> 5] >> (P & 31);
         if constexpr ((P & 31) + 2 * F::HB > 32 && (P >> 5) + 1 < F::WPR) field |= ws[(P >> 5) + 1] << (32 - (P & 31));
-        if constexpr (N == 2) {
+        if constexpr (N == 4) {
+            // 4:8 with at most two kept values per aligned four (the pack's flag, asserted by the caller): every
+            // full group of eight holds exactly two in its lower and two in its upper four, stored in ascending
+            // column order, so the stored values are the operand as they are (like 2:4) and a value's position
+            // inside its four is the low two bits of its 3-bit position.  (Groups past K or S hold zeros at
+            // positions 0..3: two "values" per four as well.)
+            a4 = u32x4{av[2 * s2][0], av[2 * s2][1], av[2 * s2 + 1][0], av[2 * s2 + 1][1]};
+            idx = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) idx |= ((field >> (3 * i)) & 3u) << (2 * i);
+        } else if constexpr (N == 2) {
             // group g: stored (v0, v1) at positions (p0, p1); the lower 4-group takes those with
             // position < 4, the upper the others, both with in-group positions (p0 & 3, p1 & 3)
             uint32_t d[4];
@@ -408,6 +419,14 @@ __device__ __forceinline__ void smf_operand(const uint32_t (&av)[Fmt<N, M, B>::K
 // aligned four): the 8-group's stored values go to the lower or the upper 4-group by position bit 2.
 template <int N, int M>
 constexpr bool smf_pattern() { return N <= 2; }
+// 4:8 also qualifies when the packed layer holds at most two values per aligned four (the flag crisp_pack
+// reports; SpmmArgs::two_of_four carries the caller's assertion).  Only the kernel families for plain X
+// are instantiated for it (register kernels, X-resident kernels, LDS-resident sparse operands).
+template <int N, int M>
+constexpr bool smf_flagged_pattern() { return N == 4 && M == 8; }
+// whether the launch of pattern N:M goes to the sparse matrix-core instantiation
+template <int N, int M>
+inline bool smf_wanted(const SpmmArgs& a) { return a.use_smf && (smf_pattern<N, M>() || a.two_of_four); }
 
 template <int N, int M, int B, int WD, bool PREFETCH, int CONV, bool SMF = false>
 struct BlockBody {
@@ -990,8 +1009,8 @@ hipError_t launch_reg_k(const SpmmArgs& a, hipStream_t st) {
 
 template <int N, int M, int B, int WD, int NWK, int PF, int CONV>
 hipError_t launch_reg(const SpmmArgs& a, hipStream_t st) {
-    if constexpr (smf_pattern<N, M>()) {
-        if (a.use_smf) return launch_reg_k<N, M, B, WD, NWK, PF, CONV, true>(a, st);
+    if constexpr (smf_pattern<N, M>() || (smf_flagged_pattern<N, M>() && CONV == 0)) {
+        if (smf_wanted<N, M>(a)) return launch_reg_k<N, M, B, WD, NWK, PF, CONV, true>(a, st);
     }
     return launch_reg_k<N, M, B, WD, NWK, PF, CONV, false>(a, st);
 }

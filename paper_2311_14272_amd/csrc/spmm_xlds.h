@@ -275,8 +275,8 @@ hipError_t launch_xlds_k(const SpmmArgs& a, hipStream_t st) {
 template <int N, int M>
 hipError_t launch_xlds(const SpmmArgs& a, hipStream_t st) {
     const bool strided = a.act != nullptr;
-    if constexpr (smf_pattern<N, M>()) {
-        if (a.use_smf) return strided ? launch_xlds_k<N, M, true, 4>(a, st) : launch_xlds_k<N, M, true, 0>(a, st);
+    if constexpr (smf_pattern<N, M>() || smf_flagged_pattern<N, M>()) {
+        if (smf_wanted<N, M>(a)) return strided ? launch_xlds_k<N, M, true, 4>(a, st) : launch_xlds_k<N, M, true, 0>(a, st);
     }
     return strided ? launch_xlds_k<N, M, false, 4>(a, st) : launch_xlds_k<N, M, false, 0>(a, st);
 }

@@ -183,8 +183,8 @@ hipError_t launch_xres_k(const SpmmArgs& a, hipStream_t st) {
 
 template <int N, int M>
 hipError_t launch_xres(const SpmmArgs& a, hipStream_t st) {
-    if constexpr (smf_pattern<N, M>()) {
-        if (a.use_smf) return a.K <= 64 ? launch_xres_k<N, M, true, 1>(a, st) : launch_xres_k<N, M, true, 2>(a, st);
+    if constexpr (smf_pattern<N, M>() || smf_flagged_pattern<N, M>()) {
+        if (smf_wanted<N, M>(a)) return a.K <= 64 ? launch_xres_k<N, M, true, 1>(a, st) : launch_xres_k<N, M, true, 2>(a, st);
     }
     return a.K <= 64 ? launch_xres_k<N, M, false, 1>(a, st) : launch_xres_k<N, M, false, 2>(a, st);
 }

@@ -232,6 +232,16 @@ def small_cases() -> List[LayerSpec]:
     ]
 
 
+def draw_two_per_quad_weight(rng: np.random.Generator, S: int, K: int) -> np.ndarray:
+    """bf16 bits of a weight whose four largest magnitudes in every group of eight columns are two per aligned
+    group of four (random places, random signs): what a 4:8 pruning keeps of it passes the 2-of-4 test of the
+    pack.  K must be a multiple of 4."""
+    r = rng.random((S, K // 4, 4))
+    big = (np.argsort(np.argsort(r, axis=2), axis=2) >= 2).reshape(S, K)
+    mag = np.where(big, 2.0, 0.3) * rng.uniform(1.0, 1.4, size=(S, K))
+    return f32_to_bf16_bits((mag * rng.choice([-1.0, 1.0], size=(S, K))).astype(np.float32))
+
+
 def b16_cases() -> List[LayerSpec]:
     """16 x 16 blocks (the paper's smallest block size)."""
     mk = LayerSpec

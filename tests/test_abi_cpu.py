@@ -80,6 +80,8 @@ def test_pack_sizes_values():
     (dict(B=16, m=8, n=2), None), (dict(block_density=0.0), crisp.EINVAL), (dict(block_density=1.5), crisp.EINVAL),
     (dict(block_density=float("nan")), crisp.EINVAL), (dict(S=0), crisp.ESHAPE), (dict(K=-3), crisp.ESHAPE),
     (dict(sal_kind=7), crisp.EINVAL), (dict(select_mode=2), crisp.EINVAL),
+    # hints: the one defined bit is accepted for any pattern (it only means something for 4:8), unknown bits are refused
+    (dict(hints=1), None), (dict(hints=1, n=4, m=8), None), (dict(hints=2), crisp.EINVAL), (dict(hints=-1), crisp.EINVAL),
     # packed values of the whole grid: 4 GiB and one block column less
     (dict(S=32768, K=65536, n=4, m=4, B=64), crisp.ESHAPE), (dict(S=32768, K=65536 - 64, n=4, m=4, B=64), None)])
 def test_descriptor_validation(kw, status):
