@@ -80,6 +80,10 @@ __global__ __launch_bounds__(256, 4) void conv_lds_kernel(SpmmArgs p, ConvLdsSch
 
     // ---- the wave's kept blocks in (channel block, tap) order -------------------------------------
     for (int e = tid; e < 4 * (CONV_LDS_MAX_KB / 32); e += 256) (&kept_bits[0][0])[e] = 0u;
+    // selector table of the dense 4:8 expansion (visible after the barriers below)
+    constexpr bool LUT48 = lut48_pattern<N, M, SMF>();
+    __shared__ u32x4 lut48[LUT48 ? 256 : 1];
+    if constexpr (LUT48) lut48_fill(lut48, tid, 256);
     __syncthreads();
     int t_begin = 0, cnt = 0;
     if (works) {
@@ -211,7 +215,9 @@ __global__ __launch_bounds__(256, 4) void conv_lds_kernel(SpmmArgs p, ConvLdsSch
                     bfrag[c] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(base + c * col_step + ks * 32));
 #pragma unroll
                 for (int rt = 0; rt < RT; ++rt) {
-                    const u32x4 a4 = expand_frag<N, M, B, ks>(av[rt][ks], ws[rt]);
+                    u32x4 a4;
+                    if constexpr (LUT48) a4 = expand_frag_lut48<B, ks>(av[rt][ks], ws[rt], lut48);
+                    else a4 = expand_frag<N, M, B, ks>(av[rt][ks], ws[rt]);
                     const bf16x8 afrag = __builtin_bit_cast(bf16x8, a4);
 #pragma unroll
                     for (int c = 0; c < NACC; ++c)

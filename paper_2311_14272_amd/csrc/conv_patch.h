@@ -59,6 +59,10 @@ __global__ __launch_bounds__(256, 3) void conv_patch_kernel(SpmmArgs p, ConvPatc
     const int t_last = __builtin_amdgcn_readlane(my_ptr, p.Sb) - 1;
     const int my_bj = p.col_idx[max(min(lane, t_last), 0)];
 
+    // selector table of the dense 4:8 expansion (visible after the barriers below)
+    constexpr bool LUT48 = lut48_pattern<N, M, SMF>();
+    __shared__ u32x4 lut48[LUT48 ? 256 : 1];
+    if constexpr (LUT48) lut48_fill(lut48, tid, 256);
     // ---- K-row table, zeroed patch ------------------------------------------------------------------
     uint32_t* koff = reinterpret_cast<uint32_t*>(lds);
     unsigned char* patch = lds + sc.patch_off;
@@ -196,7 +200,9 @@ __global__ __launch_bounds__(256, 3) void conv_patch_kernel(SpmmArgs p, ConvPatc
                     operands(bj, ks, bo[0], bo[1]);
 #pragma unroll
                     for (int rt = 0; rt < RT; ++rt) {
-                        const u32x4 a4 = expand_frag<N, M, B, ks>(av[rt][ks], ws[rt]);
+                        u32x4 a4;
+                        if constexpr (LUT48) a4 = expand_frag_lut48<B, ks>(av[rt][ks], ws[rt], lut48);
+                        else a4 = expand_frag<N, M, B, ks>(av[rt][ks], ws[rt]);
                         const bf16x8 afrag = __builtin_bit_cast(bf16x8, a4);
 #pragma unroll
                         for (int c = 0; c < NACC; ++c)

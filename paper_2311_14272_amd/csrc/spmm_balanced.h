@@ -48,6 +48,10 @@ __global__ __launch_bounds__(64 * BAL_NW) __attribute__((amdgpu_waves_per_eu(2, 
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // selector table of the dense 4:8 expansion (visible after the barrier that follows the row_ptr copy)
+    constexpr bool LUT48 = lut48_pattern<N, M, SMF>();
+    __shared__ u32x4 lut48[LUT48 ? 256 : 1];
+    if constexpr (LUT48) lut48_fill(lut48, tid, 64 * NW);
     const int jj = lane & 31, hh = lane >> 5;
     const int64_t wave_col = (int64_t)nt * 64;
     const int64_t col0 = wave_col + jj * NACC;
@@ -119,7 +123,7 @@ __global__ __launch_bounds__(64 * BAL_NW) __attribute__((amdgpu_waves_per_eu(2, 
         }
     }
     int pending_row = -1;                                 // row begun here that later waves continue
-    const ConvPos cp = {0, 0, 0, 0u, 0, 0, 0};
+    const ConvPos cp = {0, 0, 0, 0u, 0, 0, 0, lut48};
     for (int bi = r0; bi < r1; ++bi) {
         const int row_begin = rpu(bi), row_end = rpu(bi + 1);
         bool store = false;

@@ -131,8 +131,15 @@ void spmm_k8_kernel(SpmmArgs p) {
     if (nt >= p.NT) return;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int jj = lane & 31, hh = lane >> 5;
+    // selector table of the dense 4:8 expansion, built by the whole workgroup before any wave leaves
+    constexpr bool LUT48 = lut48_pattern<N, M, SMF>();
+    __shared__ u32x4 lut48[LUT48 ? 256 : 1];
+    if constexpr (LUT48) {
+        lut48_fill(lut48, tid, 256);
+        __syncthreads();
+    }
     const int64_t wave_col = ((int64_t)nt * 4 + wave) * 64;
-    if (wave_col >= p.Ncol) return;                          // no barriers in this kernel
+    if (wave_col >= p.Ncol) return;                          // no further barriers in this kernel
     const int64_t col[2] = {wave_col + jj, wave_col + 32 + jj};
     const bool ok[2] = {col[0] < p.Ncol, col[1] < p.Ncol};
     // lanes past the last column read the last column instead (in bounds) and never store
@@ -156,7 +163,7 @@ void spmm_k8_kernel(SpmmArgs p) {
         uint32_t xr[PF][KS][8];
         uint32_t av[PF][RT][KS][F::VW], aw[PF][RT][F::WPR];
         XCtx cx[PF];
-        const ConvPos cp = {0, 0, 0, 0u, 0, 0, 0};
+        const ConvPos cp = {0, 0, 0, 0u, 0, 0, 0, lut48};
         // ---- prologue: up to PF blocks in flight ------------------------------------------------
 #pragma unroll
         for (int d = 0; d < PF; ++d) {

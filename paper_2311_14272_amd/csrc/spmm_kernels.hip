@@ -436,6 +436,10 @@ static int pick_shape(const Geometry& g, int64_t Ncol, int blocks_per_row, bool 
         // are very few: c1 with 392 tiles 9.5 vs 11.7 us, c4a with 490 tiles 14.7 vs 12.2 us)
         return (blocks_per_row >= 8 && (g.B == 64 || narrow < 448)) ? 2 : 1;
     }
+    // 4:8 expands through a selector table (a handful of instructions per operand): as with the sparse
+    // instruction there is little to share between columns, and narrow strips win from two blocks per row on
+    // (five 1x1 layers of ResNet-50 at batch 256: 44-86 us against 52-94 us; equal or slower for single blocks)
+    if (g.n == 4 && g.m == 8 && blocks_per_row >= 2 && narrow >= 1024) return 1;
     if (wide >= 4096) return 0;
     if (blocks_per_row >= 8 && wide >= 512) return 0;
     if (narrow >= 3072 || blocks_per_row < 3) return 1;
@@ -458,6 +462,9 @@ static bool prefer_lds(const Geometry& g, int64_t Ncol, int blocks_per_row) {
     if (g.n <= 2 || g.two_of_four) return false;
     const int64_t narrow = (int64_t)g.Sb * ((Ncol + 63) / 64);
     const int slots_per_operand = (8 / g.m) * g.n;
+    // (4:8 in registers goes through the selector table: residency only pays on long rows there -- 12 blocks:
+    // 54 against 57 us, 9 blocks: 49 against 47 us, 3 blocks: 48-95 against 44-86 us)
+    if (g.n == 4 && g.m == 8) return narrow >= 2048 && blocks_per_row >= 10;
     return narrow >= 2048 && (slots_per_operand >= 4 || blocks_per_row >= 6);
 }
 
@@ -509,7 +516,9 @@ bool xlds_conv_would_run(const Geometry& g, const crisp_conv_desc& conv, int64_t
     const int64_t Wo = ((int64_t)conv.W + 2 * conv.pad - conv.kw) / conv.stride + 1;
     const bool strided_1x1 = conv.kh == 1 && conv.kw == 1 && conv.stride == 2 && conv.pad == 0 && (conv.W & 1) == 0 &&
                              (Wo & 1) == 0 && conv.C % 64 == 0;
-    return strided_1x1 && g.B == 64 && (g.n <= 2 || g.two_of_four) && g.K <= XLDS_MAX_KB * 64 && (Ncol % 4) == 0 && xlds_pays(g.Sb, g.Kb, Ncol, true);
+    const bool sparse_ok = g.n <= 2 || g.two_of_four, dense48 = g.n == 4 && g.m == 8;
+    return strided_1x1 && g.B == 64 && g.K <= XLDS_MAX_KB * 64 && (Ncol % 4) == 0 &&
+           ((sparse_ok && xlds_pays(g.Sb, g.Kb, Ncol, true)) || (dense48 && xlds_pays(g.Sb, g.Kb, Ncol, false)));
 }
 
 // Whether launch_spmm, left to its own choice, runs this convolution in the kernel that stages the
@@ -634,11 +643,17 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
         report(CRISP_KERNEL_LDS, (variant == 2 || bpr > 14) ? 2 : 0, 0, 1);
         return launch_spmm_lds_smf(a, bpr, variant, st);
     }
-    if (lds_smf_ok && force_shape < 0 && hint && uniform_rows && prefer_lds_smf(g, Ncol, bpr)) {
+    // the kernels that keep X on chip for all block-rows come first where their rules (further down) apply
+    const bool x_dense48 = g.n == 4 && g.m == 8;           // dense expansion through the selector table
+    const bool xres_auto = !conv && g.Kb == 1 && g.Sb >= 2 && (smf_ok || x_dense48) && Ncol >= ((int64_t)1 << 18);
+    const bool xlds_auto = (smf_ok && xlds_pays(g.Sb, g.Kb, Ncol, conv != nullptr)) ||
+                           (x_dense48 && xlds_pays(g.Sb, g.Kb, Ncol, false));
+    const bool x_on_chip = force_shape < 0 && g.B == 64 && (g.K % 16) == 0 && (Ncol % 4) == 0 && (xres_auto || xlds_auto);
+    if (lds_smf_ok && force_shape < 0 && hint && uniform_rows && !x_on_chip && prefer_lds_smf(g, Ncol, bpr)) {
         report(CRISP_KERNEL_LDS, 2, 0, 1);
         return launch_spmm_lds_smf(a, bpr, 2, st);
     }
-    if (lds_ok && force_shape < 0 && hint && uniform_rows && prefer_lds(g, Ncol, bpr)) {
+    if (lds_ok && force_shape < 0 && hint && uniform_rows && !x_on_chip && prefer_lds(g, Ncol, bpr)) {
         report(CRISP_KERNEL_LDS, lds_variant(bpr <= 1), 0, 0);
         return launch_spmm_lds(a, g.B, bpr, bpr <= 1, st);
     }
@@ -668,22 +683,26 @@ hipError_t launch_spmm(const Geometry& g, double density_hint, bool uniform_rows
     // X-resident kernel for short K (forced shape 13).  Chosen for one block column, several
     // block-rows, patterns that go to the sparse matrix-core instruction and long X rows: 1.12x on the
     // 64 -> 256 channel layers of ResNet-50 at batch 256 (107 vs 120 us for 103 MB read and 411 MB
-    // written; a plain fill of 411 MB takes 61 us, a copy of 257 + 257 MB 97 us); equal within
-    // 6 % either way for two block columns or the dense-expansion patterns
+    // written; a plain fill of 411 MB takes 61 us, a copy of 257 + 257 MB 97 us), 1.19x for 4:8 expanded
+    // through the selector table (117 vs 140 us in the LDS-resident kernel); equal within 6 % either way for
+    // two block columns or the other dense-expansion patterns
     const bool xres = xres_covers(a, g.B) &&
-        (force_shape == 13 || (force_shape < 0 && g.Kb == 1 && g.Sb >= 2 && smf_ok && Ncol >= ((int64_t)1 << 18)));
+        (force_shape == 13 || (force_shape < 0 && xres_auto));
     // X strip resident in LDS as operands for all block-rows (forced shape 18)
     // Chosen for patterns that go to the sparse matrix-core instruction when at least 16 block-rows share
     // two to eight block columns and there are enough columns for a workgroup per compute unit: 1.2-1.45x on
     // the 256 -> 1024 and 512 -> 2048 channel layers of ResNet-50 at batch 256 (rows of one to three blocks:
     // 29-37 us against 37-52 us, 20-23 us against 23-28 us); 0.75-1.0x with 8 block-rows or fewer, with one
-    // block column (the register-resident kernel above is for those) and for the dense-expansion patterns.
+    // block column (the register-resident kernel above is for those).  4:8 expanded through the selector table
+    // gains as well from 16 block-rows on (1024 x 256 x 50176: 39.5 against 49.4 us in the LDS-resident kernel,
+    // 2048 x 512 x 12544: 39.7 against 48.7 us; stage-3 shortcut of ResNet-50 with the strided lowering fused in:
+    // 112 us against 123 us through a materialised X); the other dense-expansion patterns do not.
     // With the lowering of a strided 1 x 1 filter fused in, the strided gather is done once per strip instead of
     // once per block-row: chosen from 8 block-rows on (512 x 256 x 200704 1:8: 134 against 165 us; the input
     // alone is 411 MB there, of which every line is touched).
     const bool xlds = !xres && xlds_covers(a, g.B) &&
         (force_shape == CRISP_SHAPE_XLDS ||
-         (force_shape < 0 && smf_ok && xlds_pays(g.Sb, g.Kb, Ncol, conv != nullptr)));
+         (force_shape < 0 && xlds_auto));
     const int shape = xres ? XRES_SHAPE : xlds ? XLDS_SHAPE
                     : (force_shape >= 0 && force_shape <= 3) ? force_shape
                     : (force_shape >= 7 && force_shape <= 10) ? force_shape - 7

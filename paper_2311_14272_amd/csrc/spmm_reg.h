@@ -94,6 +94,7 @@ struct ConvPos {
     int img, oh, ow;
     uint32_t half_off;   // hh * 8 channel planes, in bytes
     int img1, oh1, ow1;  // conv mode 2: position of the lane's second column
+    const u32x4* lut48;  // selector table of the dense 4:8 expansion (LDS; set by the kernels that expand 4:8)
 };
 
 __device__ __forceinline__ uint16_t float_to_bf16_rne(float f) {
@@ -340,6 +341,48 @@ __device__ __forceinline__ u32x4 expand_frag(const uint32_t (&v)[Fmt<N, M, B>::V
         }
     }
     return out;
+}
+
+// 4:8 through a table: the four 3-bit positions of a full group of eight are distinct and ascending, so the
+// group's 8-bit occupancy mask names the layout, and the j-th stored value belongs to the j-th set bit.  The
+// table (256 entries of four v_perm_b32 selectors, 4 KB of LDS, built once per workgroup) turns the two stored
+// dwords straight into the four operand dwords: 4 bit-field extracts, 4 shift-ors, one 16-byte LDS read and 4
+// permutes instead of about 76 vector instructions.  Needs whole groups (K a multiple of 8: the specialised
+// kernels require 16); groups wholly past K or S hold zeros at positions 0..3, which the same rule covers.
+// Entry of mask m, operand dword x: low half from position 2x, high half from 2x + 1; a position that is the
+// r-th set bit of m takes bytes 2r, 2r + 1 of the stored pair (v_perm_b32 numbers the second source's bytes
+// 0..3 and the first's 4..7), an empty position the selector 0x0c (zero).
+__device__ __forceinline__ void lut48_fill(u32x4* lut, int tid, int nthreads) {
+    for (int m = tid; m < 256; m += nthreads) {
+        u32x4 e;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            uint32_t sel = 0;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int q = 2 * x + h;
+                const uint32_t r = (uint32_t)__builtin_popcount((unsigned)m & ((1u << q) - 1u)) & 3u;
+                const uint32_t half = ((unsigned)m >> q) & 1u ? ((2u * r + 1u) << 8 | 2u * r) : 0x0C0Cu;
+                sel |= half << (16 * h);
+            }
+            e[x] = sel;
+        }
+        lut[m] = e;
+    }
+}
+// patterns whose dense expansion goes through the table
+template <int N, int M, bool SMF>
+constexpr bool lut48_pattern() { return !SMF && N == 4 && M == 8; }
+template <int B, int KSTEP>
+__device__ __forceinline__ u32x4 expand_frag_lut48(const uint32_t (&v)[2], const uint32_t (&ws)[Fmt<4, 8, B>::WPR], const u32x4* lut) {
+    typedef Fmt<4, 8, B> F;
+    constexpr int P0 = KSTEP * 2 * F::HB;          // first position bit of this step in the lane's (shifted) stream
+    constexpr int wi = P0 >> 5, sh = P0 & 31;
+    const uint32_t field = sh + F::HB > 32 ? __builtin_amdgcn_alignbit(ws[wi + 1 < F::WPR ? wi + 1 : wi], ws[wi], sh) : ws[wi] >> sh;
+    const uint32_t m = (1u << (field & 7u)) | (1u << ((field >> 3) & 7u)) | (1u << ((field >> 6) & 7u)) | (1u << ((field >> 9) & 7u));
+    const u32x4 sel = lut[m];
+    return u32x4{__builtin_amdgcn_perm(v[1], v[0], sel[0]), __builtin_amdgcn_perm(v[1], v[0], sel[1]),
+                 __builtin_amdgcn_perm(v[1], v[0], sel[2]), __builtin_amdgcn_perm(v[1], v[0], sel[3])};
 }
 
 // A operand and index register of the sparse matrix-core instruction for 32-row tile values `av`
@@ -650,7 +693,9 @@ struct BlockBody {
         if constexpr (PREFETCH) load_x(xr[ks], p, cp, next.off, next.off2, bj_next, ks);
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
-            const u32x4 a4 = expand_frag<N, M, B, ks>(av[rt][ks], ws[rt]);
+            u32x4 a4;
+            if constexpr (lut48_pattern<N, M, SMF>()) a4 = expand_frag_lut48<B, ks>(av[rt][ks], ws[rt], cp.lut48);
+            else a4 = expand_frag<N, M, B, ks>(av[rt][ks], ws[rt]);
             const bf16x8 afrag = __builtin_bit_cast(bf16x8, a4);
 #pragma unroll
             for (int c = 0; c < NACC; ++c)
@@ -876,14 +921,21 @@ void spmm_reg_kernel(SpmmArgs p) {
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int jj = lane & 31, hh = lane >> 5;
+    // selector table of the dense 4:8 expansion, built by the whole workgroup before any wave leaves
+    constexpr bool LUT48 = lut48_pattern<N, M, SMF>();
+    __shared__ u32x4 lut48[LUT48 ? 256 : 1];
+    if constexpr (LUT48) {
+        lut48_fill(lut48, tid, NWK > 1 ? 64 * NWK : 256);
+        __syncthreads();
+    }
     const int64_t wave_col = ((int64_t)nt * STRIPS + (NWK > 1 ? 0 : wave)) * (64 * WD);
-    if (NWK == 1 && wave_col >= p.Ncol) return;   // no barriers in this mode
+    if (NWK == 1 && wave_col >= p.Ncol) return;   // no further barriers in this mode
     const int64_t col0 = wave_col + jj * NACC;
     const bool col_ok = col0 < p.Ncol;
     // lane part of every X address (bytes): its 8-row half and its columns; lanes past the last
     // column read column 0 instead (in bounds) and never store
     const int64_t col_ld = col_ok ? col0 : 0;
-    ConvPos cp = {0, 0, 0, 0u, 0, 0, 0};
+    ConvPos cp = {0, 0, 0, 0u, 0, 0, 0, lut48};
     uint32_t lane_off = 0;
     if constexpr (CONV != 0) {
         // column -> (image, oh, ow); exact division through fp64 reciprocals (col < 2^31)

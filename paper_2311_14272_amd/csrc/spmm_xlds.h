@@ -39,6 +39,8 @@ __global__ __launch_bounds__(256, 4) void spmm_xlds_kernel(SpmmArgs p, int rows_
     typedef BlockBody<N, M, B, 1, false, 0, SMF> Body;
     extern __shared__ __attribute__((aligned(16))) unsigned char xl[];   // Kb * 8 KB of operands, then the block list
     int* lst = reinterpret_cast<int*>(xl + (size_t)Kb * KS * NACC * 1024);
+    constexpr bool LUT48 = lut48_pattern<N, M, SMF>();     // dense expansion of 4:8 through the selector table
+    __shared__ u32x4 lut48[LUT48 ? 256 : 1];
 
     const int id = blockIdx.x;
     const int rg = id % row_groups, nt = id / row_groups;
@@ -75,6 +77,7 @@ __global__ __launch_bounds__(256, 4) void spmm_xlds_kernel(SpmmArgs p, int rows_
     const int t0 = __builtin_amdgcn_readfirstlane(my_ptr);
     const int t1 = __builtin_amdgcn_readlane(my_ptr, bi1 - bi0);                  // end of the group's list
     for (int i = tid; i < min(t1 - t0, XLDS_LIST); i += 256) lst[i] = p.col_idx[t0 + i];
+    if constexpr (LUT48) lut48_fill(lut48, tid, 256);
 
     // ---- X rows of the strip -> B operands in LDS.  Unit u = (block column, 16-deep step); a wave takes
     // every fourth unit, four units (32 requests) in flight before the first is transposed ----
@@ -166,7 +169,9 @@ __global__ __launch_bounds__(256, 4) void spmm_xlds_kernel(SpmmArgs p, int rows_
                 for (int c = 0; c < NACC; ++c) b4[c] = *reinterpret_cast<const u32x4*>(bo + (ks * NACC + c) * 1024);
 #pragma unroll
                 for (int rt = 0; rt < RT; ++rt) {
-                    const u32x4 a4 = expand_frag<N, M, B, ks>(av[rt][ks], ws[rt]);
+                    u32x4 a4;
+                    if constexpr (LUT48) a4 = expand_frag_lut48<B, ks>(av[rt][ks], ws[rt], lut48);
+                    else a4 = expand_frag<N, M, B, ks>(av[rt][ks], ws[rt]);
                     const bf16x8 afrag = __builtin_bit_cast(bf16x8, a4);
 #pragma unroll
                     for (int c = 0; c < NACC; ++c)

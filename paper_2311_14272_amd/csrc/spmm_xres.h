@@ -31,8 +31,15 @@ __global__ __launch_bounds__(256, 2) void spmm_xres_kernel(SpmmArgs p, int rows_
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int jj = lane & 31, hh = lane >> 5;
+    // selector table of the dense 4:8 expansion, built by the whole workgroup before any wave leaves
+    constexpr bool LUT48 = lut48_pattern<N, M, SMF>();
+    __shared__ u32x4 lut48[LUT48 ? 256 : 1];
+    if constexpr (LUT48) {
+        lut48_fill(lut48, tid, 256);
+        __syncthreads();
+    }
     const int64_t wave_col = ((int64_t)nt * 4 + wave) * 64;
-    if (wave_col >= p.Ncol) return;                // no barriers in this kernel
+    if (wave_col >= p.Ncol) return;                // no further barriers in this kernel
     const int64_t col0 = wave_col + jj * NACC;
     const bool col_ok = col0 < p.Ncol;
     const int64_t col_ld = col_ok ? col0 : 0;     // lanes past the last column read column 0 and never store
@@ -111,7 +118,9 @@ __global__ __launch_bounds__(256, 2) void spmm_xres_kernel(SpmmArgs p, int rows_
                 constexpr int ks = decltype(ks_c)::value;
 #pragma unroll
                 for (int rt = 0; rt < RT; ++rt) {
-                    const u32x4 a4 = expand_frag<N, M, B, ks>(av[rt][ks], ws[rt]);
+                    u32x4 a4;
+                    if constexpr (LUT48) a4 = expand_frag_lut48<B, ks>(av[rt][ks], ws[rt], lut48);
+                    else a4 = expand_frag<N, M, B, ks>(av[rt][ks], ws[rt]);
                     const bf16x8 afrag = __builtin_bit_cast(bf16x8, a4);
 #pragma unroll
                     for (int c = 0; c < NACC; ++c)
