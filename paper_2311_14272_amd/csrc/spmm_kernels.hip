@@ -464,7 +464,8 @@ static bool prefer_lds(const Geometry& g, int64_t Ncol, int blocks_per_row) {
     const int slots_per_operand = (8 / g.m) * g.n;
     // (4:8 in registers goes through the selector table: residency only pays on long rows there -- 12 blocks:
     // 54 against 57 us, 9 blocks: 49 against 47 us, 3 blocks: 48-95 against 44-86 us)
-    if (g.n == 4 && g.m == 8) return narrow >= 2048 && blocks_per_row >= 10;
+    // (single blocks: the wide LDS-resident kernel, 76 against 81 us)
+    if (g.n == 4 && g.m == 8) return narrow >= 2048 && (blocks_per_row >= 10 || blocks_per_row <= 1);
     return narrow >= 2048 && (slots_per_operand >= 4 || blocks_per_row >= 6);
 }
 
