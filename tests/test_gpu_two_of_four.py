@@ -76,3 +76,36 @@ def test_hint_is_ignored_for_other_patterns():
             outs.append(run_spmm(layer, dX, L.Ncol, L.Ncol, crisp.Y_F32, L.S, shape=8, with_code=True))
         assert outs[0][1] == outs[1][1] and np.array_equal(outs[0][0], outs[1][0])
         layer.desc = plain
+
+
+@pytest.mark.parametrize("geom", [
+    # C, H, W, batch, k, stride, pad, S: strided 1x1 (the X-strip kernel gathers it; sparse instruction with the hint),
+    # 3x3 (the fused-lowering kernels do not take the hint: dense expansion, same results)
+    (128, 12, 12, 3, 1, 2, 0, 1100), (256, 8, 8, 4, 1, 2, 0, 192), (64, 10, 10, 2, 3, 1, 1, 128), (64, 14, 14, 2, 3, 2, 1, 256)],
+    ids=lambda g: "C%d_k%d_s%d_S%d" % (g[0], g[4], g[5], g[7]))
+def test_hint_with_fused_lowering(geom):
+    from gpu_util import conv_spmm
+    import torch
+    C_, H, Wd, b, k, stride, pad, S = geom
+    cv = synth.ConvShape(C_, H, Wd, b, k, k, stride, pad)
+    L = synth.LayerSpec("two_of_four_conv", S, cv.K, cv.Ncol, 4, 8, 64, 0.6, synth.SAL_MAG, 1.0, conv=cv)
+    rng = np.random.default_rng(C_ + S)
+    W = synth.draw_two_per_quad_weight(rng, S, cv.K)
+    act = synth.draw_relu_normal(rng, (C_, b, H, Wd))
+    sel = oracle.select(W, None, 4, 8, 64, L.density, synth.SAL_MAG, synth.ROW_UNIFORM)
+    layer, out = run_select_pack(L, W, None)
+    assert int(out["flags"][0]) == 1
+    Yref, Aref = oracle.gemm_masked(W, sel.mask, oracle.im2col(act, k, k, stride, pad))
+    conv = crisp.conv_desc_of(cv)
+    hinted = crisp.layer_desc(S, cv.K, 4, 8, 64, L.density, synth.SAL_MAG, synth.ROW_UNIFORM, hints=crisp.HINT_TWO_OF_FOUR)
+    Ncol = cv.Ncol
+    ld = (Ncol + 7) // 8 * 8
+    dact = dev(act)
+    for desc in (hinted, layer.desc):
+        for shape in (None, 1, 18):
+            for yd, tdt in ((crisp.Y_F32, torch.float32), (crisp.Y_BF16, torch.bfloat16)):
+                Y = torch.full((S, ld), float("nan"), dtype=tdt, device="cuda")
+                conv_spmm(desc, conv, layer.row_ptr, layer.col_idx, layer.vals, layer.idx_words, dact, Y, ld, yd, shape=shape)
+                torch.cuda.synchronize()
+                check_product(Y.float().cpu().numpy().astype(np.float64)[:, :Ncol], Yref, Aref, yd,
+                              "conv %s hints %d shape %s" % (geom, desc.hints, shape))
