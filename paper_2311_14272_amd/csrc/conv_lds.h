@@ -50,11 +50,12 @@ __global__ __launch_bounds__(256, 4) void conv_lds_kernel(SpmmArgs p, ConvLdsSch
     constexpr int RT = F::RT, KS = F::KS, NACC = 2;
     typedef BlockBody<N, M, B, 1, false, 0, SMF> Body;
     constexpr int PB = CONV_LDS_POS_BYTES;
-    // packed slices in flight per wave (ring).  One: the kernel then fits 128 registers and four
-    // workgroups share a compute unit, which gains more than a deeper prefetch of the slices (a ring
-    // of two at three workgroups per compute unit was 1.2-1.3x slower on the 14x14 layers of
-    // ResNet-50, whose 1024 workgroups are exactly four per compute unit)
-    constexpr int R = 1;
+    // packed slices in flight per wave (ring).  The kernel has to fit 128 registers so that four workgroups
+    // share a compute unit (at three per compute unit it was 1.2-1.3x slower on the 14x14 layers of ResNet-50,
+    // whose 1024 workgroups are exactly four per compute unit): two slices where a slice is ten or twelve
+    // registers (at most two stored values per eight columns; 1.0-1.1x over a ring of one, most on 1:8),
+    // else one
+    constexpr int R = F::FS <= 2 ? 2 : 1;
     extern __shared__ __attribute__((aligned(16))) unsigned char patch[];      // [PR][PC][PB]
     __shared__ uint32_t kept_bits[4][CONV_LDS_MAX_KB / 32];
     // per wave: its kept blocks in (channel block, tap) order, each channel block's run padded with
